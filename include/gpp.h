@@ -1,0 +1,195 @@
+/*
+ * gpp.h -- C ABI of the MI355X graph-pipeline-parallel (GPP) stage library.
+ *
+ * A DNN is a DAG of operators G_C = (V_C, E_C) that GPP cuts into a DAG of
+ * stages; a stage is S_i = <G_i, b_i, D_i, Pi_i>: a sub-graph of operators, a
+ * micro-batch size, a device set and a micro-batch schedule (paper section 3,
+ * "Problem Formulation").  This library executes ONE stage on ONE GPU
+ * (|D_i| = 1): for each micro-batch j it runs the forward pass fw_j and later
+ * the backward pass bw_j of G_i, keeps fw_j's activations until bw_j (paper
+ * section 1: a micro-batch is "in flight" until its backward finishes), and
+ * adds weight gradients over the micro-batches of a mini-batch, because under
+ * the synchronous schedule weights change only between iterations (paper
+ * section 6, default configuration; section 8, synchronous pipelines).  The
+ * schedule Pi_i is the caller's order of calls; the library enforces the
+ * ordering condition C4 of section 3.  Branches of G_i that are
+ * computationally independent are kept side by side: all operators of one
+ * topological level run as ONE grouped kernel launch (paper section 2).
+ *
+ * Conventions
+ *   - plain C, no C++ or PyTorch types; every function returns a status and
+ *     never throws or aborts; out-parameters are untouched on error.
+ *   - "DEVICE" pointers are HIP device memory owned by the caller; "HOST"
+ *     pointers are ordinary host memory.  The library allocates no device
+ *     memory: parameters, gradient accumulators, the workspace and all
+ *     per-call tensors belong to the caller.
+ *   - forward / backward / grad_reset only enqueue kernels on the given HIP
+ *     stream (a hipStream_t passed as void*); they neither allocate nor
+ *     synchronise.  All calls on one stage must be issued on one stream (or be
+ *     ordered by the caller), and must not overlap from several host threads.
+ *   - 2-D tensors are row-major [rows, features].  rows = micro_batch*seq_len
+ *     (+ rows_extra for inputs).  Tensors passed per call (inputs, outputs and
+ *     their gradients) are dense: leading dimension == features.  Parameters
+ *     and gradient accumulators with a feature dimension use the padded
+ *     leading dimension gpp_ld(features) (next multiple of 8 elements); the
+ *     padding columns of parameters must hold zeros and the library never
+ *     writes padding columns of gradient accumulators.
+ *   - all device base pointers must be 16-byte aligned; the workspace 256.
+ */
+#ifndef GPP_H
+#define GPP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gpp_stage gpp_stage_t; /* opaque, owned by the library between create and destroy */
+
+typedef enum {
+  GPP_OK = 0,
+  GPP_ERR_INVALID_ARG = 1, /* null pointer, bad enum, bad size */
+  GPP_ERR_BAD_GRAPH = 2,   /* cycle, dangling edge, wrong arity: G_i is not a DAG of known operators */
+  GPP_ERR_SHAPE = 3,       /* feature / row counts of connected operators disagree */
+  GPP_ERR_UNSUPPORTED = 4, /* valid graph this library has no kernel for (e.g. dtype mix) */
+  GPP_ERR_WORKSPACE = 5,   /* workspace too small or misaligned */
+  GPP_ERR_ORDER = 6,       /* ordering condition C4 violated, or slot busy / free */
+  GPP_ERR_INDEX = 7,       /* an embedding index or offset was out of range (see gpp_stage_sync_status) */
+  GPP_ERR_DEVICE = 8       /* a HIP call failed, see gpp_last_error */
+} gpp_status_t;
+
+typedef enum { GPP_F32 = 0, GPP_BF16 = 1, GPP_I32 = 2 } gpp_dtype_t;
+
+/* Operator kinds: the operator types of the paper's evaluation models
+ * (appendix "DNN Model Configurations": feed-forward layers, transformer
+ * layers with multi-head attention, embedding bags, an interaction, and the
+ * concatenation that merges branches) plus loss heads for a last stage. */
+typedef enum {
+  GPP_OP_INPUT = 0,         /* tensor entering the stage along a stage-graph edge, or a target */
+  GPP_OP_LINEAR = 1,        /* y = act(x W^T + b); W is [out_features, gpp_ld(in_features)] */
+  GPP_OP_LAYERNORM = 2,     /* over features, biased variance, affine gamma/beta, eps */
+  GPP_OP_ATTENTION = 3,     /* input [b*S, 3d] = Q|K|V column blocks; softmax(QK^T/sqrt(d/heads))V, non-causal */
+  GPP_OP_ADD = 4,           /* elementwise sum of two producers */
+  GPP_OP_MEANPOOL_SEQ = 5,  /* [b*S, d] -> [b, d], mean over the S rows of each sample */
+  GPP_OP_CONCAT = 6,        /* feature-wise concatenation of its producers, in the order given */
+  GPP_OP_EMBEDDING_BAG_SUM = 7, /* in[0] = indices input (i32, [b, bag_size] capacity), in[1] = offsets input
+                                   (i32, b+1 entries, offsets[0] = 0, non-decreasing, offsets[b] <= b*bag_size);
+                                   out[s,:] = sum_{j in [off[s], off[s+1])} table[idx[j],:] */
+  GPP_OP_DOT_INTERACT = 8,  /* input [b, F*d] seen as F vectors of d = in_features; out = [vector 0 |
+                               <v_i,v_j> for i>j in row-major order (1,0),(2,0),(2,1),...] */
+  GPP_OP_LOSS_MSE = 9,      /* in = (prediction, target f32); L = loss_scale * sum (y-t)^2 */
+  GPP_OP_LOSS_CE = 10,      /* in = (logits, labels i32 [b,1]); L = -loss_scale * sum log softmax(y)[label] */
+  GPP_OP_LOSS_BCE_LOGITS = 11 /* in = (logits, targets f32); L = loss_scale * sum softplus(y) - t*y */
+} gpp_op_kind_t;
+
+typedef enum { GPP_ACT_NONE = 0, GPP_ACT_RELU = 1, GPP_ACT_GELU_ERF = 2 } gpp_act_t;
+
+/* One vertex of G_i.  `in` lists producer op ids (the edges E_C inside the
+ * stage).  HOST memory; the library copies what it needs during create. */
+typedef struct {
+  int32_t kind;          /* gpp_op_kind_t */
+  int32_t n_in;
+  const int32_t *in;     /* HOST, n_in producer ids */
+  int32_t branch;        /* branch label (>= 0), -1 for merge / tail operators; informational */
+  int64_t in_features;   /* LINEAR: K; DOT_INTERACT: vector width d */
+  int64_t out_features;  /* feature count of the output (INPUT: of the tensor itself) */
+  int32_t act;           /* gpp_act_t, LINEAR only */
+  int32_t has_bias;      /* LINEAR only */
+  int32_t heads;         /* ATTENTION */
+  int32_t seq_len;       /* rows per sample of the output (INPUT, LAYERNORM, ATTENTION, ...: S; 1 = plain) */
+  int32_t rows_extra;    /* INPUT only: extra rows beyond micro_batch*seq_len (1 for bag offsets) */
+  int32_t requires_grad; /* INPUT only: 1 = float tensor from a predecessor stage whose gradient is returned */
+  int64_t num_rows;      /* EMBEDDING_BAG_SUM: table rows */
+  int64_t bag_size;      /* EMBEDDING_BAG_SUM: maximum indices per bag (capacity b*bag_size) */
+  double eps;            /* LAYERNORM */
+  double loss_scale;     /* LOSS_*: carries the 1/B normalisation of the whole mini-batch, so that
+                            micro-batch gradients sum to the full-batch gradient */
+  int32_t dtype;         /* gpp_dtype_t of the output tensor as stored */
+  int32_t param_dtype;   /* LINEAR: dtype of W (must equal the producer's dtype); others ignored */
+  void *param[2];        /* DEVICE. LINEAR: W, bias(f32) | LAYERNORM: gamma(f32), beta(f32) |
+                            EMBEDDING: table f32 [num_rows, gpp_ld(out_features)] */
+  void *grad[2];         /* DEVICE, f32 accumulators with the layout of param[] (W's gradient is f32
+                            [out_features, gpp_ld(in_features)]) */
+} gpp_op_desc_t;
+
+typedef struct {
+  int32_t n_ops;
+  const gpp_op_desc_t *ops;   /* HOST */
+  int64_t micro_batch;        /* b_i */
+  int32_t in_flight_slots;    /* how many micro-batches may be in flight (activation stash slots) */
+  int32_t flags;              /* bit 0: force the generic (non-MFMA) GEMM kernels, for testing */
+} gpp_stage_desc_t;
+
+/* Leading dimension used for parameters and gradient accumulators. */
+int64_t gpp_ld(int64_t features);
+
+/* Bytes of workspace a stage needs (activation stash for every slot, backward
+ * scratch, launch tables, sort buffers).  Host-only: needs no GPU.  Validates
+ * the descriptor (parameter pointers are not looked at). */
+gpp_status_t gpp_stage_workspace_bytes(const gpp_stage_desc_t *desc, size_t *bytes);
+
+/* Validates G_i (C1: it must be a DAG; shapes must agree), plans the grouped
+ * launches and copies the launch tables into the workspace (synchronous
+ * copies; the only calls of this library that synchronise are create,
+ * destroy-free-of-device-work and sync_status).  `workspace` is DEVICE memory
+ * of at least gpp_stage_workspace_bytes bytes, 256-byte aligned, owned by the
+ * caller and reserved for this stage until destroy.  Its content is cleared. */
+gpp_status_t gpp_stage_create(const gpp_stage_desc_t *desc, void *workspace, size_t workspace_bytes,
+                              gpp_stage_t **out);
+
+/* fw_j: forward pass of one micro-batch into stash slot `slot`.
+ *   inputs[i]   DEVICE, dense tensor of the i-th GPP_OP_INPUT in op-id order (read during the call's
+ *               kernels only; the stage keeps its own copy for the backward pass)
+ *   outputs[i]  DEVICE, dense tensor for the i-th stage output (non-loss operator without consumer,
+ *               op-id order); entries may be NULL
+ *   loss_out    DEVICE float or NULL: receives the sum of this micro-batch's loss operators
+ * Errors: GPP_ERR_ORDER if the slot is still in flight. */
+gpp_status_t gpp_stage_forward(gpp_stage_t *stage, int32_t slot, const void *const *inputs,
+                               void *const *outputs, float *loss_out, void *hip_stream);
+
+/* bw_j: backward pass of the micro-batch held in `slot`; frees the slot.
+ *   grad_outputs[i] DEVICE, dense gradient w.r.t. the i-th stage output (same dtype); the array may be
+ *                   NULL when the stage has no outputs (loss-terminated)
+ *   grad_inputs[i]  DEVICE or NULL, dense gradient w.r.t. the i-th GPP_OP_INPUT (written only for
+ *                   inputs with requires_grad; same dtype as the input)
+ * Weight gradients are ADDED into the accumulators (the first backward after gpp_stage_grad_reset
+ * overwrites instead of reading them).  Errors: GPP_ERR_ORDER unless `slot` holds the OLDEST forward
+ * that has not been backpropagated (C4: fw_k before bw_k, bw_k before bw_{k+1}). */
+gpp_status_t gpp_stage_backward(gpp_stage_t *stage, int32_t slot, const void *const *grad_outputs,
+                                void *const *grad_inputs, void *hip_stream);
+
+/* Iteration boundary (weights are updated once per mini-batch): the next backward starts new sums.
+ * Dense accumulators are not touched by this call (their next write overwrites); embedding-table
+ * accumulators are cleared on the stream.  Errors: GPP_ERR_ORDER while a micro-batch is in flight. */
+gpp_status_t gpp_stage_grad_reset(gpp_stage_t *stage, void *hip_stream);
+
+/* Waits for the stream and reports GPP_ERR_INDEX if any kernel since the last call met an embedding
+ * index or offset out of range (such entries are skipped, never dereferenced). */
+gpp_status_t gpp_stage_sync_status(gpp_stage_t *stage, void *hip_stream);
+
+gpp_status_t gpp_stage_destroy(gpp_stage_t *stage);
+
+/* Introspection (tests, benchmarks). */
+int32_t gpp_stage_num_inputs(const gpp_stage_t *stage);
+int32_t gpp_stage_num_outputs(const gpp_stage_t *stage);
+/* op id of the i-th input / output; -1 if out of range */
+int32_t gpp_stage_input_op(const gpp_stage_t *stage, int32_t i);
+int32_t gpp_stage_output_op(const gpp_stage_t *stage, int32_t i);
+/* number of kernel launches of one forward / backward call */
+int32_t gpp_stage_num_launches(const gpp_stage_t *stage, int32_t backward);
+/* Integer artefacts of the last backward of embedding op `op`: DEVICE pointers into the workspace.
+ * sorted_pos[n_used]: index positions stably sorted by row; unique_rows[n_unique] ascending;
+ * seg_offsets[n_unique+1]; counts[0] = n_used, counts[1] = n_unique (DEVICE int32[2]). */
+gpp_status_t gpp_stage_embedding_sort_result(gpp_stage_t *stage, int32_t op, const int32_t **sorted_pos,
+                                             const int32_t **unique_rows, const int32_t **seg_offsets,
+                                             const int32_t **counts);
+
+/* Thread-local description of the last error returned on this thread. */
+const char *gpp_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GPP_H */

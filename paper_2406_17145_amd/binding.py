@@ -1,0 +1,347 @@
+"""ctypes binding of libgpp.so: the C ABI's functions under their own names, plus
+`Stage`, a marshalling helper (device buffers through PyTorch, padded parameter
+layout, dtype conversion).  No step of the stage's arithmetic runs here: every
+forward/backward operation is a HIP kernel inside the library.
+
+The library must have been built (`python -m paper_2406_17145_amd.build`);
+`load()` raises if it is missing -- there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgpp.so")
+
+GPP_OK = 0
+STATUS_NAMES = ["GPP_OK", "GPP_ERR_INVALID_ARG", "GPP_ERR_BAD_GRAPH", "GPP_ERR_SHAPE", "GPP_ERR_UNSUPPORTED",
+                "GPP_ERR_WORKSPACE", "GPP_ERR_ORDER", "GPP_ERR_INDEX", "GPP_ERR_DEVICE"]
+(GPP_ERR_INVALID_ARG, GPP_ERR_BAD_GRAPH, GPP_ERR_SHAPE, GPP_ERR_UNSUPPORTED, GPP_ERR_WORKSPACE, GPP_ERR_ORDER,
+ GPP_ERR_INDEX, GPP_ERR_DEVICE) = range(1, 9)
+DTYPES = {"f32": 0, "bf16": 1, "i32": 2}
+KINDS = {"input": 0, "linear": 1, "layernorm": 2, "attention": 3, "add": 4, "meanpool": 5, "concat": 6,
+         "embedding_bag_sum": 7, "dot_interact": 8, "loss_mse": 9, "loss_ce": 10, "loss_bce": 11}
+ACTS = {"none": 0, "relu": 1, "gelu": 2}
+FLAG_FORCE_GENERIC_GEMM = 1
+
+
+class OpDesc(C.Structure):
+    _fields_ = [
+        ("kind", C.c_int32), ("n_in", C.c_int32), ("in_", C.POINTER(C.c_int32)), ("branch", C.c_int32),
+        ("in_features", C.c_int64), ("out_features", C.c_int64), ("act", C.c_int32), ("has_bias", C.c_int32),
+        ("heads", C.c_int32), ("seq_len", C.c_int32), ("rows_extra", C.c_int32), ("requires_grad", C.c_int32),
+        ("num_rows", C.c_int64), ("bag_size", C.c_int64), ("eps", C.c_double), ("loss_scale", C.c_double),
+        ("dtype", C.c_int32), ("param_dtype", C.c_int32), ("param", C.c_void_p * 2), ("grad", C.c_void_p * 2),
+    ]
+
+
+class StageDesc(C.Structure):
+    _fields_ = [("n_ops", C.c_int32), ("ops", C.POINTER(OpDesc)), ("micro_batch", C.c_int64),
+                ("in_flight_slots", C.c_int32), ("flags", C.c_int32)]
+
+
+EXPORTS = [
+    "gpp_ld", "gpp_stage_workspace_bytes", "gpp_stage_create", "gpp_stage_forward", "gpp_stage_backward",
+    "gpp_stage_grad_reset", "gpp_stage_sync_status", "gpp_stage_destroy", "gpp_stage_num_inputs",
+    "gpp_stage_num_outputs", "gpp_stage_input_op", "gpp_stage_output_op", "gpp_stage_num_launches",
+    "gpp_stage_embedding_sort_result", "gpp_last_error",
+]
+
+_lib = None
+
+
+def load():
+    """Loads libgpp.so; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2406_17145_amd.build` "
+                           "(there is no fallback implementation)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    lib.gpp_ld.restype, lib.gpp_ld.argtypes = i64, [i64]
+    lib.gpp_stage_workspace_bytes.restype = i32
+    lib.gpp_stage_workspace_bytes.argtypes = [C.POINTER(StageDesc), C.POINTER(C.c_size_t)]
+    lib.gpp_stage_create.restype = i32
+    lib.gpp_stage_create.argtypes = [C.POINTER(StageDesc), vp, C.c_size_t, C.POINTER(vp)]
+    lib.gpp_stage_forward.restype = i32
+    lib.gpp_stage_forward.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(vp), vp, vp]
+    lib.gpp_stage_backward.restype = i32
+    lib.gpp_stage_backward.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(vp), vp]
+    lib.gpp_stage_grad_reset.restype, lib.gpp_stage_grad_reset.argtypes = i32, [vp, vp]
+    lib.gpp_stage_sync_status.restype, lib.gpp_stage_sync_status.argtypes = i32, [vp, vp]
+    lib.gpp_stage_destroy.restype, lib.gpp_stage_destroy.argtypes = i32, [vp]
+    for name in ("gpp_stage_num_inputs", "gpp_stage_num_outputs"):
+        getattr(lib, name).restype, getattr(lib, name).argtypes = i32, [vp]
+    for name in ("gpp_stage_input_op", "gpp_stage_output_op", "gpp_stage_num_launches"):
+        getattr(lib, name).restype, getattr(lib, name).argtypes = i32, [vp, i32]
+    lib.gpp_stage_embedding_sort_result.restype = i32
+    lib.gpp_stage_embedding_sort_result.argtypes = [vp, i32] + [C.POINTER(vp)] * 4
+    lib.gpp_last_error.restype, lib.gpp_last_error.argtypes = C.c_char_p, []
+    _lib = lib
+    return lib
+
+
+class GppError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"{STATUS_NAMES[status] if 0 <= status < len(STATUS_NAMES) else status}: {message}")
+        self.status = status
+
+
+def _check(status):
+    if status != GPP_OK:
+        raise GppError(status, load().gpp_last_error().decode())
+
+
+def gpp_ld(features):
+    return int(load().gpp_ld(int(features)))
+
+
+def build_desc(ops, micro_batch, slots=1, flags=0, param_ptrs=None, grad_ptrs=None):
+    """ops: list of op dicts (see workloads.py).  Returns (StageDesc, keepalive)."""
+    n = len(ops)
+    arr = (OpDesc * n)()
+    keep = [arr]
+    for i, op in enumerate(ops):
+        d = arr[i]
+        d.kind = KINDS[op["kind"]]
+        ins = (C.c_int32 * max(1, len(op["inputs"])))(*op["inputs"])
+        keep.append(ins)
+        d.n_in = len(op["inputs"])
+        d.in_ = C.cast(ins, C.POINTER(C.c_int32))
+        d.branch = op.get("branch", -1)
+        d.in_features = op.get("in_features", 0)
+        d.out_features = op.get("out_features", 0)
+        d.act = ACTS[op.get("act", "none")]
+        d.has_bias = 1 if op.get("bias", False) else 0
+        d.heads = op.get("heads", 0)
+        d.seq_len = op.get("seq_len", 1)
+        d.rows_extra = op.get("rows_extra", 0)
+        d.requires_grad = 1 if (op["kind"] == "input" and op.get("role", "data") == "data"
+                                and op.get("dtype") != "i32") else 0
+        d.num_rows = op.get("num_rows", 0)
+        d.bag_size = op.get("bag_size", 0)
+        d.eps = op.get("eps", 0.0)
+        d.loss_scale = op.get("loss_scale", 0.0)
+        d.dtype = DTYPES[op.get("out_dtype", op.get("dtype", "f32"))]
+        d.param_dtype = DTYPES[op.get("dtype", "f32")]
+        for k in range(2):
+            d.param[k] = (param_ptrs or {}).get(i, [None, None])[k]
+            d.grad[k] = (grad_ptrs or {}).get(i, [None, None])[k]
+    sd = StageDesc(n, C.cast(arr, C.POINTER(OpDesc)), int(micro_batch), int(slots), int(flags))
+    return sd, keep
+
+
+def gpp_stage_workspace_bytes(desc):
+    out = C.c_size_t(0)
+    _check(load().gpp_stage_workspace_bytes(C.byref(desc), C.byref(out)))
+    return out.value
+
+
+def gpp_stage_create(desc, workspace_ptr, workspace_bytes):
+    h = C.c_void_p()
+    _check(load().gpp_stage_create(C.byref(desc), workspace_ptr, workspace_bytes, C.byref(h)))
+    return h
+
+
+def _ptr_array(ptrs):
+    arr = (C.c_void_p * max(1, len(ptrs)))(*ptrs)
+    return arr
+
+
+def gpp_stage_forward(handle, slot, input_ptrs, output_ptrs, loss_ptr, stream):
+    _check(load().gpp_stage_forward(handle, slot, _ptr_array(input_ptrs),
+                                    _ptr_array(output_ptrs) if output_ptrs is not None else None,
+                                    loss_ptr, stream))
+
+
+def gpp_stage_backward(handle, slot, grad_output_ptrs, grad_input_ptrs, stream):
+    _check(load().gpp_stage_backward(handle, slot,
+                                     _ptr_array(grad_output_ptrs) if grad_output_ptrs is not None else None,
+                                     _ptr_array(grad_input_ptrs) if grad_input_ptrs is not None else None, stream))
+
+
+def gpp_stage_grad_reset(handle, stream):
+    _check(load().gpp_stage_grad_reset(handle, stream))
+
+
+def gpp_stage_sync_status(handle, stream):
+    _check(load().gpp_stage_sync_status(handle, stream))
+
+
+def gpp_stage_destroy(handle):
+    _check(load().gpp_stage_destroy(handle))
+
+
+# ---------------------------------------------------------------------------
+# marshalling helper
+# ---------------------------------------------------------------------------
+class Stage:
+    """Owns the device buffers of one stage (PyTorch tensors) and marshals numpy
+    arrays to and from the C ABI."""
+
+    def __init__(self, ops, micro_batch, params, slots=1, flags=0, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.dev = torch.device(device)
+        torch.cuda.set_device(self.dev)
+        self.ops, self.b, self.slots = ops, int(micro_batch), int(slots)
+        self.tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "i32": torch.int32}
+        self.p_t, self.g_t, pp, gp = {}, {}, {}, {}
+        for i, p in params.items():
+            op = ops[i]
+            names = {"linear": ["W", "b"], "layernorm": ["gamma", "beta"], "embedding_bag_sum": ["table"]}[op["kind"]]
+            self.p_t[i], self.g_t[i] = {}, {}
+            pp[i], gp[i] = [None, None], [None, None]
+            for k, nm in enumerate(names):
+                if nm not in p:
+                    continue
+                a = np.asarray(p[nm], dtype=np.float32)
+                if a.ndim == 2:
+                    ld = gpp_ld(a.shape[1])
+                    pad = np.zeros((a.shape[0], ld), np.float32)
+                    pad[:, :a.shape[1]] = a
+                    a = pad
+                dt = self.tdt[op["dtype"]] if nm == "W" else torch.float32
+                t = torch.from_numpy(a).to(self.dev).to(dt).contiguous()
+                g = torch.zeros(a.shape, dtype=torch.float32, device=self.dev)
+                self.p_t[i][nm], self.g_t[i][nm] = t, g
+                pp[i][k], gp[i][k] = t.data_ptr(), g.data_ptr()
+        self.desc, self._keep = build_desc(ops, micro_batch, slots, flags, pp, gp)
+        self.ws_bytes = gpp_stage_workspace_bytes(self.desc)
+        self.ws = torch.empty(self.ws_bytes + 256, dtype=torch.uint8, device=self.dev)
+        base = (self.ws.data_ptr() + 255) // 256 * 256
+        self.handle = gpp_stage_create(self.desc, base, self.ws_bytes)
+        lib = load()
+        self.input_ids = [lib.gpp_stage_input_op(self.handle, k) for k in range(lib.gpp_stage_num_inputs(self.handle))]
+        self.output_ids = [lib.gpp_stage_output_op(self.handle, k) for k in range(lib.gpp_stage_num_outputs(self.handle))]
+        self.loss = torch.zeros(1, dtype=torch.float32, device=self.dev)
+        self._held = {}
+
+    # -- helpers --
+    def stream(self):
+        return self.torch.cuda.current_stream(self.dev).cuda_stream
+
+    def _rows(self, op_id):
+        op = self.ops[op_id]
+        if op["kind"] == "input":
+            return self.b * op.get("seq_len", 1) + op.get("rows_extra", 0)
+        if op["kind"] == "meanpool" or op["kind"] == "embedding_bag_sum":
+            return self.b
+        return self._rows(op["inputs"][0])
+
+    def to_device(self, op_id, a):
+        torch = self.torch
+        if isinstance(a, torch.Tensor):
+            return a
+        op = self.ops[op_id]
+        dt = self.tdt[op.get("out_dtype", op["dtype"])]
+        t = torch.from_numpy(np.ascontiguousarray(a))
+        if dt == torch.int32:
+            t = t.to(torch.int32)
+        else:
+            t = t.to(torch.float32)
+        return t.to(self.dev).to(dt).contiguous()
+
+    def stage_inputs(self, inputs):
+        """numpy dict -> list of device tensors in input order (marshalling, untimed)."""
+        return [self.to_device(i, inputs[i]) for i in self.input_ids]
+
+    def alloc_outputs(self):
+        torch = self.torch
+        return [torch.empty((self._rows(i), self.ops[i]["out_features"]),
+                            dtype=self.tdt[self.ops[i].get("out_dtype", self.ops[i]["dtype"])], device=self.dev)
+                for i in self.output_ids]
+
+    def alloc_grad_inputs(self):
+        torch = self.torch
+        outs = []
+        for i in self.input_ids:
+            op = self.ops[i]
+            if op.get("role", "data") == "data" and op["dtype"] != "i32":
+                outs.append(torch.empty((self._rows(i), op["out_features"]), dtype=self.tdt[op["dtype"]], device=self.dev))
+            else:
+                outs.append(None)
+        return outs
+
+    # -- the four calls --
+    def forward(self, slot, inputs, outputs=None, loss=None):
+        """inputs: list of device tensors (stage_inputs) or dict of numpy arrays."""
+        if isinstance(inputs, dict):
+            inputs = self.stage_inputs(inputs)
+        if outputs is None:
+            outputs = self.alloc_outputs()
+        loss = self.loss if loss is None else loss
+        gpp_stage_forward(self.handle, slot, [t.data_ptr() for t in inputs], [t.data_ptr() for t in outputs],
+                          loss.data_ptr(), self.stream())
+        self._held[slot] = inputs
+        return outputs, loss
+
+    def backward(self, slot, grad_outputs=None, grad_inputs=None):
+        if grad_outputs is not None and isinstance(grad_outputs, dict):
+            grad_outputs = [self.to_device(i, grad_outputs[i]) for i in self.output_ids]
+        if grad_inputs is None:
+            grad_inputs = self.alloc_grad_inputs()
+        gpp_stage_backward(self.handle, slot,
+                           [t.data_ptr() for t in grad_outputs] if grad_outputs else None,
+                           [t.data_ptr() if t is not None else None for t in grad_inputs], self.stream())
+        self._held[("g", slot)] = grad_outputs
+        return grad_inputs
+
+    def grad_reset(self):
+        gpp_stage_grad_reset(self.handle, self.stream())
+
+    def sync_status(self):
+        gpp_stage_sync_status(self.handle, self.stream())
+
+    def num_launches(self, backward):
+        return load().gpp_stage_num_launches(self.handle, 1 if backward else 0)
+
+    # -- results back to numpy (unpadded) --
+    def grads_numpy(self):
+        self.torch.cuda.synchronize(self.dev)
+        out = {}
+        for i, g in self.g_t.items():
+            out[i] = {}
+            for nm, t in g.items():
+                a = t.cpu().numpy()
+                if a.ndim == 2:
+                    ref_cols = {"W": self.ops[i].get("in_features"), "table": self.ops[i].get("out_features")}[nm]
+                    a = a[:, :ref_cols]
+                out[i][nm] = a
+        return out
+
+    def embedding_sort_result(self, op_id):
+        torch = self.torch
+        torch.cuda.synchronize(self.dev)
+        ptrs = [C.c_void_p() for _ in range(4)]
+        _check(load().gpp_stage_embedding_sort_result(self.handle, op_id, *[C.byref(p) for p in ptrs]))
+        cap = self.b * self.ops[op_id]["bag_size"]
+
+        def read(ptr, n):
+            buf = torch.empty(n, dtype=torch.int32, device=self.dev)
+            from torch.cuda import current_stream  # noqa: F401
+            C_hip = C.CDLL("libamdhip64.so")
+            C_hip.hipMemcpy(C.c_void_p(buf.data_ptr()), ptr, C.c_size_t(4 * n), C.c_int(3))
+            return buf.cpu().numpy()
+
+        counts = read(ptrs[3], 2)
+        n_used, n_unique = int(counts[0]), int(counts[1])
+        assert 0 <= n_used <= cap and 0 <= n_unique <= n_used
+        return (read(ptrs[0], cap)[:n_used], read(ptrs[1], cap)[:n_unique], read(ptrs[2], cap + 1)[:n_unique + 1])
+
+    def close(self):
+        if self.handle is not None:
+            self.torch.cuda.synchronize(self.dev)
+            gpp_stage_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

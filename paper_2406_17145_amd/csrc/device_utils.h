@@ -1,0 +1,88 @@
+// Small device helpers: dtype-tagged loads/stores, bf16 conversion, activation
+// functions, wave/block reductions for 64-wide wavefronts.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kernels.h"
+
+namespace gpp {
+
+typedef __bf16 bf16_t;
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t u) {
+  return __uint_as_float(((uint32_t)u) << 16);
+}
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  bf16_t b = (bf16_t)f;  // round to nearest even
+  return __builtin_bit_cast(uint16_t, b);
+}
+
+__device__ __forceinline__ float load_as_f32(const void *p, int32_t dtype, int64_t i) {
+  if (dtype == DT_BF16) return bf16_bits_to_f32(((const uint16_t *)p)[i]);
+  return ((const float *)p)[i];
+}
+__device__ __forceinline__ void store_from_f32(void *p, int32_t dtype, int64_t i, float v) {
+  if (dtype == DT_BF16)
+    ((uint16_t *)p)[i] = f32_to_bf16_bits(v);
+  else
+    ((float *)p)[i] = v;
+}
+
+template <typename T>
+__device__ __forceinline__ float to_f32(T v);
+template <>
+__device__ __forceinline__ float to_f32<float>(float v) {
+  return v;
+}
+template <>
+__device__ __forceinline__ float to_f32<uint16_t>(uint16_t v) {
+  return bf16_bits_to_f32(v);
+}
+
+// exact (erf) GELU and its derivative Phi(z) + z*phi(z)
+__device__ __forceinline__ float gelu_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_grad_f(float z) {
+  float cdf = 0.5f * (1.0f + erff(z * 0.70710678118654752f));
+  float pdf = 0.3989422804014327f * __expf(-0.5f * z * z);
+  return cdf + z * pdf;
+}
+__device__ __forceinline__ float act_apply(float z, int32_t act) {
+  if (act == ACT_RELU) return z > 0.0f ? z : 0.0f;
+  if (act == ACT_GELU) return gelu_f(z);
+  return z;
+}
+// derivative factor from the mask source: ReLU uses the stored output (y > 0 <=> z > 0),
+// GELU the stored pre-activation
+__device__ __forceinline__ float act_grad(float src, int32_t act) {
+  if (act == ACT_RELU) return src > 0.0f ? 1.0f : 0.0f;
+  if (act == ACT_GELU) return gelu_grad_f(src);
+  return 1.0f;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// Finds the record whose [blk_begin, next blk_begin) range holds `blk`.
+template <typename P>
+__device__ __forceinline__ int find_prob(const P *probs, int n, int blk) {
+  int lo = 0, hi = n - 1;
+  while (lo < hi) {
+    int mid = (lo + hi + 1) >> 1;
+    if (probs[mid].blk_begin <= blk)
+      lo = mid;
+    else
+      hi = mid - 1;
+  }
+  return lo;
+}
+
+}  // namespace gpp

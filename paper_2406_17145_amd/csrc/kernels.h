@@ -1,0 +1,197 @@
+// Device-side problem records and launch entry points shared by the stage
+// planner (host) and the HIP kernels.  One record describes one branch's share
+// of a grouped launch: all independent operators of one topological level of
+// the stage's operator graph run in one kernel, each workgroup finding its
+// record through the per-record prefix sums (`blk_begin`).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gpp {
+
+enum : int32_t { DT_F32 = 0, DT_BF16 = 1, DT_I32 = 2 };
+enum : int32_t { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU = 2 };
+enum : int32_t { FORM_FWD = 0, FORM_DX = 1, FORM_DW = 2 };
+
+// ---- grouped GEMM -----------------------------------------------------
+// FORM_FWD  C[m,n] = act( sum_k A[m,k] * B[n,k] + bias[n] ) (+ res[m,n])      A = X, B = W
+// FORM_DX   C[m,k] = ( sum_n A[m,n] * B[n,k] (+ res[m,k]) ) * act'(aux[m,k])   A = dZ, B = W
+// FORM_DW   C[n,k] (+)= sum_m A[m,n] * B[m,k]                                  A = dZ, B = X
+// M, N are the output's rows / columns, K the contraction length.
+struct GemmProb {
+  const void *A, *B;
+  void *C;
+  const float *bias;
+  void *aux;        // FWD + GELU: pre-activation stash (written). DX: mask source (read).
+  const void *res;  // FWD: residual addend. DX: gradient addend (may equal C: accumulate).
+  int64_t lda, ldb, ldc, ldaux, ldres;
+  int32_t M, N, K;
+  int32_t form, act;
+  int32_t in_dtype;   // dtype of A and B (DT_F32 or DT_BF16)
+  int32_t c_dtype, aux_dtype, res_dtype;
+  int32_t blk_begin;  // first workgroup of this record
+  int32_t tiles_n;    // tile columns of this record
+  int32_t split_k;    // reserved (1)
+};
+
+// ---- 2-D copy / convert / accumulate / activation backward --------------
+// dst[r,c] = cvt(src[r,c]) (+ addend[r,c]); rows x cols elements.
+// mode 1 (act backward, in place on dst): dst[r,c] = dst[r,c] * act'(src[r,c])
+// mode 2 (add): dst = src + addend
+struct EltProb {
+  const void *src;
+  void *dst;
+  const void *addend;
+  int64_t ld_src, ld_dst, ld_add;
+  int32_t rows, cols;
+  int32_t src_dtype, dst_dtype, add_dtype;
+  int32_t mode, act;
+  int32_t ext_src, ext_dst;  // >= 0: pointer comes from the per-call pointer block instead
+  int32_t blk_begin;
+};
+
+// ---- column sums: out[c] (+)= sum_r src[r,c]  (bias gradients) ----------
+struct ColsumProb {
+  const void *src;
+  float *out;
+  int64_t ld;
+  int32_t rows, cols, dtype;
+  int32_t blk_begin;
+};
+
+// ---- LayerNorm ------------------------------------------------------------
+struct LnProb {
+  const void *x;      // input rows
+  void *y;            // fwd: output; bwd: dx
+  const void *dy;     // bwd
+  const void *addend; // bwd: optional gradient addend for dx
+  const float *gamma, *beta;
+  float *mean, *rstd;        // per-row statistics (written fwd, read bwd)
+  float *dgamma, *dbeta;     // accumulators
+  float *partial;            // bwd scratch: [row_blocks, 2, d]
+  int64_t ldx, ldy, lddy, ldadd;
+  int32_t rows, d;
+  int32_t x_dtype, y_dtype, dy_dtype, add_dtype;
+  float eps;
+  int32_t blk_begin;
+  int32_t row_blocks;
+};
+
+// ---- attention -------------------------------------------------------------
+struct AttnProb {
+  const void *qkv;   // [b*S, 3d]
+  void *out;         // fwd: O [b*S, d]; bwd: dqkv [b*S, 3d]
+  const void *dout;  // bwd: dO
+  const void *o;     // bwd: O (forward output)
+  float *lse;        // [b*heads, S] log-sum-exp of scaled scores
+  float *delta;      // [b*heads, S] rowsum(dO * O)
+  int64_t ld_qkv, ld_out, ld_dout, ld_o;
+  int32_t batch, heads, seq, dh;
+  int32_t dtype, out_dtype;
+  int32_t grad_dtype;  // bwd: dtype of dqkv
+  int32_t blk_begin;
+};
+
+// ---- mean-pool over the sequence -------------------------------------------
+struct PoolProb {
+  const void *src;
+  void *dst;
+  int64_t ld_src, ld_dst;
+  int32_t batch, seq, d;
+  int32_t src_dtype, dst_dtype;
+  int32_t backward;  // 0: dst[b,:] = mean_s src[b*S+s,:]; 1: dst[b*S+s,:] = src[b,:]/S
+  int32_t blk_begin;
+};
+
+// ---- embedding bag ------------------------------------------------------------
+struct EmbProb {
+  const float *table;
+  float *dtable;
+  const int32_t *indices;  // [capacity]
+  const int32_t *offsets;  // [n_bags+1]
+  void *out;               // fwd: pooled output; bwd: gradient w.r.t. pooled output (read)
+  int32_t *bag_of;         // [capacity] bag id of each index position (written fwd)
+  int32_t *keys_a, *keys_b, *pos_a, *pos_b;  // sort ping-pong buffers [capacity]
+  int32_t *hist;           // [radix, sort_blocks]
+  int32_t *unique_rows, *seg_offsets;  // [capacity], [capacity+1]
+  int32_t *counts;         // [0] n_used, [1] n_unique
+  int64_t ld_table, ld_out;
+  int32_t n_bags, capacity, dim, num_rows;
+  int32_t out_dtype;
+  int32_t sort_blocks, passes;
+  int32_t blk_begin;
+};
+
+// ---- pairwise-dot interaction --------------------------------------------------
+struct InteractProb {
+  const void *x;   // [b, F*d]
+  void *y;         // fwd: [b, d + F(F-1)/2]; bwd: dx [b, F*d]
+  const void *dy;  // bwd
+  int64_t ld_x, ld_y, ld_dy;
+  int32_t batch, F, d;
+  int32_t x_dtype, y_dtype, dy_dtype;
+  int32_t blk_begin;
+};
+
+// ---- loss heads -------------------------------------------------------------------
+struct LossProb {
+  const void *y;        // prediction
+  const void *target;   // f32 targets or i32 labels
+  float *loss;          // fwd: scalar out
+  void *dy;             // bwd: gradient out
+  int64_t ld_y, ld_t, ld_dy;
+  int32_t rows, cols, kind;   // kind = gpp_op_kind_t value
+  int32_t y_dtype, dy_dtype;
+  float scale;
+};
+
+struct ExtPtrs {
+  void *p[64];
+};
+
+// per-stage device flags
+struct StageFlags {
+  int32_t index_error;
+};
+
+// ---- launch entry points (defined next to the kernels) -------------------------
+void launch_gemm_generic(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int in_dtype, hipStream_t s);
+void launch_gemm_mfma(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int form, hipStream_t s);
+// tile geometry used by the planner to count workgroups
+int gemm_generic_tiles(int M, int N, int *tiles_n);
+int gemm_mfma_tiles(int form, int M, int N, int K, int *tiles_n);
+bool gemm_mfma_supported(const GemmProb &p);
+
+void launch_elt(const EltProb *probs, int n, int total_blocks, const ExtPtrs &ext, hipStream_t s);
+int elt_blocks(int rows, int cols);
+void launch_colsum(const ColsumProb *probs, int n, int total_blocks, int accumulate, hipStream_t s);
+int colsum_blocks(int cols);
+
+void launch_ln_fwd(const LnProb *probs, int n, int total_blocks, hipStream_t s);
+void launch_ln_bwd(const LnProb *probs, int n, int total_blocks, hipStream_t s);
+void launch_ln_bwd_params(const LnProb *probs, int n, int total_blocks, int accumulate, hipStream_t s);
+int ln_rows_per_block();
+int ln_param_blocks(int d);
+
+int attn_blocks(int batch, int heads, int seq);
+
+void launch_pool(const PoolProb *probs, int n, int total_blocks, hipStream_t s);
+int pool_blocks(const PoolProb &p);
+
+void launch_emb_fwd(const EmbProb *probs, int n, int total_blocks, StageFlags *flags, hipStream_t s);
+int emb_fwd_blocks(int n_bags);
+// sort + segment detection + segment sum; returns the number of launches it enqueues
+int launch_emb_bwd(const EmbProb *probs, int n, int max_capacity, int max_sort_blocks, int max_passes,
+                   StageFlags *flags, hipStream_t s);
+int emb_bwd_num_launches(int max_passes);
+int emb_sort_chunk();
+int emb_radix_bits();
+void launch_emb_reset(const EmbProb *probs, int n, hipStream_t s);
+
+void launch_loss_fwd(const LossProb *probs, int n, hipStream_t s);
+void launch_loss_bwd(const LossProb *probs, int n, int total_blocks, hipStream_t s);
+int loss_bwd_blocks(const LossProb &p);
+
+void launch_fill_zero(void *ptr, size_t bytes, hipStream_t s);
+
+}  // namespace gpp

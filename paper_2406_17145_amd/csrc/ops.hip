@@ -1,0 +1,313 @@
+// Grouped non-GEMM kernels of a stage: 2-D copy / convert / accumulate and
+// activation backward, bias-gradient column sums, LayerNorm forward/backward,
+// sequence mean-pool, loss heads.  All are bound by HBM traffic; every launch
+// covers all branches of one topological level.
+#include "device_utils.h"
+
+namespace gpp {
+
+// ------------------------------------------------------------------ elt
+constexpr int ELT_PER_BLOCK = 2048;
+int elt_blocks(int rows, int cols) {
+  int64_t e = (int64_t)rows * cols;
+  return (int)((e + ELT_PER_BLOCK - 1) / ELT_PER_BLOCK);
+}
+
+__global__ __launch_bounds__(256) void k_elt(const EltProb *__restrict__ probs, int n, ExtPtrs ext) {
+  const int pi = find_prob(probs, n, blockIdx.x);
+  const EltProb p = probs[pi];
+  const void *src = p.ext_src >= 0 ? ext.p[p.ext_src] : p.src;
+  void *dst = p.ext_dst >= 0 ? ext.p[p.ext_dst] : p.dst;
+  if (!src || !dst) return;
+  const int64_t total = (int64_t)p.rows * p.cols;
+  const int64_t base = (int64_t)(blockIdx.x - p.blk_begin) * ELT_PER_BLOCK;
+#pragma unroll
+  for (int it = 0; it < ELT_PER_BLOCK / 256; ++it) {
+    const int64_t e = base + it * 256 + threadIdx.x;
+    if (e >= total) break;
+    const int r = (int)(e / p.cols), c = (int)(e - (int64_t)r * p.cols);
+    const int64_t si = (int64_t)r * p.ld_src + c, di = (int64_t)r * p.ld_dst + c;
+    if (p.src_dtype == DT_I32) {
+      ((int32_t *)dst)[di] = ((const int32_t *)src)[si];
+      continue;
+    }
+    if (p.mode == 1) {
+      float g = load_as_f32(dst, p.dst_dtype, di);
+      store_from_f32(dst, p.dst_dtype, di, g * act_grad(load_as_f32(src, p.src_dtype, si), p.act));
+    } else {
+      float v = load_as_f32(src, p.src_dtype, si);
+      if (p.addend) v += load_as_f32(p.addend, p.add_dtype, (int64_t)r * p.ld_add + c);
+      store_from_f32(dst, p.dst_dtype, di, v);
+    }
+  }
+}
+
+void launch_elt(const EltProb *probs, int n, int total_blocks, const ExtPtrs &ext, hipStream_t s) {
+  if (total_blocks <= 0) return;
+  hipLaunchKernelGGL(k_elt, dim3(total_blocks), dim3(256), 0, s, probs, n, ext);
+}
+
+__global__ __launch_bounds__(256) void k_fill_zero(uint32_t *p, size_t words) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (; i < words; i += stride) p[i] = 0u;
+}
+void launch_fill_zero(void *ptr, size_t bytes, hipStream_t s) {
+  size_t words = bytes / 4;
+  if (!words) return;
+  int blocks = (int)((words + 256 * 16 - 1) / (256 * 16));
+  if (blocks > 8192) blocks = 8192;
+  hipLaunchKernelGGL(k_fill_zero, dim3(blocks), dim3(256), 0, s, (uint32_t *)ptr, words);
+}
+
+// ------------------------------------------------------------------ column sums
+int colsum_blocks(int cols) { return (cols + 63) / 64; }
+
+__global__ __launch_bounds__(256) void k_colsum(const ColsumProb *__restrict__ probs, int n, int accumulate) {
+  __shared__ float red[4][64];
+  const int pi = find_prob(probs, n, blockIdx.x);
+  const ColsumProb p = probs[pi];
+  const int c = (blockIdx.x - p.blk_begin) * 64 + (threadIdx.x & 63);
+  const int rg = threadIdx.x >> 6;
+  float s = 0.0f;
+  if (c < p.cols)
+    for (int r = rg; r < p.rows; r += 4) s += load_as_f32(p.src, p.dtype, (int64_t)r * p.ld + c);
+  red[rg][threadIdx.x & 63] = s;
+  __syncthreads();
+  if (rg == 0 && c < p.cols) {
+    float v = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+    p.out[c] = accumulate ? p.out[c] + v : v;
+  }
+}
+void launch_colsum(const ColsumProb *probs, int n, int total_blocks, int accumulate, hipStream_t s) {
+  if (total_blocks <= 0) return;
+  hipLaunchKernelGGL(k_colsum, dim3(total_blocks), dim3(256), 0, s, probs, n, accumulate);
+}
+
+// ------------------------------------------------------------------ LayerNorm
+int ln_rows_per_block() { return 4; }
+int ln_param_blocks(int d) { return (d + 63) / 64; }
+
+__global__ __launch_bounds__(256) void k_ln_fwd(const LnProb *__restrict__ probs, int n) {
+  const int pi = find_prob(probs, n, blockIdx.x);
+  const LnProb p = probs[pi];
+  const int lane = threadIdx.x & 63;
+  const int row = (blockIdx.x - p.blk_begin) * 4 + (threadIdx.x >> 6);
+  if (row >= p.rows) return;
+  const int64_t xo = (int64_t)row * p.ldx;
+  float s = 0.0f;
+  for (int c = lane; c < p.d; c += 64) s += load_as_f32(p.x, p.x_dtype, xo + c);
+  const float mu = wave_sum(s) / (float)p.d;
+  float q = 0.0f;
+  for (int c = lane; c < p.d; c += 64) {
+    float v = load_as_f32(p.x, p.x_dtype, xo + c) - mu;
+    q += v * v;
+  }
+  const float rstd = rsqrtf(wave_sum(q) / (float)p.d + p.eps);
+  for (int c = lane; c < p.d; c += 64) {
+    float v = (load_as_f32(p.x, p.x_dtype, xo + c) - mu) * rstd;
+    store_from_f32(p.y, p.y_dtype, (int64_t)row * p.ldy + c, v * p.gamma[c] + p.beta[c]);
+  }
+  if (lane == 0) {
+    p.mean[row] = mu;
+    p.rstd[row] = rstd;
+  }
+}
+void launch_ln_fwd(const LnProb *probs, int n, int total_blocks, hipStream_t s) {
+  if (total_blocks <= 0) return;
+  hipLaunchKernelGGL(k_ln_fwd, dim3(total_blocks), dim3(256), 0, s, probs, n);
+}
+
+// dx = rstd * (g - mean(g) - xhat * mean(g * xhat)) (+ addend), g = dy * gamma
+__global__ __launch_bounds__(256) void k_ln_bwd(const LnProb *__restrict__ probs, int n) {
+  const int pi = find_prob(probs, n, blockIdx.x);
+  const LnProb p = probs[pi];
+  const int lane = threadIdx.x & 63;
+  const int row = (blockIdx.x - p.blk_begin) * 4 + (threadIdx.x >> 6);
+  if (row >= p.rows) return;
+  const float mu = p.mean[row], rstd = p.rstd[row];
+  const int64_t xo = (int64_t)row * p.ldx, go = (int64_t)row * p.lddy;
+  float s1 = 0.0f, s2 = 0.0f;
+  for (int c = lane; c < p.d; c += 64) {
+    float xh = (load_as_f32(p.x, p.x_dtype, xo + c) - mu) * rstd;
+    float g = load_as_f32(p.dy, p.dy_dtype, go + c) * p.gamma[c];
+    s1 += g;
+    s2 += g * xh;
+  }
+  const float m1 = wave_sum(s1) / (float)p.d, m2 = wave_sum(s2) / (float)p.d;
+  for (int c = lane; c < p.d; c += 64) {
+    float xh = (load_as_f32(p.x, p.x_dtype, xo + c) - mu) * rstd;
+    float g = load_as_f32(p.dy, p.dy_dtype, go + c) * p.gamma[c];
+    float v = rstd * (g - m1 - xh * m2);
+    if (p.addend) v += load_as_f32(p.addend, p.add_dtype, (int64_t)row * p.ldadd + c);
+    store_from_f32(p.y, p.y_dtype, (int64_t)row * p.ldy + c, v);
+  }
+}
+void launch_ln_bwd(const LnProb *probs, int n, int total_blocks, hipStream_t s) {
+  if (total_blocks <= 0) return;
+  hipLaunchKernelGGL(k_ln_bwd, dim3(total_blocks), dim3(256), 0, s, probs, n);
+}
+
+// dgamma[c] (+)= sum_r dy*xhat ; dbeta[c] (+)= sum_r dy.  64 columns per workgroup,
+// four row groups reduced through LDS in a fixed order.
+__global__ __launch_bounds__(256) void k_ln_bwd_params(const LnProb *__restrict__ probs, int n, int accumulate) {
+  __shared__ float red[2][4][64];
+  const int pi = find_prob(probs, n, blockIdx.x);
+  const LnProb p = probs[pi];
+  const int cl = threadIdx.x & 63, rg = threadIdx.x >> 6;
+  const int c = (blockIdx.x - p.blk_begin) * 64 + cl;
+  float sg = 0.0f, sb = 0.0f;
+  if (c < p.d)
+    for (int r = rg; r < p.rows; r += 4) {
+      float dy = load_as_f32(p.dy, p.dy_dtype, (int64_t)r * p.lddy + c);
+      float xh = (load_as_f32(p.x, p.x_dtype, (int64_t)r * p.ldx + c) - p.mean[r]) * p.rstd[r];
+      sg += dy * xh;
+      sb += dy;
+    }
+  red[0][rg][cl] = sg;
+  red[1][rg][cl] = sb;
+  __syncthreads();
+  if (rg == 0 && c < p.d) {
+    float g = (red[0][0][cl] + red[0][1][cl]) + (red[0][2][cl] + red[0][3][cl]);
+    float b = (red[1][0][cl] + red[1][1][cl]) + (red[1][2][cl] + red[1][3][cl]);
+    p.dgamma[c] = accumulate ? p.dgamma[c] + g : g;
+    p.dbeta[c] = accumulate ? p.dbeta[c] + b : b;
+  }
+}
+void launch_ln_bwd_params(const LnProb *probs, int n, int total_blocks, int accumulate, hipStream_t s) {
+  if (total_blocks <= 0) return;
+  hipLaunchKernelGGL(k_ln_bwd_params, dim3(total_blocks), dim3(256), 0, s, probs, n, accumulate);
+}
+
+// ------------------------------------------------------------------ mean-pool
+int pool_blocks(const PoolProb &p) {
+  int64_t e = p.backward ? (int64_t)p.batch * p.seq * p.d : (int64_t)p.batch * p.d;
+  return (int)((e + 255) / 256);
+}
+__global__ __launch_bounds__(256) void k_pool(const PoolProb *__restrict__ probs, int n) {
+  const int pi = find_prob(probs, n, blockIdx.x);
+  const PoolProb p = probs[pi];
+  const int64_t e = (int64_t)(blockIdx.x - p.blk_begin) * 256 + threadIdx.x;
+  if (!p.backward) {
+    if (e >= (int64_t)p.batch * p.d) return;
+    const int b = (int)(e / p.d), c = (int)(e % p.d);
+    float s = 0.0f;
+    for (int t = 0; t < p.seq; ++t) s += load_as_f32(p.src, p.src_dtype, ((int64_t)b * p.seq + t) * p.ld_src + c);
+    store_from_f32(p.dst, p.dst_dtype, (int64_t)b * p.ld_dst + c, s / (float)p.seq);
+  } else {
+    if (e >= (int64_t)p.batch * p.seq * p.d) return;
+    const int r = (int)(e / p.d), c = (int)(e % p.d);
+    float v = load_as_f32(p.src, p.src_dtype, (int64_t)(r / p.seq) * p.ld_src + c) / (float)p.seq;
+    store_from_f32(p.dst, p.dst_dtype, (int64_t)r * p.ld_dst + c, v);
+  }
+}
+void launch_pool(const PoolProb *probs, int n, int total_blocks, hipStream_t s) {
+  if (total_blocks <= 0) return;
+  hipLaunchKernelGGL(k_pool, dim3(total_blocks), dim3(256), 0, s, probs, n);
+}
+
+// ------------------------------------------------------------------ loss heads
+// kinds follow gpp_op_kind_t: 9 MSE, 10 softmax cross-entropy, 11 BCE with logits
+__device__ __forceinline__ float softplus_f(float y) { return fmaxf(y, 0.0f) + log1pf(__expf(-fabsf(y))); }
+__device__ __forceinline__ float sigmoid_f(float y) {
+  float e = __expf(-fabsf(y));
+  return y >= 0.0f ? 1.0f / (1.0f + e) : e / (1.0f + e);
+}
+
+// one workgroup of 1024 threads per loss operator; wave w takes rows w, w+16, ...
+__global__ __launch_bounds__(1024) void k_loss_fwd(const LossProb *__restrict__ probs) {
+  __shared__ float red[16];
+  const LossProb p = probs[blockIdx.x];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  float acc = 0.0f;
+  for (int r = w; r < p.rows; r += 16) {
+    const int64_t yo = (int64_t)r * p.ld_y;
+    if (p.kind == 10) {
+      float m = -INFINITY;
+      for (int c = lane; c < p.cols; c += 64) m = fmaxf(m, load_as_f32(p.y, p.y_dtype, yo + c));
+      m = wave_max(m);
+      float se = 0.0f;
+      for (int c = lane; c < p.cols; c += 64) se += __expf(load_as_f32(p.y, p.y_dtype, yo + c) - m);
+      se = wave_sum(se);
+      const int lab = ((const int32_t *)p.target)[(int64_t)r * p.ld_t];
+      if (lane == 0 && lab >= 0 && lab < p.cols) acc += (m + __logf(se)) - load_as_f32(p.y, p.y_dtype, yo + lab);
+    } else {
+      const float *t = (const float *)p.target + (int64_t)r * p.ld_t;
+      for (int c = lane; c < p.cols; c += 64) {
+        float y = load_as_f32(p.y, p.y_dtype, yo + c);
+        if (p.kind == 9) {
+          float d = y - t[c];
+          acc += d * d;
+        } else {
+          acc += softplus_f(y) - t[c] * y;
+        }
+      }
+    }
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) red[w] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float s = 0.0f;
+    for (int i = 0; i < 16; ++i) s += red[i];
+    p.loss[0] = s * p.scale;
+  }
+}
+void launch_loss_fwd(const LossProb *probs, int n, hipStream_t s) {
+  if (n <= 0) return;
+  hipLaunchKernelGGL(k_loss_fwd, dim3(n), dim3(1024), 0, s, probs);
+}
+
+int loss_bwd_blocks(const LossProb &p) { return (p.rows + 3) / 4; }
+// one wave per row; LossProb has no prefix field, so block ranges are passed as rows/4 per record in order
+__global__ __launch_bounds__(256) void k_loss_bwd(const LossProb *__restrict__ probs, int n) {
+  int blk = blockIdx.x, pi = 0;
+  for (; pi < n; ++pi) {
+    int nb = (probs[pi].rows + 3) / 4;
+    if (blk < nb) break;
+    blk -= nb;
+  }
+  if (pi >= n) return;
+  const LossProb p = probs[pi];
+  const int lane = threadIdx.x & 63;
+  const int r = blk * 4 + (threadIdx.x >> 6);
+  if (r >= p.rows) return;
+  const int64_t yo = (int64_t)r * p.ld_y, go = (int64_t)r * p.ld_dy;
+  if (p.kind == 10) {
+    float m = -INFINITY;
+    for (int c = lane; c < p.cols; c += 64) m = fmaxf(m, load_as_f32(p.y, p.y_dtype, yo + c));
+    m = wave_max(m);
+    float se = 0.0f;
+    for (int c = lane; c < p.cols; c += 64) se += __expf(load_as_f32(p.y, p.y_dtype, yo + c) - m);
+    const float inv = 1.0f / wave_sum(se);
+    const int lab = ((const int32_t *)p.target)[(int64_t)r * p.ld_t];
+    for (int c = lane; c < p.cols; c += 64) {
+      float pr = __expf(load_as_f32(p.y, p.y_dtype, yo + c) - m) * inv;
+      store_from_f32(p.dy, p.dy_dtype, go + c, p.scale * (pr - (c == lab ? 1.0f : 0.0f)));
+    }
+  } else {
+    const float *t = (const float *)p.target + (int64_t)r * p.ld_t;
+    for (int c = lane; c < p.cols; c += 64) {
+      float y = load_as_f32(p.y, p.y_dtype, yo + c);
+      float g = p.kind == 9 ? 2.0f * p.scale * (y - t[c]) : p.scale * (sigmoid_f(y) - t[c]);
+      store_from_f32(p.dy, p.dy_dtype, go + c, g);
+    }
+  }
+}
+void launch_loss_bwd(const LossProb *probs, int n, int total_blocks, hipStream_t s) {
+  if (total_blocks <= 0) return;
+  hipLaunchKernelGGL(k_loss_bwd, dim3(total_blocks), dim3(256), 0, s, probs, n);
+}
+
+__global__ void k_loss_sum(const float *losses, int n, float *out) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    float s = 0.0f;
+    for (int i = 0; i < n; ++i) s += losses[i];
+    out[0] = s;
+  }
+}
+void launch_loss_sum(const float *losses, int n, float *out, hipStream_t s) {
+  hipLaunchKernelGGL(k_loss_sum, dim3(1), dim3(64), 0, s, losses, n, out);
+}
+
+}  // namespace gpp

@@ -1,0 +1,1258 @@
+// Stage planner (host code).  See plan.h.
+#include "plan.h"
+
+#include <algorithm>
+#include <cstring>
+#include <functional>
+
+namespace gpp {
+
+// launch helpers defined next to their kernels
+int attn_max_seq();
+size_t interact_lds_bytes(int F, int d);
+
+static int64_t align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+static int64_t ld_of(int64_t features) { return align_up(features, 8); }
+static int64_t esize(int32_t dt) { return dt == DT_BF16 ? 2 : 4; }
+static bool is_float(int32_t dt) { return dt == DT_F32 || dt == DT_BF16; }
+
+#define FAIL(code, msg)      \
+  do {                       \
+    error = (msg);           \
+    return (code);           \
+  } while (0)
+
+// ===========================================================================
+// analysis: validation (condition C1: the stage's sub-graph is a DAG), shapes,
+// levels, fusion and aliasing decisions, buffer allocation
+// ===========================================================================
+gpp_status_t Plan::analyse(const gpp_stage_desc_t *desc) {
+  if (!desc || !desc->ops) FAIL(GPP_ERR_INVALID_ARG, "null descriptor");
+  if (desc->n_ops <= 0 || desc->n_ops > 65536) FAIL(GPP_ERR_INVALID_ARG, "n_ops out of range");
+  if (desc->micro_batch <= 0 || desc->micro_batch > (1 << 24)) FAIL(GPP_ERR_INVALID_ARG, "micro_batch out of range");
+  if (desc->in_flight_slots <= 0 || desc->in_flight_slots > 1024) FAIL(GPP_ERR_INVALID_ARG, "in_flight_slots out of range");
+  micro_batch = desc->micro_batch;
+  slots = desc->in_flight_slots;
+  flags = desc->flags;
+  const int n = desc->n_ops;
+  nodes.assign(n, Node());
+  for (int i = 0; i < n; ++i) {
+    Node &nd = nodes[i];
+    nd.d = desc->ops[i];
+    if (nd.d.kind < GPP_OP_INPUT || nd.d.kind > GPP_OP_LOSS_BCE_LOGITS) FAIL(GPP_ERR_INVALID_ARG, "unknown operator kind");
+    if (nd.d.n_in < 0 || nd.d.n_in > 4096 || (nd.d.n_in > 0 && !nd.d.in)) FAIL(GPP_ERR_INVALID_ARG, "bad producer list");
+    for (int k = 0; k < nd.d.n_in; ++k) {
+      int p = nd.d.in[k];
+      if (p < 0 || p >= n) FAIL(GPP_ERR_BAD_GRAPH, "dangling edge: producer id out of range");
+      nd.in.push_back(p);
+    }
+    nd.d.in = nullptr;
+  }
+  for (int i = 0; i < n; ++i)
+    for (int p : nodes[i].in) nodes[p].users.push_back(i);
+
+  // arity
+  for (int i = 0; i < n; ++i) {
+    const Node &nd = nodes[i];
+    int want = -1;
+    switch (nd.d.kind) {
+      case GPP_OP_INPUT: want = 0; break;
+      case GPP_OP_LINEAR: case GPP_OP_LAYERNORM: case GPP_OP_ATTENTION: case GPP_OP_MEANPOOL_SEQ:
+      case GPP_OP_DOT_INTERACT: want = 1; break;
+      case GPP_OP_ADD: case GPP_OP_EMBEDDING_BAG_SUM: case GPP_OP_LOSS_MSE: case GPP_OP_LOSS_CE:
+      case GPP_OP_LOSS_BCE_LOGITS: want = 2; break;
+      default: break;
+    }
+    if (want >= 0 && (int)nd.in.size() != want) FAIL(GPP_ERR_BAD_GRAPH, "operator has the wrong number of producers");
+    if (nd.d.kind == GPP_OP_CONCAT && nd.in.empty()) FAIL(GPP_ERR_BAD_GRAPH, "concat without producers");
+  }
+
+  // topological order (Kahn); leftovers mean a cycle
+  {
+    std::vector<int> indeg(n);
+    for (int i = 0; i < n; ++i) indeg[i] = (int)nodes[i].in.size();
+    std::vector<int> ready;
+    for (int i = 0; i < n; ++i)
+      if (!indeg[i]) ready.push_back(i);
+    size_t head = 0;
+    while (head < ready.size()) {
+      int i = ready[head++];
+      order.push_back(i);
+      for (int u : nodes[i].users)
+        if (--indeg[u] == 0) ready.push_back(u);
+    }
+    if ((int)order.size() != n) FAIL(GPP_ERR_BAD_GRAPH, "operator graph has a cycle");
+  }
+
+  // shapes, dtypes, levels
+  int max_level = 0;
+  for (int i : order) {
+    Node &nd = nodes[i];
+    const gpp_op_desc_t &d = nd.d;
+    auto in = [&](int k) -> Node & { return nodes[nd.in[k]]; };
+    nd.level = 0;
+    for (int p : nd.in) nd.level = std::max(nd.level, nodes[p].level + 1);
+    max_level = std::max(max_level, nd.level);
+    nd.is_loss = d.kind >= GPP_OP_LOSS_MSE;
+    if (!nd.is_loss && (d.out_features <= 0 || d.out_features > (1ll << 31) - 64)) FAIL(GPP_ERR_SHAPE, "out_features out of range");
+    if (d.dtype < GPP_F32 || d.dtype > GPP_I32) FAIL(GPP_ERR_INVALID_ARG, "bad dtype");
+    for (int p : nd.in)
+      if (nodes[p].is_loss) FAIL(GPP_ERR_BAD_GRAPH, "a loss operator cannot feed another operator");
+    nd.feat = d.out_features;
+    switch (d.kind) {
+      case GPP_OP_INPUT:
+        if (d.seq_len <= 0 || d.rows_extra < 0) FAIL(GPP_ERR_SHAPE, "input: seq_len must be >= 1, rows_extra >= 0");
+        nd.rows = micro_batch * d.seq_len + d.rows_extra;
+        if (d.requires_grad && !is_float(d.dtype)) FAIL(GPP_ERR_INVALID_ARG, "integer input cannot require a gradient");
+        break;
+      case GPP_OP_LINEAR:
+        nd.rows = in(0).rows;
+        if (in(0).feat != d.in_features) FAIL(GPP_ERR_SHAPE, "linear: in_features differs from the producer's features");
+        if (!is_float(d.dtype) || !is_float(d.param_dtype)) FAIL(GPP_ERR_UNSUPPORTED, "linear: float dtypes only");
+        if (in(0).d.dtype != d.param_dtype) FAIL(GPP_ERR_UNSUPPORTED, "linear: weight dtype must equal the producer's dtype");
+        if (d.act < GPP_ACT_NONE || d.act > GPP_ACT_GELU_ERF) FAIL(GPP_ERR_INVALID_ARG, "linear: bad activation");
+        break;
+      case GPP_OP_LAYERNORM:
+        nd.rows = in(0).rows;
+        if (in(0).feat != d.out_features) FAIL(GPP_ERR_SHAPE, "layernorm: feature count differs from the producer's");
+        if (!is_float(d.dtype) || !is_float(in(0).d.dtype)) FAIL(GPP_ERR_UNSUPPORTED, "layernorm: float dtypes only");
+        if (!(d.eps > 0)) FAIL(GPP_ERR_INVALID_ARG, "layernorm: eps must be positive");
+        break;
+      case GPP_OP_ATTENTION:
+        nd.rows = in(0).rows;
+        if (in(0).feat != 3 * d.out_features) FAIL(GPP_ERR_SHAPE, "attention: producer must have 3*out_features columns (Q|K|V)");
+        if (d.heads <= 0 || d.out_features % d.heads) FAIL(GPP_ERR_SHAPE, "attention: heads must divide out_features");
+        if (d.seq_len <= 0 || nd.rows != micro_batch * d.seq_len) FAIL(GPP_ERR_SHAPE, "attention: rows must equal micro_batch*seq_len");
+        if (d.out_features / d.heads > 128) FAIL(GPP_ERR_UNSUPPORTED, "attention: head dimension above 128");
+        if (d.seq_len > attn_max_seq()) FAIL(GPP_ERR_UNSUPPORTED, "attention: sequence too long for this build");
+        if (!is_float(d.dtype) || !is_float(in(0).d.dtype)) FAIL(GPP_ERR_UNSUPPORTED, "attention: float dtypes only");
+        break;
+      case GPP_OP_ADD:
+        nd.rows = in(0).rows;
+        if (in(0).rows != in(1).rows || in(0).feat != in(1).feat || in(0).feat != d.out_features)
+          FAIL(GPP_ERR_SHAPE, "add: operand shapes differ");
+        if (!is_float(d.dtype) || !is_float(in(0).d.dtype) || !is_float(in(1).d.dtype)) FAIL(GPP_ERR_UNSUPPORTED, "add: float dtypes only");
+        break;
+      case GPP_OP_MEANPOOL_SEQ:
+        if (d.seq_len <= 0 || in(0).rows != micro_batch * d.seq_len) FAIL(GPP_ERR_SHAPE, "meanpool: producer rows must equal micro_batch*seq_len");
+        if (in(0).feat != d.out_features) FAIL(GPP_ERR_SHAPE, "meanpool: feature count differs");
+        if (!is_float(d.dtype) || !is_float(in(0).d.dtype)) FAIL(GPP_ERR_UNSUPPORTED, "meanpool: float dtypes only");
+        nd.rows = micro_batch;
+        break;
+      case GPP_OP_CONCAT: {
+        int64_t w = 0;
+        nd.rows = in(0).rows;
+        for (size_t k = 0; k < nd.in.size(); ++k) {
+          if (in(k).rows != nd.rows) FAIL(GPP_ERR_SHAPE, "concat: producers have different row counts");
+          if (in(k).d.dtype != d.dtype) FAIL(GPP_ERR_UNSUPPORTED, "concat: producers must share the concat's dtype");
+          w += in(k).feat;
+        }
+        if (w != d.out_features) FAIL(GPP_ERR_SHAPE, "concat: out_features is not the sum of the producers' features");
+        if (!is_float(d.dtype)) FAIL(GPP_ERR_UNSUPPORTED, "concat: float dtypes only");
+        break;
+      }
+      case GPP_OP_EMBEDDING_BAG_SUM:
+        nd.rows = micro_batch;
+        if (in(0).d.kind != GPP_OP_INPUT || in(1).d.kind != GPP_OP_INPUT || in(0).d.dtype != GPP_I32 || in(1).d.dtype != GPP_I32)
+          FAIL(GPP_ERR_BAD_GRAPH, "embedding bag: producers must be i32 inputs (indices, offsets)");
+        if (d.bag_size <= 0 || in(0).feat != d.bag_size || in(0).rows != micro_batch) FAIL(GPP_ERR_SHAPE, "embedding bag: indices input must be [micro_batch, bag_size]");
+        if (in(1).feat != 1 || in(1).rows != micro_batch + 1) FAIL(GPP_ERR_SHAPE, "embedding bag: offsets input must have micro_batch+1 entries");
+        if (d.num_rows <= 0 || d.num_rows > (1ll << 31) - 1) FAIL(GPP_ERR_SHAPE, "embedding bag: num_rows out of range");
+        if (d.out_features > 256) FAIL(GPP_ERR_UNSUPPORTED, "embedding bag: dimension above 256");
+        if (micro_batch * d.bag_size > (1ll << 30)) FAIL(GPP_ERR_UNSUPPORTED, "embedding bag: too many indices");
+        if (!is_float(d.dtype)) FAIL(GPP_ERR_UNSUPPORTED, "embedding bag: float output only");
+        break;
+      case GPP_OP_DOT_INTERACT: {
+        nd.rows = in(0).rows;
+        if (d.in_features <= 0 || in(0).feat % d.in_features) FAIL(GPP_ERR_SHAPE, "interaction: producer features must be a multiple of the vector width");
+        int64_t F = in(0).feat / d.in_features;
+        if (d.out_features != d.in_features + F * (F - 1) / 2) FAIL(GPP_ERR_SHAPE, "interaction: out_features must be d + F(F-1)/2");
+        if (interact_lds_bytes((int)F, (int)d.in_features) > 60000) FAIL(GPP_ERR_UNSUPPORTED, "interaction: F*d too large");
+        if (!is_float(d.dtype) || !is_float(in(0).d.dtype)) FAIL(GPP_ERR_UNSUPPORTED, "interaction: float dtypes only");
+        break;
+      }
+      case GPP_OP_LOSS_MSE: case GPP_OP_LOSS_BCE_LOGITS:
+        if (in(1).d.kind != GPP_OP_INPUT || in(1).d.dtype != GPP_F32) FAIL(GPP_ERR_BAD_GRAPH, "loss: target must be an f32 input");
+        if (in(0).rows != in(1).rows || in(0).feat != in(1).feat) FAIL(GPP_ERR_SHAPE, "loss: prediction and target shapes differ");
+        if (!is_float(in(0).d.dtype)) FAIL(GPP_ERR_UNSUPPORTED, "loss: float prediction only");
+        break;
+      case GPP_OP_LOSS_CE:
+        if (in(1).d.kind != GPP_OP_INPUT || in(1).d.dtype != GPP_I32) FAIL(GPP_ERR_BAD_GRAPH, "cross-entropy: labels must be an i32 input");
+        if (in(0).rows != in(1).rows || in(1).feat != 1) FAIL(GPP_ERR_SHAPE, "cross-entropy: labels must be [rows, 1]");
+        if (!is_float(in(0).d.dtype)) FAIL(GPP_ERR_UNSUPPORTED, "loss: float prediction only");
+        break;
+    }
+    if (nd.rows > (1ll << 31) - 64) FAIL(GPP_ERR_SHAPE, "too many rows");
+  }
+  by_level.assign(max_level + 1, {});
+  for (int i : order) by_level[nodes[i].level].push_back(i);
+  for (auto &v : by_level) std::sort(v.begin(), v.end());
+
+  // roles
+  for (int i = 0; i < n; ++i) {
+    Node &nd = nodes[i];
+    if (nd.d.kind == GPP_OP_INPUT) {
+      nd.input_index = (int)input_ops.size();
+      input_ops.push_back(i);
+      if (nd.users.empty()) FAIL(GPP_ERR_BAD_GRAPH, "an input has no consumer");
+    } else if (nd.is_loss) {
+      nd.loss_index = (int)loss_ops.size();
+      loss_ops.push_back(i);
+    } else if (nd.users.empty()) {
+      nd.is_output = true;
+      nd.output_index = (int)output_ops.size();
+      output_ops.push_back(i);
+      if (!is_float(nd.d.dtype)) FAIL(GPP_ERR_UNSUPPORTED, "stage outputs must be float tensors");
+    }
+  }
+  if (loss_ops.empty() && output_ops.empty()) FAIL(GPP_ERR_BAD_GRAPH, "stage has neither an output nor a loss");
+  for (int i : order) {
+    Node &nd = nodes[i];
+    const int k = nd.d.kind;
+    nd.wants_grad = (k == GPP_OP_INPUT) ? nd.d.requires_grad != 0
+                                        : (k == GPP_OP_LINEAR || k == GPP_OP_LAYERNORM || k == GPP_OP_EMBEDDING_BAG_SUM);
+    if (k != GPP_OP_INPUT && !nd.is_loss)
+      for (int p : nd.in) nd.wants_grad = nd.wants_grad || nodes[p].wants_grad;
+    if (nd.is_loss) nd.wants_grad = false;
+    nd.gdtype = (k == GPP_OP_LINEAR) ? nd.d.param_dtype : nd.d.dtype;
+  }
+
+  // ---- fusion / aliasing decisions -------------------------------------
+  for (int i = 0; i < n; ++i) {
+    Node &nd = nodes[i];
+    // a LINEAR without activation whose only consumer is an ADD performs the add in its epilogue
+    if (nd.d.kind == GPP_OP_LINEAR && nd.d.act == GPP_ACT_NONE && nd.users.size() == 1) {
+      Node &a = nodes[nd.users[0]];
+      if (a.d.kind == GPP_OP_ADD && a.fused_by < 0 && a.in[0] != a.in[1]) {
+        int other = a.in[0] == i ? a.in[1] : a.in[0];
+        if (nodes[other].level < nd.level && nodes[other].d.kind != GPP_OP_INPUT) {
+          nd.fused_add = nd.users[0];
+          a.fused_by = i;
+        } else if (nodes[other].level < nd.level) {  // inputs are staged before level 1, also fine
+          nd.fused_add = nd.users[0];
+          a.fused_by = i;
+        }
+      }
+    }
+  }
+  for (int i = 0; i < n; ++i) {
+    Node &c = nodes[i];
+    if (c.d.kind != GPP_OP_CONCAT) continue;
+    int64_t col = 0;
+    for (int p : c.in) {
+      Node &m = nodes[p];
+      const bool sole = m.users.size() == 1 && std::count(c.in.begin(), c.in.end(), p) == 1;
+      if (sole && m.fused_add < 0 && m.d.kind != GPP_OP_CONCAT) {
+        m.val_parent = i;
+        m.val_col = col;
+      }
+      if (sole && m.gdtype == c.gdtype && m.wants_grad) {
+        m.gout_parent = i;
+        m.gout_col = col;
+      }
+      col += m.feat;
+    }
+  }
+  for (int i = 0; i < n; ++i) {
+    Node &a = nodes[i];
+    if (a.d.kind != GPP_OP_ADD || a.in[0] == a.in[1]) continue;
+    for (int p : a.in) {
+      Node &m = nodes[p];
+      const bool plain = !(m.d.kind == GPP_OP_LINEAR && m.d.act != GPP_ACT_NONE);
+      if (m.users.size() == 1 && plain && m.gdtype == a.gdtype && m.wants_grad && m.d.kind != GPP_OP_INPUT) {
+        m.gout_parent = i;
+        m.gout_col = 0;
+      }
+    }
+  }
+
+  // ---- buffers ----------------------------------------------------------
+  int64_t slot_top = 0, shared_top = 0;
+  auto alloc = [&](int32_t space, int64_t rows, int64_t cols, int32_t dt) {
+    Buf b;
+    b.space = space;
+    b.ld = ld_of(cols);
+    b.dtype = dt;
+    int64_t &top = space == SP_SLOT ? slot_top : shared_top;
+    b.off = top;
+    top = align_up(top + rows * b.ld * esize(dt), 256);
+    return b;
+  };
+  // values: parents (concats) first so members can alias into them
+  std::function<void(int)> alloc_val = [&](int i) {
+    Node &nd = nodes[i];
+    if (nd.val.valid() || nd.is_loss) return;
+    if (nd.d.kind == GPP_OP_LINEAR && nd.fused_add >= 0) return;  // lives in the ADD's buffer
+    if (nd.val_parent >= 0) {
+      alloc_val(nd.val_parent);
+      const Node &c = nodes[nd.val_parent];
+      nd.val = c.val;
+      nd.val.off += nd.val_col * esize(c.val.dtype);
+      return;
+    }
+    nd.val = alloc(SP_SLOT, nd.rows, nd.feat, nd.d.dtype);
+  };
+  for (int i = 0; i < n; ++i) alloc_val(i);
+  std::function<void(int)> alloc_gout = [&](int i) {
+    Node &nd = nodes[i];
+    if (nd.gout.valid() || nd.is_loss || !nd.wants_grad) return;
+    if (nd.gout_parent >= 0) {
+      alloc_gout(nd.gout_parent);
+      const Node &c = nodes[nd.gout_parent];
+      nd.gout = c.gout;
+      nd.gout.off += nd.gout_col * esize(c.gout.dtype);
+      return;
+    }
+    nd.gout = alloc(SP_SHARED, nd.rows, nd.feat, nd.gdtype);
+  };
+  for (int i = 0; i < n; ++i) alloc_gout(i);
+  for (int i = 0; i < n; ++i) {
+    Node &nd = nodes[i];
+    const gpp_op_desc_t &d = nd.d;
+    if (d.kind == GPP_OP_LINEAR && d.act == GPP_ACT_GELU_ERF) nd.aux = alloc(SP_SLOT, nd.rows, nd.feat, d.dtype);
+    if (d.kind == GPP_OP_LAYERNORM) {
+      nd.stat0 = alloc(SP_SLOT, 1, nd.rows, DT_F32);
+      nd.stat1 = alloc(SP_SLOT, 1, nd.rows, DT_F32);
+    }
+    if (d.kind == GPP_OP_ATTENTION) {
+      nd.stat0 = alloc(SP_SLOT, 1, micro_batch * d.heads * d.seq_len, DT_F32);    // log-sum-exp
+      nd.stat1 = alloc(SP_SHARED, 1, micro_batch * d.heads * d.seq_len, DT_F32);  // rowsum(dO*O)
+    }
+    if (d.kind == GPP_OP_EMBEDDING_BAG_SUM) {
+      const int64_t cap = micro_batch * d.bag_size;
+      nd.extra = alloc(SP_SLOT, 1, cap, DT_I32);  // bag id of each position
+      int bits = 0;
+      while ((1ll << bits) < d.num_rows) ++bits;
+      const int passes = std::max(1, (bits + emb_radix_bits() - 1) / emb_radix_bits());
+      const int sort_blocks = (int)((cap + emb_sort_chunk() - 1) / emb_sort_chunk());
+      nd.more.clear();
+      for (int k = 0; k < 4; ++k) nd.more.push_back(alloc(SP_SHARED, 1, cap, DT_I32));            // keys a/b, pos a/b
+      nd.more.push_back(alloc(SP_SHARED, 1, (int64_t)(1 << emb_radix_bits()) * sort_blocks, DT_I32));  // hist
+      nd.more.push_back(alloc(SP_SHARED, 1, cap, DT_I32));      // unique rows
+      nd.more.push_back(alloc(SP_SHARED, 1, cap + 1, DT_I32));  // segment offsets
+      nd.more.push_back(alloc(SP_SHARED, 1, 8, DT_I32));        // counts
+      nd.emb_passes = passes;
+      nd.emb_sort_blocks = sort_blocks;
+    }
+  }
+  loss_scalars = alloc(SP_SLOT, 1, std::max<int64_t>(1, (int64_t)loss_ops.size()), DT_F32);
+  slot_bytes = align_up(slot_top, 256);
+  shared_bytes = align_up(shared_top, 256);
+  return GPP_OK;
+}
+
+void Plan::layout() {
+  off_flags = 0;
+  off_tables = 256;
+  off_slots = align_up(off_tables + (int64_t)slots * table_bytes, 256);
+  off_shared = off_slots + (int64_t)slots * slot_bytes;
+  total_bytes = off_shared + shared_bytes + tmp_bytes;
+}
+
+// ===========================================================================
+// emission
+// ===========================================================================
+namespace {
+
+struct Emitter {
+  Plan &pl;
+  int slot;
+  char *ws;
+  std::vector<Step> *steps = nullptr;
+  // gradient assembly state per node
+  enum { G_EMPTY, G_ADDEND, G_WRITTEN };
+  std::vector<int> gstate;
+  std::vector<Buf> gaddend;
+  std::vector<char> dz_ready;
+  std::vector<int> written_level;   // level whose launches first wrote the node's gradient
+  int cur_level = 0;
+  int64_t shared_tmp_top;
+
+  Emitter(Plan &p, int s, char *w) : pl(p), slot(s), ws(w) { shared_tmp_top = 0; }
+
+  void *ptr(const Buf &b) const {
+    if (!b.valid()) return nullptr;
+    if (b.space == SP_ABS) return (void *)b.off;
+    if (b.space == SP_SLOT) return ws + pl.off_slots + (int64_t)slot * pl.slot_bytes + b.off;
+    return ws + pl.off_shared + b.off;
+  }
+  template <typename T>
+  int64_t push_table(const std::vector<T> &recs) {
+    int64_t off = align_up((int64_t)pl.blob.size(), 64);
+    pl.blob.resize(off + recs.size() * sizeof(T));
+    if (!recs.empty()) memcpy(pl.blob.data() + off, recs.data(), recs.size() * sizeof(T));
+    return off;
+  }
+  Step &add_step(int kern, int64_t table_off, int n, int blocks) {
+    Step s;
+    memset(&s, 0, sizeof(s));
+    s.kern = kern;
+    s.table_off = table_off;
+    s.n = n;
+    s.blocks = blocks;
+    s.launches = 1;
+    steps->push_back(s);
+    return steps->back();
+  }
+
+  // ---- elementwise helper ------------------------------------------------
+  EltProb elt(const Buf &src, const Buf &dst, int64_t rows, int64_t cols) {
+    EltProb e;
+    memset(&e, 0, sizeof(e));
+    e.src = ptr(src);
+    e.dst = ptr(dst);
+    e.ld_src = src.ld;
+    e.ld_dst = dst.ld;
+    e.rows = (int32_t)rows;
+    e.cols = (int32_t)cols;
+    e.src_dtype = src.dtype;
+    e.dst_dtype = dst.dtype;
+    e.ext_src = e.ext_dst = -1;
+    return e;
+  }
+  void with_addend(EltProb &e, const Buf &a) {
+    e.addend = ptr(a);
+    e.ld_add = a.ld;
+    e.add_dtype = a.dtype;
+  }
+  void emit_elt(std::vector<EltProb> &recs, int ext_kind = EXT_NONE, int ext_base = 0) {
+    if (recs.empty()) return;
+    int blocks = 0;
+    for (auto &e : recs) {
+      e.blk_begin = blocks;
+      blocks += elt_blocks(e.rows, e.cols);
+    }
+    Step &s = add_step(K_ELT, push_table(recs), (int)recs.size(), blocks);
+    s.ext_kind = ext_kind;
+    s.ext_base = ext_base;
+    recs.clear();
+  }
+
+  // ---- gradient targets ----------------------------------------------------
+  struct Target {
+    Buf dst, addend;      // addend valid: kernel must add it (may equal dst)
+    bool post = false;    // kernel wrote into a temporary `dst`; accumulate into `final` afterwards
+    Buf final_dst;
+  };
+  std::vector<EltProb> post_copies;
+
+  Buf tmp_like(const Node &nd) {
+    Buf b = nd.gout;
+    b.space = SP_SHARED;
+    b.ld = ld_of(nd.feat);
+    b.off = pl.shared_bytes + shared_tmp_top;  // temporaries sit behind the planned shared region
+    shared_tmp_top = align_up(shared_tmp_top + nd.rows * b.ld * esize(b.dtype), 256);
+    return b;
+  }
+  void copy_now(const Buf &src, const Buf &dst, const Node &nd, bool accumulate) {
+    std::vector<EltProb> r;
+    EltProb e = elt(src, dst, nd.rows, nd.feat);
+    if (accumulate) with_addend(e, dst);
+    r.push_back(e);
+    emit_elt(r);
+  }
+  Target acquire(int p, bool can_addend) {
+    Node &nd = pl.nodes[p];
+    Target t;
+    t.dst = nd.gout;
+    if (gstate[p] == G_ADDEND && !can_addend) {
+      copy_now(gaddend[p], nd.gout, nd, false);
+      gstate[p] = G_WRITTEN;
+      written_level[p] = cur_level + 1;   // already launched
+    }
+    if (gstate[p] == G_EMPTY) {
+      gstate[p] = G_WRITTEN;
+      written_level[p] = cur_level;
+    } else if (gstate[p] == G_ADDEND) {
+      t.addend = gaddend[p];
+      gstate[p] = G_WRITTEN;
+      written_level[p] = cur_level;
+    } else if (can_addend && written_level[p] != cur_level) {
+      t.addend = nd.gout;   // accumulate in place: every earlier writer ran in an earlier launch
+    } else {                // a launch of this same level also writes it: go through a temporary
+      t.post = true;
+      t.final_dst = nd.gout;
+      t.dst = tmp_like(nd);
+      EltProb e = elt(t.dst, t.final_dst, nd.rows, nd.feat);
+      with_addend(e, t.final_dst);
+      post_copies.push_back(e);
+    }
+    return t;
+  }
+  // accumulate-copies run after the level's kernels; two copies into one destination never share a launch
+  void flush_post() {
+    while (!post_copies.empty()) {
+      std::vector<EltProb> now, later;
+      for (auto &e : post_copies) {
+        bool clash = false;
+        for (auto &o : now) clash = clash || o.dst == e.dst;
+        (clash ? later : now).push_back(e);
+      }
+      emit_elt(now);
+      post_copies.swap(later);
+    }
+  }
+  // a consumer hands `view` through unchanged (ADD, CONCAT)
+  void pass_through(int p, const Buf &view) {
+    Node &nd = pl.nodes[p];
+    if (!nd.wants_grad || nd.gout_parent >= 0) return;
+    if (gstate[p] == G_EMPTY) {
+      gstate[p] = G_ADDEND;
+      gaddend[p] = view;
+      return;
+    }
+    if (gstate[p] == G_ADDEND) {
+      copy_now(gaddend[p], nd.gout, nd, false);
+      gstate[p] = G_WRITTEN;
+      written_level[p] = cur_level + 1;   // already launched
+    }
+    if (written_level[p] == cur_level) {  // first writer is a kernel of this level, not launched yet
+      EltProb e = elt(view, nd.gout, nd.rows, nd.feat);
+      with_addend(e, nd.gout);
+      post_copies.push_back(e);
+    } else {
+      copy_now(view, nd.gout, nd, true);
+    }
+  }
+
+  // ---- GEMM grouping ---------------------------------------------------------
+  void emit_gemms(std::vector<GemmProb> &recs) {
+    if (recs.empty()) return;
+    // split by kernel and operand dtype; each group is one launch
+    for (int use_mfma = 0; use_mfma < 2; ++use_mfma)
+      for (int dt = 0; dt < 2; ++dt)
+        for (int form = 0; form < 3; ++form) {
+          std::vector<GemmProb> g;
+          for (auto &r : recs) {
+            bool m = !(pl.flags & 1) && r.in_dtype == DT_BF16 && gemm_mfma_supported(r);
+            if ((int)m == use_mfma && r.in_dtype == dt && (r.form == form || !use_mfma)) g.push_back(r);
+          }
+          if (!use_mfma && form > 0) continue;  // the generic kernel mixes forms in one launch
+          if (g.empty()) continue;
+          int blocks = 0;
+          for (auto &r : g) {
+            r.blk_begin = blocks;
+            r.split_k = 1;
+            blocks += use_mfma ? gemm_mfma_tiles(r.form, r.M, r.N, r.K, &r.tiles_n) : gemm_generic_tiles(r.M, r.N, &r.tiles_n);
+          }
+          Step &s = add_step(use_mfma ? K_GEMM_MFMA : K_GEMM_GENERIC, push_table(g), (int)g.size(), blocks);
+          s.a0 = dt;
+          s.a1 = form;
+        }
+    recs.clear();
+  }
+
+  gpp_status_t run();
+  void forward();
+  void backward();
+};
+
+// ---------------------------------------------------------------------------
+void Emitter::forward() {
+  steps = &pl.fwd;
+  steps->clear();
+  auto &N = pl.nodes;
+
+  // ingest: copy the caller's dense inputs into the (padded) stash buffers
+  {
+    std::vector<EltProb> recs;
+    int base = 0;
+    for (size_t k = 0; k < pl.input_ops.size(); ++k) {
+      Node &nd = N[pl.input_ops[k]];
+      if ((int)k - base == 64) {
+        emit_elt(recs, EXT_INPUTS, base);
+        base = (int)k;
+      }
+      Buf src;
+      src.space = SP_ABS;
+      src.ld = nd.feat;
+      src.dtype = nd.d.dtype;
+      EltProb e = elt(src, nd.val, nd.rows, nd.feat);
+      e.ext_src = (int32_t)(k - base);
+      recs.push_back(e);
+    }
+    emit_elt(recs, EXT_INPUTS, base);
+  }
+
+  for (size_t L = 1; L < pl.by_level.size(); ++L) {
+    std::vector<GemmProb> gemms;
+    std::vector<LnProb> lns;
+    std::vector<AttnProb> attns;
+    std::vector<EltProb> elts;
+    std::vector<PoolProb> pools;
+    std::vector<EmbProb> embs;
+    std::vector<InteractProb> inters;
+    std::vector<LossProb> losses;
+    for (int i : pl.by_level[L]) {
+      Node &nd = N[i];
+      const gpp_op_desc_t &d = nd.d;
+      switch (d.kind) {
+        case GPP_OP_LINEAR: {
+          const Node &x = N[nd.in[0]];
+          GemmProb g;
+          memset(&g, 0, sizeof(g));
+          g.form = FORM_FWD;
+          g.A = ptr(x.val);
+          g.lda = x.val.ld;
+          g.B = d.param[0];
+          g.ldb = ld_of(d.in_features);
+          g.bias = d.has_bias ? (const float *)d.param[1] : nullptr;
+          g.M = (int32_t)nd.rows;
+          g.N = (int32_t)nd.feat;
+          g.K = (int32_t)d.in_features;
+          g.act = d.act;
+          g.in_dtype = d.param_dtype;
+          Buf out = nd.val;
+          if (nd.fused_add >= 0) {
+            const Node &a = N[nd.fused_add];
+            const Node &r = N[a.in[0] == i ? a.in[1] : a.in[0]];
+            out = a.val;
+            g.res = ptr(r.val);
+            g.ldres = r.val.ld;
+            g.res_dtype = r.val.dtype;
+          }
+          g.C = ptr(out);
+          g.ldc = out.ld;
+          g.c_dtype = out.dtype;
+          if (nd.aux.valid()) {
+            g.aux = ptr(nd.aux);
+            g.ldaux = nd.aux.ld;
+            g.aux_dtype = nd.aux.dtype;
+          }
+          gemms.push_back(g);
+          break;
+        }
+        case GPP_OP_LAYERNORM: {
+          const Node &x = N[nd.in[0]];
+          LnProb l;
+          memset(&l, 0, sizeof(l));
+          l.x = ptr(x.val);
+          l.ldx = x.val.ld;
+          l.x_dtype = x.val.dtype;
+          l.y = ptr(nd.val);
+          l.ldy = nd.val.ld;
+          l.y_dtype = nd.val.dtype;
+          l.gamma = (const float *)d.param[0];
+          l.beta = (const float *)d.param[1];
+          l.mean = (float *)ptr(nd.stat0);
+          l.rstd = (float *)ptr(nd.stat1);
+          l.rows = (int32_t)nd.rows;
+          l.d = (int32_t)nd.feat;
+          l.eps = (float)d.eps;
+          lns.push_back(l);
+          break;
+        }
+        case GPP_OP_ATTENTION: {
+          const Node &x = N[nd.in[0]];
+          AttnProb a;
+          memset(&a, 0, sizeof(a));
+          a.qkv = ptr(x.val);
+          a.ld_qkv = x.val.ld;
+          a.dtype = x.val.dtype;
+          a.out = ptr(nd.val);
+          a.ld_out = nd.val.ld;
+          a.out_dtype = nd.val.dtype;
+          a.lse = (float *)ptr(nd.stat0);
+          a.batch = (int32_t)pl.micro_batch;
+          a.heads = d.heads;
+          a.seq = d.seq_len;
+          a.dh = (int32_t)(nd.feat / d.heads);
+          attns.push_back(a);
+          break;
+        }
+        case GPP_OP_ADD: {
+          if (nd.fused_by >= 0) break;
+          EltProb e = elt(N[nd.in[0]].val, nd.val, nd.rows, nd.feat);
+          with_addend(e, N[nd.in[1]].val);
+          elts.push_back(e);
+          break;
+        }
+        case GPP_OP_MEANPOOL_SEQ: {
+          const Node &x = N[nd.in[0]];
+          PoolProb p;
+          memset(&p, 0, sizeof(p));
+          p.src = ptr(x.val);
+          p.ld_src = x.val.ld;
+          p.src_dtype = x.val.dtype;
+          p.dst = ptr(nd.val);
+          p.ld_dst = nd.val.ld;
+          p.dst_dtype = nd.val.dtype;
+          p.batch = (int32_t)pl.micro_batch;
+          p.seq = d.seq_len;
+          p.d = (int32_t)nd.feat;
+          pools.push_back(p);
+          break;
+        }
+        case GPP_OP_CONCAT: {
+          int64_t col = 0;
+          for (int p : nd.in) {
+            const Node &m = N[p];
+            if (m.val_parent != i) {  // member could not be produced in place
+              Buf dst = nd.val;
+              dst.off += col * esize(dst.dtype);
+              elts.push_back(elt(m.fused_add >= 0 ? N[m.fused_add].val : m.val, dst, m.rows, m.feat));
+            }
+            col += m.feat;
+          }
+          break;
+        }
+        case GPP_OP_EMBEDDING_BAG_SUM: {
+          EmbProb e;
+          memset(&e, 0, sizeof(e));
+          e.table = (const float *)d.param[0];
+          e.ld_table = ld_of(nd.feat);
+          e.indices = (const int32_t *)ptr(N[nd.in[0]].val);
+          e.offsets = (const int32_t *)ptr(N[nd.in[1]].val);
+          e.out = ptr(nd.val);
+          e.ld_out = nd.val.ld;
+          e.out_dtype = nd.val.dtype;
+          e.bag_of = (int32_t *)ptr(nd.extra);
+          e.n_bags = (int32_t)pl.micro_batch;
+          e.capacity = (int32_t)(pl.micro_batch * d.bag_size);
+          e.dim = (int32_t)nd.feat;
+          e.num_rows = (int32_t)d.num_rows;
+          embs.push_back(e);
+          break;
+        }
+        case GPP_OP_DOT_INTERACT: {
+          const Node &x = N[nd.in[0]];
+          InteractProb p;
+          memset(&p, 0, sizeof(p));
+          p.x = ptr(x.val);
+          p.ld_x = x.val.ld;
+          p.x_dtype = x.val.dtype;
+          p.y = ptr(nd.val);
+          p.ld_y = nd.val.ld;
+          p.y_dtype = nd.val.dtype;
+          p.batch = (int32_t)nd.rows;
+          p.d = (int32_t)d.in_features;
+          p.F = (int32_t)(x.feat / d.in_features);
+          inters.push_back(p);
+          break;
+        }
+        case GPP_OP_LOSS_MSE: case GPP_OP_LOSS_CE: case GPP_OP_LOSS_BCE_LOGITS: {
+          const Node &y = N[nd.in[0]];
+          const Node &t = N[nd.in[1]];
+          const Buf &yv = y.fused_add >= 0 ? N[y.fused_add].val : y.val;
+          LossProb l;
+          memset(&l, 0, sizeof(l));
+          l.y = ptr(yv);
+          l.ld_y = yv.ld;
+          l.y_dtype = yv.dtype;
+          l.target = ptr(t.val);
+          l.ld_t = t.val.ld;
+          l.loss = (float *)ptr(pl.loss_scalars) + nd.loss_index;
+          l.rows = (int32_t)y.rows;
+          l.cols = (int32_t)y.feat;
+          l.kind = d.kind;
+          l.scale = (float)d.loss_scale;
+          losses.push_back(l);
+          break;
+        }
+        default: break;
+      }
+    }
+    emit_gemms(gemms);
+    if (!lns.empty()) {
+      int blocks = 0;
+      for (auto &l : lns) {
+        l.blk_begin = blocks;
+        blocks += (l.rows + ln_rows_per_block() - 1) / ln_rows_per_block();
+      }
+      add_step(K_LN_FWD, push_table(lns), (int)lns.size(), blocks);
+    }
+    if (!attns.empty()) {
+      int blocks = 0, ms = 0;
+      for (auto &a : attns) {
+        a.blk_begin = blocks;
+        blocks += attn_blocks(a.batch, a.heads, a.seq);
+        ms = std::max(ms, a.seq);
+      }
+      add_step(K_ATTN_FWD, push_table(attns), (int)attns.size(), blocks).a0 = ms;
+    }
+    emit_elt(elts);
+    if (!pools.empty()) {
+      int blocks = 0;
+      for (auto &p : pools) {
+        p.blk_begin = blocks;
+        blocks += pool_blocks(p);
+      }
+      add_step(K_POOL, push_table(pools), (int)pools.size(), blocks);
+    }
+    if (!embs.empty()) {
+      int blocks = 0;
+      for (auto &e : embs) {
+        e.blk_begin = blocks;
+        blocks += emb_fwd_blocks(e.n_bags);
+      }
+      add_step(K_EMB_FWD, push_table(embs), (int)embs.size(), blocks);
+    }
+    if (!inters.empty()) {
+      int blocks = 0, mf = 0, md = 0;
+      for (auto &p : inters) {
+        p.blk_begin = blocks;
+        blocks += p.batch;
+        mf = std::max(mf, p.F);
+        md = std::max(md, p.d);
+      }
+      Step &s = add_step(K_INTERACT_FWD, push_table(inters), (int)inters.size(), blocks);
+      s.a0 = mf;
+      s.a1 = md;
+    }
+    if (!losses.empty()) add_step(K_LOSS_FWD, push_table(losses), (int)losses.size(), (int)losses.size());
+  }
+
+  // egress: stage outputs to the caller's dense buffers, loss scalars summed
+  {
+    std::vector<EltProb> recs;
+    int base = 0;
+    for (size_t k = 0; k < pl.output_ops.size(); ++k) {
+      Node &nd = N[pl.output_ops[k]];
+      if ((int)k - base == 64) {
+        emit_elt(recs, EXT_OUTPUTS, base);
+        base = (int)k;
+      }
+      Buf dst;
+      dst.space = SP_ABS;
+      dst.ld = nd.feat;
+      dst.dtype = nd.d.dtype;
+      const Buf &v = nd.fused_add >= 0 ? N[nd.fused_add].val : nd.val;
+      EltProb e = elt(v, dst, nd.rows, nd.feat);
+      e.ext_dst = (int32_t)(k - base);
+      recs.push_back(e);
+    }
+    emit_elt(recs, EXT_OUTPUTS, base);
+    add_step(K_LOSS_SUM, 0, (int)pl.loss_ops.size(), 1);
+  }
+}
+
+// ---------------------------------------------------------------------------
+void Emitter::backward() {
+  steps = &pl.bwd;
+  steps->clear();
+  auto &N = pl.nodes;
+  const int n = (int)N.size();
+  gstate.assign(n, G_EMPTY);
+  gaddend.assign(n, Buf());
+  dz_ready.assign(n, 0);
+  written_level.assign(n, -1);
+  post_copies.clear();
+
+  // ingest the caller's output gradients
+  {
+    std::vector<EltProb> recs;
+    int base = 0;
+    for (size_t k = 0; k < pl.output_ops.size(); ++k) {
+      Node &nd = N[pl.output_ops[k]];
+      if ((int)k - base == 64) {
+        emit_elt(recs, EXT_GRAD_OUTPUTS, base);
+        base = (int)k;
+      }
+      if (!nd.wants_grad) continue;
+      Buf src;
+      src.space = SP_ABS;
+      src.ld = nd.feat;
+      src.dtype = nd.d.dtype;
+      EltProb e = elt(src, nd.gout, nd.rows, nd.feat);
+      e.ext_src = (int32_t)(k - base);
+      recs.push_back(e);
+      gstate[pl.output_ops[k]] = G_WRITTEN;
+      written_level[pl.output_ops[k]] = (int)pl.by_level.size();
+    }
+    emit_elt(recs, EXT_GRAD_OUTPUTS, base);
+  }
+
+  auto mask_source = [&](const Node &p) -> Buf { return p.d.act == GPP_ACT_GELU_ERF ? p.aux : p.val; };
+  // a member that shares its consumer's gradient buffer is "written" once the consumer is
+  std::function<int(int)> state_of = [&](int i) -> int {
+    return N[i].gout_parent >= 0 ? state_of(N[i].gout_parent) : gstate[i];
+  };
+
+  for (int L = (int)pl.by_level.size() - 1; L >= 0; --L) {
+    cur_level = L;
+    // 1. losses seed the gradient of their prediction
+    {
+      std::vector<LossProb> losses;
+      int blocks = 0;
+      for (int i : pl.by_level[L]) {
+        Node &nd = N[i];
+        if (!nd.is_loss) continue;
+        Node &y = N[nd.in[0]];
+        if (!y.wants_grad) continue;
+        const Node &t = N[nd.in[1]];
+        const Buf &yv = y.fused_add >= 0 ? N[y.fused_add].val : y.val;
+        Target tg = acquire(nd.in[0], false);
+        LossProb l;
+        memset(&l, 0, sizeof(l));
+        l.y = ptr(yv);
+        l.ld_y = yv.ld;
+        l.y_dtype = yv.dtype;
+        l.target = ptr(t.val);
+        l.ld_t = t.val.ld;
+        l.dy = ptr(tg.dst);
+        l.ld_dy = tg.dst.ld;
+        l.dy_dtype = tg.dst.dtype;
+        l.rows = (int32_t)y.rows;
+        l.cols = (int32_t)y.feat;
+        l.kind = nd.d.kind;
+        l.scale = (float)nd.d.loss_scale;
+        blocks += loss_bwd_blocks(l);
+        losses.push_back(l);
+      }
+      if (!losses.empty()) add_step(K_LOSS_BWD, push_table(losses), (int)losses.size(), blocks);
+      flush_post();
+    }
+
+    // 2. complete the gradients of this level's operators
+    std::vector<int> live;
+    {
+      std::vector<EltProb> copies, masks;
+      for (int i : pl.by_level[L]) {
+        Node &nd = N[i];
+        if (nd.is_loss || !nd.wants_grad) continue;
+        if (nd.gout_parent < 0 && gstate[i] == G_ADDEND) {
+          copies.push_back(elt(gaddend[i], nd.gout, nd.rows, nd.feat));
+          gstate[i] = G_WRITTEN;
+        }
+        if (state_of(i) != G_WRITTEN) continue;  // no gradient reaches this operator
+        live.push_back(i);
+        if (nd.d.kind == GPP_OP_LINEAR && nd.d.act != GPP_ACT_NONE && !dz_ready[i]) {
+          EltProb e = elt(mask_source(nd), nd.gout, nd.rows, nd.feat);
+          e.mode = 1;
+          e.act = nd.d.act;
+          masks.push_back(e);
+        }
+      }
+      emit_elt(copies);
+      emit_elt(masks);
+    }
+
+    // 3. per-kind grouped backward launches
+    std::vector<ColsumProb> colsums;
+    std::vector<GemmProb> gemms;
+    std::vector<LnProb> lns;
+    std::vector<AttnProb> attns;
+    std::vector<PoolProb> pools;
+    std::vector<EmbProb> embs;
+    std::vector<InteractProb> inters;
+    for (int i : live) {
+      Node &nd = N[i];
+      const gpp_op_desc_t &d = nd.d;
+      switch (d.kind) {
+        case GPP_OP_LINEAR: {
+          const Node &x = N[nd.in[0]];
+          if (d.has_bias) {
+            ColsumProb c;
+            memset(&c, 0, sizeof(c));
+            c.src = ptr(nd.gout);
+            c.ld = nd.gout.ld;
+            c.dtype = nd.gout.dtype;
+            c.out = (float *)d.grad[1];
+            c.rows = (int32_t)nd.rows;
+            c.cols = (int32_t)nd.feat;
+            colsums.push_back(c);
+          }
+          GemmProb w;
+          memset(&w, 0, sizeof(w));
+          w.form = FORM_DW;
+          w.A = ptr(nd.gout);
+          w.lda = nd.gout.ld;
+          w.B = ptr(x.val);
+          w.ldb = x.val.ld;
+          w.C = d.grad[0];
+          w.ldc = ld_of(d.in_features);
+          w.c_dtype = DT_F32;
+          w.M = (int32_t)nd.feat;           // rows of dW = out_features
+          w.N = (int32_t)d.in_features;     // columns of dW
+          w.K = (int32_t)nd.rows;           // contraction over the micro-batch rows
+          w.in_dtype = d.param_dtype;
+          gemms.push_back(w);
+          if (x.wants_grad) {
+            Target tg = acquire(nd.in[0], true);
+            GemmProb g;
+            memset(&g, 0, sizeof(g));
+            g.form = FORM_DX;
+            g.A = ptr(nd.gout);
+            g.lda = nd.gout.ld;
+            g.B = d.param[0];
+            g.ldb = ld_of(d.in_features);
+            g.C = ptr(tg.dst);
+            g.ldc = tg.dst.ld;
+            g.c_dtype = tg.dst.dtype;
+            g.M = (int32_t)nd.rows;
+            g.N = (int32_t)d.in_features;
+            g.K = (int32_t)nd.feat;
+            g.in_dtype = d.param_dtype;
+            if (tg.addend.valid()) {
+              g.res = ptr(tg.addend);
+              g.ldres = tg.addend.ld;
+              g.res_dtype = tg.addend.dtype;
+            }
+            // fold the producer's activation derivative into this epilogue when we are its only consumer
+            if (x.d.kind == GPP_OP_LINEAR && x.d.act != GPP_ACT_NONE && x.users.size() == 1 && x.gout_parent < 0) {
+              Buf ms = mask_source(x);
+              g.act = x.d.act;
+              g.aux = ptr(ms);
+              g.ldaux = ms.ld;
+              g.aux_dtype = ms.dtype;
+              dz_ready[nd.in[0]] = 1;
+            }
+            gemms.push_back(g);
+          }
+          break;
+        }
+        case GPP_OP_LAYERNORM: {
+          const Node &x = N[nd.in[0]];
+          LnProb l;
+          memset(&l, 0, sizeof(l));
+          l.x = ptr(x.val);
+          l.ldx = x.val.ld;
+          l.x_dtype = x.val.dtype;
+          l.dy = ptr(nd.gout);
+          l.lddy = nd.gout.ld;
+          l.dy_dtype = nd.gout.dtype;
+          l.gamma = (const float *)d.param[0];
+          l.mean = (float *)ptr(nd.stat0);
+          l.rstd = (float *)ptr(nd.stat1);
+          l.dgamma = (float *)d.grad[0];
+          l.dbeta = (float *)d.grad[1];
+          l.rows = (int32_t)nd.rows;
+          l.d = (int32_t)nd.feat;
+          l.eps = (float)d.eps;
+          if (x.wants_grad) {
+            Target tg = acquire(nd.in[0], true);
+            l.y = ptr(tg.dst);
+            l.ldy = tg.dst.ld;
+            l.y_dtype = tg.dst.dtype;
+            if (tg.addend.valid()) {
+              l.addend = ptr(tg.addend);
+              l.ldadd = tg.addend.ld;
+              l.add_dtype = tg.addend.dtype;
+            }
+          }
+          lns.push_back(l);
+          break;
+        }
+        case GPP_OP_ATTENTION: {
+          const Node &x = N[nd.in[0]];
+          if (!x.wants_grad) break;
+          Target tg = acquire(nd.in[0], false);
+          AttnProb a;
+          memset(&a, 0, sizeof(a));
+          a.qkv = ptr(x.val);
+          a.ld_qkv = x.val.ld;
+          a.dtype = x.val.dtype;
+          a.out = ptr(tg.dst);
+          a.ld_out = tg.dst.ld;
+          a.grad_dtype = tg.dst.dtype;
+          a.dout = ptr(nd.gout);
+          a.ld_dout = nd.gout.ld;
+          a.o = ptr(nd.val);
+          a.ld_o = nd.val.ld;
+          a.out_dtype = nd.val.dtype;
+          a.lse = (float *)ptr(nd.stat0);
+          a.delta = (float *)ptr(nd.stat1);
+          a.batch = (int32_t)pl.micro_batch;
+          a.heads = d.heads;
+          a.seq = d.seq_len;
+          a.dh = (int32_t)(nd.feat / d.heads);
+          attns.push_back(a);
+          break;
+        }
+        case GPP_OP_ADD:
+          pass_through(nd.in[0], nd.gout);
+          pass_through(nd.in[1], nd.gout);
+          break;
+        case GPP_OP_CONCAT: {
+          int64_t col = 0;
+          for (int p : nd.in) {
+            Buf view = nd.gout;
+            view.off += col * esize(view.dtype);
+            pass_through(p, view);
+            col += N[p].feat;
+          }
+          break;
+        }
+        case GPP_OP_MEANPOOL_SEQ: {
+          const Node &x = N[nd.in[0]];
+          if (!x.wants_grad) break;
+          Target tg = acquire(nd.in[0], false);
+          PoolProb p;
+          memset(&p, 0, sizeof(p));
+          p.backward = 1;
+          p.src = ptr(nd.gout);
+          p.ld_src = nd.gout.ld;
+          p.src_dtype = nd.gout.dtype;
+          p.dst = ptr(tg.dst);
+          p.ld_dst = tg.dst.ld;
+          p.dst_dtype = tg.dst.dtype;
+          p.batch = (int32_t)pl.micro_batch;
+          p.seq = d.seq_len;
+          p.d = (int32_t)nd.feat;
+          pools.push_back(p);
+          break;
+        }
+        case GPP_OP_EMBEDDING_BAG_SUM: {
+          EmbProb e;
+          memset(&e, 0, sizeof(e));
+          e.table = (const float *)d.param[0];
+          e.dtable = (float *)d.grad[0];
+          e.ld_table = ld_of(nd.feat);
+          e.indices = (const int32_t *)ptr(N[nd.in[0]].val);
+          e.offsets = (const int32_t *)ptr(N[nd.in[1]].val);
+          e.out = ptr(nd.gout);
+          e.ld_out = nd.gout.ld;
+          e.out_dtype = nd.gout.dtype;
+          e.bag_of = (int32_t *)ptr(nd.extra);
+          e.keys_a = (int32_t *)ptr(nd.more[0]);
+          e.keys_b = (int32_t *)ptr(nd.more[1]);
+          e.pos_a = (int32_t *)ptr(nd.more[2]);
+          e.pos_b = (int32_t *)ptr(nd.more[3]);
+          e.hist = (int32_t *)ptr(nd.more[4]);
+          e.unique_rows = (int32_t *)ptr(nd.more[5]);
+          e.seg_offsets = (int32_t *)ptr(nd.more[6]);
+          e.counts = (int32_t *)ptr(nd.more[7]);
+          e.n_bags = (int32_t)pl.micro_batch;
+          e.capacity = (int32_t)(pl.micro_batch * d.bag_size);
+          e.dim = (int32_t)nd.feat;
+          e.num_rows = (int32_t)d.num_rows;
+          e.passes = nd.emb_passes;
+          e.sort_blocks = nd.emb_sort_blocks;
+          embs.push_back(e);
+          break;
+        }
+        case GPP_OP_DOT_INTERACT: {
+          const Node &x = N[nd.in[0]];
+          if (!x.wants_grad) break;
+          Target tg = acquire(nd.in[0], false);
+          InteractProb p;
+          memset(&p, 0, sizeof(p));
+          p.x = ptr(x.val);
+          p.ld_x = x.val.ld;
+          p.x_dtype = x.val.dtype;
+          p.dy = ptr(nd.gout);
+          p.ld_dy = nd.gout.ld;
+          p.dy_dtype = nd.gout.dtype;
+          p.y = ptr(tg.dst);
+          p.ld_y = tg.dst.ld;
+          p.y_dtype = tg.dst.dtype;
+          p.batch = (int32_t)nd.rows;
+          p.d = (int32_t)d.in_features;
+          p.F = (int32_t)(x.feat / d.in_features);
+          inters.push_back(p);
+          break;
+        }
+        default: break;
+      }
+    }
+    if (!colsums.empty()) {
+      int blocks = 0;
+      for (auto &c : colsums) {
+        c.blk_begin = blocks;
+        blocks += colsum_blocks(c.cols);
+      }
+      add_step(K_COLSUM, push_table(colsums), (int)colsums.size(), blocks);
+    }
+    emit_gemms(gemms);
+    if (!lns.empty()) {
+      std::vector<LnProb> dx;
+      int blocks = 0;
+      for (auto &l : lns)
+        if (l.y) {
+          LnProb c = l;
+          c.blk_begin = blocks;
+          blocks += (l.rows + ln_rows_per_block() - 1) / ln_rows_per_block();
+          dx.push_back(c);
+        }
+      if (!dx.empty()) add_step(K_LN_BWD, push_table(dx), (int)dx.size(), blocks);
+      blocks = 0;
+      for (auto &l : lns) {
+        l.blk_begin = blocks;
+        blocks += ln_param_blocks(l.d);
+      }
+      add_step(K_LN_BWD_PARAMS, push_table(lns), (int)lns.size(), blocks);
+    }
+    if (!attns.empty()) {
+      int blocks = 0, ms = 0;
+      for (auto &a : attns) {
+        a.blk_begin = blocks;
+        blocks += attn_blocks(a.batch, a.heads, a.seq);
+        ms = std::max(ms, a.seq);
+      }
+      int64_t off = push_table(attns);
+      add_step(K_ATTN_DQ, off, (int)attns.size(), blocks).a0 = ms;
+      add_step(K_ATTN_DKV, off, (int)attns.size(), blocks).a0 = ms;
+    }
+    if (!pools.empty()) {
+      int blocks = 0;
+      for (auto &p : pools) {
+        p.blk_begin = blocks;
+        blocks += pool_blocks(p);
+      }
+      add_step(K_POOL, push_table(pools), (int)pools.size(), blocks);
+    }
+    if (!embs.empty()) {
+      int cap = 0, sb = 0, ps = 0;
+      for (auto &e : embs) {
+        cap = std::max(cap, e.capacity);
+        sb = std::max(sb, e.sort_blocks);
+        ps = std::max(ps, e.passes);
+      }
+      Step &s = add_step(K_EMB_BWD, push_table(embs), (int)embs.size(), 0);
+      s.a0 = cap;
+      s.a1 = sb;
+      s.a2 = ps;
+      s.launches = emb_bwd_num_launches(ps);
+    }
+    if (!inters.empty()) {
+      int blocks = 0, mf = 0, md = 0;
+      for (auto &p : inters) {
+        p.blk_begin = blocks;
+        blocks += p.batch;
+        mf = std::max(mf, p.F);
+        md = std::max(md, p.d);
+      }
+      Step &s = add_step(K_INTERACT_BWD, push_table(inters), (int)inters.size(), blocks);
+      s.a0 = mf;
+      s.a1 = md;
+    }
+    flush_post();
+  }
+
+  // egress: input gradients to the caller's dense buffers
+  {
+    std::vector<EltProb> recs;
+    int base = 0;
+    for (size_t k = 0; k < pl.input_ops.size(); ++k) {
+      Node &nd = N[pl.input_ops[k]];
+      if ((int)k - base == 64) {
+        emit_elt(recs, EXT_GRAD_INPUTS, base);
+        base = (int)k;
+      }
+      if (!nd.wants_grad || state_of(pl.input_ops[k]) != G_WRITTEN) continue;
+      Buf dst;
+      dst.space = SP_ABS;
+      dst.ld = nd.feat;
+      dst.dtype = nd.d.dtype;
+      EltProb e = elt(nd.gout, dst, nd.rows, nd.feat);
+      e.ext_dst = (int32_t)(k - base);
+      recs.push_back(e);
+    }
+    emit_elt(recs, EXT_GRAD_INPUTS, base);
+  }
+}
+
+}  // namespace
+
+gpp_status_t Plan::emit(int slot, char *ws) {
+  blob.clear();
+  Emitter em(*this, slot, ws);
+  em.forward();
+  em.backward();
+  table_bytes = std::max<int64_t>(table_bytes, align_up((int64_t)blob.size(), 256));
+  // temporaries requested during emission extend the shared region (same for every slot)
+  tmp_bytes = std::max<int64_t>(tmp_bytes, em.shared_tmp_top);
+  return GPP_OK;
+}
+
+}  // namespace gpp

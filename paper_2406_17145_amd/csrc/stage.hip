@@ -1,0 +1,294 @@
+// C ABI of the GPP stage library: descriptor validation, planning, the
+// micro-batch state machine (ordering condition C4 of the paper's problem
+// formulation) and the launch loop.  Everything numeric runs in the HIP kernels.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <deque>
+#include <new>
+#include <string>
+
+#include "plan.h"
+
+using namespace gpp;
+
+namespace gpp {
+void launch_gemm_generic(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int in_dtype, hipStream_t s);
+void launch_attn_fwd(const AttnProb *probs, int n, int total_blocks, int max_seq, hipStream_t s);
+void launch_attn_bwd_dq(const AttnProb *probs, int n, int total_blocks, int max_seq, hipStream_t s);
+void launch_attn_bwd_dkv(const AttnProb *probs, int n, int total_blocks, int max_seq, hipStream_t s);
+void launch_interact_fwd(const InteractProb *probs, int n, int total_blocks, int maxF, int maxd, hipStream_t s);
+void launch_interact_bwd(const InteractProb *probs, int n, int total_blocks, int maxF, int maxd, hipStream_t s);
+void launch_loss_sum(const float *losses, int n, float *out, hipStream_t s);
+}  // namespace gpp
+
+static thread_local std::string g_last_error;
+static gpp_status_t fail(gpp_status_t st, const std::string &msg) {
+  g_last_error = msg;
+  return st;
+}
+
+struct gpp_stage {
+  Plan plan;
+  char *ws = nullptr;
+  std::vector<char> slot_busy;
+  std::deque<int> fifo;          // slots in the order their forwards were issued
+  bool fresh = true;             // no backward since the last grad_reset: next one overwrites dense accumulators
+  bool emb_clear_pending = true; // table accumulators not yet cleared since create
+  int64_t emb_table_off = -1;    // table of all embedding records (slot 0) for the clear kernel
+  int emb_count = 0;
+};
+
+extern "C" {
+
+int64_t gpp_ld(int64_t features) { return (features + 7) / 8 * 8; }
+
+const char *gpp_last_error(void) { return g_last_error.c_str(); }
+
+static gpp_status_t build_plan(const gpp_stage_desc_t *desc, Plan &pl) {
+  gpp_status_t st = pl.analyse(desc);
+  if (st != GPP_OK) return st;
+  pl.layout();
+  st = pl.emit(0, nullptr);  // sizing pass: table and temporary sizes
+  if (st != GPP_OK) return st;
+  pl.layout();
+  return GPP_OK;
+}
+
+gpp_status_t gpp_stage_workspace_bytes(const gpp_stage_desc_t *desc, size_t *bytes) {
+  if (!bytes) return fail(GPP_ERR_INVALID_ARG, "bytes is null");
+  Plan pl;
+  gpp_status_t st = build_plan(desc, pl);
+  if (st != GPP_OK) return fail(st, pl.error);
+  *bytes = (size_t)pl.total_bytes;
+  return GPP_OK;
+}
+
+gpp_status_t gpp_stage_create(const gpp_stage_desc_t *desc, void *workspace, size_t workspace_bytes, gpp_stage_t **out) {
+  if (!out) return fail(GPP_ERR_INVALID_ARG, "out is null");
+  gpp_stage *st = new (std::nothrow) gpp_stage();
+  if (!st) return fail(GPP_ERR_INVALID_ARG, "out of host memory");
+  gpp_status_t rc = build_plan(desc, st->plan);
+  if (rc != GPP_OK) {
+    std::string e = st->plan.error;
+    delete st;
+    return fail(rc, e);
+  }
+  Plan &pl = st->plan;
+  // parameters must be present
+  for (size_t i = 0; i < pl.nodes.size(); ++i) {
+    const gpp_op_desc_t &d = pl.nodes[i].d;
+    bool need2 = (d.kind == GPP_OP_LINEAR && d.has_bias) || d.kind == GPP_OP_LAYERNORM;
+    bool need1 = d.kind == GPP_OP_LINEAR || d.kind == GPP_OP_LAYERNORM || d.kind == GPP_OP_EMBEDDING_BAG_SUM;
+    if ((need1 && (!d.param[0] || !d.grad[0])) || (need2 && (!d.param[1] || !d.grad[1]))) {
+      delete st;
+      return fail(GPP_ERR_INVALID_ARG, "operator " + std::to_string(i) + ": parameter or gradient pointer is null");
+    }
+    for (int k = 0; k < 2; ++k)
+      if (((uintptr_t)d.param[k] | (uintptr_t)d.grad[k]) & 15) {
+        delete st;
+        return fail(GPP_ERR_INVALID_ARG, "operator " + std::to_string(i) + ": parameter pointers must be 16-byte aligned");
+      }
+  }
+  if (!workspace || ((uintptr_t)workspace & 255)) {
+    delete st;
+    return fail(GPP_ERR_WORKSPACE, "workspace is null or not 256-byte aligned");
+  }
+  if (workspace_bytes < (size_t)pl.total_bytes) {
+    delete st;
+    return fail(GPP_ERR_WORKSPACE, "workspace too small: need " + std::to_string(pl.total_bytes) + " bytes");
+  }
+  st->ws = (char *)workspace;
+  hipError_t he = hipMemset(workspace, 0, (size_t)pl.total_bytes);
+  for (int s = 0; he == hipSuccess && s < pl.slots; ++s) {
+    rc = pl.emit(s, st->ws);
+    if (rc != GPP_OK) break;
+    if (!pl.blob.empty())
+      he = hipMemcpy(st->ws + pl.off_tables + (int64_t)s * pl.table_bytes, pl.blob.data(), pl.blob.size(), hipMemcpyHostToDevice);
+  }
+  if (he == hipSuccess) he = hipDeviceSynchronize();
+  if (he != hipSuccess || rc != GPP_OK) {
+    std::string e = he != hipSuccess ? std::string("HIP: ") + hipGetErrorString(he) : pl.error;
+    delete st;
+    return fail(he != hipSuccess ? GPP_ERR_DEVICE : rc, e);
+  }
+  st->slot_busy.assign(pl.slots, 0);
+  for (const Step &s : pl.bwd)
+    if (s.kern == K_EMB_BWD) {
+      st->emb_table_off = s.table_off;
+      st->emb_count = s.n;
+    }
+  *out = st;
+  return GPP_OK;
+}
+
+gpp_status_t gpp_stage_destroy(gpp_stage_t *stage) {
+  delete stage;
+  return GPP_OK;
+}
+
+int32_t gpp_stage_num_inputs(const gpp_stage_t *s) { return s ? (int32_t)s->plan.input_ops.size() : -1; }
+int32_t gpp_stage_num_outputs(const gpp_stage_t *s) { return s ? (int32_t)s->plan.output_ops.size() : -1; }
+int32_t gpp_stage_input_op(const gpp_stage_t *s, int32_t i) {
+  return (s && i >= 0 && i < (int32_t)s->plan.input_ops.size()) ? s->plan.input_ops[i] : -1;
+}
+int32_t gpp_stage_output_op(const gpp_stage_t *s, int32_t i) {
+  return (s && i >= 0 && i < (int32_t)s->plan.output_ops.size()) ? s->plan.output_ops[i] : -1;
+}
+int32_t gpp_stage_num_launches(const gpp_stage_t *s, int32_t backward) {
+  if (!s) return -1;
+  int32_t n = 0;
+  for (const Step &st : backward ? s->plan.bwd : s->plan.fwd) n += st.launches;
+  return n;
+}
+
+}  // extern "C"
+
+// ---------------------------------------------------------------------------
+static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int slot, const void *const *ext_in,
+                              void *const *ext_out, float *loss_out, int accumulate, hipStream_t s) {
+  Plan &pl = st->plan;
+  const char *tables = st->ws + pl.off_tables + (int64_t)slot * pl.table_bytes;
+  StageFlags *flags = (StageFlags *)(st->ws + pl.off_flags);
+  for (const Step &sp : steps) {
+    const void *tab = tables + sp.table_off;
+    switch (sp.kern) {
+      case K_ELT: {
+        ExtPtrs ext;
+        memset(&ext, 0, sizeof(ext));
+        if (sp.ext_kind != EXT_NONE) {
+          const bool in_side = sp.ext_kind == EXT_INPUTS || sp.ext_kind == EXT_GRAD_OUTPUTS;
+          const int total = (sp.ext_kind == EXT_INPUTS || sp.ext_kind == EXT_GRAD_INPUTS) ? (int)pl.input_ops.size()
+                                                                                         : (int)pl.output_ops.size();
+          for (int k = 0; k < 64 && sp.ext_base + k < total; ++k) {
+            if (in_side)
+              ext.p[k] = ext_in ? (void *)ext_in[sp.ext_base + k] : nullptr;
+            else
+              ext.p[k] = ext_out ? ext_out[sp.ext_base + k] : nullptr;
+          }
+        }
+        launch_elt((const EltProb *)tab, sp.n, sp.blocks, ext, s);
+        break;
+      }
+      case K_GEMM_GENERIC: launch_gemm_generic((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a0, s); break;
+      case K_GEMM_MFMA: launch_gemm_mfma((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a1, s); break;
+      case K_COLSUM: launch_colsum((const ColsumProb *)tab, sp.n, sp.blocks, accumulate, s); break;
+      case K_LN_FWD: launch_ln_fwd((const LnProb *)tab, sp.n, sp.blocks, s); break;
+      case K_LN_BWD: launch_ln_bwd((const LnProb *)tab, sp.n, sp.blocks, s); break;
+      case K_LN_BWD_PARAMS: launch_ln_bwd_params((const LnProb *)tab, sp.n, sp.blocks, accumulate, s); break;
+      case K_ATTN_FWD: launch_attn_fwd((const AttnProb *)tab, sp.n, sp.blocks, sp.a0, s); break;
+      case K_ATTN_DQ: launch_attn_bwd_dq((const AttnProb *)tab, sp.n, sp.blocks, sp.a0, s); break;
+      case K_ATTN_DKV: launch_attn_bwd_dkv((const AttnProb *)tab, sp.n, sp.blocks, sp.a0, s); break;
+      case K_POOL: launch_pool((const PoolProb *)tab, sp.n, sp.blocks, s); break;
+      case K_EMB_FWD: launch_emb_fwd((const EmbProb *)tab, sp.n, sp.blocks, flags, s); break;
+      case K_EMB_BWD:
+        if (st->emb_clear_pending) {
+          launch_emb_reset((const EmbProb *)tab, sp.n, s);
+          st->emb_clear_pending = false;
+        }
+        launch_emb_bwd((const EmbProb *)tab, sp.n, sp.a0, sp.a1, sp.a2, flags, s);
+        break;
+      case K_INTERACT_FWD: launch_interact_fwd((const InteractProb *)tab, sp.n, sp.blocks, sp.a0, sp.a1, s); break;
+      case K_INTERACT_BWD: launch_interact_bwd((const InteractProb *)tab, sp.n, sp.blocks, sp.a0, sp.a1, s); break;
+      case K_LOSS_FWD: launch_loss_fwd((const LossProb *)tab, sp.n, s); break;
+      case K_LOSS_BWD: launch_loss_bwd((const LossProb *)tab, sp.n, sp.blocks, s); break;
+      case K_LOSS_SUM:
+        if (loss_out) {
+          Buf b = pl.loss_scalars;
+          const float *ls = (const float *)(st->ws + pl.off_slots + (int64_t)slot * pl.slot_bytes + b.off);
+          launch_loss_sum(ls, sp.n, loss_out, s);
+        }
+        break;
+      default: return fail(GPP_ERR_UNSUPPORTED, "internal: unknown step");
+    }
+  }
+  hipError_t he = hipGetLastError();
+  if (he != hipSuccess) return fail(GPP_ERR_DEVICE, std::string("HIP launch: ") + hipGetErrorString(he));
+  return GPP_OK;
+}
+
+extern "C" {
+
+gpp_status_t gpp_stage_forward(gpp_stage_t *st, int32_t slot, const void *const *inputs, void *const *outputs,
+                               float *loss_out, void *hip_stream) {
+  if (!st) return fail(GPP_ERR_INVALID_ARG, "stage is null");
+  Plan &pl = st->plan;
+  if (slot < 0 || slot >= pl.slots) return fail(GPP_ERR_INVALID_ARG, "slot out of range");
+  if (!inputs) return fail(GPP_ERR_INVALID_ARG, "inputs is null");
+  for (size_t k = 0; k < pl.input_ops.size(); ++k)
+    if (!inputs[k] || ((uintptr_t)inputs[k] & 3)) return fail(GPP_ERR_INVALID_ARG, "input " + std::to_string(k) + " is null or misaligned");
+  if (!pl.output_ops.empty() && !outputs) return fail(GPP_ERR_INVALID_ARG, "outputs is null but the stage has outputs");
+  if (st->slot_busy[slot]) return fail(GPP_ERR_ORDER, "slot " + std::to_string(slot) + " still holds a micro-batch in flight");
+  gpp_status_t rc = run_steps(st, pl.fwd, slot, inputs, outputs, loss_out, 0, (hipStream_t)hip_stream);
+  if (rc != GPP_OK) return rc;
+  st->slot_busy[slot] = 1;
+  st->fifo.push_back(slot);
+  return GPP_OK;
+}
+
+gpp_status_t gpp_stage_backward(gpp_stage_t *st, int32_t slot, const void *const *grad_outputs, void *const *grad_inputs,
+                                void *hip_stream) {
+  if (!st) return fail(GPP_ERR_INVALID_ARG, "stage is null");
+  Plan &pl = st->plan;
+  if (slot < 0 || slot >= pl.slots) return fail(GPP_ERR_INVALID_ARG, "slot out of range");
+  if (!st->slot_busy[slot]) return fail(GPP_ERR_ORDER, "backward before forward on slot " + std::to_string(slot) + " (C4: fw_k precedes bw_k)");
+  if (st->fifo.empty() || st->fifo.front() != slot)
+    return fail(GPP_ERR_ORDER, "backward out of order (C4: bw_k precedes bw_{k+1}); oldest forward is in slot " +
+                                   std::to_string(st->fifo.empty() ? -1 : st->fifo.front()));
+  if (!pl.output_ops.empty()) {
+    if (!grad_outputs) return fail(GPP_ERR_INVALID_ARG, "grad_outputs is null but the stage has outputs");
+    for (size_t k = 0; k < pl.output_ops.size(); ++k)
+      if (pl.nodes[pl.output_ops[k]].wants_grad && !grad_outputs[k]) return fail(GPP_ERR_INVALID_ARG, "grad_outputs[" + std::to_string(k) + "] is null");
+  }
+  gpp_status_t rc = run_steps(st, pl.bwd, slot, grad_outputs, grad_inputs, nullptr, st->fresh ? 0 : 1, (hipStream_t)hip_stream);
+  if (rc != GPP_OK) return rc;
+  st->fresh = false;
+  st->slot_busy[slot] = 0;
+  st->fifo.pop_front();
+  return GPP_OK;
+}
+
+gpp_status_t gpp_stage_grad_reset(gpp_stage_t *st, void *hip_stream) {
+  if (!st) return fail(GPP_ERR_INVALID_ARG, "stage is null");
+  if (!st->fifo.empty()) return fail(GPP_ERR_ORDER, "grad_reset while a micro-batch is in flight");
+  st->fresh = true;
+  if (st->emb_count > 0) {
+    const char *tables = st->ws + st->plan.off_tables;  // slot 0's records carry the same accumulators
+    launch_emb_reset((const EmbProb *)(tables + st->emb_table_off), st->emb_count, (hipStream_t)hip_stream);
+    st->emb_clear_pending = false;
+    hipError_t he = hipGetLastError();
+    if (he != hipSuccess) return fail(GPP_ERR_DEVICE, std::string("HIP launch: ") + hipGetErrorString(he));
+  }
+  return GPP_OK;
+}
+
+gpp_status_t gpp_stage_sync_status(gpp_stage_t *st, void *hip_stream) {
+  if (!st) return fail(GPP_ERR_INVALID_ARG, "stage is null");
+  hipError_t he = hipStreamSynchronize((hipStream_t)hip_stream);
+  StageFlags f;
+  if (he == hipSuccess) he = hipMemcpy(&f, st->ws + st->plan.off_flags, sizeof(f), hipMemcpyDeviceToHost);
+  if (he != hipSuccess) return fail(GPP_ERR_DEVICE, std::string("HIP: ") + hipGetErrorString(he));
+  if (f.index_error) {
+    hipMemset(st->ws + st->plan.off_flags, 0, sizeof(f));
+    return fail(GPP_ERR_INDEX, "an embedding index or offset was out of range");
+  }
+  return GPP_OK;
+}
+
+gpp_status_t gpp_stage_embedding_sort_result(gpp_stage_t *st, int32_t op, const int32_t **sorted_pos, const int32_t **unique_rows,
+                                             const int32_t **seg_offsets, const int32_t **counts) {
+  if (!st) return fail(GPP_ERR_INVALID_ARG, "stage is null");
+  Plan &pl = st->plan;
+  if (op < 0 || op >= (int32_t)pl.nodes.size() || pl.nodes[op].d.kind != GPP_OP_EMBEDDING_BAG_SUM)
+    return fail(GPP_ERR_INVALID_ARG, "op is not an embedding bag");
+  const Node &nd = pl.nodes[op];
+  auto sh = [&](const Buf &b) { return (const int32_t *)(st->ws + pl.off_shared + b.off); };
+  if (sorted_pos) *sorted_pos = sh((nd.emb_passes & 1) ? nd.more[2] : nd.more[3]);
+  if (unique_rows) *unique_rows = sh(nd.more[5]);
+  if (seg_offsets) *seg_offsets = sh(nd.more[6]);
+  if (counts) *counts = sh(nd.more[7]);
+  return GPP_OK;
+}
+
+}  // extern "C"

@@ -243,8 +243,7 @@ def dlrm(micro_batch=2048, n_micro=1, seed=4, n_dense=13, bottom=(512, 256, 128)
     x = g.input(n_dense, dtype, branch=0)
     k = n_dense
     for j, w in enumerate(bottom):
-        last = j == len(bottom) - 1
-        x = g.linear(x, k, w, "relu", dtype, branch=0, out_dtype=F32 if last else dtype)
+        x = g.linear(x, k, w, "relu", dtype, branch=0)
         k = w
     vecs = [x]
     idx_ids, off_ids = [], []
@@ -254,9 +253,9 @@ def dlrm(micro_batch=2048, n_micro=1, seed=4, n_dense=13, bottom=(512, 256, 128)
         idx_ids.append(idx)
         off_ids.append(off)
         vecs.append(g.add("embedding_bag_sum", (idx, off), out_features=dim, num_rows=num_rows,
-                          bag_size=bag, dtype=F32, branch=1 + t))
+                          bag_size=bag, dtype=dtype, branch=1 + t))
     n_vec = n_tables + 1
-    cat = g.add("concat", vecs, out_features=dim * n_vec, dtype=F32)
+    cat = g.add("concat", vecs, out_features=dim * n_vec, dtype=dtype)
     n_terms = n_vec * (n_vec - 1) // 2
     z = g.add("dot_interact", (cat,), in_features=dim, out_features=dim + n_terms, dtype=dtype)
     k = dim + n_terms

@@ -1,0 +1,85 @@
+"""Shared helpers of the GPU parity tests: run a workload through the HIP
+library and through the oracle and compare every tensor.
+
+Error measure (per tensor): l2-relative  ||gpu-ref||_2 / ||ref||_2  and
+max-relative  max|gpu-ref| / max|ref|, both under the numeric mode's
+tolerance (1e-4 fp32 path, 2e-2 bf16 storage with fp32 accumulation).
+Elementwise relative error is ill-defined at the zeros ReLU and sparse table
+gradients produce, hence the norm-wise form.
+"""
+import numpy as np
+
+from oracle import gpp_oracle as O
+from paper_2406_17145_amd import binding as B
+
+
+def rel_errors(got, ref):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    n = np.linalg.norm(ref)
+    m = np.abs(ref).max() if ref.size else 0.0
+    if n == 0.0:
+        return (np.linalg.norm(got), np.abs(got).max() if got.size else 0.0)
+    return np.linalg.norm(got - ref) / n, np.abs(got - ref).max() / m
+
+
+def t2n(t):
+    return t.float().cpu().numpy()
+
+
+def run_gpu(wl, slots=1, flags=0, gouts=None, schedule=None, keep=False):
+    """schedule: list of ("f", j) / ("b", j) over micro-batch ids; default fw_j, bw_j in turn.
+    Micro-batch j uses slot j % slots."""
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=slots, flags=flags)
+    st.grad_reset()
+    n = len(wl.batches)
+    schedule = schedule or [x for j in range(n) for x in (("f", j), ("b", j))]
+    res = [dict() for _ in range(n)]
+    import torch
+    for what, j in schedule:
+        if what == "f":
+            loss = torch.zeros(1, dtype=torch.float32, device=st.dev)
+            outs, _ = st.forward(j % slots, wl.batches[j], loss=loss)
+            res[j]["loss"], res[j]["outs"] = loss, outs
+        else:
+            res[j]["gin"] = st.backward(j % slots, None if gouts is None else gouts[j])
+    st.sync_status()
+    out = []
+    for r in res:
+        out.append(dict(loss=float(r["loss"].cpu()[0]),
+                        outs={i: t2n(t) for i, t in zip(st.output_ids, r["outs"])},
+                        gin={i: t2n(t) for i, t in zip(st.input_ids, r["gin"]) if t is not None}))
+    grads = st.grads_numpy()
+    if keep:
+        return out, grads, st
+    st.close()
+    return out, grads
+
+
+def run_oracle(wl, gouts=None):
+    stage, res = O.run_minibatch(wl.ops, wl.micro_batch, wl.params, wl.batches, gouts)
+    return stage, res
+
+
+def compare(wl, gpu_res, gpu_grads, ora_stage, ora_res, tol=None, label=""):
+    tol = wl.tol if tol is None else tol
+    worst = {}
+
+    def chk(name, got, ref):
+        e2, em = rel_errors(got, ref)
+        worst[name] = (e2, em)
+        assert e2 <= tol and em <= tol, f"{label} {name}: l2-rel {e2:.3e} max-rel {em:.3e} > {tol}"
+
+    for j, (g, (st, gin)) in enumerate(zip(gpu_res, ora_res)):
+        if ora_stage.ops and any(op["kind"].startswith("loss") for op in ora_stage.ops):
+            assert abs(g["loss"] - st.loss) <= tol * max(abs(st.loss), 1e-30), (label, "loss", j, g["loss"], st.loss)
+        for i in ora_stage.output_ids:
+            chk(f"mb{j}.out{i}", g["outs"][i], st.values[i])
+        assert set(g["gin"]) == set(gin), (set(g["gin"]), set(gin))
+        for i, ref in gin.items():
+            chk(f"mb{j}.gin{i}", g["gin"][i], ref)
+    for i, gr in ora_stage.grads.items():
+        for k, ref in gr.items():
+            chk(f"op{i}.d{k}", gpu_grads[i][k], ref)
+    return worst

@@ -1,0 +1,209 @@
+"""GPU parity: the HIP stage library against the CPU fp64 oracle, element by
+element (norm-wise bar, see parity_util), on the same seeded inputs.  Every
+call goes through the C ABI (ctypes binding)."""
+import numpy as np
+import pytest
+
+from paper_2406_17145_amd import binding as B
+from paper_2406_17145_amd import workloads as W
+from tests.parity_util import compare, run_gpu, run_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+def both(wl, gouts=None, **kw):
+    print(f"[case] {wl.name} b={wl.micro_batch} Mb={wl.n_micro} ops={len(wl.ops)} kw={kw}", flush=True)
+    gpu_res, gpu_grads = run_gpu(wl, gouts=gouts, **kw)
+    ora_stage, ora_res = run_oracle(wl, gouts)
+    worst = compare(wl, gpu_res, gpu_grads, ora_stage, ora_res, label=wl.name)
+    w = max(worst.items(), key=lambda kv: kv[1][0])
+    print(f"[ok] {wl.name}: worst l2-rel {w[1][0]:.2e} ({w[0]}) of {len(worst)} tensors, tol {wl.tol}", flush=True)
+    return gpu_res, gpu_grads, ora_stage, ora_res
+
+
+# ---- config 1 (exact) and fp32 variants of every graph family (1e-4) ----------------
+
+def test_config1_tiny_mlp_fp32():
+    both(W.tiny_mlp())
+
+
+def test_config1_interleaved_schedule_two_slots():
+    # 1F1B-like order over two stash slots: fw0 fw1 bw0 fw2 bw1 fw3 bw2 bw3 (satisfies C4)
+    wl = W.tiny_mlp()
+    sched = [("f", 0), ("f", 1), ("b", 0), ("f", 2), ("b", 1), ("f", 3), ("b", 2), ("b", 3)]
+    both(wl, slots=2, schedule=sched)
+
+
+def test_towers_fp32_ragged():
+    both(W.candle_uno(micro_batch=37, n_micro=3, widths=(70, 131, 1, 33), hidden=100, dtype="f32"))
+
+
+def test_transformer_fp32_small():
+    both(W.mmt(micro_batch=3, n_micro=2, n_branches=2, n_layers=2, d_model=96, heads=4, d_ff=200,
+               seq_len=70, d_head_out=50, n_classes=37, dtype="f32"))
+
+
+@pytest.mark.parametrize("ragged", [False, True])
+def test_dlrm_fp32_small(ragged):
+    wl = W.dlrm(micro_batch=150, n_micro=2, n_dense=13, bottom=(40, 24), n_tables=5, num_rows=700,
+                dim=24, bag=7, top=(60, 30, 1), dtype="f32", ragged=ragged)
+    for p in wl.params.values():
+        if "table" in p:
+            p["table"] = p["table"] * 30
+    both(wl)
+
+
+def test_hetero_fp32_small_with_loss():
+    both(W.hetero(micro_batch=19, n_micro=2, base_width=24, out_width=40, dtype="f32"))
+
+
+def test_mid_pipeline_stage_without_loss_fp32():
+    wl = W.hetero(micro_batch=9, n_micro=2, base_width=16, out_width=24, dtype="f32", with_loss=False)
+    out = len(wl.ops) - 1
+    rng = np.random.default_rng(5)
+    gouts = [{out: rng.standard_normal((9, 192)).astype(np.float32)} for _ in range(2)]
+    both(wl, gouts=gouts)
+
+
+# ---- bf16 storage / fp32 accumulation (2e-2) -----------------------------------------
+
+def test_towers_bf16_ragged():
+    both(W.candle_uno(micro_batch=37, n_micro=3, widths=(70, 131, 1, 33), hidden=100))
+
+
+def test_transformer_bf16_small():
+    both(W.mmt(micro_batch=2, n_micro=2, n_branches=2, n_layers=2, d_model=128, heads=2, d_ff=256,
+               seq_len=96, d_head_out=64, n_classes=50))
+
+
+def test_dlrm_bf16_small():
+    both(W.dlrm(micro_batch=256, n_micro=2, n_tables=6, num_rows=5000, bottom=(64, 32, 128),
+                top=(128, 64, 1)))
+
+
+@pytest.mark.parametrize("b", [1, 2, 4, 8, 16, 32, 64, 128])
+def test_config5_hetero_sweep(b):
+    both(W.hetero(micro_batch=b))
+
+
+def test_config2_candle_uno_full():
+    both(W.candle_uno())
+
+
+def test_config3_mmt_full():
+    both(W.mmt())
+
+
+def test_config4_dlrm_full():
+    wl = W.dlrm()
+    gpu_res, gpu_grads, st = run_gpu(wl, keep=True)
+    ora_stage, ora_res = run_oracle(wl)
+    compare(wl, gpu_res, gpu_grads, ora_stage, ora_res, label="dlrm")
+    # integer artefacts of the sorted segment reduction: bit-exact
+    for i, (sp, ur, so) in ora_res[-1][0].embedding_artefacts.items():
+        g_sp, g_ur, g_so = st.embedding_sort_result(i)
+        assert np.array_equal(g_sp, sp) and np.array_equal(g_ur, ur) and np.array_equal(g_so, so), i
+    st.close()
+
+
+# ---- embedding: integer artefacts, empty/ragged bags, determinism, index errors --------
+
+def test_embedding_sort_artefacts_bit_exact_ragged():
+    wl = W.dlrm(micro_batch=300, n_micro=1, n_tables=3, num_rows=1000, dim=16, bag=9, bottom=(8, 16),
+                top=(16, 1), dtype="f32", ragged=True, seed=21)
+    gpu_res, gpu_grads, st = run_gpu(wl, keep=True)
+    ora_stage, ora_res = run_oracle(wl)
+    compare(wl, gpu_res, gpu_grads, ora_stage, ora_res, label="dlrm-ragged")
+    arte = ora_res[0][0].embedding_artefacts
+    assert len(arte) == 3
+    for i, (sp, ur, so) in arte.items():
+        g_sp, g_ur, g_so = st.embedding_sort_result(i)
+        assert np.array_equal(g_sp, sp), i
+        assert np.array_equal(g_ur, ur), i
+        assert np.array_equal(g_so, so), i
+    st.close()
+
+
+def test_embedding_all_bags_empty():
+    wl = W.dlrm(micro_batch=40, n_micro=1, n_tables=2, num_rows=50, dim=8, bag=4, bottom=(8,), top=(8, 1),
+                dtype="f32")
+    for mb in wl.batches:
+        for i, op in enumerate(wl.ops):
+            if op.get("role") == "offsets":
+                mb[i] = np.zeros_like(mb[i])
+    both(wl)
+
+
+def test_backward_is_bitwise_deterministic():
+    wl = W.dlrm(micro_batch=512, n_micro=1, n_tables=4, num_rows=2000, bottom=(64, 128), top=(64, 1))
+    _, g1 = run_gpu(wl)
+    _, g2 = run_gpu(wl)
+    for i in g1:
+        for k in g1[i]:
+            assert np.array_equal(g1[i][k], g2[i][k]), (i, k)
+
+
+def test_out_of_range_index_is_reported_not_dereferenced():
+    wl = W.dlrm(micro_batch=32, n_micro=1, n_tables=2, num_rows=64, dim=8, bag=4, bottom=(8,), top=(8, 1),
+                dtype="f32")
+    idx_id = next(i for i, op in enumerate(wl.ops) if op.get("role") == "indices")
+    wl.batches[0][idx_id][3, 1] = 64            # == num_rows
+    wl.batches[0][idx_id][5, 0] = -7
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params)
+    st.grad_reset()
+    st.forward(0, wl.batches[0])
+    st.backward(0)
+    with pytest.raises(B.GppError) as e:
+        st.sync_status()
+    assert e.value.status == B.GPP_ERR_INDEX
+    st.sync_status()                            # flag is cleared by the report
+    st.close()
+
+
+# ---- ordering condition C4 and the slot state machine ---------------------------------
+
+def test_c4_order_violations_are_errors():
+    wl = W.tiny_mlp()
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=2)
+    with pytest.raises(B.GppError) as e:
+        st.backward(0)                                   # bw_0 before fw_0
+    assert e.value.status == B.GPP_ERR_ORDER
+    st.forward(0, wl.batches[0])
+    with pytest.raises(B.GppError) as e:
+        st.forward(0, wl.batches[1])                     # slot still in flight
+    assert e.value.status == B.GPP_ERR_ORDER
+    st.forward(1, wl.batches[1])
+    with pytest.raises(B.GppError) as e:
+        st.backward(1)                                   # bw_1 before bw_0
+    assert e.value.status == B.GPP_ERR_ORDER
+    with pytest.raises(B.GppError) as e:
+        st.grad_reset()                                  # micro-batches in flight
+    assert e.value.status == B.GPP_ERR_ORDER
+    st.backward(0)
+    st.backward(1)
+    st.grad_reset()
+    st.sync_status()
+    st.close()
+
+
+def test_grad_reset_starts_new_sums():
+    wl = W.tiny_mlp()
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params)
+    for rep in range(2):
+        st.grad_reset()
+        for mb in wl.batches:
+            st.forward(0, mb)
+            st.backward(0)
+        g = st.grads_numpy()
+        if rep == 0:
+            first = g
+    for i in first:
+        for k in first[i]:
+            assert np.array_equal(first[i][k], g[i][k])
+    st.close()
+
+
+def test_generic_and_default_gemm_paths_agree_with_oracle():
+    wl = W.candle_uno(micro_batch=64, n_micro=2, widths=(96, 200, 8, 64), hidden=128)
+    both(wl, flags=B.FLAG_FORCE_GENERIC_GEMM)
+    both(wl)
