@@ -21,6 +21,11 @@ an interaction); it states no activation, normalisation, loss or constant, so
 every formula below is the textbook one and the constants are this build's
 readings (listed in the design notes).
 
+Precision: float64 throughout.  For the "bf16 storage, fp32 accumulation" mode
+the stage can additionally round operator outputs to bf16 where the workload
+declares bf16 storage (store_as); this is a model of storage, not of the
+kernels.
+
 Pins (tests/test_oracle_*.py): central finite differences on every operator
 and on whole small stages; sum of micro-batch gradients == full-batch
 gradient; branch independence; closed-form special cases; dense one-hot brute
@@ -272,6 +277,24 @@ def loss_fwd_bwd(kind, y, target, scale):
 
 
 # ---------------------------------------------------------------------------
+# storage precision
+# ---------------------------------------------------------------------------
+
+def store_as(x, dtype):
+    """Value of x after being stored in `dtype`.  "bf16": nearest number with an
+    8-bit significand, ties to even (1 sign, 8 exponent, 7 explicit fraction
+    bits); anything else: unchanged.  The numeric mode "bf16 storage with fp32
+    accumulation" keeps tensors between operators in bf16; the oracle models
+    that storage step, and nothing else of the kernels' arithmetic, so that
+    the 0/1 decisions taken from stored values (which side of a ReLU kink an
+    element is on) are taken from the same numbers on both sides."""
+    if dtype != "bf16":
+        return x
+    m, e = np.frexp(x)                       # x = m * 2^e, 0.5 <= |m| < 1
+    return np.ldexp(np.rint(m * 256.0) / 256.0, e)
+
+
+# ---------------------------------------------------------------------------
 # the stage
 # ---------------------------------------------------------------------------
 
@@ -313,9 +336,12 @@ class Stash:
 
 
 class OracleStage:
-    def __init__(self, ops, micro_batch, params):
+    def __init__(self, ops, micro_batch, params, model_storage=False):
+        """model_storage: round every operator output whose declared dtype is
+        bf16 to bf16 (see store_as); all arithmetic stays float64."""
         self.ops = ops
         self.b = int(micro_batch)
+        self.model_storage = bool(model_storage)
         self.order, self.users = topological_order(ops)
         self.params = {i: {k: np.asarray(v, dtype=np.float64) for k, v in p.items()}
                        for i, p in params.items()}
@@ -364,6 +390,8 @@ class OracleStage:
                 val[i] = None
             else:
                 raise ValueError(k)
+            if self.model_storage and val[i] is not None and k != "input":
+                val[i] = store_as(val[i], op.get("out_dtype", op.get("dtype")))
         return st
 
     # -- bw_j ---------------------------------------------------------------
@@ -420,11 +448,11 @@ class OracleStage:
                 and op.get("role", "data") == "data" and i in gval}
 
 
-def run_minibatch(ops, micro_batch, params, batches, grad_outputs=None):
+def run_minibatch(ops, micro_batch, params, batches, grad_outputs=None, model_storage=False):
     """Convenience for tests: fw_j then bw_j for j = 0..Mb-1 (a schedule that
     satisfies ordering condition C4), gradients accumulated.  Returns the
     stage and per-micro-batch (stash, input gradients)."""
-    stage = OracleStage(ops, micro_batch, params)
+    stage = OracleStage(ops, micro_batch, params, model_storage)
     results = []
     for j, mb in enumerate(batches):
         st = stage.forward(mb)

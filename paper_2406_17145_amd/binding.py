@@ -51,6 +51,7 @@ EXPORTS = [
 ]
 
 _lib = None
+_hip = None
 
 
 def load():
@@ -61,6 +62,12 @@ def load():
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2406_17145_amd.build` "
                            "(there is no fallback implementation)")
+    # One HIP runtime per process: PyTorch ships its own libamdhip64 (same SONAME as the system
+    # one).  Loading it first makes the dynamic linker bind libgpp.so to that copy, so device
+    # pointers and streams created by PyTorch are valid inside the library.
+    import torch  # noqa: F401
+    global _hip
+    _hip = C.CDLL(os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so"), mode=C.RTLD_GLOBAL)
     lib = C.CDLL(LIB_PATH)
     vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
     lib.gpp_ld.restype, lib.gpp_ld.argtypes = i64, [i64]
@@ -324,9 +331,8 @@ class Stage:
 
         def read(ptr, n):
             buf = torch.empty(n, dtype=torch.int32, device=self.dev)
-            from torch.cuda import current_stream  # noqa: F401
-            C_hip = C.CDLL("libamdhip64.so")
-            C_hip.hipMemcpy(C.c_void_p(buf.data_ptr()), ptr, C.c_size_t(4 * n), C.c_int(3))
+            rc = _hip.hipMemcpy(C.c_void_p(buf.data_ptr()), ptr, C.c_size_t(4 * n), C.c_int(3))
+            assert rc == 0, rc
             return buf.cpu().numpy()
 
         counts = read(ptrs[3], 2)

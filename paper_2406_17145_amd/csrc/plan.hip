@@ -291,6 +291,7 @@ gpp_status_t Plan::analyse(const gpp_stage_desc_t *desc) {
       return;
     }
     nd.val = alloc(SP_SLOT, nd.rows, nd.feat, nd.d.dtype);
+    if (nd.d.dtype == DT_I32) nd.val.ld = nd.feat;  // index / offset / label lists stay dense
   };
   for (int i = 0; i < n; ++i) alloc_val(i);
   std::function<void(int)> alloc_gout = [&](int i) {

@@ -58,7 +58,9 @@ def run_gpu(wl, slots=1, flags=0, gouts=None, schedule=None, keep=False):
 
 
 def run_oracle(wl, gouts=None):
-    stage, res = O.run_minibatch(wl.ops, wl.micro_batch, wl.params, wl.batches, gouts)
+    # bf16-storage workloads: the oracle rounds stored operator outputs to bf16 as well, so that
+    # ReLU masks are decided from the same stored values on both sides
+    stage, res = O.run_minibatch(wl.ops, wl.micro_batch, wl.params, wl.batches, gouts, model_storage=True)
     return stage, res
 
 

@@ -469,3 +469,29 @@ def test_graph_validation():
         O.topological_order([dict(kind="add", inputs=[1, 1]), dict(kind="add", inputs=[0, 0])])
     with pytest.raises(ValueError):
         O.topological_order([dict(kind="add", inputs=[5, 5])])
+
+
+# --------------------------------------------------------------------------
+# storage model
+# --------------------------------------------------------------------------
+
+def test_store_as_bf16_rounds_to_nearest_even_on_8_bit_significands():
+    x = np.array([1.0, 1.0 + 2.0 ** -7, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20,
+                  -3.1415926, 0.0, 2.0 ** -100, 65504.0])
+    r = O.store_as(x, "bf16")
+    assert r[0] == 1.0 and r[1] == 1.0 + 2.0 ** -7
+    assert r[2] == 1.0                      # tie -> even significand
+    assert r[3] == 1.0 + 2.0 ** -6          # tie -> even significand (1.0000010b)
+    assert r[4] == 1.0 + 2.0 ** -7          # just above the tie
+    assert r[5] == -3.140625 and r[6] == 0.0 and r[7] == 2.0 ** -100
+    assert r[8] == 65536.0
+    # agrees with the float32-bit-pattern formulation used for input generation
+    v = np.random.default_rng(0).standard_normal(10000).astype(np.float32)
+    assert np.array_equal(O.store_as(v.astype(np.float64), "bf16"), W.round_to_bf16(v).astype(np.float64))
+    assert O.store_as(x, "f32") is x
+    # idempotent, and inert for fp32 workloads
+    assert np.array_equal(O.store_as(r, "bf16"), r)
+    wl = W.tiny_mlp()
+    a, _ = O.run_minibatch(wl.ops, wl.micro_batch, wl.params, wl.batches, model_storage=True)
+    b, _ = O.run_minibatch(wl.ops, wl.micro_batch, wl.params, wl.batches)
+    assert all(np.array_equal(a.grads[i][k], b.grads[i][k]) for i in a.grads for k in a.grads[i])
