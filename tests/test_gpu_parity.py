@@ -68,7 +68,10 @@ def test_mid_pipeline_stage_without_loss_fp32():
 # ---- bf16 storage / fp32 accumulation (2e-2) -----------------------------------------
 
 def test_towers_bf16_ragged():
-    both(W.candle_uno(micro_batch=37, n_micro=3, widths=(70, 131, 1, 33), hidden=100))
+    # smooth activation: every tile edge and ragged tail is checked with a wide margin
+    both(W.candle_uno(micro_batch=37, n_micro=3, widths=(70, 131, 1, 33), hidden=100, act="gelu"))
+    # ReLU masks at a size where one mask decision is a small part of a tensor
+    both(W.candle_uno(micro_batch=300, n_micro=2, widths=(70, 131, 1, 33), hidden=250))
 
 
 def test_transformer_bf16_small():
@@ -204,6 +207,6 @@ def test_grad_reset_starts_new_sums():
 
 
 def test_generic_and_default_gemm_paths_agree_with_oracle():
-    wl = W.candle_uno(micro_batch=64, n_micro=2, widths=(96, 200, 8, 64), hidden=128)
+    wl = W.candle_uno(micro_batch=64, n_micro=2, widths=(96, 200, 8, 64), hidden=128, act="gelu")
     both(wl, flags=B.FLAG_FORCE_GENERIC_GEMM)
     both(wl)
