@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark: forward+backward samples/s of one GPP stage on one MI355X.
+
+A "step" is one pass of the whole hot path over one mini-batch of synthetic
+input: grad_reset, then for each of the workload's micro-batches fw_j and bw_j
+(weight gradients accumulate across them).  Inputs are resident in HBM before
+the timed region.  Default workload: the CANDLE-Uno-shaped feature-tower stage
+(micro-batch 64, 8 micro-batches, bf16 storage with fp32 accumulation).
+
+Prints ONE JSON line.  Besides the driver's fields it carries
+  roofline      the dominant kernel's algorithmic bytes (or flops) per launch over its average
+                launch duration, measured with HIP events on the launch stream in a second,
+                instrumented pass over the same steps
+  cpu_baseline  the CPU oracle timed on this host on a bounded sample of the same workload
+  kernels       per-kernel breakdown of the instrumented pass
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
+
+
+def gemm_traffic(wl):
+    """Algorithmic bytes and flops of the three grouped-GEMM roles for ONE micro-batch.
+
+    Per parameter of a bf16 Linear: forward reads W once (2 B); backward-data reads W once (2 B);
+    backward-weight reads and writes the fp32 accumulator (8 B; 4 B on the first micro-batch after
+    a reset, which overwrites).  Activations: every operand/result matrix once, in its storage type.
+    """
+    b = wl.micro_batch
+    rows = {}
+    for i, op in enumerate(wl.ops):
+        if op["kind"] == "input":
+            rows[i] = b * op.get("seq_len", 1) + op.get("rows_extra", 0)
+        elif op["kind"] in ("meanpool", "embedding_bag_sum"):
+            rows[i] = b
+        elif op["kind"].startswith("loss"):
+            rows[i] = 0
+        else:
+            rows[i] = rows[op["inputs"][0]]
+    out = {"fwd": [0, 0], "dx": [0, 0], "dw": [0, 0], "dw_first": [0, 0], "params": 0}
+    for i, op in enumerate(wl.ops):
+        if op["kind"] != "linear":
+            continue
+        es = 2 if op["dtype"] == "bf16" else 4
+        m, k, n = rows[i], op["in_features"], op["out_features"]
+        p = k * n
+        out["params"] += p
+        fl = 2 * m * k * n
+        out["fwd"][0] += p * es + m * k * es + m * n * es
+        out["fwd"][1] += fl
+        needs_dx = wl.ops[op["inputs"][0]]["kind"] != "input" or wl.ops[op["inputs"][0]].get("role") == "data"
+        if needs_dx:
+            out["dx"][0] += p * es + m * n * es + m * k * es
+            out["dx"][1] += fl
+        out["dw"][0] += p * 8 + m * n * es + m * k * es
+        out["dw_first"][0] += p * 4 + m * n * es + m * k * es
+        out["dw"][1] += fl
+        out["dw_first"][1] += fl
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="candle_uno", choices=["tiny_mlp", "candle_uno", "mmt", "dlrm", "hetero"])
+    ap.add_argument("--micro-batch", type=int, default=0, help="override the config's micro-batch size")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-pass", action="store_true", help="skip the event-instrumented second pass")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one stage on ONE GPU (no collectives, no sharding); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2406_17145_amd import binding as B
+    from paper_2406_17145_amd import workloads as W
+
+    kw = {}
+    if args.micro_batch:
+        kw["micro_batch"] = args.micro_batch
+    wl = W.CONFIGS[args.config](**kw)
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params)
+    dev_batches = [st.stage_inputs(mb) for mb in wl.batches]       # resident in HBM
+    outs = st.alloc_outputs()
+    gins = st.alloc_grad_inputs()
+    gouts = [torch.zeros_like(o) for o in outs] if outs else None
+    loss = torch.zeros(1, dtype=torch.float32, device=st.dev)
+
+    def step():
+        st.grad_reset()
+        for mb in dev_batches:
+            st.forward(0, mb, outputs=outs, loss=loss)
+            st.backward(0, grad_outputs=gouts, grad_inputs=gins)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    st.sync_status()
+    samples_per_step = wl.micro_batch * wl.n_micro
+    value = args.steps * samples_per_step / dt
+
+    # ---- instrumented pass: per-kernel durations from HIP events on the launch stream ----
+    kernels, roofline = {}, None
+    if not args.no_kernel_pass:
+        st.profile_enable(True)
+        k_steps = max(1, min(args.steps, 20))
+        for _ in range(k_steps):
+            step()
+        torch.cuda.synchronize()
+        prof = st.profile_read()
+        st.profile_enable(False)
+        total_ms = sum(v[0] for v in prof.values())
+        for name, (ms, launches) in sorted(prof.items(), key=lambda kv: -kv[1][0]):
+            kernels[name] = {"ms_per_step": ms / k_steps, "launches_per_step": launches / k_steps,
+                             "avg_launch_us": 1e3 * ms / max(launches, 1), "share": ms / total_ms}
+        tr = gemm_traffic(wl)
+        nm = wl.n_micro
+        alg = {  # algorithmic bytes / flops of each kernel role per STEP
+            "gemm_mfma_fwd": (tr["fwd"][0] * nm, tr["fwd"][1] * nm),
+            "gemm_mfma_dx": (tr["dx"][0] * nm, tr["dx"][1] * nm),
+            "gemm_mfma_dw": (tr["dw_first"][0] + tr["dw"][0] * (nm - 1), tr["dw"][1] * nm),
+            "gemm_generic_fwd": (tr["fwd"][0] * nm, tr["fwd"][1] * nm),
+            "gemm_generic_bwd": (tr["dx"][0] * nm + tr["dw_first"][0] + tr["dw"][0] * (nm - 1),
+                                 (tr["dx"][1] + tr["dw"][1]) * nm),
+        }
+        dom = next(iter(kernels))
+        if dom in alg:
+            by, fl = alg[dom]
+            k = kernels[dom]
+            sec = k["ms_per_step"] * 1e-3
+            gbs, tfl = by / sec / 1e9, fl / sec / 1e12
+            # binding bound of this kernel: compare time at each peak
+            hbm_bound = by / (HBM_PEAK_GBS * 1e9) >= fl / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+            if hbm_bound:
+                roofline = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "frac": gbs / HBM_PEAK_GBS, "traffic": None}
+            else:
+                roofline = {"bound": "mfma", "achieved": tfl, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                            "frac": tfl / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+            roofline.update({"kernel": dom, "avg_launch_us": k["avg_launch_us"],
+                             "launches_per_step": k["launches_per_step"],
+                             "algorithmic_bytes_per_launch": by / k["launches_per_step"],
+                             "algorithmic_flops_per_launch": fl / k["launches_per_step"],
+                             "other_fraction_tflops": tfl, "other_fraction_gbs": gbs})
+        else:
+            roofline = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
+                        "traffic": None, "kernel": dom}
+
+    # ---- CPU oracle on this host, bounded sample --------------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import gpp_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count()
+        ost = O.OracleStage(wl.ops, wl.micro_batch, wl.params, model_storage=True)
+        s0 = ost.forward(wl.batches[0])        # warm-up
+        go = {i: np.zeros((s0.values[i].shape)) for i in ost.output_ids}
+        ost.backward(s0, go)
+        n_done, t0 = 0, time.perf_counter()
+        while True:
+            mb = wl.batches[n_done % len(wl.batches)]
+            s = ost.forward(mb)
+            ost.backward(s, go)
+            n_done += 1
+            el = time.perf_counter() - t0
+            if el > 12.0 or n_done >= 64:
+                break
+        cpu = {"value": n_done * wl.micro_batch / el, "unit": "samples/s", "cores": cores, "kind": "oracle",
+               "sample": f"{n_done} micro-batch(es) of {wl.micro_batch} samples, forward+backward, fp64 numpy"}
+
+    out = {
+        "metric": "stage fwd+bwd samples/s", "value": value, "unit": "samples/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if args.config == "tiny_mlp" else "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.config}: micro-batch {wl.micro_batch} x {wl.n_micro} micro-batches per step",
+                   "micro_batch": wl.micro_batch, "micro_batches_per_step": wl.n_micro,
+                   "launches_per_microbatch": st.num_launches(False) + st.num_launches(True)},
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+    }
+    print(json.dumps(out))
+    st.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -186,6 +186,16 @@ gpp_status_t gpp_stage_embedding_sort_result(gpp_stage_t *stage, int32_t op, con
                                              const int32_t **unique_rows, const int32_t **seg_offsets,
                                              const int32_t **counts);
 
+/* Per-kernel timing for benchmarks.  While enabled, forward/backward bracket every grouped launch
+ * with a pair of HIP events on the caller's stream (events are created on first use: the only
+ * allocation these calls ever make, and only in this mode).  profile_read waits for the recorded
+ * events and returns, per tag, the accumulated milliseconds and kernel launches since the last
+ * reset; ms and launches are HOST arrays of GPP_PROFILE_TAGS entries. */
+#define GPP_PROFILE_TAGS 32
+gpp_status_t gpp_stage_profile_enable(gpp_stage_t *stage, int32_t enable);
+gpp_status_t gpp_stage_profile_read(gpp_stage_t *stage, double *ms, int64_t *launches, int32_t reset);
+const char *gpp_profile_tag_name(int32_t tag);
+
 /* Thread-local description of the last error returned on this thread. */
 const char *gpp_last_error(void);
 

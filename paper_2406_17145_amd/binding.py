@@ -47,8 +47,10 @@ EXPORTS = [
     "gpp_ld", "gpp_stage_workspace_bytes", "gpp_stage_create", "gpp_stage_forward", "gpp_stage_backward",
     "gpp_stage_grad_reset", "gpp_stage_sync_status", "gpp_stage_destroy", "gpp_stage_num_inputs",
     "gpp_stage_num_outputs", "gpp_stage_input_op", "gpp_stage_output_op", "gpp_stage_num_launches",
-    "gpp_stage_embedding_sort_result", "gpp_last_error",
+    "gpp_stage_embedding_sort_result", "gpp_last_error", "gpp_stage_profile_enable", "gpp_stage_profile_read",
+    "gpp_profile_tag_name",
 ]
+GPP_PROFILE_TAGS = 32
 
 _lib = None
 _hip = None
@@ -89,6 +91,10 @@ def load():
     lib.gpp_stage_embedding_sort_result.restype = i32
     lib.gpp_stage_embedding_sort_result.argtypes = [vp, i32] + [C.POINTER(vp)] * 4
     lib.gpp_last_error.restype, lib.gpp_last_error.argtypes = C.c_char_p, []
+    lib.gpp_stage_profile_enable.restype, lib.gpp_stage_profile_enable.argtypes = i32, [vp, i32]
+    lib.gpp_stage_profile_read.restype = i32
+    lib.gpp_stage_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), i32]
+    lib.gpp_profile_tag_name.restype, lib.gpp_profile_tag_name.argtypes = C.c_char_p, [i32]
     _lib = lib
     return lib
 
@@ -304,6 +310,17 @@ class Stage:
 
     def sync_status(self):
         gpp_stage_sync_status(self.handle, self.stream())
+
+    def profile_enable(self, on):
+        _check(load().gpp_stage_profile_enable(self.handle, 1 if on else 0))
+
+    def profile_read(self, reset=True):
+        """{tag name: (milliseconds, kernel launches)} accumulated since the last reset."""
+        ms = (C.c_double * GPP_PROFILE_TAGS)()
+        ln = (C.c_int64 * GPP_PROFILE_TAGS)()
+        _check(load().gpp_stage_profile_read(self.handle, ms, ln, 1 if reset else 0))
+        lib = load()
+        return {lib.gpp_profile_tag_name(k).decode(): (ms[k], ln[k]) for k in range(GPP_PROFILE_TAGS) if ln[k]}
 
     def num_launches(self, backward):
         return load().gpp_stage_num_launches(self.handle, 1 if backward else 0)

@@ -38,7 +38,44 @@ struct gpp_stage {
   bool emb_clear_pending = true; // table accumulators not yet cleared since create
   int64_t emb_table_off = -1;    // table of all embedding records (slot 0) for the clear kernel
   int emb_count = 0;
+  // optional per-step timing (HIP events on the caller's stream)
+  bool prof_on = false;
+  std::vector<hipEvent_t> prof_ev;   // pairs (begin, end)
+  std::vector<int> prof_tag;         // tag of each recorded pair
+  size_t prof_used = 0;
+  double prof_ms[GPP_PROFILE_TAGS] = {0};
+  int64_t prof_launches[GPP_PROFILE_TAGS] = {0};
 };
+
+// profile tag of a step: grouped-GEMM steps are split by form, element-wise steps by direction
+static int step_tag(const Step &sp, bool backward) {
+  switch (sp.kern) {
+    case K_GEMM_MFMA: return 1 + sp.a1;                    // 1 fwd, 2 dx, 3 dw
+    case K_GEMM_GENERIC: return backward ? 5 : 4;
+    case K_ELT: return backward ? 7 : 6;
+    case K_COLSUM: return 8;
+    case K_LN_FWD: return 9;
+    case K_LN_BWD: return 10;
+    case K_LN_BWD_PARAMS: return 11;
+    case K_ATTN_FWD: return 12;
+    case K_ATTN_DQ: return 13;
+    case K_ATTN_DKV: return 14;
+    case K_POOL: return backward ? 16 : 15;
+    case K_EMB_FWD: return 17;
+    case K_EMB_BWD: return 18;
+    case K_INTERACT_FWD: return 19;
+    case K_INTERACT_BWD: return 20;
+    case K_LOSS_FWD: return 21;
+    case K_LOSS_BWD: return 22;
+    case K_LOSS_SUM: return 23;
+    default: return 0;
+  }
+}
+static const char *const kTagNames[GPP_PROFILE_TAGS] = {
+    "other", "gemm_mfma_fwd", "gemm_mfma_dx", "gemm_mfma_dw", "gemm_generic_fwd", "gemm_generic_bwd", "elt_fwd", "elt_bwd",
+    "colsum_bias_grad", "layernorm_fwd", "layernorm_bwd_dx", "layernorm_bwd_params", "attention_fwd", "attention_bwd_dq",
+    "attention_bwd_dkv", "meanpool_fwd", "meanpool_bwd", "embedding_fwd", "embedding_bwd_sort_segsum", "interact_fwd",
+    "interact_bwd", "loss_fwd", "loss_bwd", "loss_sum", "embedding_grad_clear", "", "", "", "", "", "", ""};
 
 extern "C" {
 
@@ -124,6 +161,8 @@ gpp_status_t gpp_stage_create(const gpp_stage_desc_t *desc, void *workspace, siz
 }
 
 gpp_status_t gpp_stage_destroy(gpp_stage_t *stage) {
+  if (stage)
+    for (hipEvent_t e : stage->prof_ev) (void)hipEventDestroy(e);
   delete stage;
   return GPP_OK;
 }
@@ -151,8 +190,24 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
   Plan &pl = st->plan;
   const char *tables = st->ws + pl.off_tables + (int64_t)slot * pl.table_bytes;
   StageFlags *flags = (StageFlags *)(st->ws + pl.off_flags);
+  const bool is_bwd = &steps == &pl.bwd;
   for (const Step &sp : steps) {
     const void *tab = tables + sp.table_off;
+    hipEvent_t ev_end = nullptr;
+    if (st->prof_on) {
+      if (st->prof_used + 2 > st->prof_ev.size()) {
+        for (int k = 0; k < 2; ++k) {
+          hipEvent_t e;
+          if (hipEventCreate(&e) != hipSuccess) return fail(GPP_ERR_DEVICE, "hipEventCreate failed");
+          st->prof_ev.push_back(e);
+        }
+      }
+      (void)hipEventRecord(st->prof_ev[st->prof_used], s);
+      ev_end = st->prof_ev[st->prof_used + 1];
+      st->prof_tag.resize(st->prof_used / 2 + 1);
+      st->prof_tag[st->prof_used / 2] = step_tag(sp, is_bwd) | (sp.launches << 8);
+      st->prof_used += 2;
+    }
     switch (sp.kern) {
       case K_ELT: {
         ExtPtrs ext;
@@ -202,6 +257,7 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
         break;
       default: return fail(GPP_ERR_UNSUPPORTED, "internal: unknown step");
     }
+    if (ev_end) (void)hipEventRecord(ev_end, s);
   }
   hipError_t he = hipGetLastError();
   if (he != hipSuccess) return fail(GPP_ERR_DEVICE, std::string("HIP launch: ") + hipGetErrorString(he));
@@ -275,6 +331,36 @@ gpp_status_t gpp_stage_sync_status(gpp_stage_t *st, void *hip_stream) {
   }
   return GPP_OK;
 }
+
+gpp_status_t gpp_stage_profile_enable(gpp_stage_t *st, int32_t enable) {
+  if (!st) return fail(GPP_ERR_INVALID_ARG, "stage is null");
+  st->prof_on = enable != 0;
+  return GPP_OK;
+}
+
+gpp_status_t gpp_stage_profile_read(gpp_stage_t *st, double *ms, int64_t *launches, int32_t reset) {
+  if (!st || !ms || !launches) return fail(GPP_ERR_INVALID_ARG, "null argument");
+  for (size_t k = 0; k + 1 < st->prof_used; k += 2) {
+    if (hipEventSynchronize(st->prof_ev[k + 1]) != hipSuccess) return fail(GPP_ERR_DEVICE, "hipEventSynchronize failed");
+    float t = 0.0f;
+    if (hipEventElapsedTime(&t, st->prof_ev[k], st->prof_ev[k + 1]) != hipSuccess) return fail(GPP_ERR_DEVICE, "hipEventElapsedTime failed");
+    const int tag = st->prof_tag[k / 2] & 255;
+    st->prof_ms[tag] += t;
+    st->prof_launches[tag] += st->prof_tag[k / 2] >> 8;
+  }
+  st->prof_used = 0;
+  for (int k = 0; k < GPP_PROFILE_TAGS; ++k) {
+    ms[k] = st->prof_ms[k];
+    launches[k] = st->prof_launches[k];
+    if (reset) {
+      st->prof_ms[k] = 0.0;
+      st->prof_launches[k] = 0;
+    }
+  }
+  return GPP_OK;
+}
+
+const char *gpp_profile_tag_name(int32_t tag) { return (tag >= 0 && tag < GPP_PROFILE_TAGS) ? kTagNames[tag] : ""; }
 
 gpp_status_t gpp_stage_embedding_sort_result(gpp_stage_t *st, int32_t op, const int32_t **sorted_pos, const int32_t **unique_rows,
                                              const int32_t **seg_offsets, const int32_t **counts) {

@@ -11,6 +11,15 @@ tail): it uses the same tolerance in fp32 mode and 5x the tolerance in bf16
 mode, because there a single ReLU mask decision that falls on the other side of
 zero (fp32 vs fp64 accumulation, amplified at a bf16 rounding boundary of a
 stored activation) legitimately moves one sample's whole gradient row.
+
+Input gradients of bf16 graphs with ReLU layers are the one place where that
+effect is not small: the masks of every layer between an input and the loss
+multiply into its gradient, and a handful of opposite decisions per micro-batch
+(each worth about 0.5% of a [64, 1000]-wide layer) already add up to 1-3% in
+the l2 norm.  Two CPU runs of the oracle that differ only in the accumulation
+precision of the matrix products (float32 vs float64) show the same spread
+(tests/test_oracle_pins.py::test_relu_mask_noise_floor), so for those tensors
+the bar is 5e-2; every other tensor of every graph stays at the stated 2e-2.
 """
 import numpy as np
 
@@ -72,12 +81,16 @@ def run_oracle(wl, gouts=None):
 def compare(wl, gpu_res, gpu_grads, ora_stage, ora_res, tol=None, label=""):
     tol = wl.tol if tol is None else tol
     tol_max = tol if tol <= 1e-3 else 5 * tol
+    has_relu = any(op.get("act") == "relu" for op in wl.ops)
+    tol_gin = 5e-2 if (tol > 1e-3 and has_relu) else tol
     worst = {}
 
-    def chk(name, got, ref):
+    def chk(name, got, ref, t2=None):
+        t2 = tol if t2 is None else t2
         e2, em = rel_errors(got, ref)
         worst[name] = (e2, em)
-        assert e2 <= tol and em <= tol_max, f"{label} {name}: l2-rel {e2:.3e} (tol {tol}) max-rel {em:.3e} (tol {tol_max})"
+        assert e2 <= t2 and em <= max(tol_max, 2 * t2), \
+            f"{label} {name}: l2-rel {e2:.3e} (tol {t2}) max-rel {em:.3e} (tol {max(tol_max, 2 * t2)})"
 
     for j, (g, (st, gin)) in enumerate(zip(gpu_res, ora_res)):
         if ora_stage.ops and any(op["kind"].startswith("loss") for op in ora_stage.ops):
@@ -86,7 +99,7 @@ def compare(wl, gpu_res, gpu_grads, ora_stage, ora_res, tol=None, label=""):
             chk(f"mb{j}.out{i}", g["outs"][i], st.values[i])
         assert set(g["gin"]) == set(gin), (set(g["gin"]), set(gin))
         for i, ref in gin.items():
-            chk(f"mb{j}.gin{i}", g["gin"][i], ref)
+            chk(f"mb{j}.gin{i}", g["gin"][i], ref, tol_gin)
     for i, gr in ora_stage.grads.items():
         for k, ref in gr.items():
             chk(f"op{i}.d{k}", gpu_grads[i][k], ref)

@@ -495,3 +495,30 @@ def test_store_as_bf16_rounds_to_nearest_even_on_8_bit_significands():
     a, _ = O.run_minibatch(wl.ops, wl.micro_batch, wl.params, wl.batches, model_storage=True)
     b, _ = O.run_minibatch(wl.ops, wl.micro_batch, wl.params, wl.batches)
     assert all(np.array_equal(a.grads[i][k], b.grads[i][k]) for i in a.grads for k in a.grads[i])
+
+
+def test_relu_mask_noise_floor():
+    """Input gradients of a bf16-storage ReLU stack are decided by a few mask bits: the oracle run
+    with float32 instead of float64 accumulation of the matrix products (nothing else changed)
+    already moves them by about a percent, while weight gradients summed over the mini-batch move
+    far less.  This fixes the scale of the GPU parity bar for those tensors."""
+    wl = W.candle_uno(n_micro=4)
+    ref, res = O.run_minibatch(wl.ops, wl.micro_batch, wl.params, wl.batches, model_storage=True)
+    orig = O.linear_fwd
+
+    def linear_fwd_f32(x, p, op):
+        z = (x.astype(np.float32) @ p["W"].T.astype(np.float32)).astype(np.float64)
+        if "b" in p:
+            z = z + p["b"]
+        return O.act_fwd(z, op["act"]), (x, z)
+
+    O.linear_fwd = linear_fwd_f32
+    try:
+        ref2, res2 = O.run_minibatch(wl.ops, wl.micro_batch, wl.params, wl.batches, model_storage=True)
+    finally:
+        O.linear_fwd = orig
+    gin = [np.linalg.norm(a[1][i] - b[1][i]) / np.linalg.norm(a[1][i]) for a, b in zip(res, res2) for i in a[1]]
+    dw = [np.linalg.norm(ref.grads[i]["W"] - ref2.grads[i]["W"]) / np.linalg.norm(ref.grads[i]["W"])
+          for i in ref.grads]
+    assert 2e-3 < max(gin) < 5e-2, max(gin)       # percent-level, from a handful of mask bits
+    assert max(dw) < 2e-2
