@@ -1,13 +1,258 @@
-// Branch-grouped bf16 GEMM on the CDNA4 matrix cores (placeholder until the
-// MFMA kernels land: reports every problem as unsupported, so the planner
-// routes all GEMMs to the generic kernel).
+// Branch-grouped bf16 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16),
+// fp32 accumulation, LDS-staged tiles with a register prefetch of the next
+// k-step.  One launch covers every independent branch of a topological level:
+// the workgroup index is first spread XCD-aware (consecutive tiles of a
+// problem land on one XCD and share its L2), then mapped to (problem, tile)
+// through the records' workgroup prefix sums.
+//
+// Three forms share the kernel.  What differs is which dimension of an
+// operand is contiguous in memory:
+//   FWD  C[m,n] = sum_k X[m,k] W[n,k]      A k-contiguous,  B k-contiguous
+//   DX   C[m,k] = sum_n dZ[m,n] W[n,k]     A k-contiguous,  B row = contraction index
+//   DW   C[n,k] += sum_m dZ[m,n] X[m,k]    A and B: row = contraction index
+// Operands whose rows run along the contraction index are stored in LDS as
+// they are in memory and fetched with the transposing LDS read
+// (ds_read_b64_tr_b16), which hands each lane four consecutive contraction
+// steps of its own row/column, exactly what the MFMA operand layout wants.
 #include "device_utils.h"
 
 namespace gpp {
-bool gemm_mfma_supported(const GemmProb &) { return false; }
-int gemm_mfma_tiles(int, int, int, int, int *tiles_n) {
-  if (tiles_n) *tiles_n = 0;
-  return 0;
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr int BK = 32;        // contraction elements per k-step
+constexpr int PAD = 8;        // LDS row padding (elements)
+
+struct TileCfg {
+  int bm, bn;
+};
+__host__ __device__ constexpr int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+// ---- global -> register tile fetch -------------------------------------------
+// A tile is ROWS x COLS elements, COLS contiguous in memory; each thread owns
+// 16-byte chunks (8 elements).  Out-of-range rows / columns read as zero.
+template <int ROWS, int COLS>
+struct TileRegs {
+  static constexpr int CHUNKS = ROWS * COLS / 8;
+  static constexpr int PER_THREAD = (CHUNKS + 255) / 256;
+  u32x4 v[PER_THREAD];
+};
+
+template <int ROWS, int COLS>
+__device__ __forceinline__ void tile_fetch(TileRegs<ROWS, COLS> &t, const uint16_t *__restrict__ base, int64_t ld,
+                                           int row0, int col0, int row_lim, int col_lim) {
+  constexpr int CPR = COLS / 8;  // chunks per row
+#pragma unroll
+  for (int q = 0; q < TileRegs<ROWS, COLS>::PER_THREAD; ++q) {
+    const int c = threadIdx.x + 256 * q;
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (TileRegs<ROWS, COLS>::CHUNKS % 256 == 0 || c < TileRegs<ROWS, COLS>::CHUNKS) {
+      const int r = row0 + c / CPR, cc = col0 + (c % CPR) * 8;
+      if (r < row_lim && cc < col_lim) {
+        v = *(const u32x4 *)(base + (int64_t)r * ld + cc);
+        if (cc + 8 > col_lim) {  // ragged tail: clear the elements past the limit
+          const int keep = col_lim - cc;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            if (2 * e >= keep) v[e] = 0u;
+            else if (2 * e + 1 >= keep) v[e] &= 0xffffu;
+          }
+        }
+      }
+    }
+    t.v[q] = v;
+  }
 }
-void launch_gemm_mfma(const GemmProb *, int, int, int, int, hipStream_t) {}
+
+template <int ROWS, int COLS>
+__device__ __forceinline__ void tile_store_lds(const TileRegs<ROWS, COLS> &t, uint16_t *lds) {
+  constexpr int CPR = COLS / 8;
+  constexpr int STRIDE = COLS + PAD;
+#pragma unroll
+  for (int q = 0; q < TileRegs<ROWS, COLS>::PER_THREAD; ++q) {
+    const int c = threadIdx.x + 256 * q;
+    if (TileRegs<ROWS, COLS>::CHUNKS % 256 == 0 || c < TileRegs<ROWS, COLS>::CHUNKS)
+      *(u32x4 *)(lds + (c / CPR) * STRIDE + (c % CPR) * 8) = t.v[q];
+  }
+}
+
+// ---- LDS -> MFMA operand ---------------------------------------------------------
+// k-contiguous tile [rows][BK + PAD]: lane l takes row (l % 32), 8 k-values at 8 * (l / 32)
+__device__ __forceinline__ bf16x8 frag_kmajor(const uint16_t *lds, int row0, int k0) {
+  const int l = threadIdx.x & 63;
+  return *(const bf16x8 *)(lds + (row0 + (l & 31)) * (BK + PAD) + k0 + 8 * (l >> 5));
+}
+// contraction-row tile [BK][cols + PAD]: transposing read.  In each block of 16 lanes, lane q
+// addresses row (q / 4) at columns 4 * (q % 4) .. +3 and receives rows 0..3 of column q.
+template <int COLS>
+__device__ __forceinline__ bf16x8 frag_tr(const uint16_t *lds, int col0, int k0) {
+  const int l = threadIdx.x & 63;
+  const int blk = l >> 4, q = l & 15;
+  const uint16_t *p = lds + (k0 + 8 * (blk >> 1) + (q >> 2)) * (COLS + PAD) + col0 + 16 * (blk & 1) + 4 * (q & 3);
+  typedef __attribute__((address_space(3))) s16x4 lds_v4;
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)p);
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(p + 4 * (COLS + PAD)));
+  typedef __attribute__((ext_vector_type(8))) short s16x8;
+  s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// ---- the kernel ---------------------------------------------------------------------
+template <int FORM, int BM, int BN>
+__global__ __launch_bounds__(256) void k_gemm_mfma(const GemmProb *__restrict__ probs, int n, int total_blocks,
+                                                   int accumulate_dw) {
+  constexpr bool A_TR = FORM == FORM_DW;                  // A rows run along the contraction index
+  constexpr bool B_TR = FORM != FORM_FWD;
+  constexpr int WM = BM / 2, WN = BN / 2;                 // 2 x 2 waves
+  constexpr int TI = WM / 32, TJ = WN / 32;               // 32x32 MFMA tiles per wave
+  constexpr int A_ELEMS = A_TR ? BK * (BM + PAD) : BM * (BK + PAD);
+  constexpr int B_ELEMS = B_TR ? BK * (BN + PAD) : BN * (BK + PAD);
+  __shared__ __attribute__((aligned(16))) uint16_t lds_a[2][A_ELEMS];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_b[2][B_ELEMS];
+
+  // XCD-aware spreading: hardware deals consecutive workgroup ids round-robin over the 8 XCDs;
+  // give each XCD one contiguous range of tiles instead
+  int bid = blockIdx.x;
+  {
+    const int xcd = bid & 7, idx = bid >> 3, per = total_blocks >> 3, rem = total_blocks & 7;
+    bid = xcd * per + min(xcd, rem) + idx;
+  }
+  const int pi = find_prob(probs, n, bid);
+  const GemmProb p = probs[pi];
+  const int tile = bid - p.blk_begin;
+  const int tiles_m = cdiv(p.M, BM);
+  const int m0 = (tile % tiles_m) * BM, n0 = (tile / tiles_m) * BN;   // consecutive tiles share the B panel
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wi0 = (wave >> 1) * WM, wj0 = (wave & 1) * WN;
+  const uint16_t *A = (const uint16_t *)p.A;
+  const uint16_t *B = (const uint16_t *)p.B;
+
+  f32x16 acc[TI][TJ];
+#pragma unroll
+  for (int i = 0; i < TI; ++i)
+#pragma unroll
+    for (int j = 0; j < TJ; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  typedef TileRegs<A_TR ? BK : BM, A_TR ? BM : BK> RegsA;
+  typedef TileRegs<B_TR ? BK : BN, B_TR ? BN : BK> RegsB;
+  RegsA ra;
+  RegsB rb;
+  auto fetch = [&](int k0) {
+    if (A_TR) tile_fetch<A_TR ? BK : BM, A_TR ? BM : BK>(ra, A, p.lda, k0, m0, p.K, p.M);
+    else      tile_fetch<A_TR ? BK : BM, A_TR ? BM : BK>(ra, A, p.lda, m0, k0, p.M, p.K);
+    if (B_TR) tile_fetch<B_TR ? BK : BN, B_TR ? BN : BK>(rb, B, p.ldb, k0, n0, p.K, p.N);
+    else      tile_fetch<B_TR ? BK : BN, B_TR ? BN : BK>(rb, B, p.ldb, n0, k0, p.N, p.K);
+  };
+  const int nk = cdiv(p.K, BK);
+  fetch(0);
+  tile_store_lds<A_TR ? BK : BM, A_TR ? BM : BK>(ra, lds_a[0]);
+  tile_store_lds<B_TR ? BK : BN, B_TR ? BN : BK>(rb, lds_b[0]);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = kt & 1;
+    if (kt + 1 < nk) fetch((kt + 1) * BK);
+#pragma unroll
+    for (int kc = 0; kc < BK; kc += 16) {
+      bf16x8 a[TI], b[TJ];
+#pragma unroll
+      for (int i = 0; i < TI; ++i)
+        a[i] = A_TR ? frag_tr<BM>(lds_a[cur], wi0 + 32 * i, kc) : frag_kmajor(lds_a[cur], wi0 + 32 * i, kc);
+#pragma unroll
+      for (int j = 0; j < TJ; ++j)
+        b[j] = B_TR ? frag_tr<BN>(lds_b[cur], wj0 + 32 * j, kc) : frag_kmajor(lds_b[cur], wj0 + 32 * j, kc);
+#pragma unroll
+      for (int i = 0; i < TI; ++i)
+#pragma unroll
+        for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) {
+      tile_store_lds<A_TR ? BK : BM, A_TR ? BM : BK>(ra, lds_a[cur ^ 1]);
+      tile_store_lds<B_TR ? BK : BN, B_TR ? BN : BK>(rb, lds_b[cur ^ 1]);
+    }
+    __syncthreads();
+  }
+
+  // ---- epilogue: accumulator register r of a 32x32 tile holds row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
+#pragma unroll
+  for (int i = 0; i < TI; ++i)
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) {
+      const int col = n0 + wj0 + 32 * j + (lane & 31);
+      if (col >= p.N) continue;
+      float bias = 0.0f;
+      if (FORM == FORM_FWD && p.bias) bias = p.bias[col];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wi0 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (row >= p.M) continue;
+        float v = acc[i][j][r];
+        const int64_t ci = (int64_t)row * p.ldc + col;
+        if (FORM == FORM_FWD) {
+          v += bias;
+          if (p.aux) store_from_f32(p.aux, p.aux_dtype, (int64_t)row * p.ldaux + col, v);
+          v = act_apply(v, p.act);
+          if (p.res) v += load_as_f32(p.res, p.res_dtype, (int64_t)row * p.ldres + col);
+          store_from_f32(p.C, p.c_dtype, ci, v);
+        } else if (FORM == FORM_DX) {
+          if (p.res) v += load_as_f32(p.res, p.res_dtype, (int64_t)row * p.ldres + col);
+          if (p.act != ACT_NONE) v *= act_grad(load_as_f32(p.aux, p.aux_dtype, (int64_t)row * p.ldaux + col), p.act);
+          store_from_f32(p.C, p.c_dtype, ci, v);
+        } else {
+          float *c = (float *)p.C;
+          c[ci] = accumulate_dw ? c[ci] + v : v;
+        }
+      }
+    }
+}
+
+// ---- host side -------------------------------------------------------------------------
+static TileCfg pick_cfg(int form, int M, int N) {
+  (void)form;
+  TileCfg c;
+  c.bm = M > 64 ? 128 : 64;
+  c.bn = N > 64 ? 128 : 64;
+  if (c.bm != c.bn) c.bm = c.bn = (M > 64 && N > 64) ? 128 : 64;
+  return c;
+}
+
+bool gemm_mfma_supported(const GemmProb &p) {
+  if (p.in_dtype != DT_BF16) return false;
+  if (((uintptr_t)p.A | (uintptr_t)p.B) & 15) return false;
+  if ((p.lda | p.ldb) & 7) return false;
+  if (p.M <= 0 || p.N <= 0 || p.K <= 0) return false;
+  return true;
+}
+
+// A launch uses one tile shape for all of its problems: the planner asks for it with the largest
+// M and N of the group, then counts each problem's workgroups for that shape.
+int gemm_mfma_group_tile(int form, int maxM, int maxN) {
+  TileCfg c = pick_cfg(form, maxM, maxN);
+  return c.bm;  // square shapes only: 64 or 128
+}
+int gemm_mfma_tiles_for(int tile, int M, int N, int *tiles_n) {
+  if (tiles_n) *tiles_n = cdiv(N, tile);
+  return cdiv(M, tile) * cdiv(N, tile);
+}
+
+template <int FORM>
+static void launch_form(const GemmProb *probs, int n, int blocks, int acc, int tile, hipStream_t s) {
+  if (tile == 128)
+    hipLaunchKernelGGL((k_gemm_mfma<FORM, 128, 128>), dim3(blocks), dim3(256), 0, s, probs, n, blocks, acc);
+  else
+    hipLaunchKernelGGL((k_gemm_mfma<FORM, 64, 64>), dim3(blocks), dim3(256), 0, s, probs, n, blocks, acc);
+}
+
+void launch_gemm_mfma(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int form, int tile,
+                      hipStream_t s) {
+  if (total_blocks <= 0) return;
+  if (form == FORM_FWD) launch_form<FORM_FWD>(probs, n, total_blocks, accumulate_dw, tile, s);
+  else if (form == FORM_DX) launch_form<FORM_DX>(probs, n, total_blocks, accumulate_dw, tile, s);
+  else launch_form<FORM_DW>(probs, n, total_blocks, accumulate_dw, tile, s);
+}
+
 }  // namespace gpp

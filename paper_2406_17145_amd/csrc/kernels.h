@@ -156,10 +156,12 @@ struct StageFlags {
 
 // ---- launch entry points (defined next to the kernels) -------------------------
 void launch_gemm_generic(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int in_dtype, hipStream_t s);
-void launch_gemm_mfma(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int form, hipStream_t s);
+void launch_gemm_mfma(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int form, int tile,
+                      hipStream_t s);
 // tile geometry used by the planner to count workgroups
 int gemm_generic_tiles(int M, int N, int *tiles_n);
-int gemm_mfma_tiles(int form, int M, int N, int K, int *tiles_n);
+int gemm_mfma_group_tile(int form, int maxM, int maxN);
+int gemm_mfma_tiles_for(int tile, int M, int N, int *tiles_n);
 bool gemm_mfma_supported(const GemmProb &p);
 
 void launch_elt(const EltProb *probs, int n, int total_blocks, const ExtPtrs &ext, hipStream_t s);

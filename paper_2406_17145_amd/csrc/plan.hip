@@ -530,15 +530,21 @@ struct Emitter {
           }
           if (!use_mfma && form > 0) continue;  // the generic kernel mixes forms in one launch
           if (g.empty()) continue;
-          int blocks = 0;
+          int blocks = 0, tile = 0, max_m = 0, max_n = 0;
+          for (auto &r : g) {
+            max_m = std::max(max_m, r.M);
+            max_n = std::max(max_n, r.N);
+          }
+          if (use_mfma) tile = gemm_mfma_group_tile(form, max_m, max_n);
           for (auto &r : g) {
             r.blk_begin = blocks;
             r.split_k = 1;
-            blocks += use_mfma ? gemm_mfma_tiles(r.form, r.M, r.N, r.K, &r.tiles_n) : gemm_generic_tiles(r.M, r.N, &r.tiles_n);
+            blocks += use_mfma ? gemm_mfma_tiles_for(tile, r.M, r.N, &r.tiles_n) : gemm_generic_tiles(r.M, r.N, &r.tiles_n);
           }
           Step &s = add_step(use_mfma ? K_GEMM_MFMA : K_GEMM_GENERIC, push_table(g), (int)g.size(), blocks);
           s.a0 = dt;
           s.a1 = form;
+          s.a2 = tile;
         }
     recs.clear();
   }

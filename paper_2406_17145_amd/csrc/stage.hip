@@ -227,7 +227,7 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
         break;
       }
       case K_GEMM_GENERIC: launch_gemm_generic((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a0, s); break;
-      case K_GEMM_MFMA: launch_gemm_mfma((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a1, s); break;
+      case K_GEMM_MFMA: launch_gemm_mfma((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a1, sp.a2, s); break;
       case K_COLSUM: launch_colsum((const ColsumProb *)tab, sp.n, sp.blocks, accumulate, s); break;
       case K_LN_FWD: launch_ln_fwd((const LnProb *)tab, sp.n, sp.blocks, s); break;
       case K_LN_BWD: launch_ln_bwd((const LnProb *)tab, sp.n, sp.blocks, s); break;
