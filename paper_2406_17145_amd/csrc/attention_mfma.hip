@@ -1,0 +1,371 @@
+// Multi-head softmax attention on the CDNA4 matrix cores (bf16 in, fp32
+// accumulate, head dimension 64), forward and backward, grouped over all
+// transformer branches of a level.  Flash-style: scores are never written to
+// memory; the forward keeps the row log-sum-exp, the backward recomputes the
+// probabilities from it.
+//
+// Orientation.  v_mfma_f32_32x32x16 leaves lane l with column (l % 32) of the
+// result and 16 of its rows.  Every kernel arranges its score product so that
+// the softmax row (a query) is a lane's column wherever a row reduction is
+// needed, and so that the probabilities a lane holds are, without any
+// cross-lane traffic, the operand of the next product: the 8 contraction slots
+// a lane feeds into one MFMA are accumulator registers 8c .. 8c+7, i.e. score
+// rows 16c + {0..3, 8..11} + 4*(l / 32); the other operand is fetched from LDS
+// with the transposing read at exactly those rows (tr_frag).  Summation order
+// inside a product does not matter, so both operands only have to agree.
+//
+//   forward      S^T = K Q^T            O^T  += V^T P^T
+//   backward dQ  S^T = K Q^T, dP^T = V dO^T,  dQ^T += K^T dS^T
+//   backward dKV S   = Q K^T, dP   = dO V^T,  dV += P^T dO,  dK += dS^T Q
+// No atomics: dQ and dK/dV come from two kernels that each own their outputs.
+#include "device_utils.h"
+
+namespace gpp {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr int DH = 64;            // head dimension of the MFMA path
+constexpr int LDS_ST = DH + 8;    // LDS row stride (elements)
+constexpr int QT = 128;           // rows (queries or keys) owned by a workgroup: 4 waves x 32
+constexpr int KT = 32;            // rows of the streamed tile
+
+int attn_mfma_blocks(int batch, int heads, int seq) { return batch * heads * ((seq + QT - 1) / QT); }
+
+bool attn_mfma_supported(const AttnProb &p) {
+  if (p.dh != DH || p.dtype != DT_BF16 || p.out_dtype != DT_BF16) return false;
+  if ((p.ld_qkv | p.ld_out | p.ld_dout | p.ld_o) & 7) return false;
+  if (((uintptr_t)p.qkv | (uintptr_t)p.out | (uintptr_t)p.dout | (uintptr_t)p.o) & 15) return false;
+  return true;
+}
+
+struct Where {
+  int b, h, r0;  // sample, head, first row of this workgroup's 128-row block
+};
+__device__ __forceinline__ Where where(const AttnProb &p, int blk) {
+  const int nb = (p.seq + QT - 1) / QT;
+  const int bh = blk / nb;
+  Where w;
+  w.b = bh / p.heads;
+  w.h = bh % p.heads;
+  w.r0 = (blk % nb) * QT;
+  return w;
+}
+
+// 16-byte chunk of row `row` (zero when the row is outside the sequence)
+__device__ __forceinline__ u32x4 row_chunk(const void *base, int64_t ld, int64_t first_row, int row, int seq, int col) {
+  u32x4 v = {0u, 0u, 0u, 0u};
+  if (row < seq) v = *(const u32x4 *)((const uint16_t *)base + (first_row + row) * ld + col);
+  return v;
+}
+// the four 8-element slices of a lane's own row that one MFMA operand chain over DH = 64 needs
+struct RowFrags {
+  bf16x8 f[4];
+};
+__device__ __forceinline__ RowFrags load_row_frags(const void *base, int64_t ld, int64_t first_row, int row, int seq, int col0) {
+  const int h = (threadIdx.x & 63) >> 5;
+  RowFrags r;
+#pragma unroll
+  for (int s = 0; s < 4; ++s) r.f[s] = __builtin_bit_cast(bf16x8, row_chunk(base, ld, first_row, row, seq, col0 + 16 * s + 8 * h));
+  return r;
+}
+// k-contiguous operand from an LDS tile [rows][LDS_ST]: lane takes row (l % 32), columns 16 s + 8 (l / 32) ..
+__device__ __forceinline__ bf16x8 row_frag(const uint16_t *lds, int s) {
+  const int l = threadIdx.x & 63;
+  return *(const bf16x8 *)(lds + (l & 31) * LDS_ST + 16 * s + 8 * (l >> 5));
+}
+// transposed operand from an LDS tile [rows][LDS_ST]: lane takes column col0 + (l % 32) and rows
+// 16 c + 4 (l / 32) + {0..3} and + 8 (matching accumulator registers 8c .. 8c+7 of a score tile)
+__device__ __forceinline__ bf16x8 tr_frag(const uint16_t *lds, int col0, int c) {
+  const int l = threadIdx.x & 63;
+  const int blk = l >> 4, q = l & 15;
+  const uint16_t *p = lds + (16 * c + 4 * (blk >> 1) + (q >> 2)) * LDS_ST + col0 + 16 * (blk & 1) + 4 * (q & 3);
+  typedef __attribute__((address_space(3))) s16x4 lds_v4;
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)p);
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(p + 8 * LDS_ST));
+  s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+__device__ __forceinline__ bf16x8 pack8(const f32x16 &v, int c) {
+  bf16x8 r;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) r[e] = (bf16_t)v[8 * c + e];
+  return r;
+}
+__device__ __forceinline__ f32x16 zero16() {
+  f32x16 z;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) z[r] = 0.0f;
+  return z;
+}
+// row index inside a 32-row score tile held by accumulator register r of this lane
+__device__ __forceinline__ int acc_row(int r) { return 8 * (r >> 2) + 4 * ((threadIdx.x & 63) >> 5) + (r & 3); }
+
+// two streamed 32 x 64 tiles (one 16-byte chunk per thread each)
+struct Stream2 {
+  u32x4 a, b;
+};
+__device__ __forceinline__ void stream_store(const Stream2 &t, uint16_t *la, uint16_t *lb) {
+  const int c = threadIdx.x;
+  *(u32x4 *)(la + (c >> 3) * LDS_ST + (c & 7) * 8) = t.a;
+  *(u32x4 *)(lb + (c >> 3) * LDS_ST + (c & 7) * 8) = t.b;
+}
+
+// writes a wave's transposed 64 x 32 accumulator pair (rows = dh, lane column = its row of the block)
+// through LDS to out[row][dh] with coalesced rows
+__device__ __forceinline__ void store_transposed(uint16_t *stage, const f32x16 (&acc)[2], float mul, void *out, int64_t ld,
+                                                 int64_t first_row, int r0, int seq, int col0) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int d = 0; d < 2; ++d)
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      stage[(wave * 32 + (lane & 31)) * LDS_ST + 32 * d + acc_row(r)] = f32_to_bf16_bits(acc[d][r] * mul);
+  __syncthreads();
+  for (int c = threadIdx.x; c < QT * (DH / 8); c += 256) {
+    const int row = c >> 3, cc = (c & 7) * 8;
+    if (r0 + row < seq)
+      *(u32x4 *)((uint16_t *)out + (first_row + r0 + row) * ld + col0 + cc) = *(const u32x4 *)(stage + row * LDS_ST + cc);
+  }
+}
+
+// ======================================================================= forward
+__global__ __launch_bounds__(256) void k_attn_fwd_mfma(const AttnProb *__restrict__ probs, int n) {
+  __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][KT * LDS_ST];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][KT * LDS_ST];
+  __shared__ __attribute__((aligned(16))) uint16_t stage[QT * LDS_ST];
+  const int pi = find_prob(probs, n, blockIdx.x);
+  const AttnProb p = probs[pi];
+  const Where w = where(p, blockIdx.x - p.blk_begin);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int d = p.heads * DH;
+  const int64_t first = (int64_t)w.b * p.seq;
+  const int qcol = w.h * DH, kcol = d + w.h * DH, vcol = 2 * d + w.h * DH;
+  const int my_q = w.r0 + wave * 32 + (lane & 31);
+  const float scale = rsqrtf((float)DH);
+
+  const RowFrags qf = load_row_frags(p.qkv, p.ld_qkv, first, my_q, p.seq, qcol);
+  f32x16 o[2] = {zero16(), zero16()};
+  float m = -1e30f, lsum = 0.0f;
+
+  const int nt = (p.seq + KT - 1) / KT;
+  auto fetch = [&](int t) {
+    Stream2 s;
+    const int row = t * KT + (threadIdx.x >> 3), cc = (threadIdx.x & 7) * 8;
+    s.a = row_chunk(p.qkv, p.ld_qkv, first, row, p.seq, kcol + cc);
+    s.b = row_chunk(p.qkv, p.ld_qkv, first, row, p.seq, vcol + cc);
+    return s;
+  };
+  Stream2 nxt = fetch(0);
+  stream_store(nxt, lds_k[0], lds_v[0]);
+  __syncthreads();
+  for (int t = 0; t < nt; ++t) {
+    const int cur = t & 1;
+    if (t + 1 < nt) nxt = fetch(t + 1);
+    f32x16 st = zero16();
+#pragma unroll
+    for (int s = 0; s < 4; ++s) st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(lds_k[cur], s), qf.f[s], st, 0, 0, 0);
+    float mx = -1e30f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      st[r] = (t * KT + acc_row(r) < p.seq) ? st[r] * scale : -1e30f;
+      mx = fmaxf(mx, st[r]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m, mx);
+    const float alpha = __expf(m - m_new);
+    float ps = 0.0f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      st[r] = __expf(st[r] - m_new);
+      ps += st[r];
+    }
+    lsum = lsum * alpha + ps;
+    m = m_new;
+#pragma unroll
+    for (int dd = 0; dd < 2; ++dd)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[dd][r] *= alpha;
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      const bf16x8 pf = pack8(st, c);
+#pragma unroll
+      for (int dd = 0; dd < 2; ++dd) o[dd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(lds_v[cur], 32 * dd, c), pf, o[dd], 0, 0, 0);
+    }
+    if (t + 1 < nt) stream_store(nxt, lds_k[cur ^ 1], lds_v[cur ^ 1]);
+    __syncthreads();
+  }
+  lsum += __shfl_xor(lsum, 32, 64);
+  if (lane < 32 && my_q < p.seq) p.lse[((int64_t)w.b * p.heads + w.h) * p.seq + my_q] = m + __logf(lsum);
+  store_transposed(stage, o, 1.0f / lsum, p.out, p.ld_out, first, w.r0, p.seq, w.h * DH);
+}
+
+// ======================================================================= backward: dQ (and delta)
+__global__ __launch_bounds__(256) void k_attn_bwd_dq_mfma(const AttnProb *__restrict__ probs, int n) {
+  __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][KT * LDS_ST];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][KT * LDS_ST];
+  __shared__ __attribute__((aligned(16))) uint16_t stage[QT * LDS_ST];
+  const int pi = find_prob(probs, n, blockIdx.x);
+  const AttnProb p = probs[pi];
+  const Where w = where(p, blockIdx.x - p.blk_begin);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int d = p.heads * DH;
+  const int64_t first = (int64_t)w.b * p.seq;
+  const int qcol = w.h * DH, kcol = d + w.h * DH, vcol = 2 * d + w.h * DH;
+  const int my_q = w.r0 + wave * 32 + (lane & 31);
+  const float scale = rsqrtf((float)DH);
+  const int64_t stat = ((int64_t)w.b * p.heads + w.h) * p.seq + my_q;
+
+  const RowFrags qf = load_row_frags(p.qkv, p.ld_qkv, first, my_q, p.seq, qcol);
+  const RowFrags gf = load_row_frags(p.dout, p.ld_dout, first, my_q, p.seq, w.h * DH);
+  float delta;
+  {  // delta = rowsum(dO * O); a lane holds half of its row, its partner (lane ^ 32) the other half
+    const RowFrags of = load_row_frags(p.o, p.ld_o, first, my_q, p.seq, w.h * DH);
+    float s = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s += (float)gf.f[k][e] * (float)of.f[k][e];
+    delta = s + __shfl_xor(s, 32, 64);
+    if (lane < 32 && my_q < p.seq) p.delta[stat] = delta;
+  }
+  const float lse = my_q < p.seq ? p.lse[stat] : 0.0f;
+  f32x16 dq[2] = {zero16(), zero16()};
+
+  const int nt = (p.seq + KT - 1) / KT;
+  auto fetch = [&](int t) {
+    Stream2 s;
+    const int row = t * KT + (threadIdx.x >> 3), cc = (threadIdx.x & 7) * 8;
+    s.a = row_chunk(p.qkv, p.ld_qkv, first, row, p.seq, kcol + cc);
+    s.b = row_chunk(p.qkv, p.ld_qkv, first, row, p.seq, vcol + cc);
+    return s;
+  };
+  Stream2 nxt = fetch(0);
+  stream_store(nxt, lds_k[0], lds_v[0]);
+  __syncthreads();
+  for (int t = 0; t < nt; ++t) {
+    const int cur = t & 1;
+    if (t + 1 < nt) nxt = fetch(t + 1);
+    f32x16 st = zero16(), dp = zero16();
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(lds_k[cur], s), qf.f[s], st, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(lds_v[cur], s), gf.f[s], dp, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float pr = (t * KT + acc_row(r) < p.seq) ? __expf(st[r] * scale - lse) : 0.0f;
+      st[r] = pr * (dp[r] - delta);
+    }
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      const bf16x8 sf = pack8(st, c);
+#pragma unroll
+      for (int dd = 0; dd < 2; ++dd) dq[dd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(lds_k[cur], 32 * dd, c), sf, dq[dd], 0, 0, 0);
+    }
+    if (t + 1 < nt) stream_store(nxt, lds_k[cur ^ 1], lds_v[cur ^ 1]);
+    __syncthreads();
+  }
+  store_transposed(stage, dq, scale, p.out, p.ld_out, first, w.r0, p.seq, w.h * DH);
+}
+
+// ======================================================================= backward: dK, dV
+__global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(const AttnProb *__restrict__ probs, int n) {
+  __shared__ __attribute__((aligned(16))) uint16_t lds_q[2][KT * LDS_ST];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_g[2][KT * LDS_ST];
+  __shared__ float lds_lse[2][KT], lds_delta[2][KT];
+  const int pi = find_prob(probs, n, blockIdx.x);
+  const AttnProb p = probs[pi];
+  const Where w = where(p, blockIdx.x - p.blk_begin);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int d = p.heads * DH;
+  const int64_t first = (int64_t)w.b * p.seq;
+  const int qcol = w.h * DH, kcol = d + w.h * DH, vcol = 2 * d + w.h * DH;
+  const int my_k = w.r0 + wave * 32 + (lane & 31);
+  const float scale = rsqrtf((float)DH);
+  const int64_t stat0 = ((int64_t)w.b * p.heads + w.h) * p.seq;
+
+  const RowFrags kf = load_row_frags(p.qkv, p.ld_qkv, first, my_k, p.seq, kcol);
+  const RowFrags vf = load_row_frags(p.qkv, p.ld_qkv, first, my_k, p.seq, vcol);
+  f32x16 dk[2] = {zero16(), zero16()}, dv[2] = {zero16(), zero16()};
+
+  const int nt = (p.seq + KT - 1) / KT;
+  float n_lse = 0.0f, n_delta = 0.0f;
+  auto fetch = [&](int t) {
+    Stream2 s;
+    const int row = t * KT + (threadIdx.x >> 3), cc = (threadIdx.x & 7) * 8;
+    s.a = row_chunk(p.qkv, p.ld_qkv, first, row, p.seq, qcol + cc);
+    s.b = row_chunk(p.dout, p.ld_dout, first, row, p.seq, w.h * DH + cc);
+    if (threadIdx.x < KT) {
+      const int q = t * KT + threadIdx.x;
+      n_lse = q < p.seq ? p.lse[stat0 + q] : 0.0f;
+      n_delta = q < p.seq ? p.delta[stat0 + q] : 0.0f;
+    }
+    return s;
+  };
+  auto put = [&](const Stream2 &s, int buf) {
+    stream_store(s, lds_q[buf], lds_g[buf]);
+    if (threadIdx.x < KT) {
+      lds_lse[buf][threadIdx.x] = n_lse;
+      lds_delta[buf][threadIdx.x] = n_delta;
+    }
+  };
+  Stream2 nxt = fetch(0);
+  put(nxt, 0);
+  __syncthreads();
+  for (int t = 0; t < nt; ++t) {
+    const int cur = t & 1;
+    if (t + 1 < nt) nxt = fetch(t + 1);
+    f32x16 st = zero16(), dp = zero16();   // rows = queries of the tile, lane column = this lane's key
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(lds_q[cur], s), kf.f[s], st, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(lds_g[cur], s), vf.f[s], dp, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int qi = acc_row(r);
+      const float pr = (t * KT + qi < p.seq) ? __expf(st[r] * scale - lds_lse[cur][qi]) : 0.0f;
+      dp[r] = pr * (dp[r] - lds_delta[cur][qi]);
+      st[r] = pr;
+    }
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      const bf16x8 pf = pack8(st, c), sf = pack8(dp, c);
+#pragma unroll
+      for (int dd = 0; dd < 2; ++dd) {
+        dv[dd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, tr_frag(lds_g[cur], 32 * dd, c), dv[dd], 0, 0, 0);
+        dk[dd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sf, tr_frag(lds_q[cur], 32 * dd, c), dk[dd], 0, 0, 0);
+      }
+    }
+    if (t + 1 < nt) put(nxt, cur ^ 1);
+    __syncthreads();
+  }
+  // dk/dv: rows = this wave's keys (accumulator rows), lane column = dh: 64-byte runs per register
+  uint16_t *out = (uint16_t *)p.out;
+#pragma unroll
+  for (int dd = 0; dd < 2; ++dd)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int key = w.r0 + wave * 32 + acc_row(r);
+      if (key >= p.seq) continue;
+      const int64_t ro = (first + key) * p.ld_out + w.h * DH + 32 * dd + (lane & 31);
+      out[ro + d] = f32_to_bf16_bits(dk[dd][r] * scale);
+      out[ro + 2 * d] = f32_to_bf16_bits(dv[dd][r]);
+    }
+}
+
+void launch_attn_fwd_mfma(const AttnProb *probs, int n, int total_blocks, hipStream_t s) {
+  if (total_blocks > 0) hipLaunchKernelGGL(k_attn_fwd_mfma, dim3(total_blocks), dim3(256), 0, s, probs, n);
+}
+void launch_attn_bwd_dq_mfma(const AttnProb *probs, int n, int total_blocks, hipStream_t s) {
+  if (total_blocks > 0) hipLaunchKernelGGL(k_attn_bwd_dq_mfma, dim3(total_blocks), dim3(256), 0, s, probs, n);
+}
+void launch_attn_bwd_dkv_mfma(const AttnProb *probs, int n, int total_blocks, hipStream_t s) {
+  if (total_blocks > 0) hipLaunchKernelGGL(k_attn_bwd_dkv_mfma, dim3(total_blocks), dim3(256), 0, s, probs, n);
+}
+
+}  // namespace gpp

@@ -9,6 +9,8 @@ namespace gpp {
 
 // launch helpers defined next to their kernels
 int attn_max_seq();
+int attn_mfma_blocks(int batch, int heads, int seq);
+bool attn_mfma_supported(const AttnProb &p);
 size_t interact_lds_bytes(int F, int d);
 
 static int64_t align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
@@ -770,12 +772,16 @@ void Emitter::forward() {
     }
     if (!attns.empty()) {
       int blocks = 0, ms = 0;
+      bool mfma = !(pl.flags & 1);
+      for (auto &a : attns) mfma = mfma && attn_mfma_supported(a);
       for (auto &a : attns) {
         a.blk_begin = blocks;
-        blocks += attn_blocks(a.batch, a.heads, a.seq);
+        blocks += mfma ? attn_mfma_blocks(a.batch, a.heads, a.seq) : attn_blocks(a.batch, a.heads, a.seq);
         ms = std::max(ms, a.seq);
       }
-      add_step(K_ATTN_FWD, push_table(attns), (int)attns.size(), blocks).a0 = ms;
+      Step &s = add_step(K_ATTN_FWD, push_table(attns), (int)attns.size(), blocks);
+      s.a0 = ms;
+      s.a1 = mfma ? 1 : 0;
     }
     emit_elt(elts);
     if (!pools.empty()) {
@@ -1181,14 +1187,20 @@ void Emitter::backward() {
     }
     if (!attns.empty()) {
       int blocks = 0, ms = 0;
+      bool mfma = !(pl.flags & 1);
+      for (auto &a : attns) mfma = mfma && attn_mfma_supported(a) && a.grad_dtype == DT_BF16;
       for (auto &a : attns) {
         a.blk_begin = blocks;
-        blocks += attn_blocks(a.batch, a.heads, a.seq);
+        blocks += mfma ? attn_mfma_blocks(a.batch, a.heads, a.seq) : attn_blocks(a.batch, a.heads, a.seq);
         ms = std::max(ms, a.seq);
       }
       int64_t off = push_table(attns);
-      add_step(K_ATTN_DQ, off, (int)attns.size(), blocks).a0 = ms;
-      add_step(K_ATTN_DKV, off, (int)attns.size(), blocks).a0 = ms;
+      Step &s1 = add_step(K_ATTN_DQ, off, (int)attns.size(), blocks);
+      s1.a0 = ms;
+      s1.a1 = mfma ? 1 : 0;
+      Step &s2 = add_step(K_ATTN_DKV, off, (int)attns.size(), blocks);
+      s2.a0 = ms;
+      s2.a1 = mfma ? 1 : 0;
     }
     if (!pools.empty()) {
       int blocks = 0;

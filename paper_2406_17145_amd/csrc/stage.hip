@@ -18,6 +18,9 @@ void launch_gemm_generic(const GemmProb *probs, int n, int total_blocks, int acc
 void launch_attn_fwd(const AttnProb *probs, int n, int total_blocks, int max_seq, hipStream_t s);
 void launch_attn_bwd_dq(const AttnProb *probs, int n, int total_blocks, int max_seq, hipStream_t s);
 void launch_attn_bwd_dkv(const AttnProb *probs, int n, int total_blocks, int max_seq, hipStream_t s);
+void launch_attn_fwd_mfma(const AttnProb *probs, int n, int total_blocks, hipStream_t s);
+void launch_attn_bwd_dq_mfma(const AttnProb *probs, int n, int total_blocks, hipStream_t s);
+void launch_attn_bwd_dkv_mfma(const AttnProb *probs, int n, int total_blocks, hipStream_t s);
 void launch_interact_fwd(const InteractProb *probs, int n, int total_blocks, int maxF, int maxd, hipStream_t s);
 void launch_interact_bwd(const InteractProb *probs, int n, int total_blocks, int maxF, int maxd, hipStream_t s);
 void launch_loss_sum(const float *losses, int n, float *out, hipStream_t s);
@@ -232,9 +235,18 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
       case K_LN_FWD: launch_ln_fwd((const LnProb *)tab, sp.n, sp.blocks, s); break;
       case K_LN_BWD: launch_ln_bwd((const LnProb *)tab, sp.n, sp.blocks, s); break;
       case K_LN_BWD_PARAMS: launch_ln_bwd_params((const LnProb *)tab, sp.n, sp.blocks, accumulate, s); break;
-      case K_ATTN_FWD: launch_attn_fwd((const AttnProb *)tab, sp.n, sp.blocks, sp.a0, s); break;
-      case K_ATTN_DQ: launch_attn_bwd_dq((const AttnProb *)tab, sp.n, sp.blocks, sp.a0, s); break;
-      case K_ATTN_DKV: launch_attn_bwd_dkv((const AttnProb *)tab, sp.n, sp.blocks, sp.a0, s); break;
+      case K_ATTN_FWD:
+        if (sp.a1) launch_attn_fwd_mfma((const AttnProb *)tab, sp.n, sp.blocks, s);
+        else launch_attn_fwd((const AttnProb *)tab, sp.n, sp.blocks, sp.a0, s);
+        break;
+      case K_ATTN_DQ:
+        if (sp.a1) launch_attn_bwd_dq_mfma((const AttnProb *)tab, sp.n, sp.blocks, s);
+        else launch_attn_bwd_dq((const AttnProb *)tab, sp.n, sp.blocks, sp.a0, s);
+        break;
+      case K_ATTN_DKV:
+        if (sp.a1) launch_attn_bwd_dkv_mfma((const AttnProb *)tab, sp.n, sp.blocks, s);
+        else launch_attn_bwd_dkv((const AttnProb *)tab, sp.n, sp.blocks, sp.a0, s);
+        break;
       case K_POOL: launch_pool((const PoolProb *)tab, sp.n, sp.blocks, s); break;
       case K_EMB_FWD: launch_emb_fwd((const EmbProb *)tab, sp.n, sp.blocks, flags, s); break;
       case K_EMB_BWD:

@@ -79,6 +79,14 @@ def test_transformer_bf16_small():
                seq_len=96, d_head_out=64, n_classes=50))
 
 
+def test_transformer_bf16_ragged_sequence():
+    # head dimension 64 (matrix-core attention path), sequence length not a multiple of any tile
+    both(W.mmt(micro_batch=3, n_micro=1, n_branches=2, n_layers=1, d_model=192, heads=3, d_ff=200,
+               seq_len=83, d_head_out=40, n_classes=30))
+    both(W.mmt(micro_batch=1, n_micro=1, n_branches=1, n_layers=1, d_model=64, heads=1, d_ff=64,
+               seq_len=301, d_head_out=16, n_classes=5))
+
+
 def test_dlrm_bf16_small():
     both(W.dlrm(micro_batch=256, n_micro=2, n_tables=6, num_rows=5000, bottom=(64, 32, 128),
                 top=(128, 64, 1)))
