@@ -162,7 +162,8 @@ gpp_status_t gpp_stage_backward(gpp_stage_t *stage, int32_t slot, const void *co
 
 /* Iteration boundary (weights are updated once per mini-batch): the next backward starts new sums.
  * Dense accumulators are not touched by this call (their next write overwrites); embedding-table
- * accumulators are cleared on the stream.  Errors: GPP_ERR_ORDER while a micro-batch is in flight. */
+ * accumulators are cleared on the stream: only the rows that the backward passes since the previous
+ * reset touched when at most four such passes ran, whole tables otherwise (and the first time).  Errors: GPP_ERR_ORDER while a micro-batch is in flight. */
 gpp_status_t gpp_stage_grad_reset(gpp_stage_t *stage, void *hip_stream);
 
 /* Waits for the stream and reports GPP_ERR_INDEX if any kernel since the last call met an embedding

@@ -3,7 +3,8 @@
 //   backward  deterministic sorted segment reduction:
 //             stable LSD radix sort of (row, position) keys -> segment heads ->
 //             per-row sums in sorted order -> one read-modify-write per distinct row
-// plus the pairwise-dot feature interaction.  No float atomics anywhere, so two
+//   reset     clears only the rows the backward passes since the last reset touched
+// No float atomics anywhere and every sum has a fixed association order, so two
 // runs give bit-identical gradients.
 #include "device_utils.h"
 
@@ -11,13 +12,53 @@ namespace gpp {
 
 constexpr int RADIX_BITS = 9;
 constexpr int RADIX = 1 << RADIX_BITS;
-constexpr int SORT_CHUNK = 2048;  // keys per workgroup per pass (256 threads x 8 rounds)
+constexpr int SORT_CHUNK = 2048;   // keys per workgroup per pass (256 threads x 8 rounds)
+constexpr int LONG_SEG = 256;      // segments longer than this get a whole workgroup
+constexpr int LOG_SLOTS = 4;       // backward passes whose touched-row lists are kept for the reset
 
 int emb_sort_chunk() { return SORT_CHUNK; }
 int emb_radix_bits() { return RADIX_BITS; }
+int emb_long_segment() { return LONG_SEG; }
+int emb_log_slots() { return LOG_SLOTS; }
 int emb_fwd_blocks(int n_bags) { return (n_bags + 3) / 4; }
 
+// number of index positions in use = last offset, clamped to the capacity
+__device__ __forceinline__ int used_positions(const EmbProb &p) { return max(0, min(p.offsets[p.n_bags], p.capacity)); }
+// out-of-range rows are sorted as the nearest valid row; the segment sum skips them
+__device__ __forceinline__ int clamp_row(int r, int num_rows) { return max(0, min(r, num_rows - 1)); }
+
+// lanes that share one table row in the vector kernels: dim/4 rounded up to a power of two
+__device__ __forceinline__ int lanes_per_row(int dim) {
+  int l = 1;
+  while (l * 4 < dim) l <<= 1;
+  return l;
+}
+__device__ __forceinline__ float4 f4_add(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
+__device__ __forceinline__ float4 f4_shfl_down(float4 v, int d) {
+  return make_float4(__shfl_down(v.x, d, 64), __shfl_down(v.y, d, 64), __shfl_down(v.z, d, 64), __shfl_down(v.w, d, 64));
+}
+// four consecutive elements of a pooled-output (or its gradient) row as floats
+__device__ __forceinline__ float4 load4(const void *base, int dtype, int64_t idx) {
+  if (dtype == DT_BF16) {
+    const uint2 u = *(const uint2 *)((const uint16_t *)base + idx);
+    return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u), __uint_as_float(u.y << 16),
+                       __uint_as_float(u.y & 0xffff0000u));
+  }
+  return *(const float4 *)((const float *)base + idx);
+}
+__device__ __forceinline__ void store4(void *base, int dtype, int64_t idx, float4 v) {
+  if (dtype == DT_BF16) {
+    uint2 u;
+    u.x = (uint32_t)f32_to_bf16_bits(v.x) | ((uint32_t)f32_to_bf16_bits(v.y) << 16);
+    u.y = (uint32_t)f32_to_bf16_bits(v.z) | ((uint32_t)f32_to_bf16_bits(v.w) << 16);
+    *(uint2 *)((uint16_t *)base + idx) = u;
+  } else {
+    *(float4 *)((float *)base + idx) = v;
+  }
+}
+
 // ------------------------------------------------------------------ forward
+// generic: one wave per bag, a lane per column (any dimension up to 256)
 __global__ __launch_bounds__(256) void k_emb_fwd(const EmbProb *__restrict__ probs, int n, StageFlags *flags) {
   const int pi = find_prob(probs, n, blockIdx.x);
   const EmbProb p = probs[pi];
@@ -50,9 +91,55 @@ __global__ __launch_bounds__(256) void k_emb_fwd(const EmbProb *__restrict__ pro
   }
   if (bad && lane == 0) flags->index_error = 1;
 }
-void launch_emb_fwd(const EmbProb *probs, int n, int total_blocks, StageFlags *flags, hipStream_t s) {
+
+// vector: one wave per bag; LPR lanes read one 16-byte piece of a row each, so a wave has
+// 64/LPR rows in flight per step and four steps unrolled; the sub-groups are combined in lane order
+__global__ __launch_bounds__(256) void k_emb_fwd_vec(const EmbProb *__restrict__ probs, int n, StageFlags *flags) {
+  const int pi = find_prob(probs, n, blockIdx.x);
+  const EmbProb p = probs[pi];
+  const int lane = threadIdx.x & 63;
+  const int bag = (blockIdx.x - p.blk_begin) * 4 + (threadIdx.x >> 6);
+  if (bag >= p.n_bags) return;
+  int lo = p.offsets[bag], hi = p.offsets[bag + 1];
+  bool bad = lo < 0 || hi < lo || hi > p.capacity;
+  lo = max(0, min(lo, p.capacity));
+  hi = max(lo, min(hi, p.capacity));
+  const int lpr = lanes_per_row(p.dim), rpi = 64 / lpr;
+  const int sub = lane / lpr, c4 = (lane % lpr) * 4;
+  const bool col_ok = c4 < p.dim;
+  float4 acc = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+  for (int base = lo; base < hi; base += 64) {
+    const int cnt = min(64, hi - base);
+    int my = -1;
+    if (lane < cnt) {
+      my = p.indices[base + lane];
+      p.bag_of[base + lane] = bag;
+      if (my < 0 || my >= p.num_rows) {
+        bad = true;
+        my = -1;
+      }
+    }
+#pragma unroll 4
+    for (int j = 0; j < cnt; j += rpi) {
+      const int r = __shfl(my, min(j + sub, 63), 64);
+      if (j + sub < cnt && r >= 0 && col_ok) acc = f4_add(acc, *(const float4 *)(p.table + (int64_t)r * p.ld_table + c4));
+    }
+  }
+  for (int d = lpr; d < 64; d <<= 1) acc = f4_add(acc, f4_shfl_down(acc, d));
+  if (sub == 0 && col_ok) store4(p.out, p.out_dtype, (int64_t)bag * p.ld_out + c4, acc);
+  if (__any(bad) && lane == 0) flags->index_error = 1;
+}
+
+bool emb_vec_supported(const EmbProb &p) {
+  if ((p.dim & 3) || p.dim > 256 || (p.ld_table & 3) || (p.ld_out & 3)) return false;
+  if (((uintptr_t)p.table | (uintptr_t)p.dtable) & 15) return false;
+  if ((uintptr_t)p.out & 15) return false;
+  return true;
+}
+void launch_emb_fwd(const EmbProb *probs, int n, int total_blocks, int vec, StageFlags *flags, hipStream_t s) {
   if (total_blocks <= 0) return;
-  hipLaunchKernelGGL(k_emb_fwd, dim3(total_blocks), dim3(256), 0, s, probs, n, flags);
+  if (vec) hipLaunchKernelGGL(k_emb_fwd_vec, dim3(total_blocks), dim3(256), 0, s, probs, n, flags);
+  else hipLaunchKernelGGL(k_emb_fwd, dim3(total_blocks), dim3(256), 0, s, probs, n, flags);
 }
 
 // ------------------------------------------------------------------ stable radix sort by row
@@ -72,10 +159,6 @@ __device__ __forceinline__ SortIo sort_io(const EmbProb &p, int pass) {
   }
   return io;
 }
-// number of index positions in use = last offset, clamped to the capacity
-__device__ __forceinline__ int used_positions(const EmbProb &p) { return max(0, min(p.offsets[p.n_bags], p.capacity)); }
-// out-of-range rows are sorted as the nearest valid row; the segment sum skips them
-__device__ __forceinline__ int clamp_row(int r, int num_rows) { return max(0, min(r, num_rows - 1)); }
 
 __global__ __launch_bounds__(256) void k_sort_hist(const EmbProb *__restrict__ probs, int pass) {
   __shared__ int hist[RADIX];
@@ -97,39 +180,46 @@ __global__ __launch_bounds__(256) void k_sort_hist(const EmbProb *__restrict__ p
   for (int d = threadIdx.x; d < RADIX; d += 256) p.hist[d * p.sort_blocks + blockIdx.x] = hist[d];
 }
 
-// exclusive scan over the digit-major [RADIX][sort_blocks] counts of one table
-__global__ __launch_bounds__(1024) void k_sort_scan(const EmbProb *__restrict__ probs, int pass) {
-  __shared__ int part[1024];
-  const EmbProb p = probs[blockIdx.x];
-  if (pass >= p.passes) return;
-  const int total = RADIX * p.sort_blocks;
-  const int per = (total + 1023) / 1024;
-  const int lo = threadIdx.x * per, hi = min(total, lo + per);
-  int s = 0;
-  for (int i = lo; i < hi; ++i) s += p.hist[i];
-  part[threadIdx.x] = s;
-  __syncthreads();
-  for (int o = 1; o < 1024; o <<= 1) {
-    int v = threadIdx.x >= o ? part[threadIdx.x - o] : 0;
-    __syncthreads();
-    part[threadIdx.x] += v;
-    __syncthreads();
-  }
-  int run = part[threadIdx.x] - s;
-  for (int i = lo; i < hi; ++i) {
-    int c = p.hist[i];
-    p.hist[i] = run;
-    run += c;
-  }
-}
-
+// Each workgroup first derives its own output offsets from the digit-major [RADIX][sort_blocks]
+// count table (exclusive scan over digits of the per-digit totals, plus the counts of the blocks
+// before it), then ranks its keys round by round, waves in order, so the scatter is stable.
 __global__ __launch_bounds__(256) void k_sort_scatter(const EmbProb *__restrict__ probs, int pass) {
   __shared__ int next[RADIX];
+  __shared__ int scan[256];
   const EmbProb p = probs[blockIdx.y];
   if ((int)blockIdx.x >= p.sort_blocks || pass >= p.passes) return;
   const int n_used = used_positions(p);
   const SortIo io = sort_io(p, pass);
-  for (int d = threadIdx.x; d < RADIX; d += 256) next[d] = p.hist[d * p.sort_blocks + blockIdx.x];
+  {
+    int tot[RADIX / 256], mine[RADIX / 256], pair = 0;
+#pragma unroll
+    for (int k = 0; k < RADIX / 256; ++k) {
+      const int d = threadIdx.x * (RADIX / 256) + k;
+      int t = 0, m = 0;
+      for (int b = 0; b < p.sort_blocks; ++b) {
+        const int c = p.hist[d * p.sort_blocks + b];
+        t += c;
+        if (b < (int)blockIdx.x) m += c;
+      }
+      tot[k] = t;
+      mine[k] = m;
+      pair += t;
+    }
+    scan[threadIdx.x] = pair;
+    __syncthreads();
+    for (int o = 1; o < 256; o <<= 1) {
+      const int v = (int)threadIdx.x >= o ? scan[threadIdx.x - o] : 0;
+      __syncthreads();
+      scan[threadIdx.x] += v;
+      __syncthreads();
+    }
+    int run = scan[threadIdx.x] - pair;
+#pragma unroll
+    for (int k = 0; k < RADIX / 256; ++k) {
+      next[threadIdx.x * (RADIX / 256) + k] = run + mine[k];
+      run += tot[k];
+    }
+  }
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint64_t lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
@@ -166,47 +256,170 @@ __global__ __launch_bounds__(256) void k_sort_scatter(const EmbProb *__restrict_
   }
 }
 
-// segment heads of the sorted keys -> unique_rows, seg_offsets, counts[1]
-__global__ __launch_bounds__(1024) void k_segments(const EmbProb *__restrict__ probs) {
-  __shared__ int part[1024];
-  const EmbProb p = probs[blockIdx.x];
+// ------------------------------------------------------------------ segment heads
+__device__ __forceinline__ const int32_t *sorted_keys(const EmbProb &p) { return (p.passes & 1) ? p.keys_a : p.keys_b; }
+__device__ __forceinline__ const int32_t *sorted_pos(const EmbProb &p) { return (p.passes & 1) ? p.pos_a : p.pos_b; }
+
+// heads per chunk of SORT_CHUNK sorted keys (stored in the first sort_blocks entries of `hist`)
+__global__ __launch_bounds__(256) void k_seg_count(const EmbProb *__restrict__ probs, int slot) {
+  __shared__ int red[4];
+  const EmbProb p = probs[blockIdx.y];
+  if ((int)blockIdx.x >= p.sort_blocks) return;
   const int n_used = used_positions(p);
-  const int32_t *keys = (p.passes & 1) ? p.keys_a : p.keys_b;
-  const int per = (n_used + 1023) / 1024;
-  const int lo = min(n_used, (int)threadIdx.x * per), hi = min(n_used, lo + per);
+  const int32_t *keys = sorted_keys(p);
+  const int base = blockIdx.x * SORT_CHUNK + threadIdx.x * (SORT_CHUNK / 256);
   int s = 0;
-  for (int i = lo; i < hi; ++i) s += (i == 0 || keys[i] != keys[i - 1]) ? 1 : 0;
-  part[threadIdx.x] = s;
-  __syncthreads();
-  for (int o = 1; o < 1024; o <<= 1) {
-    int v = threadIdx.x >= o ? part[threadIdx.x - o] : 0;
-    __syncthreads();
-    part[threadIdx.x] += v;
-    __syncthreads();
+#pragma unroll
+  for (int e = 0; e < SORT_CHUNK / 256; ++e) {
+    const int i = base + e;
+    if (i < n_used && (i == 0 || keys[i] != keys[i - 1])) ++s;
   }
-  int u = part[threadIdx.x] - s;
-  for (int i = lo; i < hi; ++i)
-    if (i == 0 || keys[i] != keys[i - 1]) {
-      p.unique_rows[u] = keys[i];
-      p.seg_offsets[u] = i;
-      ++u;
-    }
-  if (threadIdx.x == 1023) {
-    p.counts[0] = n_used;
-    p.counts[1] = part[1023];
-    p.seg_offsets[part[1023]] = n_used;
+  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    p.hist[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
+    if (blockIdx.x == 0) p.counts[slot * 4 + 2] = 0;  // long-segment counter
   }
 }
 
-// one wave per distinct row: sum the pooled-output gradients of its positions in sorted order
-__global__ __launch_bounds__(256) void k_emb_bwd(const EmbProb *__restrict__ probs) {
+// unique_rows[slot], seg_offsets, counts[slot] = {n_used, n_unique, n_long}
+__global__ __launch_bounds__(256) void k_seg_write(const EmbProb *__restrict__ probs, int slot) {
+  __shared__ int scan[256];
+  __shared__ int before_s, total_s;
+  const EmbProb p = probs[blockIdx.y];
+  if ((int)blockIdx.x >= p.sort_blocks) return;
+  const int n_used = used_positions(p);
+  const int32_t *keys = sorted_keys(p);
+  int32_t *uniq = p.unique_rows + (int64_t)slot * p.capacity;
+  if (threadIdx.x < 64) {   // one wave folds the per-chunk head counts
+    int before = 0, total = 0;
+    for (int b = threadIdx.x; b < p.sort_blocks; b += 64) {
+      const int c = p.hist[b];
+      total += c;
+      if (b < (int)blockIdx.x) before += c;
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+      before += __shfl_xor(before, o, 64);
+      total += __shfl_xor(total, o, 64);
+    }
+    if (threadIdx.x == 0) {
+      before_s = before;
+      total_s = total;
+    }
+  }
+  const int base = blockIdx.x * SORT_CHUNK + threadIdx.x * (SORT_CHUNK / 256);
+  int s = 0;
+#pragma unroll
+  for (int e = 0; e < SORT_CHUNK / 256; ++e) {
+    const int i = base + e;
+    if (i < n_used && (i == 0 || keys[i] != keys[i - 1])) ++s;
+  }
+  scan[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = 1; o < 256; o <<= 1) {
+    const int v = (int)threadIdx.x >= o ? scan[threadIdx.x - o] : 0;
+    __syncthreads();
+    scan[threadIdx.x] += v;
+    __syncthreads();
+  }
+  int u = before_s + scan[threadIdx.x] - s;
+#pragma unroll
+  for (int e = 0; e < SORT_CHUNK / 256; ++e) {
+    const int i = base + e;
+    if (i < n_used && (i == 0 || keys[i] != keys[i - 1])) {
+      uniq[u] = keys[i];
+      p.seg_offsets[u] = i;
+      ++u;
+    }
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    p.counts[slot * 4 + 0] = n_used;
+    p.counts[slot * 4 + 1] = total_s;
+    p.seg_offsets[total_s] = n_used;
+  }
+}
+
+// ------------------------------------------------------------------ segment sums
+// Sum of the pooled-output gradient rows of sorted positions [lo, hi), in sorted order within each
+// of the wave's 64/LPR lane groups; the groups are then combined in lane order.  Every lane ends up
+// with the same float4 for its columns only in group 0 (the caller uses that one).
+__device__ __forceinline__ float4 segment_partial(const EmbProb &p, const int32_t *spos, int lo, int hi, int lpr) {
+  const int lane = threadIdx.x & 63;
+  const int rpi = 64 / lpr, sub = lane / lpr, c4 = (lane % lpr) * 4;
+  const bool col_ok = c4 < p.dim;
+  float4 acc = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+  for (int base = lo; base < hi; base += 64) {
+    const int cnt = min(64, hi - base);
+    int my_bag = -1;
+    if (lane < cnt) {
+      const int pos = spos[base + lane];
+      const int r = p.indices[pos];
+      if (r >= 0 && r < p.num_rows) my_bag = p.bag_of[pos];
+    }
+#pragma unroll 4
+    for (int j = 0; j < cnt; j += rpi) {
+      const int bag = __shfl(my_bag, min(j + sub, 63), 64);
+      if (j + sub < cnt && bag >= 0 && col_ok) acc = f4_add(acc, load4(p.out, p.out_dtype, (int64_t)bag * p.ld_out + c4));
+    }
+  }
+  for (int d = lpr; d < 64; d <<= 1) acc = f4_add(acc, f4_shfl_down(acc, d));
+  return acc;
+}
+
+// one wave per distinct row; rows with more than LONG_SEG positions are queued for k_emb_bwd_long
+__global__ __launch_bounds__(256) void k_emb_bwd_short(const EmbProb *__restrict__ probs, int slot) {
   const EmbProb p = probs[blockIdx.y];
   const int lane = threadIdx.x & 63;
   const int u = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (u >= p.counts[1]) return;
-  const int32_t *spos = (p.passes & 1) ? p.pos_a : p.pos_b;
+  if (u >= p.counts[slot * 4 + 1]) return;
   const int lo = p.seg_offsets[u], hi = p.seg_offsets[u + 1];
-  const int row = p.unique_rows[u];
+  if (hi - lo > LONG_SEG) {
+    if (lane == 0) p.long_list[atomicAdd(&p.counts[slot * 4 + 2], 1)] = u;
+    return;
+  }
+  const int lpr = lanes_per_row(p.dim);
+  const float4 acc = segment_partial(p, sorted_pos(p), lo, hi, lpr);
+  const int c4 = (lane % lpr) * 4;
+  if (lane < lpr && c4 < p.dim) {
+    float4 *d = (float4 *)(p.dtable + (int64_t)p.unique_rows[(int64_t)slot * p.capacity + u] * p.ld_table + c4);
+    *d = f4_add(*d, acc);
+  }
+}
+
+// one workgroup of 16 waves per long segment: each wave sums a contiguous slice, slices are
+// combined in order through LDS
+__global__ __launch_bounds__(1024) void k_emb_bwd_long(const EmbProb *__restrict__ probs, int slot) {
+  __shared__ float4 part[16][64];
+  const EmbProb p = probs[blockIdx.y];
+  if ((int)blockIdx.x >= p.counts[slot * 4 + 2]) return;
+  const int u = p.long_list[blockIdx.x];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lo = p.seg_offsets[u], hi = p.seg_offsets[u + 1];
+  const int per = (hi - lo + 15) / 16;
+  const int a = min(hi, lo + wave * per), b = min(hi, a + per);
+  const int lpr = lanes_per_row(p.dim);
+  part[wave][lane] = segment_partial(p, sorted_pos(p), a, b, lpr);
+  __syncthreads();
+  const int c4 = lane * 4;
+  if (wave == 0 && lane < lpr && c4 < p.dim) {
+    float4 acc = part[0][lane];
+#pragma unroll
+    for (int w = 1; w < 16; ++w) acc = f4_add(acc, part[w][lane]);
+    float4 *d = (float4 *)(p.dtable + (int64_t)p.unique_rows[(int64_t)slot * p.capacity + u] * p.ld_table + c4);
+    *d = f4_add(*d, acc);
+  }
+}
+
+// scalar fallback (dimension not a multiple of 4): one wave per distinct row, a lane per column
+__global__ __launch_bounds__(256) void k_emb_bwd_generic(const EmbProb *__restrict__ probs, int slot) {
+  const EmbProb p = probs[blockIdx.y];
+  const int lane = threadIdx.x & 63;
+  const int u = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (u >= p.counts[slot * 4 + 1]) return;
+  const int32_t *spos = sorted_pos(p);
+  const int lo = p.seg_offsets[u], hi = p.seg_offsets[u + 1];
+  const int row = p.unique_rows[(int64_t)slot * p.capacity + u];
   float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
   for (int q = lo; q < hi; ++q) {
     const int pos = spos[q];
@@ -227,23 +440,28 @@ __global__ __launch_bounds__(256) void k_emb_bwd(const EmbProb *__restrict__ pro
   }
 }
 
-int emb_bwd_num_launches(int max_passes) { return 3 * max_passes + 2; }
+int emb_bwd_num_launches(int max_passes, int vec) { return 2 * max_passes + 2 + (vec ? 2 : 1); }
 
-int launch_emb_bwd(const EmbProb *probs, int n, int max_capacity, int max_sort_blocks, int max_passes,
-                   StageFlags *flags, hipStream_t s) {
-  (void)flags;
+int launch_emb_bwd(const EmbProb *probs, int n, int max_capacity, int max_sort_blocks, int max_passes, int vec,
+                   int slot, hipStream_t s) {
   if (n <= 0) return 0;
   for (int pass = 0; pass < max_passes; ++pass) {
     hipLaunchKernelGGL(k_sort_hist, dim3(max_sort_blocks, n), dim3(256), 0, s, probs, pass);
-    hipLaunchKernelGGL(k_sort_scan, dim3(n), dim3(1024), 0, s, probs, pass);
     hipLaunchKernelGGL(k_sort_scatter, dim3(max_sort_blocks, n), dim3(256), 0, s, probs, pass);
   }
-  hipLaunchKernelGGL(k_segments, dim3(n), dim3(1024), 0, s, probs);
-  hipLaunchKernelGGL(k_emb_bwd, dim3((max_capacity + 3) / 4, n), dim3(256), 0, s, probs);
-  return emb_bwd_num_launches(max_passes);
+  hipLaunchKernelGGL(k_seg_count, dim3(max_sort_blocks, n), dim3(256), 0, s, probs, slot);
+  hipLaunchKernelGGL(k_seg_write, dim3(max_sort_blocks, n), dim3(256), 0, s, probs, slot);
+  if (vec) {
+    hipLaunchKernelGGL(k_emb_bwd_short, dim3((max_capacity + 3) / 4, n), dim3(256), 0, s, probs, slot);
+    hipLaunchKernelGGL(k_emb_bwd_long, dim3(max_capacity / LONG_SEG + 1, n), dim3(1024), 0, s, probs, slot);
+  } else {
+    hipLaunchKernelGGL(k_emb_bwd_generic, dim3((max_capacity + 3) / 4, n), dim3(256), 0, s, probs, slot);
+  }
+  return emb_bwd_num_launches(max_passes, vec);
 }
 
-// clears the table-gradient accumulators (iteration boundary)
+// ------------------------------------------------------------------ gradient clear
+// full clear of the table-gradient accumulators
 __global__ __launch_bounds__(256) void k_emb_reset(const EmbProb *__restrict__ probs) {
   const EmbProb p = probs[blockIdx.y];
   const int64_t total = (int64_t)p.num_rows * p.ld_table / 4;  // ld_table is a multiple of 8
@@ -251,77 +469,19 @@ __global__ __launch_bounds__(256) void k_emb_reset(const EmbProb *__restrict__ p
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256)
     d[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 }
-void launch_emb_reset(const EmbProb *probs, int n, hipStream_t s) {
+// sparse clear: only the rows listed by the last `slots` backward passes (one wave per listed row)
+__global__ __launch_bounds__(256) void k_emb_reset_rows(const EmbProb *__restrict__ probs) {
+  const EmbProb p = probs[blockIdx.y];
+  const int slot = blockIdx.z;
+  const int u = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (u >= p.counts[slot * 4 + 1]) return;
+  float *drow = p.dtable + (int64_t)p.unique_rows[(int64_t)slot * p.capacity + u] * p.ld_table;
+  for (int c = threadIdx.x & 63; c < p.dim; c += 64) drow[c] = 0.0f;
+}
+void launch_emb_reset(const EmbProb *probs, int n, int max_capacity, int slots, hipStream_t s) {
   if (n <= 0) return;
-  hipLaunchKernelGGL(k_emb_reset, dim3(1024, n), dim3(256), 0, s, probs);
+  if (slots <= 0) hipLaunchKernelGGL(k_emb_reset, dim3(1024, n), dim3(256), 0, s, probs);
+  else hipLaunchKernelGGL(k_emb_reset_rows, dim3((max_capacity + 3) / 4, n, slots), dim3(256), 0, s, probs);
 }
-
-// ------------------------------------------------------------------ pairwise-dot interaction
-// one workgroup per sample; the F vectors sit in LDS
-__device__ __forceinline__ void term_to_pair(int t, int &i, int &j) {
-  i = (int)((1.0f + sqrtf(1.0f + 8.0f * (float)t)) * 0.5f);
-  while (i * (i - 1) / 2 > t) --i;
-  while ((i + 1) * i / 2 <= t) ++i;
-  j = t - i * (i - 1) / 2;
-}
-
-__global__ __launch_bounds__(256) void k_interact_fwd(const InteractProb *__restrict__ probs, int n) {
-  extern __shared__ float lds[];
-  const int pi = find_prob(probs, n, blockIdx.x);
-  const InteractProb p = probs[pi];
-  const int s = blockIdx.x - p.blk_begin;
-  const int st = p.d + 1;
-  for (int e = threadIdx.x; e < p.F * p.d; e += 256)
-    lds[(e / p.d) * st + (e % p.d)] = load_as_f32(p.x, p.x_dtype, (int64_t)s * p.ld_x + e);
-  __syncthreads();
-  for (int c = threadIdx.x; c < p.d; c += 256) store_from_f32(p.y, p.y_dtype, (int64_t)s * p.ld_y + c, lds[c]);
-  const int terms = p.F * (p.F - 1) / 2;
-  for (int t = threadIdx.x; t < terms; t += 256) {
-    int i, j;
-    term_to_pair(t, i, j);
-    float a = 0.0f;
-    for (int c = 0; c < p.d; ++c) a += lds[i * st + c] * lds[j * st + c];
-    store_from_f32(p.y, p.y_dtype, (int64_t)s * p.ld_y + p.d + t, a);
-  }
-}
-
-__global__ __launch_bounds__(256) void k_interact_bwd(const InteractProb *__restrict__ probs, int n) {
-  extern __shared__ float lds[];
-  const int pi = find_prob(probs, n, blockIdx.x);
-  const InteractProb p = probs[pi];
-  const int s = blockIdx.x - p.blk_begin;
-  const int st = p.d + 1;
-  float *T = lds;
-  float *G = lds + p.F * st;  // symmetric F x F, zero diagonal
-  for (int e = threadIdx.x; e < p.F * p.d; e += 256)
-    T[(e / p.d) * st + (e % p.d)] = load_as_f32(p.x, p.x_dtype, (int64_t)s * p.ld_x + e);
-  for (int e = threadIdx.x; e < p.F; e += 256) G[e * p.F + e] = 0.0f;
-  const int terms = p.F * (p.F - 1) / 2;
-  for (int t = threadIdx.x; t < terms; t += 256) {
-    int i, j;
-    term_to_pair(t, i, j);
-    float g = load_as_f32(p.dy, p.dy_dtype, (int64_t)s * p.ld_dy + p.d + t);
-    G[i * p.F + j] = g;
-    G[j * p.F + i] = g;
-  }
-  __syncthreads();
-  for (int e = threadIdx.x; e < p.F * p.d; e += 256) {
-    const int i = e / p.d, c = e % p.d;
-    float a = i == 0 ? load_as_f32(p.dy, p.dy_dtype, (int64_t)s * p.ld_dy + c) : 0.0f;
-    for (int j = 0; j < p.F; ++j) a += G[i * p.F + j] * T[j * st + c];
-    store_from_f32(p.y, p.y_dtype, (int64_t)s * p.ld_y + e, a);
-  }
-}
-
-static size_t interact_lds(int F, int d) { return ((size_t)F * (d + 1) + (size_t)F * F) * sizeof(float); }
-void launch_interact_fwd(const InteractProb *probs, int n, int total_blocks, int maxF, int maxd, hipStream_t s) {
-  if (total_blocks <= 0) return;
-  hipLaunchKernelGGL(k_interact_fwd, dim3(total_blocks), dim3(256), interact_lds(maxF, maxd), s, probs, n);
-}
-void launch_interact_bwd(const InteractProb *probs, int n, int total_blocks, int maxF, int maxd, hipStream_t s) {
-  if (total_blocks <= 0) return;
-  hipLaunchKernelGGL(k_interact_bwd, dim3(total_blocks), dim3(256), interact_lds(maxF, maxd), s, probs, n);
-}
-size_t interact_lds_bytes(int F, int d) { return interact_lds(F, d); }
 
 }  // namespace gpp

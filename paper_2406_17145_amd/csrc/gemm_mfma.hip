@@ -148,6 +148,11 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const GemmProb *__restrict__ 
     if (B_TR) tile_fetch<B_TR ? BK : BN, B_TR ? BN : BK>(rb, B, p.ldb, k0, n0, p.K, p.N);
     else      tile_fetch<B_TR ? BK : BN, B_TR ? BN : BK>(rb, B, p.ldb, n0, k0, p.N, p.K);
   };
+  // backward-weight tiles of the first column block also sum the rows of dZ^T they stream: the bias
+  // gradient db[n] = sum_m dZ[m,n] comes out of the same launch
+  constexpr int BGROUPS = 256 / BM, BROWS = BK / BGROUPS;
+  const bool do_bias = FORM == FORM_DW && p.bias != nullptr && n0 == 0;
+  float bsum = 0.0f;
   const int nk = cdiv(p.K, BK);
   fetch(0);
   tile_store_lds<A_TR ? BK : BM, A_TR ? BM : BK>(ra, lds_a[0]);
@@ -170,11 +175,29 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const GemmProb *__restrict__ 
 #pragma unroll
         for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
+    if (FORM == FORM_DW && do_bias) {
+      const uint16_t *la = lds_a[cur] + (threadIdx.x / BM) * BROWS * (BM + PAD) + (threadIdx.x % BM);
+#pragma unroll
+      for (int rr = 0; rr < BROWS; ++rr) bsum += bf16_bits_to_f32(la[rr * (BM + PAD)]);
+    }
     if (kt + 1 < nk) {
       tile_store_lds<A_TR ? BK : BM, A_TR ? BM : BK>(ra, lds_a[cur ^ 1]);
       tile_store_lds<B_TR ? BK : BN, B_TR ? BN : BK>(rb, lds_b[cur ^ 1]);
     }
     __syncthreads();
+  }
+
+  if (FORM == FORM_DW && do_bias) {   // fold the row groups in a fixed order (the k-loop ended with a barrier)
+    float *red = (float *)&lds_b[0][0];
+    red[threadIdx.x] = bsum;
+    __syncthreads();
+    if (threadIdx.x < BM && m0 + (int)threadIdx.x < p.M) {
+      float v = 0.0f;
+#pragma unroll
+      for (int g = 0; g < BGROUPS; ++g) v += red[g * BM + threadIdx.x];
+      float *db = const_cast<float *>(p.bias) + m0 + threadIdx.x;
+      *db = accumulate_dw ? *db + v : v;
+    }
   }
 
   // ---- epilogue: accumulator register r of a 32x32 tile holds row 8*(r/4) + 4*(lane/32) + r%4, column lane%32

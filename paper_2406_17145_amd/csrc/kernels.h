@@ -113,8 +113,10 @@ struct EmbProb {
   int32_t *bag_of;         // [capacity] bag id of each index position (written fwd)
   int32_t *keys_a, *keys_b, *pos_a, *pos_b;  // sort ping-pong buffers [capacity]
   int32_t *hist;           // [radix, sort_blocks]
-  int32_t *unique_rows, *seg_offsets;  // [capacity], [capacity+1]
-  int32_t *counts;         // [0] n_used, [1] n_unique
+  int32_t *unique_rows;    // [log_slots][capacity]: distinct rows of the last backward passes
+  int32_t *seg_offsets;    // [capacity+1]
+  int32_t *counts;         // [log_slots][4]: n_used, n_unique, n_long, -
+  int32_t *long_list;      // segments longer than the one-wave limit
   int64_t ld_table, ld_out;
   int32_t n_bags, capacity, dim, num_rows;
   int32_t out_dtype;
@@ -143,6 +145,7 @@ struct LossProb {
   int32_t rows, cols, kind;   // kind = gpp_op_kind_t value
   int32_t y_dtype, dy_dtype;
   float scale;
+  int32_t blk_begin;
 };
 
 struct ExtPtrs {
@@ -170,7 +173,10 @@ void launch_colsum(const ColsumProb *probs, int n, int total_blocks, int accumul
 int colsum_blocks(int cols);
 
 void launch_ln_fwd(const LnProb *probs, int n, int total_blocks, hipStream_t s);
-void launch_ln_bwd(const LnProb *probs, int n, int total_blocks, hipStream_t s);
+void launch_ln_bwd(const LnProb *probs, int n, int total_blocks, int max_d, int vec, hipStream_t s);
+bool ln_bwd_vec_supported(const LnProb &p);
+int ln_bwd_rows_per_block();
+int ln_bwd_max_d();
 void launch_ln_bwd_params(const LnProb *probs, int n, int total_blocks, int accumulate, hipStream_t s);
 int ln_rows_per_block();
 int ln_param_blocks(int d);
@@ -180,17 +186,22 @@ int attn_blocks(int batch, int heads, int seq);
 void launch_pool(const PoolProb *probs, int n, int total_blocks, hipStream_t s);
 int pool_blocks(const PoolProb &p);
 
-void launch_emb_fwd(const EmbProb *probs, int n, int total_blocks, StageFlags *flags, hipStream_t s);
+void launch_emb_fwd(const EmbProb *probs, int n, int total_blocks, int vec, StageFlags *flags, hipStream_t s);
 int emb_fwd_blocks(int n_bags);
-// sort + segment detection + segment sum; returns the number of launches it enqueues
-int launch_emb_bwd(const EmbProb *probs, int n, int max_capacity, int max_sort_blocks, int max_passes,
-                   StageFlags *flags, hipStream_t s);
-int emb_bwd_num_launches(int max_passes);
+bool emb_vec_supported(const EmbProb &p);
+// sort + segment heads + segment sums into log slot `slot`; returns the number of launches it enqueues
+int launch_emb_bwd(const EmbProb *probs, int n, int max_capacity, int max_sort_blocks, int max_passes, int vec,
+                   int slot, hipStream_t s);
+int emb_bwd_num_launches(int max_passes, int vec);
 int emb_sort_chunk();
 int emb_radix_bits();
-void launch_emb_reset(const EmbProb *probs, int n, hipStream_t s);
+int emb_long_segment();
+int emb_log_slots();
+// slots <= 0: clear whole tables; otherwise only the rows logged in slots [0, slots)
+void launch_emb_reset(const EmbProb *probs, int n, int max_capacity, int slots, hipStream_t s);
 
-void launch_loss_fwd(const LossProb *probs, int n, hipStream_t s);
+void launch_loss_fwd(const LossProb *probs, int n, int total_blocks, hipStream_t s);
+int loss_fwd_blocks(const LossProb &p);
 void launch_loss_bwd(const LossProb *probs, int n, int total_blocks, hipStream_t s);
 int loss_bwd_blocks(const LossProb &p);
 

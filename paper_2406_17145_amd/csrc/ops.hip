@@ -118,38 +118,179 @@ void launch_ln_fwd(const LnProb *probs, int n, int total_blocks, hipStream_t s) 
   hipLaunchKernelGGL(k_ln_fwd, dim3(total_blocks), dim3(256), 0, s, probs, n);
 }
 
-// dx = rstd * (g - mean(g) - xhat * mean(g * xhat)) (+ addend), g = dy * gamma
+// LayerNorm backward.  One workgroup owns 32 consecutive rows (8 per wave):
+//   dx = rstd * (g - mean(g) - xhat * mean(g * xhat)) (+ addend), g = dy * gamma
+// and, while the rows are in flight, each lane adds dy*xhat and dy of its own columns into
+// per-wave LDS sums; the four waves are combined in a fixed order into partial[row_block][2][d].
+// k_ln_bwd_params then folds the row blocks, again in a fixed order, into dgamma / dbeta.
+int ln_bwd_rows_per_block() { return 32; }
+int ln_bwd_max_d() { return 2048; }
+
 __global__ __launch_bounds__(256) void k_ln_bwd(const LnProb *__restrict__ probs, int n) {
+  extern __shared__ float part[];
   const int pi = find_prob(probs, n, blockIdx.x);
   const LnProb p = probs[pi];
-  const int lane = threadIdx.x & 63;
-  const int row = (blockIdx.x - p.blk_begin) * 4 + (threadIdx.x >> 6);
-  if (row >= p.rows) return;
-  const float mu = p.mean[row], rstd = p.rstd[row];
-  const int64_t xo = (int64_t)row * p.ldx, go = (int64_t)row * p.lddy;
-  float s1 = 0.0f, s2 = 0.0f;
-  for (int c = lane; c < p.d; c += 64) {
-    float xh = (load_as_f32(p.x, p.x_dtype, xo + c) - mu) * rstd;
-    float g = load_as_f32(p.dy, p.dy_dtype, go + c) * p.gamma[c];
-    s1 += g;
-    s2 += g * xh;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int blk = blockIdx.x - p.blk_begin;
+  float *pg = part + (size_t)wave * 2 * p.d, *pb = pg + p.d;
+  if (p.partial)
+    for (int c = lane; c < p.d; c += 64) pg[c] = pb[c] = 0.0f;
+  for (int rr = 0; rr < 8; ++rr) {
+    const int row = blk * 32 + wave * 8 + rr;
+    if (row >= p.rows) break;
+    const float mu = p.mean[row], rstd = p.rstd[row];
+    const int64_t xo = (int64_t)row * p.ldx, go = (int64_t)row * p.lddy;
+    float s1 = 0.0f, s2 = 0.0f;
+    for (int c = lane; c < p.d; c += 64) {
+      float xh = (load_as_f32(p.x, p.x_dtype, xo + c) - mu) * rstd;
+      float dy = load_as_f32(p.dy, p.dy_dtype, go + c);
+      float g = dy * p.gamma[c];
+      s1 += g;
+      s2 += g * xh;
+      if (p.partial) {
+        pg[c] += dy * xh;
+        pb[c] += dy;
+      }
+    }
+    if (!p.y) continue;
+    const float m1 = wave_sum(s1) / (float)p.d, m2 = wave_sum(s2) / (float)p.d;
+    for (int c = lane; c < p.d; c += 64) {
+      float xh = (load_as_f32(p.x, p.x_dtype, xo + c) - mu) * rstd;
+      float g = load_as_f32(p.dy, p.dy_dtype, go + c) * p.gamma[c];
+      float v = rstd * (g - m1 - xh * m2);
+      if (p.addend) v += load_as_f32(p.addend, p.add_dtype, (int64_t)row * p.ldadd + c);
+      store_from_f32(p.y, p.y_dtype, (int64_t)row * p.ldy + c, v);
+    }
   }
-  const float m1 = wave_sum(s1) / (float)p.d, m2 = wave_sum(s2) / (float)p.d;
-  for (int c = lane; c < p.d; c += 64) {
-    float xh = (load_as_f32(p.x, p.x_dtype, xo + c) - mu) * rstd;
-    float g = load_as_f32(p.dy, p.dy_dtype, go + c) * p.gamma[c];
-    float v = rstd * (g - m1 - xh * m2);
-    if (p.addend) v += load_as_f32(p.addend, p.add_dtype, (int64_t)row * p.ldadd + c);
-    store_from_f32(p.y, p.y_dtype, (int64_t)row * p.ldy + c, v);
+  if (!p.partial) return;
+  __syncthreads();
+  for (int c = threadIdx.x; c < 2 * p.d; c += 256) {
+    const float v = (part[c] + part[2 * p.d + c]) + (part[4 * p.d + c] + part[6 * p.d + c]);
+    p.partial[(int64_t)blk * 2 * p.d + c] = v;
   }
 }
-void launch_ln_bwd(const LnProb *probs, int n, int total_blocks, hipStream_t s) {
-  if (total_blocks <= 0) return;
-  hipLaunchKernelGGL(k_ln_bwd, dim3(total_blocks), dim3(256), 0, s, probs, n);
+// Vector variant for bf16 rows whose width is a multiple of 8: a lane owns NCH chunks of 8 columns,
+// keeps the row in registers between the two passes, and carries the parameter partial sums of its
+// columns in registers across the wave's 8 rows.
+typedef __attribute__((ext_vector_type(4))) uint32_t ln_u32x4;
+__device__ __forceinline__ void unpack8(const ln_u32x4 &v, float (&f)[8]) {
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    f[2 * e] = __uint_as_float(v[e] << 16);
+    f[2 * e + 1] = __uint_as_float(v[e] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ ln_u32x4 pack8f(const float (&f)[8]) {
+  ln_u32x4 v;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) v[e] = (uint32_t)f32_to_bf16_bits(f[2 * e]) | ((uint32_t)f32_to_bf16_bits(f[2 * e + 1]) << 16);
+  return v;
+}
+template <int NCH>
+__global__ __launch_bounds__(256) void k_ln_bwd_vec(const LnProb *__restrict__ probs, int n) {
+  extern __shared__ float part[];
+  const int pi = find_prob(probs, n, blockIdx.x);
+  const LnProb p = probs[pi];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int blk = blockIdx.x - p.blk_begin;
+  const int nchunks = p.d >> 3;
+  float gam[NCH][8], pg[NCH][8], pb[NCH][8];
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const int ch = lane + 64 * j;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      gam[j][e] = ch < nchunks ? p.gamma[ch * 8 + e] : 0.0f;
+      pg[j][e] = pb[j][e] = 0.0f;
+    }
+  }
+  for (int rr = 0; rr < 8; ++rr) {
+    const int row = blk * 32 + wave * 8 + rr;
+    if (row >= p.rows) break;
+    const float mu = p.mean[row], rstd = p.rstd[row];
+    const uint16_t *xr = (const uint16_t *)p.x + (int64_t)row * p.ldx;
+    const uint16_t *gr = (const uint16_t *)p.dy + (int64_t)row * p.lddy;
+    float xh[NCH][8], g[NCH][8];
+    float s1 = 0.0f, s2 = 0.0f;
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      const int ch = lane + 64 * j;
+      ln_u32x4 xv = {0u, 0u, 0u, 0u}, gv = {0u, 0u, 0u, 0u};
+      if (ch < nchunks) {
+        xv = *(const ln_u32x4 *)(xr + ch * 8);
+        gv = *(const ln_u32x4 *)(gr + ch * 8);
+      }
+      float xf[8], dyf[8];
+      unpack8(xv, xf);
+      unpack8(gv, dyf);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        xh[j][e] = ch < nchunks ? (xf[e] - mu) * rstd : 0.0f;
+        pg[j][e] += dyf[e] * xh[j][e];
+        pb[j][e] += dyf[e];
+        g[j][e] = dyf[e] * gam[j][e];
+        s1 += g[j][e];
+        s2 += g[j][e] * xh[j][e];
+      }
+    }
+    if (!p.y) continue;
+    const float m1 = wave_sum(s1) / (float)p.d, m2 = wave_sum(s2) / (float)p.d;
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      const int ch = lane + 64 * j;
+      if (ch >= nchunks) continue;
+      float v[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = rstd * (g[j][e] - m1 - xh[j][e] * m2);
+      if (p.addend) {
+        float af[8];
+        unpack8(*(const ln_u32x4 *)((const uint16_t *)p.addend + (int64_t)row * p.ldadd + ch * 8), af);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] += af[e];
+      }
+      *(ln_u32x4 *)((uint16_t *)p.y + (int64_t)row * p.ldy + ch * 8) = pack8f(v);
+    }
+  }
+  if (!p.partial) return;
+  float *mine = part + (size_t)wave * 2 * p.d;
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const int ch = lane + 64 * j;
+    if (ch >= nchunks) continue;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      mine[ch * 8 + e] = pg[j][e];
+      mine[p.d + ch * 8 + e] = pb[j][e];
+    }
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < 2 * p.d; c += 256) {
+    const float v = (part[c] + part[2 * p.d + c]) + (part[4 * p.d + c] + part[6 * p.d + c]);
+    p.partial[(int64_t)blk * 2 * p.d + c] = v;
+  }
 }
 
-// dgamma[c] (+)= sum_r dy*xhat ; dbeta[c] (+)= sum_r dy.  64 columns per workgroup,
-// four row groups reduced through LDS in a fixed order.
+bool ln_bwd_vec_supported(const LnProb &p) {
+  if (p.x_dtype != DT_BF16 || p.dy_dtype != DT_BF16 || (p.d & 7) || p.d > 2048) return false;
+  if ((p.ldx | p.lddy) & 7) return false;
+  if (((uintptr_t)p.x | (uintptr_t)p.dy) & 15) return false;
+  if (p.y && (p.y_dtype != DT_BF16 || (p.ldy & 7) || ((uintptr_t)p.y & 15))) return false;
+  if (p.addend && (p.add_dtype != DT_BF16 || (p.ldadd & 7) || ((uintptr_t)p.addend & 15))) return false;
+  return true;
+}
+
+// vec: 0 = generic kernel, otherwise the number of 8-column chunks per lane (1, 2 or 4)
+void launch_ln_bwd(const LnProb *probs, int n, int total_blocks, int max_d, int vec, hipStream_t s) {
+  if (total_blocks <= 0) return;
+  const size_t sh = (size_t)8 * max_d * sizeof(float);
+  if (vec == 1) hipLaunchKernelGGL(k_ln_bwd_vec<1>, dim3(total_blocks), dim3(256), sh, s, probs, n);
+  else if (vec == 2) hipLaunchKernelGGL(k_ln_bwd_vec<2>, dim3(total_blocks), dim3(256), sh, s, probs, n);
+  else if (vec == 4) hipLaunchKernelGGL(k_ln_bwd_vec<4>, dim3(total_blocks), dim3(256), sh, s, probs, n);
+  else hipLaunchKernelGGL(k_ln_bwd, dim3(total_blocks), dim3(256), sh, s, probs, n);
+}
+
+// dgamma[c] (+)= sum over rows of dy*xhat ; dbeta[c] (+)= sum of dy.  64 columns per workgroup, four
+// groups of row blocks (or of rows, when no partial sums exist) reduced through LDS in a fixed order.
 __global__ __launch_bounds__(256) void k_ln_bwd_params(const LnProb *__restrict__ probs, int n, int accumulate) {
   __shared__ float red[2][4][64];
   const int pi = find_prob(probs, n, blockIdx.x);
@@ -157,13 +298,21 @@ __global__ __launch_bounds__(256) void k_ln_bwd_params(const LnProb *__restrict_
   const int cl = threadIdx.x & 63, rg = threadIdx.x >> 6;
   const int c = (blockIdx.x - p.blk_begin) * 64 + cl;
   float sg = 0.0f, sb = 0.0f;
-  if (c < p.d)
-    for (int r = rg; r < p.rows; r += 4) {
-      float dy = load_as_f32(p.dy, p.dy_dtype, (int64_t)r * p.lddy + c);
-      float xh = (load_as_f32(p.x, p.x_dtype, (int64_t)r * p.ldx + c) - p.mean[r]) * p.rstd[r];
-      sg += dy * xh;
-      sb += dy;
+  if (c < p.d) {
+    if (p.partial) {
+      for (int rb = rg; rb < p.row_blocks; rb += 4) {
+        sg += p.partial[(int64_t)rb * 2 * p.d + c];
+        sb += p.partial[(int64_t)rb * 2 * p.d + p.d + c];
+      }
+    } else {
+      for (int r = rg; r < p.rows; r += 4) {
+        float dy = load_as_f32(p.dy, p.dy_dtype, (int64_t)r * p.lddy + c);
+        float xh = (load_as_f32(p.x, p.x_dtype, (int64_t)r * p.ldx + c) - p.mean[r]) * p.rstd[r];
+        sg += dy * xh;
+        sb += dy;
+      }
     }
+  }
   red[0][rg][cl] = sg;
   red[1][rg][cl] = sb;
   __syncthreads();
@@ -180,21 +329,32 @@ void launch_ln_bwd_params(const LnProb *probs, int n, int total_blocks, int accu
 }
 
 // ------------------------------------------------------------------ mean-pool
+// forward: one workgroup per (sample, 64 columns), four row groups combined in a fixed order;
+// backward: one thread per element
 int pool_blocks(const PoolProb &p) {
-  int64_t e = p.backward ? (int64_t)p.batch * p.seq * p.d : (int64_t)p.batch * p.d;
+  if (!p.backward) return p.batch * ((p.d + 63) / 64);
+  int64_t e = (int64_t)p.batch * p.seq * p.d;
   return (int)((e + 255) / 256);
 }
 __global__ __launch_bounds__(256) void k_pool(const PoolProb *__restrict__ probs, int n) {
+  __shared__ float red[4][64];
   const int pi = find_prob(probs, n, blockIdx.x);
   const PoolProb p = probs[pi];
-  const int64_t e = (int64_t)(blockIdx.x - p.blk_begin) * 256 + threadIdx.x;
+  const int blk = blockIdx.x - p.blk_begin;
   if (!p.backward) {
-    if (e >= (int64_t)p.batch * p.d) return;
-    const int b = (int)(e / p.d), c = (int)(e % p.d);
+    const int chunks = (p.d + 63) / 64;
+    const int b = blk / chunks, cl = threadIdx.x & 63, rg = threadIdx.x >> 6;
+    const int c = (blk % chunks) * 64 + cl;
     float s = 0.0f;
-    for (int t = 0; t < p.seq; ++t) s += load_as_f32(p.src, p.src_dtype, ((int64_t)b * p.seq + t) * p.ld_src + c);
-    store_from_f32(p.dst, p.dst_dtype, (int64_t)b * p.ld_dst + c, s / (float)p.seq);
+    if (c < p.d)
+      for (int t = rg; t < p.seq; t += 4) s += load_as_f32(p.src, p.src_dtype, ((int64_t)b * p.seq + t) * p.ld_src + c);
+    red[rg][cl] = s;
+    __syncthreads();
+    if (rg == 0 && c < p.d)
+      store_from_f32(p.dst, p.dst_dtype, (int64_t)b * p.ld_dst + c,
+                     ((red[0][cl] + red[1][cl]) + (red[2][cl] + red[3][cl])) / (float)p.seq);
   } else {
+    const int64_t e = (int64_t)blk * 256 + threadIdx.x;
     if (e >= (int64_t)p.batch * p.seq * p.d) return;
     const int r = (int)(e / p.d), c = (int)(e % p.d);
     float v = load_as_f32(p.src, p.src_dtype, (int64_t)(r / p.seq) * p.ld_src + c) / (float)p.seq;
@@ -214,13 +374,17 @@ __device__ __forceinline__ float sigmoid_f(float y) {
   return y >= 0.0f ? 1.0f / (1.0f + e) : e / (1.0f + e);
 }
 
-// one workgroup of 1024 threads per loss operator; wave w takes rows w, w+16, ...
-__global__ __launch_bounds__(1024) void k_loss_fwd(const LossProb *__restrict__ probs) {
-  __shared__ float red[16];
-  const LossProb p = probs[blockIdx.x];
+// four rows per workgroup (one wave each); every workgroup writes one partial sum, already scaled
+int loss_fwd_blocks(const LossProb &p) { return (p.rows + 3) / 4; }
+__global__ __launch_bounds__(256) void k_loss_fwd(const LossProb *__restrict__ probs, int n) {
+  __shared__ float red[4];
+  const int pi = find_prob(probs, n, blockIdx.x);
+  const LossProb p = probs[pi];
+  const int blk = blockIdx.x - p.blk_begin;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int r = blk * 4 + w;
   float acc = 0.0f;
-  for (int r = w; r < p.rows; r += 16) {
+  if (r < p.rows) {
     const int64_t yo = (int64_t)r * p.ld_y;
     if (p.kind == 10) {
       float m = -INFINITY;
@@ -230,7 +394,7 @@ __global__ __launch_bounds__(1024) void k_loss_fwd(const LossProb *__restrict__ 
       for (int c = lane; c < p.cols; c += 64) se += __expf(load_as_f32(p.y, p.y_dtype, yo + c) - m);
       se = wave_sum(se);
       const int lab = ((const int32_t *)p.target)[(int64_t)r * p.ld_t];
-      if (lane == 0 && lab >= 0 && lab < p.cols) acc += (m + __logf(se)) - load_as_f32(p.y, p.y_dtype, yo + lab);
+      if (lane == 0 && lab >= 0 && lab < p.cols) acc = (m + __logf(se)) - load_as_f32(p.y, p.y_dtype, yo + lab);
     } else {
       const float *t = (const float *)p.target + (int64_t)r * p.ld_t;
       for (int c = lane; c < p.cols; c += 64) {
@@ -247,15 +411,11 @@ __global__ __launch_bounds__(1024) void k_loss_fwd(const LossProb *__restrict__ 
   acc = wave_sum(acc);
   if (lane == 0) red[w] = acc;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    float s = 0.0f;
-    for (int i = 0; i < 16; ++i) s += red[i];
-    p.loss[0] = s * p.scale;
-  }
+  if (threadIdx.x == 0) p.loss[blk] = ((red[0] + red[1]) + (red[2] + red[3])) * p.scale;
 }
-void launch_loss_fwd(const LossProb *probs, int n, hipStream_t s) {
-  if (n <= 0) return;
-  hipLaunchKernelGGL(k_loss_fwd, dim3(n), dim3(1024), 0, s, probs);
+void launch_loss_fwd(const LossProb *probs, int n, int total_blocks, hipStream_t s) {
+  if (total_blocks <= 0) return;
+  hipLaunchKernelGGL(k_loss_fwd, dim3(total_blocks), dim3(256), 0, s, probs, n);
 }
 
 int loss_bwd_blocks(const LossProb &p) { return (p.rows + 3) / 4; }
@@ -299,12 +459,12 @@ void launch_loss_bwd(const LossProb *probs, int n, int total_blocks, hipStream_t
   hipLaunchKernelGGL(k_loss_bwd, dim3(total_blocks), dim3(256), 0, s, probs, n);
 }
 
+// one wave: lane-strided sums, then a butterfly; the order is fixed, so the result is reproducible
 __global__ void k_loss_sum(const float *losses, int n, float *out) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) {
-    float s = 0.0f;
-    for (int i = 0; i < n; ++i) s += losses[i];
-    out[0] = s;
-  }
+  float s = 0.0f;
+  for (int i = threadIdx.x; i < n; i += 64) s += losses[i];
+  s = wave_sum(s);
+  if (threadIdx.x == 0) out[0] = s;
 }
 void launch_loss_sum(const float *losses, int n, float *out, hipStream_t s) {
   hipLaunchKernelGGL(k_loss_sum, dim3(1), dim3(64), 0, s, losses, n, out);

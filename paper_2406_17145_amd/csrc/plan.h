@@ -68,7 +68,8 @@ struct Plan {
   int32_t slots = 1, flags = 0;
   int64_t slot_bytes = 0, shared_bytes = 0, table_bytes = 0, tmp_bytes = 0;
   int64_t off_flags = 0, off_tables = 0, off_slots = 0, off_shared = 0, total_bytes = 0;
-  Buf loss_scalars;                  // f32 [n_loss] per slot
+  Buf loss_scalars;                  // f32 partial losses per slot
+  int loss_parts = 0;
   std::vector<Step> fwd, bwd;
   std::vector<uint8_t> blob;         // tables of the slot being emitted
   std::string error;

@@ -316,6 +316,10 @@ gpp_status_t Plan::analyse(const gpp_stage_desc_t *desc) {
     if (d.kind == GPP_OP_LAYERNORM) {
       nd.stat0 = alloc(SP_SLOT, 1, nd.rows, DT_F32);
       nd.stat1 = alloc(SP_SLOT, 1, nd.rows, DT_F32);
+      if (nd.feat <= ln_bwd_max_d()) {  // per-row-block partial sums of the gamma / beta gradients
+        const int64_t rb = (nd.rows + ln_bwd_rows_per_block() - 1) / ln_bwd_rows_per_block();
+        nd.extra = alloc(SP_SHARED, 1, rb * 2 * nd.feat, DT_F32);
+      }
     }
     if (d.kind == GPP_OP_ATTENTION) {
       nd.stat0 = alloc(SP_SLOT, 1, micro_batch * d.heads * d.seq_len, DT_F32);    // log-sum-exp
@@ -331,14 +335,23 @@ gpp_status_t Plan::analyse(const gpp_stage_desc_t *desc) {
       nd.more.clear();
       for (int k = 0; k < 4; ++k) nd.more.push_back(alloc(SP_SHARED, 1, cap, DT_I32));            // keys a/b, pos a/b
       nd.more.push_back(alloc(SP_SHARED, 1, (int64_t)(1 << emb_radix_bits()) * sort_blocks, DT_I32));  // hist
-      nd.more.push_back(alloc(SP_SHARED, 1, cap, DT_I32));      // unique rows
-      nd.more.push_back(alloc(SP_SHARED, 1, cap + 1, DT_I32));  // segment offsets
-      nd.more.push_back(alloc(SP_SHARED, 1, 8, DT_I32));        // counts
+      nd.more.push_back(alloc(SP_SHARED, 1, cap * emb_log_slots(), DT_I32));  // unique rows per log slot
+      nd.more.push_back(alloc(SP_SHARED, 1, cap + 1, DT_I32));                // segment offsets
+      nd.more.push_back(alloc(SP_SHARED, 1, 4 * emb_log_slots(), DT_I32));    // counts per log slot
+      nd.more.push_back(alloc(SP_SHARED, 1, cap / emb_long_segment() + 2, DT_I32));  // long segments
       nd.emb_passes = passes;
       nd.emb_sort_blocks = sort_blocks;
     }
   }
-  loss_scalars = alloc(SP_SLOT, 1, std::max<int64_t>(1, (int64_t)loss_ops.size()), DT_F32);
+  {  // one partial loss per four prediction rows; the egress kernel folds them
+    int64_t parts = 0;
+    for (int i : loss_ops) {
+      nodes[i].loss_index = (int)parts;
+      parts += (nodes[nodes[i].in[0]].rows + 3) / 4;
+    }
+    loss_parts = (int)parts;
+    loss_scalars = alloc(SP_SLOT, 1, std::max<int64_t>(1, parts), DT_F32);
+  }
   slot_bytes = align_up(slot_top, 256);
   shared_bytes = align_up(shared_top, 256);
   return GPP_OK;
@@ -798,7 +811,9 @@ void Emitter::forward() {
         e.blk_begin = blocks;
         blocks += emb_fwd_blocks(e.n_bags);
       }
-      add_step(K_EMB_FWD, push_table(embs), (int)embs.size(), blocks);
+      bool vec = true;
+      for (auto &e : embs) vec = vec && emb_vec_supported(e);
+      add_step(K_EMB_FWD, push_table(embs), (int)embs.size(), blocks).a0 = vec ? 1 : 0;
     }
     if (!inters.empty()) {
       int blocks = 0, mf = 0, md = 0;
@@ -812,7 +827,14 @@ void Emitter::forward() {
       s.a0 = mf;
       s.a1 = md;
     }
-    if (!losses.empty()) add_step(K_LOSS_FWD, push_table(losses), (int)losses.size(), (int)losses.size());
+    if (!losses.empty()) {
+      int blocks = 0;
+      for (auto &l : losses) {
+        l.blk_begin = blocks;
+        blocks += loss_fwd_blocks(l);
+      }
+      add_step(K_LOSS_FWD, push_table(losses), (int)losses.size(), blocks);
+    }
   }
 
   // egress: stage outputs to the caller's dense buffers, loss scalars summed
@@ -835,7 +857,7 @@ void Emitter::forward() {
       recs.push_back(e);
     }
     emit_elt(recs, EXT_OUTPUTS, base);
-    add_step(K_LOSS_SUM, 0, (int)pl.loss_ops.size(), 1);
+    add_step(K_LOSS_SUM, 0, pl.loss_parts, 1);
   }
 }
 
@@ -954,17 +976,6 @@ void Emitter::backward() {
       switch (d.kind) {
         case GPP_OP_LINEAR: {
           const Node &x = N[nd.in[0]];
-          if (d.has_bias) {
-            ColsumProb c;
-            memset(&c, 0, sizeof(c));
-            c.src = ptr(nd.gout);
-            c.ld = nd.gout.ld;
-            c.dtype = nd.gout.dtype;
-            c.out = (float *)d.grad[1];
-            c.rows = (int32_t)nd.rows;
-            c.cols = (int32_t)nd.feat;
-            colsums.push_back(c);
-          }
           GemmProb w;
           memset(&w, 0, sizeof(w));
           w.form = FORM_DW;
@@ -979,6 +990,20 @@ void Emitter::backward() {
           w.N = (int32_t)d.in_features;     // columns of dW
           w.K = (int32_t)nd.rows;           // contraction over the micro-batch rows
           w.in_dtype = d.param_dtype;
+          // on the matrix-core path the bias gradient rides along in the backward-weight launch
+          const bool fuse_db = d.has_bias && !(pl.flags & 1) && w.in_dtype == DT_BF16 && gemm_mfma_supported(w);
+          if (fuse_db) w.bias = (const float *)d.grad[1];
+          if (d.has_bias && !fuse_db) {
+            ColsumProb c;
+            memset(&c, 0, sizeof(c));
+            c.src = ptr(nd.gout);
+            c.ld = nd.gout.ld;
+            c.dtype = nd.gout.dtype;
+            c.out = (float *)d.grad[1];
+            c.rows = (int32_t)nd.rows;
+            c.cols = (int32_t)nd.feat;
+            colsums.push_back(c);
+          }
           gemms.push_back(w);
           if (x.wants_grad) {
             Target tg = acquire(nd.in[0], true);
@@ -1029,6 +1054,7 @@ void Emitter::backward() {
           l.rstd = (float *)ptr(nd.stat1);
           l.dgamma = (float *)d.grad[0];
           l.dbeta = (float *)d.grad[1];
+          l.partial = (float *)ptr(nd.extra);
           l.rows = (int32_t)nd.rows;
           l.d = (int32_t)nd.feat;
           l.eps = (float)d.eps;
@@ -1125,6 +1151,7 @@ void Emitter::backward() {
           e.unique_rows = (int32_t *)ptr(nd.more[5]);
           e.seg_offsets = (int32_t *)ptr(nd.more[6]);
           e.counts = (int32_t *)ptr(nd.more[7]);
+          e.long_list = (int32_t *)ptr(nd.more[8]);
           e.n_bags = (int32_t)pl.micro_batch;
           e.capacity = (int32_t)(pl.micro_batch * d.bag_size);
           e.dim = (int32_t)nd.feat;
@@ -1168,16 +1195,30 @@ void Emitter::backward() {
     }
     emit_gemms(gemms);
     if (!lns.empty()) {
+      // first kernel: dx rows and per-row-block partial parameter sums; operators without partial
+      // scratch and without a dx consumer skip it
       std::vector<LnProb> dx;
-      int blocks = 0;
+      int blocks = 0, max_d = 0;
       for (auto &l : lns)
-        if (l.y) {
+        if (l.y || l.partial) {
+          l.row_blocks = (l.rows + ln_bwd_rows_per_block() - 1) / ln_bwd_rows_per_block();
           LnProb c = l;
           c.blk_begin = blocks;
-          blocks += (l.rows + ln_rows_per_block() - 1) / ln_rows_per_block();
+          blocks += l.row_blocks;
+          max_d = std::max(max_d, l.partial ? l.d : 0);
           dx.push_back(c);
         }
-      if (!dx.empty()) add_step(K_LN_BWD, push_table(dx), (int)dx.size(), blocks);
+      if (!dx.empty()) {
+        bool vec = true;
+        int widest = 0;
+        for (auto &l : dx) {
+          vec = vec && ln_bwd_vec_supported(l) && l.partial;
+          widest = std::max(widest, l.d);
+        }
+        Step &st = add_step(K_LN_BWD, push_table(dx), (int)dx.size(), blocks);
+        st.a0 = max_d;
+        st.a1 = !vec ? 0 : (widest <= 512 ? 1 : (widest <= 1024 ? 2 : 4));
+      }
       blocks = 0;
       for (auto &l : lns) {
         l.blk_begin = blocks;
@@ -1217,11 +1258,13 @@ void Emitter::backward() {
         sb = std::max(sb, e.sort_blocks);
         ps = std::max(ps, e.passes);
       }
+      bool vec = true;
+      for (auto &e : embs) vec = vec && emb_vec_supported(e);
       Step &s = add_step(K_EMB_BWD, push_table(embs), (int)embs.size(), 0);
       s.a0 = cap;
       s.a1 = sb;
-      s.a2 = ps;
-      s.launches = emb_bwd_num_launches(ps);
+      s.a2 = ps | (vec ? 256 : 0);
+      s.launches = emb_bwd_num_launches(ps, vec ? 1 : 0);
     }
     if (!inters.empty()) {
       int blocks = 0, mf = 0, md = 0;

@@ -41,6 +41,10 @@ struct gpp_stage {
   bool emb_clear_pending = true; // table accumulators not yet cleared since create
   int64_t emb_table_off = -1;    // table of all embedding records (slot 0) for the clear kernel
   int emb_count = 0;
+  int emb_capacity = 0;          // largest index capacity among the tables
+  int emb_logged = 0;            // backward passes since the last reset whose touched rows are logged
+  bool emb_log_overflow = false; // more passes than log slots: the next reset clears whole tables
+  int emb_last_slot = 0;
   // optional per-step timing (HIP events on the caller's stream)
   bool prof_on = false;
   std::vector<hipEvent_t> prof_ev;   // pairs (begin, end)
@@ -158,6 +162,7 @@ gpp_status_t gpp_stage_create(const gpp_stage_desc_t *desc, void *workspace, siz
     if (s.kern == K_EMB_BWD) {
       st->emb_table_off = s.table_off;
       st->emb_count = s.n;
+      st->emb_capacity = s.a0;
     }
   *out = st;
   return GPP_OK;
@@ -233,7 +238,7 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
       case K_GEMM_MFMA: launch_gemm_mfma((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a1, sp.a2, s); break;
       case K_COLSUM: launch_colsum((const ColsumProb *)tab, sp.n, sp.blocks, accumulate, s); break;
       case K_LN_FWD: launch_ln_fwd((const LnProb *)tab, sp.n, sp.blocks, s); break;
-      case K_LN_BWD: launch_ln_bwd((const LnProb *)tab, sp.n, sp.blocks, s); break;
+      case K_LN_BWD: launch_ln_bwd((const LnProb *)tab, sp.n, sp.blocks, sp.a0, sp.a1, s); break;
       case K_LN_BWD_PARAMS: launch_ln_bwd_params((const LnProb *)tab, sp.n, sp.blocks, accumulate, s); break;
       case K_ATTN_FWD:
         if (sp.a1) launch_attn_fwd_mfma((const AttnProb *)tab, sp.n, sp.blocks, s);
@@ -248,17 +253,23 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
         else launch_attn_bwd_dkv((const AttnProb *)tab, sp.n, sp.blocks, sp.a0, s);
         break;
       case K_POOL: launch_pool((const PoolProb *)tab, sp.n, sp.blocks, s); break;
-      case K_EMB_FWD: launch_emb_fwd((const EmbProb *)tab, sp.n, sp.blocks, flags, s); break;
-      case K_EMB_BWD:
+      case K_EMB_FWD: launch_emb_fwd((const EmbProb *)tab, sp.n, sp.blocks, sp.a0, flags, s); break;
+      case K_EMB_BWD: {
         if (st->emb_clear_pending) {
-          launch_emb_reset((const EmbProb *)tab, sp.n, s);
+          launch_emb_reset((const EmbProb *)tab, sp.n, sp.a0, 0, s);
           st->emb_clear_pending = false;
         }
-        launch_emb_bwd((const EmbProb *)tab, sp.n, sp.a0, sp.a1, sp.a2, flags, s);
+        // the rows this pass touches are logged so that the next reset clears only those
+        if (st->emb_logged >= emb_log_slots()) st->emb_log_overflow = true;
+        const int slot = st->emb_logged < emb_log_slots() ? st->emb_logged : emb_log_slots() - 1;
+        launch_emb_bwd((const EmbProb *)tab, sp.n, sp.a0, sp.a1, sp.a2 & 255, (sp.a2 >> 8) & 1, slot, s);
+        st->emb_last_slot = slot;
+        st->emb_logged++;
         break;
+      }
       case K_INTERACT_FWD: launch_interact_fwd((const InteractProb *)tab, sp.n, sp.blocks, sp.a0, sp.a1, s); break;
       case K_INTERACT_BWD: launch_interact_bwd((const InteractProb *)tab, sp.n, sp.blocks, sp.a0, sp.a1, s); break;
-      case K_LOSS_FWD: launch_loss_fwd((const LossProb *)tab, sp.n, s); break;
+      case K_LOSS_FWD: launch_loss_fwd((const LossProb *)tab, sp.n, sp.blocks, s); break;
       case K_LOSS_BWD: launch_loss_bwd((const LossProb *)tab, sp.n, sp.blocks, s); break;
       case K_LOSS_SUM:
         if (loss_out) {
@@ -323,8 +334,14 @@ gpp_status_t gpp_stage_grad_reset(gpp_stage_t *st, void *hip_stream) {
   st->fresh = true;
   if (st->emb_count > 0) {
     const char *tables = st->ws + st->plan.off_tables;  // slot 0's records carry the same accumulators
-    launch_emb_reset((const EmbProb *)(tables + st->emb_table_off), st->emb_count, (hipStream_t)hip_stream);
+    const EmbProb *recs = (const EmbProb *)(tables + st->emb_table_off);
+    if (st->emb_clear_pending || st->emb_log_overflow)
+      launch_emb_reset(recs, st->emb_count, st->emb_capacity, 0, (hipStream_t)hip_stream);
+    else if (st->emb_logged > 0)
+      launch_emb_reset(recs, st->emb_count, st->emb_capacity, st->emb_logged, (hipStream_t)hip_stream);
     st->emb_clear_pending = false;
+    st->emb_log_overflow = false;
+    st->emb_logged = 0;
     hipError_t he = hipGetLastError();
     if (he != hipSuccess) return fail(GPP_ERR_DEVICE, std::string("HIP launch: ") + hipGetErrorString(he));
   }
@@ -383,9 +400,10 @@ gpp_status_t gpp_stage_embedding_sort_result(gpp_stage_t *st, int32_t op, const 
   const Node &nd = pl.nodes[op];
   auto sh = [&](const Buf &b) { return (const int32_t *)(st->ws + pl.off_shared + b.off); };
   if (sorted_pos) *sorted_pos = sh((nd.emb_passes & 1) ? nd.more[2] : nd.more[3]);
-  if (unique_rows) *unique_rows = sh(nd.more[5]);
+  const int64_t cap = pl.micro_batch * nd.d.bag_size;
+  if (unique_rows) *unique_rows = sh(nd.more[5]) + st->emb_last_slot * cap;
   if (seg_offsets) *seg_offsets = sh(nd.more[6]);
-  if (counts) *counts = sh(nd.more[7]);
+  if (counts) *counts = sh(nd.more[7]) + st->emb_last_slot * 4;
   return GPP_OK;
 }
 
