@@ -119,7 +119,9 @@ typedef struct {
   const gpp_op_desc_t *ops;   /* HOST */
   int64_t micro_batch;        /* b_i */
   int32_t in_flight_slots;    /* how many micro-batches may be in flight (activation stash slots) */
-  int32_t flags;              /* bit 0: force the generic (non-MFMA) GEMM kernels, for testing */
+  int32_t flags;              /* bit 0: force the generic (non-MFMA) GEMM kernels (testing);
+                                 bit 1: split the contraction of small grouped GEMMs over several
+                                 workgroups (deterministic; measured slower, off by default) */
 } gpp_stage_desc_t;
 
 /* Leading dimension used for parameters and gradient accumulators. */

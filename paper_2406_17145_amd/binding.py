@@ -26,6 +26,7 @@ KINDS = {"input": 0, "linear": 1, "layernorm": 2, "attention": 3, "add": 4, "mea
          "embedding_bag_sum": 7, "dot_interact": 8, "loss_mse": 9, "loss_ce": 10, "loss_bce": 11}
 ACTS = {"none": 0, "relu": 1, "gelu": 2}
 FLAG_FORCE_GENERIC_GEMM = 1
+FLAG_SPLIT_K = 2
 
 
 class OpDesc(C.Structure):

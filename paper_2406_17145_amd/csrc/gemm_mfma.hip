@@ -100,6 +100,17 @@ __device__ __forceinline__ bf16x8 frag_tr(const uint16_t *lds, int col0, int k0)
   return __builtin_bit_cast(bf16x8, v);
 }
 
+// Split-K partial sums cross workgroups (and XCDs, whose L2 caches are not coherent with each other
+// inside a kernel).  They are written and read with device-scope relaxed atomics, which go through
+// to memory instead of staying in the writer's L2, so no cache-wide write-back or invalidate is
+// needed: ordering comes from waiting for the stores' acknowledgements before the ticket is taken.
+__device__ __forceinline__ void put_partial(float *p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float get_partial(const float *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // ---- the kernel ---------------------------------------------------------------------
 template <int FORM, int BM, int BN>
 __global__ __launch_bounds__(256) void k_gemm_mfma(const GemmProb *__restrict__ probs, int n, int total_blocks,
@@ -122,7 +133,11 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const GemmProb *__restrict__ 
   }
   const int pi = find_prob(probs, n, bid);
   const GemmProb p = probs[pi];
-  const int tile = bid - p.blk_begin;
+  // split-K: `split` workgroups with consecutive ids share one output tile, each sums a slice of K
+  const int S = p.split_k, split = (bid - p.blk_begin) % S;
+  const int tile = (bid - p.blk_begin) / S;
+  const int kslice = cdiv(cdiv(p.K, BK), S) * BK;
+  const int k_begin = split * kslice, k_end = min(p.K, k_begin + kslice);
   const int tiles_m = cdiv(p.M, BM);
   const int m0 = (tile % tiles_m) * BM, n0 = (tile / tiles_m) * BN;   // consecutive tiles share the B panel
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -140,64 +155,115 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const GemmProb *__restrict__ 
 
   typedef TileRegs<A_TR ? BK : BM, A_TR ? BM : BK> RegsA;
   typedef TileRegs<B_TR ? BK : BN, B_TR ? BN : BK> RegsB;
-  RegsA ra;
-  RegsB rb;
-  auto fetch = [&](int k0) {
-    if (A_TR) tile_fetch<A_TR ? BK : BM, A_TR ? BM : BK>(ra, A, p.lda, k0, m0, p.K, p.M);
-    else      tile_fetch<A_TR ? BK : BM, A_TR ? BM : BK>(ra, A, p.lda, m0, k0, p.M, p.K);
-    if (B_TR) tile_fetch<B_TR ? BK : BN, B_TR ? BN : BK>(rb, B, p.ldb, k0, n0, p.K, p.N);
-    else      tile_fetch<B_TR ? BK : BN, B_TR ? BN : BK>(rb, B, p.ldb, n0, k0, p.N, p.K);
+  // NS k-steps are kept in flight in registers: the tile consumed at step kt was requested NS-1
+  // steps earlier, so the k-loop runs at the rate of its own work, not of the memory latency
+  constexpr int NS = BM * BN >= 128 * 128 ? 4 : 8;
+  RegsA ra[NS];
+  RegsB rb[NS];
+  auto fetch = [&](RegsA &xa, RegsB &xb, int k0) {
+    if (A_TR) tile_fetch<A_TR ? BK : BM, A_TR ? BM : BK>(xa, A, p.lda, k0, m0, k_end, p.M);
+    else      tile_fetch<A_TR ? BK : BM, A_TR ? BM : BK>(xa, A, p.lda, m0, k0, p.M, k_end);
+    if (B_TR) tile_fetch<B_TR ? BK : BN, B_TR ? BN : BK>(xb, B, p.ldb, k0, n0, k_end, p.N);
+    else      tile_fetch<B_TR ? BK : BN, B_TR ? BN : BK>(xb, B, p.ldb, n0, k0, p.N, k_end);
   };
   // backward-weight tiles of the first column block also sum the rows of dZ^T they stream: the bias
   // gradient db[n] = sum_m dZ[m,n] comes out of the same launch
   constexpr int BGROUPS = 256 / BM, BROWS = BK / BGROUPS;
   const bool do_bias = FORM == FORM_DW && p.bias != nullptr && n0 == 0;
   float bsum = 0.0f;
-  const int nk = cdiv(p.K, BK);
-  fetch(0);
-  tile_store_lds<A_TR ? BK : BM, A_TR ? BM : BK>(ra, lds_a[0]);
-  tile_store_lds<B_TR ? BK : BN, B_TR ? BN : BK>(rb, lds_b[0]);
+  const int nk = max(0, cdiv(k_end - k_begin, BK));
+#pragma unroll
+  for (int u = 0; u < NS; ++u)
+    if (u < nk || u == 0) fetch(ra[u], rb[u], k_begin + u * BK);
+  tile_store_lds<A_TR ? BK : BM, A_TR ? BM : BK>(ra[0], lds_a[0]);
+  tile_store_lds<B_TR ? BK : BN, B_TR ? BN : BK>(rb[0], lds_b[0]);
   __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < nk) fetch((kt + 1) * BK);
+  for (int kt0 = 0; kt0 < nk; kt0 += NS) {
 #pragma unroll
-    for (int kc = 0; kc < BK; kc += 16) {
-      bf16x8 a[TI], b[TJ];
+    for (int u = 0; u < NS; ++u) {
+      const int kt = kt0 + u;
+      if (kt >= nk) break;
+      const int cur = u & 1;   // NS is even, so the LDS buffer of step kt is kt & 1 = u & 1
+      // slot u held tile kt, already copied to LDS: reuse it for tile kt + NS
+      if (kt + NS < nk) fetch(ra[u], rb[u], k_begin + (kt + NS) * BK);
 #pragma unroll
-      for (int i = 0; i < TI; ++i)
-        a[i] = A_TR ? frag_tr<BM>(lds_a[cur], wi0 + 32 * i, kc) : frag_kmajor(lds_a[cur], wi0 + 32 * i, kc);
+      for (int kc = 0; kc < BK; kc += 16) {
+        bf16x8 a[TI], b[TJ];
 #pragma unroll
-      for (int j = 0; j < TJ; ++j)
-        b[j] = B_TR ? frag_tr<BN>(lds_b[cur], wj0 + 32 * j, kc) : frag_kmajor(lds_b[cur], wj0 + 32 * j, kc);
+        for (int i = 0; i < TI; ++i)
+          a[i] = A_TR ? frag_tr<BM>(lds_a[cur], wi0 + 32 * i, kc) : frag_kmajor(lds_a[cur], wi0 + 32 * i, kc);
 #pragma unroll
-      for (int i = 0; i < TI; ++i)
+        for (int j = 0; j < TJ; ++j)
+          b[j] = B_TR ? frag_tr<BN>(lds_b[cur], wj0 + 32 * j, kc) : frag_kmajor(lds_b[cur], wj0 + 32 * j, kc);
 #pragma unroll
-        for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        for (int i = 0; i < TI; ++i)
+#pragma unroll
+          for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+      }
+      if (FORM == FORM_DW && do_bias) {
+        const uint16_t *la = lds_a[cur] + (threadIdx.x / BM) * BROWS * (BM + PAD) + (threadIdx.x % BM);
+#pragma unroll
+        for (int rr = 0; rr < BROWS; ++rr) bsum += bf16_bits_to_f32(la[rr * (BM + PAD)]);
+      }
+      if (kt + 1 < nk) {
+        tile_store_lds<A_TR ? BK : BM, A_TR ? BM : BK>(ra[(u + 1) % NS], lds_a[cur ^ 1]);
+        tile_store_lds<B_TR ? BK : BN, B_TR ? BN : BK>(rb[(u + 1) % NS], lds_b[cur ^ 1]);
+      }
+      __syncthreads();
     }
-    if (FORM == FORM_DW && do_bias) {
-      const uint16_t *la = lds_a[cur] + (threadIdx.x / BM) * BROWS * (BM + PAD) + (threadIdx.x % BM);
-#pragma unroll
-      for (int rr = 0; rr < BROWS; ++rr) bsum += bf16_bits_to_f32(la[rr * (BM + PAD)]);
-    }
-    if (kt + 1 < nk) {
-      tile_store_lds<A_TR ? BK : BM, A_TR ? BM : BK>(ra, lds_a[cur ^ 1]);
-      tile_store_lds<B_TR ? BK : BN, B_TR ? BN : BK>(rb, lds_b[cur ^ 1]);
-    }
-    __syncthreads();
   }
 
+  float bias_total = 0.0f;            // threads < BM: this split's column sum of the dZ^T tile
   if (FORM == FORM_DW && do_bias) {   // fold the row groups in a fixed order (the k-loop ended with a barrier)
     float *red = (float *)&lds_b[0][0];
     red[threadIdx.x] = bsum;
     __syncthreads();
-    if (threadIdx.x < BM && m0 + (int)threadIdx.x < p.M) {
-      float v = 0.0f;
+    if (threadIdx.x < BM) {
 #pragma unroll
-      for (int g = 0; g < BGROUPS; ++g) v += red[g * BM + threadIdx.x];
-      float *db = const_cast<float *>(p.bias) + m0 + threadIdx.x;
-      *db = accumulate_dw ? *db + v : v;
+      for (int g = 0; g < BGROUPS; ++g) bias_total += red[g * BM + threadIdx.x];
     }
+  }
+
+  if (S > 1) {
+    // Deterministic split-K: every split stores its fp32 partial tile; the split that arrives last
+    // (arrival counter, no waiting) adds all partials in split order and runs the epilogue.
+    constexpr int PSTRIDE = BM * BN + BM;
+    float *mine = p.partial + ((int64_t)tile * S + split) * PSTRIDE;
+#pragma unroll
+    for (int i = 0; i < TI; ++i)
+#pragma unroll
+      for (int j = 0; j < TJ; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) put_partial(mine + ((i * TJ + j) * 16 + r) * 256 + threadIdx.x, acc[i][j][r]);
+    if (FORM == FORM_DW && threadIdx.x < BM) put_partial(mine + BM * BN + threadIdx.x, bias_total);
+    // the partial stores go through to memory; once this wave's stores have been acknowledged and
+    // the workgroup has met, one thread takes a ticket
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    __shared__ int ticket;
+    if (threadIdx.x == 0) ticket = __hip_atomic_fetch_add(&p.counters[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (ticket != S - 1) return;
+    if (threadIdx.x == 0) __hip_atomic_store(&p.counters[tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
+    const float *all = p.partial + (int64_t)tile * S * PSTRIDE;
+#pragma unroll
+    for (int i = 0; i < TI; ++i)
+#pragma unroll
+      for (int j = 0; j < TJ; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float v = 0.0f;
+          for (int q = 0; q < S; ++q) v += get_partial(all + (int64_t)q * PSTRIDE + ((i * TJ + j) * 16 + r) * 256 + threadIdx.x);
+          acc[i][j][r] = v;
+        }
+    if (FORM == FORM_DW && threadIdx.x < BM) {
+      bias_total = 0.0f;
+      for (int q = 0; q < S; ++q) bias_total += get_partial(all + (int64_t)q * PSTRIDE + BM * BN + threadIdx.x);
+    }
+  }
+  if (FORM == FORM_DW && do_bias && threadIdx.x < BM && m0 + (int)threadIdx.x < p.M) {
+    float *db = const_cast<float *>(p.bias) + m0 + threadIdx.x;
+    *db = accumulate_dw ? *db + bias_total : bias_total;
   }
 
   // ---- epilogue: accumulator register r of a 32x32 tile holds row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
@@ -260,6 +326,21 @@ int gemm_mfma_group_tile(int form, int maxM, int maxN) {
 int gemm_mfma_tiles_for(int tile, int M, int N, int *tiles_n) {
   if (tiles_n) *tiles_n = cdiv(N, tile);
   return cdiv(M, tile) * cdiv(N, tile);
+}
+// floats of one split's partial tile (the tile plus one row of bias-gradient partials)
+int gemm_mfma_partial_floats(int tile) { return tile * tile + tile; }
+// Split factor for a problem of a launch whose unsplit tiles add up to `launch_tiles`: aim at a few
+// workgroups per CU, keep every slice long enough that the partial tiles (written and read once,
+// fp32) do not exceed the operand bytes the slice streams.
+int gemm_mfma_pick_split(int tile, int launch_tiles, int rows_in_tile, int K) {
+  if (launch_tiles >= 512) return 1;
+  int want = (1024 + launch_tiles - 1) / launch_tiles;
+  int min_slice = 2 * (rows_in_tile < tile ? rows_in_tile : tile);
+  if (min_slice < 2 * BK) min_slice = 2 * BK;
+  int cap = K / min_slice;
+  if (cap < 1) cap = 1;
+  int s = want < cap ? want : cap;
+  return s > 32 ? 32 : s;
 }
 
 template <int FORM>

@@ -31,7 +31,9 @@ struct GemmProb {
   int32_t c_dtype, aux_dtype, res_dtype;
   int32_t blk_begin;  // first workgroup of this record
   int32_t tiles_n;    // tile columns of this record
-  int32_t split_k;    // reserved (1)
+  int32_t split_k;    // workgroups that share one output tile, each summing a slice of K
+  float *partial;     // split_k > 1: fp32 partial tiles [tile][split][tile elements + tile rows]
+  int32_t *counters;  // split_k > 1: arrival counter per tile (zero between launches)
 };
 
 // ---- 2-D copy / convert / accumulate / activation backward --------------
@@ -165,6 +167,12 @@ void launch_gemm_mfma(const GemmProb *probs, int n, int total_blocks, int accumu
 int gemm_generic_tiles(int M, int N, int *tiles_n);
 int gemm_mfma_group_tile(int form, int maxM, int maxN);
 int gemm_mfma_tiles_for(int tile, int M, int N, int *tiles_n);
+int gemm_mfma_partial_floats(int tile);
+// few-row (micro-batch <= 256 rows) forward / backward-data kernel
+void launch_gemm_skinny(const GemmProb *probs, int n, int total_blocks, int form, int row_tiles, hipStream_t s);
+int gemm_skinny_blocks(int M, int N, int row_tiles);
+int gemm_skinny_row_tiles(int M);
+int gemm_mfma_pick_split(int tile, int launch_tiles, int rows_in_tile, int K);
 bool gemm_mfma_supported(const GemmProb &p);
 
 void launch_elt(const EltProb *probs, int n, int total_blocks, const ExtPtrs &ext, hipStream_t s);

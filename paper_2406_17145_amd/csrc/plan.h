@@ -26,7 +26,8 @@ struct Buf {
 
 enum Kern : int32_t {
   K_ELT, K_GEMM_GENERIC, K_GEMM_MFMA, K_COLSUM, K_LN_FWD, K_LN_BWD, K_LN_BWD_PARAMS, K_ATTN_FWD, K_ATTN_DQ,
-  K_ATTN_DKV, K_POOL, K_EMB_FWD, K_EMB_BWD, K_INTERACT_FWD, K_INTERACT_BWD, K_LOSS_FWD, K_LOSS_BWD, K_LOSS_SUM
+  K_ATTN_DKV, K_POOL, K_EMB_FWD, K_EMB_BWD, K_INTERACT_FWD, K_INTERACT_BWD, K_LOSS_FWD, K_LOSS_BWD, K_LOSS_SUM,
+  K_GEMM_SKINNY
 };
 enum ExtKind : int32_t { EXT_NONE = 0, EXT_INPUTS, EXT_OUTPUTS, EXT_GRAD_OUTPUTS, EXT_GRAD_INPUTS };
 
@@ -67,6 +68,7 @@ struct Plan {
   int64_t micro_batch = 0;
   int32_t slots = 1, flags = 0;
   int64_t slot_bytes = 0, shared_bytes = 0, table_bytes = 0, tmp_bytes = 0;
+  int64_t gemm_partial_bytes = 0, gemm_counter_bytes = 0;   // split-K partial tiles and arrival counters
   int64_t off_flags = 0, off_tables = 0, off_slots = 0, off_shared = 0, total_bytes = 0;
   Buf loss_scalars;                  // f32 partial losses per slot
   int loss_parts = 0;

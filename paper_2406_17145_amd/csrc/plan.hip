@@ -362,7 +362,7 @@ void Plan::layout() {
   off_tables = 256;
   off_slots = align_up(off_tables + (int64_t)slots * table_bytes, 256);
   off_shared = off_slots + (int64_t)slots * slot_bytes;
-  total_bytes = off_shared + shared_bytes + tmp_bytes;
+  total_bytes = off_shared + shared_bytes + tmp_bytes + gemm_partial_bytes + gemm_counter_bytes;
 }
 
 // ===========================================================================
@@ -380,6 +380,7 @@ struct Emitter {
   std::vector<int> gstate;
   std::vector<Buf> gaddend;
   std::vector<char> dz_ready;
+  int64_t part_need = 0, cnt_need = 0;  // split-K scratch high-water marks over all launches
   std::vector<int> written_level;   // level whose launches first wrote the node's gradient
   int cur_level = 0;
   int64_t shared_tmp_top;
@@ -551,11 +552,45 @@ struct Emitter {
             max_n = std::max(max_n, r.N);
           }
           if (use_mfma) tile = gemm_mfma_group_tile(form, max_m, max_n);
+          // few rows: the weight-streaming kernel (forward and backward-data only)
+          const int row_tiles = (use_mfma && form != FORM_DW) ? gemm_skinny_row_tiles(max_m) : 0;
+          if (row_tiles > 0) {
+            int blocks = 0;
+            for (auto &r : g) {
+              r.blk_begin = blocks;
+              r.split_k = 1;
+              blocks += gemm_skinny_blocks(r.M, r.N, row_tiles);
+            }
+            Step &s = add_step(K_GEMM_SKINNY, push_table(g), (int)g.size(), blocks);
+            s.a0 = dt;
+            s.a1 = form;
+            s.a2 = row_tiles;
+            continue;
+          }
+          int launch_tiles = 0;
+          if (use_mfma)
+            for (auto &r : g) launch_tiles += gemm_mfma_tiles_for(tile, r.M, r.N, nullptr);
+          int64_t part_off = 0, cnt_off = 0;
           for (auto &r : g) {
             r.blk_begin = blocks;
             r.split_k = 1;
-            blocks += use_mfma ? gemm_mfma_tiles_for(tile, r.M, r.N, &r.tiles_n) : gemm_generic_tiles(r.M, r.N, &r.tiles_n);
+            if (!use_mfma) {
+              blocks += gemm_generic_tiles(r.M, r.N, &r.tiles_n);
+              continue;
+            }
+            const int tiles = gemm_mfma_tiles_for(tile, r.M, r.N, &r.tiles_n);
+            // rows of the streamed operands that one tile covers: the output's rows for FWD / DX
+            r.split_k = (pl.flags & 2) ? gemm_mfma_pick_split(tile, launch_tiles, form == FORM_DW ? tile : r.M, r.K) : 1;
+            if (r.split_k > 1) {  // partial tiles and arrival counters live behind the shared region
+              r.partial = (float *)(ws + pl.off_shared + pl.shared_bytes + pl.tmp_bytes + part_off);
+              r.counters = (int32_t *)(ws + pl.off_shared + pl.shared_bytes + pl.tmp_bytes + pl.gemm_partial_bytes + cnt_off);
+              part_off += (int64_t)tiles * r.split_k * gemm_mfma_partial_floats(tile) * 4;
+              cnt_off += align_up((int64_t)tiles * 4, 256);
+            }
+            blocks += tiles * r.split_k;
           }
+          part_need = std::max(part_need, align_up(part_off, 256));
+          cnt_need = std::max(cnt_need, cnt_off);
           Step &s = add_step(use_mfma ? K_GEMM_MFMA : K_GEMM_GENERIC, push_table(g), (int)g.size(), blocks);
           s.a0 = dt;
           s.a1 = form;
@@ -1314,6 +1349,8 @@ gpp_status_t Plan::emit(int slot, char *ws) {
   table_bytes = std::max<int64_t>(table_bytes, align_up((int64_t)blob.size(), 256));
   // temporaries requested during emission extend the shared region (same for every slot)
   tmp_bytes = std::max<int64_t>(tmp_bytes, em.shared_tmp_top);
+  gemm_partial_bytes = std::max<int64_t>(gemm_partial_bytes, em.part_need);
+  gemm_counter_bytes = std::max<int64_t>(gemm_counter_bytes, em.cnt_need);
   return GPP_OK;
 }
 

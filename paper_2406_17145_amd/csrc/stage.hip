@@ -58,6 +58,7 @@ struct gpp_stage {
 static int step_tag(const Step &sp, bool backward) {
   switch (sp.kern) {
     case K_GEMM_MFMA: return 1 + sp.a1;                    // 1 fwd, 2 dx, 3 dw
+    case K_GEMM_SKINNY: return 25 + sp.a1;                 // 25 fwd, 26 dx
     case K_GEMM_GENERIC: return backward ? 5 : 4;
     case K_ELT: return backward ? 7 : 6;
     case K_COLSUM: return 8;
@@ -82,7 +83,8 @@ static const char *const kTagNames[GPP_PROFILE_TAGS] = {
     "other", "gemm_mfma_fwd", "gemm_mfma_dx", "gemm_mfma_dw", "gemm_generic_fwd", "gemm_generic_bwd", "elt_fwd", "elt_bwd",
     "colsum_bias_grad", "layernorm_fwd", "layernorm_bwd_dx", "layernorm_bwd_params", "attention_fwd", "attention_bwd_dq",
     "attention_bwd_dkv", "meanpool_fwd", "meanpool_bwd", "embedding_fwd", "embedding_bwd_sort_segsum", "interact_fwd",
-    "interact_bwd", "loss_fwd", "loss_bwd", "loss_sum", "embedding_grad_clear", "", "", "", "", "", "", ""};
+    "interact_bwd", "loss_fwd", "loss_bwd", "loss_sum", "embedding_grad_clear", "gemm_skinny_fwd", "gemm_skinny_dx", "", "", "", "",
+    ""};
 
 extern "C" {
 
@@ -236,6 +238,7 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
       }
       case K_GEMM_GENERIC: launch_gemm_generic((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a0, s); break;
       case K_GEMM_MFMA: launch_gemm_mfma((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a1, sp.a2, s); break;
+      case K_GEMM_SKINNY: launch_gemm_skinny((const GemmProb *)tab, sp.n, sp.blocks, sp.a1, sp.a2, s); break;
       case K_COLSUM: launch_colsum((const ColsumProb *)tab, sp.n, sp.blocks, accumulate, s); break;
       case K_LN_FWD: launch_ln_fwd((const LnProb *)tab, sp.n, sp.blocks, s); break;
       case K_LN_BWD: launch_ln_bwd((const LnProb *)tab, sp.n, sp.blocks, sp.a0, sp.a1, s); break;

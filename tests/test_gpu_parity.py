@@ -217,4 +217,19 @@ def test_grad_reset_starts_new_sums():
 def test_generic_and_default_gemm_paths_agree_with_oracle():
     wl = W.candle_uno(micro_batch=64, n_micro=2, widths=(96, 200, 8, 64), hidden=128, act="gelu")
     both(wl, flags=B.FLAG_FORCE_GENERIC_GEMM)
+    both(wl, flags=B.FLAG_SPLIT_K)
     both(wl)
+
+
+def test_split_k_is_deterministic_and_matches_unsplit():
+    # long contraction, few output tiles: with the flag set the planner splits K across workgroups
+    wl = W.candle_uno(micro_batch=48, n_micro=2, widths=(2048, 1500, 8, 64), hidden=96, act="gelu")
+    _, g1 = run_gpu(wl, flags=B.FLAG_SPLIT_K)
+    _, g2 = run_gpu(wl, flags=B.FLAG_SPLIT_K)
+    _, g0 = run_gpu(wl)
+    for i in g1:
+        for k in g1[i]:
+            assert np.array_equal(g1[i][k], g2[i][k]), (i, k)
+            d = np.linalg.norm(g1[i][k] - g0[i][k]) / max(np.linalg.norm(g0[i][k]), 1e-30)
+            assert d <= 2e-2, (i, k, d)
+    both(wl, flags=B.FLAG_SPLIT_K)
