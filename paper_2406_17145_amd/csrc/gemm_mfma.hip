@@ -24,7 +24,9 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int BK = 32;        // contraction elements per k-step
-constexpr int PAD = 8;        // LDS row padding (elements)
+constexpr int PAD = 8;        // LDS row padding (elements) of k-contiguous tiles: 80-byte rows, conflict-free b128 reads
+constexpr int PAD_TR = 32;    // padding of contraction-row tiles: the four rows a 16-lane block of the transposing
+                              // read touches then start 16 banks apart (measured: halves LDS bank-conflict cycles)
 
 struct TileCfg {
   int bm, bn;
@@ -70,7 +72,7 @@ __device__ __forceinline__ void tile_fetch(TileRegs<ROWS, COLS> &t, const uint16
 template <int ROWS, int COLS>
 __device__ __forceinline__ void tile_store_lds(const TileRegs<ROWS, COLS> &t, uint16_t *lds) {
   constexpr int CPR = COLS / 8;
-  constexpr int STRIDE = COLS + PAD;
+  constexpr int STRIDE = COLS + (COLS == BK ? PAD : PAD_TR);
 #pragma unroll
   for (int q = 0; q < TileRegs<ROWS, COLS>::PER_THREAD; ++q) {
     const int c = threadIdx.x + 256 * q;
@@ -85,16 +87,16 @@ __device__ __forceinline__ bf16x8 frag_kmajor(const uint16_t *lds, int row0, int
   const int l = threadIdx.x & 63;
   return *(const bf16x8 *)(lds + (row0 + (l & 31)) * (BK + PAD) + k0 + 8 * (l >> 5));
 }
-// contraction-row tile [BK][cols + PAD]: transposing read.  In each block of 16 lanes, lane q
+// contraction-row tile [BK][cols + PAD_TR]: transposing read.  In each block of 16 lanes, lane q
 // addresses row (q / 4) at columns 4 * (q % 4) .. +3 and receives rows 0..3 of column q.
 template <int COLS>
 __device__ __forceinline__ bf16x8 frag_tr(const uint16_t *lds, int col0, int k0) {
   const int l = threadIdx.x & 63;
   const int blk = l >> 4, q = l & 15;
-  const uint16_t *p = lds + (k0 + 8 * (blk >> 1) + (q >> 2)) * (COLS + PAD) + col0 + 16 * (blk & 1) + 4 * (q & 3);
+  const uint16_t *p = lds + (k0 + 8 * (blk >> 1) + (q >> 2)) * (COLS + PAD_TR) + col0 + 16 * (blk & 1) + 4 * (q & 3);
   typedef __attribute__((address_space(3))) s16x4 lds_v4;
   s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)p);
-  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(p + 4 * (COLS + PAD)));
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(p + 4 * (COLS + PAD_TR)));
   typedef __attribute__((ext_vector_type(8))) short s16x8;
   s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(bf16x8, v);
@@ -119,8 +121,8 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const GemmProb *__restrict__ 
   constexpr bool B_TR = FORM != FORM_FWD;
   constexpr int WM = BM / 2, WN = BN / 2;                 // 2 x 2 waves
   constexpr int TI = WM / 32, TJ = WN / 32;               // 32x32 MFMA tiles per wave
-  constexpr int A_ELEMS = A_TR ? BK * (BM + PAD) : BM * (BK + PAD);
-  constexpr int B_ELEMS = B_TR ? BK * (BN + PAD) : BN * (BK + PAD);
+  constexpr int A_ELEMS = A_TR ? BK * (BM + PAD_TR) : BM * (BK + PAD);
+  constexpr int B_ELEMS = B_TR ? BK * (BN + PAD_TR) : BN * (BK + PAD);
   __shared__ __attribute__((aligned(16))) uint16_t lds_a[2][A_ELEMS];
   __shared__ __attribute__((aligned(16))) uint16_t lds_b[2][B_ELEMS];
 
@@ -152,6 +154,24 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const GemmProb *__restrict__ 
     for (int j = 0; j < TJ; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  // backward-weight with accumulation: request the old gradient tile now, so that its latency is
+  // hidden behind the operand fetch and the MFMAs instead of sitting between them and the store
+  const bool c_prefetch = FORM == FORM_DW && accumulate_dw && S == 1;
+  f32x16 c_old[TI][TJ];
+  if (FORM == FORM_DW && c_prefetch) {
+#pragma unroll
+    for (int i = 0; i < TI; ++i)
+#pragma unroll
+      for (int j = 0; j < TJ; ++j) {
+        const int col = n0 + wj0 + 32 * j + (lane & 31);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = m0 + wi0 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          c_old[i][j][r] = (row < p.M && col < p.N) ? ((const float *)p.C)[(int64_t)row * p.ldc + col] : 0.0f;
+        }
+      }
+  }
 
   typedef TileRegs<A_TR ? BK : BM, A_TR ? BM : BK> RegsA;
   typedef TileRegs<B_TR ? BK : BN, B_TR ? BN : BK> RegsB;
@@ -201,9 +221,9 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const GemmProb *__restrict__ 
           for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
       }
       if (FORM == FORM_DW && do_bias) {
-        const uint16_t *la = lds_a[cur] + (threadIdx.x / BM) * BROWS * (BM + PAD) + (threadIdx.x % BM);
+        const uint16_t *la = lds_a[cur] + (threadIdx.x / BM) * BROWS * (BM + PAD_TR) + (threadIdx.x % BM);
 #pragma unroll
-        for (int rr = 0; rr < BROWS; ++rr) bsum += bf16_bits_to_f32(la[rr * (BM + PAD)]);
+        for (int rr = 0; rr < BROWS; ++rr) bsum += bf16_bits_to_f32(la[rr * (BM + PAD_TR)]);
       }
       if (kt + 1 < nk) {
         tile_store_lds<A_TR ? BK : BM, A_TR ? BM : BK>(ra[(u + 1) % NS], lds_a[cur ^ 1]);
@@ -293,7 +313,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const GemmProb *__restrict__ 
           store_from_f32(p.C, p.c_dtype, ci, v);
         } else {
           float *c = (float *)p.C;
-          c[ci] = accumulate_dw ? c[ci] + v : v;
+          c[ci] = c_prefetch ? c_old[i][j][r] + v : (accumulate_dw ? c[ci] + v : v);
         }
       }
     }

@@ -23,7 +23,8 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int SK_BN = 64;             // output columns per workgroup
-constexpr int SK_ST = SK_BN + 8;      // LDS row stride of a staged 64-wide tile (elements)
+constexpr int SK_ST = SK_BN + 8;      // LDS row stride of a k-contiguous 64-wide tile (elements)
+constexpr int SK_ST_TR = SK_BN + 32;  // row stride of the contraction-row W tile read with the transposing read
 
 // 32-row tiles per workgroup (1 or 2); 0 when the problem has too many rows for this kernel.
 // More than 64 rows are covered by several workgroups per column block, which re-read W from L2.
@@ -68,7 +69,10 @@ __global__ __launch_bounds__(64 * SkWaves<TI>::value) void k_gemm_skinny(const G
   constexpr int NW = SkWaves<TI>::value;
   constexpr int BM = 32 * TI;
   constexpr int RED_FLOATS = (NW / 2) * BM * SK_BN;
-  constexpr int WAVE_ELEMS = (BM + 64) * SK_ST;            // a wave's private A and B tiles
+  // row stride of the B tile: the conflict-free stride of the transposing read when the waves' tiles
+  // still fit in the 160 KB of LDS, else the compact one
+  constexpr int SB = (FORM == FORM_DX && NW * (BM * SK_ST + 64 * SK_ST_TR) * 2 <= 160 * 1024) ? SK_ST_TR : SK_ST;
+  constexpr int WAVE_ELEMS = BM * SK_ST + 64 * SB;         // a wave's private A and B tiles
   constexpr int LDS_BYTES = RED_FLOATS * 4 > NW * WAVE_ELEMS * 2 ? RED_FLOATS * 4 : NW * WAVE_ELEMS * 2;
   __shared__ __attribute__((aligned(16))) unsigned char lds_raw[LDS_BYTES];
   float *red = (float *)lds_raw;           // after the k-loop: two BM x 64 fp32 buffers
@@ -111,7 +115,7 @@ __global__ __launch_bounds__(64 * SkWaves<TI>::value) void k_gemm_skinny(const G
 #pragma unroll
     for (int q = 0; q < 4 * TI; ++q) *(u32x4 *)(lds_a + (8 * q + crow) * SK_ST + ccol) = f.a[q];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) *(u32x4 *)(lds_b + (8 * q + crow) * SK_ST + ccol) = f.b[q];
+    for (int q = 0; q < 8; ++q) *(u32x4 *)(lds_b + (8 * q + crow) * SB + ccol) = f.b[q];
   };
   auto multiply = [&]() {
     const int blk = lane >> 4, q16 = lane & 15;
@@ -127,9 +131,9 @@ __global__ __launch_bounds__(64 * SkWaves<TI>::value) void k_gemm_skinny(const G
           b[j] = *(const bf16x8 *)(lds_b + (32 * j + r) * SK_ST + 16 * c + 8 * h);
         } else {
           // transposing read: in each block of 16 lanes, lane q addresses row (q / 4), columns 4 (q % 4)..+3
-          const uint16_t *ptr = lds_b + (16 * c + 8 * (blk >> 1) + (q16 >> 2)) * SK_ST + 32 * j + 16 * (blk & 1) + 4 * (q16 & 3);
+          const uint16_t *ptr = lds_b + (16 * c + 8 * (blk >> 1) + (q16 >> 2)) * SB + 32 * j + 16 * (blk & 1) + 4 * (q16 & 3);
           s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)ptr);
-          s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(ptr + 4 * SK_ST));
+          s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(ptr + 4 * SB));
           b[j] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         }
       }
