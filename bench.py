@@ -67,6 +67,51 @@ def gemm_traffic(wl):
     return out
 
 
+def other_traffic(wl):
+    """Algorithmic (bytes, flops) per micro-batch of the non-GEMM kernels that can dominate a workload.
+
+    embedding forward   compulsory HBM bytes: every distinct table row of the micro-batch once, the index
+                        and offset arrays once, the pooled output once (the logical gather, one row read
+                        per index, is reported beside it as `logical`)
+    embedding backward  pooled-output gradient once, index array once, every distinct row of the fp32
+                        gradient table read and written once
+    attention           forward 4*S*S*dh flops per (sample, head): QK^T and PV; backward 8: dV, dP, dQ, dK
+    """
+    import numpy as np
+    out = {}
+    emb_ops = [(i, op) for i, op in enumerate(wl.ops) if op["kind"] == "embedding_bag_sum"]
+    if emb_ops:
+        mb = wl.batches[0]
+        fwd = bwd = logical = 0
+        for i, op in emb_ops:
+            ins = op["inputs"]
+            idx, off = np.asarray(mb[ins[0]]), np.asarray(mb[ins[1]])
+            n_used = int(off[-1])
+            uniq = int(np.unique(idx[:n_used]).size)
+            dim = op["out_features"]
+            es_out = 2 if op.get("dtype", "f32") == "bf16" else 4
+            pooled = wl.micro_batch * dim * es_out
+            fwd += uniq * dim * 4 + n_used * 4 + off.size * 4 + pooled
+            logical += n_used * dim * 4 + n_used * 4 + off.size * 4 + pooled
+            bwd += pooled + n_used * 4 + 2 * uniq * dim * 4
+        out["embedding_fwd"] = (fwd, 0, logical)
+        out["embedding_bwd_sort_segsum"] = (bwd, 0, bwd)
+    att = [op for op in wl.ops if op["kind"] == "attention"]
+    if att:
+        fl = sum(wl.micro_batch * op["seq_len"] ** 2 * op["out_features"] for op in att)   # heads * dh = d_model
+        by = sum(wl.micro_batch * op["seq_len"] * op["out_features"] * 2 * 4 for op in att)   # q, k, v, o in bf16
+        out["attention_fwd"] = (by, 4 * fl, by)
+        out["attention_bwd_dq"] = (by, 4 * fl, by)
+        out["attention_bwd_dkv"] = (by, 4 * fl, by)
+    return out
+
+
+# HBM bytes per launch of the dominant kernel of each workload, from two rocprofv3 --pmc runs
+# (FETCH_SIZE, then WRITE_SIZE) scaled by what the same counters read for a copy of known size
+# (--copy-calibration); the summaries are kept under profiles/.  None where not measured.
+MEASURED_TRAFFIC = {}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -76,6 +121,8 @@ def main():
     ap.add_argument("--micro-batch", type=int, default=0, help="override the config's micro-batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-pass", action="store_true", help="skip the event-instrumented second pass")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="before the steps, run 3 plain elementwise copies of MIB mebibytes (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one stage on ONE GPU (no collectives, no sharding); "
@@ -103,6 +150,15 @@ def main():
         for mb in dev_batches:
             st.forward(0, mb, outputs=outs, loss=loss)
             st.backward(0, grad_outputs=gouts, grad_inputs=gins)
+
+    if args.copy_calibration:
+        # a copy of known size: reads MIB and writes MIB per launch (torch's elementwise kernel)
+        src = torch.ones(args.copy_calibration * (1 << 18), dtype=torch.float32, device=st.dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
@@ -142,6 +198,10 @@ def main():
             "gemm_generic_bwd": (tr["dx"][0] * nm + tr["dw_first"][0] + tr["dw"][0] * (nm - 1),
                                  (tr["dx"][1] + tr["dw"][1]) * nm),
         }
+        logical = {}
+        for name, (by, fl, lg) in other_traffic(wl).items():
+            alg[name] = (by * nm, fl * nm)
+            logical[name] = lg * nm
         dom = next(iter(kernels))
         if dom in alg:
             by, fl = alg[dom]
@@ -152,15 +212,23 @@ def main():
             hbm_bound = by / (HBM_PEAK_GBS * 1e9) >= fl / (MFMA_BF16_PEAK_TFLOPS * 1e12)
             if hbm_bound:
                 roofline = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                            "frac": gbs / HBM_PEAK_GBS, "traffic": None}
+                            "frac": gbs / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((args.config, dom))}
             else:
                 roofline = {"bound": "mfma", "achieved": tfl, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                            "frac": tfl / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+                            "frac": tfl / MFMA_BF16_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC.get((args.config, dom))}
             roofline.update({"kernel": dom, "avg_launch_us": k["avg_launch_us"],
                              "launches_per_step": k["launches_per_step"],
                              "algorithmic_bytes_per_launch": by / k["launches_per_step"],
                              "algorithmic_flops_per_launch": fl / k["launches_per_step"],
                              "other_fraction_tflops": tfl, "other_fraction_gbs": gbs})
+            if dom in logical:
+                roofline["logical_gbs"] = logical[dom] / sec / 1e9
+        # every kernel with a known algorithmic count: achieved rates beside the durations
+        for name, k in kernels.items():
+            if name in alg and k["ms_per_step"] > 0:
+                k["algorithmic_gbs"] = alg[name][0] / (k["ms_per_step"] * 1e-3) / 1e9
+                k["algorithmic_tflops"] = alg[name][1] / (k["ms_per_step"] * 1e-3) / 1e12
+
         else:
             roofline = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
                         "traffic": None, "kernel": dom}
