@@ -194,6 +194,8 @@ def main():
             "gemm_mfma_dw": (tr["dw_first"][0] + tr["dw"][0] * (nm - 1), tr["dw"][1] * nm),
             "gemm_skinny_fwd": (tr["fwd"][0] * nm, tr["fwd"][1] * nm),
             "gemm_skinny_dx": (tr["dx"][0] * nm, tr["dx"][1] * nm),
+            "gemm_bwd_merged_dx_dw": (tr["dx"][0] * nm + tr["dw_first"][0] + tr["dw"][0] * (nm - 1),
+                                      (tr["dx"][1] + tr["dw"][1]) * nm),
             "gemm_generic_fwd": (tr["fwd"][0] * nm, tr["fwd"][1] * nm),
             "gemm_generic_bwd": (tr["dx"][0] * nm + tr["dw_first"][0] + tr["dw"][0] * (nm - 1),
                                  (tr["dx"][1] + tr["dw"][1]) * nm),

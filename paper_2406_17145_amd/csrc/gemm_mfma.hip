@@ -1,131 +1,19 @@
-// Branch-grouped bf16 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16),
-// fp32 accumulation, LDS-staged tiles with a register prefetch of the next
-// k-step.  One launch covers every independent branch of a topological level:
-// the workgroup index is first spread XCD-aware (consecutive tiles of a
-// problem land on one XCD and share its L2), then mapped to (problem, tile)
-// through the records' workgroup prefix sums.
-//
-// Three forms share the kernel.  What differs is which dimension of an
-// operand is contiguous in memory:
-//   FWD  C[m,n] = sum_k X[m,k] W[n,k]      A k-contiguous,  B k-contiguous
-//   DX   C[m,k] = sum_n dZ[m,n] W[n,k]     A k-contiguous,  B row = contraction index
-//   DW   C[n,k] += sum_m dZ[m,n] X[m,k]    A and B: row = contraction index
-// Operands whose rows run along the contraction index are stored in LDS as
-// they are in memory and fetched with the transposing LDS read
-// (ds_read_b64_tr_b16), which hands each lane four consecutive contraction
-// steps of its own row/column, exactly what the MFMA operand layout wants.
-#include "device_utils.h"
+// Branch-grouped bf16 GEMM on the CDNA4 matrix cores: the stand-alone kernel around the tile body.
+// One launch covers every independent branch of a topological level: the workgroup index is first
+// spread XCD-aware (consecutive tiles of a problem land on one XCD and share its L2), then mapped to
+// (problem, tile) through the records' workgroup prefix sums.
+#include "gemm_tile_body.h"
 
 namespace gpp {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-
-constexpr int BK = 32;        // contraction elements per k-step
-constexpr int PAD = 8;        // LDS row padding (elements) of k-contiguous tiles: 80-byte rows, conflict-free b128 reads
-constexpr int PAD_TR = 32;    // padding of contraction-row tiles: the four rows a 16-lane block of the transposing
-                              // read touches then start 16 banks apart (measured: halves LDS bank-conflict cycles)
 
 struct TileCfg {
   int bm, bn;
 };
-__host__ __device__ constexpr int cdiv(int a, int b) { return (a + b - 1) / b; }
 
-// ---- global -> register tile fetch -------------------------------------------
-// A tile is ROWS x COLS elements, COLS contiguous in memory; each thread owns
-// 16-byte chunks (8 elements).  Out-of-range rows / columns read as zero.
-template <int ROWS, int COLS>
-struct TileRegs {
-  static constexpr int CHUNKS = ROWS * COLS / 8;
-  static constexpr int PER_THREAD = (CHUNKS + 255) / 256;
-  u32x4 v[PER_THREAD];
-};
-
-template <int ROWS, int COLS>
-__device__ __forceinline__ void tile_fetch(TileRegs<ROWS, COLS> &t, const uint16_t *__restrict__ base, int64_t ld,
-                                           int row0, int col0, int row_lim, int col_lim) {
-  constexpr int CPR = COLS / 8;  // chunks per row
-#pragma unroll
-  for (int q = 0; q < TileRegs<ROWS, COLS>::PER_THREAD; ++q) {
-    const int c = threadIdx.x + 256 * q;
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (TileRegs<ROWS, COLS>::CHUNKS % 256 == 0 || c < TileRegs<ROWS, COLS>::CHUNKS) {
-      const int r = row0 + c / CPR, cc = col0 + (c % CPR) * 8;
-      if (r < row_lim && cc < col_lim) {
-        v = *(const u32x4 *)(base + (int64_t)r * ld + cc);
-        if (cc + 8 > col_lim) {  // ragged tail: clear the elements past the limit
-          const int keep = col_lim - cc;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            if (2 * e >= keep) v[e] = 0u;
-            else if (2 * e + 1 >= keep) v[e] &= 0xffffu;
-          }
-        }
-      }
-    }
-    t.v[q] = v;
-  }
-}
-
-template <int ROWS, int COLS>
-__device__ __forceinline__ void tile_store_lds(const TileRegs<ROWS, COLS> &t, uint16_t *lds) {
-  constexpr int CPR = COLS / 8;
-  constexpr int STRIDE = COLS + (COLS == BK ? PAD : PAD_TR);
-#pragma unroll
-  for (int q = 0; q < TileRegs<ROWS, COLS>::PER_THREAD; ++q) {
-    const int c = threadIdx.x + 256 * q;
-    if (TileRegs<ROWS, COLS>::CHUNKS % 256 == 0 || c < TileRegs<ROWS, COLS>::CHUNKS)
-      *(u32x4 *)(lds + (c / CPR) * STRIDE + (c % CPR) * 8) = t.v[q];
-  }
-}
-
-// ---- LDS -> MFMA operand ---------------------------------------------------------
-// k-contiguous tile [rows][BK + PAD]: lane l takes row (l % 32), 8 k-values at 8 * (l / 32)
-__device__ __forceinline__ bf16x8 frag_kmajor(const uint16_t *lds, int row0, int k0) {
-  const int l = threadIdx.x & 63;
-  return *(const bf16x8 *)(lds + (row0 + (l & 31)) * (BK + PAD) + k0 + 8 * (l >> 5));
-}
-// contraction-row tile [BK][cols + PAD_TR]: transposing read.  In each block of 16 lanes, lane q
-// addresses row (q / 4) at columns 4 * (q % 4) .. +3 and receives rows 0..3 of column q.
-template <int COLS>
-__device__ __forceinline__ bf16x8 frag_tr(const uint16_t *lds, int col0, int k0) {
-  const int l = threadIdx.x & 63;
-  const int blk = l >> 4, q = l & 15;
-  const uint16_t *p = lds + (k0 + 8 * (blk >> 1) + (q >> 2)) * (COLS + PAD_TR) + col0 + 16 * (blk & 1) + 4 * (q & 3);
-  typedef __attribute__((address_space(3))) s16x4 lds_v4;
-  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)p);
-  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(p + 4 * (COLS + PAD_TR)));
-  typedef __attribute__((ext_vector_type(8))) short s16x8;
-  s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, v);
-}
-
-// Split-K partial sums cross workgroups (and XCDs, whose L2 caches are not coherent with each other
-// inside a kernel).  They are written and read with device-scope relaxed atomics, which go through
-// to memory instead of staying in the writer's L2, so no cache-wide write-back or invalidate is
-// needed: ordering comes from waiting for the stores' acknowledgements before the ticket is taken.
-__device__ __forceinline__ void put_partial(float *p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float get_partial(const float *p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// ---- the kernel ---------------------------------------------------------------------
 template <int FORM, int BM, int BN>
 __global__ __launch_bounds__(256) void k_gemm_mfma(const GemmProb *__restrict__ probs, int n, int total_blocks,
-                                                   int accumulate_dw) {
-  constexpr bool A_TR = FORM == FORM_DW;                  // A rows run along the contraction index
-  constexpr bool B_TR = FORM != FORM_FWD;
-  constexpr int WM = BM / 2, WN = BN / 2;                 // 2 x 2 waves
-  constexpr int TI = WM / 32, TJ = WN / 32;               // 32x32 MFMA tiles per wave
-  constexpr int A_ELEMS = A_TR ? BK * (BM + PAD_TR) : BM * (BK + PAD);
-  constexpr int B_ELEMS = B_TR ? BK * (BN + PAD_TR) : BN * (BK + PAD);
-  __shared__ __attribute__((aligned(16))) uint16_t lds_a[2][A_ELEMS];
-  __shared__ __attribute__((aligned(16))) uint16_t lds_b[2][B_ELEMS];
-
+                                                   int accumulate_dw, ExtPtrs ext) {
+  __shared__ __attribute__((aligned(16))) uint16_t lds[TileLds<FORM, BM, BN>::ELEMS];
   // XCD-aware spreading: hardware deals consecutive workgroup ids round-robin over the 8 XCDs;
   // give each XCD one contiguous range of tiles instead
   int bid = blockIdx.x;
@@ -135,188 +23,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const GemmProb *__restrict__ 
   }
   const int pi = find_prob(probs, n, bid);
   const GemmProb p = probs[pi];
-  // split-K: `split` workgroups with consecutive ids share one output tile, each sums a slice of K
-  const int S = p.split_k, split = (bid - p.blk_begin) % S;
-  const int tile = (bid - p.blk_begin) / S;
-  const int kslice = cdiv(cdiv(p.K, BK), S) * BK;
-  const int k_begin = split * kslice, k_end = min(p.K, k_begin + kslice);
-  const int tiles_m = cdiv(p.M, BM);
-  const int m0 = (tile % tiles_m) * BM, n0 = (tile / tiles_m) * BN;   // consecutive tiles share the B panel
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int wi0 = (wave >> 1) * WM, wj0 = (wave & 1) * WN;
-  const uint16_t *A = (const uint16_t *)p.A;
-  const uint16_t *B = (const uint16_t *)p.B;
-
-  f32x16 acc[TI][TJ];
-#pragma unroll
-  for (int i = 0; i < TI; ++i)
-#pragma unroll
-    for (int j = 0; j < TJ; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
-  // backward-weight with accumulation: request the old gradient tile now, so that its latency is
-  // hidden behind the operand fetch and the MFMAs instead of sitting between them and the store
-  const bool c_prefetch = FORM == FORM_DW && accumulate_dw && S == 1;
-  f32x16 c_old[TI][TJ];
-  if (FORM == FORM_DW && c_prefetch) {
-#pragma unroll
-    for (int i = 0; i < TI; ++i)
-#pragma unroll
-      for (int j = 0; j < TJ; ++j) {
-        const int col = n0 + wj0 + 32 * j + (lane & 31);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = m0 + wi0 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-          c_old[i][j][r] = (row < p.M && col < p.N) ? ((const float *)p.C)[(int64_t)row * p.ldc + col] : 0.0f;
-        }
-      }
-  }
-
-  typedef TileRegs<A_TR ? BK : BM, A_TR ? BM : BK> RegsA;
-  typedef TileRegs<B_TR ? BK : BN, B_TR ? BN : BK> RegsB;
-  // NS k-steps are kept in flight in registers: the tile consumed at step kt was requested NS-1
-  // steps earlier, so the k-loop runs at the rate of its own work, not of the memory latency
-  constexpr int NS = BM * BN >= 128 * 128 ? 4 : 8;
-  RegsA ra[NS];
-  RegsB rb[NS];
-  auto fetch = [&](RegsA &xa, RegsB &xb, int k0) {
-    if (A_TR) tile_fetch<A_TR ? BK : BM, A_TR ? BM : BK>(xa, A, p.lda, k0, m0, k_end, p.M);
-    else      tile_fetch<A_TR ? BK : BM, A_TR ? BM : BK>(xa, A, p.lda, m0, k0, p.M, k_end);
-    if (B_TR) tile_fetch<B_TR ? BK : BN, B_TR ? BN : BK>(xb, B, p.ldb, k0, n0, k_end, p.N);
-    else      tile_fetch<B_TR ? BK : BN, B_TR ? BN : BK>(xb, B, p.ldb, n0, k0, p.N, k_end);
-  };
-  // backward-weight tiles of the first column block also sum the rows of dZ^T they stream: the bias
-  // gradient db[n] = sum_m dZ[m,n] comes out of the same launch
-  constexpr int BGROUPS = 256 / BM, BROWS = BK / BGROUPS;
-  const bool do_bias = FORM == FORM_DW && p.bias != nullptr && n0 == 0;
-  float bsum = 0.0f;
-  const int nk = max(0, cdiv(k_end - k_begin, BK));
-#pragma unroll
-  for (int u = 0; u < NS; ++u)
-    if (u < nk || u == 0) fetch(ra[u], rb[u], k_begin + u * BK);
-  tile_store_lds<A_TR ? BK : BM, A_TR ? BM : BK>(ra[0], lds_a[0]);
-  tile_store_lds<B_TR ? BK : BN, B_TR ? BN : BK>(rb[0], lds_b[0]);
-  __syncthreads();
-  for (int kt0 = 0; kt0 < nk; kt0 += NS) {
-#pragma unroll
-    for (int u = 0; u < NS; ++u) {
-      const int kt = kt0 + u;
-      if (kt >= nk) break;
-      const int cur = u & 1;   // NS is even, so the LDS buffer of step kt is kt & 1 = u & 1
-      // slot u held tile kt, already copied to LDS: reuse it for tile kt + NS
-      if (kt + NS < nk) fetch(ra[u], rb[u], k_begin + (kt + NS) * BK);
-#pragma unroll
-      for (int kc = 0; kc < BK; kc += 16) {
-        bf16x8 a[TI], b[TJ];
-#pragma unroll
-        for (int i = 0; i < TI; ++i)
-          a[i] = A_TR ? frag_tr<BM>(lds_a[cur], wi0 + 32 * i, kc) : frag_kmajor(lds_a[cur], wi0 + 32 * i, kc);
-#pragma unroll
-        for (int j = 0; j < TJ; ++j)
-          b[j] = B_TR ? frag_tr<BN>(lds_b[cur], wj0 + 32 * j, kc) : frag_kmajor(lds_b[cur], wj0 + 32 * j, kc);
-#pragma unroll
-        for (int i = 0; i < TI; ++i)
-#pragma unroll
-          for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-      }
-      if (FORM == FORM_DW && do_bias) {
-        const uint16_t *la = lds_a[cur] + (threadIdx.x / BM) * BROWS * (BM + PAD_TR) + (threadIdx.x % BM);
-#pragma unroll
-        for (int rr = 0; rr < BROWS; ++rr) bsum += bf16_bits_to_f32(la[rr * (BM + PAD_TR)]);
-      }
-      if (kt + 1 < nk) {
-        tile_store_lds<A_TR ? BK : BM, A_TR ? BM : BK>(ra[(u + 1) % NS], lds_a[cur ^ 1]);
-        tile_store_lds<B_TR ? BK : BN, B_TR ? BN : BK>(rb[(u + 1) % NS], lds_b[cur ^ 1]);
-      }
-      __syncthreads();
-    }
-  }
-
-  float bias_total = 0.0f;            // threads < BM: this split's column sum of the dZ^T tile
-  if (FORM == FORM_DW && do_bias) {   // fold the row groups in a fixed order (the k-loop ended with a barrier)
-    float *red = (float *)&lds_b[0][0];
-    red[threadIdx.x] = bsum;
-    __syncthreads();
-    if (threadIdx.x < BM) {
-#pragma unroll
-      for (int g = 0; g < BGROUPS; ++g) bias_total += red[g * BM + threadIdx.x];
-    }
-  }
-
-  if (S > 1) {
-    // Deterministic split-K: every split stores its fp32 partial tile; the split that arrives last
-    // (arrival counter, no waiting) adds all partials in split order and runs the epilogue.
-    constexpr int PSTRIDE = BM * BN + BM;
-    float *mine = p.partial + ((int64_t)tile * S + split) * PSTRIDE;
-#pragma unroll
-    for (int i = 0; i < TI; ++i)
-#pragma unroll
-      for (int j = 0; j < TJ; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) put_partial(mine + ((i * TJ + j) * 16 + r) * 256 + threadIdx.x, acc[i][j][r]);
-    if (FORM == FORM_DW && threadIdx.x < BM) put_partial(mine + BM * BN + threadIdx.x, bias_total);
-    // the partial stores go through to memory; once this wave's stores have been acknowledged and
-    // the workgroup has met, one thread takes a ticket
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __syncthreads();
-    __shared__ int ticket;
-    if (threadIdx.x == 0) ticket = __hip_atomic_fetch_add(&p.counters[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __syncthreads();
-    if (ticket != S - 1) return;
-    if (threadIdx.x == 0) __hip_atomic_store(&p.counters[tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
-    const float *all = p.partial + (int64_t)tile * S * PSTRIDE;
-#pragma unroll
-    for (int i = 0; i < TI; ++i)
-#pragma unroll
-      for (int j = 0; j < TJ; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float v = 0.0f;
-          for (int q = 0; q < S; ++q) v += get_partial(all + (int64_t)q * PSTRIDE + ((i * TJ + j) * 16 + r) * 256 + threadIdx.x);
-          acc[i][j][r] = v;
-        }
-    if (FORM == FORM_DW && threadIdx.x < BM) {
-      bias_total = 0.0f;
-      for (int q = 0; q < S; ++q) bias_total += get_partial(all + (int64_t)q * PSTRIDE + BM * BN + threadIdx.x);
-    }
-  }
-  if (FORM == FORM_DW && do_bias && threadIdx.x < BM && m0 + (int)threadIdx.x < p.M) {
-    float *db = const_cast<float *>(p.bias) + m0 + threadIdx.x;
-    *db = accumulate_dw ? *db + bias_total : bias_total;
-  }
-
-  // ---- epilogue: accumulator register r of a 32x32 tile holds row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
-#pragma unroll
-  for (int i = 0; i < TI; ++i)
-#pragma unroll
-    for (int j = 0; j < TJ; ++j) {
-      const int col = n0 + wj0 + 32 * j + (lane & 31);
-      if (col >= p.N) continue;
-      float bias = 0.0f;
-      if (FORM == FORM_FWD && p.bias) bias = p.bias[col];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wi0 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (row >= p.M) continue;
-        float v = acc[i][j][r];
-        const int64_t ci = (int64_t)row * p.ldc + col;
-        if (FORM == FORM_FWD) {
-          v += bias;
-          if (p.aux) store_from_f32(p.aux, p.aux_dtype, (int64_t)row * p.ldaux + col, v);
-          v = act_apply(v, p.act);
-          if (p.res) v += load_as_f32(p.res, p.res_dtype, (int64_t)row * p.ldres + col);
-          store_from_f32(p.C, p.c_dtype, ci, v);
-        } else if (FORM == FORM_DX) {
-          if (p.res) v += load_as_f32(p.res, p.res_dtype, (int64_t)row * p.ldres + col);
-          if (p.act != ACT_NONE) v *= act_grad(load_as_f32(p.aux, p.aux_dtype, (int64_t)row * p.ldaux + col), p.act);
-          store_from_f32(p.C, p.c_dtype, ci, v);
-        } else {
-          float *c = (float *)p.C;
-          c[ci] = c_prefetch ? c_old[i][j][r] + v : (accumulate_dw ? c[ci] + v : v);
-        }
-      }
-    }
+  gemm_tile_body<FORM, BM, BN, true>(p, bid - p.blk_begin, threadIdx.x, lds, accumulate_dw, ext);
 }
 
 // ---- host side -------------------------------------------------------------------------
@@ -364,19 +71,19 @@ int gemm_mfma_pick_split(int tile, int launch_tiles, int rows_in_tile, int K) {
 }
 
 template <int FORM>
-static void launch_form(const GemmProb *probs, int n, int blocks, int acc, int tile, hipStream_t s) {
+static void launch_form(const GemmProb *probs, int n, int blocks, int acc, int tile, const ExtPtrs &ext, hipStream_t s) {
   if (tile == 128)
-    hipLaunchKernelGGL((k_gemm_mfma<FORM, 128, 128>), dim3(blocks), dim3(256), 0, s, probs, n, blocks, acc);
+    hipLaunchKernelGGL((k_gemm_mfma<FORM, 128, 128>), dim3(blocks), dim3(256), 0, s, probs, n, blocks, acc, ext);
   else
-    hipLaunchKernelGGL((k_gemm_mfma<FORM, 64, 64>), dim3(blocks), dim3(256), 0, s, probs, n, blocks, acc);
+    hipLaunchKernelGGL((k_gemm_mfma<FORM, 64, 64>), dim3(blocks), dim3(256), 0, s, probs, n, blocks, acc, ext);
 }
 
 void launch_gemm_mfma(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int form, int tile,
-                      hipStream_t s) {
+                      const ExtPtrs &ext, hipStream_t s) {
   if (total_blocks <= 0) return;
-  if (form == FORM_FWD) launch_form<FORM_FWD>(probs, n, total_blocks, accumulate_dw, tile, s);
-  else if (form == FORM_DX) launch_form<FORM_DX>(probs, n, total_blocks, accumulate_dw, tile, s);
-  else launch_form<FORM_DW>(probs, n, total_blocks, accumulate_dw, tile, s);
+  if (form == FORM_FWD) launch_form<FORM_FWD>(probs, n, total_blocks, accumulate_dw, tile, ext, s);
+  else if (form == FORM_DX) launch_form<FORM_DX>(probs, n, total_blocks, accumulate_dw, tile, ext, s);
+  else launch_form<FORM_DW>(probs, n, total_blocks, accumulate_dw, tile, ext, s);
 }
 
 }  // namespace gpp

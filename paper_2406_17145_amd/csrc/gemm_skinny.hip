@@ -12,25 +12,25 @@
 // and reads MFMA operands from there; W in the backward-data form is read
 // with the transposing LDS read.  The partial accumulators are added in a
 // fixed tree order through LDS, then all waves share the epilogue.
-#include "device_utils.h"
+//
+// The backward pass of a level runs both consumers of dZ in ONE launch: workgroups of the first
+// records compute dX with the few-row body, the rest compute dW (+ db) with the tile body, two
+// 256-thread teams per workgroup on neighbouring tiles.
+#include "gemm_tile_body.h"
 
 namespace gpp {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(8))) short s16x8;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-
-constexpr int SK_BN = 64;             // output columns per workgroup
-constexpr int SK_ST = SK_BN + 8;      // LDS row stride of a k-contiguous 64-wide tile (elements)
-constexpr int SK_ST_TR = SK_BN + 32;  // row stride of the contraction-row W tile read with the transposing read
+constexpr int SK_KS = 64;             // contraction elements per k-step of a wave
+constexpr int SK_ST = SK_KS + 8;      // LDS row stride of a k-contiguous 64-wide tile (elements)
 
 // 32-row tiles per workgroup (1 or 2); 0 when the problem has too many rows for this kernel.
 // More than 64 rows are covered by several workgroups per column block, which re-read W from L2.
 int gemm_skinny_row_tiles(int M) { return M <= 32 ? 1 : (M <= 256 ? 2 : 0); }
-int gemm_skinny_blocks(int M, int N, int row_tiles) {
-  return ((N + SK_BN - 1) / SK_BN) * ((M + 32 * row_tiles - 1) / (32 * row_tiles));
+// 32-column tiles per workgroup: 2 (64 output columns) unless that leaves most of the chip idle;
+// `blocks64` is the launch's workgroup count at 64 columns
+int gemm_skinny_col_tiles(int blocks64) { return blocks64 >= 128 ? 2 : 1; }
+int gemm_skinny_blocks(int M, int N, int row_tiles, int col_tiles) {
+  return ((N + 32 * col_tiles - 1) / (32 * col_tiles)) * ((M + 32 * row_tiles - 1) / (32 * row_tiles));
 }
 
 // 8 consecutive elements of one row; zero outside [0,row_lim) x [0,col_lim), ragged tail cleared
@@ -50,12 +50,13 @@ __device__ __forceinline__ u32x4 load8(const uint16_t *__restrict__ base, int64_
   return v;
 }
 
-// one 64-wide k-step of a wave, as fetched from memory: BM x 64 of A and 64 x 64 of B in 16-byte
-// chunks, eight lanes per 128-byte row, so every load instruction covers whole cache lines
-template <int TI>
+// one 64-wide k-step of a wave, as fetched from memory: BM x 64 of A and the W tile (BN x 64 forward,
+// 64 x BN backward-data) in 16-byte chunks of whole rows, so every load instruction covers whole
+// 128-byte (64-byte for a 32-wide backward tile) row segments
+template <int TI, int TJ>
 struct SkStep {
   u32x4 a[4 * TI];
-  u32x4 b[8];
+  u32x4 b[4 * TJ];
 };
 
 // NW waves per workgroup split K: 8 when the private tiles of 8 waves fit in LDS (up to 64 rows), else 4
@@ -64,71 +65,88 @@ struct SkWaves {
   static constexpr int value = TI <= 2 ? 8 : 4;
 };
 
-template <int FORM, int TI>
-__global__ __launch_bounds__(64 * SkWaves<TI>::value) void k_gemm_skinny(const GemmProb *__restrict__ probs, int n) {
-  constexpr int NW = SkWaves<TI>::value;
-  constexpr int BM = 32 * TI;
-  constexpr int RED_FLOATS = (NW / 2) * BM * SK_BN;
-  // row stride of the B tile: the conflict-free stride of the transposing read when the waves' tiles
-  // still fit in the 160 KB of LDS, else the compact one
-  constexpr int SB = (FORM == FORM_DX && NW * (BM * SK_ST + 64 * SK_ST_TR) * 2 <= 160 * 1024) ? SK_ST_TR : SK_ST;
-  constexpr int WAVE_ELEMS = BM * SK_ST + 64 * SB;         // a wave's private A and B tiles
-  constexpr int LDS_BYTES = RED_FLOATS * 4 > NW * WAVE_ELEMS * 2 ? RED_FLOATS * 4 : NW * WAVE_ELEMS * 2;
-  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[LDS_BYTES];
-  float *red = (float *)lds_raw;           // after the k-loop: two BM x 64 fp32 buffers
+// LDS bytes of the few-row body
+template <int FORM, int TI, int TJ>
+struct SkLds {
+  static constexpr int NW = SkWaves<TI>::value;
+  static constexpr int BM = 32 * TI, BN = 32 * TJ;
+  static constexpr int RED_FLOATS = (NW / 2) * BM * BN;
+  // W tile: forward [BN][64 + 8]; backward-data [64][BN + pad], read with the transposing read.  A
+  // 16-lane block of that read touches 32 bytes in each of four consecutive rows, so the row stride
+  // should put those rows on disjoint banks: 96 bytes for 32-wide rows, 192 for 64-wide ones (the
+  // latter only when the waves' tiles still fit in the 160 KB of LDS, else 144)
+  static constexpr int SB = FORM == FORM_FWD ? SK_ST
+                            : BN == 32       ? BN + 16
+                                             : (NW * (BM * SK_ST + SK_KS * (BN + 32)) * 2 <= 160 * 1024 ? BN + 32 : BN + 8);
+  static constexpr int B_ROWS = FORM == FORM_FWD ? BN : SK_KS;
+  static constexpr int WAVE_ELEMS = BM * SK_ST + B_ROWS * SB;     // a wave's private A and B tiles
+  static constexpr int BYTES = RED_FLOATS * 4 > NW * WAVE_ELEMS * 2 ? RED_FLOATS * 4 : NW * WAVE_ELEMS * 2;
+};
 
-  const int pi = find_prob(probs, n, blockIdx.x);
-  const GemmProb p = probs[pi];
+// `local`: index of this workgroup inside the record (column block major, row blocks neighbours)
+template <int FORM, int TI, int TJ>
+__device__ __forceinline__ void gemm_skinny_body(const GemmProb &p, int local, unsigned char *lds_raw, const ExtPtrs &ext) {
+  typedef SkLds<FORM, TI, TJ> L;
+  constexpr int NW = L::NW, BM = L::BM, BN = L::BN, SB = L::SB, WAVE_ELEMS = L::WAVE_ELEMS;
+  float *red = (float *)lds_raw;           // after the k-loop: NW/2 BM x BN fp32 buffers
+  void *Cout = result_ptr(p, ext);
+
   const int m_blocks = (p.M + BM - 1) / BM;                      // row blocks of one column block are neighbours
-  const int n0 = ((blockIdx.x - p.blk_begin) / m_blocks) * SK_BN;
-  const int m0 = ((blockIdx.x - p.blk_begin) % m_blocks) * BM;
+  const int n0 = (local / m_blocks) * BN;
+  const int m0 = (local % m_blocks) * BM;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 31, h = lane >> 5;
   const uint16_t *A = (const uint16_t *)p.A;
   const uint16_t *B = (const uint16_t *)p.B;
   uint16_t *lds_a = (uint16_t *)lds_raw + wave * WAVE_ELEMS;   // [BM][SK_ST]
-  uint16_t *lds_b = lds_a + BM * SK_ST;                        // [64][SK_ST]
+  uint16_t *lds_b = lds_a + BM * SK_ST;                        // [B_ROWS][SB]
 
-  f32x16 acc[TI][2];
+  f32x16 acc[TI][TJ];
 #pragma unroll
   for (int i = 0; i < TI; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < TJ; ++j)
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.0f;
 
-  const int steps = (p.K + 63) / 64, per = (steps + NW - 1) / NW;
+  const int steps = (p.K + SK_KS - 1) / SK_KS, per = (steps + NW - 1) / NW;
   const int s_lo = wave * per, s_hi = min(steps, s_lo + per);
-  const int crow = lane >> 3, ccol = (lane & 7) * 8;     // this lane's chunk inside an 8-row slab
+  const int crow = lane >> 3, ccol = (lane & 7) * 8;     // this lane's chunk inside an 8-row slab of 64-wide rows
+  // backward-data W tile rows are BN wide: BN / 8 chunks per row, 512 / BN rows per load instruction
+  constexpr int DX_CPR = BN / 8, DX_RPI = 64 / DX_CPR;
+  const int drow = lane / DX_CPR, dcol = (lane % DX_CPR) * 8;
 
-  auto load = [&](SkStep<TI> &f, int s) {
-    const int k0 = 64 * s;
+  auto load = [&](SkStep<TI, TJ> &f, int s) {
+    const int k0 = SK_KS * s;
 #pragma unroll
     for (int q = 0; q < 4 * TI; ++q) f.a[q] = load8(A, p.lda, m0 + 8 * q + crow, p.M, k0 + ccol, p.K);
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      if (FORM == FORM_FWD) f.b[q] = load8(B, p.ldb, n0 + 8 * q + crow, p.N, k0 + ccol, p.K);   // W[n][k]
-      else f.b[q] = load8(B, p.ldb, k0 + 8 * q + crow, p.K, n0 + ccol, p.N);                    // W[k][n]
+    for (int q = 0; q < 4 * TJ; ++q) {
+      if (FORM == FORM_FWD) f.b[q] = load8(B, p.ldb, n0 + 8 * q + crow, p.N, k0 + ccol, p.K);          // W[n][k]
+      else f.b[q] = load8(B, p.ldb, k0 + DX_RPI * q + drow, p.K, n0 + dcol, p.N);                      // W[k][n]
     }
   };
-  auto stage = [&](const SkStep<TI> &f) {
+  auto stage = [&](const SkStep<TI, TJ> &f) {
 #pragma unroll
     for (int q = 0; q < 4 * TI; ++q) *(u32x4 *)(lds_a + (8 * q + crow) * SK_ST + ccol) = f.a[q];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) *(u32x4 *)(lds_b + (8 * q + crow) * SB + ccol) = f.b[q];
+    for (int q = 0; q < 4 * TJ; ++q) {
+      if (FORM == FORM_FWD) *(u32x4 *)(lds_b + (8 * q + crow) * SB + ccol) = f.b[q];
+      else *(u32x4 *)(lds_b + (DX_RPI * q + drow) * SB + dcol) = f.b[q];
+    }
   };
   auto multiply = [&]() {
     const int blk = lane >> 4, q16 = lane & 15;
     typedef __attribute__((address_space(3))) s16x4 lds_v4;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {            // four 16-wide chunks of the step
-      bf16x8 a[TI], b[2];
+      bf16x8 a[TI], b[TJ];
 #pragma unroll
       for (int i = 0; i < TI; ++i) a[i] = *(const bf16x8 *)(lds_a + (32 * i + r) * SK_ST + 16 * c + 8 * h);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
+      for (int j = 0; j < TJ; ++j) {
         if (FORM == FORM_FWD) {
-          b[j] = *(const bf16x8 *)(lds_b + (32 * j + r) * SK_ST + 16 * c + 8 * h);
+          b[j] = *(const bf16x8 *)(lds_b + (32 * j + r) * SB + 16 * c + 8 * h);
         } else {
           // transposing read: in each block of 16 lanes, lane q addresses row (q / 4), columns 4 (q % 4)..+3
           const uint16_t *ptr = lds_b + (16 * c + 8 * (blk >> 1) + (q16 >> 2)) * SB + 32 * j + 16 * (blk & 1) + 4 * (q16 & 3);
@@ -140,13 +158,14 @@ __global__ __launch_bounds__(64 * SkWaves<TI>::value) void k_gemm_skinny(const G
 #pragma unroll
       for (int i = 0; i < TI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
   };
 
   // NS register sets rotate: while one step is multiplied, the next NS-1 are on their way from memory
-  constexpr int NS = NW == 8 ? 2 : 3;   // bounded by the register file: 256 VGPRs per lane at 8 waves
-  SkStep<TI> f[NS];
+  // (bounded by the register file: 256 VGPRs per lane at 8 waves)
+  constexpr int NS = NW == 8 ? (TI + TJ <= 3 ? 3 : 2) : 3;
+  SkStep<TI, TJ> f[NS];
 #pragma unroll
   for (int u = 0; u < NS; ++u)
     if (s_lo + u < s_hi) load(f[u], s_lo + u);
@@ -165,17 +184,17 @@ __global__ __launch_bounds__(64 * SkWaves<TI>::value) void k_gemm_skinny(const G
 #pragma unroll
     for (int i = 0; i < TI; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < TJ; ++j)
 #pragma unroll
-        for (int q = 0; q < 16; ++q) buf[(32 * i + 8 * (q >> 2) + 4 * h + (q & 3)) * SK_BN + 32 * j + r] = acc[i][j][q];
+        for (int q = 0; q < 16; ++q) buf[(32 * i + 8 * (q >> 2) + 4 * h + (q & 3)) * BN + 32 * j + r] = acc[i][j][q];
   };
   auto add = [&](const float *buf) {
 #pragma unroll
     for (int i = 0; i < TI; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < TJ; ++j)
 #pragma unroll
-        for (int q = 0; q < 16; ++q) acc[i][j][q] += buf[(32 * i + 8 * (q >> 2) + 4 * h + (q & 3)) * SK_BN + 32 * j + r];
+        for (int q = 0; q < 16; ++q) acc[i][j][q] += buf[(32 * i + 8 * (q >> 2) + 4 * h + (q & 3)) * BN + 32 * j + r];
   };
   // binary tree with a fixed shape: in every round the upper half of the live waves hands its tile
   // to the lower half; the final sum ends up in buffer 0
@@ -183,25 +202,27 @@ __global__ __launch_bounds__(64 * SkWaves<TI>::value) void k_gemm_skinny(const G
 #pragma unroll
   for (int live = NW; live > 1; live >>= 1) {
     const int half = live >> 1;
-    if (wave >= half && wave < live) put(red + (wave - half) * BM * SK_BN);
+    if (wave >= half && wave < live) put(red + (wave - half) * BM * BN);
     __syncthreads();
-    if (wave < half) add(red + wave * BM * SK_BN);
+    if (wave < half) add(red + wave * BM * BN);
     __syncthreads();
   }
   if (wave == 0) put(red);
   __syncthreads();
   const float *r1 = red;
+  if (Cout == nullptr) return;     // the caller does not want this result (all barriers are behind us)
 
-  // ---- epilogue, all waves: thread t owns 8 consecutive columns of rows t/8, t/8 + 8 NW, ...
-  const int cg = (threadIdx.x & 7) * 8;
-  for (int lr = threadIdx.x >> 3; lr < BM; lr += 8 * NW) {
+  // ---- epilogue, all waves: thread t owns 8 consecutive columns; BN / 8 threads per row
+  constexpr int TPR = BN / 8, ROWS_PER_PASS = 64 * NW / TPR;
+  const int cg = (threadIdx.x % TPR) * 8;
+  for (int lr = threadIdx.x / TPR; lr < BM; lr += ROWS_PER_PASS) {
     const int row = m0 + lr;
     if (row >= p.M) break;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const int col = n0 + cg + e;
       if (col >= p.N) break;
-      float v = r1[lr * SK_BN + cg + e];
+      float v = r1[lr * BN + cg + e];
       const int64_t ci = (int64_t)row * p.ldc + col;
       if (FORM == FORM_FWD) {
         if (p.bias) v += p.bias[col];
@@ -212,20 +233,71 @@ __global__ __launch_bounds__(64 * SkWaves<TI>::value) void k_gemm_skinny(const G
         if (p.res) v += load_as_f32(p.res, p.res_dtype, (int64_t)row * p.ldres + col);
         if (p.act != ACT_NONE) v *= act_grad(load_as_f32(p.aux, p.aux_dtype, (int64_t)row * p.ldaux + col), p.act);
       }
-      store_from_f32(p.C, p.c_dtype, ci, v);
+      store_from_f32(Cout, p.c_dtype, ci, v);
     }
   }
 }
 
-template <int FORM>
-static void launch_rows(const GemmProb *probs, int n, int blocks, int row_tiles, hipStream_t s) {
-  if (row_tiles == 1) hipLaunchKernelGGL((k_gemm_skinny<FORM, 1>), dim3(blocks), dim3(64 * SkWaves<1>::value), 0, s, probs, n);
-  else hipLaunchKernelGGL((k_gemm_skinny<FORM, 2>), dim3(blocks), dim3(64 * SkWaves<2>::value), 0, s, probs, n);
+template <int FORM, int TI, int TJ>
+__global__ __launch_bounds__(64 * SkWaves<TI>::value) void k_gemm_skinny(const GemmProb *__restrict__ probs, int n, ExtPtrs ext) {
+  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[SkLds<FORM, TI, TJ>::BYTES];
+  const int pi = find_prob(probs, n, blockIdx.x);
+  const GemmProb p = probs[pi];
+  gemm_skinny_body<FORM, TI, TJ>(p, blockIdx.x - p.blk_begin, lds_raw, ext);
 }
-void launch_gemm_skinny(const GemmProb *probs, int n, int total_blocks, int form, int row_tiles, hipStream_t s) {
+
+// backward of one level in one launch: records with form DX run the few-row body, records with
+// form DW the 128 x 128 tile body, two teams per workgroup on tiles 2 * local and 2 * local + 1
+constexpr int BWD_DW_TILE = 128;
+template <int TI, int TJ>
+__global__ __launch_bounds__(512) void k_gemm_bwd_merged(const GemmProb *__restrict__ probs, int n, int accumulate_dw,
+                                                         ExtPtrs ext) {
+  static_assert(SkWaves<TI>::value == 8, "the merged launch uses 512-thread workgroups");
+  typedef TileLds<FORM_DW, BWD_DW_TILE, BWD_DW_TILE> DwLds;
+  typedef SkLds<FORM_DX, TI, TJ> DxLds;
+  constexpr int BYTES = DxLds::BYTES > 4 * DwLds::ELEMS ? DxLds::BYTES : 4 * DwLds::ELEMS;
+  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[BYTES];
+  const int pi = find_prob(probs, n, blockIdx.x);
+  const GemmProb p = probs[pi];
+  const int local = blockIdx.x - p.blk_begin;
+  if (p.form == FORM_DX) {
+    gemm_skinny_body<FORM_DX, TI, TJ>(p, local, lds_raw, ext);
+  } else {
+    const int team = threadIdx.x >> 8;
+    // few rows to contract over: two k-steps in flight are enough and keep the kernel free of spills
+    gemm_tile_body<FORM_DW, BWD_DW_TILE, BWD_DW_TILE, false, 2>(p, 2 * local + team, threadIdx.x & 255,
+                                                             (uint16_t *)lds_raw + team * DwLds::ELEMS, accumulate_dw, ext);
+  }
+}
+int gemm_bwd_merged_dw_tile() { return BWD_DW_TILE; }
+// workgroups of one backward-weight record in the merged launch
+int gemm_bwd_merged_dw_blocks(int M, int N) {
+  const int tiles = cdiv(M, BWD_DW_TILE) * cdiv(N, BWD_DW_TILE);
+  return (tiles + 1) / 2;
+}
+
+template <int FORM>
+static void launch_rows(const GemmProb *probs, int n, int blocks, int row_tiles, int col_tiles, const ExtPtrs &ext, hipStream_t s) {
+  const dim3 g(blocks), b(512);
+  if (row_tiles == 1 && col_tiles == 1) hipLaunchKernelGGL((k_gemm_skinny<FORM, 1, 1>), g, b, 0, s, probs, n, ext);
+  else if (row_tiles == 1) hipLaunchKernelGGL((k_gemm_skinny<FORM, 1, 2>), g, b, 0, s, probs, n, ext);
+  else if (col_tiles == 1) hipLaunchKernelGGL((k_gemm_skinny<FORM, 2, 1>), g, b, 0, s, probs, n, ext);
+  else hipLaunchKernelGGL((k_gemm_skinny<FORM, 2, 2>), g, b, 0, s, probs, n, ext);
+}
+void launch_gemm_skinny(const GemmProb *probs, int n, int total_blocks, int form, int row_tiles, int col_tiles,
+                        const ExtPtrs &ext, hipStream_t s) {
   if (total_blocks <= 0) return;
-  if (form == FORM_FWD) launch_rows<FORM_FWD>(probs, n, total_blocks, row_tiles, s);
-  else launch_rows<FORM_DX>(probs, n, total_blocks, row_tiles, s);
+  if (form == FORM_FWD) launch_rows<FORM_FWD>(probs, n, total_blocks, row_tiles, col_tiles, ext, s);
+  else launch_rows<FORM_DX>(probs, n, total_blocks, row_tiles, col_tiles, ext, s);
+}
+void launch_gemm_bwd_merged(const GemmProb *probs, int n, int total_blocks, int row_tiles, int col_tiles, int accumulate_dw,
+                            const ExtPtrs &ext, hipStream_t s) {
+  if (total_blocks <= 0) return;
+  const dim3 g(total_blocks), b(512);
+  if (row_tiles == 1 && col_tiles == 1) hipLaunchKernelGGL((k_gemm_bwd_merged<1, 1>), g, b, 0, s, probs, n, accumulate_dw, ext);
+  else if (row_tiles == 1) hipLaunchKernelGGL((k_gemm_bwd_merged<1, 2>), g, b, 0, s, probs, n, accumulate_dw, ext);
+  else if (col_tiles == 1) hipLaunchKernelGGL((k_gemm_bwd_merged<2, 1>), g, b, 0, s, probs, n, accumulate_dw, ext);
+  else hipLaunchKernelGGL((k_gemm_bwd_merged<2, 2>), g, b, 0, s, probs, n, accumulate_dw, ext);
 }
 
 }  // namespace gpp

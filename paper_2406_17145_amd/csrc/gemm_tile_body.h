@@ -1,0 +1,335 @@
+// Device-side body of the tiled bf16 MFMA GEMM (v_mfma_f32_32x32x16_bf16, fp32
+// accumulation, LDS-staged tiles, register ring of k-steps in flight).  It is a
+// function of (record, tile index, thread index in a 256-thread team, LDS block)
+// so that one kernel can run it stand-alone and another can run two teams side
+// by side in a 512-thread workgroup next to other roles.
+//
+// Three forms share the body.  What differs is which dimension of an operand is
+// contiguous in memory:
+//   FWD  C[m,n] = sum_k X[m,k] W[n,k]      A k-contiguous,  B k-contiguous
+//   DX   C[m,k] = sum_n dZ[m,n] W[n,k]     A k-contiguous,  B row = contraction index
+//   DW   C[n,k] += sum_m dZ[m,n] X[m,k]    A and B: row = contraction index
+// Operands whose rows run along the contraction index are stored in LDS as they
+// are in memory and fetched with the transposing LDS read (ds_read_b64_tr_b16),
+// which hands each lane four consecutive contraction steps of its own
+// row/column, exactly what the MFMA operand layout wants.
+#pragma once
+#include "device_utils.h"
+
+namespace gpp {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr int BK = 32;        // contraction elements per k-step
+constexpr int PAD = 8;        // LDS row padding (elements) of k-contiguous tiles: 80-byte rows, conflict-free b128 reads
+constexpr int PAD_TR = 32;    // padding of contraction-row tiles: the four rows a 16-lane block of the transposing
+                              // read touches then start 16 banks apart (measured: halves LDS bank-conflict cycles)
+
+__host__ __device__ constexpr int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+// the caller's buffer when the record's result goes straight to a per-call pointer
+__device__ __forceinline__ void *result_ptr(const GemmProb &p, const ExtPtrs &ext) {
+  return p.c_ext > 0 ? ext.p[p.c_ext - 1] : p.C;
+}
+
+// ---- global -> register tile fetch -------------------------------------------
+// A tile is ROWS x COLS elements, COLS contiguous in memory; each thread of the
+// 256-thread team owns 16-byte chunks (8 elements).  Out-of-range rows / columns read as zero.
+template <int ROWS, int COLS>
+struct TileRegs {
+  static constexpr int CHUNKS = ROWS * COLS / 8;
+  static constexpr int PER_THREAD = (CHUNKS + 255) / 256;
+  u32x4 v[PER_THREAD];
+};
+
+template <int ROWS, int COLS>
+__device__ __forceinline__ void tile_fetch(TileRegs<ROWS, COLS> &t, const uint16_t *__restrict__ base, int64_t ld,
+                                           int row0, int col0, int row_lim, int col_lim, int tid) {
+  constexpr int CPR = COLS / 8;  // chunks per row
+#pragma unroll
+  for (int q = 0; q < TileRegs<ROWS, COLS>::PER_THREAD; ++q) {
+    const int c = tid + 256 * q;
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (TileRegs<ROWS, COLS>::CHUNKS % 256 == 0 || c < TileRegs<ROWS, COLS>::CHUNKS) {
+      const int r = row0 + c / CPR, cc = col0 + (c % CPR) * 8;
+      if (r < row_lim && cc < col_lim) {
+        v = *(const u32x4 *)(base + (int64_t)r * ld + cc);
+        if (cc + 8 > col_lim) {  // ragged tail: clear the elements past the limit
+          const int keep = col_lim - cc;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            if (2 * e >= keep) v[e] = 0u;
+            else if (2 * e + 1 >= keep) v[e] &= 0xffffu;
+          }
+        }
+      }
+    }
+    t.v[q] = v;
+  }
+}
+
+template <int ROWS, int COLS>
+__device__ __forceinline__ void tile_store_lds(const TileRegs<ROWS, COLS> &t, uint16_t *lds, int tid) {
+  constexpr int CPR = COLS / 8;
+  constexpr int STRIDE = COLS + (COLS == BK ? PAD : PAD_TR);
+#pragma unroll
+  for (int q = 0; q < TileRegs<ROWS, COLS>::PER_THREAD; ++q) {
+    const int c = tid + 256 * q;
+    if (TileRegs<ROWS, COLS>::CHUNKS % 256 == 0 || c < TileRegs<ROWS, COLS>::CHUNKS)
+      *(u32x4 *)(lds + (c / CPR) * STRIDE + (c % CPR) * 8) = t.v[q];
+  }
+}
+
+// ---- LDS -> MFMA operand ---------------------------------------------------------
+// k-contiguous tile [rows][BK + PAD]: lane l takes row (l % 32), 8 k-values at 8 * (l / 32)
+__device__ __forceinline__ bf16x8 frag_kmajor(const uint16_t *lds, int row0, int k0) {
+  const int l = threadIdx.x & 63;
+  return *(const bf16x8 *)(lds + (row0 + (l & 31)) * (BK + PAD) + k0 + 8 * (l >> 5));
+}
+// contraction-row tile [BK][cols + PAD_TR]: transposing read.  In each block of 16 lanes, lane q
+// addresses row (q / 4) at columns 4 * (q % 4) .. +3 and receives rows 0..3 of column q.
+template <int COLS>
+__device__ __forceinline__ bf16x8 frag_tr(const uint16_t *lds, int col0, int k0) {
+  const int l = threadIdx.x & 63;
+  const int blk = l >> 4, q = l & 15;
+  const uint16_t *p = lds + (k0 + 8 * (blk >> 1) + (q >> 2)) * (COLS + PAD_TR) + col0 + 16 * (blk & 1) + 4 * (q & 3);
+  typedef __attribute__((address_space(3))) s16x4 lds_v4;
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)p);
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(p + 4 * (COLS + PAD_TR)));
+  s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// Split-K partial sums cross workgroups (and XCDs, whose L2 caches are not coherent with each other
+// inside a kernel).  They are written and read with device-scope relaxed atomics, which go through
+// to memory instead of staying in the writer's L2, so no cache-wide write-back or invalidate is
+// needed: ordering comes from waiting for the stores' acknowledgements before the ticket is taken.
+__device__ __forceinline__ void put_partial(float *p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float get_partial(const float *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// LDS elements (uint16) one 256-thread team needs: both operands, double buffered
+template <int FORM, int BM, int BN>
+struct TileLds {
+  static constexpr bool A_TR = FORM == FORM_DW;
+  static constexpr bool B_TR = FORM != FORM_FWD;
+  static constexpr int A_ELEMS = A_TR ? BK * (BM + PAD_TR) : BM * (BK + PAD);
+  static constexpr int B_ELEMS = B_TR ? BK * (BN + PAD_TR) : BN * (BK + PAD);
+  static constexpr int ELEMS = 2 * (A_ELEMS + B_ELEMS);
+};
+
+// ---- the body -----------------------------------------------------------------------
+// `local`  index of this team's unit of work inside the record: tile * split_k + split
+// `tid`    thread index inside the 256-thread team (0..255)
+// `lds`    TileLds<FORM,BM,BN>::ELEMS elements, private to the team
+// Every team of a workgroup must call with records of the same K range: the body synchronises with
+// workgroup barriers.  A `local` beyond the record's tiles computes on zeros and stores nothing.
+// SPLIT = false ignores the record's split_k (taken as 1).  RING = k-steps kept in flight in
+// registers (even; 0 picks the default for the tile size).
+template <int FORM, int BM, int BN, bool SPLIT, int RING = 0>
+__device__ __forceinline__ void gemm_tile_body(const GemmProb &p, int local, int tid, uint16_t *lds, int accumulate_dw,
+                                               const ExtPtrs &ext) {
+  constexpr bool A_TR = TileLds<FORM, BM, BN>::A_TR;     // A rows run along the contraction index
+  constexpr bool B_TR = TileLds<FORM, BM, BN>::B_TR;
+  constexpr int WM = BM / 2, WN = BN / 2;                 // 2 x 2 waves
+  constexpr int TI = WM / 32, TJ = WN / 32;               // 32x32 MFMA tiles per wave
+  constexpr int A_ELEMS = TileLds<FORM, BM, BN>::A_ELEMS;
+  constexpr int B_ELEMS = TileLds<FORM, BM, BN>::B_ELEMS;
+  uint16_t *lds_a[2] = {lds, lds + A_ELEMS};
+  uint16_t *lds_b[2] = {lds + 2 * A_ELEMS, lds + 2 * A_ELEMS + B_ELEMS};
+
+  // split-K: `split` teams with consecutive ids share one output tile, each sums a slice of K
+  const int S = SPLIT ? p.split_k : 1, split = local % S;
+  const int tile = local / S;
+  const int kslice = cdiv(cdiv(p.K, BK), S) * BK;
+  const int k_begin = split * kslice, k_end = min(p.K, k_begin + kslice);
+  const int tiles_m = cdiv(p.M, BM);
+  const int m0 = (tile % tiles_m) * BM, n0 = (tile / tiles_m) * BN;   // consecutive tiles share the B panel
+  const int wave = tid >> 6, lane = tid & 63;
+  const int wi0 = (wave >> 1) * WM, wj0 = (wave & 1) * WN;
+  const uint16_t *A = (const uint16_t *)p.A;
+  const uint16_t *B = (const uint16_t *)p.B;
+  void *Cout = FORM == FORM_DW ? p.C : result_ptr(p, ext);
+
+  f32x16 acc[TI][TJ];
+#pragma unroll
+  for (int i = 0; i < TI; ++i)
+#pragma unroll
+    for (int j = 0; j < TJ; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  // backward-weight with accumulation: request the old gradient tile now, so that its latency is
+  // hidden behind the operand fetch and the MFMAs instead of sitting between them and the store
+  const bool c_prefetch = FORM == FORM_DW && accumulate_dw && S == 1;
+  f32x16 c_old[TI][TJ];
+  if (FORM == FORM_DW && c_prefetch) {
+#pragma unroll
+    for (int i = 0; i < TI; ++i)
+#pragma unroll
+      for (int j = 0; j < TJ; ++j) {
+        const int col = n0 + wj0 + 32 * j + (lane & 31);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = m0 + wi0 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          c_old[i][j][r] = (row < p.M && col < p.N) ? ((const float *)p.C)[(int64_t)row * p.ldc + col] : 0.0f;
+        }
+      }
+  }
+
+  typedef TileRegs<A_TR ? BK : BM, A_TR ? BM : BK> RegsA;
+  typedef TileRegs<B_TR ? BK : BN, B_TR ? BN : BK> RegsB;
+  // NS k-steps are kept in flight in registers: the tile consumed at step kt was requested NS-1
+  // steps earlier, so the k-loop runs at the rate of its own work, not of the memory latency
+  constexpr int NS = RING > 0 ? RING : (BM * BN >= 128 * 128 ? 4 : 8);
+  static_assert(NS % 2 == 0, "the LDS double buffer alternates with the ring slot");
+  RegsA ra[NS];
+  RegsB rb[NS];
+  auto fetch = [&](RegsA &xa, RegsB &xb, int k0) {
+    if (A_TR) tile_fetch<A_TR ? BK : BM, A_TR ? BM : BK>(xa, A, p.lda, k0, m0, k_end, p.M, tid);
+    else      tile_fetch<A_TR ? BK : BM, A_TR ? BM : BK>(xa, A, p.lda, m0, k0, p.M, k_end, tid);
+    if (B_TR) tile_fetch<B_TR ? BK : BN, B_TR ? BN : BK>(xb, B, p.ldb, k0, n0, k_end, p.N, tid);
+    else      tile_fetch<B_TR ? BK : BN, B_TR ? BN : BK>(xb, B, p.ldb, n0, k0, p.N, k_end, tid);
+  };
+  // backward-weight tiles of the first column block also sum the rows of dZ^T they stream: the bias
+  // gradient db[n] = sum_m dZ[m,n] comes out of the same launch
+  constexpr int BGROUPS = 256 / BM, BROWS = BK / BGROUPS;
+  const bool do_bias = FORM == FORM_DW && p.bias != nullptr && n0 == 0 && m0 < p.M;
+  float bsum = 0.0f;
+  const int nk = max(0, cdiv(k_end - k_begin, BK));
+#pragma unroll
+  for (int u = 0; u < NS; ++u)
+    if (u < nk || u == 0) fetch(ra[u], rb[u], k_begin + u * BK);
+  tile_store_lds<A_TR ? BK : BM, A_TR ? BM : BK>(ra[0], lds_a[0], tid);
+  tile_store_lds<B_TR ? BK : BN, B_TR ? BN : BK>(rb[0], lds_b[0], tid);
+  __syncthreads();
+  for (int kt0 = 0; kt0 < nk; kt0 += NS) {
+#pragma unroll
+    for (int u = 0; u < NS; ++u) {
+      const int kt = kt0 + u;
+      if (kt >= nk) break;
+      const int cur = u & 1;   // NS is even, so the LDS buffer of step kt is kt & 1 = u & 1
+      // slot u held tile kt, already copied to LDS: reuse it for tile kt + NS
+      if (kt + NS < nk) fetch(ra[u], rb[u], k_begin + (kt + NS) * BK);
+#pragma unroll
+      for (int kc = 0; kc < BK; kc += 16) {
+        bf16x8 a[TI], b[TJ];
+#pragma unroll
+        for (int i = 0; i < TI; ++i)
+          a[i] = A_TR ? frag_tr<BM>(lds_a[cur], wi0 + 32 * i, kc) : frag_kmajor(lds_a[cur], wi0 + 32 * i, kc);
+#pragma unroll
+        for (int j = 0; j < TJ; ++j)
+          b[j] = B_TR ? frag_tr<BN>(lds_b[cur], wj0 + 32 * j, kc) : frag_kmajor(lds_b[cur], wj0 + 32 * j, kc);
+#pragma unroll
+        for (int i = 0; i < TI; ++i)
+#pragma unroll
+          for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+      }
+      if (FORM == FORM_DW && do_bias) {
+        const uint16_t *la = lds_a[cur] + (tid / BM) * BROWS * (BM + PAD_TR) + (tid % BM);
+#pragma unroll
+        for (int rr = 0; rr < BROWS; ++rr) bsum += bf16_bits_to_f32(la[rr * (BM + PAD_TR)]);
+      }
+      if (kt + 1 < nk) {
+        tile_store_lds<A_TR ? BK : BM, A_TR ? BM : BK>(ra[(u + 1) % NS], lds_a[cur ^ 1], tid);
+        tile_store_lds<B_TR ? BK : BN, B_TR ? BN : BK>(rb[(u + 1) % NS], lds_b[cur ^ 1], tid);
+      }
+      __syncthreads();
+    }
+  }
+
+  float bias_total = 0.0f;            // threads < BM: this split's column sum of the dZ^T tile
+  if (FORM == FORM_DW) {              // fold the row groups in a fixed order (the k-loop ended with a barrier)
+    float *red = (float *)lds_b[0];
+    if (do_bias) red[tid] = bsum;
+    __syncthreads();                  // unconditional: every team of the workgroup passes here
+    if (do_bias && tid < BM) {
+#pragma unroll
+      for (int g = 0; g < BGROUPS; ++g) bias_total += red[g * BM + tid];
+    }
+  }
+
+  if (SPLIT && S > 1) {
+    // Deterministic split-K: every split stores its fp32 partial tile; the split that arrives last
+    // (arrival counter, no waiting) adds all partials in split order and runs the epilogue.
+    constexpr int PSTRIDE = BM * BN + BM;
+    float *mine = p.partial + ((int64_t)tile * S + split) * PSTRIDE;
+#pragma unroll
+    for (int i = 0; i < TI; ++i)
+#pragma unroll
+      for (int j = 0; j < TJ; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) put_partial(mine + ((i * TJ + j) * 16 + r) * 256 + tid, acc[i][j][r]);
+    if (FORM == FORM_DW && tid < BM) put_partial(mine + BM * BN + tid, bias_total);
+    // the partial stores go through to memory; once this wave's stores have been acknowledged and
+    // the workgroup has met, one thread takes a ticket
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    int *ticket = (int *)lds_a[0];
+    if (tid == 0) *ticket = __hip_atomic_fetch_add(&p.counters[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (*ticket != S - 1) return;
+    if (tid == 0) __hip_atomic_store(&p.counters[tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
+    const float *all = p.partial + (int64_t)tile * S * PSTRIDE;
+#pragma unroll
+    for (int i = 0; i < TI; ++i)
+#pragma unroll
+      for (int j = 0; j < TJ; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float v = 0.0f;
+          for (int q = 0; q < S; ++q) v += get_partial(all + (int64_t)q * PSTRIDE + ((i * TJ + j) * 16 + r) * 256 + tid);
+          acc[i][j][r] = v;
+        }
+    if (FORM == FORM_DW && tid < BM) {
+      bias_total = 0.0f;
+      for (int q = 0; q < S; ++q) bias_total += get_partial(all + (int64_t)q * PSTRIDE + BM * BN + tid);
+    }
+  }
+  if (FORM == FORM_DW && do_bias && tid < BM && m0 + tid < p.M) {
+    float *db = const_cast<float *>(p.bias) + m0 + tid;
+    *db = accumulate_dw ? *db + bias_total : bias_total;
+  }
+  if (Cout == nullptr) return;   // the caller does not want this result (all barriers are behind us)
+
+  // ---- epilogue: accumulator register r of a 32x32 tile holds row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
+#pragma unroll
+  for (int i = 0; i < TI; ++i)
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) {
+      const int col = n0 + wj0 + 32 * j + (lane & 31);
+      if (col >= p.N) continue;
+      float bias = 0.0f;
+      if (FORM == FORM_FWD && p.bias) bias = p.bias[col];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wi0 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (row >= p.M) continue;
+        float v = acc[i][j][r];
+        const int64_t ci = (int64_t)row * p.ldc + col;
+        if (FORM == FORM_FWD) {
+          v += bias;
+          if (p.aux) store_from_f32(p.aux, p.aux_dtype, (int64_t)row * p.ldaux + col, v);
+          v = act_apply(v, p.act);
+          if (p.res) v += load_as_f32(p.res, p.res_dtype, (int64_t)row * p.ldres + col);
+          store_from_f32(Cout, p.c_dtype, ci, v);
+        } else if (FORM == FORM_DX) {
+          if (p.res) v += load_as_f32(p.res, p.res_dtype, (int64_t)row * p.ldres + col);
+          if (p.act != ACT_NONE) v *= act_grad(load_as_f32(p.aux, p.aux_dtype, (int64_t)row * p.ldaux + col), p.act);
+          store_from_f32(Cout, p.c_dtype, ci, v);
+        } else {
+          float *c = (float *)Cout;
+          c[ci] = c_prefetch ? c_old[i][j][r] + v : (accumulate_dw ? c[ci] + v : v);
+        }
+      }
+    }
+}
+
+}  // namespace gpp

@@ -34,6 +34,7 @@ struct GemmProb {
   int32_t split_k;    // workgroups that share one output tile, each summing a slice of K
   float *partial;     // split_k > 1: fp32 partial tiles [tile][split][tile elements + tile rows]
   int32_t *counters;  // split_k > 1: arrival counter per tile (zero between launches)
+  int32_t c_ext;      // > 0: C is entry c_ext - 1 of the launch's per-call pointer block (may be null: result not wanted)
 };
 
 // ---- 2-D copy / convert / accumulate / activation backward --------------
@@ -162,16 +163,24 @@ struct StageFlags {
 // ---- launch entry points (defined next to the kernels) -------------------------
 void launch_gemm_generic(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int in_dtype, hipStream_t s);
 void launch_gemm_mfma(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int form, int tile,
-                      hipStream_t s);
+                      const ExtPtrs &ext, hipStream_t s);
 // tile geometry used by the planner to count workgroups
 int gemm_generic_tiles(int M, int N, int *tiles_n);
 int gemm_mfma_group_tile(int form, int maxM, int maxN);
 int gemm_mfma_tiles_for(int tile, int M, int N, int *tiles_n);
 int gemm_mfma_partial_floats(int tile);
 // few-row (micro-batch <= 256 rows) forward / backward-data kernel
-void launch_gemm_skinny(const GemmProb *probs, int n, int total_blocks, int form, int row_tiles, hipStream_t s);
-int gemm_skinny_blocks(int M, int N, int row_tiles);
+void launch_gemm_skinny(const GemmProb *probs, int n, int total_blocks, int form, int row_tiles, int col_tiles,
+                        const ExtPtrs &ext, hipStream_t s);
+// backward of a level with few rows in one launch: records of form DX (few-row body) first, then
+// records of form DW (tile body, two tiles per workgroup)
+void launch_gemm_bwd_merged(const GemmProb *probs, int n, int total_blocks, int row_tiles, int col_tiles,
+                            int accumulate_dw, const ExtPtrs &ext, hipStream_t s);
+int gemm_bwd_merged_dw_tile();
+int gemm_bwd_merged_dw_blocks(int M, int N);
+int gemm_skinny_blocks(int M, int N, int row_tiles, int col_tiles);
 int gemm_skinny_row_tiles(int M);
+int gemm_skinny_col_tiles(int blocks_at_64_columns);
 int gemm_mfma_pick_split(int tile, int launch_tiles, int rows_in_tile, int K);
 bool gemm_mfma_supported(const GemmProb &p);
 
@@ -210,6 +219,10 @@ void launch_emb_reset(const EmbProb *probs, int n, int max_capacity, int slots, 
 
 void launch_loss_fwd(const LossProb *probs, int n, int total_blocks, hipStream_t s);
 int loss_fwd_blocks(const LossProb &p);
+// every loss of the stage and their sum in one single-workgroup launch (rows x cols summed over the
+// records at most loss_small_limit()); a null `out` skips the launch
+void launch_loss_fwd_small(const LossProb *probs, int n, float *out, hipStream_t s);
+int loss_small_limit();
 void launch_loss_bwd(const LossProb *probs, int n, int total_blocks, hipStream_t s);
 int loss_bwd_blocks(const LossProb &p);
 

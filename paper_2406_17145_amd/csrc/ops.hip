@@ -418,6 +418,56 @@ void launch_loss_fwd(const LossProb *probs, int n, int total_blocks, hipStream_t
   hipLaunchKernelGGL(k_loss_fwd, dim3(total_blocks), dim3(256), 0, s, probs, n);
 }
 
+// Small heads (all of a stage's losses together at most a few tens of thousands of elements): one
+// workgroup computes every loss and their sum, so the forward pass needs one launch, not two.
+// MSE / BCE: a thread per element, strided; cross-entropy: a wave per row.  All sums in a fixed order.
+int loss_small_limit() { return 65536; }
+__global__ __launch_bounds__(256) void k_loss_fwd_small(const LossProb *__restrict__ probs, int n, float *out) {
+  __shared__ float red[4];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  float total = 0.0f;
+  for (int pi = 0; pi < n; ++pi) {
+    const LossProb p = probs[pi];
+    float acc = 0.0f;
+    if (p.kind == 10) {
+      for (int r = w; r < p.rows; r += 4) {
+        const int64_t yo = (int64_t)r * p.ld_y;
+        float m = -INFINITY;
+        for (int c = lane; c < p.cols; c += 64) m = fmaxf(m, load_as_f32(p.y, p.y_dtype, yo + c));
+        m = wave_max(m);
+        float se = 0.0f;
+        for (int c = lane; c < p.cols; c += 64) se += __expf(load_as_f32(p.y, p.y_dtype, yo + c) - m);
+        se = wave_sum(se);
+        const int lab = ((const int32_t *)p.target)[(int64_t)r * p.ld_t];
+        if (lane == 0 && lab >= 0 && lab < p.cols) acc += (m + __logf(se)) - load_as_f32(p.y, p.y_dtype, yo + lab);
+      }
+    } else {
+      const int total_e = p.rows * p.cols;
+      for (int e = threadIdx.x; e < total_e; e += 256) {
+        const int r = e / p.cols, c = e - r * p.cols;
+        const float y = load_as_f32(p.y, p.y_dtype, (int64_t)r * p.ld_y + c);
+        const float t = ((const float *)p.target)[(int64_t)r * p.ld_t + c];
+        if (p.kind == 9) {
+          const float d = y - t;
+          acc += d * d;
+        } else {
+          acc += softplus_f(y) - t * y;
+        }
+      }
+    }
+    acc = wave_sum(acc);
+    __syncthreads();               // red is free again
+    if (lane == 0) red[w] = acc;
+    __syncthreads();
+    total += ((red[0] + red[1]) + (red[2] + red[3])) * p.scale;
+  }
+  if (threadIdx.x == 0) out[0] = total;
+}
+void launch_loss_fwd_small(const LossProb *probs, int n, float *out, hipStream_t s) {
+  if (n <= 0 || !out) return;
+  hipLaunchKernelGGL(k_loss_fwd_small, dim3(1), dim3(256), 0, s, probs, n, out);
+}
+
 int loss_bwd_blocks(const LossProb &p) { return (p.rows + 3) / 4; }
 // one wave per row; LossProb has no prefix field, so block ranges are passed as rows/4 per record in order
 __global__ __launch_bounds__(256) void k_loss_bwd(const LossProb *__restrict__ probs, int n) {

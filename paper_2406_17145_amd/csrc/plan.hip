@@ -536,15 +536,61 @@ struct Emitter {
   void emit_gemms(std::vector<GemmProb> &recs) {
     if (recs.empty()) return;
     // split by kernel and operand dtype; each group is one launch
+    auto on_mfma = [&](const GemmProb &r) { return !(pl.flags & 1) && r.in_dtype == DT_BF16 && gemm_mfma_supported(r); };
+    auto wants_ext = [](const std::vector<GemmProb> &g) {
+      for (auto &r : g)
+        if (r.c_ext > 0) return true;
+      return false;
+    };
+    // few rows, backward: both consumers of a level's dZ (dX and dW) share one launch
+    bool merged_bwd = false;
+    {
+      std::vector<GemmProb> dx, dw;
+      int max_m = 0;
+      for (auto &r : recs)
+        if (on_mfma(r)) {
+          if (r.form == FORM_DX) {
+            dx.push_back(r);
+            max_m = std::max(max_m, r.M);
+          } else if (r.form == FORM_DW) {
+            dw.push_back(r);
+          }
+        }
+      const int row_tiles = dx.empty() ? 0 : gemm_skinny_row_tiles(max_m);
+      if (!dx.empty() && !dw.empty() && row_tiles > 0 && !(pl.flags & 2)) {
+        int blocks = 0, blocks64 = 0;
+        for (auto &r : dx) blocks64 += gemm_skinny_blocks(r.M, r.N, row_tiles, 2);
+        const int col_tiles = gemm_skinny_col_tiles(blocks64);
+        for (auto &r : dx) {
+          r.blk_begin = blocks;
+          r.split_k = 1;
+          blocks += gemm_skinny_blocks(r.M, r.N, row_tiles, col_tiles);
+        }
+        for (auto &r : dw) {
+          r.blk_begin = blocks;
+          r.split_k = 1;
+          r.tiles_n = (r.N + gemm_bwd_merged_dw_tile() - 1) / gemm_bwd_merged_dw_tile();
+          blocks += gemm_bwd_merged_dw_blocks(r.M, r.N);
+        }
+        const bool ext = wants_ext(dx);
+        dx.insert(dx.end(), dw.begin(), dw.end());
+        Step &s = add_step(K_GEMM_BWD_MERGED, push_table(dx), (int)dx.size(), blocks);
+        s.a1 = col_tiles;
+        s.a2 = row_tiles;
+        if (ext) s.ext_kind = EXT_GRAD_INPUTS;
+        merged_bwd = true;
+      }
+    }
     for (int use_mfma = 0; use_mfma < 2; ++use_mfma)
       for (int dt = 0; dt < 2; ++dt)
         for (int form = 0; form < 3; ++form) {
           std::vector<GemmProb> g;
           for (auto &r : recs) {
-            bool m = !(pl.flags & 1) && r.in_dtype == DT_BF16 && gemm_mfma_supported(r);
+            bool m = on_mfma(r);
             if ((int)m == use_mfma && r.in_dtype == dt && (r.form == form || !use_mfma)) g.push_back(r);
           }
           if (!use_mfma && form > 0) continue;  // the generic kernel mixes forms in one launch
+          if (use_mfma && form > 0 && merged_bwd) continue;
           if (g.empty()) continue;
           int blocks = 0, tile = 0, max_m = 0, max_n = 0;
           for (auto &r : g) {
@@ -555,16 +601,19 @@ struct Emitter {
           // few rows: the weight-streaming kernel (forward and backward-data only)
           const int row_tiles = (use_mfma && form != FORM_DW) ? gemm_skinny_row_tiles(max_m) : 0;
           if (row_tiles > 0) {
-            int blocks = 0;
+            int blocks = 0, blocks64 = 0;
+            for (auto &r : g) blocks64 += gemm_skinny_blocks(r.M, r.N, row_tiles, 2);
+            const int col_tiles = gemm_skinny_col_tiles(blocks64);
             for (auto &r : g) {
               r.blk_begin = blocks;
               r.split_k = 1;
-              blocks += gemm_skinny_blocks(r.M, r.N, row_tiles);
+              blocks += gemm_skinny_blocks(r.M, r.N, row_tiles, col_tiles);
             }
             Step &s = add_step(K_GEMM_SKINNY, push_table(g), (int)g.size(), blocks);
-            s.a0 = dt;
+            s.a0 = col_tiles;
             s.a1 = form;
             s.a2 = row_tiles;
+            if (wants_ext(g)) s.ext_kind = EXT_GRAD_INPUTS;
             continue;
           }
           int launch_tiles = 0;
@@ -595,6 +644,7 @@ struct Emitter {
           s.a0 = dt;
           s.a1 = form;
           s.a2 = tile;
+          if (use_mfma && wants_ext(g)) s.ext_kind = EXT_GRAD_INPUTS;
         }
     recs.clear();
   }
@@ -608,6 +658,7 @@ struct Emitter {
 void Emitter::forward() {
   steps = &pl.fwd;
   steps->clear();
+  bool loss_summed = false;
   auto &N = pl.nodes;
 
   // ingest: copy the caller's dense inputs into the (padded) stash buffers
@@ -864,11 +915,18 @@ void Emitter::forward() {
     }
     if (!losses.empty()) {
       int blocks = 0;
+      int64_t elems = 0;
       for (auto &l : losses) {
         l.blk_begin = blocks;
         blocks += loss_fwd_blocks(l);
+        elems += (int64_t)l.rows * l.cols;
       }
-      add_step(K_LOSS_FWD, push_table(losses), (int)losses.size(), blocks);
+      if (losses.size() == pl.loss_ops.size() && elems <= loss_small_limit()) {
+        add_step(K_LOSS_FWD_SMALL, push_table(losses), (int)losses.size(), 1);   // value and sum in one launch
+        loss_summed = true;
+      } else {
+        add_step(K_LOSS_FWD, push_table(losses), (int)losses.size(), blocks);
+      }
     }
   }
 
@@ -892,7 +950,7 @@ void Emitter::forward() {
       recs.push_back(e);
     }
     emit_elt(recs, EXT_OUTPUTS, base);
-    add_step(K_LOSS_SUM, 0, pl.loss_parts, 1);
+    if (!loss_summed) add_step(K_LOSS_SUM, 0, pl.loss_parts, 1);
   }
 }
 
@@ -933,6 +991,17 @@ void Emitter::backward() {
   }
 
   auto mask_source = [&](const Node &p) -> Buf { return p.d.act == GPP_ACT_GELU_ERF ? p.aux : p.val; };
+  // every member of concat `c` is a ReLU layer stored in place whose only consumer is the concat and
+  // whose gradient is a view of the concat's gradient
+  auto concat_relu_members = [&](int c) -> bool {
+    for (int m : N[c].in) {
+      const Node &mm = N[m];
+      if (mm.d.kind != GPP_OP_LINEAR || mm.d.act != GPP_ACT_RELU || mm.users.size() != 1 || mm.val_parent != c ||
+          mm.gout_parent != c || mm.fused_add >= 0 || dz_ready[m])
+        return false;
+    }
+    return true;
+  };
   // a member that shares its consumer's gradient buffer is "written" once the consumer is
   std::function<int(int)> state_of = [&](int i) -> int {
     return N[i].gout_parent >= 0 ? state_of(N[i].gout_parent) : gstate[i];
@@ -1060,6 +1129,25 @@ void Emitter::backward() {
               g.res = ptr(tg.addend);
               g.ldres = tg.addend.ld;
               g.res_dtype = tg.addend.dtype;
+            }
+            // a stage input with this single consumer: the matrix-core kernels store its gradient
+            // straight into the caller's dense buffer, no export copy
+            if (x.input_index >= 0 && x.input_index < 64 && x.users.size() == 1 && !tg.addend.valid() && !tg.post &&
+                !(pl.flags & 1) && g.in_dtype == DT_BF16 && gemm_mfma_supported(g)) {
+              g.C = nullptr;
+              g.c_ext = x.input_index + 1;
+              g.ldc = x.feat;
+              g.c_dtype = x.d.dtype;
+              N[nd.in[0]].grad_direct = true;
+            }
+            // a concat of ReLU layers written in place: the members' activation derivative is one mask
+            // over the whole merge buffer (the sign of the stored outputs), applied in this epilogue
+            if (x.d.kind == GPP_OP_CONCAT && x.users.size() == 1 && concat_relu_members(nd.in[0])) {
+              g.act = ACT_RELU;
+              g.aux = ptr(x.val);
+              g.ldaux = x.val.ld;
+              g.aux_dtype = x.val.dtype;
+              for (int m : x.in) dz_ready[m] = 1;
             }
             // fold the producer's activation derivative into this epilogue when we are its only consumer
             if (x.d.kind == GPP_OP_LINEAR && x.d.act != GPP_ACT_NONE && x.users.size() == 1 && x.gout_parent < 0) {
@@ -1326,7 +1414,7 @@ void Emitter::backward() {
         emit_elt(recs, EXT_GRAD_INPUTS, base);
         base = (int)k;
       }
-      if (!nd.wants_grad || state_of(pl.input_ops[k]) != G_WRITTEN) continue;
+      if (!nd.wants_grad || nd.grad_direct || state_of(pl.input_ops[k]) != G_WRITTEN) continue;
       Buf dst;
       dst.space = SP_ABS;
       dst.ld = nd.feat;

@@ -59,6 +59,8 @@ static int step_tag(const Step &sp, bool backward) {
   switch (sp.kern) {
     case K_GEMM_MFMA: return 1 + sp.a1;                    // 1 fwd, 2 dx, 3 dw
     case K_GEMM_SKINNY: return 25 + sp.a1;                 // 25 fwd, 26 dx
+    case K_GEMM_BWD_MERGED: return 27;
+    case K_LOSS_FWD_SMALL: return 21;
     case K_GEMM_GENERIC: return backward ? 5 : 4;
     case K_ELT: return backward ? 7 : 6;
     case K_COLSUM: return 8;
@@ -83,7 +85,7 @@ static const char *const kTagNames[GPP_PROFILE_TAGS] = {
     "other", "gemm_mfma_fwd", "gemm_mfma_dx", "gemm_mfma_dw", "gemm_generic_fwd", "gemm_generic_bwd", "elt_fwd", "elt_bwd",
     "colsum_bias_grad", "layernorm_fwd", "layernorm_bwd_dx", "layernorm_bwd_params", "attention_fwd", "attention_bwd_dq",
     "attention_bwd_dkv", "meanpool_fwd", "meanpool_bwd", "embedding_fwd", "embedding_bwd_sort_segsum", "interact_fwd",
-    "interact_bwd", "loss_fwd", "loss_bwd", "loss_sum", "embedding_grad_clear", "gemm_skinny_fwd", "gemm_skinny_dx", "", "", "", "",
+    "interact_bwd", "loss_fwd", "loss_bwd", "loss_sum", "embedding_grad_clear", "gemm_skinny_fwd", "gemm_skinny_dx", "gemm_bwd_merged_dx_dw", "", "", "",
     ""};
 
 extern "C" {
@@ -218,27 +220,27 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
       st->prof_tag[st->prof_used / 2] = step_tag(sp, is_bwd) | (sp.launches << 8);
       st->prof_used += 2;
     }
-    switch (sp.kern) {
-      case K_ELT: {
-        ExtPtrs ext;
-        memset(&ext, 0, sizeof(ext));
-        if (sp.ext_kind != EXT_NONE) {
-          const bool in_side = sp.ext_kind == EXT_INPUTS || sp.ext_kind == EXT_GRAD_OUTPUTS;
-          const int total = (sp.ext_kind == EXT_INPUTS || sp.ext_kind == EXT_GRAD_INPUTS) ? (int)pl.input_ops.size()
-                                                                                         : (int)pl.output_ops.size();
-          for (int k = 0; k < 64 && sp.ext_base + k < total; ++k) {
-            if (in_side)
-              ext.p[k] = ext_in ? (void *)ext_in[sp.ext_base + k] : nullptr;
-            else
-              ext.p[k] = ext_out ? ext_out[sp.ext_base + k] : nullptr;
-          }
-        }
-        launch_elt((const EltProb *)tab, sp.n, sp.blocks, ext, s);
-        break;
+    // per-call pointers the step's records refer to by index
+    ExtPtrs ext;
+    memset(&ext, 0, sizeof(ext));
+    if (sp.ext_kind != EXT_NONE) {
+      const bool in_side = sp.ext_kind == EXT_INPUTS || sp.ext_kind == EXT_GRAD_OUTPUTS;
+      const int total = (sp.ext_kind == EXT_INPUTS || sp.ext_kind == EXT_GRAD_INPUTS) ? (int)pl.input_ops.size()
+                                                                                     : (int)pl.output_ops.size();
+      for (int k = 0; k < 64 && sp.ext_base + k < total; ++k) {
+        if (in_side)
+          ext.p[k] = ext_in ? (void *)ext_in[sp.ext_base + k] : nullptr;
+        else
+          ext.p[k] = ext_out ? ext_out[sp.ext_base + k] : nullptr;
       }
+    }
+    switch (sp.kern) {
+      case K_ELT: launch_elt((const EltProb *)tab, sp.n, sp.blocks, ext, s); break;
       case K_GEMM_GENERIC: launch_gemm_generic((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a0, s); break;
-      case K_GEMM_MFMA: launch_gemm_mfma((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a1, sp.a2, s); break;
-      case K_GEMM_SKINNY: launch_gemm_skinny((const GemmProb *)tab, sp.n, sp.blocks, sp.a1, sp.a2, s); break;
+      case K_GEMM_MFMA: launch_gemm_mfma((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a1, sp.a2, ext, s); break;
+      case K_GEMM_SKINNY: launch_gemm_skinny((const GemmProb *)tab, sp.n, sp.blocks, sp.a1, sp.a2, sp.a0, ext, s); break;
+      case K_GEMM_BWD_MERGED: launch_gemm_bwd_merged((const GemmProb *)tab, sp.n, sp.blocks, sp.a2, sp.a1, accumulate, ext, s); break;
+      case K_LOSS_FWD_SMALL: launch_loss_fwd_small((const LossProb *)tab, sp.n, loss_out, s); break;
       case K_COLSUM: launch_colsum((const ColsumProb *)tab, sp.n, sp.blocks, accumulate, s); break;
       case K_LN_FWD: launch_ln_fwd((const LnProb *)tab, sp.n, sp.blocks, s); break;
       case K_LN_BWD: launch_ln_bwd((const LnProb *)tab, sp.n, sp.blocks, sp.a0, sp.a1, s); break;
