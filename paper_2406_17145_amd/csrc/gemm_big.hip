@@ -1,0 +1,254 @@
+// Branch-grouped bf16 GEMM for problems with many rows AND many columns (the transformer and MLP
+// stacks at full micro-batch): large output tiles so that the matrix cores, not the LDS or the
+// L1 <-> L2 path, set the pace.
+//
+// Eight waves (512 threads) share a 256 x 256 (or 128 x 256) output tile as a 2 x 4 grid of wave
+// tiles of 128 x 64 (64 x 64) elements = 4 x 2 (2 x 2) MFMA tiles of 32 x 32.  Per 16-wide
+// contraction chunk a wave reads 6 KB (4 KB) of operand fragments from LDS for 8 (4) MFMAs, which
+// keeps the LDS at well under half of its 256 B/clk while two waves per SIMD take turns on the
+// matrix pipe and hide each other's LDS and barrier waits.
+//
+// A k-step is 64 contraction elements, so a k-contiguous operand row contributes one whole 128-byte
+// cache line per step (with 32 every line was fetched from L2 twice, half used each time).
+// Operands come from memory through buffer loads (out-of-range rows read as zero without a branch;
+// a chunk beyond the contraction length is steered out of range), are held NS k-steps ahead in
+// registers and go through a double-buffered LDS tile.  The three forms and the two LDS layouts
+// (k-contiguous rows read with b128, contraction-major rows read with the transposing read) are
+// those of the smaller tile kernel.
+#include "gemm_tile_body.h"
+
+namespace gpp {
+
+constexpr int GB_BK = 64;           // contraction elements per k-step
+constexpr int GB_KST = GB_BK + 8;   // LDS row stride of k-contiguous tiles: 144-byte rows, conflict-free b128 reads
+
+template <int FORM, int WTM, int WTN>
+struct BigCfg {
+  static constexpr int WGM = 2, WGN = 4, NW = 8, THREADS = 512;
+  static constexpr int BM = 32 * WTM * WGM, BN = 32 * WTN * WGN;
+  static constexpr bool A_TR = FORM == FORM_DW, B_TR = FORM != FORM_FWD;
+  static constexpr int A_ELEMS = A_TR ? GB_BK * (BM + PAD_TR) : BM * GB_KST;
+  static constexpr int B_ELEMS = B_TR ? GB_BK * (BN + PAD_TR) : BN * GB_KST;
+  static constexpr int LDS_ELEMS = 2 * (A_ELEMS + B_ELEMS);
+  static_assert(LDS_ELEMS * 2 <= 160 * 1024, "tile does not fit the LDS");
+};
+
+// one k-step of one operand in registers: EXT rows/columns of the tile, 16-byte chunks, 512 threads
+template <int EXT>
+struct BigRegs {
+  static constexpr int PER_THREAD = EXT * GB_BK / 8 / 512;
+  u32x4 v[PER_THREAD];
+};
+
+// k-contiguous operand: tile rows [r0, r0 + EXT) x k [k0, k0 + 64); eight lanes read one 128-byte row
+// segment.  Rows beyond the buffer read zero, chunks at k >= k_lim are steered out of range (k_lim
+// is a multiple of 8).
+template <int EXT>
+__device__ __forceinline__ void big_fetch_kmajor(BigRegs<EXT> &t, __amdgpu_buffer_rsrc_t rs, int64_t ld, int r0, int k0,
+                                                 int k_lim, int tid) {
+#pragma unroll
+  for (int q = 0; q < BigRegs<EXT>::PER_THREAD; ++q) {
+    const int row = r0 + (tid >> 3) + 64 * q, k = k0 + (tid & 7) * 8;
+    // branch-free (a branch here makes the compiler wait for earlier loads between the loads)
+    const uint32_t oob = (uint32_t)-(int32_t)(k >= k_lim) & OOB_OFFSET;
+    const uint32_t off = (uint32_t)(((int64_t)row * ld + k) * 2) | oob;
+    t.v[q] = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0);
+  }
+}
+template <int EXT>
+__device__ __forceinline__ void big_store_kmajor(const BigRegs<EXT> &t, uint16_t *lds, int tid) {
+#pragma unroll
+  for (int q = 0; q < BigRegs<EXT>::PER_THREAD; ++q)
+    *(u32x4 *)(lds + ((tid >> 3) + 64 * q) * GB_KST + (tid & 7) * 8) = t.v[q];
+}
+// contraction-major operand: rows k [k0, k0 + 64) x columns [c0, c0 + EXT); rows beyond the buffer
+// (k >= contraction length) read zero; columns beyond the matrix only feed outputs that are never stored
+template <int EXT>
+__device__ __forceinline__ void big_fetch_tr(BigRegs<EXT> &t, __amdgpu_buffer_rsrc_t rs, int64_t ld, int k0, int c0,
+                                             int tid) {
+  constexpr int CPR = EXT / 8, RPP = 512 / CPR;   // chunks per row, rows per pass
+#pragma unroll
+  for (int q = 0; q < BigRegs<EXT>::PER_THREAD; ++q) {
+    const int row = k0 + tid / CPR + RPP * q, col = c0 + (tid % CPR) * 8;
+    t.v[q] = __builtin_amdgcn_raw_buffer_load_b128(rs, (uint32_t)(((int64_t)row * ld + col) * 2), 0, 0);
+  }
+}
+template <int EXT>
+__device__ __forceinline__ void big_store_tr(const BigRegs<EXT> &t, uint16_t *lds, int tid) {
+  constexpr int CPR = EXT / 8, RPP = 512 / CPR;
+#pragma unroll
+  for (int q = 0; q < BigRegs<EXT>::PER_THREAD; ++q)
+    *(u32x4 *)(lds + (tid / CPR + RPP * q) * (EXT + PAD_TR) + (tid % CPR) * 8) = t.v[q];
+}
+
+// LDS -> MFMA operand.  k-contiguous tile [rows][64 + 8]: lane l takes row (l % 32), 8 k-values at 8 * (l / 32)
+__device__ __forceinline__ bf16x8 big_frag_kmajor(const uint16_t *lds, int row0, int k0) {
+  const int l = threadIdx.x & 63;
+  return *(const bf16x8 *)(lds + (row0 + (l & 31)) * GB_KST + k0 + 8 * (l >> 5));
+}
+
+template <int FORM, int WTM, int WTN, int NS>
+__global__ __launch_bounds__(512) void k_gemm_big(const GemmProb *__restrict__ probs, int n, int total_blocks,
+                                                  int accumulate_dw, ExtPtrs ext) {
+  typedef BigCfg<FORM, WTM, WTN> C;
+  constexpr int BM = C::BM, BN = C::BN;
+  constexpr bool A_TR = C::A_TR, B_TR = C::B_TR;
+  __shared__ __attribute__((aligned(16))) uint16_t lds[C::LDS_ELEMS];
+  uint16_t *lds_a[2] = {lds, lds + C::A_ELEMS};
+  uint16_t *lds_b[2] = {lds + 2 * C::A_ELEMS, lds + 2 * C::A_ELEMS + C::B_ELEMS};
+
+  // XCD-aware spreading: consecutive workgroup ids go round-robin over the 8 XCDs; give each XCD one
+  // contiguous range of tiles instead, so that neighbours share operand panels in one L2
+  int bid = blockIdx.x;
+  {
+    const int xcd = bid & 7, idx = bid >> 3, per = total_blocks >> 3, rem = total_blocks & 7;
+    bid = xcd * per + min(xcd, rem) + idx;
+  }
+  const int pi = find_prob(probs, n, bid);
+  const GemmProb p = probs[pi];
+  const int tile = bid - p.blk_begin;
+  const int tiles_m = cdiv(p.M, BM);
+  const int m0 = (tile % tiles_m) * BM, n0 = (tile / tiles_m) * BN;   // consecutive tiles share the B panel
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int wi0 = (wave >> 2) * (32 * WTM), wj0 = (wave & 3) * (32 * WTN);
+
+  // operand buffers: rows beyond the matrix read as zero
+  //   FWD: A = X [M x K],  B = W [N x K]      DX: A = dZ [M x K],  B = W [K x N]
+  //   DW:  A = dZ [K x M], B = X [K x N]      (K = contraction length in every form)
+  const __amdgpu_buffer_rsrc_t rs_a = matrix_rsrc(p.A, A_TR ? p.K : p.M, p.lda, A_TR ? p.M : p.K);
+  const __amdgpu_buffer_rsrc_t rs_b = matrix_rsrc(p.B, B_TR ? p.K : p.N, p.ldb, B_TR ? p.N : p.K);
+
+  f32x16 acc[WTM][WTN];
+#pragma unroll
+  for (int i = 0; i < WTM; ++i)
+#pragma unroll
+    for (int j = 0; j < WTN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  BigRegs<BM> ra[NS];
+  BigRegs<BN> rb[NS];
+  auto fetch = [&](BigRegs<BM> &xa, BigRegs<BN> &xb, int k0) {
+    if (A_TR) big_fetch_tr<BM>(xa, rs_a, p.lda, k0, m0, tid);
+    else      big_fetch_kmajor<BM>(xa, rs_a, p.lda, m0, k0, p.K, tid);
+    if (B_TR) big_fetch_tr<BN>(xb, rs_b, p.ldb, k0, n0, tid);
+    else      big_fetch_kmajor<BN>(xb, rs_b, p.ldb, n0, k0, p.K, tid);
+  };
+  auto to_lds = [&](const BigRegs<BM> &xa, const BigRegs<BN> &xb, int buf) {
+    if (A_TR) big_store_tr<BM>(xa, lds_a[buf], tid);
+    else      big_store_kmajor<BM>(xa, lds_a[buf], tid);
+    if (B_TR) big_store_tr<BN>(xb, lds_b[buf], tid);
+    else      big_store_kmajor<BN>(xb, lds_b[buf], tid);
+  };
+
+  // backward-weight tiles of the first column block also sum the rows of dZ^T they stream: the bias
+  // gradient db[n] = sum_m dZ[m,n] comes out of the same launch
+  constexpr int BGROUPS = 512 / BM, BROWS = GB_BK / BGROUPS;
+  const bool do_bias = FORM == FORM_DW && p.bias != nullptr && n0 == 0;
+  float bsum = 0.0f;
+
+  const int nk = cdiv(p.K, GB_BK);
+#pragma unroll
+  for (int u = 0; u < NS - 1; ++u)
+    if (u < nk) fetch(ra[u], rb[u], u * GB_BK);
+  to_lds(ra[0], rb[0], 0);
+  __syncthreads();
+  for (int kt0 = 0; kt0 < nk; kt0 += NS) {
+#pragma unroll
+    for (int u = 0; u < NS; ++u) {
+      const int kt = kt0 + u;
+      if (kt >= nk) break;
+      const int cur = u & 1;   // NS is even: the LDS buffer of step kt is kt & 1 = u & 1
+      // ring slot (u + NS - 1) % NS was copied to LDS one step ago: refill it with step kt + NS - 1
+      if (kt + NS - 1 < nk) fetch(ra[(u + NS - 1) % NS], rb[(u + NS - 1) % NS], (kt + NS - 1) * GB_BK);
+#pragma unroll
+      for (int kc = 0; kc < GB_BK; kc += 16) {
+        bf16x8 a[WTM], b[WTN];
+#pragma unroll
+        for (int i = 0; i < WTM; ++i)
+          a[i] = A_TR ? frag_tr<BM>(lds_a[cur], wi0 + 32 * i, kc) : big_frag_kmajor(lds_a[cur], wi0 + 32 * i, kc);
+#pragma unroll
+        for (int j = 0; j < WTN; ++j)
+          b[j] = B_TR ? frag_tr<BN>(lds_b[cur], wj0 + 32 * j, kc) : big_frag_kmajor(lds_b[cur], wj0 + 32 * j, kc);
+#pragma unroll
+        for (int i = 0; i < WTM; ++i)
+#pragma unroll
+          for (int j = 0; j < WTN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+      }
+      if (FORM == FORM_DW && do_bias) {
+        const uint16_t *la = lds_a[cur] + (tid / BM) * BROWS * (BM + PAD_TR) + (tid % BM);
+#pragma unroll
+        for (int rr = 0; rr < BROWS; ++rr) bsum += bf16_bits_to_f32(la[rr * (BM + PAD_TR)]);
+      }
+      if (kt + 1 < nk) to_lds(ra[(u + 1) % NS], rb[(u + 1) % NS], cur ^ 1);
+      __syncthreads();
+    }
+  }
+
+  if (FORM == FORM_DW && do_bias) {   // fold the row groups in a fixed order (the k-loop ended with a barrier)
+    float *red = (float *)lds;
+    red[tid] = bsum;
+    __syncthreads();
+    if (tid < BM && m0 + tid < p.M) {
+      float total = 0.0f;
+#pragma unroll
+      for (int g = 0; g < BGROUPS; ++g) total += red[g * BM + tid];
+      float *db = const_cast<float *>(p.bias) + m0 + tid;
+      *db = accumulate_dw ? *db + total : total;
+    }
+  }
+
+  void *Cout = FORM == FORM_DW ? p.C : result_ptr(p, ext);
+  if (Cout == nullptr) return;
+  // ---- epilogue, one 32 x 32 accumulator tile at a time; tiles inside the matrix skip the bounds checks
+  const bool interior = m0 + BM <= p.M && n0 + BN <= p.N;
+#pragma unroll
+  for (int i = 0; i < WTM; ++i)
+#pragma unroll
+    for (int j = 0; j < WTN; ++j) {
+      const int col = n0 + wj0 + 32 * j + (lane & 31);
+      const int row0 = m0 + wi0 + 32 * i + 4 * (lane >> 5);
+      if (interior) epilogue_tile<FORM, false>(p, Cout, acc[i][j], row0, col, accumulate_dw, acc[i][j], false);
+      else epilogue_tile<FORM, true>(p, Cout, acc[i][j], row0, col, accumulate_dw, acc[i][j], false);
+    }
+}
+
+// ---- host side -------------------------------------------------------------------------
+// The kernel takes a problem when the chunks of its k-contiguous operands are whole (contraction
+// length a multiple of 8) and the matrices fit the 32-bit buffer offsets.
+bool gemm_big_supported(const GemmProb &p) {
+  if (!gemm_mfma_supported(p)) return false;
+  if (p.form != FORM_DW && (p.K & 7)) return false;
+  const int64_t a_rows = p.form == FORM_DW ? p.K : p.M, b_rows = p.form == FORM_FWD ? p.N : p.K;
+  if (a_rows * p.lda * 2 >= 0xffffff00ll || b_rows * p.ldb * 2 >= 0xffffff00ll) return false;
+  return true;
+}
+// tile rows for a launch whose largest problem is maxM x maxN, or 0 when the smaller tile kernel
+// should run it: big tiles need enough of them to fill the chip
+int gemm_big_tile_rows(int maxM, int maxN, int64_t launch_elems) {
+  if (maxM < 256 || maxN < 256) return 0;
+  if (launch_elems >= (int64_t)256 * 256 * 192) return 256;   // 256 x 256 tiles for at least 3/4 of the CUs
+  if (launch_elems >= (int64_t)128 * 256 * 128) return 128;
+  return 0;
+}
+int gemm_big_tiles_for(int tile_rows, int M, int N, int *tiles_n) {
+  if (tiles_n) *tiles_n = cdiv(N, 256);
+  return cdiv(M, tile_rows) * cdiv(N, 256);
+}
+
+template <int FORM>
+static void launch_big_form(const GemmProb *probs, int n, int blocks, int acc, int tile_rows, const ExtPtrs &ext, hipStream_t s) {
+  if (tile_rows == 256)
+    hipLaunchKernelGGL((k_gemm_big<FORM, 4, 2, 2>), dim3(blocks), dim3(512), 0, s, probs, n, blocks, acc, ext);
+  else
+    hipLaunchKernelGGL((k_gemm_big<FORM, 2, 2, 2>), dim3(blocks), dim3(512), 0, s, probs, n, blocks, acc, ext);
+}
+void launch_gemm_big(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int form, int tile_rows,
+                     const ExtPtrs &ext, hipStream_t s) {
+  if (total_blocks <= 0) return;
+  if (form == FORM_FWD) launch_big_form<FORM_FWD>(probs, n, total_blocks, accumulate_dw, tile_rows, ext, s);
+  else if (form == FORM_DX) launch_big_form<FORM_DX>(probs, n, total_blocks, accumulate_dw, tile_rows, ext, s);
+  else launch_big_form<FORM_DW>(probs, n, total_blocks, accumulate_dw, tile_rows, ext, s);
+}
+
+}  // namespace gpp

@@ -33,23 +33,6 @@ int gemm_skinny_blocks(int M, int N, int row_tiles, int col_tiles) {
   return ((N + 32 * col_tiles - 1) / (32 * col_tiles)) * ((M + 32 * row_tiles - 1) / (32 * row_tiles));
 }
 
-// 8 consecutive elements of one row; zero outside [0,row_lim) x [0,col_lim), ragged tail cleared
-__device__ __forceinline__ u32x4 load8(const uint16_t *__restrict__ base, int64_t ld, int row, int row_lim, int col, int col_lim) {
-  u32x4 v = {0u, 0u, 0u, 0u};
-  if (row < row_lim && col < col_lim) {
-    v = *(const u32x4 *)(base + (int64_t)row * ld + col);
-    if (col + 8 > col_lim) {
-      const int keep = col_lim - col;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        if (2 * e >= keep) v[e] = 0u;
-        else if (2 * e + 1 >= keep) v[e] &= 0xffffu;
-      }
-    }
-  }
-  return v;
-}
-
 // one 64-wide k-step of a wave, as fetched from memory: BM x 64 of A and the W tile (BN x 64 forward,
 // 64 x BN backward-data) in 16-byte chunks of whole rows, so every load instruction covers whole
 // 128-byte (64-byte for a 32-wide backward tile) row segments
@@ -96,8 +79,10 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmProb &p, int local, u
   const int m0 = (local % m_blocks) * BM;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 31, h = lane >> 5;
-  const uint16_t *A = (const uint16_t *)p.A;
-  const uint16_t *B = (const uint16_t *)p.B;
+  // operand descriptors: A = X or dZ [M x K]; B = W, [N x K] forward, [K x N] backward-data
+  const __amdgpu_buffer_rsrc_t rs_a = matrix_rsrc(p.A, p.M, p.lda, p.K);
+  const __amdgpu_buffer_rsrc_t rs_b = matrix_rsrc(p.B, FORM == FORM_FWD ? p.N : p.K, p.ldb, FORM == FORM_FWD ? p.K : p.N);
+  const bool ragged_k = (p.K & 7) != 0;                        // forward: both operands end inside a chunk; backward-data: A
   uint16_t *lds_a = (uint16_t *)lds_raw + wave * WAVE_ELEMS;   // [BM][SK_ST]
   uint16_t *lds_b = lds_a + BM * SK_ST;                        // [B_ROWS][SB]
 
@@ -119,11 +104,19 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmProb &p, int local, u
   auto load = [&](SkStep<TI, TJ> &f, int s) {
     const int k0 = SK_KS * s;
 #pragma unroll
-    for (int q = 0; q < 4 * TI; ++q) f.a[q] = load8(A, p.lda, m0 + 8 * q + crow, p.M, k0 + ccol, p.K);
+    for (int q = 0; q < 4 * TI; ++q) f.a[q] = chunk_load(rs_a, p.lda, m0 + 8 * q + crow, k0 + ccol, p.M, p.K);
 #pragma unroll
     for (int q = 0; q < 4 * TJ; ++q) {
-      if (FORM == FORM_FWD) f.b[q] = load8(B, p.ldb, n0 + 8 * q + crow, p.N, k0 + ccol, p.K);          // W[n][k]
-      else f.b[q] = load8(B, p.ldb, k0 + DX_RPI * q + drow, p.K, n0 + dcol, p.N);                      // W[k][n]
+      if (FORM == FORM_FWD) f.b[q] = chunk_load(rs_b, p.ldb, n0 + 8 * q + crow, k0 + ccol, p.N, p.K);          // W[n][k]
+      else f.b[q] = chunk_load(rs_b, p.ldb, k0 + DX_RPI * q + drow, n0 + dcol, p.K, p.N);                      // W[k][n]
+    }
+    if (ragged_k) {   // the contraction ends inside a chunk: clear what lies beyond it (row padding)
+#pragma unroll
+      for (int q = 0; q < 4 * TI; ++q) f.a[q] = chunk_clear_tail(f.a[q], k0 + ccol, p.K);
+      if (FORM == FORM_FWD) {
+#pragma unroll
+        for (int q = 0; q < 4 * TJ; ++q) f.b[q] = chunk_clear_tail(f.b[q], k0 + ccol, p.K);
+      }
     }
   };
   auto stage = [&](const SkStep<TI, TJ> &f) {

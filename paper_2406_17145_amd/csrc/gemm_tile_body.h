@@ -46,29 +46,58 @@ struct TileRegs {
   u32x4 v[PER_THREAD];
 };
 
+// ---- branch-free 16-byte operand loads -------------------------------------------------
+// Operands are read through buffer descriptors: an offset beyond the descriptor's size returns zeros,
+// so rows and chunks outside the matrix need no branch (a branch around a load makes the compiler
+// wait for earlier loads in between, which exposes the memory latency once per load).
+constexpr uint32_t OOB_OFFSET = 0xfffffff0u;   // beyond any descriptor's size
+
+// bytes from the first to the last valid element of a [rows x width] bf16 matrix with row stride ld
+// (it may be a column slice of a wider buffer); the descriptor holds 32 bits
+__device__ __forceinline__ uint32_t matrix_bytes(int rows, int64_t ld, int width) {
+  const int64_t b = ((int64_t)(rows - 1) * ld + ((width + 7) & ~7)) * 2;   // whole 16-byte chunks (ld is a multiple of 8)
+  return (uint32_t)(b < 0xffffff00ll ? b : 0xffffff00ll);
+}
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t matrix_rsrc(const void *base, int rows, int64_t ld, int width) {
+  return __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, matrix_bytes(rows, ld, width), 0x00020000);
+}
+// 8 consecutive elements of row r starting at column c; zero when r >= row_lim or c >= col_lim
+__device__ __forceinline__ u32x4 chunk_load(__amdgpu_buffer_rsrc_t rs, int64_t ld, int r, int c, int row_lim, int col_lim) {
+  const uint32_t oob = (uint32_t)-(int32_t)((r >= row_lim) | (c >= col_lim)) & OOB_OFFSET;
+  return __builtin_amdgcn_raw_buffer_load_b128(rs, (uint32_t)(((int64_t)r * ld + c) * 2) | oob, 0, 0);
+}
+// clears the elements at columns >= col_lim of a chunk that starts at column c (only matrices whose
+// width is not a multiple of 8 need it: the rest of such a chunk is row padding)
+__device__ __forceinline__ u32x4 chunk_clear_tail(u32x4 v, int c, int col_lim) {
+  const int keep = col_lim - c;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const uint32_t lo = 2 * e < keep ? 0x0000ffffu : 0u, hi = 2 * e + 1 < keep ? 0xffff0000u : 0u;
+    v[e] &= lo | hi;
+  }
+  return v;
+}
+
+// ---- global -> register tile fetch -------------------------------------------
+// (rows [row0, ..) x columns [col0, ..) of the operand behind `rs`; `ragged`: col_lim is not a multiple of 8)
 template <int ROWS, int COLS>
-__device__ __forceinline__ void tile_fetch(TileRegs<ROWS, COLS> &t, const uint16_t *__restrict__ base, int64_t ld,
-                                           int row0, int col0, int row_lim, int col_lim, int tid) {
+__device__ __forceinline__ void tile_fetch(TileRegs<ROWS, COLS> &t, __amdgpu_buffer_rsrc_t rs, int64_t ld, int row0, int col0,
+                                           int row_lim, int col_lim, bool ragged, int tid) {
   constexpr int CPR = COLS / 8;  // chunks per row
 #pragma unroll
   for (int q = 0; q < TileRegs<ROWS, COLS>::PER_THREAD; ++q) {
     const int c = tid + 256 * q;
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (TileRegs<ROWS, COLS>::CHUNKS % 256 == 0 || c < TileRegs<ROWS, COLS>::CHUNKS) {
-      const int r = row0 + c / CPR, cc = col0 + (c % CPR) * 8;
-      if (r < row_lim && cc < col_lim) {
-        v = *(const u32x4 *)(base + (int64_t)r * ld + cc);
-        if (cc + 8 > col_lim) {  // ragged tail: clear the elements past the limit
-          const int keep = col_lim - cc;
+    const int r = row0 + c / CPR, cc = col0 + (c % CPR) * 8;
+    // a thread without a chunk in a partial last round reads out of range
+    const bool mine = TileRegs<ROWS, COLS>::CHUNKS % 256 == 0 || c < TileRegs<ROWS, COLS>::CHUNKS;
+    t.v[q] = chunk_load(rs, ld, r, cc, mine ? row_lim : 0, col_lim);
+  }
+  if (ragged) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            if (2 * e >= keep) v[e] = 0u;
-            else if (2 * e + 1 >= keep) v[e] &= 0xffffu;
-          }
-        }
-      }
+    for (int q = 0; q < TileRegs<ROWS, COLS>::PER_THREAD; ++q) {
+      const int c = tid + 256 * q;
+      t.v[q] = chunk_clear_tail(t.v[q], col0 + (c % CPR) * 8, col_lim);
     }
-    t.v[q] = v;
   }
 }
 
@@ -115,6 +144,105 @@ __device__ __forceinline__ float get_partial(const float *p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// ---- epilogue of one 32 x 32 accumulator tile ------------------------------------------
+// Register r of the tile holds row row0 + 8 * (r / 4) + r % 4 (row0 already includes this lane's
+// 4 * (lane / 32)) of column `col`.  Everything that does not depend on r (which optional operands
+// exist, the activation, the storage types, the 64-bit base addresses) is decided once per tile, so
+// the sixteen elements cost a handful of instructions each.  CHECK = false: the tile is known to lie
+// inside the matrix.  With `has_old`, `c_old` holds the old values of a backward-weight tile.
+__device__ __forceinline__ float elem_load(const void *base, int32_t dtype, int64_t at) {
+  return dtype == DT_BF16 ? bf16_bits_to_f32(((const uint16_t *)base)[at]) : ((const float *)base)[at];
+}
+template <int FORM, bool CHECK>
+__device__ __forceinline__ void epilogue_tile(const GemmProb &p, void *Cout, const f32x16 &acc, int row0, int col,
+                                              int accumulate_dw, const f32x16 &c_old, bool has_old) {
+  if (CHECK && col >= p.N) return;
+  float v[16];
+  bool ok[16];
+  int ro[16];   // row offsets from row0
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    v[r] = acc[r];
+    ro[r] = 8 * (r >> 2) + (r & 3);
+    ok[r] = !CHECK || row0 + ro[r] < p.M;
+  }
+  const int64_t cbase = (int64_t)row0 * p.ldc + col;
+  const int ldc = (int)p.ldc;
+  if (FORM == FORM_FWD) {
+    if (p.bias) {
+      const float b = p.bias[col];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) v[r] += b;
+    }
+    if (p.aux) {   // pre-activation stash
+      const int64_t abase = (int64_t)row0 * p.ldaux + col;
+      const int lda = (int)p.ldaux;
+      if (p.aux_dtype == DT_BF16) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (ok[r]) ((uint16_t *)p.aux)[abase + ro[r] * lda] = f32_to_bf16_bits(v[r]);
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (ok[r]) ((float *)p.aux)[abase + ro[r] * lda] = v[r];
+      }
+    }
+    if (p.act == ACT_RELU) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) v[r] = v[r] > 0.0f ? v[r] : 0.0f;
+    } else if (p.act == ACT_GELU) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) v[r] = gelu_f(v[r]);
+    }
+  }
+  if (FORM != FORM_DW && p.res) {   // forward: residual addend; backward-data: gradient addend
+    const int64_t rbase = (int64_t)row0 * p.ldres + col;
+    const int ldr = (int)p.ldres;
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      if (ok[r]) v[r] += elem_load(p.res, p.res_dtype, rbase + ro[r] * ldr);
+  }
+  if (FORM == FORM_DX && p.act != ACT_NONE) {
+    const int64_t abase = (int64_t)row0 * p.ldaux + col;
+    const int lda = (int)p.ldaux;
+    if (p.act == ACT_RELU) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (ok[r]) v[r] = elem_load(p.aux, p.aux_dtype, abase + ro[r] * lda) > 0.0f ? v[r] : 0.0f;
+    } else {
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (ok[r]) v[r] *= gelu_grad_f(elem_load(p.aux, p.aux_dtype, abase + ro[r] * lda));
+    }
+  }
+  if (FORM == FORM_DW) {
+    float *c = (float *)Cout + cbase;
+    if (has_old) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (ok[r]) c[ro[r] * ldc] = c_old[r] + v[r];
+    } else if (accumulate_dw) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (ok[r]) c[ro[r] * ldc] += v[r];
+    } else {
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (ok[r]) c[ro[r] * ldc] = v[r];
+    }
+  } else if (p.c_dtype == DT_BF16) {
+    uint16_t *c = (uint16_t *)Cout + cbase;
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      if (ok[r]) c[ro[r] * ldc] = f32_to_bf16_bits(v[r]);
+  } else {
+    float *c = (float *)Cout + cbase;
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      if (ok[r]) c[ro[r] * ldc] = v[r];
+  }
+}
+
 // LDS elements (uint16) one 256-thread team needs: both operands, double buffered
 template <int FORM, int BM, int BN>
 struct TileLds {
@@ -154,8 +282,11 @@ __device__ __forceinline__ void gemm_tile_body(const GemmProb &p, int local, int
   const int m0 = (tile % tiles_m) * BM, n0 = (tile / tiles_m) * BN;   // consecutive tiles share the B panel
   const int wave = tid >> 6, lane = tid & 63;
   const int wi0 = (wave >> 1) * WM, wj0 = (wave & 1) * WN;
-  const uint16_t *A = (const uint16_t *)p.A;
-  const uint16_t *B = (const uint16_t *)p.B;
+  // operand descriptors: FWD A = X [M x K], B = W [N x K]; DX A = dZ [M x K], B = W [K x N];
+  // DW A = dZ [K x M], B = X [K x N]  (K = contraction length)
+  const __amdgpu_buffer_rsrc_t rs_a = matrix_rsrc(p.A, A_TR ? p.K : p.M, p.lda, A_TR ? p.M : p.K);
+  const __amdgpu_buffer_rsrc_t rs_b = matrix_rsrc(p.B, B_TR ? p.K : p.N, p.ldb, B_TR ? p.N : p.K);
+  const bool ragged_a = ((A_TR ? p.M : p.K) & 7) != 0, ragged_b = ((B_TR ? p.N : p.K) & 7) != 0;
   void *Cout = FORM == FORM_DW ? p.C : result_ptr(p, ext);
 
   f32x16 acc[TI][TJ];
@@ -193,10 +324,10 @@ __device__ __forceinline__ void gemm_tile_body(const GemmProb &p, int local, int
   RegsA ra[NS];
   RegsB rb[NS];
   auto fetch = [&](RegsA &xa, RegsB &xb, int k0) {
-    if (A_TR) tile_fetch<A_TR ? BK : BM, A_TR ? BM : BK>(xa, A, p.lda, k0, m0, k_end, p.M, tid);
-    else      tile_fetch<A_TR ? BK : BM, A_TR ? BM : BK>(xa, A, p.lda, m0, k0, p.M, k_end, tid);
-    if (B_TR) tile_fetch<B_TR ? BK : BN, B_TR ? BN : BK>(xb, B, p.ldb, k0, n0, k_end, p.N, tid);
-    else      tile_fetch<B_TR ? BK : BN, B_TR ? BN : BK>(xb, B, p.ldb, n0, k0, p.N, k_end, tid);
+    if (A_TR) tile_fetch<A_TR ? BK : BM, A_TR ? BM : BK>(xa, rs_a, p.lda, k0, m0, k_end, p.M, ragged_a, tid);
+    else      tile_fetch<A_TR ? BK : BM, A_TR ? BM : BK>(xa, rs_a, p.lda, m0, k0, p.M, k_end, ragged_a, tid);
+    if (B_TR) tile_fetch<B_TR ? BK : BN, B_TR ? BN : BK>(xb, rs_b, p.ldb, k0, n0, k_end, p.N, ragged_b, tid);
+    else      tile_fetch<B_TR ? BK : BN, B_TR ? BN : BK>(xb, rs_b, p.ldb, n0, k0, p.N, k_end, ragged_b, tid);
   };
   // backward-weight tiles of the first column block also sum the rows of dZ^T they stream: the bias
   // gradient db[n] = sum_m dZ[m,n] comes out of the same launch
@@ -299,36 +430,17 @@ __device__ __forceinline__ void gemm_tile_body(const GemmProb &p, int local, int
   }
   if (Cout == nullptr) return;   // the caller does not want this result (all barriers are behind us)
 
-  // ---- epilogue: accumulator register r of a 32x32 tile holds row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
+  // ---- epilogue, one 32 x 32 accumulator tile at a time; tiles inside the matrix skip the bounds checks
+  const bool interior = m0 + BM <= p.M && n0 + BN <= p.N;
 #pragma unroll
   for (int i = 0; i < TI; ++i)
 #pragma unroll
     for (int j = 0; j < TJ; ++j) {
       const int col = n0 + wj0 + 32 * j + (lane & 31);
-      if (col >= p.N) continue;
-      float bias = 0.0f;
-      if (FORM == FORM_FWD && p.bias) bias = p.bias[col];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wi0 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (row >= p.M) continue;
-        float v = acc[i][j][r];
-        const int64_t ci = (int64_t)row * p.ldc + col;
-        if (FORM == FORM_FWD) {
-          v += bias;
-          if (p.aux) store_from_f32(p.aux, p.aux_dtype, (int64_t)row * p.ldaux + col, v);
-          v = act_apply(v, p.act);
-          if (p.res) v += load_as_f32(p.res, p.res_dtype, (int64_t)row * p.ldres + col);
-          store_from_f32(Cout, p.c_dtype, ci, v);
-        } else if (FORM == FORM_DX) {
-          if (p.res) v += load_as_f32(p.res, p.res_dtype, (int64_t)row * p.ldres + col);
-          if (p.act != ACT_NONE) v *= act_grad(load_as_f32(p.aux, p.aux_dtype, (int64_t)row * p.ldaux + col), p.act);
-          store_from_f32(Cout, p.c_dtype, ci, v);
-        } else {
-          float *c = (float *)Cout;
-          c[ci] = c_prefetch ? c_old[i][j][r] + v : (accumulate_dw ? c[ci] + v : v);
-        }
-      }
+      const int row0 = m0 + wi0 + 32 * i + 4 * (lane >> 5);
+      const bool has_old = FORM == FORM_DW && c_prefetch;
+      if (interior) epilogue_tile<FORM, false>(p, Cout, acc[i][j], row0, col, accumulate_dw, c_old[i][j], has_old);
+      else epilogue_tile<FORM, true>(p, Cout, acc[i][j], row0, col, accumulate_dw, c_old[i][j], has_old);
     }
 }
 

@@ -616,6 +616,30 @@ struct Emitter {
             if (wants_ext(g)) s.ext_kind = EXT_GRAD_INPUTS;
             continue;
           }
+          // many rows and columns: the large-tile kernel
+          if (use_mfma && !(pl.flags & 2)) {
+            bool ok = true;
+            int64_t elems = 0;
+            for (auto &r : g) {
+              ok = ok && gemm_big_supported(r);
+              elems += (int64_t)r.M * r.N;
+            }
+            const int tile_rows = ok ? gemm_big_tile_rows(max_m, max_n, elems) : 0;
+            if (tile_rows > 0) {
+              int blocks = 0;
+              for (auto &r : g) {
+                r.blk_begin = blocks;
+                r.split_k = 1;
+                blocks += gemm_big_tiles_for(tile_rows, r.M, r.N, &r.tiles_n);
+              }
+              Step &s = add_step(K_GEMM_BIG, push_table(g), (int)g.size(), blocks);
+              s.a0 = dt;
+              s.a1 = form;
+              s.a2 = tile_rows;
+              if (wants_ext(g)) s.ext_kind = EXT_GRAD_INPUTS;
+              continue;
+            }
+          }
           int launch_tiles = 0;
           if (use_mfma)
             for (auto &r : g) launch_tiles += gemm_mfma_tiles_for(tile, r.M, r.N, nullptr);
