@@ -40,24 +40,44 @@ __device__ __forceinline__ float to_f32<uint16_t>(uint16_t v) {
   return bf16_bits_to_f32(v);
 }
 
-// exact (erf) GELU and its derivative Phi(z) + z*phi(z)
-__device__ __forceinline__ float gelu_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f)); }
+// GELU in its erf form, y = z * Phi(z), and its derivative Phi(z) + z * phi(z), from ONE exponential:
+// erf(z / sqrt 2) = sign(z) * (1 - P(t) * exp(-z^2 / 2)), t = 1 / (1 + c |z| / sqrt 2), with the five-term
+// polynomial P of Abramowitz & Stegun 7.1.26 (absolute error of erf below 1.5e-7), and phi(z) is that
+// same exponential over sqrt(2 pi).
+__device__ __forceinline__ void gelu_both(float z, float &y, float &dy) {
+  const float az = fabsf(z) * 0.70710678118654752f;
+  const float t = __frcp_rn(1.0f + 0.3275911f * az);
+  const float e = __expf(-az * az);
+  const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+  const float erf_abs = 1.0f - poly * e;
+  const float cdf = 0.5f * (1.0f + copysignf(erf_abs, z));
+  y = z * cdf;
+  dy = cdf + z * (0.3989422804014327f * e);
+}
+__device__ __forceinline__ float gelu_f(float z) {
+  float y, dy;
+  gelu_both(z, y, dy);
+  return y;
+}
 __device__ __forceinline__ float gelu_grad_f(float z) {
-  float cdf = 0.5f * (1.0f + erff(z * 0.70710678118654752f));
-  float pdf = 0.3989422804014327f * __expf(-0.5f * z * z);
-  return cdf + z * pdf;
+  float y, dy;
+  gelu_both(z, y, dy);
+  return dy;
 }
 __device__ __forceinline__ float act_apply(float z, int32_t act) {
   if (act == ACT_RELU) return z > 0.0f ? z : 0.0f;
   if (act == ACT_GELU) return gelu_f(z);
   return z;
 }
-// derivative factor from the mask source: ReLU uses the stored output (y > 0 <=> z > 0),
-// GELU the stored pre-activation
+// What a forward epilogue stashes for the backward pass of an activation that needs more than the
+// sign of its output: for GELU the DERIVATIVE at the pre-activation (the forward pass has the
+// exponential at hand), so that the backward epilogue is one multiplication.
+__device__ __forceinline__ float act_stash(float z, int32_t act) { return act == ACT_GELU ? gelu_grad_f(z) : z; }
+// derivative factor from the mask source: ReLU uses the stored output (y > 0 <=> z > 0), GELU the
+// stashed derivative
 __device__ __forceinline__ float act_grad(float src, int32_t act) {
   if (act == ACT_RELU) return src > 0.0f ? 1.0f : 0.0f;
-  if (act == ACT_GELU) return gelu_grad_f(src);
-  return 1.0f;
+  return src;
 }
 
 __device__ __forceinline__ float wave_sum(float v) {

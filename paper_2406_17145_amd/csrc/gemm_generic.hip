@@ -87,7 +87,7 @@ __global__ __launch_bounds__(256) void k_gemm_generic(const GemmProb *__restrict
       const int64_t ci = (int64_t)row * p.ldc + col;
       if (p.form == FORM_FWD) {
         if (p.bias) v += p.bias[col];
-        if (p.aux) store_from_f32(p.aux, p.aux_dtype, (int64_t)row * p.ldaux + col, v);
+        if (p.aux) store_from_f32(p.aux, p.aux_dtype, (int64_t)row * p.ldaux + col, act_stash(v, p.act));
         v = act_apply(v, p.act);
         if (p.res) v += load_as_f32(p.res, p.res_dtype, (int64_t)row * p.ldres + col);
         store_from_f32(p.C, p.c_dtype, ci, v);

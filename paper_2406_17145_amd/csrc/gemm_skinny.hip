@@ -219,7 +219,7 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmProb &p, int local, u
       const int64_t ci = (int64_t)row * p.ldc + col;
       if (FORM == FORM_FWD) {
         if (p.bias) v += p.bias[col];
-        if (p.aux) store_from_f32(p.aux, p.aux_dtype, (int64_t)row * p.ldaux + col, v);
+        if (p.aux) store_from_f32(p.aux, p.aux_dtype, (int64_t)row * p.ldaux + col, act_stash(v, p.act));
         v = act_apply(v, p.act);
         if (p.res) v += load_as_f32(p.res, p.res_dtype, (int64_t)row * p.ldres + col);
       } else {

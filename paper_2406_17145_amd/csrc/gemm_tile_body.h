@@ -174,25 +174,26 @@ __device__ __forceinline__ void epilogue_tile(const GemmProb &p, void *Cout, con
 #pragma unroll
       for (int r = 0; r < 16; ++r) v[r] += b;
     }
-    if (p.aux) {   // pre-activation stash
-      const int64_t abase = (int64_t)row0 * p.ldaux + col;
-      const int lda = (int)p.ldaux;
-      if (p.aux_dtype == DT_BF16) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (ok[r]) ((uint16_t *)p.aux)[abase + ro[r] * lda] = f32_to_bf16_bits(v[r]);
-      } else {
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (ok[r]) ((float *)p.aux)[abase + ro[r] * lda] = v[r];
-      }
-    }
     if (p.act == ACT_RELU) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) v[r] = v[r] > 0.0f ? v[r] : 0.0f;
     } else if (p.act == ACT_GELU) {
+      float d[16];   // derivative at the pre-activation: what the backward pass multiplies by
 #pragma unroll
-      for (int r = 0; r < 16; ++r) v[r] = gelu_f(v[r]);
+      for (int r = 0; r < 16; ++r) gelu_both(v[r], v[r], d[r]);
+      if (p.aux) {
+        const int64_t abase = (int64_t)row0 * p.ldaux + col;
+        const int lda = (int)p.ldaux;
+        if (p.aux_dtype == DT_BF16) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (ok[r]) ((uint16_t *)p.aux)[abase + ro[r] * lda] = f32_to_bf16_bits(d[r]);
+        } else {
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (ok[r]) ((float *)p.aux)[abase + ro[r] * lda] = d[r];
+        }
+      }
     }
   }
   if (FORM != FORM_DW && p.res) {   // forward: residual addend; backward-data: gradient addend
@@ -212,7 +213,7 @@ __device__ __forceinline__ void epilogue_tile(const GemmProb &p, void *Cout, con
     } else {
 #pragma unroll
       for (int r = 0; r < 16; ++r)
-        if (ok[r]) v[r] *= gelu_grad_f(elem_load(p.aux, p.aux_dtype, abase + ro[r] * lda));
+        if (ok[r]) v[r] *= elem_load(p.aux, p.aux_dtype, abase + ro[r] * lda);   // stashed derivative
     }
   }
   if (FORM == FORM_DW) {

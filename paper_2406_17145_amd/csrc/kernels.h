@@ -22,7 +22,7 @@ struct GemmProb {
   const void *A, *B;
   void *C;
   const float *bias;
-  void *aux;        // FWD + GELU: pre-activation stash (written). DX: mask source (read).
+  void *aux;        // FWD + GELU: stash of the activation derivative (written). DX: mask source / derivative (read).
   const void *res;  // FWD: residual addend. DX: gradient addend (may equal C: accumulate).
   int64_t lda, ldb, ldc, ldaux, ldres;
   int32_t M, N, K;
