@@ -200,17 +200,9 @@ __global__ __launch_bounds__(512) void k_gemm_big(const GemmProb *__restrict__ p
 
   void *Cout = FORM == FORM_DW ? p.C : result_ptr(p, ext);
   if (Cout == nullptr) return;
-  // ---- epilogue, one 32 x 32 accumulator tile at a time; tiles inside the matrix skip the bounds checks
-  const bool interior = m0 + BM <= p.M && n0 + BN <= p.N;
-#pragma unroll
-  for (int i = 0; i < WTM; ++i)
-#pragma unroll
-    for (int j = 0; j < WTN; ++j) {
-      const int col = n0 + wj0 + 32 * j + (lane & 31);
-      const int row0 = m0 + wi0 + 32 * i + 4 * (lane >> 5);
-      if (interior) epilogue_tile<FORM, false>(p, Cout, acc[i][j], row0, col, accumulate_dw, acc[i][j], false);
-      else epilogue_tile<FORM, true>(p, Cout, acc[i][j], row0, col, accumulate_dw, acc[i][j], false);
-    }
+  // ---- epilogue; tiles inside the matrix skip the bounds checks
+  if (m0 + BM <= p.M && n0 + BN <= p.N) epilogue_wave<FORM, false, WTM, WTN>(p, Cout, acc, m0 + wi0, n0 + wj0, lane, accumulate_dw);
+  else epilogue_wave<FORM, true, WTM, WTN>(p, Cout, acc, m0 + wi0, n0 + wj0, lane, accumulate_dw);
 }
 
 // ---- host side -------------------------------------------------------------------------

@@ -258,7 +258,7 @@ __global__ __launch_bounds__(512) void k_gemm_bwd_merged(const GemmProb *__restr
   } else {
     const int team = threadIdx.x >> 8;
     // few rows to contract over: two k-steps in flight are enough and keep the kernel free of spills
-    gemm_tile_body<FORM_DW, BWD_DW_TILE, BWD_DW_TILE, false, 2>(p, 2 * local + team, threadIdx.x & 255,
+    gemm_tile_body<FORM_DW, BWD_DW_TILE, BWD_DW_TILE, false, 2, true>(p, 2 * local + team, threadIdx.x & 255,
                                                              (uint16_t *)lds_raw + team * DwLds::ELEMS, accumulate_dw, ext);
   }
 }

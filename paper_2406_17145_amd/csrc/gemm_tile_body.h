@@ -144,18 +144,53 @@ __device__ __forceinline__ float get_partial(const float *p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// ---- epilogue of one 32 x 32 accumulator tile ------------------------------------------
+// ---- epilogue of one 32 x 32 accumulator tile, in two phases -----------------------------
 // Register r of the tile holds row row0 + 8 * (r / 4) + r % 4 (row0 already includes this lane's
 // 4 * (lane / 32)) of column `col`.  Everything that does not depend on r (which optional operands
 // exist, the activation, the storage types, the 64-bit base addresses) is decided once per tile, so
 // the sixteen elements cost a handful of instructions each.  CHECK = false: the tile is known to lie
-// inside the matrix.  With `has_old`, `c_old` holds the old values of a backward-weight tile.
+// inside the matrix.
+// Phase 1 (epi_fetch) issues the loads a tile's epilogue needs -- residual / gradient addend, the
+// stashed activation derivative, the old gradient of a backward-weight tile -- and phase 2
+// (epi_finish) consumes them, so a caller can fetch tile t + 1 before it finishes tile t and the
+// memory latency is paid once per workgroup, not once per tile.
+struct EpiIn {
+  f32x16 a;   // DX: stashed derivative / mask source; DW: old gradient values
+  f32x16 r;   // FWD: residual addend; DX: gradient addend
+};
 __device__ __forceinline__ float elem_load(const void *base, int32_t dtype, int64_t at) {
   return dtype == DT_BF16 ? bf16_bits_to_f32(((const uint16_t *)base)[at]) : ((const float *)base)[at];
 }
+__device__ __forceinline__ int epi_row(int r) { return 8 * (r >> 2) + (r & 3); }
+
 template <int FORM, bool CHECK>
-__device__ __forceinline__ void epilogue_tile(const GemmProb &p, void *Cout, const f32x16 &acc, int row0, int col,
-                                              int accumulate_dw, const f32x16 &c_old, bool has_old) {
+__device__ __forceinline__ void epi_fetch(const GemmProb &p, const void *Cout, int row0, int col, int accumulate_dw, EpiIn &in) {
+  const bool col_ok = !CHECK || col < p.N;
+  if (FORM != FORM_DW && p.res) {
+    const int64_t base = (int64_t)row0 * p.ldres + col;
+    const int ld = (int)p.ldres;
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      in.r[r] = (col_ok && (!CHECK || row0 + epi_row(r) < p.M)) ? elem_load(p.res, p.res_dtype, base + epi_row(r) * ld) : 0.0f;
+  }
+  if (FORM == FORM_DX && p.act != ACT_NONE) {
+    const int64_t base = (int64_t)row0 * p.ldaux + col;
+    const int ld = (int)p.ldaux;
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      in.a[r] = (col_ok && (!CHECK || row0 + epi_row(r) < p.M)) ? elem_load(p.aux, p.aux_dtype, base + epi_row(r) * ld) : 0.0f;
+  }
+  if (FORM == FORM_DW && accumulate_dw) {
+    const float *c = (const float *)Cout + (int64_t)row0 * p.ldc + col;
+    const int ld = (int)p.ldc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) in.a[r] = (col_ok && (!CHECK || row0 + epi_row(r) < p.M)) ? c[epi_row(r) * ld] : 0.0f;
+  }
+}
+
+template <int FORM, bool CHECK>
+__device__ __forceinline__ void epi_finish(const GemmProb &p, void *Cout, const f32x16 &acc, int row0, int col,
+                                           int accumulate_dw, const EpiIn &in) {
   if (CHECK && col >= p.N) return;
   float v[16];
   bool ok[16];
@@ -163,7 +198,7 @@ __device__ __forceinline__ void epilogue_tile(const GemmProb &p, void *Cout, con
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     v[r] = acc[r];
-    ro[r] = 8 * (r >> 2) + (r & 3);
+    ro[r] = epi_row(r);
     ok[r] = !CHECK || row0 + ro[r] < p.M;
   }
   const int64_t cbase = (int64_t)row0 * p.ldc + col;
@@ -197,35 +232,24 @@ __device__ __forceinline__ void epilogue_tile(const GemmProb &p, void *Cout, con
     }
   }
   if (FORM != FORM_DW && p.res) {   // forward: residual addend; backward-data: gradient addend
-    const int64_t rbase = (int64_t)row0 * p.ldres + col;
-    const int ldr = (int)p.ldres;
 #pragma unroll
-    for (int r = 0; r < 16; ++r)
-      if (ok[r]) v[r] += elem_load(p.res, p.res_dtype, rbase + ro[r] * ldr);
+    for (int r = 0; r < 16; ++r) v[r] += in.r[r];
   }
   if (FORM == FORM_DX && p.act != ACT_NONE) {
-    const int64_t abase = (int64_t)row0 * p.ldaux + col;
-    const int lda = (int)p.ldaux;
     if (p.act == ACT_RELU) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r)
-        if (ok[r]) v[r] = elem_load(p.aux, p.aux_dtype, abase + ro[r] * lda) > 0.0f ? v[r] : 0.0f;
+      for (int r = 0; r < 16; ++r) v[r] = in.a[r] > 0.0f ? v[r] : 0.0f;
     } else {
 #pragma unroll
-      for (int r = 0; r < 16; ++r)
-        if (ok[r]) v[r] *= elem_load(p.aux, p.aux_dtype, abase + ro[r] * lda);   // stashed derivative
+      for (int r = 0; r < 16; ++r) v[r] *= in.a[r];   // stashed derivative
     }
   }
   if (FORM == FORM_DW) {
     float *c = (float *)Cout + cbase;
-    if (has_old) {
+    if (accumulate_dw) {
 #pragma unroll
       for (int r = 0; r < 16; ++r)
-        if (ok[r]) c[ro[r] * ldc] = c_old[r] + v[r];
-    } else if (accumulate_dw) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        if (ok[r]) c[ro[r] * ldc] += v[r];
+        if (ok[r]) c[ro[r] * ldc] = in.a[r] + v[r];
     } else {
 #pragma unroll
       for (int r = 0; r < 16; ++r)
@@ -241,6 +265,30 @@ __device__ __forceinline__ void epilogue_tile(const GemmProb &p, void *Cout, con
 #pragma unroll
     for (int r = 0; r < 16; ++r)
       if (ok[r]) c[ro[r] * ldc] = v[r];
+  }
+}
+
+// all TI x TJ accumulator tiles of a wave (wave tile origin wr0 x wc0), the fetch of tile t + 1
+// issued before tile t is finished
+template <int FORM, bool CHECK, int TI, int TJ>
+__device__ __forceinline__ void epilogue_wave(const GemmProb &p, void *Cout, const f32x16 (&acc)[TI][TJ], int wr0, int wc0,
+                                              int lane, int accumulate_dw) {
+  EpiIn in[2];
+  auto origin = [&](int t, int &row0, int &col) {
+    row0 = wr0 + 32 * (t / TJ) + 4 * (lane >> 5);
+    col = wc0 + 32 * (t % TJ) + (lane & 31);
+  };
+  int row0, col;
+  origin(0, row0, col);
+  epi_fetch<FORM, CHECK>(p, Cout, row0, col, accumulate_dw, in[0]);
+#pragma unroll
+  for (int t = 0; t < TI * TJ; ++t) {
+    if (t + 1 < TI * TJ) {
+      origin(t + 1, row0, col);
+      epi_fetch<FORM, CHECK>(p, Cout, row0, col, accumulate_dw, in[(t + 1) & 1]);
+    }
+    origin(t, row0, col);
+    epi_finish<FORM, CHECK>(p, Cout, acc[t / TJ][t % TJ], row0, col, accumulate_dw, in[t & 1]);
   }
 }
 
@@ -261,8 +309,10 @@ struct TileLds {
 // Every team of a workgroup must call with records of the same K range: the body synchronises with
 // workgroup barriers.  A `local` beyond the record's tiles computes on zeros and stores nothing.
 // SPLIT = false ignores the record's split_k (taken as 1).  RING = k-steps kept in flight in
-// registers (even; 0 picks the default for the tile size).
-template <int FORM, int BM, int BN, bool SPLIT, int RING = 0>
+// registers (even; 0 picks the default for the tile size).  EARLY_OLD (backward-weight): request the
+// old gradient tile before the k-loop instead of in the epilogue -- worth its registers when the
+// contraction is short and the tile's time is mostly that round trip.
+template <int FORM, int BM, int BN, bool SPLIT, int RING = 0, bool EARLY_OLD = false>
 __device__ __forceinline__ void gemm_tile_body(const GemmProb &p, int local, int tid, uint16_t *lds, int accumulate_dw,
                                                const ExtPtrs &ext) {
   constexpr bool A_TR = TileLds<FORM, BM, BN>::A_TR;     // A rows run along the contraction index
@@ -298,11 +348,9 @@ __device__ __forceinline__ void gemm_tile_body(const GemmProb &p, int local, int
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  // backward-weight with accumulation: request the old gradient tile now, so that its latency is
-  // hidden behind the operand fetch and the MFMAs instead of sitting between them and the store
-  const bool c_prefetch = FORM == FORM_DW && accumulate_dw && S == 1;
+  const bool early_old = EARLY_OLD && FORM == FORM_DW && accumulate_dw && Cout != nullptr;
   f32x16 c_old[TI][TJ];
-  if (FORM == FORM_DW && c_prefetch) {
+  if (EARLY_OLD && early_old) {
 #pragma unroll
     for (int i = 0; i < TI; ++i)
 #pragma unroll
@@ -310,12 +358,11 @@ __device__ __forceinline__ void gemm_tile_body(const GemmProb &p, int local, int
         const int col = n0 + wj0 + 32 * j + (lane & 31);
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int row = m0 + wi0 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-          c_old[i][j][r] = (row < p.M && col < p.N) ? ((const float *)p.C)[(int64_t)row * p.ldc + col] : 0.0f;
+          const int row = m0 + wi0 + 32 * i + 4 * (lane >> 5) + epi_row(r);
+          c_old[i][j][r] = (row < p.M && col < p.N) ? ((const float *)Cout)[(int64_t)row * p.ldc + col] : 0.0f;
         }
       }
   }
-
   typedef TileRegs<A_TR ? BK : BM, A_TR ? BM : BK> RegsA;
   typedef TileRegs<B_TR ? BK : BN, B_TR ? BN : BK> RegsB;
   // NS k-steps are kept in flight in registers: the tile consumed at step kt was requested NS-1
@@ -431,18 +478,20 @@ __device__ __forceinline__ void gemm_tile_body(const GemmProb &p, int local, int
   }
   if (Cout == nullptr) return;   // the caller does not want this result (all barriers are behind us)
 
-  // ---- epilogue, one 32 x 32 accumulator tile at a time; tiles inside the matrix skip the bounds checks
-  const bool interior = m0 + BM <= p.M && n0 + BN <= p.N;
+  // ---- epilogue; tiles inside the matrix skip the bounds checks
+  if (EARLY_OLD && early_old) {
 #pragma unroll
-  for (int i = 0; i < TI; ++i)
+    for (int i = 0; i < TI; ++i)
 #pragma unroll
-    for (int j = 0; j < TJ; ++j) {
-      const int col = n0 + wj0 + 32 * j + (lane & 31);
-      const int row0 = m0 + wi0 + 32 * i + 4 * (lane >> 5);
-      const bool has_old = FORM == FORM_DW && c_prefetch;
-      if (interior) epilogue_tile<FORM, false>(p, Cout, acc[i][j], row0, col, accumulate_dw, c_old[i][j], has_old);
-      else epilogue_tile<FORM, true>(p, Cout, acc[i][j], row0, col, accumulate_dw, c_old[i][j], has_old);
-    }
+      for (int j = 0; j < TJ; ++j) {
+        EpiIn in;
+        in.a = c_old[i][j];
+        epi_finish<FORM, true>(p, Cout, acc[i][j], m0 + wi0 + 32 * i + 4 * (lane >> 5), n0 + wj0 + 32 * j + (lane & 31), 1, in);
+      }
+    return;
+  }
+  if (m0 + BM <= p.M && n0 + BN <= p.N) epilogue_wave<FORM, false, TI, TJ>(p, Cout, acc, m0 + wi0, n0 + wj0, lane, accumulate_dw);
+  else epilogue_wave<FORM, true, TI, TJ>(p, Cout, acc, m0 + wi0, n0 + wj0, lane, accumulate_dw);
 }
 
 }  // namespace gpp
