@@ -13,7 +13,9 @@ namespace gpp {
 constexpr int RADIX_BITS = 9;
 constexpr int RADIX = 1 << RADIX_BITS;
 constexpr int SORT_CHUNK = 2048;   // keys per workgroup per pass (256 threads x 8 rounds)
-constexpr int LONG_SEG = 256;      // segments longer than this get a whole workgroup
+constexpr int LONG_SEG = 256;      // slice length of the segments that are summed by whole workgroups
+constexpr int SHORT_MAX = 32;      // segments up to this length are summed by one 16-lane group, serially:
+                                   // the longest serial chain sets that kernel's duration, so it is kept short
 constexpr int LOG_SLOTS = 4;       // backward passes whose touched-row lists are kept for the reset
 
 int emb_sort_chunk() { return SORT_CHUNK; }
@@ -259,6 +261,9 @@ __global__ __launch_bounds__(256) void k_sort_scatter(const EmbProb *__restrict_
 // ------------------------------------------------------------------ segment heads
 __device__ __forceinline__ const int32_t *sorted_keys(const EmbProb &p) { return (p.passes & 1) ? p.keys_a : p.keys_b; }
 __device__ __forceinline__ const int32_t *sorted_pos(const EmbProb &p) { return (p.passes & 1) ? p.pos_a : p.pos_b; }
+// bag id of every sorted position (-1 where the index was out of range), in the key buffer the sort
+// no longer needs: the segment sums then read one array instead of chasing position -> index -> bag
+__device__ __forceinline__ int32_t *sorted_bag(const EmbProb &p) { return (p.passes & 1) ? p.keys_b : p.keys_a; }
 
 // heads per chunk of SORT_CHUNK sorted keys (stored in the first sort_blocks entries of `hist`)
 __global__ __launch_bounds__(256) void k_seg_count(const EmbProb *__restrict__ probs, int slot) {
@@ -273,6 +278,19 @@ __global__ __launch_bounds__(256) void k_seg_count(const EmbProb *__restrict__ p
   for (int e = 0; e < SORT_CHUNK / 256; ++e) {
     const int i = base + e;
     if (i < n_used && (i == 0 || keys[i] != keys[i - 1])) ++s;
+  }
+  {  // the gather list, coalesced: thread t takes positions chunk + t, chunk + t + 256, ...
+    const int32_t *spos = sorted_pos(p);
+    int32_t *sbag = sorted_bag(p);
+#pragma unroll
+    for (int e = 0; e < SORT_CHUNK / 256; ++e) {
+      const int i = blockIdx.x * SORT_CHUNK + e * 256 + threadIdx.x;
+      if (i < n_used) {
+        const int pos = spos[i];
+        const int r = p.indices[pos];
+        sbag[i] = (r >= 0 && r < p.num_rows) ? p.bag_of[pos] : -1;
+      }
+    }
   }
   for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
@@ -341,75 +359,135 @@ __global__ __launch_bounds__(256) void k_seg_write(const EmbProb *__restrict__ p
 }
 
 // ------------------------------------------------------------------ segment sums
-// Sum of the pooled-output gradient rows of sorted positions [lo, hi), in sorted order within each
-// of the wave's 64/LPR lane groups; the groups are then combined in lane order.  Every lane ends up
-// with the same float4 for its columns only in group 0 (the caller uses that one).
-__device__ __forceinline__ float4 segment_partial(const EmbProb &p, const int32_t *spos, int lo, int hi, int lpr) {
-  const int lane = threadIdx.x & 63;
-  const int rpi = 64 / lpr, sub = lane / lpr, c4 = (lane % lpr) * 4;
-  const bool col_ok = c4 < p.dim;
-  float4 acc = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-  for (int base = lo; base < hi; base += 64) {
-    const int cnt = min(64, hi - base);
-    int my_bag = -1;
-    if (lane < cnt) {
-      const int pos = spos[base + lane];
-      const int r = p.indices[pos];
-      if (r >= 0 && r < p.num_rows) my_bag = p.bag_of[pos];
-    }
-#pragma unroll 4
-    for (int j = 0; j < cnt; j += rpi) {
-      const int bag = __shfl(my_bag, min(j + sub, 63), 64);
-      if (j + sub < cnt && bag >= 0 && col_ok) acc = f4_add(acc, load4(p.out, p.out_dtype, (int64_t)bag * p.ld_out + c4));
+// Vector path (dimension a multiple of 4, at most 256): a GROUP of 16 lanes owns one distinct row;
+// lane l of the group holds columns 4 l + 64 k .. +3 for k < KV.  A wave therefore works on four
+// rows at once and every lane has KV independent 16-byte loads in flight per position.
+constexpr int GROUP = 16;
+constexpr int KV_MAX = 4;
+struct RowAcc {
+  float4 v[KV_MAX];
+};
+__device__ __forceinline__ void acc_zero(RowAcc &a) {
+#pragma unroll
+  for (int k = 0; k < KV_MAX; ++k) a.v[k] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+}
+// a += pooled-output gradient row of `bag` (bag < 0: nothing)
+__device__ __forceinline__ void acc_add_bag(RowAcc &a, const EmbProb &p, int bag, int l16) {
+  if (bag < 0) return;
+#pragma unroll
+  for (int k = 0; k < KV_MAX; ++k) {
+    const int c4 = 4 * l16 + 64 * k;
+    if (c4 < p.dim) a.v[k] = f4_add(a.v[k], load4(p.out, p.out_dtype, (int64_t)bag * p.ld_out + c4));
+  }
+}
+// sum over sorted positions lo, lo + stride, ... < hi, in that order, four positions in flight
+__device__ __forceinline__ void acc_positions(RowAcc &a, const EmbProb &p, const int32_t *sbag, int lo, int hi, int stride, int l16) {
+  int q = lo;
+  for (; q + 3 * stride < hi; q += 4 * stride) {
+    const int b0 = sbag[q], b1 = sbag[q + stride], b2 = sbag[q + 2 * stride], b3 = sbag[q + 3 * stride];
+    RowAcc t0, t1;
+    acc_zero(t0);
+    acc_zero(t1);
+    acc_add_bag(a, p, b0, l16);
+    acc_add_bag(t0, p, b1, l16);
+    acc_add_bag(t1, p, b2, l16);
+    // fixed association: ((a + b0) + b1) + b2) + b3, with the loads issued together
+#pragma unroll
+    for (int k = 0; k < KV_MAX; ++k) a.v[k] = f4_add(f4_add(a.v[k], t0.v[k]), t1.v[k]);
+    acc_add_bag(a, p, b3, l16);
+  }
+  for (; q < hi; q += stride) acc_add_bag(a, p, sbag[q], l16);
+}
+// `first`: no backward pass has touched the table since it was cleared, so every row still holds
+// zeros and the sum is stored without reading the row
+__device__ __forceinline__ void row_add(float *row, const RowAcc &a, int dim, int l16, bool first) {
+#pragma unroll
+  for (int k = 0; k < KV_MAX; ++k) {
+    const int c4 = 4 * l16 + 64 * k;
+    if (c4 < dim) {
+      float4 *d = (float4 *)(row + c4);
+      *d = first ? a.v[k] : f4_add(*d, a.v[k]);
     }
   }
-  for (int d = lpr; d < 64; d <<= 1) acc = f4_add(acc, f4_shfl_down(acc, d));
-  return acc;
 }
 
-// one wave per distinct row; rows with more than LONG_SEG positions are queued for k_emb_bwd_long
-__global__ __launch_bounds__(256) void k_emb_bwd_short(const EmbProb *__restrict__ probs, int slot) {
+// a group per distinct row; rows with more than SHORT_MAX positions are cut into slices of LONG_SEG
+// and queued (entries (row id, slice) in consecutive list slots, slice order) for the two kernels below
+__global__ __launch_bounds__(256) void k_emb_bwd_short(const EmbProb *__restrict__ probs, int slot, int first) {
   const EmbProb p = probs[blockIdx.y];
-  const int lane = threadIdx.x & 63;
-  const int u = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int l16 = threadIdx.x & (GROUP - 1);
+  const int u = blockIdx.x * (256 / GROUP) + (threadIdx.x / GROUP);
   if (u >= p.counts[slot * 4 + 1]) return;
   const int lo = p.seg_offsets[u], hi = p.seg_offsets[u + 1];
-  if (hi - lo > LONG_SEG) {
-    if (lane == 0) p.long_list[atomicAdd(&p.counts[slot * 4 + 2], 1)] = u;
+  if (hi - lo > SHORT_MAX) {
+    if (l16 == 0) {
+      const int n_slices = (hi - lo + LONG_SEG - 1) / LONG_SEG;
+      const int base = atomicAdd(&p.counts[slot * 4 + 2], n_slices);
+      for (int sl = 0; sl < n_slices; ++sl) {
+        p.long_list[2 * (base + sl)] = u;
+        p.long_list[2 * (base + sl) + 1] = sl;
+      }
+    }
     return;
   }
-  const int lpr = lanes_per_row(p.dim);
-  const float4 acc = segment_partial(p, sorted_pos(p), lo, hi, lpr);
-  const int c4 = (lane % lpr) * 4;
-  if (lane < lpr && c4 < p.dim) {
-    float4 *d = (float4 *)(p.dtable + (int64_t)p.unique_rows[(int64_t)slot * p.capacity + u] * p.ld_table + c4);
-    *d = f4_add(*d, acc);
-  }
+  RowAcc a;
+  acc_zero(a);
+  acc_positions(a, p, sorted_bag(p), lo, hi, 1, l16);
+  row_add(p.dtable + (int64_t)p.unique_rows[(int64_t)slot * p.capacity + u] * p.ld_table, a, p.dim, l16, first != 0);
 }
 
-// one workgroup of 16 waves per long segment: each wave sums a contiguous slice, slices are
-// combined in order through LDS
-__global__ __launch_bounds__(1024) void k_emb_bwd_long(const EmbProb *__restrict__ probs, int slot) {
-  __shared__ float4 part[16][64];
+// one workgroup of 16 groups per queued slice: group g sums positions g, g + 16, ... of the slice,
+// the 16 partial rows are added in group order through LDS and stored as the slice's partial row
+__global__ __launch_bounds__(256) void k_emb_bwd_long_partial(const EmbProb *__restrict__ probs, int slot) {
+  __shared__ float4 part[256 / GROUP][KV_MAX][GROUP];
   const EmbProb p = probs[blockIdx.y];
   if ((int)blockIdx.x >= p.counts[slot * 4 + 2]) return;
-  const int u = p.long_list[blockIdx.x];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int lo = p.seg_offsets[u], hi = p.seg_offsets[u + 1];
-  const int per = (hi - lo + 15) / 16;
-  const int a = min(hi, lo + wave * per), b = min(hi, a + per);
-  const int lpr = lanes_per_row(p.dim);
-  part[wave][lane] = segment_partial(p, sorted_pos(p), a, b, lpr);
-  __syncthreads();
-  const int c4 = lane * 4;
-  if (wave == 0 && lane < lpr && c4 < p.dim) {
-    float4 acc = part[0][lane];
+  const int u = p.long_list[2 * blockIdx.x], sl = p.long_list[2 * blockIdx.x + 1];
+  const int l16 = threadIdx.x & (GROUP - 1), g = threadIdx.x / GROUP;
+  const int lo = p.seg_offsets[u] + sl * LONG_SEG, hi = min(p.seg_offsets[u + 1], lo + LONG_SEG);
+  RowAcc a;
+  acc_zero(a);
+  acc_positions(a, p, sorted_bag(p), lo + g, hi, 256 / GROUP, l16);
 #pragma unroll
-    for (int w = 1; w < 16; ++w) acc = f4_add(acc, part[w][lane]);
-    float4 *d = (float4 *)(p.dtable + (int64_t)p.unique_rows[(int64_t)slot * p.capacity + u] * p.ld_table + c4);
-    *d = f4_add(*d, acc);
+  for (int k = 0; k < KV_MAX; ++k) part[g][k][l16] = a.v[k];
+  __syncthreads();
+  if (g == 0) {
+    float *dst = p.partial + (int64_t)blockIdx.x * p.ld_table;
+#pragma unroll
+    for (int k = 0; k < KV_MAX; ++k) {
+      const int c4 = 4 * l16 + 64 * k;
+      if (c4 < p.dim) {
+        float4 t = part[0][k][l16];
+#pragma unroll
+        for (int w = 1; w < 256 / GROUP; ++w) t = f4_add(t, part[w][k][l16]);
+        *(float4 *)(dst + c4) = t;
+      }
+    }
   }
 }
+// a group per queued entry; the entry of a row's slice 0 adds that row's slice partials in slice order
+__global__ __launch_bounds__(256) void k_emb_bwd_long_final(const EmbProb *__restrict__ probs, int slot, int first) {
+  const EmbProb p = probs[blockIdx.y];
+  const int e = blockIdx.x * (256 / GROUP) + (threadIdx.x / GROUP);
+  if (e >= p.counts[slot * 4 + 2]) return;
+  const int u = p.long_list[2 * e];
+  if (p.long_list[2 * e + 1] != 0) return;
+  const int l16 = threadIdx.x & (GROUP - 1);
+  const int n_slices = (p.seg_offsets[u + 1] - p.seg_offsets[u] + LONG_SEG - 1) / LONG_SEG;
+  RowAcc a;
+  acc_zero(a);
+  for (int sl = 0; sl < n_slices; ++sl) {
+    const float *src = p.partial + (int64_t)(e + sl) * p.ld_table;
+#pragma unroll
+    for (int k = 0; k < KV_MAX; ++k) {
+      const int c4 = 4 * l16 + 64 * k;
+      if (c4 < p.dim) a.v[k] = f4_add(a.v[k], *(const float4 *)(src + c4));
+    }
+  }
+  row_add(p.dtable + (int64_t)p.unique_rows[(int64_t)slot * p.capacity + u] * p.ld_table, a, p.dim, l16, first != 0);
+}
+// upper bound of queued slices: every segment longer than SHORT_MAX has at most len / LONG_SEG + 1 of them
+int emb_long_entries(int capacity) { return capacity / SHORT_MAX + capacity / LONG_SEG + 2; }
 
 // scalar fallback (dimension not a multiple of 4): one wave per distinct row, a lane per column
 __global__ __launch_bounds__(256) void k_emb_bwd_generic(const EmbProb *__restrict__ probs, int slot) {
@@ -440,10 +518,10 @@ __global__ __launch_bounds__(256) void k_emb_bwd_generic(const EmbProb *__restri
   }
 }
 
-int emb_bwd_num_launches(int max_passes, int vec) { return 2 * max_passes + 2 + (vec ? 2 : 1); }
+int emb_bwd_num_launches(int max_passes, int vec) { return 2 * max_passes + 2 + (vec ? 3 : 1); }
 
 int launch_emb_bwd(const EmbProb *probs, int n, int max_capacity, int max_sort_blocks, int max_passes, int vec,
-                   int slot, hipStream_t s) {
+                   int slot, int first, hipStream_t s) {
   if (n <= 0) return 0;
   for (int pass = 0; pass < max_passes; ++pass) {
     hipLaunchKernelGGL(k_sort_hist, dim3(max_sort_blocks, n), dim3(256), 0, s, probs, pass);
@@ -452,8 +530,11 @@ int launch_emb_bwd(const EmbProb *probs, int n, int max_capacity, int max_sort_b
   hipLaunchKernelGGL(k_seg_count, dim3(max_sort_blocks, n), dim3(256), 0, s, probs, slot);
   hipLaunchKernelGGL(k_seg_write, dim3(max_sort_blocks, n), dim3(256), 0, s, probs, slot);
   if (vec) {
-    hipLaunchKernelGGL(k_emb_bwd_short, dim3((max_capacity + 3) / 4, n), dim3(256), 0, s, probs, slot);
-    hipLaunchKernelGGL(k_emb_bwd_long, dim3(max_capacity / LONG_SEG + 1, n), dim3(1024), 0, s, probs, slot);
+    constexpr int GPB = 256 / GROUP;   // groups per workgroup
+    hipLaunchKernelGGL(k_emb_bwd_short, dim3((max_capacity + GPB - 1) / GPB, n), dim3(256), 0, s, probs, slot, first);
+    const int entries = emb_long_entries(max_capacity);
+    hipLaunchKernelGGL(k_emb_bwd_long_partial, dim3(entries, n), dim3(256), 0, s, probs, slot);
+    hipLaunchKernelGGL(k_emb_bwd_long_final, dim3((entries + GPB - 1) / GPB, n), dim3(256), 0, s, probs, slot, first);
   } else {
     hipLaunchKernelGGL(k_emb_bwd_generic, dim3((max_capacity + 3) / 4, n), dim3(256), 0, s, probs, slot);
   }
@@ -469,19 +550,23 @@ __global__ __launch_bounds__(256) void k_emb_reset(const EmbProb *__restrict__ p
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256)
     d[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 }
-// sparse clear: only the rows listed by the last `slots` backward passes (one wave per listed row)
+// sparse clear: only the rows listed by the last `slots` backward passes (16 lanes per listed row)
 __global__ __launch_bounds__(256) void k_emb_reset_rows(const EmbProb *__restrict__ probs) {
   const EmbProb p = probs[blockIdx.y];
   const int slot = blockIdx.z;
-  const int u = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int u = blockIdx.x * 16 + (threadIdx.x >> 4);
   if (u >= p.counts[slot * 4 + 1]) return;
   float *drow = p.dtable + (int64_t)p.unique_rows[(int64_t)slot * p.capacity + u] * p.ld_table;
-  for (int c = threadIdx.x & 63; c < p.dim; c += 64) drow[c] = 0.0f;
+  if ((p.dim & 3) == 0 && (p.ld_table & 3) == 0) {
+    for (int c = (threadIdx.x & 15) * 4; c < p.dim; c += 64) *(float4 *)(drow + c) = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+  } else {
+    for (int c = threadIdx.x & 15; c < p.dim; c += 16) drow[c] = 0.0f;
+  }
 }
 void launch_emb_reset(const EmbProb *probs, int n, int max_capacity, int slots, hipStream_t s) {
   if (n <= 0) return;
   if (slots <= 0) hipLaunchKernelGGL(k_emb_reset, dim3(1024, n), dim3(256), 0, s, probs);
-  else hipLaunchKernelGGL(k_emb_reset_rows, dim3((max_capacity + 3) / 4, n, slots), dim3(256), 0, s, probs);
+  else hipLaunchKernelGGL(k_emb_reset_rows, dim3((max_capacity + 15) / 16, n, slots), dim3(256), 0, s, probs);
 }
 
 }  // namespace gpp

@@ -119,7 +119,8 @@ struct EmbProb {
   int32_t *unique_rows;    // [log_slots][capacity]: distinct rows of the last backward passes
   int32_t *seg_offsets;    // [capacity+1]
   int32_t *counts;         // [log_slots][4]: n_used, n_unique, n_long, -
-  int32_t *long_list;      // segments longer than the one-wave limit
+  int32_t *long_list;      // [emb_long_entries][2]: (distinct-row id, slice) of segments cut into slices
+  float *partial;          // [emb_long_entries][ld_table]: partial row of each queued slice
   int64_t ld_table, ld_out;
   int32_t n_bags, capacity, dim, num_rows;
   int32_t out_dtype;
@@ -213,12 +214,14 @@ void launch_emb_fwd(const EmbProb *probs, int n, int total_blocks, int vec, Stag
 int emb_fwd_blocks(int n_bags);
 bool emb_vec_supported(const EmbProb &p);
 // sort + segment heads + segment sums into log slot `slot`; returns the number of launches it enqueues
+// `first`: the gradient tables are all zero (no backward since they were cleared): sums are stored, not added
 int launch_emb_bwd(const EmbProb *probs, int n, int max_capacity, int max_sort_blocks, int max_passes, int vec,
-                   int slot, hipStream_t s);
+                   int slot, int first, hipStream_t s);
 int emb_bwd_num_launches(int max_passes, int vec);
 int emb_sort_chunk();
 int emb_radix_bits();
 int emb_long_segment();
+int emb_long_entries(int capacity);
 int emb_log_slots();
 // slots <= 0: clear whole tables; otherwise only the rows logged in slots [0, slots)
 void launch_emb_reset(const EmbProb *probs, int n, int max_capacity, int slots, hipStream_t s);

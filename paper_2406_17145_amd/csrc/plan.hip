@@ -338,7 +338,8 @@ gpp_status_t Plan::analyse(const gpp_stage_desc_t *desc) {
       nd.more.push_back(alloc(SP_SHARED, 1, cap * emb_log_slots(), DT_I32));  // unique rows per log slot
       nd.more.push_back(alloc(SP_SHARED, 1, cap + 1, DT_I32));                // segment offsets
       nd.more.push_back(alloc(SP_SHARED, 1, 4 * emb_log_slots(), DT_I32));    // counts per log slot
-      nd.more.push_back(alloc(SP_SHARED, 1, cap / emb_long_segment() + 2, DT_I32));  // long segments
+      nd.more.push_back(alloc(SP_SHARED, 1, 2 * (int64_t)emb_long_entries((int)cap), DT_I32));       // queued slices of long segments
+      nd.more.push_back(alloc(SP_SHARED, emb_long_entries((int)cap), ld_of(nd.feat), DT_F32));       // their partial rows
       nd.emb_passes = passes;
       nd.emb_sort_blocks = sort_blocks;
     }
@@ -1299,6 +1300,7 @@ void Emitter::backward() {
           e.seg_offsets = (int32_t *)ptr(nd.more[6]);
           e.counts = (int32_t *)ptr(nd.more[7]);
           e.long_list = (int32_t *)ptr(nd.more[8]);
+          e.partial = (float *)ptr(nd.more[9]);
           e.n_bags = (int32_t)pl.micro_batch;
           e.capacity = (int32_t)(pl.micro_batch * d.bag_size);
           e.dim = (int32_t)nd.feat;

@@ -269,7 +269,7 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
         // the rows this pass touches are logged so that the next reset clears only those
         if (st->emb_logged >= emb_log_slots()) st->emb_log_overflow = true;
         const int slot = st->emb_logged < emb_log_slots() ? st->emb_logged : emb_log_slots() - 1;
-        launch_emb_bwd((const EmbProb *)tab, sp.n, sp.a0, sp.a1, sp.a2 & 255, (sp.a2 >> 8) & 1, slot, s);
+        launch_emb_bwd((const EmbProb *)tab, sp.n, sp.a0, sp.a1, sp.a2 & 255, (sp.a2 >> 8) & 1, slot, st->emb_logged == 0 ? 1 : 0, s);
         st->emb_last_slot = slot;
         st->emb_logged++;
         break;
