@@ -176,6 +176,9 @@ void launch_gemm_big(const GemmProb *probs, int n, int total_blocks, int accumul
 bool gemm_big_supported(const GemmProb &p);
 int gemm_big_tile_rows(int maxM, int maxN, int64_t launch_elems);
 int gemm_big_tiles_for(int tile_rows, int M, int N, int *tiles_n);
+// backward-weight for small weight matrices and many rows: 64 x 64 tiles, the contraction split over the waves
+void launch_gemm_dw_ksplit(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, hipStream_t s);
+int gemm_dw_ksplit_blocks(int M, int N);
 // few-row (micro-batch <= 256 rows) forward / backward-data kernel
 void launch_gemm_skinny(const GemmProb *probs, int n, int total_blocks, int form, int row_tiles, int col_tiles,
                         const ExtPtrs &ext, hipStream_t s);

@@ -641,6 +641,25 @@ struct Emitter {
               continue;
             }
           }
+          // backward-weight with a long contraction and too few 128 x 128 tiles to fill the chip:
+          // small tiles, the contraction split over the waves of each workgroup
+          if (use_mfma && form == FORM_DW && !(pl.flags & 2)) {
+            int tiles128 = 0, min_k = 1 << 30;
+            for (auto &r : g) {
+              tiles128 += gemm_mfma_tiles_for(128, r.M, r.N, nullptr);
+              min_k = std::min(min_k, r.K);
+            }
+            if (min_k >= 512 && tiles128 < 192) {
+              int blocks = 0;
+              for (auto &r : g) {
+                r.blk_begin = blocks;
+                r.split_k = 1;
+                blocks += gemm_dw_ksplit_blocks(r.M, r.N);
+              }
+              add_step(K_GEMM_DW_KSPLIT, push_table(g), (int)g.size(), blocks);
+              continue;
+            }
+          }
           int launch_tiles = 0;
           if (use_mfma)
             for (auto &r : g) launch_tiles += gemm_mfma_tiles_for(tile, r.M, r.N, nullptr);

@@ -61,6 +61,7 @@ static int step_tag(const Step &sp, bool backward) {
     case K_GEMM_BIG: return 28 + sp.a1;                    // 28 fwd, 29 dx, 30 dw
     case K_GEMM_SKINNY: return 25 + sp.a1;                 // 25 fwd, 26 dx
     case K_GEMM_BWD_MERGED: return 27;
+    case K_GEMM_DW_KSPLIT: return 31;
     case K_LOSS_FWD_SMALL: return 21;
     case K_GEMM_GENERIC: return backward ? 5 : 4;
     case K_ELT: return backward ? 7 : 6;
@@ -87,7 +88,7 @@ static const char *const kTagNames[GPP_PROFILE_TAGS] = {
     "colsum_bias_grad", "layernorm_fwd", "layernorm_bwd_dx", "layernorm_bwd_params", "attention_fwd", "attention_bwd_dq",
     "attention_bwd_dkv", "meanpool_fwd", "meanpool_bwd", "embedding_fwd", "embedding_bwd_sort_segsum", "interact_fwd",
     "interact_bwd", "loss_fwd", "loss_bwd", "loss_sum", "embedding_grad_clear", "gemm_skinny_fwd", "gemm_skinny_dx", "gemm_bwd_merged_dx_dw", "gemm_big_fwd", "gemm_big_dx", "gemm_big_dw",
-    ""};
+    "gemm_dw_ksplit"};
 
 extern "C" {
 
@@ -240,6 +241,7 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
       case K_GEMM_GENERIC: launch_gemm_generic((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a0, s); break;
       case K_GEMM_MFMA: launch_gemm_mfma((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a1, sp.a2, ext, s); break;
       case K_GEMM_BIG: launch_gemm_big((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a1, sp.a2, ext, s); break;
+      case K_GEMM_DW_KSPLIT: launch_gemm_dw_ksplit((const GemmProb *)tab, sp.n, sp.blocks, accumulate, s); break;
       case K_GEMM_SKINNY: launch_gemm_skinny((const GemmProb *)tab, sp.n, sp.blocks, sp.a1, sp.a2, sp.a0, ext, s); break;
       case K_GEMM_BWD_MERGED: launch_gemm_bwd_merged((const GemmProb *)tab, sp.n, sp.blocks, sp.a2, sp.a1, accumulate, ext, s); break;
       case K_LOSS_FWD_SMALL: launch_loss_fwd_small((const LossProb *)tab, sp.n, loss_out, s); break;
