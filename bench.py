@@ -109,7 +109,18 @@ def other_traffic(wl):
 # HBM bytes per launch of the dominant kernel of each workload, from two rocprofv3 --pmc runs
 # (FETCH_SIZE, then WRITE_SIZE) scaled by what the same counters read for a copy of known size
 # (--copy-calibration); the summaries are kept under profiles/.  None where not measured.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # bytes per launch, averaged over the launches of the kernel family within a step
+    ("candle_uno", "gemm_bwd_merged_dx_dw"): 55.3e6,
+    ("candle_uno", "gemm_skinny_fwd"): 12.1e6,
+    ("hetero", "gemm_bwd_merged_dx_dw"): 145.3e6,
+    ("hetero", "gemm_skinny_fwd"): 70.3e6,
+    ("mmt", "gemm_big_fwd"): 173.0e6,
+    ("mmt", "gemm_big_dx"): 160.9e6,
+    ("mmt", "gemm_big_dw"): 162.2e6,
+    ("dlrm", "embedding_bwd_sort_segsum"): 65.8e6,
+    ("dlrm", "embedding_fwd"): 254.5e6,
+}
 
 
 def main():
@@ -188,18 +199,27 @@ def main():
                              "avg_launch_us": 1e3 * ms / max(launches, 1), "share": ms / total_ms}
         tr = gemm_traffic(wl)
         nm = wl.n_micro
-        alg = {  # algorithmic bytes / flops of each kernel role per STEP
-            "gemm_mfma_fwd": (tr["fwd"][0] * nm, tr["fwd"][1] * nm),
-            "gemm_mfma_dx": (tr["dx"][0] * nm, tr["dx"][1] * nm),
-            "gemm_mfma_dw": (tr["dw_first"][0] + tr["dw"][0] * (nm - 1), tr["dw"][1] * nm),
-            "gemm_skinny_fwd": (tr["fwd"][0] * nm, tr["fwd"][1] * nm),
-            "gemm_skinny_dx": (tr["dx"][0] * nm, tr["dx"][1] * nm),
-            "gemm_bwd_merged_dx_dw": (tr["dx"][0] * nm + tr["dw_first"][0] + tr["dw"][0] * (nm - 1),
-                                      (tr["dx"][1] + tr["dw"][1]) * nm),
-            "gemm_generic_fwd": (tr["fwd"][0] * nm, tr["fwd"][1] * nm),
-            "gemm_generic_bwd": (tr["dx"][0] * nm + tr["dw_first"][0] + tr["dw"][0] * (nm - 1),
-                                 (tr["dx"][1] + tr["dw"][1]) * nm),
+        # algorithmic bytes / flops per STEP of each GEMM role; a role's figure goes to the kernel family
+        # that spends the most time on it (the planner may route a few small layers of a role elsewhere)
+        role_alg = {
+            "fwd": (tr["fwd"][0] * nm, tr["fwd"][1] * nm),
+            "dx": (tr["dx"][0] * nm, tr["dx"][1] * nm),
+            "dw": (tr["dw_first"][0] + tr["dw"][0] * (nm - 1), tr["dw"][1] * nm),
         }
+        role_alg["dx+dw"] = (role_alg["dx"][0] + role_alg["dw"][0], role_alg["dx"][1] + role_alg["dw"][1])
+        role_tags = {
+            "fwd": ["gemm_big_fwd", "gemm_mfma_fwd", "gemm_skinny_fwd", "gemm_generic_fwd"],
+            "dx": ["gemm_big_dx", "gemm_mfma_dx", "gemm_skinny_dx"],
+            "dw": ["gemm_big_dw", "gemm_mfma_dw", "gemm_dw_ksplit"],
+            "dx+dw": ["gemm_bwd_merged_dx_dw", "gemm_generic_bwd"],
+        }
+        alg = {}
+        for role, tags in role_tags.items():
+            present = [t for t in tags if t in kernels]
+            if role == "dx+dw" and present and any(t in kernels for t in role_tags["dx"] + role_tags["dw"]):
+                continue   # split roles also ran: the merged launch holds only part of the traffic
+            if present:
+                alg[max(present, key=lambda t: kernels[t]["ms_per_step"])] = role_alg[role]
         logical = {}
         for name, (by, fl, lg) in other_traffic(wl).items():
             alg[name] = (by * nm, fl * nm)
@@ -225,15 +245,14 @@ def main():
                              "other_fraction_tflops": tfl, "other_fraction_gbs": gbs})
             if dom in logical:
                 roofline["logical_gbs"] = logical[dom] / sec / 1e9
+        else:
+            roofline = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
+                        "traffic": None, "kernel": dom}
         # every kernel with a known algorithmic count: achieved rates beside the durations
         for name, k in kernels.items():
             if name in alg and k["ms_per_step"] > 0:
                 k["algorithmic_gbs"] = alg[name][0] / (k["ms_per_step"] * 1e-3) / 1e9
                 k["algorithmic_tflops"] = alg[name][1] / (k["ms_per_step"] * 1e-3) / 1e12
-
-        else:
-            roofline = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
-                        "traffic": None, "kernel": dom}
 
     # ---- CPU oracle on this host, bounded sample --------------------------------------------
     cpu = None

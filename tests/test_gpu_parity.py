@@ -92,6 +92,19 @@ def test_dlrm_bf16_small():
                 top=(128, 64, 1)))
 
 
+def test_large_tile_gemm_ragged_edges():
+    # many rows AND wide layers: the launches of the hidden layers go to the large-tile kernel
+    # (forward, backward-data and backward-weight), with rows, columns and contraction lengths
+    # that are multiples of no tile edge (1100 = 8*128 + 76, 1096 = 4*256 + 72, 264 = 4*64 + 8)
+    both(W.candle_uno(micro_batch=1100, n_micro=2, widths=(512, 264, 1000, 8), hidden=1096, act="gelu"))
+
+
+def test_backward_weight_contraction_split_ragged():
+    # many rows, small weight matrices: the backward-weight launches split the contraction over the
+    # waves of a workgroup; 600 rows = 9 steps of 64 + 24, matrix edges 200 / 70 / 131 / 1 / 33
+    both(W.candle_uno(micro_batch=600, n_micro=2, widths=(70, 131, 1, 33), hidden=200, act="gelu"))
+
+
 @pytest.mark.parametrize("b", [1, 2, 4, 8, 16, 32, 64, 128])
 def test_config5_hetero_sweep(b):
     both(W.hetero(micro_batch=b))
