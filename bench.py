@@ -130,6 +130,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="candle_uno", choices=["tiny_mlp", "candle_uno", "mmt", "dlrm", "hetero"])
     ap.add_argument("--micro-batch", type=int, default=0, help="override the config's micro-batch size")
+    ap.add_argument("--schedule", default="auto", choices=["auto", "serial", "overlap"],
+                    help="micro-batch schedule of a step: serial = fw_k bw_k in turn on one stream; overlap = fw_{k+1} "
+                         "runs while bw_k runs (two in-flight slots, two streams); auto = overlap when the workload "
+                         "has at least two micro-batches per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-pass", action="store_true", help="skip the event-instrumented second pass")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -149,18 +153,22 @@ def main():
     if args.micro_batch:
         kw["micro_batch"] = args.micro_batch
     wl = W.CONFIGS[args.config](**kw)
-    st = B.Stage(wl.ops, wl.micro_batch, wl.params)
+    from paper_2406_17145_amd.schedule import OverlapSchedule, SerialSchedule
+    overlap = args.schedule == "overlap" or (args.schedule == "auto" and wl.n_micro >= 2)
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=2 if overlap else 1)
     dev_batches = [st.stage_inputs(mb) for mb in wl.batches]       # resident in HBM
-    outs = st.alloc_outputs()
+    outs = [st.alloc_outputs(), st.alloc_outputs()]                # one set per in-flight slot
     gins = st.alloc_grad_inputs()
-    gouts = [torch.zeros_like(o) for o in outs] if outs else None
-    loss = torch.zeros(1, dtype=torch.float32, device=st.dev)
+    gouts = [torch.zeros_like(o) for o in outs[0]] if outs[0] else None
+    losses = [torch.zeros(1, dtype=torch.float32, device=st.dev) for _ in range(2)]
+    serial = SerialSchedule(st)
+    sched = OverlapSchedule(st) if overlap else serial
 
-    def step():
-        st.grad_reset()
-        for mb in dev_batches:
-            st.forward(0, mb, outputs=outs, loss=loss)
-            st.backward(0, grad_outputs=gouts, grad_inputs=gins)
+    def step(schedule=sched):
+        if schedule is serial:
+            schedule.minibatch(dev_batches, outputs=outs[0], grad_outputs=gouts, grad_inputs=gins, losses=losses[:1])
+        else:
+            schedule.minibatch(dev_batches, outputs=outs, grad_outputs=gouts, grad_inputs=gins, losses=losses)
 
     if args.copy_calibration:
         # a copy of known size: reads MIB and writes MIB per launch (torch's elementwise kernel)
@@ -182,6 +190,16 @@ def main():
     st.sync_status()
     samples_per_step = wl.micro_batch * wl.n_micro
     value = args.steps * samples_per_step / dt
+    serial_value = None
+    if overlap:                       # the same steps with the calls in serial order, for reference
+        for _ in range(2):
+            step(serial)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            step(serial)
+        torch.cuda.synchronize()
+        serial_value = args.steps * samples_per_step / (time.perf_counter() - t1)
 
     # ---- instrumented pass: per-kernel durations from HIP events on the launch stream ----
     kernels, roofline = {}, None
@@ -189,7 +207,7 @@ def main():
         st.profile_enable(True)
         k_steps = max(1, min(args.steps, 20))
         for _ in range(k_steps):
-            step()
+            step(serial)            # per-kernel durations are taken with the calls back to back on one stream
         torch.cuda.synchronize()
         prof = st.profile_read()
         st.profile_enable(False)
@@ -286,7 +304,9 @@ def main():
         "dtype": "f32" if args.config == "tiny_mlp" else "bf16", "data": "synthetic",
         "config": {"workload": f"{args.config}: micro-batch {wl.micro_batch} x {wl.n_micro} micro-batches per step",
                    "micro_batch": wl.micro_batch, "micro_batches_per_step": wl.n_micro,
-                   "launches_per_microbatch": st.num_launches(False) + st.num_launches(True)},
+                   "schedule": "overlap: fw_{k+1} concurrent with bw_k, two in-flight slots" if overlap else "serial",
+                   "launches_per_microbatch": st.num_launches(False) + st.num_launches(True),
+                   "serial_schedule_samples_per_s": serial_value},
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
     }
     print(json.dumps(out))

@@ -95,7 +95,12 @@ __global__ __launch_bounds__(256) void k_emb_fwd(const EmbProb *__restrict__ pro
 }
 
 // vector: one wave per bag; LPR lanes read one 16-byte piece of a row each, so a wave has
-// 64/LPR rows in flight per step and four steps unrolled; the sub-groups are combined in lane order
+// 64/LPR rows in flight per load instruction.  FWD_UNROLL such instructions are issued back to back
+// before any of them is consumed (a bag of 20 rows of 128 floats is then two batches: one memory
+// round trip each instead of one per few rows); the loads are unconditional -- a lane without a row
+// reads row 0 and discards it -- because a branch around a load would make the wave wait for the
+// loads before it.  Sums run in index order within a sub-group; the sub-groups are combined in lane order.
+constexpr int FWD_UNROLL = 8;
 __global__ __launch_bounds__(256) void k_emb_fwd_vec(const EmbProb *__restrict__ probs, int n, StageFlags *flags) {
   const int pi = find_prob(probs, n, blockIdx.x);
   const EmbProb p = probs[pi];
@@ -109,6 +114,7 @@ __global__ __launch_bounds__(256) void k_emb_fwd_vec(const EmbProb *__restrict__
   const int lpr = lanes_per_row(p.dim), rpi = 64 / lpr;
   const int sub = lane / lpr, c4 = (lane % lpr) * 4;
   const bool col_ok = c4 < p.dim;
+  const float *col_base = p.table + (col_ok ? c4 : 0);
   float4 acc = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
   for (int base = lo; base < hi; base += 64) {
     const int cnt = min(64, hi - base);
@@ -121,10 +127,19 @@ __global__ __launch_bounds__(256) void k_emb_fwd_vec(const EmbProb *__restrict__
         my = -1;
       }
     }
-#pragma unroll 4
-    for (int j = 0; j < cnt; j += rpi) {
-      const int r = __shfl(my, min(j + sub, 63), 64);
-      if (j + sub < cnt && r >= 0 && col_ok) acc = f4_add(acc, *(const float4 *)(p.table + (int64_t)r * p.ld_table + c4));
+    for (int j0 = 0; j0 < cnt; j0 += rpi * FWD_UNROLL) {
+      float4 v[FWD_UNROLL];
+      bool ok[FWD_UNROLL];
+#pragma unroll
+      for (int u = 0; u < FWD_UNROLL; ++u) {
+        const int j = j0 + u * rpi + sub;
+        const int r = __shfl(my, min(j, 63), 64);
+        ok[u] = j < cnt && r >= 0 && col_ok;
+        v[u] = *(const float4 *)(col_base + (int64_t)(ok[u] ? r : 0) * p.ld_table);
+      }
+#pragma unroll
+      for (int u = 0; u < FWD_UNROLL; ++u)
+        if (ok[u]) acc = f4_add(acc, v[u]);
     }
   }
   for (int d = lpr; d < 64; d <<= 1) acc = f4_add(acc, f4_shfl_down(acc, d));

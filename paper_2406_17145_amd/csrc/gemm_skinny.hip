@@ -66,7 +66,10 @@ struct SkLds {
   static constexpr int BYTES = RED_FLOATS * 4 > NW * WAVE_ELEMS * 2 ? RED_FLOATS * 4 : NW * WAVE_ELEMS * 2;
 };
 
-// `local`: index of this workgroup inside the record (column block major, row blocks neighbours)
+// `local`: index of this workgroup inside the record.  Hardware deals consecutive workgroup ids
+// round-robin over the 8 XCDs (one L2 each): the column blocks of a record are spread over all of them
+// (a wide problem's weights then stream through every L2 and memory channel), while the row blocks
+// of ONE column block, which read the same slice of W, get ids 8 apart and so meet in one L2.
 template <int FORM, int TI, int TJ>
 __device__ __forceinline__ void gemm_skinny_body(const GemmProb &p, int local, unsigned char *lds_raw, const ExtPtrs &ext) {
   typedef SkLds<FORM, TI, TJ> L;
@@ -74,9 +77,16 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmProb &p, int local, u
   float *red = (float *)lds_raw;           // after the k-loop: NW/2 BM x BN fp32 buffers
   void *Cout = result_ptr(p, ext);
 
-  const int m_blocks = (p.M + BM - 1) / BM;                      // row blocks of one column block are neighbours
-  const int n0 = (local / m_blocks) * BN;
-  const int m0 = (local % m_blocks) * BM;
+  const int m_blocks = (p.M + BM - 1) / BM, n_blocks = (p.N + BN - 1) / BN;
+  int cb, rb;                      // column block, row block
+  {
+    const int grp = local / (8 * m_blocks), r = local - grp * 8 * m_blocks;
+    const int cols_here = min(8, n_blocks - 8 * grp);            // the last group may hold fewer than 8 column blocks
+    cb = 8 * grp + r % cols_here;
+    rb = r / cols_here;
+  }
+  const int n0 = cb * BN;
+  const int m0 = rb * BM;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 31, h = lane >> 5;
   // operand descriptors: A = X or dZ [M x K]; B = W, [N x K] forward, [K x N] backward-data

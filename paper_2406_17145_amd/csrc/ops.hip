@@ -374,6 +374,39 @@ __device__ __forceinline__ float sigmoid_f(float y) {
   return y >= 0.0f ? 1.0f / (1.0f + e) : e / (1.0f + e);
 }
 
+// eight consecutive elements starting at element index i (a multiple of 8 from a 16-byte aligned base)
+__device__ __forceinline__ void load8_as_f32(const void *base, int32_t dtype, int64_t i, float (&v)[8]) {
+  if (dtype == DT_BF16) {
+    const uint4 u = *(const uint4 *)((const uint16_t *)base + i);
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      v[2 * e] = __uint_as_float(w[e] << 16);
+      v[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
+    }
+  } else {
+    const float4 a = *(const float4 *)((const float *)base + i), b = *(const float4 *)((const float *)base + i + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+}
+__device__ __forceinline__ void store8_from_f32(void *base, int32_t dtype, int64_t i, const float (&v)[8]) {
+  if (dtype == DT_BF16) {
+    uint4 u;
+    u.x = (uint32_t)f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16);
+    u.y = (uint32_t)f32_to_bf16_bits(v[2]) | ((uint32_t)f32_to_bf16_bits(v[3]) << 16);
+    u.z = (uint32_t)f32_to_bf16_bits(v[4]) | ((uint32_t)f32_to_bf16_bits(v[5]) << 16);
+    u.w = (uint32_t)f32_to_bf16_bits(v[6]) | ((uint32_t)f32_to_bf16_bits(v[7]) << 16);
+    *(uint4 *)((uint16_t *)base + i) = u;
+  } else {
+    *(float4 *)((float *)base + i) = make_float4(v[0], v[1], v[2], v[3]);
+    *(float4 *)((float *)base + i + 4) = make_float4(v[4], v[5], v[6], v[7]);
+  }
+}
+// MSE / BCE rows can be read eight columns at a time: whole chunks, aligned rows
+__device__ __forceinline__ bool loss_row_vec_ok(const LossProb &p) {
+  return (p.cols & 7) == 0 && (p.ld_y & 7) == 0 && (p.ld_t & 7) == 0 && (((uintptr_t)p.y | (uintptr_t)p.target) & 15) == 0;
+}
+
 // four rows per workgroup (one wave each); every workgroup writes one partial sum, already scaled
 int loss_fwd_blocks(const LossProb &p) { return (p.rows + 3) / 4; }
 __global__ __launch_bounds__(256) void k_loss_fwd(const LossProb *__restrict__ probs, int n) {
@@ -397,13 +430,33 @@ __global__ __launch_bounds__(256) void k_loss_fwd(const LossProb *__restrict__ p
       if (lane == 0 && lab >= 0 && lab < p.cols) acc = (m + __logf(se)) - load_as_f32(p.y, p.y_dtype, yo + lab);
     } else {
       const float *t = (const float *)p.target + (int64_t)r * p.ld_t;
-      for (int c = lane; c < p.cols; c += 64) {
-        float y = load_as_f32(p.y, p.y_dtype, yo + c);
-        if (p.kind == 9) {
-          float d = y - t[c];
-          acc += d * d;
-        } else {
-          acc += softplus_f(y) - t[c] * y;
+      if (loss_row_vec_ok(p)) {
+        // eight consecutive columns per lane and step, 16-byte loads, the steps unrolled so that a
+        // row's loads are in flight together
+#pragma unroll 4
+        for (int c = 8 * lane; c < p.cols; c += 512) {
+          float y[8], tv[8];
+          load8_as_f32(p.y, p.y_dtype, yo + c, y);
+          load8_as_f32(t, DT_F32, c, tv);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            if (p.kind == 9) {
+              const float d = y[e] - tv[e];
+              acc += d * d;
+            } else {
+              acc += softplus_f(y[e]) - tv[e] * y[e];
+            }
+          }
+        }
+      } else {
+        for (int c = lane; c < p.cols; c += 64) {
+          float y = load_as_f32(p.y, p.y_dtype, yo + c);
+          if (p.kind == 9) {
+            float d = y - t[c];
+            acc += d * d;
+          } else {
+            acc += softplus_f(y) - t[c] * y;
+          }
         }
       }
     }
@@ -497,10 +550,22 @@ __global__ __launch_bounds__(256) void k_loss_bwd(const LossProb *__restrict__ p
     }
   } else {
     const float *t = (const float *)p.target + (int64_t)r * p.ld_t;
-    for (int c = lane; c < p.cols; c += 64) {
-      float y = load_as_f32(p.y, p.y_dtype, yo + c);
-      float g = p.kind == 9 ? 2.0f * p.scale * (y - t[c]) : p.scale * (sigmoid_f(y) - t[c]);
-      store_from_f32(p.dy, p.dy_dtype, go + c, g);
+    if (loss_row_vec_ok(p) && (p.ld_dy & 7) == 0 && ((uintptr_t)p.dy & 15) == 0) {
+#pragma unroll 4
+      for (int c = 8 * lane; c < p.cols; c += 512) {
+        float y[8], tv[8], g[8];
+        load8_as_f32(p.y, p.y_dtype, yo + c, y);
+        load8_as_f32(t, DT_F32, c, tv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) g[e] = p.kind == 9 ? 2.0f * p.scale * (y[e] - tv[e]) : p.scale * (sigmoid_f(y[e]) - tv[e]);
+        store8_from_f32(p.dy, p.dy_dtype, go + c, g);
+      }
+    } else {
+      for (int c = lane; c < p.cols; c += 64) {
+        float y = load_as_f32(p.y, p.y_dtype, yo + c);
+        float g = p.kind == 9 ? 2.0f * p.scale * (y - t[c]) : p.scale * (sigmoid_f(y) - t[c]);
+        store_from_f32(p.dy, p.dy_dtype, go + c, g);
+      }
     }
   }
 }

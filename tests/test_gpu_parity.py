@@ -114,6 +114,34 @@ def test_config2_candle_uno_full():
     both(W.candle_uno())
 
 
+def test_config2_overlapped_schedule_matches_serial_and_oracle():
+    # the launch configuration bench.py times: fw_{k+1} on one stream while bw_k runs on another, two
+    # stash slots.  Backward calls stay in micro-batch order, so the accumulated gradients must be
+    # bit-identical to the serial order, and they must match the oracle like the serial run does.
+    import torch
+    from paper_2406_17145_amd.schedule import OverlapSchedule
+    wl = W.candle_uno()
+    print(f"[case] {wl.name} overlapped schedule, two slots", flush=True)
+    _, g_serial = run_gpu(wl)
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=2)
+    dev_batches = [st.stage_inputs(mb) for mb in wl.batches]
+    losses = [torch.zeros(1, dtype=torch.float32, device=st.dev) for _ in wl.batches]
+    gins = st.alloc_grad_inputs()
+    sched = OverlapSchedule(st)
+    for _ in range(3):                 # repeated mini-batches: events and slots are reused
+        sched.minibatch(dev_batches, outputs=[[], []], grad_inputs=gins, losses=losses)
+    st.sync_status()
+    g_overlap = st.grads_numpy()
+    for i in g_serial:
+        for k in g_serial[i]:
+            assert np.array_equal(g_serial[i][k], g_overlap[i][k]), (i, k)
+    ora_stage, ora_res = run_oracle(wl)
+    for j, (ost, _) in enumerate(ora_res):
+        got = float(losses[j].cpu()[0])
+        assert abs(got - ost.loss) <= wl.tol * abs(ost.loss), (j, got, ost.loss)
+    st.close()
+
+
 def test_config3_mmt_full():
     both(W.mmt())
 
