@@ -1,20 +1,21 @@
 // Branch-grouped bf16 GEMM for problems with many rows AND many columns (the transformer and MLP
-// stacks at full micro-batch): large output tiles so that the matrix cores, not the LDS or the
-// L1 <-> L2 path, set the pace.
+// stacks at full micro-batch), on v_mfma_f32_32x32x16_bf16 with fp32 accumulation.  Two kernels:
 //
-// Eight waves (512 threads) share a 256 x 256 (or 128 x 256) output tile as a 2 x 4 grid of wave
-// tiles of 128 x 64 (64 x 64) elements = 4 x 2 (2 x 2) MFMA tiles of 32 x 32.  Per 16-wide
-// contraction chunk a wave reads 6 KB (4 KB) of operand fragments from LDS for 8 (4) MFMAs, which
-// keeps the LDS at well under half of its 256 B/clk while two waves per SIMD take turns on the
-// matrix pipe and hide each other's LDS and barrier waits.
+// k_gemm_big   eight waves (512 threads) share a 256 x 256 (or 128 x 256) output tile as a 2 x 4 grid
+//              of wave tiles of 128 x 64 (64 x 64) elements.  Per 16-wide contraction chunk a wave reads
+//              6 KB (4 KB) of operand fragments from LDS for 8 (4) MFMAs.  One workgroup per compute
+//              unit (the double-buffered tiles fill the LDS), so prologue and epilogue of a tile are
+//              exposed: best when the launch has a whole number of tiles per compute unit.
+// k_gemm_mid   four waves (256 threads), 128 x 128 tile, ONE LDS buffer (37 KB) and a register
+//              budget of three waves per SIMD, so three workgroups share a compute unit and one
+//              workgroup's loads, barriers and epilogue hide behind the others' MFMAs.  Best when the
+//              large tiles would leave compute units idle (few tiles) or quantise badly.
 //
 // A k-step is 64 contraction elements, so a k-contiguous operand row contributes one whole 128-byte
-// cache line per step (with 32 every line was fetched from L2 twice, half used each time).
-// Operands come from memory through buffer loads (out-of-range rows read as zero without a branch;
-// a chunk beyond the contraction length is steered out of range), are held NS k-steps ahead in
-// registers and go through a double-buffered LDS tile.  The three forms and the two LDS layouts
-// (k-contiguous rows read with b128, contraction-major rows read with the transposing read) are
-// those of the smaller tile kernel.
+// cache line per step.  Operands come from memory through buffer loads (out-of-range rows read as
+// zero without a branch; a chunk beyond the contraction length is steered out of range), wait in
+// registers and go through LDS.  The three forms and the two LDS layouts (k-contiguous rows read
+// with b128, contraction-major rows read with the transposing read) are those of the smaller tile kernel.
 #include "gemm_tile_body.h"
 
 namespace gpp {
@@ -22,62 +23,63 @@ namespace gpp {
 constexpr int GB_BK = 64;           // contraction elements per k-step
 constexpr int GB_KST = GB_BK + 8;   // LDS row stride of k-contiguous tiles: 144-byte rows, conflict-free b128 reads
 
-template <int FORM, int WTM, int WTN>
+// tile geometry: WGM x WGN waves, each WTM x WTN MFMA tiles of 32 x 32; LDS buffers (1 or 2)
+template <int FORM, int WGM, int WGN, int WTM, int WTN, int BUFS>
 struct BigCfg {
-  static constexpr int WGM = 2, WGN = 4, NW = 8, THREADS = 512;
+  static constexpr int NW = WGM * WGN, THREADS = 64 * NW;
   static constexpr int BM = 32 * WTM * WGM, BN = 32 * WTN * WGN;
   static constexpr bool A_TR = FORM == FORM_DW, B_TR = FORM != FORM_FWD;
   static constexpr int A_ELEMS = A_TR ? GB_BK * (BM + PAD_TR) : BM * GB_KST;
   static constexpr int B_ELEMS = B_TR ? GB_BK * (BN + PAD_TR) : BN * GB_KST;
-  static constexpr int LDS_ELEMS = 2 * (A_ELEMS + B_ELEMS);
+  static constexpr int LDS_ELEMS = BUFS * (A_ELEMS + B_ELEMS);
   static_assert(LDS_ELEMS * 2 <= 160 * 1024, "tile does not fit the LDS");
 };
 
-// one k-step of one operand in registers: EXT rows/columns of the tile, 16-byte chunks, 512 threads
-template <int EXT>
+// one k-step of one operand in registers: EXT rows/columns of the tile, 16-byte chunks, THREADS threads
+template <int EXT, int THREADS>
 struct BigRegs {
-  static constexpr int PER_THREAD = EXT * GB_BK / 8 / 512;
+  static constexpr int PER_THREAD = EXT * GB_BK / 8 / THREADS;
   u32x4 v[PER_THREAD];
 };
 
 // k-contiguous operand: tile rows [r0, r0 + EXT) x k [k0, k0 + 64); eight lanes read one 128-byte row
 // segment.  Rows beyond the buffer read zero, chunks at k >= k_lim are steered out of range (k_lim
 // is a multiple of 8).
-template <int EXT>
-__device__ __forceinline__ void big_fetch_kmajor(BigRegs<EXT> &t, __amdgpu_buffer_rsrc_t rs, int64_t ld, int r0, int k0,
+template <int EXT, int THREADS>
+__device__ __forceinline__ void big_fetch_kmajor(BigRegs<EXT, THREADS> &t, __amdgpu_buffer_rsrc_t rs, int64_t ld, int r0, int k0,
                                                  int k_lim, int tid) {
 #pragma unroll
-  for (int q = 0; q < BigRegs<EXT>::PER_THREAD; ++q) {
-    const int row = r0 + (tid >> 3) + 64 * q, k = k0 + (tid & 7) * 8;
+  for (int q = 0; q < BigRegs<EXT, THREADS>::PER_THREAD; ++q) {
+    const int row = r0 + (tid >> 3) + (THREADS / 8) * q, k = k0 + (tid & 7) * 8;
     // branch-free (a branch here makes the compiler wait for earlier loads between the loads)
     const uint32_t oob = (uint32_t)-(int32_t)(k >= k_lim) & OOB_OFFSET;
     const uint32_t off = (uint32_t)(((int64_t)row * ld + k) * 2) | oob;
     t.v[q] = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0);
   }
 }
-template <int EXT>
-__device__ __forceinline__ void big_store_kmajor(const BigRegs<EXT> &t, uint16_t *lds, int tid) {
+template <int EXT, int THREADS>
+__device__ __forceinline__ void big_store_kmajor(const BigRegs<EXT, THREADS> &t, uint16_t *lds, int tid) {
 #pragma unroll
-  for (int q = 0; q < BigRegs<EXT>::PER_THREAD; ++q)
-    *(u32x4 *)(lds + ((tid >> 3) + 64 * q) * GB_KST + (tid & 7) * 8) = t.v[q];
+  for (int q = 0; q < BigRegs<EXT, THREADS>::PER_THREAD; ++q)
+    *(u32x4 *)(lds + ((tid >> 3) + (THREADS / 8) * q) * GB_KST + (tid & 7) * 8) = t.v[q];
 }
 // contraction-major operand: rows k [k0, k0 + 64) x columns [c0, c0 + EXT); rows beyond the buffer
 // (k >= contraction length) read zero; columns beyond the matrix only feed outputs that are never stored
-template <int EXT>
-__device__ __forceinline__ void big_fetch_tr(BigRegs<EXT> &t, __amdgpu_buffer_rsrc_t rs, int64_t ld, int k0, int c0,
+template <int EXT, int THREADS>
+__device__ __forceinline__ void big_fetch_tr(BigRegs<EXT, THREADS> &t, __amdgpu_buffer_rsrc_t rs, int64_t ld, int k0, int c0,
                                              int tid) {
-  constexpr int CPR = EXT / 8, RPP = 512 / CPR;   // chunks per row, rows per pass
+  constexpr int CPR = EXT / 8, RPP = THREADS / CPR;   // chunks per row, rows per pass
 #pragma unroll
-  for (int q = 0; q < BigRegs<EXT>::PER_THREAD; ++q) {
+  for (int q = 0; q < BigRegs<EXT, THREADS>::PER_THREAD; ++q) {
     const int row = k0 + tid / CPR + RPP * q, col = c0 + (tid % CPR) * 8;
     t.v[q] = __builtin_amdgcn_raw_buffer_load_b128(rs, (uint32_t)(((int64_t)row * ld + col) * 2), 0, 0);
   }
 }
-template <int EXT>
-__device__ __forceinline__ void big_store_tr(const BigRegs<EXT> &t, uint16_t *lds, int tid) {
-  constexpr int CPR = EXT / 8, RPP = 512 / CPR;
+template <int EXT, int THREADS>
+__device__ __forceinline__ void big_store_tr(const BigRegs<EXT, THREADS> &t, uint16_t *lds, int tid) {
+  constexpr int CPR = EXT / 8, RPP = THREADS / CPR;
 #pragma unroll
-  for (int q = 0; q < BigRegs<EXT>::PER_THREAD; ++q)
+  for (int q = 0; q < BigRegs<EXT, THREADS>::PER_THREAD; ++q)
     *(u32x4 *)(lds + (tid / CPR + RPP * q) * (EXT + PAD_TR) + (tid % CPR) * 8) = t.v[q];
 }
 
@@ -87,30 +89,43 @@ __device__ __forceinline__ bf16x8 big_frag_kmajor(const uint16_t *lds, int row0,
   return *(const bf16x8 *)(lds + (row0 + (l & 31)) * GB_KST + k0 + 8 * (l >> 5));
 }
 
-template <int FORM, int WTM, int WTN, int NS>
-__global__ __launch_bounds__(512) void k_gemm_big(const GemmProb *__restrict__ probs, int n, int total_blocks,
-                                                  int accumulate_dw, ExtPtrs ext) {
-  typedef BigCfg<FORM, WTM, WTN> C;
-  constexpr int BM = C::BM, BN = C::BN;
-  constexpr bool A_TR = C::A_TR, B_TR = C::B_TR;
-  __shared__ __attribute__((aligned(16))) uint16_t lds[C::LDS_ELEMS];
-  uint16_t *lds_a[2] = {lds, lds + C::A_ELEMS};
-  uint16_t *lds_b[2] = {lds + 2 * C::A_ELEMS, lds + 2 * C::A_ELEMS + C::B_ELEMS};
-
-  // XCD-aware spreading: consecutive workgroup ids go round-robin over the 8 XCDs; give each XCD one
-  // contiguous range of tiles instead, so that neighbours share operand panels in one L2
+// what every tile kernel of this file does first: XCD-aware spreading (consecutive workgroup ids go
+// round-robin over the 8 XCDs; give each XCD one contiguous range of tiles instead, so that
+// neighbours share operand panels in one L2), then (record, tile) from the records' prefix sums
+struct BigTile {
+  int pi, m0, n0;
+};
+template <int BM, int BN>
+__device__ __forceinline__ BigTile big_locate(const GemmProb *__restrict__ probs, int n, int total_blocks) {
   int bid = blockIdx.x;
   {
     const int xcd = bid & 7, idx = bid >> 3, per = total_blocks >> 3, rem = total_blocks & 7;
     bid = xcd * per + min(xcd, rem) + idx;
   }
-  const int pi = find_prob(probs, n, bid);
-  const GemmProb p = probs[pi];
-  const int tile = bid - p.blk_begin;
-  const int tiles_m = cdiv(p.M, BM);
-  const int m0 = (tile % tiles_m) * BM, n0 = (tile / tiles_m) * BN;   // consecutive tiles share the B panel
+  BigTile t;
+  t.pi = find_prob(probs, n, bid);
+  const int tile = bid - probs[t.pi].blk_begin;
+  const int tiles_m = cdiv(probs[t.pi].M, BM);
+  t.m0 = (tile % tiles_m) * BM;          // consecutive tiles share the B panel
+  t.n0 = (tile / tiles_m) * BN;
+  return t;
+}
+
+// k-loop + bias gradient + epilogue of one output tile.  BUFS = 2: LDS double buffer and a ring of NS
+// k-steps in registers (one barrier per step).  BUFS = 1: one LDS buffer, the next k-step waits in
+// registers while the current one is multiplied (two barriers per step; other workgroups on the
+// compute unit fill the gaps).
+template <int FORM, int WGM, int WGN, int WTM, int WTN, int BUFS, int NS>
+__device__ __forceinline__ void big_tile_body(const GemmProb &p, int m0, int n0, uint16_t *lds, int accumulate_dw,
+                                              const ExtPtrs &ext) {
+  typedef BigCfg<FORM, WGM, WGN, WTM, WTN, BUFS> C;
+  constexpr int BM = C::BM, BN = C::BN, THREADS = C::THREADS;
+  constexpr bool A_TR = C::A_TR, B_TR = C::B_TR;
+  static_assert(BUFS == 1 || NS % 2 == 0, "the LDS double buffer alternates with the ring slot");
+  uint16_t *lds_a[2] = {lds, lds + (BUFS - 1) * C::A_ELEMS};
+  uint16_t *lds_b[2] = {lds + BUFS * C::A_ELEMS, lds + BUFS * C::A_ELEMS + (BUFS - 1) * C::B_ELEMS};
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int wi0 = (wave >> 2) * (32 * WTM), wj0 = (wave & 3) * (32 * WTN);
+  const int wi0 = (wave / WGN) * (32 * WTM), wj0 = (wave % WGN) * (32 * WTN);
 
   // operand buffers: rows beyond the matrix read as zero
   //   FWD: A = X [M x K],  B = W [N x K]      DX: A = dZ [M x K],  B = W [K x N]
@@ -126,61 +141,81 @@ __global__ __launch_bounds__(512) void k_gemm_big(const GemmProb *__restrict__ p
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  BigRegs<BM> ra[NS];
-  BigRegs<BN> rb[NS];
-  auto fetch = [&](BigRegs<BM> &xa, BigRegs<BN> &xb, int k0) {
-    if (A_TR) big_fetch_tr<BM>(xa, rs_a, p.lda, k0, m0, tid);
-    else      big_fetch_kmajor<BM>(xa, rs_a, p.lda, m0, k0, p.K, tid);
-    if (B_TR) big_fetch_tr<BN>(xb, rs_b, p.ldb, k0, n0, tid);
-    else      big_fetch_kmajor<BN>(xb, rs_b, p.ldb, n0, k0, p.K, tid);
+  typedef BigRegs<BM, THREADS> RegsA;
+  typedef BigRegs<BN, THREADS> RegsB;
+  RegsA ra[NS];
+  RegsB rb[NS];
+  auto fetch = [&](RegsA &xa, RegsB &xb, int k0) {
+    if (A_TR) big_fetch_tr<BM, THREADS>(xa, rs_a, p.lda, k0, m0, tid);
+    else      big_fetch_kmajor<BM, THREADS>(xa, rs_a, p.lda, m0, k0, p.K, tid);
+    if (B_TR) big_fetch_tr<BN, THREADS>(xb, rs_b, p.ldb, k0, n0, tid);
+    else      big_fetch_kmajor<BN, THREADS>(xb, rs_b, p.ldb, n0, k0, p.K, tid);
   };
-  auto to_lds = [&](const BigRegs<BM> &xa, const BigRegs<BN> &xb, int buf) {
-    if (A_TR) big_store_tr<BM>(xa, lds_a[buf], tid);
-    else      big_store_kmajor<BM>(xa, lds_a[buf], tid);
-    if (B_TR) big_store_tr<BN>(xb, lds_b[buf], tid);
-    else      big_store_kmajor<BN>(xb, lds_b[buf], tid);
+  auto to_lds = [&](const RegsA &xa, const RegsB &xb, int buf) {
+    if (A_TR) big_store_tr<BM, THREADS>(xa, lds_a[buf], tid);
+    else      big_store_kmajor<BM, THREADS>(xa, lds_a[buf], tid);
+    if (B_TR) big_store_tr<BN, THREADS>(xb, lds_b[buf], tid);
+    else      big_store_kmajor<BN, THREADS>(xb, lds_b[buf], tid);
+  };
+  auto multiply = [&](int buf) {
+#pragma unroll
+    for (int kc = 0; kc < GB_BK; kc += 16) {
+      bf16x8 a[WTM], b[WTN];
+#pragma unroll
+      for (int i = 0; i < WTM; ++i)
+        a[i] = A_TR ? frag_tr<BM>(lds_a[buf], wi0 + 32 * i, kc) : big_frag_kmajor(lds_a[buf], wi0 + 32 * i, kc);
+#pragma unroll
+      for (int j = 0; j < WTN; ++j)
+        b[j] = B_TR ? frag_tr<BN>(lds_b[buf], wj0 + 32 * j, kc) : big_frag_kmajor(lds_b[buf], wj0 + 32 * j, kc);
+#pragma unroll
+      for (int i = 0; i < WTM; ++i)
+#pragma unroll
+        for (int j = 0; j < WTN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
   };
 
   // backward-weight tiles of the first column block also sum the rows of dZ^T they stream: the bias
   // gradient db[n] = sum_m dZ[m,n] comes out of the same launch
-  constexpr int BGROUPS = 512 / BM, BROWS = GB_BK / BGROUPS;
+  constexpr int BGROUPS = THREADS / BM, BROWS = GB_BK / BGROUPS;
   const bool do_bias = FORM == FORM_DW && p.bias != nullptr && n0 == 0;
   float bsum = 0.0f;
+  auto bias_rows = [&](int buf) {
+    if (FORM == FORM_DW && do_bias) {
+      const uint16_t *la = lds_a[buf] + (tid / BM) * BROWS * (BM + PAD_TR) + (tid % BM);
+#pragma unroll
+      for (int rr = 0; rr < BROWS; ++rr) bsum += bf16_bits_to_f32(la[rr * (BM + PAD_TR)]);
+    }
+  };
 
   const int nk = cdiv(p.K, GB_BK);
+  if (BUFS == 2) {
 #pragma unroll
-  for (int u = 0; u < NS - 1; ++u)
-    if (u < nk) fetch(ra[u], rb[u], u * GB_BK);
-  to_lds(ra[0], rb[0], 0);
-  __syncthreads();
-  for (int kt0 = 0; kt0 < nk; kt0 += NS) {
+    for (int u = 0; u < NS - 1; ++u)
+      if (u < nk) fetch(ra[u], rb[u], u * GB_BK);
+    to_lds(ra[0], rb[0], 0);
+    __syncthreads();
+    for (int kt0 = 0; kt0 < nk; kt0 += NS) {
 #pragma unroll
-    for (int u = 0; u < NS; ++u) {
-      const int kt = kt0 + u;
-      if (kt >= nk) break;
-      const int cur = u & 1;   // NS is even: the LDS buffer of step kt is kt & 1 = u & 1
-      // ring slot (u + NS - 1) % NS was copied to LDS one step ago: refill it with step kt + NS - 1
-      if (kt + NS - 1 < nk) fetch(ra[(u + NS - 1) % NS], rb[(u + NS - 1) % NS], (kt + NS - 1) * GB_BK);
-#pragma unroll
-      for (int kc = 0; kc < GB_BK; kc += 16) {
-        bf16x8 a[WTM], b[WTN];
-#pragma unroll
-        for (int i = 0; i < WTM; ++i)
-          a[i] = A_TR ? frag_tr<BM>(lds_a[cur], wi0 + 32 * i, kc) : big_frag_kmajor(lds_a[cur], wi0 + 32 * i, kc);
-#pragma unroll
-        for (int j = 0; j < WTN; ++j)
-          b[j] = B_TR ? frag_tr<BN>(lds_b[cur], wj0 + 32 * j, kc) : big_frag_kmajor(lds_b[cur], wj0 + 32 * j, kc);
-#pragma unroll
-        for (int i = 0; i < WTM; ++i)
-#pragma unroll
-          for (int j = 0; j < WTN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+      for (int u = 0; u < NS; ++u) {
+        const int kt = kt0 + u;
+        if (kt >= nk) break;
+        const int cur = u & 1;   // NS is even: the LDS buffer of step kt is kt & 1 = u & 1
+        // ring slot (u + NS - 1) % NS was copied to LDS one step ago: refill it with step kt + NS - 1
+        if (kt + NS - 1 < nk) fetch(ra[(u + NS - 1) % NS], rb[(u + NS - 1) % NS], (kt + NS - 1) * GB_BK);
+        multiply(cur);
+        bias_rows(cur);
+        if (kt + 1 < nk) to_lds(ra[(u + 1) % NS], rb[(u + 1) % NS], cur ^ 1);
+        __syncthreads();
       }
-      if (FORM == FORM_DW && do_bias) {
-        const uint16_t *la = lds_a[cur] + (tid / BM) * BROWS * (BM + PAD_TR) + (tid % BM);
-#pragma unroll
-        for (int rr = 0; rr < BROWS; ++rr) bsum += bf16_bits_to_f32(la[rr * (BM + PAD_TR)]);
-      }
-      if (kt + 1 < nk) to_lds(ra[(u + 1) % NS], rb[(u + 1) % NS], cur ^ 1);
+    }
+  } else {
+    fetch(ra[0], rb[0], 0);
+    for (int kt = 0; kt < nk; ++kt) {
+      to_lds(ra[0], rb[0], 0);
+      __syncthreads();
+      if (kt + 1 < nk) fetch(ra[0], rb[0], (kt + 1) * GB_BK);
+      multiply(0);
+      bias_rows(0);
       __syncthreads();
     }
   }
@@ -205,8 +240,29 @@ __global__ __launch_bounds__(512) void k_gemm_big(const GemmProb *__restrict__ p
   else epilogue_wave<FORM, true, WTM, WTN>(p, Cout, acc, m0 + wi0, n0 + wj0, lane, accumulate_dw);
 }
 
+template <int FORM, int WTM, int WTN, int NS>
+__global__ __launch_bounds__(512) void k_gemm_big(const GemmProb *__restrict__ probs, int n, int total_blocks,
+                                                  int accumulate_dw, ExtPtrs ext) {
+  typedef BigCfg<FORM, 2, 4, WTM, WTN, 2> C;
+  __shared__ __attribute__((aligned(16))) uint16_t lds[C::LDS_ELEMS];
+  const BigTile t = big_locate<C::BM, C::BN>(probs, n, total_blocks);
+  const GemmProb p = probs[t.pi];
+  big_tile_body<FORM, 2, 4, WTM, WTN, 2, NS>(p, t.m0, t.n0, lds, accumulate_dw, ext);
+}
+
+// 128 x 128 tile, 2 x 2 waves of 64 x 64, one LDS buffer, three waves per SIMD
+template <int FORM>
+__global__ __launch_bounds__(256, 3) void k_gemm_mid(const GemmProb *__restrict__ probs, int n, int total_blocks,
+                                                     int accumulate_dw, ExtPtrs ext) {
+  typedef BigCfg<FORM, 2, 2, 2, 2, 1> C;
+  __shared__ __attribute__((aligned(16))) uint16_t lds[C::LDS_ELEMS];
+  const BigTile t = big_locate<C::BM, C::BN>(probs, n, total_blocks);
+  const GemmProb p = probs[t.pi];
+  big_tile_body<FORM, 2, 2, 2, 2, 1, 1>(p, t.m0, t.n0, lds, accumulate_dw, ext);
+}
+
 // ---- host side -------------------------------------------------------------------------
-// The kernel takes a problem when the chunks of its k-contiguous operands are whole (contraction
+// The kernels take a problem when the chunks of its k-contiguous operands are whole (contraction
 // length a multiple of 8) and the matrices fit the 32-bit buffer offsets.
 bool gemm_big_supported(const GemmProb &p) {
   if (!gemm_mfma_supported(p)) return false;
@@ -215,25 +271,41 @@ bool gemm_big_supported(const GemmProb &p) {
   if (a_rows * p.lda * 2 >= 0xffffff00ll || b_rows * p.ldb * 2 >= 0xffffff00ll) return false;
   return true;
 }
-// tile rows for a launch whose largest problem is maxM x maxN, or 0 when the smaller tile kernel
-// should run it: big tiles need enough of them to fill the chip
-int gemm_big_tile_rows(int maxM, int maxN, int64_t launch_elems) {
-  if (maxM < 256 || maxN < 256) return 0;
-  if (launch_elems >= (int64_t)256 * 256 * 192) return 256;   // 256 x 256 tiles for at least 3/4 of the CUs
-  if (launch_elems >= (int64_t)128 * 256 * 128) return 128;
-  return 0;
+// Tile shape for a launch: 256 (256 x 256, eight waves), 128 (128 x 256, eight waves), 64 (128 x 128,
+// four waves, three workgroups per compute unit), or 0 when the smaller tile kernel should run it.
+// `tiles256` / `tiles128`: 256 x 256 / 128 x 256 tiles of the whole launch.  The eight-wave kernels
+// hold one workgroup per compute unit, so they win only when every one of the 256 compute units gets
+// the same whole number of tiles; in between, the co-resident small tiles do.  Measured, 4 branches of
+// [2048 x N] outputs with contraction K, microseconds for tile 256 / 128 / 64:
+//   forward N 4096 K 1024 (512 / 1024 tiles): 87 / 95 / 90      N 3072 K 1024 (384 / 768): 77 / 71 / 66
+//   forward N 1024 K 4096 (128 / 256):       127 / 88 / 92      N 1024 K 1024 (128 / 256): 39 / 26 / 26
+//   backward-weight [3072 x 1024], 2048 rows (192 / 384): 81 / 90 / 71     [1024 x 1024] (64 / 128): 73 / 46 / 38
+int gemm_big_tile_rows(int maxM, int maxN, int64_t launch_elems, int tiles256, int tiles128) {
+  constexpr int CUS = 256;
+  if (maxM < 128 || maxN < 128) return 0;
+  if (launch_elems < (int64_t)128 * 128 * 128) return 0;
+  if (maxM >= 256 && maxN >= 256 && tiles256 >= CUS && tiles256 % CUS == 0) return 256;
+  if (maxN >= 256 && tiles128 == CUS) return 128;
+  // the single-buffer small tiles hide their load latency only behind co-resident workgroups: with
+  // at most one per compute unit (a lone [2048 x 1024 x 1024] problem: 28 us against 20 us) they lose
+  // to the ring-buffered tile kernel
+  if (2 * tiles128 < CUS + CUS / 2) return 0;
+  return 64;
 }
 int gemm_big_tiles_for(int tile_rows, int M, int N, int *tiles_n) {
-  if (tiles_n) *tiles_n = cdiv(N, 256);
-  return cdiv(M, tile_rows) * cdiv(N, 256);
+  const int bn = tile_rows == 64 ? 128 : 256, bm = tile_rows == 64 ? 128 : tile_rows;
+  if (tiles_n) *tiles_n = cdiv(N, bn);
+  return cdiv(M, bm) * cdiv(N, bn);
 }
 
 template <int FORM>
 static void launch_big_form(const GemmProb *probs, int n, int blocks, int acc, int tile_rows, const ExtPtrs &ext, hipStream_t s) {
   if (tile_rows == 256)
     hipLaunchKernelGGL((k_gemm_big<FORM, 4, 2, 2>), dim3(blocks), dim3(512), 0, s, probs, n, blocks, acc, ext);
-  else
+  else if (tile_rows == 128)
     hipLaunchKernelGGL((k_gemm_big<FORM, 2, 2, 2>), dim3(blocks), dim3(512), 0, s, probs, n, blocks, acc, ext);
+  else
+    hipLaunchKernelGGL((k_gemm_mid<FORM>), dim3(blocks), dim3(256), 0, s, probs, n, blocks, acc, ext);
 }
 void launch_gemm_big(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int form, int tile_rows,
                      const ExtPtrs &ext, hipStream_t s) {

@@ -170,11 +170,12 @@ int gemm_generic_tiles(int M, int N, int *tiles_n);
 int gemm_mfma_group_tile(int form, int maxM, int maxN);
 int gemm_mfma_tiles_for(int tile, int M, int N, int *tiles_n);
 int gemm_mfma_partial_floats(int tile);
-// large-tile kernel (256 x 256 or 128 x 256 outputs per workgroup of eight waves)
+// large-tile kernels: 256 x 256 or 128 x 256 outputs per workgroup of eight waves (tile_rows 256 / 128),
+// 128 x 128 outputs per workgroup of four waves, three workgroups per compute unit (tile_rows 64)
 void launch_gemm_big(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int form, int tile_rows,
                      const ExtPtrs &ext, hipStream_t s);
 bool gemm_big_supported(const GemmProb &p);
-int gemm_big_tile_rows(int maxM, int maxN, int64_t launch_elems);
+int gemm_big_tile_rows(int maxM, int maxN, int64_t launch_elems, int tiles256, int tiles128);
 int gemm_big_tiles_for(int tile_rows, int M, int N, int *tiles_n);
 // backward-weight for small weight matrices and many rows: 64 x 64 tiles, the contraction split over the waves
 void launch_gemm_dw_ksplit(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, hipStream_t s);

@@ -619,11 +619,14 @@ struct Emitter {
           if (use_mfma && !(pl.flags & 2)) {
             bool ok = true;
             int64_t elems = 0;
+            int tiles256 = 0, tiles128 = 0;
             for (auto &r : g) {
               ok = ok && gemm_big_supported(r);
               elems += (int64_t)r.M * r.N;
+              tiles256 += ((r.M + 255) / 256) * ((r.N + 255) / 256);
+              tiles128 += ((r.M + 127) / 128) * ((r.N + 255) / 256);
             }
-            const int tile_rows = ok ? gemm_big_tile_rows(max_m, max_n, elems) : 0;
+            const int tile_rows = ok ? gemm_big_tile_rows(max_m, max_n, elems, tiles256, tiles128) : 0;
             if (tile_rows > 0) {
               int blocks = 0;
               for (auto &r : g) {
