@@ -184,7 +184,10 @@ int32_t gpp_stage_output_op(const gpp_stage_t *stage, int32_t i);
 int32_t gpp_stage_num_launches(const gpp_stage_t *stage, int32_t backward);
 /* Integer artefacts of the last backward of embedding op `op`: DEVICE pointers into the workspace.
  * sorted_pos[n_used]: index positions stably sorted by row; unique_rows[n_unique] ascending;
- * seg_offsets[n_unique+1]; counts[0] = n_used, counts[1] = n_unique (DEVICE int32[2]). */
+ * seg_offsets[n_unique+1]; counts[0] = n_used, counts[1] = n_unique (DEVICE int32[2]).
+ * Inspection call, not for the hot path: it enqueues two small kernels (the table of distinct rows
+ * is not needed by the backward pass itself) and synchronises the device before it returns.
+ * GPP_ERR_ORDER if no backward has run. */
 gpp_status_t gpp_stage_embedding_sort_result(gpp_stage_t *stage, int32_t op, const int32_t **sorted_pos,
                                              const int32_t **unique_rows, const int32_t **seg_offsets,
                                              const int32_t **counts);

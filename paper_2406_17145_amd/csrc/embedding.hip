@@ -1,8 +1,9 @@
 // Sparse path of a DLRM-shaped stage, grouped over all embedding tables:
 //   forward   coalesced embedding-bag gather with sum pooling
 //   backward  deterministic sorted segment reduction:
-//             stable LSD radix sort of (row, position) keys -> segment heads ->
-//             per-row sums in sorted order -> one read-modify-write per distinct row
+//             stable LSD radix sort of (row, position) keys -> per-row sums in sorted
+//             order, started by the group that sits on a segment's first position ->
+//             one read-modify-write per distinct row
 //   reset     clears only the rows the backward passes since the last reset touched
 // No float atomics anywhere and every sum has a fixed association order, so two
 // runs give bit-identical gradients.
@@ -12,7 +13,7 @@ namespace gpp {
 
 constexpr int RADIX_BITS = 9;
 constexpr int RADIX = 1 << RADIX_BITS;
-constexpr int SORT_CHUNK = 2048;   // keys per workgroup per pass (256 threads x 8 rounds)
+constexpr int SORT_CHUNK = 1024;   // keys per workgroup per pass (four waves x 4 rounds of 64)
 constexpr int LONG_SEG = 256;      // slice length of the segments that are summed by whole workgroups
 constexpr int SHORT_MAX = 32;      // segments up to this length are summed by one 16-lane group, serially:
                                    // the longest serial chain sets that kernel's duration, so it is kept short
@@ -160,12 +161,21 @@ void launch_emb_fwd(const EmbProb *probs, int n, int total_blocks, int vec, Stag
 }
 
 // ------------------------------------------------------------------ stable radix sort by row
+// LSD radix sort of (row, position) with RADIX_BITS-bit digits.  A workgroup owns SORT_CHUNK
+// consecutive keys, wave w of it the sub-range [512 w, 512 w + 512) in rounds of 64, so "key order"
+// is wave-major and the scatter can rank its keys with three workgroup barriers in all: the waves
+// count their digits privately, one pass turns the counts into per-wave start offsets (global
+// base of the digit + the workgroups before this one + the waves before this one), then every wave
+// walks its rounds alone.  The last pass writes the sorted rows into the log slot of this backward
+// pass (the next gradient reset reads them there) and, next to the sorted positions, the bag id
+// of every sorted position (-1 where the index was out of range), which is what the sums gather by.
 struct SortIo {
   const int32_t *src_keys;
   const int32_t *src_pos;  // null in pass 0: position = index
   int32_t *dst_keys, *dst_pos;
 };
-__device__ __forceinline__ SortIo sort_io(const EmbProb &p, int pass) {
+__device__ __forceinline__ int32_t *log_keys(const EmbProb &p, int slot) { return p.unique_rows + (int64_t)slot * p.capacity; }
+__device__ __forceinline__ SortIo sort_io(const EmbProb &p, int pass, int slot) {
   SortIo io;
   if (pass == 0) {
     io.src_keys = p.indices; io.src_pos = nullptr; io.dst_keys = p.keys_a; io.dst_pos = p.pos_a;
@@ -174,82 +184,144 @@ __device__ __forceinline__ SortIo sort_io(const EmbProb &p, int pass) {
   } else {
     io.src_keys = p.keys_b; io.src_pos = p.pos_b; io.dst_keys = p.keys_a; io.dst_pos = p.pos_a;
   }
+  if (pass == p.passes - 1) io.dst_keys = log_keys(p, slot);
   return io;
 }
+constexpr int SORT_ROUNDS = SORT_CHUNK / 256;   // rounds of 64 keys per wave
+// index of the key that lane `lane` of wave `wave` handles in round r of workgroup `blk`
+__device__ __forceinline__ int sort_key_index(int blk, int wave, int r, int lane) {
+  return blk * SORT_CHUNK + wave * (SORT_CHUNK / 4) + r * 64 + lane;
+}
 
-__global__ __launch_bounds__(256) void k_sort_hist(const EmbProb *__restrict__ probs, int pass) {
+__global__ __launch_bounds__(256) void k_sort_hist(const EmbProb *__restrict__ probs, int pass, int slot) {
   __shared__ int hist[RADIX];
   const EmbProb p = probs[blockIdx.y];
   if ((int)blockIdx.x >= p.sort_blocks || pass >= p.passes) return;
   const int n_used = used_positions(p);
-  const SortIo io = sort_io(p, pass);
+  const SortIo io = sort_io(p, pass, slot);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (n_used <= 0) {   // nothing to sort: this workgroup's counts are zero (the whole workgroup takes this path)
+    for (int d = threadIdx.x; d < RADIX; d += 256) p.hist[blockIdx.x * RADIX + d] = 0;
+    return;
+  }
+  // loads without a branch around them (an index beyond the end reads the last key and drops it)
+  int key[SORT_ROUNDS];
+#pragma unroll
+  for (int r = 0; r < SORT_ROUNDS; ++r) {
+    const int j = sort_key_index(blockIdx.x, wave, r, lane);
+    const int k = clamp_row(io.src_keys[min(j, n_used - 1)], p.num_rows);
+    key[r] = j < n_used ? k : -1;
+  }
   for (int d = threadIdx.x; d < RADIX; d += 256) hist[d] = 0;
   __syncthreads();
-  const int base = blockIdx.x * SORT_CHUNK;
-  for (int r = 0; r < SORT_CHUNK / 256; ++r) {
-    const int j = base + r * 256 + threadIdx.x;
-    if (j < n_used) {
-      const int key = clamp_row(io.src_keys[j], p.num_rows);
-      atomicAdd(&hist[(key >> (pass * RADIX_BITS)) & (RADIX - 1)], 1);
-    }
-  }
+#pragma unroll
+  for (int r = 0; r < SORT_ROUNDS; ++r)
+    if (key[r] >= 0) atomicAdd(&hist[(key[r] >> (pass * RADIX_BITS)) & (RADIX - 1)], 1);
   __syncthreads();
-  for (int d = threadIdx.x; d < RADIX; d += 256) p.hist[d * p.sort_blocks + blockIdx.x] = hist[d];
+  for (int d = threadIdx.x; d < RADIX; d += 256) p.hist[blockIdx.x * RADIX + d] = hist[d];   // [block][digit]
 }
 
-// Each workgroup first derives its own output offsets from the digit-major [RADIX][sort_blocks]
-// count table (exclusive scan over digits of the per-digit totals, plus the counts of the blocks
-// before it), then ranks its keys round by round, waves in order, so the scatter is stable.
-__global__ __launch_bounds__(256) void k_sort_scatter(const EmbProb *__restrict__ probs, int pass) {
-  __shared__ int next[RADIX];
+__global__ __launch_bounds__(256) void k_sort_scatter(const EmbProb *__restrict__ probs, int pass, int slot) {
+  __shared__ int off[4][RADIX];   // per wave: digit counts, then the next output index of each digit
   __shared__ int scan[256];
   const EmbProb p = probs[blockIdx.y];
   if ((int)blockIdx.x >= p.sort_blocks || pass >= p.passes) return;
   const int n_used = used_positions(p);
-  const SortIo io = sort_io(p, pass);
+  const SortIo io = sort_io(p, pass, slot);
+  const bool last = pass == p.passes - 1;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (n_used <= 0) {   // nothing to sort (the whole workgroup takes this path)
+    if (last && blockIdx.x == 0 && threadIdx.x == 0) {
+      p.counts[slot * 4 + 0] = 0;
+      p.counts[slot * 4 + 2] = 0;
+    }
+    return;
+  }
+  // all of this thread's keys are requested before anything waits for them; no branch sits around a
+  // load (an index beyond the end reads the last key and drops it)
+  int key[SORT_ROUNDS], pos[SORT_ROUNDS];
+#pragma unroll
+  for (int r = 0; r < SORT_ROUNDS; ++r) {
+    const int j = sort_key_index(blockIdx.x, wave, r, lane), jc = min(j, n_used - 1);
+    const int k = clamp_row(io.src_keys[jc], p.num_rows);
+    key[r] = j < n_used ? k : -1;
+    pos[r] = jc;
+  }
+  if (io.src_pos) {
+#pragma unroll
+    for (int r = 0; r < SORT_ROUNDS; ++r) pos[r] = io.src_pos[pos[r]];
+  }
+  int bag[SORT_ROUNDS];
+  if (last) {
+#pragma unroll
+    for (int r = 0; r < SORT_ROUNDS; ++r) {
+      const int row = p.indices[pos[r]];
+      const int b = p.bag_of[pos[r]];
+      bag[r] = (row >= 0 && row < p.num_rows) ? b : -1;
+    }
+  }
+  for (int d = threadIdx.x; d < 4 * RADIX; d += 256) (&off[0][0])[d] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < SORT_ROUNDS; ++r)
+    if (key[r] >= 0) atomicAdd(&off[wave][(key[r] >> (pass * RADIX_BITS)) & (RADIX - 1)], 1);
+  __syncthreads();
   {
-    int tot[RADIX / 256], mine[RADIX / 256], pair = 0;
+    // thread t owns digits 2 t and 2 t + 1: exclusive scan over digits of the totals of the whole
+    // table, plus the counts of the workgroups before this one, then the waves in order.  The count
+    // table is [block][digit], so a wave reads 128 consecutive counts per load.
+    int tot[RADIX / 256] = {}, mine[RADIX / 256] = {}, pair = 0;
+    static_assert(RADIX / 256 == 2, "two digits per thread");
+    for (int b0 = 0; b0 < p.sort_blocks; b0 += 8) {   // eight rows of the table in flight
+      int2 c[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        c[u] = *(const int2 *)(p.hist + (int64_t)min(b0 + u, p.sort_blocks - 1) * RADIX + threadIdx.x * (RADIX / 256));
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int b = b0 + u;
+        if (b < p.sort_blocks) {
+          tot[0] += c[u].x;
+          tot[1] += c[u].y;
+        }
+        if (b < (int)blockIdx.x) {
+          mine[0] += c[u].x;
+          mine[1] += c[u].y;
+        }
+      }
+    }
+    pair = tot[0] + tot[1];
+    // exclusive scan of `pair` over the 256 threads: within a wave by shuffles, then the waves in order
+    int incl = pair;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int v = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += v;
+    }
+    if (lane == 63) scan[wave] = incl;
+    __syncthreads();
+    int run = incl - pair;
+    for (int w = 0; w < wave; ++w) run += scan[w];
 #pragma unroll
     for (int k = 0; k < RADIX / 256; ++k) {
       const int d = threadIdx.x * (RADIX / 256) + k;
-      int t = 0, m = 0;
-      for (int b = 0; b < p.sort_blocks; ++b) {
-        const int c = p.hist[d * p.sort_blocks + b];
-        t += c;
-        if (b < (int)blockIdx.x) m += c;
-      }
-      tot[k] = t;
-      mine[k] = m;
-      pair += t;
-    }
-    scan[threadIdx.x] = pair;
-    __syncthreads();
-    for (int o = 1; o < 256; o <<= 1) {
-      const int v = (int)threadIdx.x >= o ? scan[threadIdx.x - o] : 0;
-      __syncthreads();
-      scan[threadIdx.x] += v;
-      __syncthreads();
-    }
-    int run = scan[threadIdx.x] - pair;
+      int next = run + mine[k];
 #pragma unroll
-    for (int k = 0; k < RADIX / 256; ++k) {
-      next[threadIdx.x * (RADIX / 256) + k] = run + mine[k];
+      for (int w = 0; w < 4; ++w) {
+        const int c = off[w][d];
+        off[w][d] = next;
+        next += c;
+      }
       run += tot[k];
     }
   }
   __syncthreads();
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint64_t lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
-  const int base = blockIdx.x * SORT_CHUNK;
-  for (int r = 0; r < SORT_CHUNK / 256; ++r) {
-    const int j = base + r * 256 + threadIdx.x;
-    const bool valid = j < n_used;
-    int key = 0, pos = 0, digit = 0;
-    if (valid) {
-      key = clamp_row(io.src_keys[j], p.num_rows);
-      pos = io.src_pos ? io.src_pos[j] : j;
-      digit = (key >> (pass * RADIX_BITS)) & (RADIX - 1);
-    }
+  int *mine_off = off[wave];
+#pragma unroll
+  for (int r = 0; r < SORT_ROUNDS; ++r) {
+    const bool valid = key[r] >= 0;
+    const int digit = valid ? (key[r] >> (pass * RADIX_BITS)) & (RADIX - 1) : 0;
     uint64_t peers = __ballot(valid);
 #pragma unroll
     for (int b = 0; b < RADIX_BITS; ++b) {
@@ -260,25 +332,297 @@ __global__ __launch_bounds__(256) void k_sort_scatter(const EmbProb *__restrict_
     const int rank = __popcll(peers & lt_mask);
     const int cnt = __popcll(peers);
     int dst = 0;
-    for (int w = 0; w < 4; ++w) {   // waves in order: keeps the sort stable
-      if (wave == w && valid) dst = next[digit] + rank;
-      __syncthreads();
-      if (wave == w && valid && rank == 0) next[digit] += cnt;
-      __syncthreads();
-    }
+    if (valid) dst = mine_off[digit] + rank;          // every lane of a digit reads before its first lane adds:
+    __builtin_amdgcn_wave_barrier();                   // the wave executes these LDS accesses in program order
+    if (valid && rank == 0) mine_off[digit] += cnt;
+    __builtin_amdgcn_wave_barrier();
     if (valid) {
-      io.dst_keys[dst] = key;
-      io.dst_pos[dst] = pos;
+      io.dst_keys[dst] = key[r];
+      io.dst_pos[dst] = pos[r];
+      if (last) p.sbag[dst] = bag[r];
+    }
+  }
+  if (last && blockIdx.x == 0 && threadIdx.x == 0) {
+    p.counts[slot * 4 + 0] = n_used;
+    p.counts[slot * 4 + 2] = 0;   // queue length of the long segments
+  }
+}
+
+// ------------------------------------------------------------------ segment sums
+// Vector path (dimension a multiple of 4, at most 256): a wave per 64 sorted positions finds the
+// positions that start a segment (their row differs from the row before) and its four GROUPs of 16
+// lanes sum those segments in sorted order, one read-modify-write of the gradient row each.  No
+// prefix sum over segments is needed on this path.  Lane l of a group holds columns 4 l + 64 k ..
+// +3 for k < KV, so a wave works on four rows at once and every lane has KV independent 16-byte
+// loads in flight per position.
+constexpr int GROUP = 16;
+constexpr int KV_MAX = 4;
+// KV = 16-byte pieces per lane = ceil(dimension / 64): a template parameter, so that the loads of a
+// batch of rows are straight-line code, all requested before the first is used.  They are
+// unconditional (a branch around a load makes the wave wait for the loads before it): a lane
+// without a valid bag or column reads bag 0 / column 0 and discards the value.
+template <int KV>
+struct RowAcc {
+  float4 v[KV];
+};
+template <int KV>
+__device__ __forceinline__ void acc_zero(RowAcc<KV> &a) {
+#pragma unroll
+  for (int k = 0; k < KV; ++k) a.v[k] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+}
+// the pooled-output gradient rows of NB bags, requested together.  DT is that matrix's storage type
+// as a template parameter (DT_F32 / DT_BF16; -1 = look at the record): a run-time test of the type
+// in front of every load is a branch too, and would serialise the loads.
+template <int KV, int NB, int DT>
+__device__ __forceinline__ void rows_fetch(float4 (&r)[NB][KV], const EmbProb &p, const int (&bag)[NB], int l16) {
+#pragma unroll
+  for (int q = 0; q < NB; ++q)
+#pragma unroll
+    for (int k = 0; k < KV; ++k) {
+      const int c4 = 4 * l16 + 64 * k;
+      r[q][k] = load4(p.out, DT < 0 ? p.out_dtype : DT, (int64_t)max(bag[q], 0) * p.ld_out + (c4 < p.dim ? c4 : 0));
+    }
+}
+// a = ((a + row 0) + row 1) + ... in that order; rows of bags < 0 (index out of range) are skipped
+template <int KV, int NB>
+__device__ __forceinline__ void rows_add(RowAcc<KV> &a, const float4 (&r)[NB][KV], const int (&bag)[NB]) {
+#pragma unroll
+  for (int q = 0; q < NB; ++q)
+#pragma unroll
+    for (int k = 0; k < KV; ++k)
+      if (bag[q] >= 0) a.v[k] = f4_add(a.v[k], r[q][k]);
+}
+// sum over the positions whose bag ids are bags[lo], bags[lo + stride], ... (index < hi), in that
+// order, four rows in flight; `bags` may be LDS or global memory
+template <int KV, int DT>
+__device__ __forceinline__ void acc_positions(RowAcc<KV> &a, const EmbProb &p, const int32_t *bags, int lo, int hi, int stride, int l16) {
+  for (int q = lo; q < hi; q += 4 * stride) {
+    int bag[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int b = bags[min(q + u * stride, hi - 1)];   // no branch around the load
+      bag[u] = q + u * stride < hi ? b : -1;
+    }
+    float4 r[4][KV];
+    rows_fetch<KV, 4, DT>(r, p, bag, l16);
+    rows_add<KV, 4>(a, r, bag);
+  }
+}
+// `first`: no backward pass has touched the table since it was cleared, so every row still holds
+// zeros and the sum is stored without reading the row
+template <int KV>
+__device__ __forceinline__ void row_add(float *row, const RowAcc<KV> &a, int dim, int l16, bool first) {
+#pragma unroll
+  for (int k = 0; k < KV; ++k) {
+    const int c4 = 4 * l16 + 64 * k;
+    if (c4 < dim) {
+      float4 *d = (float4 *)(row + c4);
+      *d = first ? a.v[k] : f4_add(*d, a.v[k]);
     }
   }
 }
 
-// ------------------------------------------------------------------ segment heads
-__device__ __forceinline__ const int32_t *sorted_keys(const EmbProb &p) { return (p.passes & 1) ? p.keys_a : p.keys_b; }
+// queue entry of a slice of a long segment: (first sorted position, positions, row, slices of the
+// row when this is its first slice else 0); a row's entries are consecutive, in slice order
+struct LongEntry {
+  int32_t start, count, row, n_slices;
+};
+
+// A wave looks at 64 consecutive sorted positions: lane j loads the row of position base + j
+// (coalesced), the positions whose row differs from the row before start a
+// segment, and their lane numbers are listed, in order, in the wave's corner of LDS.  Returns the
+// number of segment starts in the window.
+// The rows themselves go to `wkey` (the groups of a wave run out of step afterwards, and a lane
+// shuffle cannot read from a lane that has already left a loop; LDS can).
+__device__ __forceinline__ int window_heads(const int32_t *keys, int base, int n_used, int lane, int *wkey, uint8_t *list) {
+  const int i = base + lane;
+  const int key = i < n_used ? keys[i] : -1;
+  wkey[lane] = key;
+  const int before = base > 0 ? keys[base - 1] : -1;           // same address for the whole wave
+  int prev = __shfl_up(key, 1, 64);
+  if (lane == 0) prev = before;
+  const bool head = i < n_used && key != prev;
+  const uint64_t hm = __ballot(head);
+  if (head) list[__popcll(hm & (lane == 0 ? 0ull : (~0ull >> (64 - lane))))] = (uint8_t)lane;
+  __builtin_amdgcn_wave_barrier();
+  return __popcll(hm);
+}
+// end (exclusive) of the segment of row k0 that is known to reach position lo - 1: 16-ary search by
+// a group of 16 lanes (`gl` = the group's first lane).  Invariant: row(lo - 1) == k0, and row(hi) != k0
+// or hi == n_used.
+__device__ __forceinline__ int segment_end(const int32_t *keys, int k0, int lo, int n_used, int l16, int gl) {
+  int hi = n_used;
+  while (lo < hi) {
+    const int step = (hi - lo + 15) / 16;
+    const int q = lo + l16 * step;
+    const bool same = q < hi && keys[q] == k0;
+    const int cnt = __popc((unsigned)(__ballot(same) >> gl) & 0xffffu);
+    if (cnt == 0) {
+      hi = lo;
+    } else {
+      hi = min(hi, lo + cnt * step);
+      lo = lo + (cnt - 1) * step + 1;
+    }
+  }
+  return lo;
+}
+
+// Table -> XCD affinity for launches whose workgroups of one table re-read that table's slice of a
+// shared matrix: hardware deals consecutive workgroup ids of a 1-D grid round-robin over the 8
+// XCDs, so workgroup id b runs on XCD b % 8; table t is served only by XCD t % 8, and that L2 then
+// holds the slices of its three or four tables instead of all of them.  Grid: 8 * ceil(n / 8) *
+// per_table workgroups; returns false for the ids beyond the last table.
+__device__ __forceinline__ bool xcd_table(int bid, int n, int per_table, int &table, int &blk) {
+  const int xcd = bid & 7, k = bid >> 3;
+  table = xcd + 8 * (k / per_table);
+  blk = k % per_table;
+  return table < n;
+}
+int emb_xcd_grid(int n, int per_table) { return 8 * ((n + 7) / 8) * per_table; }
+
+template <int KV, int DT>
+__global__ __launch_bounds__(256) void k_emb_bwd_sum(const EmbProb *__restrict__ probs, int n, int per_table, int slot, int first) {
+  __shared__ uint8_t heads[4][64];
+  __shared__ int wkey[4][64], wbag[4][64];
+  int table, blk;
+  if (!xcd_table(blockIdx.x, n, per_table, table, blk)) return;
+  const EmbProb p = probs[table];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l16 = lane & (GROUP - 1), gl = lane & ~(GROUP - 1), g = lane / GROUP;
+  const int base = (blk * 4 + wave) * 64;
+  const int n_used = used_positions(p);
+  if (base >= n_used) return;
+  const int32_t *keys = log_keys(p, slot);
+  const int32_t *sbag = p.sbag;
+  wbag[wave][lane] = base + lane < n_used ? sbag[base + lane] : -1;
+  const int n_heads = window_heads(keys, base, n_used, lane, wkey[wave], heads[wave]);
+  const int *bagw = wbag[wave];
+  const int window_end = min(64, n_used - base);
+  const int after = base + 64 < n_used ? keys[base + 64] : -1;   // row of the position behind the window
+  // The wave's four groups take the segments of the window in turn, SEGS at a time each: the rows
+  // of the first two positions of all SEGS segments are requested together and their sums stored
+  // together, because a wave gets its memory replies in order -- a store between two batches of loads
+  // makes the second batch wait for the store's acknowledgement.  Most segments of a Zipf-distributed
+  // table have one or two positions; the rest of a longer one follows, four rows in flight.
+  constexpr int SEGS = 4, NG = 64 / GROUP;
+  for (int o0 = 0; o0 < n_heads; o0 += NG * SEGS) {
+    int h[SEGS], k0[SEGS], len[SEGS], bag[2 * SEGS];
+#pragma unroll
+    for (int u = 0; u < SEGS; ++u) {
+      const int o = o0 + u * NG + g;
+      const bool act = o < n_heads;
+      h[u] = act ? (int)heads[wave][o] : 0;                          // lane of the segment's first position
+      k0[u] = wkey[wave][h[u]];
+      len[u] = act ? (o + 1 < n_heads ? (int)heads[wave][o + 1] : window_end) - h[u] : 0;
+      if (act && o + 1 == n_heads && k0[u] == after)                 // runs on beyond the window
+        len[u] = segment_end(keys, k0[u], base + 64, n_used, l16, gl) - (base + h[u]);
+      if (len[u] > SHORT_MAX) {
+        if (l16 == 0) {
+          const int i = base + h[u];
+          const int n_slices = (len[u] + LONG_SEG - 1) / LONG_SEG;
+          const int qb = atomicAdd(&p.counts[slot * 4 + 2], n_slices);
+          LongEntry *q = (LongEntry *)p.long_list + qb;
+          for (int sl = 0; sl < n_slices; ++sl) {
+            LongEntry e;
+            e.start = i + sl * LONG_SEG;
+            e.count = min(LONG_SEG, len[u] - sl * LONG_SEG);
+            e.row = k0[u];
+            e.n_slices = sl == 0 ? n_slices : 0;
+            q[sl] = e;
+          }
+        }
+        len[u] = 0;
+      }
+#pragma unroll
+      for (int t = 0; t < 2; ++t) bag[2 * u + t] = (t < len[u] && h[u] + t < 64) ? bagw[h[u] + t] : -1;
+    }
+    float4 r[2 * SEGS][KV];
+    rows_fetch<KV, 2 * SEGS, DT>(r, p, bag, l16);
+    RowAcc<KV> a[SEGS];
+#pragma unroll
+    for (int u = 0; u < SEGS; ++u) {
+      acc_zero(a[u]);
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int k = 0; k < KV; ++k)
+          if (bag[2 * u + t] >= 0) a[u].v[k] = f4_add(a[u].v[k], r[2 * u + t][k]);
+    }
+#pragma unroll
+    for (int u = 0; u < SEGS; ++u) {
+      if (len[u] > 2 || (len[u] == 2 && h[u] == 63)) {
+        // positions inside the window take their bag ids from the wave's LDS copy, the rest from memory
+        const int in_window = min(len[u], 64 - h[u]);
+        if (in_window > 2) acc_positions<KV, DT>(a[u], p, bagw, h[u] + 2, h[u] + in_window, 1, l16);
+        if (len[u] > in_window) acc_positions<KV, DT>(a[u], p, sbag, base + h[u] + in_window, base + h[u] + len[u], 1, l16);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < SEGS; ++u)
+      if (len[u] > 0) row_add<KV>(p.dtable + (int64_t)k0[u] * p.ld_table, a[u], p.dim, l16, first != 0);
+  }
+}
+
+// one workgroup of 16 groups per queued slice: group g sums positions g, g + 16, ... of the slice,
+// the 16 partial rows are added in group order through LDS and stored as the slice's partial row
+template <int KV, int DT>
+__global__ __launch_bounds__(256) void k_emb_bwd_long_partial(const EmbProb *__restrict__ probs, int slot) {
+  __shared__ float4 part[256 / GROUP][KV][GROUP];
+  const EmbProb p = probs[blockIdx.y];
+  const int n_long = p.counts[slot * 4 + 2];
+  const int l16 = threadIdx.x & (GROUP - 1), g = threadIdx.x / GROUP;
+  for (int e = blockIdx.x; e < n_long; e += gridDim.x) {
+    const LongEntry le = ((const LongEntry *)p.long_list)[e];
+    RowAcc<KV> a;
+    acc_zero(a);
+    acc_positions<KV, DT>(a, p, p.sbag, le.start + g, le.start + le.count, 256 / GROUP, l16);
+    __syncthreads();   // `part` is free again
+#pragma unroll
+    for (int k = 0; k < KV; ++k) part[g][k][l16] = a.v[k];
+    __syncthreads();
+    if (g == 0) {
+      float *dst = p.partial + (int64_t)e * p.ld_table;
+#pragma unroll
+      for (int k = 0; k < KV; ++k) {
+        const int c4 = 4 * l16 + 64 * k;
+        if (c4 < p.dim) {
+          float4 t = part[0][k][l16];
+#pragma unroll
+          for (int w = 1; w < 256 / GROUP; ++w) t = f4_add(t, part[w][k][l16]);
+          *(float4 *)(dst + c4) = t;
+        }
+      }
+    }
+  }
+}
+// a group per queued entry; the entry of a row's slice 0 adds that row's slice partials in slice order
+template <int KV>
+__global__ __launch_bounds__(256) void k_emb_bwd_long_final(const EmbProb *__restrict__ probs, int slot, int first) {
+  const EmbProb p = probs[blockIdx.y];
+  const int n_long = p.counts[slot * 4 + 2];
+  const int l16 = threadIdx.x & (GROUP - 1);
+  for (int e = blockIdx.x * (256 / GROUP) + (threadIdx.x / GROUP); e < n_long; e += gridDim.x * (256 / GROUP)) {
+    const LongEntry le = ((const LongEntry *)p.long_list)[e];
+    if (le.n_slices == 0) continue;
+    RowAcc<KV> a;
+    acc_zero(a);
+    for (int sl = 0; sl < le.n_slices; ++sl) {
+      const float *src = p.partial + (int64_t)(e + sl) * p.ld_table;
+#pragma unroll
+      for (int k = 0; k < KV; ++k) {
+        const int c4 = 4 * l16 + 64 * k;
+        if (c4 < p.dim) a.v[k] = f4_add(a.v[k], *(const float4 *)(src + c4));
+      }
+    }
+    row_add<KV>(p.dtable + (int64_t)le.row * p.ld_table, a, p.dim, l16, first != 0);
+  }
+}
+// upper bound of queued slices: every segment longer than SHORT_MAX has at most len / LONG_SEG + 1 of them
+int emb_long_entries(int capacity) { return capacity / SHORT_MAX + capacity / LONG_SEG + 2; }
+
+// ------------------------------------------------------------------ segment table
+// distinct rows, segment offsets and their count: needed by the scalar fallback below and handed
+// out for inspection; the vector path does not use them.
 __device__ __forceinline__ const int32_t *sorted_pos(const EmbProb &p) { return (p.passes & 1) ? p.pos_a : p.pos_b; }
-// bag id of every sorted position (-1 where the index was out of range), in the key buffer the sort
-// no longer needs: the segment sums then read one array instead of chasing position -> index -> bag
-__device__ __forceinline__ int32_t *sorted_bag(const EmbProb &p) { return (p.passes & 1) ? p.keys_b : p.keys_a; }
 
 // heads per chunk of SORT_CHUNK sorted keys (stored in the first sort_blocks entries of `hist`)
 __global__ __launch_bounds__(256) void k_seg_count(const EmbProb *__restrict__ probs, int slot) {
@@ -286,7 +630,7 @@ __global__ __launch_bounds__(256) void k_seg_count(const EmbProb *__restrict__ p
   const EmbProb p = probs[blockIdx.y];
   if ((int)blockIdx.x >= p.sort_blocks) return;
   const int n_used = used_positions(p);
-  const int32_t *keys = sorted_keys(p);
+  const int32_t *keys = log_keys(p, slot);
   const int base = blockIdx.x * SORT_CHUNK + threadIdx.x * (SORT_CHUNK / 256);
   int s = 0;
 #pragma unroll
@@ -294,37 +638,21 @@ __global__ __launch_bounds__(256) void k_seg_count(const EmbProb *__restrict__ p
     const int i = base + e;
     if (i < n_used && (i == 0 || keys[i] != keys[i - 1])) ++s;
   }
-  {  // the gather list, coalesced: thread t takes positions chunk + t, chunk + t + 256, ...
-    const int32_t *spos = sorted_pos(p);
-    int32_t *sbag = sorted_bag(p);
-#pragma unroll
-    for (int e = 0; e < SORT_CHUNK / 256; ++e) {
-      const int i = blockIdx.x * SORT_CHUNK + e * 256 + threadIdx.x;
-      if (i < n_used) {
-        const int pos = spos[i];
-        const int r = p.indices[pos];
-        sbag[i] = (r >= 0 && r < p.num_rows) ? p.bag_of[pos] : -1;
-      }
-    }
-  }
   for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    p.hist[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
-    if (blockIdx.x == 0) p.counts[slot * 4 + 2] = 0;  // long-segment counter
-  }
+  if (threadIdx.x == 0) p.hist[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
 }
 
-// unique_rows[slot], seg_offsets, counts[slot] = {n_used, n_unique, n_long}
+// seg_rows, seg_offsets, counts[slot][1] = number of distinct rows
 __global__ __launch_bounds__(256) void k_seg_write(const EmbProb *__restrict__ probs, int slot) {
   __shared__ int scan[256];
   __shared__ int before_s, total_s;
   const EmbProb p = probs[blockIdx.y];
   if ((int)blockIdx.x >= p.sort_blocks) return;
   const int n_used = used_positions(p);
-  const int32_t *keys = sorted_keys(p);
-  int32_t *uniq = p.unique_rows + (int64_t)slot * p.capacity;
+  const int32_t *keys = log_keys(p, slot);
+  int32_t *uniq = p.seg_rows;
   if (threadIdx.x < 64) {   // one wave folds the per-chunk head counts
     int before = 0, total = 0;
     for (int b = threadIdx.x; b < p.sort_blocks; b += 64) {
@@ -367,142 +695,15 @@ __global__ __launch_bounds__(256) void k_seg_write(const EmbProb *__restrict__ p
     }
   }
   if (blockIdx.x == 0 && threadIdx.x == 0) {
-    p.counts[slot * 4 + 0] = n_used;
     p.counts[slot * 4 + 1] = total_s;
     p.seg_offsets[total_s] = n_used;
   }
 }
-
-// ------------------------------------------------------------------ segment sums
-// Vector path (dimension a multiple of 4, at most 256): a GROUP of 16 lanes owns one distinct row;
-// lane l of the group holds columns 4 l + 64 k .. +3 for k < KV.  A wave therefore works on four
-// rows at once and every lane has KV independent 16-byte loads in flight per position.
-constexpr int GROUP = 16;
-constexpr int KV_MAX = 4;
-struct RowAcc {
-  float4 v[KV_MAX];
-};
-__device__ __forceinline__ void acc_zero(RowAcc &a) {
-#pragma unroll
-  for (int k = 0; k < KV_MAX; ++k) a.v[k] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+void launch_emb_segments(const EmbProb *probs, int n, int max_sort_blocks, int slot, hipStream_t s) {
+  if (n <= 0) return;
+  hipLaunchKernelGGL(k_seg_count, dim3(max_sort_blocks, n), dim3(256), 0, s, probs, slot);
+  hipLaunchKernelGGL(k_seg_write, dim3(max_sort_blocks, n), dim3(256), 0, s, probs, slot);
 }
-// a += pooled-output gradient row of `bag` (bag < 0: nothing)
-__device__ __forceinline__ void acc_add_bag(RowAcc &a, const EmbProb &p, int bag, int l16) {
-  if (bag < 0) return;
-#pragma unroll
-  for (int k = 0; k < KV_MAX; ++k) {
-    const int c4 = 4 * l16 + 64 * k;
-    if (c4 < p.dim) a.v[k] = f4_add(a.v[k], load4(p.out, p.out_dtype, (int64_t)bag * p.ld_out + c4));
-  }
-}
-// sum over sorted positions lo, lo + stride, ... < hi, in that order, four positions in flight
-__device__ __forceinline__ void acc_positions(RowAcc &a, const EmbProb &p, const int32_t *sbag, int lo, int hi, int stride, int l16) {
-  int q = lo;
-  for (; q + 3 * stride < hi; q += 4 * stride) {
-    const int b0 = sbag[q], b1 = sbag[q + stride], b2 = sbag[q + 2 * stride], b3 = sbag[q + 3 * stride];
-    RowAcc t0, t1;
-    acc_zero(t0);
-    acc_zero(t1);
-    acc_add_bag(a, p, b0, l16);
-    acc_add_bag(t0, p, b1, l16);
-    acc_add_bag(t1, p, b2, l16);
-    // fixed association: ((a + b0) + b1) + b2) + b3, with the loads issued together
-#pragma unroll
-    for (int k = 0; k < KV_MAX; ++k) a.v[k] = f4_add(f4_add(a.v[k], t0.v[k]), t1.v[k]);
-    acc_add_bag(a, p, b3, l16);
-  }
-  for (; q < hi; q += stride) acc_add_bag(a, p, sbag[q], l16);
-}
-// `first`: no backward pass has touched the table since it was cleared, so every row still holds
-// zeros and the sum is stored without reading the row
-__device__ __forceinline__ void row_add(float *row, const RowAcc &a, int dim, int l16, bool first) {
-#pragma unroll
-  for (int k = 0; k < KV_MAX; ++k) {
-    const int c4 = 4 * l16 + 64 * k;
-    if (c4 < dim) {
-      float4 *d = (float4 *)(row + c4);
-      *d = first ? a.v[k] : f4_add(*d, a.v[k]);
-    }
-  }
-}
-
-// a group per distinct row; rows with more than SHORT_MAX positions are cut into slices of LONG_SEG
-// and queued (entries (row id, slice) in consecutive list slots, slice order) for the two kernels below
-__global__ __launch_bounds__(256) void k_emb_bwd_short(const EmbProb *__restrict__ probs, int slot, int first) {
-  const EmbProb p = probs[blockIdx.y];
-  const int l16 = threadIdx.x & (GROUP - 1);
-  const int u = blockIdx.x * (256 / GROUP) + (threadIdx.x / GROUP);
-  if (u >= p.counts[slot * 4 + 1]) return;
-  const int lo = p.seg_offsets[u], hi = p.seg_offsets[u + 1];
-  if (hi - lo > SHORT_MAX) {
-    if (l16 == 0) {
-      const int n_slices = (hi - lo + LONG_SEG - 1) / LONG_SEG;
-      const int base = atomicAdd(&p.counts[slot * 4 + 2], n_slices);
-      for (int sl = 0; sl < n_slices; ++sl) {
-        p.long_list[2 * (base + sl)] = u;
-        p.long_list[2 * (base + sl) + 1] = sl;
-      }
-    }
-    return;
-  }
-  RowAcc a;
-  acc_zero(a);
-  acc_positions(a, p, sorted_bag(p), lo, hi, 1, l16);
-  row_add(p.dtable + (int64_t)p.unique_rows[(int64_t)slot * p.capacity + u] * p.ld_table, a, p.dim, l16, first != 0);
-}
-
-// one workgroup of 16 groups per queued slice: group g sums positions g, g + 16, ... of the slice,
-// the 16 partial rows are added in group order through LDS and stored as the slice's partial row
-__global__ __launch_bounds__(256) void k_emb_bwd_long_partial(const EmbProb *__restrict__ probs, int slot) {
-  __shared__ float4 part[256 / GROUP][KV_MAX][GROUP];
-  const EmbProb p = probs[blockIdx.y];
-  if ((int)blockIdx.x >= p.counts[slot * 4 + 2]) return;
-  const int u = p.long_list[2 * blockIdx.x], sl = p.long_list[2 * blockIdx.x + 1];
-  const int l16 = threadIdx.x & (GROUP - 1), g = threadIdx.x / GROUP;
-  const int lo = p.seg_offsets[u] + sl * LONG_SEG, hi = min(p.seg_offsets[u + 1], lo + LONG_SEG);
-  RowAcc a;
-  acc_zero(a);
-  acc_positions(a, p, sorted_bag(p), lo + g, hi, 256 / GROUP, l16);
-#pragma unroll
-  for (int k = 0; k < KV_MAX; ++k) part[g][k][l16] = a.v[k];
-  __syncthreads();
-  if (g == 0) {
-    float *dst = p.partial + (int64_t)blockIdx.x * p.ld_table;
-#pragma unroll
-    for (int k = 0; k < KV_MAX; ++k) {
-      const int c4 = 4 * l16 + 64 * k;
-      if (c4 < p.dim) {
-        float4 t = part[0][k][l16];
-#pragma unroll
-        for (int w = 1; w < 256 / GROUP; ++w) t = f4_add(t, part[w][k][l16]);
-        *(float4 *)(dst + c4) = t;
-      }
-    }
-  }
-}
-// a group per queued entry; the entry of a row's slice 0 adds that row's slice partials in slice order
-__global__ __launch_bounds__(256) void k_emb_bwd_long_final(const EmbProb *__restrict__ probs, int slot, int first) {
-  const EmbProb p = probs[blockIdx.y];
-  const int e = blockIdx.x * (256 / GROUP) + (threadIdx.x / GROUP);
-  if (e >= p.counts[slot * 4 + 2]) return;
-  const int u = p.long_list[2 * e];
-  if (p.long_list[2 * e + 1] != 0) return;
-  const int l16 = threadIdx.x & (GROUP - 1);
-  const int n_slices = (p.seg_offsets[u + 1] - p.seg_offsets[u] + LONG_SEG - 1) / LONG_SEG;
-  RowAcc a;
-  acc_zero(a);
-  for (int sl = 0; sl < n_slices; ++sl) {
-    const float *src = p.partial + (int64_t)(e + sl) * p.ld_table;
-#pragma unroll
-    for (int k = 0; k < KV_MAX; ++k) {
-      const int c4 = 4 * l16 + 64 * k;
-      if (c4 < p.dim) a.v[k] = f4_add(a.v[k], *(const float4 *)(src + c4));
-    }
-  }
-  row_add(p.dtable + (int64_t)p.unique_rows[(int64_t)slot * p.capacity + u] * p.ld_table, a, p.dim, l16, first != 0);
-}
-// upper bound of queued slices: every segment longer than SHORT_MAX has at most len / LONG_SEG + 1 of them
-int emb_long_entries(int capacity) { return capacity / SHORT_MAX + capacity / LONG_SEG + 2; }
 
 // scalar fallback (dimension not a multiple of 4): one wave per distinct row, a lane per column
 __global__ __launch_bounds__(256) void k_emb_bwd_generic(const EmbProb *__restrict__ probs, int slot) {
@@ -510,15 +711,13 @@ __global__ __launch_bounds__(256) void k_emb_bwd_generic(const EmbProb *__restri
   const int lane = threadIdx.x & 63;
   const int u = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (u >= p.counts[slot * 4 + 1]) return;
-  const int32_t *spos = sorted_pos(p);
   const int lo = p.seg_offsets[u], hi = p.seg_offsets[u + 1];
-  const int row = p.unique_rows[(int64_t)slot * p.capacity + u];
+  const int row = p.seg_rows[u];
   float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
   for (int q = lo; q < hi; ++q) {
-    const int pos = spos[q];
-    const int r = p.indices[pos];
-    if (r < 0 || r >= p.num_rows) continue;
-    const int64_t go = (int64_t)p.bag_of[pos] * p.ld_out;
+    const int bag = p.sbag[q];
+    if (bag < 0) continue;
+    const int64_t go = (int64_t)bag * p.ld_out;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       const int c = lane + 64 * k;
@@ -533,24 +732,45 @@ __global__ __launch_bounds__(256) void k_emb_bwd_generic(const EmbProb *__restri
   }
 }
 
-int emb_bwd_num_launches(int max_passes, int vec) { return 2 * max_passes + 2 + (vec ? 3 : 1); }
+template <int KV, int DT>
+static void launch_sums_typed(const EmbProb *probs, int n, int per_table, dim3 g_sum, dim3 g_part, dim3 g_fin, int slot, int first,
+                              hipStream_t s) {
+  hipLaunchKernelGGL((k_emb_bwd_sum<KV, DT>), g_sum, dim3(256), 0, s, probs, n, per_table, slot, first);
+  hipLaunchKernelGGL((k_emb_bwd_long_partial<KV, DT>), g_part, dim3(256), 0, s, probs, slot);
+  hipLaunchKernelGGL((k_emb_bwd_long_final<KV>), g_fin, dim3(256), 0, s, probs, slot, first);
+}
+template <int KV>
+static void launch_sums_kv(const EmbProb *probs, int n, int per_table, int out_dtype, dim3 g_sum, dim3 g_part, dim3 g_fin, int slot,
+                           int first, hipStream_t s) {
+  if (out_dtype == DT_BF16) launch_sums_typed<KV, DT_BF16>(probs, n, per_table, g_sum, g_part, g_fin, slot, first, s);
+  else if (out_dtype == DT_F32) launch_sums_typed<KV, DT_F32>(probs, n, per_table, g_sum, g_part, g_fin, slot, first, s);
+  else launch_sums_typed<KV, -1>(probs, n, per_table, g_sum, g_part, g_fin, slot, first, s);
+}
+static void launch_sums(const EmbProb *probs, int n, int per_table, int kv, int out_dtype, dim3 g_sum, dim3 g_part, dim3 g_fin,
+                        int slot, int first, hipStream_t s) {
+  if (kv <= 1) launch_sums_kv<1>(probs, n, per_table, out_dtype, g_sum, g_part, g_fin, slot, first, s);
+  else if (kv == 2) launch_sums_kv<2>(probs, n, per_table, out_dtype, g_sum, g_part, g_fin, slot, first, s);
+  else launch_sums_kv<4>(probs, n, per_table, out_dtype, g_sum, g_part, g_fin, slot, first, s);
+}
 
-int launch_emb_bwd(const EmbProb *probs, int n, int max_capacity, int max_sort_blocks, int max_passes, int vec,
-                   int slot, int first, hipStream_t s) {
+int emb_bwd_num_launches(int max_passes, int vec) { return 2 * max_passes + (vec ? 3 : 3); }
+
+int launch_emb_bwd(const EmbProb *probs, int n, int max_capacity, int max_sort_blocks, int max_passes, int vec, int max_dim,
+                   int out_dtype, int slot, int first, hipStream_t s) {
   if (n <= 0) return 0;
   for (int pass = 0; pass < max_passes; ++pass) {
-    hipLaunchKernelGGL(k_sort_hist, dim3(max_sort_blocks, n), dim3(256), 0, s, probs, pass);
-    hipLaunchKernelGGL(k_sort_scatter, dim3(max_sort_blocks, n), dim3(256), 0, s, probs, pass);
+    hipLaunchKernelGGL(k_sort_hist, dim3(max_sort_blocks, n), dim3(256), 0, s, probs, pass, slot);
+    hipLaunchKernelGGL(k_sort_scatter, dim3(max_sort_blocks, n), dim3(256), 0, s, probs, pass, slot);
   }
-  hipLaunchKernelGGL(k_seg_count, dim3(max_sort_blocks, n), dim3(256), 0, s, probs, slot);
-  hipLaunchKernelGGL(k_seg_write, dim3(max_sort_blocks, n), dim3(256), 0, s, probs, slot);
   if (vec) {
-    constexpr int GPB = 256 / GROUP;   // groups per workgroup
-    hipLaunchKernelGGL(k_emb_bwd_short, dim3((max_capacity + GPB - 1) / GPB, n), dim3(256), 0, s, probs, slot, first);
+    // the queue of long segments is short (a few hundred slices for a Zipf-distributed table):
+    // fixed grids that loop over it
     const int entries = emb_long_entries(max_capacity);
-    hipLaunchKernelGGL(k_emb_bwd_long_partial, dim3(entries, n), dim3(256), 0, s, probs, slot);
-    hipLaunchKernelGGL(k_emb_bwd_long_final, dim3((entries + GPB - 1) / GPB, n), dim3(256), 0, s, probs, slot, first);
+    const int per_table = (max_capacity + 255) / 256;
+    const dim3 g_sum(emb_xcd_grid(n, per_table)), g_part(entries < 256 ? entries : 256, n), g_fin(16, n);
+    launch_sums(probs, n, per_table, (max_dim + 63) / 64, out_dtype, g_sum, g_part, g_fin, slot, first, s);
   } else {
+    launch_emb_segments(probs, n, max_sort_blocks, slot, s);
     hipLaunchKernelGGL(k_emb_bwd_generic, dim3((max_capacity + 3) / 4, n), dim3(256), 0, s, probs, slot);
   }
   return emb_bwd_num_launches(max_passes, vec);
@@ -565,23 +785,33 @@ __global__ __launch_bounds__(256) void k_emb_reset(const EmbProb *__restrict__ p
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256)
     d[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 }
-// sparse clear: only the rows listed by the last `slots` backward passes (16 lanes per listed row)
+// sparse clear: only the rows that the logged backward passes touched.  A wave per 64 sorted
+// positions of a log slot; the positions that start a segment are listed and their rows cleared by
+// the wave's four 16-lane groups in turn.
 __global__ __launch_bounds__(256) void k_emb_reset_rows(const EmbProb *__restrict__ probs) {
+  __shared__ uint8_t heads[4][64];
+  __shared__ int wkey[4][64];
   const EmbProb p = probs[blockIdx.y];
   const int slot = blockIdx.z;
-  const int u = blockIdx.x * 16 + (threadIdx.x >> 4);
-  if (u >= p.counts[slot * 4 + 1]) return;
-  float *drow = p.dtable + (int64_t)p.unique_rows[(int64_t)slot * p.capacity + u] * p.ld_table;
-  if ((p.dim & 3) == 0 && (p.ld_table & 3) == 0) {
-    for (int c = (threadIdx.x & 15) * 4; c < p.dim; c += 64) *(float4 *)(drow + c) = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-  } else {
-    for (int c = threadIdx.x & 15; c < p.dim; c += 16) drow[c] = 0.0f;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l16 = lane & 15, g = lane >> 4;
+  const int base = (blockIdx.x * 4 + wave) * 64;
+  const int n_used = min(p.counts[slot * 4 + 0], p.capacity);
+  if (base >= n_used) return;
+  const int n_heads = window_heads(log_keys(p, slot), base, n_used, lane, wkey[wave], heads[wave]);
+  for (int o = g; o < n_heads; o += 4) {
+    const int row = wkey[wave][heads[wave][o]];
+    float *drow = p.dtable + (int64_t)row * p.ld_table;
+    if ((p.dim & 3) == 0 && (p.ld_table & 3) == 0) {
+      for (int c = l16 * 4; c < p.dim; c += 64) *(float4 *)(drow + c) = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    } else {
+      for (int c = l16; c < p.dim; c += 16) drow[c] = 0.0f;
+    }
   }
 }
 void launch_emb_reset(const EmbProb *probs, int n, int max_capacity, int slots, hipStream_t s) {
   if (n <= 0) return;
   if (slots <= 0) hipLaunchKernelGGL(k_emb_reset, dim3(1024, n), dim3(256), 0, s, probs);
-  else hipLaunchKernelGGL(k_emb_reset_rows, dim3((max_capacity + 15) / 16, n, slots), dim3(256), 0, s, probs);
+  else hipLaunchKernelGGL(k_emb_reset_rows, dim3((max_capacity + 255) / 256, n, slots), dim3(256), 0, s, probs);
 }
 
 }  // namespace gpp

@@ -287,9 +287,9 @@ int gemm_big_tile_rows(int maxM, int maxN, int64_t launch_elems, int tiles256, i
   if (maxM >= 256 && maxN >= 256 && tiles256 >= CUS && tiles256 % CUS == 0) return 256;
   if (maxN >= 256 && tiles128 == CUS) return 128;
   // the single-buffer small tiles hide their load latency only behind co-resident workgroups: with
-  // at most one per compute unit (a lone [2048 x 1024 x 1024] problem: 28 us against 20 us) they lose
+  // fewer tiles than compute units (a lone [2048 x 1024 x 1024] problem: 28 us against 20 us) they lose
   // to the ring-buffered tile kernel
-  if (2 * tiles128 < CUS + CUS / 2) return 0;
+  if (2 * tiles128 < CUS) return 0;
   return 64;
 }
 int gemm_big_tiles_for(int tile_rows, int M, int N, int *tiles_n) {

@@ -116,10 +116,13 @@ struct EmbProb {
   int32_t *bag_of;         // [capacity] bag id of each index position (written fwd)
   int32_t *keys_a, *keys_b, *pos_a, *pos_b;  // sort ping-pong buffers [capacity]
   int32_t *hist;           // [radix, sort_blocks]
-  int32_t *unique_rows;    // [log_slots][capacity]: distinct rows of the last backward passes
-  int32_t *seg_offsets;    // [capacity+1]
-  int32_t *counts;         // [log_slots][4]: n_used, n_unique, n_long, -
-  int32_t *long_list;      // [emb_long_entries][2]: (distinct-row id, slice) of segments cut into slices
+  int32_t *unique_rows;    // [log_slots][capacity]: the SORTED rows of the last backward passes, one log slot each
+                           // (a position whose row differs from the row before starts a distinct row)
+  int32_t *sbag;           // [capacity]: bag id of every sorted position (-1: index out of range)
+  int32_t *seg_rows;       // [capacity]: distinct rows in ascending order (scalar path and inspection only)
+  int32_t *seg_offsets;    // [capacity+1]: first sorted position of every distinct row (same)
+  int32_t *counts;         // [log_slots][4]: n_used, n_unique (inspection only), queued slices, -
+  int32_t *long_list;      // [emb_long_entries][4]: queued slices of long segments (start, count, row, slices)
   float *partial;          // [emb_long_entries][ld_table]: partial row of each queued slice
   int64_t ld_table, ld_out;
   int32_t n_bags, capacity, dim, num_rows;
@@ -219,9 +222,13 @@ int emb_fwd_blocks(int n_bags);
 bool emb_vec_supported(const EmbProb &p);
 // sort + segment heads + segment sums into log slot `slot`; returns the number of launches it enqueues
 // `first`: the gradient tables are all zero (no backward since they were cleared): sums are stored, not added
-int launch_emb_bwd(const EmbProb *probs, int n, int max_capacity, int max_sort_blocks, int max_passes, int vec,
-                   int slot, int first, hipStream_t s);
+// `max_dim`: largest embedding dimension among the tables (vector path: picks the lane layout);
+// `out_dtype`: storage type of the pooled-output gradients when all tables share it, else -1
+int launch_emb_bwd(const EmbProb *probs, int n, int max_capacity, int max_sort_blocks, int max_passes, int vec, int max_dim,
+                   int out_dtype, int slot, int first, hipStream_t s);
 int emb_bwd_num_launches(int max_passes, int vec);
+// distinct rows, segment offsets and their count of log slot `slot` (the vector path does not need them)
+void launch_emb_segments(const EmbProb *probs, int n, int max_sort_blocks, int slot, hipStream_t s);
 int emb_sort_chunk();
 int emb_radix_bits();
 int emb_long_segment();

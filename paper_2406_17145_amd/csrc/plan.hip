@@ -335,11 +335,13 @@ gpp_status_t Plan::analyse(const gpp_stage_desc_t *desc) {
       nd.more.clear();
       for (int k = 0; k < 4; ++k) nd.more.push_back(alloc(SP_SHARED, 1, cap, DT_I32));            // keys a/b, pos a/b
       nd.more.push_back(alloc(SP_SHARED, 1, (int64_t)(1 << emb_radix_bits()) * sort_blocks, DT_I32));  // hist
-      nd.more.push_back(alloc(SP_SHARED, 1, cap * emb_log_slots(), DT_I32));  // unique rows per log slot
+      nd.more.push_back(alloc(SP_SHARED, 1, cap * emb_log_slots(), DT_I32));  // sorted rows per log slot
       nd.more.push_back(alloc(SP_SHARED, 1, cap + 1, DT_I32));                // segment offsets
       nd.more.push_back(alloc(SP_SHARED, 1, 4 * emb_log_slots(), DT_I32));    // counts per log slot
-      nd.more.push_back(alloc(SP_SHARED, 1, 2 * (int64_t)emb_long_entries((int)cap), DT_I32));       // queued slices of long segments
+      nd.more.push_back(alloc(SP_SHARED, 1, 4 * (int64_t)emb_long_entries((int)cap), DT_I32));       // queued slices of long segments
       nd.more.push_back(alloc(SP_SHARED, emb_long_entries((int)cap), ld_of(nd.feat), DT_F32));       // their partial rows
+      nd.more.push_back(alloc(SP_SHARED, 1, cap, DT_I32));                    // bag id of every sorted position
+      nd.more.push_back(alloc(SP_SHARED, 1, cap, DT_I32));                    // distinct rows (scalar path, inspection)
       nd.emb_passes = passes;
       nd.emb_sort_blocks = sort_blocks;
     }
@@ -1338,6 +1340,8 @@ void Emitter::backward() {
           e.counts = (int32_t *)ptr(nd.more[7]);
           e.long_list = (int32_t *)ptr(nd.more[8]);
           e.partial = (float *)ptr(nd.more[9]);
+          e.sbag = (int32_t *)ptr(nd.more[10]);
+          e.seg_rows = (int32_t *)ptr(nd.more[11]);
           e.n_bags = (int32_t)pl.micro_batch;
           e.capacity = (int32_t)(pl.micro_batch * d.bag_size);
           e.dim = (int32_t)nd.feat;
@@ -1438,18 +1442,20 @@ void Emitter::backward() {
       add_step(K_POOL, push_table(pools), (int)pools.size(), blocks);
     }
     if (!embs.empty()) {
-      int cap = 0, sb = 0, ps = 0;
+      int cap = 0, sb = 0, ps = 0, md = 0, odt = embs[0].out_dtype;
       for (auto &e : embs) {
         cap = std::max(cap, e.capacity);
         sb = std::max(sb, e.sort_blocks);
         ps = std::max(ps, e.passes);
+        md = std::max(md, e.dim);
+        if (e.out_dtype != odt) odt = 3;   // mixed
       }
       bool vec = true;
       for (auto &e : embs) vec = vec && emb_vec_supported(e);
       Step &s = add_step(K_EMB_BWD, push_table(embs), (int)embs.size(), 0);
       s.a0 = cap;
       s.a1 = sb;
-      s.a2 = ps | (vec ? 256 : 0);
+      s.a2 = ps | (vec ? 256 : 0) | (odt << 9) | (md << 11);   // passes (8 bits), vector path, gradient dtype (2 bits), largest dimension
       s.launches = emb_bwd_num_launches(ps, vec ? 1 : 0);
     }
     if (!inters.empty()) {

@@ -45,6 +45,8 @@ struct gpp_stage {
   int emb_logged = 0;            // backward passes since the last reset whose touched rows are logged
   bool emb_log_overflow = false; // more passes than log slots: the next reset clears whole tables
   int emb_last_slot = 0;
+  const void *emb_last_table = nullptr;  // device records of the last embedding backward (its stash slot's copy)
+  int emb_sort_blocks = 0;
   // optional per-step timing (HIP events on the caller's stream)
   bool prof_on = false;
   std::vector<hipEvent_t> prof_ev;   // pairs (begin, end)
@@ -271,8 +273,11 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
         // the rows this pass touches are logged so that the next reset clears only those
         if (st->emb_logged >= emb_log_slots()) st->emb_log_overflow = true;
         const int slot = st->emb_logged < emb_log_slots() ? st->emb_logged : emb_log_slots() - 1;
-        launch_emb_bwd((const EmbProb *)tab, sp.n, sp.a0, sp.a1, sp.a2 & 255, (sp.a2 >> 8) & 1, slot, st->emb_logged == 0 ? 1 : 0, s);
+        launch_emb_bwd((const EmbProb *)tab, sp.n, sp.a0, sp.a1, sp.a2 & 255, (sp.a2 >> 8) & 1, sp.a2 >> 11,
+                       ((sp.a2 >> 9) & 3) == 3 ? -1 : ((sp.a2 >> 9) & 3), slot, st->emb_logged == 0 ? 1 : 0, s);
         st->emb_last_slot = slot;
+        st->emb_last_table = tab;
+        st->emb_sort_blocks = sp.a1;
         st->emb_logged++;
         break;
       }
@@ -407,10 +412,15 @@ gpp_status_t gpp_stage_embedding_sort_result(gpp_stage_t *st, int32_t op, const 
   if (op < 0 || op >= (int32_t)pl.nodes.size() || pl.nodes[op].d.kind != GPP_OP_EMBEDDING_BAG_SUM)
     return fail(GPP_ERR_INVALID_ARG, "op is not an embedding bag");
   const Node &nd = pl.nodes[op];
+  if (!st->emb_last_table) return fail(GPP_ERR_ORDER, "no backward pass has run yet");
+  // the hot path sums segments without a table of distinct rows: build it now, for all tables,
+  // from the sorted rows the last backward pass left in its log slot, and wait for it
+  launch_emb_segments((const EmbProb *)st->emb_last_table, st->emb_count, st->emb_sort_blocks, st->emb_last_slot, nullptr);
+  hipError_t he = hipDeviceSynchronize();
+  if (he != hipSuccess) return fail(GPP_ERR_DEVICE, std::string("HIP: ") + hipGetErrorString(he));
   auto sh = [&](const Buf &b) { return (const int32_t *)(st->ws + pl.off_shared + b.off); };
   if (sorted_pos) *sorted_pos = sh((nd.emb_passes & 1) ? nd.more[2] : nd.more[3]);
-  const int64_t cap = pl.micro_batch * nd.d.bag_size;
-  if (unique_rows) *unique_rows = sh(nd.more[5]) + st->emb_last_slot * cap;
+  if (unique_rows) *unique_rows = sh(nd.more[11]);
   if (seg_offsets) *seg_offsets = sh(nd.more[6]);
   if (counts) *counts = sh(nd.more[7]) + st->emb_last_slot * 4;
   return GPP_OK;
