@@ -13,11 +13,133 @@ __device__ __forceinline__ void term_to_pair(int t, int &i, int &j) {
   j = t - i * (i - 1) / 2;
 }
 
+// ---- vector bodies: rows of whole, aligned 16-byte chunks, one storage type for x / y / dy.  The type
+// is a template parameter, so that the loads of a phase are requested together (a run-time type test in
+// front of every load is a branch, and a wave waits for its earlier loads at a branch).
+template <int DT>
+__device__ __forceinline__ void ld8(const void *base, int64_t i, float (&v)[8]) {
+  if (DT == DT_BF16) {
+    const uint4 u = *(const uint4 *)((const uint16_t *)base + i);
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      v[2 * e] = __uint_as_float(w[e] << 16);
+      v[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
+    }
+  } else {
+    const float4 a = *(const float4 *)((const float *)base + i), b = *(const float4 *)((const float *)base + i + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+}
+template <int DT>
+__device__ __forceinline__ void st8(void *base, int64_t i, const float (&v)[8]) {
+  if (DT == DT_BF16) {
+    uint4 u;
+    u.x = (uint32_t)f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16);
+    u.y = (uint32_t)f32_to_bf16_bits(v[2]) | ((uint32_t)f32_to_bf16_bits(v[3]) << 16);
+    u.z = (uint32_t)f32_to_bf16_bits(v[4]) | ((uint32_t)f32_to_bf16_bits(v[5]) << 16);
+    u.w = (uint32_t)f32_to_bf16_bits(v[6]) | ((uint32_t)f32_to_bf16_bits(v[7]) << 16);
+    *(uint4 *)((uint16_t *)base + i) = u;
+  } else {
+    *(float4 *)((float *)base + i) = make_float4(v[0], v[1], v[2], v[3]);
+    *(float4 *)((float *)base + i + 4) = make_float4(v[4], v[5], v[6], v[7]);
+  }
+}
+constexpr int INT_MAX_CHUNKS = 4;   // 8-element chunks of the F x d block per thread: F * d <= 8192
+__device__ __forceinline__ bool interact_vec_ok(const InteractProb &p, bool bwd) {
+  if ((p.d & 7) || p.F * p.d > 256 * 8 * INT_MAX_CHUNKS) return false;
+  if ((p.ld_x & 7) || ((uintptr_t)p.x & 15)) return false;
+  if (bwd && ((p.ld_y & 7) || ((uintptr_t)p.y & 15))) return false;
+  return true;
+}
+// the F x d block of sample s into LDS rows of stride d + 1
+template <int DT>
+__device__ __forceinline__ void interact_stage_x(const InteractProb &p, int s, float *T, int st) {
+  const int chunks = (p.F * p.d) >> 3;
+  float v[INT_MAX_CHUNKS][8];
+#pragma unroll
+  for (int u = 0; u < INT_MAX_CHUNKS; ++u) {
+    const int q = threadIdx.x + 256 * u;
+    ld8<DT>(p.x, (int64_t)s * p.ld_x + 8 * (q < chunks ? q : 0), v[u]);
+  }
+#pragma unroll
+  for (int u = 0; u < INT_MAX_CHUNKS; ++u) {
+    const int q = threadIdx.x + 256 * u;
+    if (q < chunks) {
+      const int row = (8 * q) / p.d, col = 8 * q - row * p.d;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) T[row * st + col + e] = v[u][e];
+    }
+  }
+}
+template <int DT>
+__device__ __forceinline__ void interact_fwd_vec(const InteractProb &p, int s, float *lds) {
+  const int st = p.d + 1;
+  interact_stage_x<DT>(p, s, lds, st);
+  __syncthreads();
+  for (int c = threadIdx.x; c < p.d; c += 256) store_from_f32(p.y, DT, (int64_t)s * p.ld_y + c, lds[c]);
+  const int terms = p.F * (p.F - 1) / 2;
+  for (int t = threadIdx.x; t < terms; t += 256) {
+    int i, j;
+    term_to_pair(t, i, j);
+    float a = 0.0f;
+    for (int c = 0; c < p.d; ++c) a += lds[i * st + c] * lds[j * st + c];
+    store_from_f32(p.y, DT, (int64_t)s * p.ld_y + p.d + t, a);
+  }
+}
+template <int DT>
+__device__ __forceinline__ void interact_bwd_vec(const InteractProb &p, int s, float *lds) {
+  const int st = p.d + 1;
+  float *T = lds;
+  float *G = lds + p.F * st;  // symmetric F x F, zero diagonal
+  const int terms = p.F * (p.F - 1) / 2;
+  // the gradients of the dot products (their offset d + t is not chunk-aligned: element loads), all
+  // of a thread's requested before the block of x is staged
+  constexpr int GT = 4;
+  float g[GT];
+#pragma unroll
+  for (int u = 0; u < GT; ++u) {
+    const int t = threadIdx.x + 256 * u;
+    g[u] = load_as_f32(p.dy, DT, (int64_t)s * p.ld_dy + p.d + (t < terms ? t : 0));
+  }
+  interact_stage_x<DT>(p, s, T, st);
+  for (int e = threadIdx.x; e < p.F; e += 256) G[e * p.F + e] = 0.0f;
+#pragma unroll
+  for (int u = 0; u < GT; ++u) {
+    const int t = threadIdx.x + 256 * u;
+    if (t < terms) {
+      int i, j;
+      term_to_pair(t, i, j);
+      G[i * p.F + j] = g[u];
+      G[j * p.F + i] = g[u];
+    }
+  }
+  for (int t = threadIdx.x + 256 * GT; t < terms; t += 256) {   // more than 1024 terms (F > 45)
+    int i, j;
+    term_to_pair(t, i, j);
+    const float gv = load_as_f32(p.dy, DT, (int64_t)s * p.ld_dy + p.d + t);
+    G[i * p.F + j] = gv;
+    G[j * p.F + i] = gv;
+  }
+  __syncthreads();
+  // a thread per element, consecutive columns in consecutive lanes (LDS reads without bank conflicts)
+  for (int e = threadIdx.x; e < p.F * p.d; e += 256) {
+    const int i = e / p.d, c = e - i * p.d;
+    float a = i == 0 ? load_as_f32(p.dy, DT, (int64_t)s * p.ld_dy + c) : 0.0f;
+    for (int j = 0; j < p.F; ++j) a += G[i * p.F + j] * T[j * st + c];
+    store_from_f32(p.y, DT, (int64_t)s * p.ld_y + e, a);
+  }
+}
+
 __global__ __launch_bounds__(256) void k_interact_fwd(const InteractProb *__restrict__ probs, int n) {
   extern __shared__ float lds[];
   const int pi = find_prob(probs, n, blockIdx.x);
   const InteractProb p = probs[pi];
   const int s = blockIdx.x - p.blk_begin;
+  if (interact_vec_ok(p, false) && p.x_dtype == p.y_dtype) {
+    if (p.x_dtype == DT_BF16) return interact_fwd_vec<DT_BF16>(p, s, lds);
+    if (p.x_dtype == DT_F32) return interact_fwd_vec<DT_F32>(p, s, lds);
+  }
   const int st = p.d + 1;
   for (int e = threadIdx.x; e < p.F * p.d; e += 256)
     lds[(e / p.d) * st + (e % p.d)] = load_as_f32(p.x, p.x_dtype, (int64_t)s * p.ld_x + e);
@@ -38,6 +160,11 @@ __global__ __launch_bounds__(256) void k_interact_bwd(const InteractProb *__rest
   const int pi = find_prob(probs, n, blockIdx.x);
   const InteractProb p = probs[pi];
   const int s = blockIdx.x - p.blk_begin;
+  if (interact_vec_ok(p, true) && p.x_dtype == p.y_dtype && p.x_dtype == p.dy_dtype && (p.ld_dy & 7) == 0 &&
+      ((uintptr_t)p.dy & 15) == 0) {
+    if (p.x_dtype == DT_BF16) return interact_bwd_vec<DT_BF16>(p, s, lds);
+    if (p.x_dtype == DT_F32) return interact_bwd_vec<DT_F32>(p, s, lds);
+  }
   const int st = p.d + 1;
   float *T = lds;
   float *G = lds + p.F * st;  // symmetric F x F, zero diagonal

@@ -203,7 +203,9 @@ int elt_blocks(int rows, int cols);
 void launch_colsum(const ColsumProb *probs, int n, int total_blocks, int accumulate, hipStream_t s);
 int colsum_blocks(int cols);
 
-void launch_ln_fwd(const LnProb *probs, int n, int total_blocks, hipStream_t s);
+// vec: 0 = generic kernel, else 8-column chunks per lane (1, 2, 4) of the bf16 vector kernel
+void launch_ln_fwd(const LnProb *probs, int n, int total_blocks, int vec, hipStream_t s);
+bool ln_fwd_vec_supported(const LnProb &p);
 void launch_ln_bwd(const LnProb *probs, int n, int total_blocks, int max_d, int vec, hipStream_t s);
 bool ln_bwd_vec_supported(const LnProb &p);
 int ln_bwd_rows_per_block();

@@ -113,9 +113,84 @@ __global__ __launch_bounds__(256) void k_ln_fwd(const LnProb *__restrict__ probs
     p.rstd[row] = rstd;
   }
 }
-void launch_ln_fwd(const LnProb *probs, int n, int total_blocks, hipStream_t s) {
+// Vector path: bf16 rows of up to 2048 columns in whole 16-byte chunks.  A wave per row; the row stays
+// in registers (NCH chunks of 8 columns per lane) for the mean, the centred second moment and the
+// output, so it is read once; loads carry no branch (a lane without a chunk reads chunk 0 and drops it).
+typedef __attribute__((ext_vector_type(4))) uint32_t lnf_u32x4;
+template <int NCH>
+__global__ __launch_bounds__(256) void k_ln_fwd_vec(const LnProb *__restrict__ probs, int n) {
+  const int pi = find_prob(probs, n, blockIdx.x);
+  const LnProb p = probs[pi];
+  const int lane = threadIdx.x & 63;
+  const int row = (blockIdx.x - p.blk_begin) * 4 + (threadIdx.x >> 6);
+  if (row >= p.rows) return;
+  const int nchunks = p.d >> 3;
+  const uint16_t *xr = (const uint16_t *)p.x + (int64_t)row * p.ldx;
+  lnf_u32x4 raw[NCH];
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const int ch = lane + 64 * j;
+    raw[j] = *(const lnf_u32x4 *)(xr + (ch < nchunks ? ch : 0) * 8);
+  }
+  float v[NCH][8];
+  float s = 0.0f;
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const bool ok = lane + 64 * j < nchunks;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      v[j][2 * e] = ok ? __uint_as_float(raw[j][e] << 16) : 0.0f;
+      v[j][2 * e + 1] = ok ? __uint_as_float(raw[j][e] & 0xffff0000u) : 0.0f;
+      s += v[j][2 * e] + v[j][2 * e + 1];
+    }
+  }
+  const float mu = wave_sum(s) / (float)p.d;
+  float q = 0.0f;
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const bool ok = lane + 64 * j < nchunks;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float c = ok ? v[j][e] - mu : 0.0f;
+      v[j][e] = c;
+      q += c * c;
+    }
+  }
+  const float rstd = rsqrtf(wave_sum(q) / (float)p.d + p.eps);
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const int ch = lane + 64 * j;
+    if (ch >= nchunks) continue;
+    const float4 g0 = *(const float4 *)(p.gamma + ch * 8), g1 = *(const float4 *)(p.gamma + ch * 8 + 4);
+    const float4 b0 = *(const float4 *)(p.beta + ch * 8), b1 = *(const float4 *)(p.beta + ch * 8 + 4);
+    const float ga[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+    const float be[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+    lnf_u32x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      o[e] = (uint32_t)f32_to_bf16_bits(v[j][2 * e] * rstd * ga[2 * e] + be[2 * e]) |
+             ((uint32_t)f32_to_bf16_bits(v[j][2 * e + 1] * rstd * ga[2 * e + 1] + be[2 * e + 1]) << 16);
+    *(lnf_u32x4 *)((uint16_t *)p.y + (int64_t)row * p.ldy + ch * 8) = o;
+  }
+  if (lane == 0) {
+    p.mean[row] = mu;
+    p.rstd[row] = rstd;
+  }
+}
+bool ln_fwd_vec_supported(const LnProb &p) {
+  if (p.x_dtype != DT_BF16 || p.y_dtype != DT_BF16 || (p.d & 7) || p.d > 2048) return false;
+  if ((p.ldx | p.ldy) & 7) return false;
+  if (((uintptr_t)p.x | (uintptr_t)p.y) & 15) return false;
+  if (((uintptr_t)p.gamma | (uintptr_t)p.beta) & 15) return false;
+  return true;
+}
+// vec: 0 = generic kernel, otherwise the number of 8-column chunks per lane (1, 2 or 4)
+void launch_ln_fwd(const LnProb *probs, int n, int total_blocks, int vec, hipStream_t s) {
   if (total_blocks <= 0) return;
-  hipLaunchKernelGGL(k_ln_fwd, dim3(total_blocks), dim3(256), 0, s, probs, n);
+  if (vec == 1) hipLaunchKernelGGL(k_ln_fwd_vec<1>, dim3(total_blocks), dim3(256), 0, s, probs, n);
+  else if (vec == 2) hipLaunchKernelGGL(k_ln_fwd_vec<2>, dim3(total_blocks), dim3(256), 0, s, probs, n);
+  else if (vec == 4) hipLaunchKernelGGL(k_ln_fwd_vec<4>, dim3(total_blocks), dim3(256), 0, s, probs, n);
+  else hipLaunchKernelGGL(k_ln_fwd, dim3(total_blocks), dim3(256), 0, s, probs, n);
 }
 
 // LayerNorm backward.  One workgroup owns 32 consecutive rows (8 per wave):
@@ -328,52 +403,6 @@ void launch_ln_bwd_params(const LnProb *probs, int n, int total_blocks, int accu
   hipLaunchKernelGGL(k_ln_bwd_params, dim3(total_blocks), dim3(256), 0, s, probs, n, accumulate);
 }
 
-// ------------------------------------------------------------------ mean-pool
-// forward: one workgroup per (sample, 64 columns), four row groups combined in a fixed order;
-// backward: one thread per element
-int pool_blocks(const PoolProb &p) {
-  if (!p.backward) return p.batch * ((p.d + 63) / 64);
-  int64_t e = (int64_t)p.batch * p.seq * p.d;
-  return (int)((e + 255) / 256);
-}
-__global__ __launch_bounds__(256) void k_pool(const PoolProb *__restrict__ probs, int n) {
-  __shared__ float red[4][64];
-  const int pi = find_prob(probs, n, blockIdx.x);
-  const PoolProb p = probs[pi];
-  const int blk = blockIdx.x - p.blk_begin;
-  if (!p.backward) {
-    const int chunks = (p.d + 63) / 64;
-    const int b = blk / chunks, cl = threadIdx.x & 63, rg = threadIdx.x >> 6;
-    const int c = (blk % chunks) * 64 + cl;
-    float s = 0.0f;
-    if (c < p.d)
-      for (int t = rg; t < p.seq; t += 4) s += load_as_f32(p.src, p.src_dtype, ((int64_t)b * p.seq + t) * p.ld_src + c);
-    red[rg][cl] = s;
-    __syncthreads();
-    if (rg == 0 && c < p.d)
-      store_from_f32(p.dst, p.dst_dtype, (int64_t)b * p.ld_dst + c,
-                     ((red[0][cl] + red[1][cl]) + (red[2][cl] + red[3][cl])) / (float)p.seq);
-  } else {
-    const int64_t e = (int64_t)blk * 256 + threadIdx.x;
-    if (e >= (int64_t)p.batch * p.seq * p.d) return;
-    const int r = (int)(e / p.d), c = (int)(e % p.d);
-    float v = load_as_f32(p.src, p.src_dtype, (int64_t)(r / p.seq) * p.ld_src + c) / (float)p.seq;
-    store_from_f32(p.dst, p.dst_dtype, (int64_t)r * p.ld_dst + c, v);
-  }
-}
-void launch_pool(const PoolProb *probs, int n, int total_blocks, hipStream_t s) {
-  if (total_blocks <= 0) return;
-  hipLaunchKernelGGL(k_pool, dim3(total_blocks), dim3(256), 0, s, probs, n);
-}
-
-// ------------------------------------------------------------------ loss heads
-// kinds follow gpp_op_kind_t: 9 MSE, 10 softmax cross-entropy, 11 BCE with logits
-__device__ __forceinline__ float softplus_f(float y) { return fmaxf(y, 0.0f) + log1pf(__expf(-fabsf(y))); }
-__device__ __forceinline__ float sigmoid_f(float y) {
-  float e = __expf(-fabsf(y));
-  return y >= 0.0f ? 1.0f / (1.0f + e) : e / (1.0f + e);
-}
-
 // eight consecutive elements starting at element index i (a multiple of 8 from a 16-byte aligned base)
 __device__ __forceinline__ void load8_as_f32(const void *base, int32_t dtype, int64_t i, float (&v)[8]) {
   if (dtype == DT_BF16) {
@@ -402,6 +431,110 @@ __device__ __forceinline__ void store8_from_f32(void *base, int32_t dtype, int64
     *(float4 *)((float *)base + i + 4) = make_float4(v[4], v[5], v[6], v[7]);
   }
 }
+
+// ------------------------------------------------------------------ mean-pool
+// forward: a workgroup per (sample, 128 columns): 16 lanes x 8 columns cover the 128 columns of a
+// row, the 16 lane groups stride over the sequence with four rows in flight, and are combined in a
+// fixed order.  backward: a thread per 8 columns of an output row.  Both have a vector body (bf16 or
+// f32 rows of whole, aligned 16-byte chunks; the storage types are template parameters, so that no
+// type test stands in front of a load) and a scalar body for everything else.
+constexpr int POOL_COLS = 128;
+int pool_blocks(const PoolProb &p) {
+  if (!p.backward) return p.batch * ((p.d + POOL_COLS - 1) / POOL_COLS);
+  int64_t chunks = (int64_t)p.batch * p.seq * ((p.d + 7) / 8);
+  return (int)((chunks + 255) / 256);
+}
+__device__ __forceinline__ bool pool_vec_ok(const PoolProb &p) {
+  return (p.d & 7) == 0 && (p.ld_src & 7) == 0 && (p.ld_dst & 7) == 0 && (((uintptr_t)p.src | (uintptr_t)p.dst) & 15) == 0;
+}
+template <int SDT, int DDT>
+__device__ __forceinline__ void pool_body(const PoolProb &p, int blk, float (*red)[POOL_COLS]) {
+  if (!p.backward) {
+    const int chunks = (p.d + POOL_COLS - 1) / POOL_COLS;
+    const int b = blk / chunks, c0 = (blk % chunks) * POOL_COLS;
+    const int l16 = threadIdx.x & 15, grp = threadIdx.x >> 4;
+    const int c = c0 + 8 * l16;
+    const bool col_ok = c < p.d;
+    float acc[8] = {};
+    const int64_t base = (int64_t)b * p.seq * p.ld_src + (col_ok ? c : 0);
+    for (int t = grp; t < p.seq; t += 64) {      // rows t, t + 16, t + 32, t + 48 in flight
+      float v[4][8];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) load8_as_f32(p.src, SDT, base + (int64_t)min(t + 16 * u, p.seq - 1) * p.ld_src, v[u]);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (t + 16 * u < p.seq) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[e] += v[u][e];
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[grp][8 * l16 + e] = acc[e];
+    __syncthreads();
+    if (threadIdx.x < POOL_COLS && c0 + (int)threadIdx.x < p.d) {
+      float s = 0.0f;
+#pragma unroll
+      for (int g = 0; g < 16; ++g) s += red[g][threadIdx.x];
+      store_from_f32(p.dst, DDT, (int64_t)b * p.ld_dst + c0 + threadIdx.x, s / (float)p.seq);
+    }
+  } else {
+    const int cpr = p.d >> 3;
+    const int64_t ch = (int64_t)blk * 256 + threadIdx.x;
+    if (ch >= (int64_t)p.batch * p.seq * cpr) return;
+    const int r = (int)(ch / cpr), c = (int)(ch % cpr) * 8;
+    float v[8];
+    load8_as_f32(p.src, SDT, (int64_t)(r / p.seq) * p.ld_src + c, v);
+    const float inv = 1.0f / (float)p.seq;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] *= inv;
+    store8_from_f32(p.dst, DDT, (int64_t)r * p.ld_dst + c, v);
+  }
+}
+__device__ __forceinline__ void pool_body_scalar(const PoolProb &p, int blk, float (*red)[POOL_COLS]) {
+  if (!p.backward) {
+    const int chunks = (p.d + POOL_COLS - 1) / POOL_COLS;
+    const int b = blk / chunks, c0 = (blk % chunks) * POOL_COLS;
+    const int cl = threadIdx.x & (POOL_COLS - 1), rg = threadIdx.x / POOL_COLS;   // two row groups
+    const int c = c0 + cl;
+    float s = 0.0f;
+    if (c < p.d)
+      for (int t = rg; t < p.seq; t += 256 / POOL_COLS) s += load_as_f32(p.src, p.src_dtype, ((int64_t)b * p.seq + t) * p.ld_src + c);
+    red[rg][cl] = s;
+    __syncthreads();
+    if (rg == 0 && c < p.d) store_from_f32(p.dst, p.dst_dtype, (int64_t)b * p.ld_dst + c, (red[0][cl] + red[1][cl]) / (float)p.seq);
+  } else {
+    const int cpr = (p.d + 7) >> 3;
+    const int64_t ch = (int64_t)blk * 256 + threadIdx.x;
+    if (ch >= (int64_t)p.batch * p.seq * cpr) return;
+    const int r = (int)(ch / cpr), c0 = (int)(ch % cpr) * 8;
+    for (int c = c0; c < min(c0 + 8, p.d); ++c)
+      store_from_f32(p.dst, p.dst_dtype, (int64_t)r * p.ld_dst + c,
+                     load_as_f32(p.src, p.src_dtype, (int64_t)(r / p.seq) * p.ld_src + c) / (float)p.seq);
+  }
+}
+__global__ __launch_bounds__(256) void k_pool(const PoolProb *__restrict__ probs, int n) {
+  __shared__ float red[16][POOL_COLS];
+  const int pi = find_prob(probs, n, blockIdx.x);
+  const PoolProb p = probs[pi];
+  const int blk = blockIdx.x - p.blk_begin;
+  const bool vec = pool_vec_ok(p);
+  if (vec && p.src_dtype == DT_BF16 && p.dst_dtype == DT_BF16) pool_body<DT_BF16, DT_BF16>(p, blk, red);
+  else if (vec && p.src_dtype == DT_F32 && p.dst_dtype == DT_F32) pool_body<DT_F32, DT_F32>(p, blk, red);
+  else pool_body_scalar(p, blk, red);
+}
+void launch_pool(const PoolProb *probs, int n, int total_blocks, hipStream_t s) {
+  if (total_blocks <= 0) return;
+  hipLaunchKernelGGL(k_pool, dim3(total_blocks), dim3(256), 0, s, probs, n);
+}
+
+// ------------------------------------------------------------------ loss heads
+// kinds follow gpp_op_kind_t: 9 MSE, 10 softmax cross-entropy, 11 BCE with logits
+__device__ __forceinline__ float softplus_f(float y) { return fmaxf(y, 0.0f) + log1pf(__expf(-fabsf(y))); }
+__device__ __forceinline__ float sigmoid_f(float y) {
+  float e = __expf(-fabsf(y));
+  return y >= 0.0f ? 1.0f / (1.0f + e) : e / (1.0f + e);
+}
+
 // MSE / BCE rows can be read eight columns at a time: whole chunks, aligned rows
 __device__ __forceinline__ bool loss_row_vec_ok(const LossProb &p) {
   return (p.cols & 7) == 0 && (p.ld_y & 7) == 0 && (p.ld_t & 7) == 0 && (((uintptr_t)p.y | (uintptr_t)p.target) & 15) == 0;

@@ -248,7 +248,7 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
       case K_GEMM_BWD_MERGED: launch_gemm_bwd_merged((const GemmProb *)tab, sp.n, sp.blocks, sp.a2, sp.a1, accumulate, ext, s); break;
       case K_LOSS_FWD_SMALL: launch_loss_fwd_small((const LossProb *)tab, sp.n, loss_out, s); break;
       case K_COLSUM: launch_colsum((const ColsumProb *)tab, sp.n, sp.blocks, accumulate, s); break;
-      case K_LN_FWD: launch_ln_fwd((const LnProb *)tab, sp.n, sp.blocks, s); break;
+      case K_LN_FWD: launch_ln_fwd((const LnProb *)tab, sp.n, sp.blocks, sp.a0, s); break;
       case K_LN_BWD: launch_ln_bwd((const LnProb *)tab, sp.n, sp.blocks, sp.a0, sp.a1, s); break;
       case K_LN_BWD_PARAMS: launch_ln_bwd_params((const LnProb *)tab, sp.n, sp.blocks, accumulate, s); break;
       case K_ATTN_FWD:

@@ -20,6 +20,11 @@ the l2 norm.  Two CPU runs of the oracle that differ only in the accumulation
 precision of the matrix products (float32 vs float64) show the same spread
 (tests/test_oracle_pins.py::test_relu_mask_noise_floor), so for those tensors
 the bar is 5e-2; every other tensor of every graph stays at the stated 2e-2.
+Their max-norm guard is 5x their own bar (0.25): one opposite mask decision
+moves one sample's whole input-gradient row, which in a narrow input (a few
+tens of columns, a few hundred rows) is one element at 10-15% of the tensor's
+largest; the guard still catches what it is for, errors of the order of the
+values themselves over a tile or a tail.
 """
 import numpy as np
 
@@ -89,8 +94,8 @@ def compare(wl, gpu_res, gpu_grads, ora_stage, ora_res, tol=None, label=""):
         t2 = tol if t2 is None else t2
         e2, em = rel_errors(got, ref)
         worst[name] = (e2, em)
-        assert e2 <= t2 and em <= max(tol_max, 2 * t2), \
-            f"{label} {name}: l2-rel {e2:.3e} (tol {t2}) max-rel {em:.3e} (tol {max(tol_max, 2 * t2)})"
+        tm = max(tol_max, 2 * t2) if t2 == tol else 5 * t2
+        assert e2 <= t2 and em <= tm, f"{label} {name}: l2-rel {e2:.3e} (tol {t2}) max-rel {em:.3e} (tol {tm})"
 
     for j, (g, (st, gin)) in enumerate(zip(gpu_res, ora_res)):
         if ora_stage.ops and any(op["kind"].startswith("loss") for op in ora_stage.ops):
