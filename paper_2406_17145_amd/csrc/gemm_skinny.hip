@@ -218,6 +218,70 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmProb &p, int local, u
   // ---- epilogue, all waves: thread t owns 8 consecutive columns; BN / 8 threads per row
   constexpr int TPR = BN / 8, ROWS_PER_PASS = 64 * NW / TPR;
   const int cg = (threadIdx.x % TPR) * 8;
+  // Fast path: bf16 result (and bf16 residual / mask source / stash where present) in whole, aligned
+  // 16-byte chunks.  Everything a row needs from memory is requested as 16-byte loads before it is
+  // used, and the storage types are known here, so no type test stands between the loads.
+  const bool chunked = p.c_dtype == DT_BF16 && (p.N & 7) == 0 && (p.ldc & 7) == 0 && ((uintptr_t)Cout & 15) == 0 &&
+                       (!p.res || (p.res_dtype == DT_BF16 && (p.ldres & 7) == 0 && ((uintptr_t)p.res & 15) == 0)) &&
+                       (!p.aux || (p.aux_dtype == DT_BF16 && (p.ldaux & 7) == 0 && ((uintptr_t)p.aux & 15) == 0)) &&
+                       (FORM == FORM_DX || !p.bias || ((uintptr_t)p.bias & 15) == 0);
+  if (chunked) {
+    const int col = n0 + cg;
+    if (col >= p.N) return;
+    float bias[8] = {};
+    if (FORM == FORM_FWD && p.bias) {
+      const float4 b0 = *(const float4 *)(p.bias + col), b1 = *(const float4 *)(p.bias + col + 4);
+      bias[0] = b0.x; bias[1] = b0.y; bias[2] = b0.z; bias[3] = b0.w;
+      bias[4] = b1.x; bias[5] = b1.y; bias[6] = b1.z; bias[7] = b1.w;
+    }
+    const bool use_aux_in = FORM == FORM_DX && p.act != ACT_NONE;
+    // an absent operand is read from the result buffer instead (valid memory, value unused): the two
+    // loads of a row then carry no branch
+    const uint16_t *resp = p.res ? (const uint16_t *)p.res : (const uint16_t *)Cout;
+    const uint16_t *auxp = use_aux_in ? (const uint16_t *)p.aux : (const uint16_t *)Cout;
+    const int64_t ldr = p.res ? p.ldres : p.ldc, lda = use_aux_in ? p.ldaux : p.ldc;
+    for (int lr = threadIdx.x / TPR; lr < BM; lr += ROWS_PER_PASS) {
+      const int row = m0 + lr;
+      if (row >= p.M) break;
+      const u32x4 res_raw = *(const u32x4 *)(resp + (int64_t)row * ldr + col);
+      const u32x4 aux_raw = *(const u32x4 *)(auxp + (int64_t)row * lda + col);
+      float v[8], rs[8], ax[8];
+      {
+        const float4 a = *(const float4 *)(r1 + lr * BN + cg), b = *(const float4 *)(r1 + lr * BN + cg + 4);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        rs[2 * e] = __uint_as_float(res_raw[e] << 16);
+        rs[2 * e + 1] = __uint_as_float(res_raw[e] & 0xffff0000u);
+        ax[2 * e] = __uint_as_float(aux_raw[e] << 16);
+        ax[2 * e + 1] = __uint_as_float(aux_raw[e] & 0xffff0000u);
+      }
+      float stash[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        if (FORM == FORM_FWD) {
+          v[e] += bias[e];
+          stash[e] = act_stash(v[e], p.act);
+          v[e] = act_apply(v[e], p.act);
+          if (p.res) v[e] += rs[e];
+        } else {
+          if (p.res) v[e] += rs[e];
+          if (use_aux_in) v[e] *= act_grad(ax[e], p.act);
+        }
+      }
+      u32x4 out;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) out[e] = (uint32_t)f32_to_bf16_bits(v[2 * e]) | ((uint32_t)f32_to_bf16_bits(v[2 * e + 1]) << 16);
+      *(u32x4 *)((uint16_t *)Cout + (int64_t)row * p.ldc + col) = out;
+      if (FORM == FORM_FWD && p.aux) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) out[e] = (uint32_t)f32_to_bf16_bits(stash[2 * e]) | ((uint32_t)f32_to_bf16_bits(stash[2 * e + 1]) << 16);
+        *(u32x4 *)((uint16_t *)p.aux + (int64_t)row * p.ldaux + col) = out;
+      }
+    }
+    return;
+  }
   for (int lr = threadIdx.x / TPR; lr < BM; lr += ROWS_PER_PASS) {
     const int row = m0 + lr;
     if (row >= p.M) break;
