@@ -221,9 +221,47 @@ __global__ __launch_bounds__(256) void k_sort_hist(const EmbProb *__restrict__ p
   for (int d = threadIdx.x; d < RADIX; d += 256) p.hist[blockIdx.x * RADIX + d] = hist[d];   // [block][digit]
 }
 
+// One workgroup per table turns the [block][digit] count table into output offsets, in place:
+// entry [b][d] becomes the number of keys with digit d in the blocks before b, and row
+// [sort_blocks] receives the exclusive scan over digits of the digit totals.  The scatter then needs
+// two small loads per thread instead of the whole table per workgroup.
+__global__ __launch_bounds__(256) void k_sort_offsets(const EmbProb *__restrict__ probs, int pass) {
+  __shared__ int scan[4];
+  const EmbProb p = probs[blockIdx.x];
+  if (pass >= p.passes) return;
+  static_assert(RADIX / 256 == 2, "two digits per thread");
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int run[2] = {0, 0};
+  for (int b0 = 0; b0 < p.sort_blocks; b0 += 8) {   // eight rows of the table in flight
+    int2 c[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      c[u] = *(const int2 *)(p.hist + (int64_t)min(b0 + u, p.sort_blocks - 1) * RADIX + threadIdx.x * 2);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (b0 + u < p.sort_blocks) {
+        *(int2 *)(p.hist + (int64_t)(b0 + u) * RADIX + threadIdx.x * 2) = make_int2(run[0], run[1]);
+        run[0] += c[u].x;
+        run[1] += c[u].y;
+      }
+    }
+  }
+  const int pair = run[0] + run[1];
+  int incl = pair;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int v = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += v;
+  }
+  if (lane == 63) scan[wave] = incl;
+  __syncthreads();
+  int base = incl - pair;
+  for (int w = 0; w < wave; ++w) base += scan[w];
+  *(int2 *)(p.hist + (int64_t)p.sort_blocks * RADIX + threadIdx.x * 2) = make_int2(base, base + run[0]);
+}
+
 __global__ __launch_bounds__(256) void k_sort_scatter(const EmbProb *__restrict__ probs, int pass, int slot) {
   __shared__ int off[4][RADIX];   // per wave: digit counts, then the next output index of each digit
-  __shared__ int scan[256];
   const EmbProb p = probs[blockIdx.y];
   if ((int)blockIdx.x >= p.sort_blocks || pass >= p.passes) return;
   const int n_used = used_positions(p);
@@ -267,52 +305,22 @@ __global__ __launch_bounds__(256) void k_sort_scatter(const EmbProb *__restrict_
     if (key[r] >= 0) atomicAdd(&off[wave][(key[r] >> (pass * RADIX_BITS)) & (RADIX - 1)], 1);
   __syncthreads();
   {
-    // thread t owns digits 2 t and 2 t + 1: exclusive scan over digits of the totals of the whole
-    // table, plus the counts of the workgroups before this one, then the waves in order.  The count
-    // table is [block][digit], so a wave reads 128 consecutive counts per load.
-    int tot[RADIX / 256] = {}, mine[RADIX / 256] = {}, pair = 0;
+    // thread t owns digits 2 t and 2 t + 1: first output index of the digit (whole table) plus the
+    // keys with that digit in the workgroups before this one, then the waves in order
     static_assert(RADIX / 256 == 2, "two digits per thread");
-    for (int b0 = 0; b0 < p.sort_blocks; b0 += 8) {   // eight rows of the table in flight
-      int2 c[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u)
-        c[u] = *(const int2 *)(p.hist + (int64_t)min(b0 + u, p.sort_blocks - 1) * RADIX + threadIdx.x * (RADIX / 256));
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int b = b0 + u;
-        if (b < p.sort_blocks) {
-          tot[0] += c[u].x;
-          tot[1] += c[u].y;
-        }
-        if (b < (int)blockIdx.x) {
-          mine[0] += c[u].x;
-          mine[1] += c[u].y;
-        }
-      }
-    }
-    pair = tot[0] + tot[1];
-    // exclusive scan of `pair` over the 256 threads: within a wave by shuffles, then the waves in order
-    int incl = pair;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const int v = __shfl_up(incl, o, 64);
-      if (lane >= o) incl += v;
-    }
-    if (lane == 63) scan[wave] = incl;
-    __syncthreads();
-    int run = incl - pair;
-    for (int w = 0; w < wave; ++w) run += scan[w];
+    const int2 basev = *(const int2 *)(p.hist + (int64_t)p.sort_blocks * RADIX + threadIdx.x * 2);
+    const int2 minev = *(const int2 *)(p.hist + (int64_t)blockIdx.x * RADIX + threadIdx.x * 2);
+    const int start[2] = {basev.x + minev.x, basev.y + minev.y};
 #pragma unroll
     for (int k = 0; k < RADIX / 256; ++k) {
       const int d = threadIdx.x * (RADIX / 256) + k;
-      int next = run + mine[k];
+      int next = start[k];
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
         const int c = off[w][d];
         off[w][d] = next;
         next += c;
       }
-      run += tot[k];
     }
   }
   __syncthreads();
@@ -753,13 +761,14 @@ static void launch_sums(const EmbProb *probs, int n, int per_table, int kv, int 
   else launch_sums_kv<4>(probs, n, per_table, out_dtype, g_sum, g_part, g_fin, slot, first, s);
 }
 
-int emb_bwd_num_launches(int max_passes, int vec) { return 2 * max_passes + (vec ? 3 : 3); }
+int emb_bwd_num_launches(int max_passes, int vec) { return 3 * max_passes + (vec ? 3 : 3); }
 
 int launch_emb_bwd(const EmbProb *probs, int n, int max_capacity, int max_sort_blocks, int max_passes, int vec, int max_dim,
                    int out_dtype, int slot, int first, hipStream_t s) {
   if (n <= 0) return 0;
   for (int pass = 0; pass < max_passes; ++pass) {
     hipLaunchKernelGGL(k_sort_hist, dim3(max_sort_blocks, n), dim3(256), 0, s, probs, pass, slot);
+    hipLaunchKernelGGL(k_sort_offsets, dim3(n), dim3(256), 0, s, probs, pass);
     hipLaunchKernelGGL(k_sort_scatter, dim3(max_sort_blocks, n), dim3(256), 0, s, probs, pass, slot);
   }
   if (vec) {

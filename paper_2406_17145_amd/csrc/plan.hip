@@ -334,7 +334,7 @@ gpp_status_t Plan::analyse(const gpp_stage_desc_t *desc) {
       const int sort_blocks = (int)((cap + emb_sort_chunk() - 1) / emb_sort_chunk());
       nd.more.clear();
       for (int k = 0; k < 4; ++k) nd.more.push_back(alloc(SP_SHARED, 1, cap, DT_I32));            // keys a/b, pos a/b
-      nd.more.push_back(alloc(SP_SHARED, 1, (int64_t)(1 << emb_radix_bits()) * sort_blocks, DT_I32));  // hist
+      nd.more.push_back(alloc(SP_SHARED, 1, (int64_t)(1 << emb_radix_bits()) * (sort_blocks + 1), DT_I32));  // digit counts per block + digit bases
       nd.more.push_back(alloc(SP_SHARED, 1, cap * emb_log_slots(), DT_I32));  // sorted rows per log slot
       nd.more.push_back(alloc(SP_SHARED, 1, cap + 1, DT_I32));                // segment offsets
       nd.more.push_back(alloc(SP_SHARED, 1, 4 * emb_log_slots(), DT_I32));    // counts per log slot
