@@ -31,7 +31,8 @@
  *     (+ rows_extra for inputs).  Tensors passed per call (inputs, outputs and
  *     their gradients) are dense: leading dimension == features.  Parameters
  *     and gradient accumulators with a feature dimension use the padded
- *     leading dimension gpp_ld(features) (next multiple of 8 elements); the
+ *     leading dimension gpp_ld(features) (next multiple of 64 elements, so that
+ *     every row of a bf16 or fp32 matrix starts on a 128-byte cache line); the
  *     padding columns of parameters must hold zeros and the library never
  *     writes padding columns of gradient accumulators.
  *   - all device base pointers must be 16-byte aligned; the workspace 256.

@@ -14,7 +14,7 @@ bool attn_mfma_supported(const AttnProb &p);
 size_t interact_lds_bytes(int F, int d);
 
 static int64_t align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
-static int64_t ld_of(int64_t features) { return align_up(features, 8); }
+static int64_t ld_of(int64_t features) { return align_up(features, 64); }
 static int64_t esize(int32_t dt) { return dt == DT_BF16 ? 2 : 4; }
 static bool is_float(int32_t dt) { return dt == DT_F32 || dt == DT_BF16; }
 

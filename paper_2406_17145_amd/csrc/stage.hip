@@ -94,7 +94,7 @@ static const char *const kTagNames[GPP_PROFILE_TAGS] = {
 
 extern "C" {
 
-int64_t gpp_ld(int64_t features) { return (features + 7) / 8 * 8; }
+int64_t gpp_ld(int64_t features) { return (features + 63) / 64 * 64; }
 
 const char *gpp_last_error(void) { return g_last_error.c_str(); }
 

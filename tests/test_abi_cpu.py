@@ -30,7 +30,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_ld_rule(lib):
-    assert [B.gpp_ld(x) for x in (1, 8, 9, 13, 479, 942, 1000, 3820)] == [8, 8, 16, 16, 480, 944, 1000, 3824]
+    assert [B.gpp_ld(x) for x in (1, 8, 64, 65, 479, 942, 1000, 3820)] == [64, 64, 64, 128, 512, 960, 1024, 3840]
 
 
 def ws(ops, b=4, slots=1):
