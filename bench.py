@@ -134,6 +134,11 @@ def main():
                     help="micro-batch schedule of a step: serial = fw_k bw_k in turn on one stream; overlap = fw_{k+1} "
                          "runs while bw_k runs (two in-flight slots, two streams); auto = overlap when the workload "
                          "has at least two micro-batches per step")
+    ap.add_argument("--graph", default="auto", choices=["auto", "on", "off"],
+                    help="on: the step (all its launches on both streams) is captured once into a HIP graph and "
+                         "replayed; off: every step is enqueued from the host; auto: on with the overlapped schedule "
+                         "(where the host would pace the two streams), off with the serial one (measured: replay is "
+                         "1-3 %% slower than eager launches there)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-pass", action="store_true", help="skip the event-instrumented second pass")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -153,22 +158,37 @@ def main():
     if args.micro_batch:
         kw["micro_batch"] = args.micro_batch
     wl = W.CONFIGS[args.config](**kw)
-    from paper_2406_17145_amd.schedule import OverlapSchedule, SerialSchedule
+    from paper_2406_17145_amd.schedule import GraphedMinibatch, OverlapSchedule, SerialSchedule
     overlap = args.schedule == "overlap" or (args.schedule == "auto" and wl.n_micro >= 2)
-    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=2 if overlap else 1)
+    # overlapped schedule: one stash slot per micro-batch of the step (at most 8), so that no forward
+    # call waits for a backward call (the form a HIP graph can hold, see schedule.py)
+    n_slots = min(wl.n_micro, 8) if overlap else 1
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=n_slots)
     dev_batches = [st.stage_inputs(mb) for mb in wl.batches]       # resident in HBM
-    outs = [st.alloc_outputs(), st.alloc_outputs()]                # one set per in-flight slot
+    outs = [st.alloc_outputs() for _ in range(max(n_slots, 2))]    # one set per in-flight slot
     gins = st.alloc_grad_inputs()
     gouts = [torch.zeros_like(o) for o in outs[0]] if outs[0] else None
-    losses = [torch.zeros(1, dtype=torch.float32, device=st.dev) for _ in range(2)]
+    losses = [torch.zeros(1, dtype=torch.float32, device=st.dev) for _ in range(max(n_slots, 2))]
     serial = SerialSchedule(st)
     sched = OverlapSchedule(st) if overlap else serial
 
-    def step(schedule=sched):
+    def eager_step(schedule=sched):
         if schedule is serial:
             schedule.minibatch(dev_batches, outputs=outs[0], grad_outputs=gouts, grad_inputs=gins, losses=losses[:1])
         else:
             schedule.minibatch(dev_batches, outputs=outs, grad_outputs=gouts, grad_inputs=gins, losses=losses)
+
+    step = eager_step
+
+    graphed = None
+    if (args.graph == "on" or (args.graph == "auto" and overlap)) and wl.n_micro <= max(n_slots, 1):
+        eager_step()                # one eager step first (see GraphedMinibatch)
+        torch.cuda.synchronize()
+        if sched is serial:
+            graphed = GraphedMinibatch(sched, dev_batches, outputs=outs[0], grad_outputs=gouts, grad_inputs=gins, losses=losses[:1])
+        else:
+            graphed = GraphedMinibatch(sched, dev_batches, outputs=outs, grad_outputs=gouts, grad_inputs=gins, losses=losses)
+        step = graphed.replay       # the timed steps replay the graph
 
     if args.copy_calibration:
         # a copy of known size: reads MIB and writes MIB per launch (torch's elementwise kernel)
@@ -191,13 +211,13 @@ def main():
     samples_per_step = wl.micro_batch * wl.n_micro
     value = args.steps * samples_per_step / dt
     serial_value = None
-    if overlap:                       # the same steps with the calls in serial order, for reference
+    if overlap or graphed is not None:   # the same steps enqueued from the host in serial order, for reference
         for _ in range(2):
-            step(serial)
+            eager_step(serial)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         for _ in range(args.steps):
-            step(serial)
+            eager_step(serial)
         torch.cuda.synchronize()
         serial_value = args.steps * samples_per_step / (time.perf_counter() - t1)
 
@@ -207,7 +227,7 @@ def main():
         st.profile_enable(True)
         k_steps = max(1, min(args.steps, 20))
         for _ in range(k_steps):
-            step(serial)            # per-kernel durations are taken with the calls back to back on one stream
+            eager_step(serial)      # per-kernel durations are taken with the calls back to back on one stream, eagerly
         torch.cuda.synchronize()
         prof = st.profile_read()
         st.profile_enable(False)
@@ -304,9 +324,10 @@ def main():
         "dtype": "f32" if args.config == "tiny_mlp" else "bf16", "data": "synthetic",
         "config": {"workload": f"{args.config}: micro-batch {wl.micro_batch} x {wl.n_micro} micro-batches per step",
                    "micro_batch": wl.micro_batch, "micro_batches_per_step": wl.n_micro,
-                   "schedule": "overlap: fw_{k+1} concurrent with bw_k, two in-flight slots" if overlap else "serial",
+                   "schedule": f"overlap: forward calls on one stream, backward calls on another, {n_slots} in-flight slots" if overlap else "serial",
+                   "launch": "HIP graph replay of the whole step" if graphed is not None else "eager",
                    "launches_per_microbatch": st.num_launches(False) + st.num_launches(True),
-                   "serial_schedule_samples_per_s": serial_value},
+                   "serial_eager_samples_per_s": serial_value},
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
     }
     print(json.dumps(out))

@@ -27,8 +27,12 @@ class SerialSchedule:
 
 
 class OverlapSchedule:
-    """1F1B with two in-flight slots on two streams: forward calls on one, backward calls (and the
-    gradient reset) on the other.  The stage must have been created with at least two slots."""
+    """Forward calls on one stream, backward calls (and the gradient reset) on another; micro-batch k
+    uses stash slot k % slots, and fw_k waits for bw_{k - slots} (the slot's previous micro-batch).
+    The stage must have at least two slots.  With as many slots as micro-batches no forward call ever
+    waits for a backward call; that is the form to capture into a HIP graph (GraphedMinibatch): on
+    this ROCm release the capture of a forward-stream wait on a backward-stream event ends in a crash
+    of the runtime when the capture is closed (host side, at three micro-batches or more)."""
 
     def __init__(self, stage):
         torch = stage.torch
@@ -37,31 +41,61 @@ class OverlapSchedule:
         self.st = stage
         self.s_f = torch.cuda.Stream(device=stage.dev)   # default priority on both
         self.s_b = torch.cuda.Stream(device=stage.dev)
-        self.ev_f = [torch.cuda.Event() for _ in range(2)]
-        self.ev_b = [torch.cuda.Event() for _ in range(2)]
+        self.ev_f, self.ev_b = [], []      # one event per micro-batch and direction (an event is recorded once per mini-batch)
         self.ev_start = torch.cuda.Event()
 
     def minibatch(self, batches, outputs=None, grad_outputs=None, grad_inputs=None, losses=None):
-        """outputs: None or [per-slot list of output tensors] x 2; losses: None or one loss tensor per micro-batch
+        """outputs: None or one list of output tensors per slot; losses: None or one loss tensor per micro-batch
         (or per slot); grad_outputs / grad_inputs are shared by all backward calls (they run in order)."""
         st, torch = self.st, self.st.torch
+        while len(self.ev_f) < len(batches):
+            self.ev_f.append(torch.cuda.Event())
+            self.ev_b.append(torch.cuda.Event())
         main = torch.cuda.current_stream(st.dev)
         self.ev_start.record(main)
         self.s_f.wait_event(self.ev_start)
         self.s_b.wait_event(self.ev_start)
         with torch.cuda.stream(self.s_b):
             st.grad_reset()
+        slots = st.slots
         for k, mb in enumerate(batches):
-            slot = k & 1
+            slot = k % slots
             with torch.cuda.stream(self.s_f):
-                if k >= 2:
-                    self.s_f.wait_event(self.ev_b[slot])      # the slot's previous micro-batch has been consumed
+                if k >= slots:
+                    self.s_f.wait_event(self.ev_b[k - slots])   # the slot's previous micro-batch has been consumed
                 st.forward(slot, mb, outputs=None if outputs is None else outputs[slot],
                            loss=None if losses is None else losses[k % len(losses)])
-                self.ev_f[slot].record(self.s_f)
+                self.ev_f[k].record(self.s_f)
             with torch.cuda.stream(self.s_b):
-                self.s_b.wait_event(self.ev_f[slot])
+                self.s_b.wait_event(self.ev_f[k])
                 st.backward(slot, grad_outputs=grad_outputs, grad_inputs=grad_inputs)
-                self.ev_b[slot].record(self.s_b)
+                self.ev_b[k].record(self.s_b)
         main.wait_stream(self.s_f)
         main.wait_stream(self.s_b)
+
+
+class GraphedMinibatch:
+    """One whole mini-batch of a schedule (gradient reset, every fw_j and bw_j, the events between
+    the streams) captured once into a HIP graph and replayed: the stage's calls only enqueue kernels
+    on the streams they are given, so nothing in them needs the host again, and a step of a dozen
+    few-microsecond launches per micro-batch is no longer paced by the host.
+
+    The captured launches carry their arguments: a replay runs the SAME device buffers (inputs,
+    outputs, losses, gradient inputs), so new data is copied into those buffers before a replay, and
+    every replay is one complete mini-batch starting with the gradient reset -- which is also what
+    keeps the stage's host-side state (overwrite-on-first-backward, slots) consistent with the
+    recorded launches.  Capture after at least one eager mini-batch (the first one may clear whole
+    embedding-gradient tables, later ones only the touched rows).
+    """
+
+    def __init__(self, schedule, batches, outputs=None, grad_outputs=None, grad_inputs=None, losses=None):
+        torch = schedule.st.torch
+        self.schedule = schedule
+        self.keep = (batches, outputs, grad_outputs, grad_inputs, losses)
+        self.graph = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize(schedule.st.dev)
+        with torch.cuda.graph(self.graph):
+            schedule.minibatch(batches, outputs=outputs, grad_outputs=grad_outputs, grad_inputs=grad_inputs, losses=losses)
+
+    def replay(self):
+        self.graph.replay()

@@ -115,30 +115,84 @@ def test_config2_candle_uno_full():
 
 
 def test_config2_overlapped_schedule_matches_serial_and_oracle():
-    # the launch configuration bench.py times: fw_{k+1} on one stream while bw_k runs on another, two
-    # stash slots.  Backward calls stay in micro-batch order, so the accumulated gradients must be
+    # the launch configuration bench.py times: forward calls on one stream, backward calls on another,
+    # a stash slot per micro-batch, the whole mini-batch replayed from one HIP graph.  Backward calls stay in micro-batch order, so the accumulated gradients must be
     # bit-identical to the serial order, and they must match the oracle like the serial run does.
     import torch
     from paper_2406_17145_amd.schedule import OverlapSchedule
     wl = W.candle_uno()
     print(f"[case] {wl.name} overlapped schedule, two slots", flush=True)
     _, g_serial = run_gpu(wl)
-    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=2)
-    dev_batches = [st.stage_inputs(mb) for mb in wl.batches]
-    losses = [torch.zeros(1, dtype=torch.float32, device=st.dev) for _ in wl.batches]
-    gins = st.alloc_grad_inputs()
-    sched = OverlapSchedule(st)
-    for _ in range(3):                 # repeated mini-batches: events and slots are reused
-        sched.minibatch(dev_batches, outputs=[[], []], grad_inputs=gins, losses=losses)
-    st.sync_status()
-    g_overlap = st.grads_numpy()
-    for i in g_serial:
-        for k in g_serial[i]:
-            assert np.array_equal(g_serial[i][k], g_overlap[i][k]), (i, k)
+    losses = None
+    for slots in (2, wl.n_micro):      # fw_k waits for bw_{k-2}; then one slot per micro-batch (no such waits)
+        if losses is not None:
+            st.close()
+        st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=slots)
+        dev_batches = [st.stage_inputs(mb) for mb in wl.batches]
+        losses = [torch.zeros(1, dtype=torch.float32, device=st.dev) for _ in wl.batches]
+        gins = st.alloc_grad_inputs()
+        sched = OverlapSchedule(st)
+        for _ in range(3):             # repeated mini-batches: events and slots are reused
+            sched.minibatch(dev_batches, outputs=[[] for _ in range(slots)], grad_inputs=gins, losses=losses)
+        st.sync_status()
+        g_overlap = st.grads_numpy()
+        for i in g_serial:
+            for k in g_serial[i]:
+                assert np.array_equal(g_serial[i][k], g_overlap[i][k]), (slots, i, k)
     ora_stage, ora_res = run_oracle(wl)
     for j, (ost, _) in enumerate(ora_res):
         got = float(losses[j].cpu()[0])
         assert abs(got - ost.loss) <= wl.tol * abs(ost.loss), (j, got, ost.loss)
+    # the same mini-batch as ONE captured HIP graph (what bench.py replays): every replay, with eager
+    # work and synchronisations in between, must reproduce the eager gradients bit for bit
+    from paper_2406_17145_amd.schedule import GraphedMinibatch
+    graphed = GraphedMinibatch(sched, dev_batches, outputs=[[] for _ in range(wl.n_micro)], grad_inputs=gins, losses=losses)
+    scratch = torch.zeros(1 << 20, device=st.dev)
+    for rep in range(3):
+        for t in st.g_t.values():              # poison the accumulators: a replay must overwrite them
+            for g in t.values():
+                g.fill_(float("nan"))
+        for l in losses:
+            l.fill_(-1.0)
+        scratch.add_(1.0)                      # eager work between the replays
+        torch.cuda.synchronize()
+        graphed.replay()
+        torch.cuda.synchronize()
+        g_replay = st.grads_numpy()
+        for i in g_serial:
+            for k in g_serial[i]:
+                assert np.array_equal(g_serial[i][k], g_replay[i][k]), (rep, i, k)
+        for j, (ost, _) in enumerate(ora_res):
+            got = float(losses[j].cpu()[0])
+            assert abs(got - ost.loss) <= wl.tol * abs(ost.loss), (rep, j, got, ost.loss)
+    st.sync_status()
+    st.close()
+
+
+def test_graph_replay_with_embedding_tables_matches_eager():
+    # sparse path under graph replay: the gradient reset of a replay clears the rows the previous
+    # replay touched (log slots), the sort buffers are reused, and the result must stay bit-identical
+    import torch
+    from paper_2406_17145_amd.schedule import GraphedMinibatch, SerialSchedule
+    wl = W.dlrm(micro_batch=256, n_micro=2, n_tables=6, num_rows=5000, bottom=(64, 32, 128), top=(128, 64, 1))
+    print(f"[case] {wl.name} graph replay, serial schedule", flush=True)
+    _, g_eager = run_gpu(wl)
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params)
+    dev_batches = [st.stage_inputs(mb) for mb in wl.batches]
+    losses = [torch.zeros(1, dtype=torch.float32, device=st.dev)]
+    gins = st.alloc_grad_inputs()
+    sched = SerialSchedule(st)
+    sched.minibatch(dev_batches, outputs=[], grad_inputs=gins, losses=losses)      # eager first
+    graphed = GraphedMinibatch(sched, dev_batches, outputs=[], grad_inputs=gins, losses=losses)
+    for rep in range(3):
+        torch.cuda.synchronize()
+        graphed.replay()
+        torch.cuda.synchronize()
+        g = st.grads_numpy()
+        for i in g_eager:
+            for k in g_eager[i]:
+                assert np.array_equal(g_eager[i][k], g[i][k]), (rep, i, k)
+    st.sync_status()
     st.close()
 
 
