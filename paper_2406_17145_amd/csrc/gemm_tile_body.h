@@ -292,6 +292,144 @@ __device__ __forceinline__ void epilogue_wave(const GemmProb &p, void *Cout, con
   }
 }
 
+// ---- epilogue through LDS: whole rows instead of accumulator columns ------------------------
+// The accumulator layout gives a lane ONE column and sixteen rows of a 32 x 32 tile, so an epilogue
+// that works on it touches memory in 2-byte (bf16) pieces, sixteen rows apart.  Here a wave passes
+// its tile through a private LDS block, 32 rows x (32 TJ) columns at a time, and reads it back row-wise:
+// a lane then owns 8 consecutive columns of a row, every optional operand (residual / gradient
+// addend, stashed derivative or mask source, old gradient) is one or two 16-byte loads, the result
+// one 16-byte store (two for fp32), and the loads of a 32-row block are all requested before the
+// first is used.  For tiles that lie inside the matrix, with 16-byte aligned rows everywhere.
+constexpr int EPI_LDS_PAD = 4;   // floats: keeps rows 16-byte aligned and spreads them over the banks
+template <int TJ>
+constexpr int epi_lds_floats() { return 32 * (32 * TJ + EPI_LDS_PAD); }
+
+__device__ __forceinline__ bool epi_lds_ok(const GemmProb &p, const void *Cout, int form) {
+  if ((p.ldc & 7) || ((uintptr_t)Cout & 15)) return false;
+  if (form == FORM_DW) return true;                       // fp32 result, no optional operands
+  if (p.c_dtype != DT_BF16) return false;
+  if (p.res && (p.res_dtype != DT_BF16 || (p.ldres & 7) || ((uintptr_t)p.res & 15))) return false;
+  if (p.aux && (p.aux_dtype != DT_BF16 || (p.ldaux & 7) || ((uintptr_t)p.aux & 15))) return false;
+  if (form == FORM_FWD && p.bias && ((uintptr_t)p.bias & 15)) return false;
+  return true;
+}
+__device__ __forceinline__ void unpack_bf16x8(const u32x4 &u, float (&v)[8]) {
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    v[2 * e] = __uint_as_float(u[e] << 16);
+    v[2 * e + 1] = __uint_as_float(u[e] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ u32x4 pack_bf16x8(const float (&v)[8]) {
+  u32x4 u;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) u[e] = (uint32_t)f32_to_bf16_bits(v[2 * e]) | ((uint32_t)f32_to_bf16_bits(v[2 * e + 1]) << 16);
+  return u;
+}
+
+template <int FORM, int TI, int TJ>
+__device__ __forceinline__ void epilogue_wave_lds(const GemmProb &p, void *Cout, const f32x16 (&acc)[TI][TJ], int wr0, int wc0,
+                                                  int lane, int accumulate_dw, float *stage) {
+  constexpr int COLS = 32 * TJ, ST = COLS + EPI_LDS_PAD;
+  constexpr int LPR = COLS / 8, RPI = 64 / LPR, ITS = 32 / RPI;   // lanes per row, rows per step, steps per block
+  const int rl = lane / LPR, c8 = (lane % LPR) * 8;
+  const int col = wc0 + c8;
+  float bias[8] = {};
+  if (FORM == FORM_FWD && p.bias) {
+    const float4 b0 = *(const float4 *)(p.bias + col), b1 = *(const float4 *)(p.bias + col + 4);
+    bias[0] = b0.x; bias[1] = b0.y; bias[2] = b0.z; bias[3] = b0.w;
+    bias[4] = b1.x; bias[5] = b1.y; bias[6] = b1.z; bias[7] = b1.w;
+  }
+  const bool use_res = FORM != FORM_DW && p.res != nullptr;
+  const bool aux_in = FORM == FORM_DX && p.act != ACT_NONE;          // stashed derivative / mask source is read
+  const bool aux_out = FORM == FORM_FWD && p.act == ACT_GELU && p.aux != nullptr;   // derivative is stashed
+  // an absent bf16 operand is read from the result buffer instead (valid memory, value unused), so
+  // that the loads of a block carry no branch
+  const uint16_t *resp = use_res ? (const uint16_t *)p.res : (const uint16_t *)Cout;
+  const uint16_t *auxp = aux_in ? (const uint16_t *)p.aux : (const uint16_t *)Cout;
+  const int64_t ldr = use_res ? p.ldres : p.ldc, lda = aux_in ? p.ldaux : p.ldc;
+#pragma unroll
+  for (int i = 0; i < TI; ++i) {
+    // accumulators of the 32-row block -> LDS, in their own layout (a half-wave writes 32 consecutive floats)
+#pragma unroll
+    for (int j = 0; j < TJ; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) stage[(epi_row(r) + 4 * (lane >> 5)) * ST + 32 * j + (lane & 31)] = acc[i][j][r];
+    __builtin_amdgcn_wave_barrier();
+    const int row0 = wr0 + 32 * i + rl;
+    if (FORM == FORM_DW) {
+      float4 old[ITS][2];
+      float *c = (float *)Cout + (int64_t)row0 * p.ldc + col;
+      if (accumulate_dw) {
+#pragma unroll
+        for (int t = 0; t < ITS; ++t) {
+          old[t][0] = *(const float4 *)(c + (int64_t)t * RPI * p.ldc);
+          old[t][1] = *(const float4 *)(c + (int64_t)t * RPI * p.ldc + 4);
+        }
+      }
+#pragma unroll
+      for (int t = 0; t < ITS; ++t) {
+        float4 v0 = *(const float4 *)(stage + (rl + RPI * t) * ST + c8), v1 = *(const float4 *)(stage + (rl + RPI * t) * ST + c8 + 4);
+        if (accumulate_dw) {
+          v0 = make_float4(old[t][0].x + v0.x, old[t][0].y + v0.y, old[t][0].z + v0.z, old[t][0].w + v0.w);
+          v1 = make_float4(old[t][1].x + v1.x, old[t][1].y + v1.y, old[t][1].z + v1.z, old[t][1].w + v1.w);
+        }
+        *(float4 *)(c + (int64_t)t * RPI * p.ldc) = v0;
+        *(float4 *)(c + (int64_t)t * RPI * p.ldc + 4) = v1;
+      }
+    } else {
+      u32x4 res_raw[ITS], aux_raw[ITS];
+#pragma unroll
+      for (int t = 0; t < ITS; ++t) {
+        res_raw[t] = *(const u32x4 *)(resp + (int64_t)(row0 + RPI * t) * ldr + col);
+        aux_raw[t] = *(const u32x4 *)(auxp + (int64_t)(row0 + RPI * t) * lda + col);
+      }
+#pragma unroll
+      for (int t = 0; t < ITS; ++t) {
+        float v[8], rs[8], ax[8], d[8];
+        {
+          const float4 a = *(const float4 *)(stage + (rl + RPI * t) * ST + c8), b = *(const float4 *)(stage + (rl + RPI * t) * ST + c8 + 4);
+          v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+        }
+        unpack_bf16x8(res_raw[t], rs);
+        unpack_bf16x8(aux_raw[t], ax);
+        if (FORM == FORM_FWD) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] += bias[e];
+          if (p.act == ACT_RELU) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = v[e] > 0.0f ? v[e] : 0.0f;
+          } else if (p.act == ACT_GELU) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) gelu_both(v[e], v[e], d[e]);
+            if (aux_out) *(u32x4 *)((uint16_t *)p.aux + (int64_t)(row0 + RPI * t) * p.ldaux + col) = pack_bf16x8(d);
+          }
+          if (use_res) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += rs[e];
+          }
+        } else {
+          if (use_res) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += rs[e];
+          }
+          if (aux_in) {
+            if (p.act == ACT_RELU) {
+#pragma unroll
+              for (int e = 0; e < 8; ++e) v[e] = ax[e] > 0.0f ? v[e] : 0.0f;
+            } else {
+#pragma unroll
+              for (int e = 0; e < 8; ++e) v[e] *= ax[e];
+            }
+          }
+        }
+        *(u32x4 *)((uint16_t *)Cout + (int64_t)(row0 + RPI * t) * p.ldc + col) = pack_bf16x8(v);
+      }
+    }
+    __builtin_amdgcn_wave_barrier();   // the block is free again
+  }
+}
+
 // LDS elements (uint16) one 256-thread team needs: both operands, double buffered
 template <int FORM, int BM, int BN>
 struct TileLds {
