@@ -111,15 +111,15 @@ def other_traffic(wl):
 # (--copy-calibration); the summaries are kept under profiles/.  None where not measured.
 MEASURED_TRAFFIC = {
     # bytes per launch, averaged over the launches of the kernel family within a step
-    ("candle_uno", "gemm_bwd_merged_dx_dw"): 55.3e6,
-    ("candle_uno", "gemm_skinny_fwd"): 12.1e6,
-    ("hetero", "gemm_bwd_merged_dx_dw"): 145.3e6,
-    ("hetero", "gemm_skinny_fwd"): 70.3e6,
-    ("mmt", "gemm_big_fwd"): 173.0e6,
-    ("mmt", "gemm_big_dx"): 160.9e6,
-    ("mmt", "gemm_big_dw"): 162.2e6,
-    ("dlrm", "embedding_bwd_sort_segsum"): 65.8e6,
-    ("dlrm", "embedding_fwd"): 254.5e6,
+    ("candle_uno", "gemm_bwd_merged_dx_dw"): 50.5e6,
+    ("candle_uno", "gemm_skinny_fwd"): 12.9e6,
+    ("hetero", "gemm_bwd_merged_dx_dw"): 122.0e6,
+    ("hetero", "gemm_skinny_fwd"): 48.8e6,
+    ("mmt", "gemm_big_fwd"): 187.2e6,
+    ("mmt", "gemm_big_dx"): 168.1e6,
+    ("mmt", "gemm_big_dw"): 190.0e6,
+    ("dlrm", "embedding_bwd_sort_segsum"): 54.3e6,
+    ("dlrm", "embedding_fwd"): 253.8e6,
 }
 
 
