@@ -16,7 +16,7 @@
 // The backward pass of a level runs both consumers of dZ in ONE launch: workgroups of the first
 // records compute dX with the few-row body, the rest compute dW (+ db) with the tile body, two
 // 256-thread teams per workgroup on neighbouring tiles.
-#include "gemm_tile_body.h"
+#include "gemm_dw_ksplit_body.h"
 
 namespace gpp {
 
@@ -313,22 +313,30 @@ __global__ __launch_bounds__(64 * SkWaves<TI>::value) void k_gemm_skinny(const G
   gemm_skinny_body<FORM, TI, TJ>(p, blockIdx.x - p.blk_begin, lds_raw, ext);
 }
 
-// backward of one level in one launch: records with form DX run the few-row body, records with
-// form DW the 128 x 128 tile body, two teams per workgroup on tiles 2 * local and 2 * local + 1
+// backward of one level in one launch: records with form DX run the few-row body; records with
+// form DW either the 128 x 128 tile body, two teams per workgroup on tiles 2 * local and 2 * local + 1
+// (few rows to contract over), or, marked by split_k == BWD_DW_KSPLIT, the 64 x 64 tile body whose
+// waves split a long contraction (many rows)
 constexpr int BWD_DW_TILE = 128;
+constexpr int BWD_DW_KSPLIT = -64;
+int gemm_bwd_merged_ksplit_mark() { return BWD_DW_KSPLIT; }
 template <int TI, int TJ>
 __global__ __launch_bounds__(512) void k_gemm_bwd_merged(const GemmProb *__restrict__ probs, int n, int accumulate_dw,
                                                          ExtPtrs ext) {
   static_assert(SkWaves<TI>::value == 8, "the merged launch uses 512-thread workgroups");
   typedef TileLds<FORM_DW, BWD_DW_TILE, BWD_DW_TILE> DwLds;
   typedef SkLds<FORM_DX, TI, TJ> DxLds;
-  constexpr int BYTES = DxLds::BYTES > 4 * DwLds::ELEMS ? DxLds::BYTES : 4 * DwLds::ELEMS;
+  constexpr int BYTES0 = DxLds::BYTES > 4 * DwLds::ELEMS ? DxLds::BYTES : 4 * DwLds::ELEMS;
+  constexpr int BYTES = BYTES0 > KS_LDS_BYTES ? BYTES0 : KS_LDS_BYTES;
+  static_assert(BYTES <= 160 * 1024, "the merged launch's bodies do not fit the LDS");
   __shared__ __attribute__((aligned(16))) unsigned char lds_raw[BYTES];
   const int pi = find_prob(probs, n, blockIdx.x);
   const GemmProb p = probs[pi];
   const int local = blockIdx.x - p.blk_begin;
   if (p.form == FORM_DX) {
     gemm_skinny_body<FORM_DX, TI, TJ>(p, local, lds_raw, ext);
+  } else if (p.split_k == BWD_DW_KSPLIT) {
+    gemm_dw_ksplit_body(p, local, lds_raw, accumulate_dw);
   } else {
     const int team = threadIdx.x >> 8;
     // few rows to contract over: two k-steps in flight are enough and keep the kernel free of spills

@@ -191,6 +191,7 @@ void launch_gemm_skinny(const GemmProb *probs, int n, int total_blocks, int form
 void launch_gemm_bwd_merged(const GemmProb *probs, int n, int total_blocks, int row_tiles, int col_tiles,
                             int accumulate_dw, const ExtPtrs &ext, hipStream_t s);
 int gemm_bwd_merged_dw_tile();
+int gemm_bwd_merged_ksplit_mark();   // split_k value of a backward-weight record that runs the contraction-split body
 int gemm_bwd_merged_dw_blocks(int M, int N);
 int gemm_skinny_blocks(int M, int N, int row_tiles, int col_tiles);
 int gemm_skinny_row_tiles(int M);

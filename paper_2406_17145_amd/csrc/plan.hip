@@ -560,6 +560,24 @@ struct Emitter {
           }
         }
       int row_tiles = dx.empty() ? 0 : gemm_skinny_row_tiles(max_m);
+      // many rows but a small level (the MLPs of the recommendation workload): backward-data by the
+      // contraction-splitting few-row body over 64-row blocks, backward-weight by the 64 x 64 tiles
+      // whose waves split the long contraction -- the same two bodies the stand-alone launches
+      // would use, in one launch instead of two
+      bool dw_ksplit = false;
+      if (!dx.empty() && !dw.empty() && row_tiles == 0 && !(pl.flags & 2)) {
+        int64_t elems = 0;
+        int tiles128 = 0, min_k = 1 << 30;
+        for (auto &r : dx) elems += (int64_t)r.M * r.N;
+        for (auto &r : dw) {
+          tiles128 += gemm_mfma_tiles_for(128, r.M, r.N, nullptr);
+          min_k = std::min(min_k, r.K);
+        }
+        if (elems < (int64_t)128 * 128 * 256 && min_k >= 512 && tiles128 < 192) {
+          row_tiles = 2;
+          dw_ksplit = true;
+        }
+      }
       if (!dx.empty() && !dw.empty() && row_tiles > 0 && !(pl.flags & 2)) {
         int blocks = 0, col_tiles = 2;
         skinny_pick_tiles(dx, row_tiles, col_tiles, false);
@@ -570,9 +588,14 @@ struct Emitter {
         }
         for (auto &r : dw) {
           r.blk_begin = blocks;
-          r.split_k = 1;
-          r.tiles_n = (r.N + gemm_bwd_merged_dw_tile() - 1) / gemm_bwd_merged_dw_tile();
-          blocks += gemm_bwd_merged_dw_blocks(r.M, r.N);
+          if (dw_ksplit) {
+            r.split_k = gemm_bwd_merged_ksplit_mark();
+            blocks += gemm_dw_ksplit_blocks(r.M, r.N);
+          } else {
+            r.split_k = 1;
+            r.tiles_n = (r.N + gemm_bwd_merged_dw_tile() - 1) / gemm_bwd_merged_dw_tile();
+            blocks += gemm_bwd_merged_dw_blocks(r.M, r.N);
+          }
         }
         const bool ext = wants_ext(dx);
         dx.insert(dx.end(), dw.begin(), dw.end());
