@@ -279,27 +279,47 @@ __global__ __launch_bounds__(256) void k_ln_bwd_vec(const LnProb *__restrict__ p
       pg[j][e] = pb[j][e] = 0.0f;
     }
   }
+  // The rows of a wave are pipelined: while row r is reduced (two wave-wide sums, each a chain of
+  // shuffles) the 16-byte pieces of row r + 1 -- x, dy and the optional addend -- are already on their
+  // way.  Loads carry no branch: a lane without a chunk reads chunk 0, a row beyond the end re-reads the
+  // last row, an absent addend reads dy; the values are dropped.
+  struct RowRaw {
+    ln_u32x4 x[NCH], g[NCH], a[NCH];
+    float mu, rstd;
+  };
+  const uint16_t *addp = p.addend ? (const uint16_t *)p.addend : (const uint16_t *)p.dy;
+  const int64_t ldadd = p.addend ? p.ldadd : p.lddy;
+  const int row_first = blk * 32 + wave * 8;
+  auto fetch_row = [&](RowRaw &r, int row) {
+    const int rc = min(row, p.rows - 1);
+    r.mu = p.mean[rc];
+    r.rstd = p.rstd[rc];
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      const int ch = lane + 64 * j, cc = (ch < nchunks ? ch : 0) * 8;
+      r.x[j] = *(const ln_u32x4 *)((const uint16_t *)p.x + (int64_t)rc * p.ldx + cc);
+      r.g[j] = *(const ln_u32x4 *)((const uint16_t *)p.dy + (int64_t)rc * p.lddy + cc);
+      r.a[j] = *(const ln_u32x4 *)(addp + (int64_t)rc * ldadd + cc);
+    }
+  };
+  RowRaw cur, nxt;
+  fetch_row(cur, row_first);
   for (int rr = 0; rr < 8; ++rr) {
-    const int row = blk * 32 + wave * 8 + rr;
+    const int row = row_first + rr;
     if (row >= p.rows) break;
-    const float mu = p.mean[row], rstd = p.rstd[row];
-    const uint16_t *xr = (const uint16_t *)p.x + (int64_t)row * p.ldx;
-    const uint16_t *gr = (const uint16_t *)p.dy + (int64_t)row * p.lddy;
+    if (rr + 1 < 8) fetch_row(nxt, row + 1);
+    const float mu = cur.mu, rstd = cur.rstd;
     float xh[NCH][8], g[NCH][8];
     float s1 = 0.0f, s2 = 0.0f;
 #pragma unroll
     for (int j = 0; j < NCH; ++j) {
       const int ch = lane + 64 * j;
-      ln_u32x4 xv = {0u, 0u, 0u, 0u}, gv = {0u, 0u, 0u, 0u};
-      if (ch < nchunks) {
-        xv = *(const ln_u32x4 *)(xr + ch * 8);
-        gv = *(const ln_u32x4 *)(gr + ch * 8);
-      }
       float xf[8], dyf[8];
-      unpack8(xv, xf);
-      unpack8(gv, dyf);
+      unpack8(cur.x[j], xf);
+      unpack8(cur.g[j], dyf);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
+        if (ch >= nchunks) dyf[e] = 0.0f;
         xh[j][e] = ch < nchunks ? (xf[e] - mu) * rstd : 0.0f;
         pg[j][e] += dyf[e] * xh[j][e];
         pb[j][e] += dyf[e];
@@ -308,23 +328,25 @@ __global__ __launch_bounds__(256) void k_ln_bwd_vec(const LnProb *__restrict__ p
         s2 += g[j][e] * xh[j][e];
       }
     }
-    if (!p.y) continue;
-    const float m1 = wave_sum(s1) / (float)p.d, m2 = wave_sum(s2) / (float)p.d;
+    if (p.y) {
+      const float m1 = wave_sum(s1) / (float)p.d, m2 = wave_sum(s2) / (float)p.d;
 #pragma unroll
-    for (int j = 0; j < NCH; ++j) {
-      const int ch = lane + 64 * j;
-      if (ch >= nchunks) continue;
-      float v[8];
+      for (int j = 0; j < NCH; ++j) {
+        const int ch = lane + 64 * j;
+        if (ch >= nchunks) continue;
+        float v[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = rstd * (g[j][e] - m1 - xh[j][e] * m2);
-      if (p.addend) {
-        float af[8];
-        unpack8(*(const ln_u32x4 *)((const uint16_t *)p.addend + (int64_t)row * p.ldadd + ch * 8), af);
+        for (int e = 0; e < 8; ++e) v[e] = rstd * (g[j][e] - m1 - xh[j][e] * m2);
+        if (p.addend) {
+          float af[8];
+          unpack8(cur.a[j], af);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] += af[e];
+          for (int e = 0; e < 8; ++e) v[e] += af[e];
+        }
+        *(ln_u32x4 *)((uint16_t *)p.y + (int64_t)row * p.ldy + ch * 8) = pack8f(v);
       }
-      *(ln_u32x4 *)((uint16_t *)p.y + (int64_t)row * p.ldy + ch * 8) = pack8f(v);
     }
+    cur = nxt;
   }
   if (!p.partial) return;
   float *mine = part + (size_t)wave * 2 * p.d;
