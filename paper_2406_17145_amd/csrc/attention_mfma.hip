@@ -55,11 +55,12 @@ __device__ __forceinline__ Where where(const AttnProb &p, int blk) {
   return w;
 }
 
-// 16-byte chunk of row `row` (zero when the row is outside the sequence)
+// 16-byte chunk of row `row`.  No branch around the load (a wave waits for its earlier loads at a
+// branch): a row outside the sequence reads the last row instead.  Such rows only ever meet
+// probabilities that the tail mask has set to zero, or belong to queries / keys whose results are
+// not stored, so finite stand-in values are all that is needed.
 __device__ __forceinline__ u32x4 row_chunk(const void *base, int64_t ld, int64_t first_row, int row, int seq, int col) {
-  u32x4 v = {0u, 0u, 0u, 0u};
-  if (row < seq) v = *(const u32x4 *)((const uint16_t *)base + (first_row + row) * ld + col);
-  return v;
+  return *(const u32x4 *)((const uint16_t *)base + (first_row + min(row, seq - 1)) * ld + col);
 }
 // the four 8-element slices of a lane's own row that one MFMA operand chain over DH = 64 needs
 struct RowFrags {
@@ -145,7 +146,7 @@ __global__ __launch_bounds__(256) void k_attn_fwd_mfma(const AttnProb *__restric
   const int64_t first = (int64_t)w.b * p.seq;
   const int qcol = w.h * DH, kcol = d + w.h * DH, vcol = 2 * d + w.h * DH;
   const int my_q = w.r0 + wave * 32 + (lane & 31);
-  const float scale = rsqrtf((float)DH);
+  const float scale2 = rsqrtf((float)DH) * 1.4426950408889634f;   // 1/sqrt(dh) * log2(e)
 
   const RowFrags qf = load_row_frags(p.qkv, p.ld_qkv, first, my_q, p.seq, qcol);
   f32x16 o[2] = {zero16(), zero16()};
@@ -168,27 +169,37 @@ __global__ __launch_bounds__(256) void k_attn_fwd_mfma(const AttnProb *__restric
     f32x16 st = zero16();
 #pragma unroll
     for (int s = 0; s < 4; ++s) st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(lds_k[cur], s), qf.f[s], st, 0, 0, 0);
+    // softmax in base 2 (one multiply folds the 1/sqrt(dh) scale and log2 e; v_exp_f32 is 2^x); only the
+    // last tile of a ragged sequence needs the key mask; the running output is rescaled only when
+    // some lane's running maximum moved
+    if (t == nt - 1 && (p.seq % KT)) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (t * KT + acc_row(r) >= p.seq) st[r] = -1e30f;
+    }
     float mx = -1e30f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      st[r] = (t * KT + acc_row(r) < p.seq) ? st[r] * scale : -1e30f;
+      st[r] *= scale2;
       mx = fmaxf(mx, st[r]);
     }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m, mx);
-    const float alpha = __expf(m - m_new);
+    const float alpha = __builtin_amdgcn_exp2f(m - m_new);
     float ps = 0.0f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      st[r] = __expf(st[r] - m_new);
+      st[r] = __builtin_amdgcn_exp2f(st[r] - m_new);
       ps += st[r];
     }
     lsum = lsum * alpha + ps;
+    if (__ballot(m_new != m) != 0ull) {
+#pragma unroll
+      for (int dd = 0; dd < 2; ++dd)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[dd][r] *= alpha;
+    }
     m = m_new;
-#pragma unroll
-    for (int dd = 0; dd < 2; ++dd)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[dd][r] *= alpha;
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
       const bf16x8 pf = pack8(st, c);
@@ -199,7 +210,7 @@ __global__ __launch_bounds__(256) void k_attn_fwd_mfma(const AttnProb *__restric
     __syncthreads();
   }
   lsum += __shfl_xor(lsum, 32, 64);
-  if (lane < 32 && my_q < p.seq) p.lse[((int64_t)w.b * p.heads + w.h) * p.seq + my_q] = m + __logf(lsum);
+  if (lane < 32 && my_q < p.seq) p.lse[((int64_t)w.b * p.heads + w.h) * p.seq + my_q] = m * 0.6931471805599453f + __logf(lsum);
   store_transposed(stage, o, 1.0f / lsum, p.out, p.ld_out, first, w.r0, p.seq, w.h * DH);
 }
 
@@ -232,7 +243,8 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dq_mfma(const AttnProb *__rest
     delta = s + __shfl_xor(s, 32, 64);
     if (lane < 32 && my_q < p.seq) p.delta[stat] = delta;
   }
-  const float lse = my_q < p.seq ? p.lse[stat] : 0.0f;
+  const float scale2 = scale * 1.4426950408889634f;                              // 1/sqrt(dh) * log2(e)
+  const float lse2 = (my_q < p.seq ? p.lse[stat] : 0.0f) * 1.4426950408889634f;   // log-sum-exp in base 2
   f32x16 dq[2] = {zero16(), zero16()};
 
   const int nt = (p.seq + KT - 1) / KT;
@@ -256,9 +268,11 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dq_mfma(const AttnProb *__rest
       dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(lds_v[cur], s), gf.f[s], dp, 0, 0, 0);
     }
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const float pr = (t * KT + acc_row(r) < p.seq) ? __expf(st[r] * scale - lse) : 0.0f;
-      st[r] = pr * (dp[r] - delta);
+    for (int r = 0; r < 16; ++r) st[r] = __builtin_amdgcn_exp2f(st[r] * scale2 - lse2) * (dp[r] - delta);
+    if (t == nt - 1 && (p.seq % KT)) {   // keys beyond a ragged sequence
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (t * KT + acc_row(r) >= p.seq) st[r] = 0.0f;
     }
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
@@ -285,7 +299,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(const AttnProb *__res
   const int64_t first = (int64_t)w.b * p.seq;
   const int qcol = w.h * DH, kcol = d + w.h * DH, vcol = 2 * d + w.h * DH;
   const int my_k = w.r0 + wave * 32 + (lane & 31);
-  const float scale = rsqrtf((float)DH);
+  const float scale = rsqrtf((float)DH), scale2 = scale * 1.4426950408889634f;
   const int64_t stat0 = ((int64_t)w.b * p.heads + w.h) * p.seq;
 
   const RowFrags kf = load_row_frags(p.qkv, p.ld_qkv, first, my_k, p.seq, kcol);
@@ -301,7 +315,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(const AttnProb *__res
     s.b = row_chunk(p.dout, p.ld_dout, first, row, p.seq, w.h * DH + cc);
     if (threadIdx.x < KT) {
       const int q = t * KT + threadIdx.x;
-      n_lse = q < p.seq ? p.lse[stat0 + q] : 0.0f;
+      n_lse = q < p.seq ? p.lse[stat0 + q] * 1.4426950408889634f : 0.0f;   // base 2
       n_delta = q < p.seq ? p.delta[stat0 + q] : 0.0f;
     }
     return s;
@@ -325,10 +339,12 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(const AttnProb *__res
       st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(lds_q[cur], s), kf.f[s], st, 0, 0, 0);
       dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(lds_g[cur], s), vf.f[s], dp, 0, 0, 0);
     }
+    const bool tail = t == nt - 1 && (p.seq % KT);
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int qi = acc_row(r);
-      const float pr = (t * KT + qi < p.seq) ? __expf(st[r] * scale - lds_lse[cur][qi]) : 0.0f;
+      float pr = __builtin_amdgcn_exp2f(st[r] * scale2 - lds_lse[cur][qi]);
+      if (tail && t * KT + qi >= p.seq) pr = 0.0f;   // queries beyond a ragged sequence
       dp[r] = pr * (dp[r] - lds_delta[cur][qi]);
       st[r] = pr;
     }
