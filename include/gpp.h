@@ -175,6 +175,61 @@ gpp_status_t gpp_stage_sync_status(gpp_stage_t *stage, void *hip_stream);
 
 gpp_status_t gpp_stage_destroy(gpp_stage_t *stage);
 
+/* ---- Static micro-batch scheduler (paper section 6, Alg. 2; appendix "Generalized Per-stage kFkB
+ * Schedule").  HOST-only integer routines (no GPU needed) and the executor that runs their result. ---- */
+
+/* ComputeInFlight, the appendix table: in-flight SAMPLES *i_x of a stage S_x that runs k_x F k_x B at
+ * micro-batch size b_x in front of a stage S_y that runs k_y F k_y B at size b_y and holds i_y in-flight
+ * samples.  All arguments positive (k, b at most 2^30), else GPP_ERR_INVALID_ARG. */
+gpp_status_t gpp_compute_in_flight(int64_t k_x, int64_t b_x, int64_t k_y, int64_t b_y, int64_t i_y, int64_t *i_x);
+
+/* Schedules of a whole stage graph (section 6: the last stage first, then against the edges; appendix:
+ * k_x = argmin over the candidates of the largest table value over the successors of S_x).
+ *   edge_from[e] -> edge_to[e]   HOST, n_edges pairs of stage ids in [0, n_stages)
+ *   b[x]                         HOST, micro-batch size of S_x
+ *   k_values[k_begin[x] .. k_begin[x+1])   HOST, the candidate k of S_x (k_begin has n_stages + 1 entries)
+ *   i_out[x], k_out[x]           HOST, written: in-flight samples and chosen k of S_x
+ * A stage without successor holds one group, k * b samples; equal counts choose the smallest k.
+ * GPP_ERR_BAD_GRAPH if the stage graph has a cycle. */
+gpp_status_t gpp_assign_schedules(int32_t n_stages, int32_t n_edges, const int32_t *edge_from, const int32_t *edge_to,
+                                  const int64_t *b, const int32_t *k_begin, const int64_t *k_values, int64_t *i_out,
+                                  int64_t *k_out);
+
+/* ScheduleTask of Alg. 2 for the configuration c = (i, k, b) and n_micro micro-batches: the kFkB order of the
+ * footnote of section 6 with a warm-up of floor(i / b) forward passes (at least one; at most n_micro), groups of
+ * min(k, warm-up) backward and forward passes, every backward pass as early as that allows.
+ *   tasks   HOST, 2 * n_micro entries written: +(j+1) stands for fw_j, -(j+1) for bw_j */
+gpp_status_t gpp_schedule_tasks(int64_t n_micro, int64_t i, int64_t k, int64_t b, int32_t *tasks);
+
+/* Pointers of one micro-batch, with the meaning they have in gpp_stage_forward / gpp_stage_backward. */
+typedef struct {
+  const void *const *inputs;
+  void *const *outputs;
+  float *loss_out;
+  const void *const *grad_outputs;
+  void *const *grad_inputs;
+} gpp_microbatch_io_t;
+
+/* One mini-batch of the stage under a task list (Pi_i of section 3): gradient reset, then every task in
+ * order; micro-batch j uses stash slot j % in_flight_slots.
+ *   tasks[n_tasks]   HOST, n_tasks = 2 * n_micro, encoded as by gpp_schedule_tasks
+ *   io[n_micro]      HOST array; the pointers inside are DEVICE pointers (arrays of them HOST)
+ *   stream_forward / stream_backward   HIP streams of the forward and of the backward passes (and the
+ *                    reset).  Equal: everything runs in task order.  Different: fw_j and bw_j' of different
+ *                    micro-batches may overlap on the GPU, which C4 allows; the call orders bw_j after fw_j and
+ *                    fw_j after bw_{j - in_flight_slots} with events (created on first use, kept by the stage).
+ *                    Ordering against earlier and later work on other streams is the caller's.
+ * The whole list is validated before anything is enqueued: GPP_ERR_ORDER if it violates C4 or holds more
+ * micro-batches in flight than the stage has slots (nothing has run then). */
+gpp_status_t gpp_stage_run_schedule(gpp_stage_t *stage, const int32_t *tasks, int64_t n_tasks,
+                                    const gpp_microbatch_io_t *io, int64_t n_micro, void *stream_forward,
+                                    void *stream_backward);
+
+/* Workspace use: bytes of ONE activation stash slot (the memory an in-flight micro-batch pins, section 2),
+ * bytes shared by all slots (backward scratch, launch tables, sort buffers), and their total for this
+ * stage's in_flight_slots.  Any pointer may be NULL. */
+gpp_status_t gpp_stage_memory(const gpp_stage_t *stage, size_t *slot_bytes, size_t *shared_bytes, size_t *total_bytes);
+
 /* Introspection (tests, benchmarks). */
 int32_t gpp_stage_num_inputs(const gpp_stage_t *stage);
 int32_t gpp_stage_num_outputs(const gpp_stage_t *stage);

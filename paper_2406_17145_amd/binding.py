@@ -49,9 +49,15 @@ EXPORTS = [
     "gpp_stage_grad_reset", "gpp_stage_sync_status", "gpp_stage_destroy", "gpp_stage_num_inputs",
     "gpp_stage_num_outputs", "gpp_stage_input_op", "gpp_stage_output_op", "gpp_stage_num_launches",
     "gpp_stage_embedding_sort_result", "gpp_last_error", "gpp_stage_profile_enable", "gpp_stage_profile_read",
-    "gpp_profile_tag_name",
+    "gpp_profile_tag_name", "gpp_compute_in_flight", "gpp_assign_schedules", "gpp_schedule_tasks",
+    "gpp_stage_run_schedule", "gpp_stage_memory",
 ]
 GPP_PROFILE_TAGS = 32
+
+class MicrobatchIO(C.Structure):
+    _fields_ = [("inputs", C.POINTER(C.c_void_p)), ("outputs", C.POINTER(C.c_void_p)), ("loss_out", C.c_void_p),
+                ("grad_outputs", C.POINTER(C.c_void_p)), ("grad_inputs", C.POINTER(C.c_void_p))]
+
 
 _lib = None
 _hip = None
@@ -96,6 +102,15 @@ def load():
     lib.gpp_stage_profile_read.restype = i32
     lib.gpp_stage_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), i32]
     lib.gpp_profile_tag_name.restype, lib.gpp_profile_tag_name.argtypes = C.c_char_p, [i32]
+    lib.gpp_compute_in_flight.restype = i32
+    lib.gpp_compute_in_flight.argtypes = [i64] * 5 + [C.POINTER(i64)]
+    lib.gpp_assign_schedules.restype = i32
+    lib.gpp_assign_schedules.argtypes = [i32, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i64), C.POINTER(i32),
+                                         C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
+    lib.gpp_schedule_tasks.restype, lib.gpp_schedule_tasks.argtypes = i32, [i64, i64, i64, i64, C.POINTER(i32)]
+    lib.gpp_stage_run_schedule.restype = i32
+    lib.gpp_stage_run_schedule.argtypes = [vp, C.POINTER(i32), i64, C.POINTER(MicrobatchIO), i64, vp, vp]
+    lib.gpp_stage_memory.restype, lib.gpp_stage_memory.argtypes = i32, [vp] + [C.POINTER(C.c_size_t)] * 3
     _lib = lib
     return lib
 
@@ -185,6 +200,61 @@ def gpp_stage_grad_reset(handle, stream):
 
 def gpp_stage_sync_status(handle, stream):
     _check(load().gpp_stage_sync_status(handle, stream))
+
+
+def gpp_compute_in_flight(k_x, b_x, k_y, b_y, i_y):
+    out = C.c_int64()
+    _check(load().gpp_compute_in_flight(k_x, b_x, k_y, b_y, i_y, C.byref(out)))
+    return out.value
+
+
+def gpp_assign_schedules(n_stages, edges, b, k_candidates):
+    """edges: (x, y) pairs, S_x feeds S_y; returns (i, k) lists, one entry per stage."""
+    n_e = len(edges)
+    ef = (C.c_int32 * max(1, n_e))(*[e[0] for e in edges])
+    et = (C.c_int32 * max(1, n_e))(*[e[1] for e in edges])
+    kb, kv = [0], []
+    for ks in k_candidates:
+        kv += list(ks)
+        kb.append(len(kv))
+    i_out, k_out = (C.c_int64 * n_stages)(), (C.c_int64 * n_stages)()
+    _check(load().gpp_assign_schedules(n_stages, n_e, ef, et, (C.c_int64 * n_stages)(*b), (C.c_int32 * len(kb))(*kb),
+                                       (C.c_int64 * max(1, len(kv)))(*kv), i_out, k_out))
+    return list(i_out), list(k_out)
+
+
+def gpp_schedule_tasks(n_micro, i, k, b):
+    """Task codes: +(j+1) = fw_j, -(j+1) = bw_j."""
+    tasks = (C.c_int32 * max(1, 2 * n_micro))()
+    _check(load().gpp_schedule_tasks(n_micro, i, k, b, tasks))
+    return list(tasks)[:2 * n_micro]
+
+
+def gpp_stage_run_schedule(handle, tasks, io, stream_forward, stream_backward):
+    """io: one (input_ptrs, output_ptrs or None, loss_ptr or None, grad_output_ptrs or None, grad_input_ptrs or None)
+    per micro-batch.  Returns the marshalled arrays; keep them while a captured graph of the call may replay
+    (the call itself reads them on the host only)."""
+    keep = []
+
+    def arr(ptrs):
+        if ptrs is None:
+            return None
+        a = _ptr_array(ptrs)
+        keep.append(a)
+        return a
+    ios = (MicrobatchIO * max(1, len(io)))()
+    for m, (inp, out, loss, gout, gin) in zip(ios, io):
+        m.inputs, m.outputs, m.loss_out, m.grad_outputs, m.grad_inputs = arr(inp), arr(out), loss, arr(gout), arr(gin)
+    t = (C.c_int32 * max(1, len(tasks)))(*tasks)
+    _check(load().gpp_stage_run_schedule(handle, t, len(tasks), ios, len(io), stream_forward, stream_backward))
+    return keep
+
+
+def gpp_stage_memory(handle):
+    """(bytes of one stash slot, bytes shared by all slots, total workspace bytes)."""
+    a, b, c = C.c_size_t(), C.c_size_t(), C.c_size_t()
+    _check(load().gpp_stage_memory(handle, C.byref(a), C.byref(b), C.byref(c)))
+    return a.value, b.value, c.value
 
 
 def gpp_stage_destroy(handle):

@@ -31,6 +31,9 @@ static gpp_status_t fail(gpp_status_t st, const std::string &msg) {
   g_last_error = msg;
   return st;
 }
+namespace gpp {
+gpp_status_t report_error(gpp_status_t st, const std::string &msg) { return fail(st, msg); }
+}
 
 struct gpp_stage {
   Plan plan;
@@ -54,6 +57,8 @@ struct gpp_stage {
   size_t prof_used = 0;
   double prof_ms[GPP_PROFILE_TAGS] = {0};
   int64_t prof_launches[GPP_PROFILE_TAGS] = {0};
+  // events of the schedule executor (created on first use, two per micro-batch, no timing)
+  std::vector<hipEvent_t> sched_ev;
 };
 
 // profile tag of a step: grouped-GEMM steps are split by form, element-wise steps by direction
@@ -177,8 +182,10 @@ gpp_status_t gpp_stage_create(const gpp_stage_desc_t *desc, void *workspace, siz
 }
 
 gpp_status_t gpp_stage_destroy(gpp_stage_t *stage) {
-  if (stage)
+  if (stage) {
     for (hipEvent_t e : stage->prof_ev) (void)hipEventDestroy(e);
+    for (hipEvent_t e : stage->sched_ev) (void)hipEventDestroy(e);
+  }
   delete stage;
   return GPP_OK;
 }
@@ -358,6 +365,79 @@ gpp_status_t gpp_stage_grad_reset(gpp_stage_t *st, void *hip_stream) {
     st->emb_logged = 0;
     hipError_t he = hipGetLastError();
     if (he != hipSuccess) return fail(GPP_ERR_DEVICE, std::string("HIP launch: ") + hipGetErrorString(he));
+  }
+  return GPP_OK;
+}
+
+gpp_status_t gpp_stage_memory(const gpp_stage_t *st, size_t *slot_bytes, size_t *shared_bytes, size_t *total_bytes) {
+  if (!st) return fail(GPP_ERR_INVALID_ARG, "stage is null");
+  if (slot_bytes) *slot_bytes = (size_t)st->plan.slot_bytes;
+  if (shared_bytes) *shared_bytes = (size_t)(st->plan.total_bytes - (int64_t)st->plan.slots * st->plan.slot_bytes);
+  if (total_bytes) *total_bytes = (size_t)st->plan.total_bytes;
+  return GPP_OK;
+}
+
+// One mini-batch under a task list.  The whole list is checked against C4 and the number of stash
+// slots before the first kernel is enqueued, so a refused list leaves the stage untouched.
+gpp_status_t gpp_stage_run_schedule(gpp_stage_t *st, const int32_t *tasks, int64_t n_tasks, const gpp_microbatch_io_t *io,
+                                    int64_t n_micro, void *stream_forward, void *stream_backward) {
+  if (!st) return fail(GPP_ERR_INVALID_ARG, "stage is null");
+  if (n_micro < 0 || n_tasks != 2 * n_micro) return fail(GPP_ERR_INVALID_ARG, "a mini-batch of n micro-batches has 2n tasks");
+  if (n_micro > 0 && (!tasks || !io)) return fail(GPP_ERR_INVALID_ARG, "tasks or io is null");
+  if (!st->fifo.empty()) return fail(GPP_ERR_ORDER, "run_schedule while a micro-batch is in flight");
+  const int slots = st->plan.slots;
+  {
+    int64_t f = 0, b = 0;   // forward / backward passes seen so far
+    for (int64_t t = 0; t < n_tasks; ++t) {
+      const int64_t v = tasks[t];
+      if (v > 0) {
+        if (v - 1 != f) return fail(GPP_ERR_ORDER, "task " + std::to_string(t) + ": forward passes must come in micro-batch order (C4)");
+        if (f - b >= slots)
+          return fail(GPP_ERR_ORDER, "task " + std::to_string(t) + ": more micro-batches in flight than the stage has stash slots (" +
+                                         std::to_string(slots) + ")");
+        ++f;
+      } else if (v < 0) {
+        if (-v - 1 != b) return fail(GPP_ERR_ORDER, "task " + std::to_string(t) + ": backward passes must come in micro-batch order (C4)");
+        if (b >= f) return fail(GPP_ERR_ORDER, "task " + std::to_string(t) + ": backward pass before its forward pass (C4)");
+        ++b;
+      } else {
+        return fail(GPP_ERR_INVALID_ARG, "task " + std::to_string(t) + " is zero");
+      }
+    }
+  }
+  hipStream_t sf = (hipStream_t)stream_forward, sb = (hipStream_t)stream_backward;
+  const bool two = sf != sb;
+  if (two) {
+    while ((int64_t)st->sched_ev.size() < 2 * n_micro) {
+      hipEvent_t e;
+      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return fail(GPP_ERR_DEVICE, "hipEventCreate failed");
+      st->sched_ev.push_back(e);
+    }
+  }
+  gpp_status_t rc = gpp_stage_grad_reset(st, sb);
+  if (rc != GPP_OK) return rc;
+  for (int64_t t = 0; t < n_tasks; ++t) {
+    const int64_t j = (tasks[t] > 0 ? tasks[t] : -tasks[t]) - 1;
+    const int32_t slot = (int32_t)(j % slots);
+    const gpp_microbatch_io_t &m = io[j];
+    hipError_t he = hipSuccess;
+    if (tasks[t] > 0) {
+      // the slot's previous micro-batch must have been consumed by its backward pass
+      if (two && j >= slots) he = hipStreamWaitEvent(sf, st->sched_ev[2 * (j - slots) + 1], 0);
+      if (he == hipSuccess) {
+        rc = gpp_stage_forward(st, slot, m.inputs, m.outputs, m.loss_out, sf);
+        if (rc != GPP_OK) return rc;
+        if (two) he = hipEventRecord(st->sched_ev[2 * j], sf);
+      }
+    } else {
+      if (two) he = hipStreamWaitEvent(sb, st->sched_ev[2 * j], 0);
+      if (he == hipSuccess) {
+        rc = gpp_stage_backward(st, slot, m.grad_outputs, m.grad_inputs, sb);
+        if (rc != GPP_OK) return rc;
+        if (two) he = hipEventRecord(st->sched_ev[2 * j + 1], sb);
+      }
+    }
+    if (he != hipSuccess) return fail(GPP_ERR_DEVICE, std::string("HIP event: ") + hipGetErrorString(he));
   }
   return GPP_OK;
 }

@@ -74,6 +74,68 @@ class OverlapSchedule:
         main.wait_stream(self.s_b)
 
 
+class TaskSchedule:
+    """The kFkB order of paper section 6 for one stage, from the library's ScheduleTask for the configuration
+    c = (i, k, b) (in-flight samples, group size, micro-batch size), run by the library's executor: warm-up of
+    i / b forward passes, then k backward and k forward passes in turn, cool-down.  The stage must have been
+    created with at least i / b stash slots.  With two_streams the forward passes go to one stream and the
+    backward passes to another (C4 allows them to overlap); otherwise everything runs in task order on the
+    current stream."""
+
+    def __init__(self, stage, in_flight_samples, k, two_streams=True):
+        from . import binding as B
+        torch = stage.torch
+        self.B, self.st = B, stage
+        self.i, self.k = int(in_flight_samples), int(k)
+        cap = max(1, self.i // stage.b)
+        if stage.slots < cap:
+            raise ValueError(f"{cap} micro-batches in flight need a stage with in_flight_slots >= {cap}")
+        self.two = bool(two_streams)
+        if self.two:
+            self.s_f = torch.cuda.Stream(device=stage.dev)   # default priority on both
+            self.s_b = torch.cuda.Stream(device=stage.dev)
+        self._keep = None
+
+    def tasks(self, n_micro):
+        return self.B.gpp_schedule_tasks(n_micro, self.i, self.k, self.st.b)
+
+    def minibatch(self, batches, outputs=None, grad_outputs=None, grad_inputs=None, losses=None):
+        """batches: one list of device tensors (Stage.stage_inputs) per micro-batch.  outputs: one list of output
+        tensors per slot or per micro-batch (micro-batch j writes outputs[j % len(outputs)]); losses likewise.
+        grad_outputs / grad_inputs: one list of tensors shared by all backward passes (they run in order), or one
+        list per micro-batch."""
+        st, torch, B = self.st, self.st.torch, self.B
+        if outputs is None:
+            outputs = self._outs = getattr(self, "_outs", None) or [st.alloc_outputs() for _ in range(st.slots)]
+        if grad_inputs is None:
+            grad_inputs = self._gin = getattr(self, "_gin", None) or st.alloc_grad_inputs()
+        if losses is None:
+            losses = [st.loss]
+
+        def per_microbatch(x, j):
+            if not x:
+                return None
+            row = x[j % len(x)] if isinstance(x[0], (list, tuple)) else x
+            return [t.data_ptr() if t is not None else None for t in row]
+        io = []
+        for j, mb in enumerate(batches):
+            io.append(([t.data_ptr() for t in mb], [t.data_ptr() for t in outputs[j % len(outputs)]],
+                       losses[j % len(losses)].data_ptr(), per_microbatch(grad_outputs, j), per_microbatch(grad_inputs, j)))
+        tasks = self.tasks(len(batches))
+        main = torch.cuda.current_stream(st.dev)
+        if self.two:
+            self.s_f.wait_stream(main)
+            self.s_b.wait_stream(main)
+            sf, sb = self.s_f.cuda_stream, self.s_b.cuda_stream
+        else:
+            sf = sb = main.cuda_stream
+        self._keep = (B.gpp_stage_run_schedule(st.handle, tasks, io, sf, sb), batches, outputs, grad_outputs, grad_inputs, losses)
+        if self.two:
+            main.wait_stream(self.s_f)
+            main.wait_stream(self.s_b)
+        return tasks
+
+
 class GraphedMinibatch:
     """One whole mini-batch of a schedule (gradient reset, every fw_j and bw_j, the events between
     the streams) captured once into a HIP graph and replayed: the stage's calls only enqueue kernels

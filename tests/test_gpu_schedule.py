@@ -1,0 +1,136 @@
+"""kFkB schedules of one stage on the GPU: the library's executor (gpp_stage_run_schedule) under the task
+lists of gpp_schedule_tasks, against the serial order and against the oracle.  Backward passes run in
+micro-batch order under every schedule, so accumulated gradients must be bit-identical to the serial run."""
+import numpy as np
+import pytest
+
+from oracle import schedule_oracle as S
+from paper_2406_17145_amd import binding as B
+from paper_2406_17145_amd import workloads as W
+from paper_2406_17145_amd.schedule import TaskSchedule
+from tests.parity_util import compare, run_gpu, run_oracle, t2n
+
+pytestmark = pytest.mark.gpu
+
+
+def _codes(tasks):
+    return [(j + 1) if w == "F" else -(j + 1) for w, j in tasks]
+
+
+def _run(wl, cap, k, two_streams, slots=None, gouts=None, reps=1):
+    import torch
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=slots or cap)
+    n = len(wl.batches)
+    dev_batches = [st.stage_inputs(mb) for mb in wl.batches]
+    losses = [torch.zeros(1, dtype=torch.float32, device=st.dev) for _ in range(n)]
+    outs = [st.alloc_outputs() for _ in range(n)]
+    gins = [st.alloc_grad_inputs() for _ in range(n)]
+    dg = None if gouts is None else [[st.to_device(i, g[i]) for i in st.output_ids] for g in gouts]
+    sched = TaskSchedule(st, cap * wl.micro_batch, k, two_streams=two_streams)
+    for _ in range(reps):
+        tasks = sched.minibatch(dev_batches, outputs=outs, grad_outputs=dg, grad_inputs=gins, losses=losses)
+    st.sync_status()
+    res = [dict(loss=float(losses[j].cpu()[0]), outs={i: t2n(t) for i, t in zip(st.output_ids, outs[j])},
+                gin={i: t2n(t) for i, t in zip(st.input_ids, gins[j]) if t is not None}) for j in range(n)]
+    grads = st.grads_numpy()
+    st.close()
+    return tasks, res, grads
+
+
+@pytest.mark.parametrize("two_streams", [False, True])
+def test_kfkb_schedules_on_loss_stage_match_serial_and_oracle(two_streams):
+    wl = W.candle_uno(micro_batch=48, n_micro=7, widths=(70, 131, 9, 33), hidden=160, act="gelu")
+    _, g_serial = run_gpu(wl)
+    ora_stage, ora_res = run_oracle(wl)
+    for cap, k in [(1, 1), (2, 1), (3, 2), (4, 2), (4, 4), (7, 3)]:
+        print(f"[case] {wl.name} kFkB cap={cap} k={k} two_streams={two_streams}", flush=True)
+        tasks, res, grads = _run(wl, cap, k, two_streams, reps=2)
+        assert tasks == _codes(S.schedule_task(wl.n_micro, cap * wl.micro_batch, k, wl.micro_batch))
+        for i in g_serial:
+            for kk in g_serial[i]:
+                assert np.array_equal(g_serial[i][kk], grads[i][kk]), (cap, k, i, kk)
+        compare(wl, res, grads, ora_stage, ora_res, label=f"kFkB cap={cap} k={k}")
+
+
+def test_kfkb_schedule_on_mid_pipeline_stage_with_per_microbatch_gradients():
+    # a stage with outputs: every micro-batch has its own output, output-gradient and input-gradient buffers
+    wl = W.hetero(micro_batch=9, n_micro=5, base_width=16, out_width=24, dtype="f32", with_loss=False)
+    out = len(wl.ops) - 1
+    rng = np.random.default_rng(5)
+    gouts = [{out: rng.standard_normal((9, 192)).astype(np.float32)} for _ in range(5)]
+    ora_stage, ora_res = run_oracle(wl, gouts)
+    res_serial, g_serial = run_gpu(wl, gouts=gouts)
+    for cap, k, two in [(3, 1, True), (2, 2, False), (5, 2, True)]:
+        print(f"[case] {wl.name} mid-pipeline kFkB cap={cap} k={k} two_streams={two}", flush=True)
+        _, res, grads = _run(wl, cap, k, two, gouts=gouts)
+        compare(wl, res, grads, ora_stage, ora_res, label=f"mid kFkB cap={cap} k={k}")
+        for i in g_serial:
+            for kk in g_serial[i]:
+                assert np.array_equal(g_serial[i][kk], grads[i][kk]), (cap, k, i, kk)
+        for a, b in zip(res_serial, res):
+            for i in a["gin"]:
+                assert np.array_equal(a["gin"][i], b["gin"][i])
+            for i in a["outs"]:
+                assert np.array_equal(a["outs"][i], b["outs"][i])
+
+
+def test_kfkb_schedule_with_embedding_tables():
+    # sparse path: sort buffers shared by the slots, touched-row log across five backward passes
+    wl = W.dlrm(micro_batch=128, n_micro=5, n_tables=4, num_rows=3000, bottom=(64, 32, 128), top=(128, 64, 1))
+    _, g_serial = run_gpu(wl)
+    ora_stage, ora_res = run_oracle(wl)
+    for cap, k, two in [(2, 1, True), (3, 2, True)]:
+        print(f"[case] {wl.name} kFkB cap={cap} k={k} two_streams={two}", flush=True)
+        _, res, grads = _run(wl, cap, k, two, reps=2)
+        compare(wl, res, grads, ora_stage, ora_res, label=f"dlrm kFkB cap={cap} k={k}")
+        for i in g_serial:
+            for kk in g_serial[i]:
+                assert np.array_equal(g_serial[i][kk], grads[i][kk]), (cap, k, i, kk)
+
+
+def test_executor_refuses_invalid_task_lists_before_running_anything():
+    import torch
+    wl = W.tiny_mlp()
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=2)
+    n = len(wl.batches)
+    dev = [st.stage_inputs(mb) for mb in wl.batches]
+    losses = [torch.zeros(1, dtype=torch.float32, device=st.dev) for _ in range(n)]
+    io = [([t.data_ptr() for t in dev[j]], [], losses[j].data_ptr(), None, [None] * len(dev[j])) for j in range(n)]
+    s = torch.cuda.current_stream().cuda_stream
+    bad = {
+        "backward before its forward": [-1, 1, 2, -2, 3, -3, 4, -4],
+        "forward out of order": [2, 1, -1, -2, 3, -3, 4, -4],
+        "backward out of order": [1, 2, -2, -1, 3, -3, 4, -4],
+        "three in flight, two slots": [1, 2, 3, -1, -2, -3, 4, -4],
+        "repeated forward": [1, 1, -1, -1, 2, -2, 3, -3],
+    }
+    for why, tasks in bad.items():
+        with pytest.raises(B.GppError) as e:
+            B.gpp_stage_run_schedule(st.handle, tasks, io, s, s)
+        assert e.value.status == B.GPP_ERR_ORDER, why
+    for tasks in ([1, 0, -1, 2, -2, 3, -3, 4], [1, -1, 2, -2]):      # a zero code; wrong length
+        with pytest.raises(B.GppError) as e:
+            B.gpp_stage_run_schedule(st.handle, tasks, io, s, s)
+        assert e.value.status == B.GPP_ERR_INVALID_ARG
+    # nothing ran and no slot is held: a valid list goes through and gives the serial result
+    B.gpp_stage_run_schedule(st.handle, B.gpp_schedule_tasks(n, 2 * wl.micro_batch, 1, wl.micro_batch), io, s, s)
+    st.sync_status()
+    got = st.grads_numpy()
+    st.close()
+    _, ref = run_gpu(wl)
+    for i in ref:
+        for k in ref[i]:
+            assert np.array_equal(ref[i][k], got[i][k])
+
+
+def test_stage_memory_report():
+    wl = W.candle_uno(micro_batch=64, n_micro=1, widths=(96, 200, 8, 64), hidden=128)
+    seen = {}
+    for slots in (1, 3):
+        st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=slots)
+        slot_b, shared_b, total_b = B.gpp_stage_memory(st.handle)
+        assert total_b == st.ws_bytes == slots * slot_b + shared_b
+        assert slot_b > 0 and slot_b % 256 == 0
+        seen[slots] = (slot_b, shared_b)
+        st.close()
+    assert seen[1][0] == seen[3][0]            # one slot costs the same whatever their number
