@@ -130,15 +130,23 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="candle_uno", choices=["tiny_mlp", "candle_uno", "mmt", "dlrm", "hetero"])
     ap.add_argument("--micro-batch", type=int, default=0, help="override the config's micro-batch size")
-    ap.add_argument("--schedule", default="auto", choices=["auto", "serial", "overlap"],
+    ap.add_argument("--in-flight", type=int, default=0, metavar="M",
+                    help="--schedule kfkb: micro-batches the stage may hold (its stash slots; i = M * micro-batch samples); "
+                         "0 = all micro-batches of a step, at most 8")
+    ap.add_argument("--k", type=int, default=0, help="--schedule kfkb: group size k of the kFkB order; 0 = M")
+    ap.add_argument("--one-stream", action="store_true", help="--schedule kfkb: all tasks on one stream, in task order")
+    ap.add_argument("--schedule", default="auto", choices=["auto", "serial", "overlap", "kfkb"],
                     help="micro-batch schedule of a step: serial = fw_k bw_k in turn on one stream; overlap = fw_{k+1} "
-                         "runs while bw_k runs (two in-flight slots, two streams); auto = overlap when the workload "
-                         "has at least two micro-batches per step")
+                         "runs while bw_k runs (a slot per micro-batch, two streams, enqueued by the Python binding); "
+                         "kfkb = the scheduler's kFkB task list for c = (i, k, b), run by the library's executor "
+                         "(forward and backward passes on two streams); auto = kfkb when the workload has at least "
+                         "two micro-batches per step, else serial")
     ap.add_argument("--graph", default="auto", choices=["auto", "on", "off"],
                     help="on: the step (all its launches on both streams) is captured once into a HIP graph and "
-                         "replayed; off: every step is enqueued from the host; auto: on with the overlapped schedule "
-                         "(where the host would pace the two streams), off with the serial one (measured: replay is "
-                         "1-3 %% slower than eager launches there)")
+                         "replayed; off: every step is enqueued from the host; auto: on with the two-stream schedules "
+                         "when the stage has a slot per micro-batch of the step (a captured forward pass cannot wait "
+                         "for a backward pass), off with the serial one (measured: replay is 1-3 %% slower than eager "
+                         "launches there)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-pass", action="store_true", help="skip the event-instrumented second pass")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -158,11 +166,15 @@ def main():
     if args.micro_batch:
         kw["micro_batch"] = args.micro_batch
     wl = W.CONFIGS[args.config](**kw)
-    from paper_2406_17145_amd.schedule import GraphedMinibatch, OverlapSchedule, SerialSchedule
-    overlap = args.schedule == "overlap" or (args.schedule == "auto" and wl.n_micro >= 2)
+    from paper_2406_17145_amd.schedule import GraphedMinibatch, OverlapSchedule, SerialSchedule, TaskSchedule
+    kfkb = args.schedule == "kfkb" or (args.schedule == "auto" and wl.n_micro >= 2)
+    overlap = args.schedule == "overlap"
+    if kfkb:
+        args.in_flight = args.in_flight or min(wl.n_micro, 8)
+        args.k = args.k or args.in_flight
     # overlapped schedule: one stash slot per micro-batch of the step (at most 8), so that no forward
     # call waits for a backward call (the form a HIP graph can hold, see schedule.py)
-    n_slots = min(wl.n_micro, 8) if overlap else 1
+    n_slots = min(wl.n_micro, 8) if overlap else (max(1, min(args.in_flight, wl.n_micro)) if kfkb else 1)
     st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=n_slots)
     dev_batches = [st.stage_inputs(mb) for mb in wl.batches]       # resident in HBM
     outs = [st.alloc_outputs() for _ in range(max(n_slots, 2))]    # one set per in-flight slot
@@ -171,6 +183,8 @@ def main():
     losses = [torch.zeros(1, dtype=torch.float32, device=st.dev) for _ in range(max(n_slots, 2))]
     serial = SerialSchedule(st)
     sched = OverlapSchedule(st) if overlap else serial
+    if kfkb:
+        sched = TaskSchedule(st, n_slots * wl.micro_batch, args.k, two_streams=not args.one_stream)
 
     def eager_step(schedule=sched):
         if schedule is serial:
@@ -181,7 +195,7 @@ def main():
     step = eager_step
 
     graphed = None
-    if (args.graph == "on" or (args.graph == "auto" and overlap)) and wl.n_micro <= max(n_slots, 1):
+    if (args.graph == "on" or (args.graph == "auto" and (overlap or kfkb))) and (wl.n_micro <= max(n_slots, 1) or (kfkb and args.one_stream)):
         eager_step()                # one eager step first (see GraphedMinibatch)
         torch.cuda.synchronize()
         if sched is serial:
@@ -211,7 +225,7 @@ def main():
     samples_per_step = wl.micro_batch * wl.n_micro
     value = args.steps * samples_per_step / dt
     serial_value = None
-    if overlap or graphed is not None:   # the same steps enqueued from the host in serial order, for reference
+    if overlap or kfkb or graphed is not None:   # the same steps enqueued from the host in serial order, for reference
         for _ in range(2):
             eager_step(serial)
         torch.cuda.synchronize()
@@ -324,7 +338,12 @@ def main():
         "dtype": "f32" if args.config == "tiny_mlp" else "bf16", "data": "synthetic",
         "config": {"workload": f"{args.config}: micro-batch {wl.micro_batch} x {wl.n_micro} micro-batches per step",
                    "micro_batch": wl.micro_batch, "micro_batches_per_step": wl.n_micro,
-                   "schedule": f"overlap: forward calls on one stream, backward calls on another, {n_slots} in-flight slots" if overlap else "serial",
+                   "schedule": (f"kFkB from the scheduler: i = {n_slots * wl.micro_batch} samples ({n_slots} micro-batches in flight), k = {args.k}, "
+                                + ("one stream" if args.one_stream else "forward and backward passes on two streams")) if kfkb else
+                               (f"overlap: forward calls on one stream, backward calls on another, {n_slots} in-flight slots" if overlap else "serial"),
+                   "stash_bytes_per_slot": B.gpp_stage_memory(st.handle)[0],
+                   "peak_stash_bytes": n_slots * B.gpp_stage_memory(st.handle)[0],
+                   "workspace_bytes": B.gpp_stage_memory(st.handle)[2],
                    "launch": "HIP graph replay of the whole step" if graphed is not None else "eager",
                    "launches_per_microbatch": st.num_launches(False) + st.num_launches(True),
                    "serial_eager_samples_per_s": serial_value},

@@ -134,3 +134,46 @@ def test_stage_memory_report():
         seen[slots] = (slot_b, shared_b)
         st.close()
     assert seen[1][0] == seen[3][0]            # one slot costs the same whatever their number
+
+
+def test_config2_full_size_in_the_launch_configuration_the_benchmark_times():
+    # the benchmark's default step: the full CANDLE-Uno-shaped stage, a stash slot per micro-batch, the scheduler's
+    # task list for that many in-flight micro-batches run by the executor on two streams, captured once into a HIP
+    # graph and replayed.  Every replay (accumulators poisoned, eager work and synchronisations in between) must
+    # reproduce the serial gradients bit for bit; losses are checked against the oracle.
+    import torch
+    from paper_2406_17145_amd.schedule import GraphedMinibatch
+    wl = W.candle_uno()
+    n = wl.n_micro
+    print(f"[case] {wl.name} full size, {n} in flight, graph replay", flush=True)
+    _, g_serial = run_gpu(wl)
+    _, ora_res = run_oracle(wl)
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=n)
+    dev_batches = [st.stage_inputs(mb) for mb in wl.batches]
+    losses = [torch.zeros(1, dtype=torch.float32, device=st.dev) for _ in range(n)]
+    gins = st.alloc_grad_inputs()
+    sched = TaskSchedule(st, n * wl.micro_batch, n, two_streams=True)
+    outs = [[] for _ in range(n)]
+    sched.minibatch(dev_batches, outputs=outs, grad_inputs=gins, losses=losses)     # eager first
+    torch.cuda.synchronize()
+    graphed = GraphedMinibatch(sched, dev_batches, outputs=outs, grad_inputs=gins, losses=losses)
+    scratch = torch.zeros(1 << 20, device=st.dev)
+    for rep in range(3):
+        for t in st.g_t.values():
+            for g in t.values():
+                g.fill_(float("nan"))
+        for l in losses:
+            l.fill_(-1.0)
+        scratch.add_(1.0)
+        torch.cuda.synchronize()
+        graphed.replay()
+        torch.cuda.synchronize()
+        got = st.grads_numpy()
+        for i in g_serial:
+            for k in g_serial[i]:
+                assert np.array_equal(g_serial[i][k], got[i][k]), (rep, i, k)
+        for j, (ost, _) in enumerate(ora_res):
+            v = float(losses[j].cpu()[0])
+            assert abs(v - ost.loss) <= wl.tol * abs(ost.loss), (rep, j, v, ost.loss)
+    st.sync_status()
+    st.close()
