@@ -134,6 +134,9 @@ def main():
                     help="--schedule kfkb: micro-batches the stage may hold (its stash slots; i = M * micro-batch samples); "
                          "0 = all micro-batches of a step, at most 8")
     ap.add_argument("--k", type=int, default=0, help="--schedule kfkb: group size k of the kFkB order; 0 = M")
+    ap.add_argument("--grouped-dw", default="auto", choices=["auto", "on", "off"],
+                    help="weight gradients of each run of backward passes in one launch over the run's stash slots "
+                         "(gpp_stage_backward_weights); auto: on with the kfkb schedule")
     ap.add_argument("--one-stream", action="store_true", help="--schedule kfkb: all tasks on one stream, in task order")
     ap.add_argument("--schedule", default="auto", choices=["auto", "serial", "overlap", "kfkb"],
                     help="micro-batch schedule of a step: serial = fw_k bw_k in turn on one stream; overlap = fw_{k+1} "
@@ -175,7 +178,8 @@ def main():
     # overlapped schedule: one stash slot per micro-batch of the step (at most 8), so that no forward
     # call waits for a backward call (the form a HIP graph can hold, see schedule.py)
     n_slots = min(wl.n_micro, 8) if overlap else (max(1, min(args.in_flight, wl.n_micro)) if kfkb else 1)
-    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=n_slots)
+    grouped = args.grouped_dw == "on" or (args.grouped_dw == "auto" and kfkb)
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=n_slots, flags=B.FLAG_GROUPED_DW if grouped else 0)
     dev_batches = [st.stage_inputs(mb) for mb in wl.batches]       # resident in HBM
     outs = [st.alloc_outputs() for _ in range(max(n_slots, 2))]    # one set per in-flight slot
     gins = st.alloc_grad_inputs()
@@ -186,7 +190,8 @@ def main():
     if kfkb:
         sched = TaskSchedule(st, n_slots * wl.micro_batch, args.k, two_streams=not args.one_stream)
 
-    def eager_step(schedule=sched):
+    def eager_step(schedule=None):
+        schedule = schedule or sched
         if schedule is serial:
             schedule.minibatch(dev_batches, outputs=outs[0], grad_outputs=gouts, grad_inputs=gins, losses=losses[:1])
         else:
@@ -240,8 +245,11 @@ def main():
     if not args.no_kernel_pass:
         st.profile_enable(True)
         k_steps = max(1, min(args.steps, 20))
+        # per-kernel durations are taken with the calls back to back on ONE stream, eagerly: in serial order, or,
+        # with grouped weight gradients (whose kernels depend on the grouping), in the timed task order
+        inst = TaskSchedule(st, n_slots * wl.micro_batch, args.k, two_streams=False) if (kfkb and grouped) else serial
         for _ in range(k_steps):
-            eager_step(serial)      # per-kernel durations are taken with the calls back to back on one stream, eagerly
+            eager_step(inst)
         torch.cuda.synchronize()
         prof = st.profile_read()
         st.profile_enable(False)
@@ -258,6 +266,13 @@ def main():
             "dx": (tr["dx"][0] * nm, tr["dx"][1] * nm),
             "dw": (tr["dw_first"][0] + tr["dw"][0] * (nm - 1), tr["dw"][1] * nm),
         }
+        if kfkb and grouped:
+            # one pass over the fp32 accumulators per run of backward tasks (the first one of a step only
+            # writes them); the operands of every micro-batch are read once
+            tasks = sched.tasks(nm)
+            runs = sum(1 for t in range(len(tasks)) if tasks[t] < 0 and (t + 1 == len(tasks) or tasks[t + 1] > 0))
+            act = tr["dw_first"][0] - 4 * tr["params"]
+            role_alg["dw"] = (4 * tr["params"] * (2 * runs - 1) + act * nm, tr["dw"][1] * nm)
         role_alg["dx+dw"] = (role_alg["dx"][0] + role_alg["dw"][0], role_alg["dx"][1] + role_alg["dw"][1])
         role_tags = {
             "fwd": ["gemm_big_fwd", "gemm_mfma_fwd", "gemm_skinny_fwd", "gemm_generic_fwd"],

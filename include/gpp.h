@@ -122,7 +122,8 @@ typedef struct {
   int32_t in_flight_slots;    /* how many micro-batches may be in flight (activation stash slots) */
   int32_t flags;              /* bit 0: force the generic (non-MFMA) GEMM kernels (testing);
                                  bit 1: split the contraction of small grouped GEMMs over several
-                                 workgroups (deterministic; measured slower, off by default) */
+                                 workgroups (deterministic; measured slower, off by default);
+                                 bit 2: grouped weight gradients, see gpp_stage_backward_weights */
 } gpp_stage_desc_t;
 
 /* Leading dimension used for parameters and gradient accumulators. */
@@ -162,6 +163,18 @@ gpp_status_t gpp_stage_forward(gpp_stage_t *stage, int32_t slot, const void *con
  * that has not been backpropagated (C4: fw_k before bw_k, bw_k before bw_{k+1}). */
 gpp_status_t gpp_stage_backward(gpp_stage_t *stage, int32_t slot, const void *const *grad_outputs,
                                 void *const *grad_inputs, void *hip_stream);
+
+/* Grouped weight gradients (stage flag bit 2; the kFkB schedules of section 6 run k backward passes in a row).
+ * With the flag, gpp_stage_backward computes input gradients and the gradients of every operator except the
+ * weights and biases of LINEAR operators in bf16 storage; those are left to this call, which contracts over the
+ * rows of ALL micro-batches backpropagated since its previous call in one launch -- one pass over the fp32
+ * accumulators for the whole group instead of one per micro-batch.  Until this call a backpropagated slot keeps
+ * its stashed activations and output gradients and cannot take a new forward pass (GPP_ERR_ORDER), and
+ * gpp_stage_grad_reset refuses to run.  The accumulated gradients are complete after this call.  The sums are
+ * formed in a fixed order (micro-batch order inside the contraction), so results are deterministic, but they
+ * round differently from per-micro-batch accumulation.  No-op without the flag or with nothing pending.
+ * LINEAR operators the grouped kernel does not take (fp32 storage) keep accumulating in gpp_stage_backward. */
+gpp_status_t gpp_stage_backward_weights(gpp_stage_t *stage, void *hip_stream);
 
 /* Iteration boundary (weights are updated once per mini-batch): the next backward starts new sums.
  * Dense accumulators are not touched by this call (their next write overwrites); embedding-table
@@ -220,7 +233,8 @@ typedef struct {
  *                    fw_j after bw_{j - in_flight_slots} with events (created on first use, kept by the stage).
  *                    Ordering against earlier and later work on other streams is the caller's.
  * The whole list is validated before anything is enqueued: GPP_ERR_ORDER if it violates C4 or holds more
- * micro-batches in flight than the stage has slots (nothing has run then). */
+ * micro-batches in flight than the stage has slots (nothing has run then).  On a stage with grouped weight
+ * gradients the call issues gpp_stage_backward_weights after every run of consecutive backward tasks. */
 gpp_status_t gpp_stage_run_schedule(gpp_stage_t *stage, const int32_t *tasks, int64_t n_tasks,
                                     const gpp_microbatch_io_t *io, int64_t n_micro, void *stream_forward,
                                     void *stream_backward);
@@ -236,7 +250,7 @@ int32_t gpp_stage_num_outputs(const gpp_stage_t *stage);
 /* op id of the i-th input / output; -1 if out of range */
 int32_t gpp_stage_input_op(const gpp_stage_t *stage, int32_t i);
 int32_t gpp_stage_output_op(const gpp_stage_t *stage, int32_t i);
-/* number of kernel launches of one forward / backward call */
+/* number of kernel launches of one forward (backward = 0) / backward (1) / grouped weight-gradient (2) call */
 int32_t gpp_stage_num_launches(const gpp_stage_t *stage, int32_t backward);
 /* Integer artefacts of the last backward of embedding op `op`: DEVICE pointers into the workspace.
  * sorted_pos[n_used]: index positions stably sorted by row; unique_rows[n_unique] ascending;

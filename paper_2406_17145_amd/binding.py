@@ -27,6 +27,7 @@ KINDS = {"input": 0, "linear": 1, "layernorm": 2, "attention": 3, "add": 4, "mea
 ACTS = {"none": 0, "relu": 1, "gelu": 2}
 FLAG_FORCE_GENERIC_GEMM = 1
 FLAG_SPLIT_K = 2
+FLAG_GROUPED_DW = 4
 
 
 class OpDesc(C.Structure):
@@ -50,7 +51,7 @@ EXPORTS = [
     "gpp_stage_num_outputs", "gpp_stage_input_op", "gpp_stage_output_op", "gpp_stage_num_launches",
     "gpp_stage_embedding_sort_result", "gpp_last_error", "gpp_stage_profile_enable", "gpp_stage_profile_read",
     "gpp_profile_tag_name", "gpp_compute_in_flight", "gpp_assign_schedules", "gpp_schedule_tasks",
-    "gpp_stage_run_schedule", "gpp_stage_memory",
+    "gpp_stage_run_schedule", "gpp_stage_memory", "gpp_stage_backward_weights",
 ]
 GPP_PROFILE_TAGS = 32
 
@@ -90,6 +91,7 @@ def load():
     lib.gpp_stage_backward.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(vp), vp]
     lib.gpp_stage_grad_reset.restype, lib.gpp_stage_grad_reset.argtypes = i32, [vp, vp]
     lib.gpp_stage_sync_status.restype, lib.gpp_stage_sync_status.argtypes = i32, [vp, vp]
+    lib.gpp_stage_backward_weights.restype, lib.gpp_stage_backward_weights.argtypes = i32, [vp, vp]
     lib.gpp_stage_destroy.restype, lib.gpp_stage_destroy.argtypes = i32, [vp]
     for name in ("gpp_stage_num_inputs", "gpp_stage_num_outputs"):
         getattr(lib, name).restype, getattr(lib, name).argtypes = i32, [vp]
@@ -194,6 +196,10 @@ def gpp_stage_backward(handle, slot, grad_output_ptrs, grad_input_ptrs, stream):
                                      _ptr_array(grad_input_ptrs) if grad_input_ptrs is not None else None, stream))
 
 
+def gpp_stage_backward_weights(handle, stream):
+    _check(load().gpp_stage_backward_weights(handle, stream))
+
+
 def gpp_stage_grad_reset(handle, stream):
     _check(load().gpp_stage_grad_reset(handle, stream))
 
@@ -274,6 +280,7 @@ class Stage:
         self.dev = torch.device(device)
         torch.cuda.set_device(self.dev)
         self.ops, self.b, self.slots = ops, int(micro_batch), int(slots)
+        self.grouped_dw = bool(flags & FLAG_GROUPED_DW)
         self.tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "i32": torch.int32}
         self.p_t, self.g_t, pp, gp = {}, {}, {}, {}
         for i, p in params.items():
@@ -376,6 +383,9 @@ class Stage:
         self._held[("g", slot)] = grad_outputs
         return grad_inputs
 
+    def backward_weights(self):
+        gpp_stage_backward_weights(self.handle, self.stream())
+
     def grad_reset(self):
         gpp_stage_grad_reset(self.handle, self.stream())
 
@@ -394,7 +404,8 @@ class Stage:
         return {lib.gpp_profile_tag_name(k).decode(): (ms[k], ln[k]) for k in range(GPP_PROFILE_TAGS) if ln[k]}
 
     def num_launches(self, backward):
-        return load().gpp_stage_num_launches(self.handle, 1 if backward else 0)
+        """backward: False / 0 forward, True / 1 backward, 2 grouped weight-gradient call."""
+        return load().gpp_stage_num_launches(self.handle, int(backward))
 
     # -- results back to numpy (unpadded) --
     def grads_numpy(self):

@@ -115,9 +115,15 @@ __device__ __forceinline__ BigTile big_locate(const GemmProb *__restrict__ probs
 // k-steps in registers (one barrier per step).  BUFS = 1: one LDS buffer, the next k-step waits in
 // registers while the current one is multiplied (two barriers per step; other workgroups on the
 // compute unit fill the gaps).
-template <int FORM, int WGM, int WGN, int WTM, int WTN, int BUFS, int NS>
+//
+// GROUP (backward-weight only): the contraction runs over the rows of SEVERAL stash slots, one after
+// the other -- the weight gradient of a group of backward passes in one pass over the accumulator.
+// Both operands live in the slots at the same offsets: slot g of the group is `grp.stride` bytes times
+// its slot number behind slot 0, whose addresses the record holds.
+template <int FORM, int WGM, int WGN, int WTM, int WTN, int BUFS, int NS, bool GROUP = false>
 __device__ __forceinline__ void big_tile_body(const GemmProb &p, int m0, int n0, uint16_t *lds, int accumulate_dw,
-                                              const ExtPtrs &ext) {
+                                              const ExtPtrs &ext, const SlotGroup grp = SlotGroup()) {
+  static_assert(!GROUP || FORM == FORM_DW, "only the weight gradient contracts over a group of slots");
   typedef BigCfg<FORM, WGM, WGN, WTM, WTN, BUFS> C;
   constexpr int BM = C::BM, BN = C::BN, THREADS = C::THREADS;
   constexpr bool A_TR = C::A_TR, B_TR = C::B_TR;
@@ -145,7 +151,22 @@ __device__ __forceinline__ void big_tile_body(const GemmProb &p, int m0, int n0,
   typedef BigRegs<BN, THREADS> RegsB;
   RegsA ra[NS];
   RegsB rb[NS];
-  auto fetch = [&](RegsA &xa, RegsB &xb, int k0) {
+  const int nk_slot = cdiv(p.K, GB_BK);              // k-steps of one slot (of the whole contraction without a group)
+  const int nk = GROUP ? nk_slot * grp.n : nk_slot;
+  // k-step `kt` of the tile: without a group, contraction elements [64 kt, 64 kt + 64)
+  auto fetch = [&](RegsA &xa, RegsB &xb, int kt) {
+    if (GROUP) {
+      const int g = kt / nk_slot, k0 = (kt - g * nk_slot) * GB_BK;    // wave-uniform
+      int slot = grp.first + g;
+      slot = slot >= grp.total ? slot - grp.total : slot;
+      const int64_t off = (int64_t)slot * grp.stride;
+      const __amdgpu_buffer_rsrc_t ga = matrix_rsrc((const char *)p.A + off, p.K, p.lda, p.M);
+      const __amdgpu_buffer_rsrc_t gb = matrix_rsrc((const char *)p.B + off, p.K, p.ldb, p.N);
+      big_fetch_tr<BM, THREADS>(xa, ga, p.lda, k0, m0, tid);
+      big_fetch_tr<BN, THREADS>(xb, gb, p.ldb, k0, n0, tid);
+      return;
+    }
+    const int k0 = kt * GB_BK;
     if (A_TR) big_fetch_tr<BM, THREADS>(xa, rs_a, p.lda, k0, m0, tid);
     else      big_fetch_kmajor<BM, THREADS>(xa, rs_a, p.lda, m0, k0, p.K, tid);
     if (B_TR) big_fetch_tr<BN, THREADS>(xb, rs_b, p.ldb, k0, n0, tid);
@@ -187,11 +208,10 @@ __device__ __forceinline__ void big_tile_body(const GemmProb &p, int m0, int n0,
     }
   };
 
-  const int nk = cdiv(p.K, GB_BK);
   if (BUFS == 2) {
 #pragma unroll
     for (int u = 0; u < NS - 1; ++u)
-      if (u < nk) fetch(ra[u], rb[u], u * GB_BK);
+      if (u < nk) fetch(ra[u], rb[u], u);
     to_lds(ra[0], rb[0], 0);
     __syncthreads();
     for (int kt0 = 0; kt0 < nk; kt0 += NS) {
@@ -201,7 +221,7 @@ __device__ __forceinline__ void big_tile_body(const GemmProb &p, int m0, int n0,
         if (kt >= nk) break;
         const int cur = u & 1;   // NS is even: the LDS buffer of step kt is kt & 1 = u & 1
         // ring slot (u + NS - 1) % NS was copied to LDS one step ago: refill it with step kt + NS - 1
-        if (kt + NS - 1 < nk) fetch(ra[(u + NS - 1) % NS], rb[(u + NS - 1) % NS], (kt + NS - 1) * GB_BK);
+        if (kt + NS - 1 < nk) fetch(ra[(u + NS - 1) % NS], rb[(u + NS - 1) % NS], kt + NS - 1);
         multiply(cur);
         bias_rows(cur);
         if (kt + 1 < nk) to_lds(ra[(u + 1) % NS], rb[(u + 1) % NS], cur ^ 1);
@@ -213,7 +233,7 @@ __device__ __forceinline__ void big_tile_body(const GemmProb &p, int m0, int n0,
     for (int kt = 0; kt < nk; ++kt) {
       to_lds(ra[0], rb[0], 0);
       __syncthreads();
-      if (kt + 1 < nk) fetch(ra[0], rb[0], (kt + 1) * GB_BK);
+      if (kt + 1 < nk) fetch(ra[0], rb[0], kt + 1);
       multiply(0);
       bias_rows(0);
       __syncthreads();
@@ -279,6 +299,27 @@ __global__ __launch_bounds__(256, 3) void k_gemm_mid(const GemmProb *__restrict_
   big_tile_body<FORM, 2, 2, 2, 2, 1, 1>(p, t.m0, t.n0, lds, accumulate_dw, ext);
 }
 
+// backward-weight over a group of stash slots (see big_tile_body)
+template <int WTM, int WTN, int NS>
+__global__ __launch_bounds__(512) void k_gemm_big_dw_group(const GemmProb *__restrict__ probs, int n, int total_blocks,
+                                                           int accumulate_dw, SlotGroup grp) {
+  typedef BigCfg<FORM_DW, 2, 4, WTM, WTN, 2> C;
+  __shared__ __attribute__((aligned(16))) uint16_t lds[C::LDS_ELEMS];
+  const BigTile t = big_locate<C::BM, C::BN>(probs, n, total_blocks);
+  const GemmProb p = probs[t.pi];
+  ExtPtrs none;
+  big_tile_body<FORM_DW, 2, 4, WTM, WTN, 2, NS, true>(p, t.m0, t.n0, lds, accumulate_dw, none, grp);
+}
+__global__ __launch_bounds__(256, 3) void k_gemm_mid_dw_group(const GemmProb *__restrict__ probs, int n, int total_blocks,
+                                                              int accumulate_dw, SlotGroup grp) {
+  typedef BigCfg<FORM_DW, 2, 2, 2, 2, 1> C;
+  __shared__ __attribute__((aligned(16))) uint16_t lds[C::LDS_ELEMS];
+  const BigTile t = big_locate<C::BM, C::BN>(probs, n, total_blocks);
+  const GemmProb p = probs[t.pi];
+  ExtPtrs none;
+  big_tile_body<FORM_DW, 2, 2, 2, 2, 1, 1, true>(p, t.m0, t.n0, lds, accumulate_dw, none, grp);
+}
+
 // ---- host side -------------------------------------------------------------------------
 // The kernels take a problem when the chunks of its k-contiguous operands are whole (contraction
 // length a multiple of 8) and the matrices fit the 32-bit buffer offsets.
@@ -331,6 +372,17 @@ void launch_gemm_big(const GemmProb *probs, int n, int total_blocks, int accumul
   if (form == FORM_FWD) launch_big_form<FORM_FWD>(probs, n, total_blocks, accumulate_dw, tile_rows, ext, s);
   else if (form == FORM_DX) launch_big_form<FORM_DX>(probs, n, total_blocks, accumulate_dw, tile_rows, ext, s);
   else launch_big_form<FORM_DW>(probs, n, total_blocks, accumulate_dw, tile_rows, ext, s);
+}
+
+void launch_gemm_dw_group(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int tile_rows,
+                          const SlotGroup &grp, hipStream_t s) {
+  if (total_blocks <= 0 || grp.n <= 0) return;
+  if (tile_rows == 256)
+    hipLaunchKernelGGL((k_gemm_big_dw_group<4, 2, 2>), dim3(total_blocks), dim3(512), 0, s, probs, n, total_blocks, accumulate_dw, grp);
+  else if (tile_rows == 128)
+    hipLaunchKernelGGL((k_gemm_big_dw_group<2, 2, 2>), dim3(total_blocks), dim3(512), 0, s, probs, n, total_blocks, accumulate_dw, grp);
+  else
+    hipLaunchKernelGGL(k_gemm_mid_dw_group, dim3(total_blocks), dim3(256), 0, s, probs, n, total_blocks, accumulate_dw, grp);
 }
 
 }  // namespace gpp

@@ -306,7 +306,8 @@ gpp_status_t Plan::analyse(const gpp_stage_desc_t *desc) {
       nd.gout.off += nd.gout_col * esize(c.gout.dtype);
       return;
     }
-    nd.gout = alloc(SP_SHARED, nd.rows, nd.feat, nd.gdtype);
+    // grouped weight gradients read dZ of several in-flight micro-batches at once: a copy per slot
+    nd.gout = alloc((flags & 4) ? SP_SLOT : SP_SHARED, nd.rows, nd.feat, nd.gdtype);
   };
   for (int i = 0; i < n; ++i) alloc_gout(i);
   for (int i = 0; i < n; ++i) {
@@ -384,6 +385,7 @@ struct Emitter {
   std::vector<Buf> gaddend;
   std::vector<char> dz_ready;
   int64_t part_need = 0, cnt_need = 0;  // split-K scratch high-water marks over all launches
+  std::vector<GemmProb> dw_group;   // backward-weight records left to the launch over a group of slots
   std::vector<int> written_level;   // level whose launches first wrote the node's gradient
   int cur_level = 0;
   int64_t shared_tmp_top;
@@ -1199,9 +1201,15 @@ void Emitter::backward() {
           w.K = (int32_t)nd.rows;           // contraction over the micro-batch rows
           w.in_dtype = d.param_dtype;
           // on the matrix-core path the bias gradient rides along in the backward-weight launch
-          const bool fuse_db = d.has_bias && !(pl.flags & 1) && w.in_dtype == DT_BF16 && gemm_mfma_supported(w);
+          bool fuse_db = d.has_bias && !(pl.flags & 1) && w.in_dtype == DT_BF16 && gemm_mfma_supported(w);
+          // grouped weight gradients: this record waits for the launch that contracts over every slot of
+          // a group of backward passes (both operands sit at the same offsets in every slot)
+          const bool grouped = (pl.flags & 4) && !(pl.flags & 1) && w.in_dtype == DT_BF16 && gemm_big_supported(w) &&
+                               nd.gout.space == SP_SLOT && x.val.space == SP_SLOT;
+          if (grouped) fuse_db = d.has_bias;
           if (fuse_db) w.bias = (const float *)d.grad[1];
-          if (d.has_bias && !fuse_db) {
+          if (grouped) dw_group.push_back(w);
+          if (!grouped && d.has_bias && !fuse_db) {
             ColsumProb c;
             memset(&c, 0, sizeof(c));
             c.src = ptr(nd.gout);
@@ -1212,7 +1220,7 @@ void Emitter::backward() {
             c.cols = (int32_t)nd.feat;
             colsums.push_back(c);
           }
-          gemms.push_back(w);
+          if (!grouped) gemms.push_back(w);
           if (x.wants_grad) {
             Target tg = acquire(nd.in[0], true);
             GemmProb g;
@@ -1534,6 +1542,33 @@ void Emitter::backward() {
     }
     emit_elt(recs, EXT_GRAD_INPUTS, base);
   }
+
+  // the weight gradients left to the group launch: every layer of the stage in ONE launch (they depend
+  // on nothing but the stashed operands), tiles chosen as for any large-tile launch
+  steps = &pl.dwg;
+  steps->clear();
+  if (!dw_group.empty()) {
+    int64_t elems = 0;
+    int tiles256 = 0, tiles128 = 0, max_m = 0, max_n = 0;
+    for (auto &r : dw_group) {
+      elems += (int64_t)r.M * r.N;
+      tiles256 += ((r.M + 255) / 256) * ((r.N + 255) / 256);
+      tiles128 += ((r.M + 127) / 128) * ((r.N + 255) / 256);
+      max_m = std::max(max_m, r.M);
+      max_n = std::max(max_n, r.N);
+    }
+    int tile_rows = gemm_big_tile_rows(max_m, max_n, elems, tiles256, tiles128);
+    if (tile_rows == 0) tile_rows = 64;
+    int blocks = 0;
+    for (auto &r : dw_group) {
+      r.blk_begin = blocks;
+      r.split_k = 1;
+      blocks += gemm_big_tiles_for(tile_rows, r.M, r.N, &r.tiles_n);
+    }
+    Step &sg = add_step(K_GEMM_DW_GROUP, push_table(dw_group), (int)dw_group.size(), blocks);
+    sg.a2 = tile_rows;
+  }
+  steps = &pl.bwd;
 }
 
 }  // namespace

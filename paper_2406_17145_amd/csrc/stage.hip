@@ -40,7 +40,9 @@ struct gpp_stage {
   char *ws = nullptr;
   std::vector<char> slot_busy;
   std::deque<int> fifo;          // slots in the order their forwards were issued
+  std::deque<int> pending;       // grouped weight gradients: backpropagated slots whose operands are still needed
   bool fresh = true;             // no backward since the last grad_reset: next one overwrites dense accumulators
+  bool fresh_w = true;           // no grouped weight-gradient launch since the last grad_reset
   bool emb_clear_pending = true; // table accumulators not yet cleared since create
   int64_t emb_table_off = -1;    // table of all embedding records (slot 0) for the clear kernel
   int emb_count = 0;
@@ -69,6 +71,7 @@ static int step_tag(const Step &sp, bool backward) {
     case K_GEMM_SKINNY: return 25 + sp.a1;                 // 25 fwd, 26 dx
     case K_GEMM_BWD_MERGED: return 27;
     case K_GEMM_DW_KSPLIT: return 31;
+    case K_GEMM_DW_GROUP: return 30;
     case K_LOSS_FWD_SMALL: return 21;
     case K_GEMM_GENERIC: return backward ? 5 : 4;
     case K_ELT: return backward ? 7 : 6;
@@ -201,7 +204,7 @@ int32_t gpp_stage_output_op(const gpp_stage_t *s, int32_t i) {
 int32_t gpp_stage_num_launches(const gpp_stage_t *s, int32_t backward) {
   if (!s) return -1;
   int32_t n = 0;
-  for (const Step &st : backward ? s->plan.bwd : s->plan.fwd) n += st.launches;
+  for (const Step &st : backward == 2 ? s->plan.dwg : (backward ? s->plan.bwd : s->plan.fwd)) n += st.launches;
   return n;
 }
 
@@ -209,7 +212,8 @@ int32_t gpp_stage_num_launches(const gpp_stage_t *s, int32_t backward) {
 
 // ---------------------------------------------------------------------------
 static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int slot, const void *const *ext_in,
-                              void *const *ext_out, float *loss_out, int accumulate, hipStream_t s) {
+                              void *const *ext_out, float *loss_out, int accumulate, hipStream_t s,
+                              const SlotGroup *grp = nullptr) {
   Plan &pl = st->plan;
   const char *tables = st->ws + pl.off_tables + (int64_t)slot * pl.table_bytes;
   StageFlags *flags = (StageFlags *)(st->ws + pl.off_flags);
@@ -251,6 +255,10 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
       case K_GEMM_MFMA: launch_gemm_mfma((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a1, sp.a2, ext, s); break;
       case K_GEMM_BIG: launch_gemm_big((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a1, sp.a2, ext, s); break;
       case K_GEMM_DW_KSPLIT: launch_gemm_dw_ksplit((const GemmProb *)tab, sp.n, sp.blocks, accumulate, s); break;
+      case K_GEMM_DW_GROUP:
+        if (!grp) return fail(GPP_ERR_UNSUPPORTED, "internal: group launch without a group");
+        launch_gemm_dw_group((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a2, *grp, s);
+        break;
       case K_GEMM_SKINNY: launch_gemm_skinny((const GemmProb *)tab, sp.n, sp.blocks, sp.a1, sp.a2, sp.a0, ext, s); break;
       case K_GEMM_BWD_MERGED: launch_gemm_bwd_merged((const GemmProb *)tab, sp.n, sp.blocks, sp.a2, sp.a1, accumulate, ext, s); break;
       case K_LOSS_FWD_SMALL: launch_loss_fwd_small((const LossProb *)tab, sp.n, loss_out, s); break;
@@ -319,6 +327,8 @@ gpp_status_t gpp_stage_forward(gpp_stage_t *st, int32_t slot, const void *const 
   for (size_t k = 0; k < pl.input_ops.size(); ++k)
     if (!inputs[k] || ((uintptr_t)inputs[k] & 3)) return fail(GPP_ERR_INVALID_ARG, "input " + std::to_string(k) + " is null or misaligned");
   if (!pl.output_ops.empty() && !outputs) return fail(GPP_ERR_INVALID_ARG, "outputs is null but the stage has outputs");
+  if (st->slot_busy[slot] == 2)
+    return fail(GPP_ERR_ORDER, "slot " + std::to_string(slot) + " waits for gpp_stage_backward_weights (grouped weight gradients)");
   if (st->slot_busy[slot]) return fail(GPP_ERR_ORDER, "slot " + std::to_string(slot) + " still holds a micro-batch in flight");
   gpp_status_t rc = run_steps(st, pl.fwd, slot, inputs, outputs, loss_out, 0, (hipStream_t)hip_stream);
   if (rc != GPP_OK) return rc;
@@ -332,7 +342,7 @@ gpp_status_t gpp_stage_backward(gpp_stage_t *st, int32_t slot, const void *const
   if (!st) return fail(GPP_ERR_INVALID_ARG, "stage is null");
   Plan &pl = st->plan;
   if (slot < 0 || slot >= pl.slots) return fail(GPP_ERR_INVALID_ARG, "slot out of range");
-  if (!st->slot_busy[slot]) return fail(GPP_ERR_ORDER, "backward before forward on slot " + std::to_string(slot) + " (C4: fw_k precedes bw_k)");
+  if (st->slot_busy[slot] != 1) return fail(GPP_ERR_ORDER, "backward before forward on slot " + std::to_string(slot) + " (C4: fw_k precedes bw_k)");
   if (st->fifo.empty() || st->fifo.front() != slot)
     return fail(GPP_ERR_ORDER, "backward out of order (C4: bw_k precedes bw_{k+1}); oldest forward is in slot " +
                                    std::to_string(st->fifo.empty() ? -1 : st->fifo.front()));
@@ -344,15 +354,44 @@ gpp_status_t gpp_stage_backward(gpp_stage_t *st, int32_t slot, const void *const
   gpp_status_t rc = run_steps(st, pl.bwd, slot, grad_outputs, grad_inputs, nullptr, st->fresh ? 0 : 1, (hipStream_t)hip_stream);
   if (rc != GPP_OK) return rc;
   st->fresh = false;
-  st->slot_busy[slot] = 0;
   st->fifo.pop_front();
+  if (pl.dwg.empty()) {
+    st->slot_busy[slot] = 0;
+  } else {   // its stashed operands feed the weight-gradient launch of the group
+    st->slot_busy[slot] = 2;
+    st->pending.push_back(slot);
+  }
+  return GPP_OK;
+}
+
+gpp_status_t gpp_stage_backward_weights(gpp_stage_t *st, void *hip_stream) {
+  if (!st) return fail(GPP_ERR_INVALID_ARG, "stage is null");
+  Plan &pl = st->plan;
+  // one launch per run of consecutive slots (wrapping at the number of slots), in backward order
+  while (!st->pending.empty()) {
+    SlotGroup g;
+    g.first = st->pending.front();
+    g.total = pl.slots;
+    g.stride = pl.slot_bytes;
+    g.n = 1;
+    while (g.n < (int)st->pending.size() && g.n < pl.slots && st->pending[g.n] == (g.first + g.n) % pl.slots) ++g.n;
+    gpp_status_t rc = run_steps(st, pl.dwg, 0, nullptr, nullptr, nullptr, st->fresh_w ? 0 : 1, (hipStream_t)hip_stream, &g);
+    if (rc != GPP_OK) return rc;
+    st->fresh_w = false;
+    for (int k = 0; k < g.n; ++k) {
+      st->slot_busy[st->pending.front()] = 0;
+      st->pending.pop_front();
+    }
+  }
   return GPP_OK;
 }
 
 gpp_status_t gpp_stage_grad_reset(gpp_stage_t *st, void *hip_stream) {
   if (!st) return fail(GPP_ERR_INVALID_ARG, "stage is null");
   if (!st->fifo.empty()) return fail(GPP_ERR_ORDER, "grad_reset while a micro-batch is in flight");
+  if (!st->pending.empty()) return fail(GPP_ERR_ORDER, "grad_reset before gpp_stage_backward_weights (grouped weight gradients pending)");
   st->fresh = true;
+  st->fresh_w = true;
   if (st->emb_count > 0) {
     const char *tables = st->ws + st->plan.off_tables;  // slot 0's records carry the same accumulators
     const EmbProb *recs = (const EmbProb *)(tables + st->emb_table_off);
@@ -384,7 +423,7 @@ gpp_status_t gpp_stage_run_schedule(gpp_stage_t *st, const int32_t *tasks, int64
   if (!st) return fail(GPP_ERR_INVALID_ARG, "stage is null");
   if (n_micro < 0 || n_tasks != 2 * n_micro) return fail(GPP_ERR_INVALID_ARG, "a mini-batch of n micro-batches has 2n tasks");
   if (n_micro > 0 && (!tasks || !io)) return fail(GPP_ERR_INVALID_ARG, "tasks or io is null");
-  if (!st->fifo.empty()) return fail(GPP_ERR_ORDER, "run_schedule while a micro-batch is in flight");
+  if (!st->fifo.empty() || !st->pending.empty()) return fail(GPP_ERR_ORDER, "run_schedule while a micro-batch is in flight");
   const int slots = st->plan.slots;
   {
     int64_t f = 0, b = 0;   // forward / backward passes seen so far
@@ -434,7 +473,18 @@ gpp_status_t gpp_stage_run_schedule(gpp_stage_t *st, const int32_t *tasks, int64
       if (he == hipSuccess) {
         rc = gpp_stage_backward(st, slot, m.grad_outputs, m.grad_inputs, sb);
         if (rc != GPP_OK) return rc;
-        if (two) he = hipEventRecord(st->sched_ev[2 * j + 1], sb);
+        // grouped weight gradients: one launch after the last backward pass of a run of backward
+        // tasks; only then are the run's slots free for the forward passes that wait for them
+        const bool run_ends = t + 1 == n_tasks || tasks[t + 1] > 0;
+        if (!st->pending.empty() && run_ends) {
+          const int64_t run = (int64_t)st->pending.size();
+          rc = gpp_stage_backward_weights(st, sb);
+          if (rc != GPP_OK) return rc;
+          if (two)
+            for (int64_t q = j - run + 1; q <= j && he == hipSuccess; ++q) he = hipEventRecord(st->sched_ev[2 * q + 1], sb);
+        } else if (two && st->pending.empty()) {
+          he = hipEventRecord(st->sched_ev[2 * j + 1], sb);
+        }
       }
     }
     if (he != hipSuccess) return fail(GPP_ERR_DEVICE, std::string("HIP event: ") + hipGetErrorString(he));

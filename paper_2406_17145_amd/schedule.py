@@ -24,6 +24,8 @@ class SerialSchedule:
         for k, mb in enumerate(batches):
             st.forward(0, mb, outputs=outputs, loss=None if losses is None else losses[k % len(losses)])
             st.backward(0, grad_outputs=grad_outputs, grad_inputs=grad_inputs)
+            if st.grouped_dw:
+                st.backward_weights()      # groups of one
 
 
 class OverlapSchedule:
@@ -69,6 +71,8 @@ class OverlapSchedule:
             with torch.cuda.stream(self.s_b):
                 self.s_b.wait_event(self.ev_f[k])
                 st.backward(slot, grad_outputs=grad_outputs, grad_inputs=grad_inputs)
+                if st.grouped_dw:
+                    st.backward_weights()  # groups of one
                 self.ev_b[k].record(self.s_b)
         main.wait_stream(self.s_f)
         main.wait_stream(self.s_b)

@@ -17,9 +17,9 @@ def _codes(tasks):
     return [(j + 1) if w == "F" else -(j + 1) for w, j in tasks]
 
 
-def _run(wl, cap, k, two_streams, slots=None, gouts=None, reps=1):
+def _run(wl, cap, k, two_streams, slots=None, gouts=None, reps=1, flags=0):
     import torch
-    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=slots or cap)
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=slots or cap, flags=flags)
     n = len(wl.batches)
     dev_batches = [st.stage_inputs(mb) for mb in wl.batches]
     losses = [torch.zeros(1, dtype=torch.float32, device=st.dev) for _ in range(n)]
@@ -138,24 +138,30 @@ def test_stage_memory_report():
 
 def test_config2_full_size_in_the_launch_configuration_the_benchmark_times():
     # the benchmark's default step: the full CANDLE-Uno-shaped stage, a stash slot per micro-batch, the scheduler's
-    # task list for that many in-flight micro-batches run by the executor on two streams, captured once into a HIP
-    # graph and replayed.  Every replay (accumulators poisoned, eager work and synchronisations in between) must
-    # reproduce the serial gradients bit for bit; losses are checked against the oracle.
+    # task list for that many in-flight micro-batches run by the executor on two streams, weight gradients of the
+    # whole run of backward passes in one grouped launch, everything captured once into a HIP graph and replayed.
+    # Checked against the oracle in full (losses, input gradients, every accumulated gradient); every replay
+    # (accumulators poisoned, eager work and synchronisations in between) must reproduce the eager run of the
+    # same configuration bit for bit.
     import torch
     from paper_2406_17145_amd.schedule import GraphedMinibatch
     wl = W.candle_uno()
     n = wl.n_micro
-    print(f"[case] {wl.name} full size, {n} in flight, graph replay", flush=True)
-    _, g_serial = run_gpu(wl)
-    _, ora_res = run_oracle(wl)
-    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=n)
+    print(f"[case] {wl.name} full size, {n} in flight, grouped weight gradients, graph replay", flush=True)
+    ora_stage, ora_res = run_oracle(wl)
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=n, flags=B.FLAG_GROUPED_DW)
+    assert st.num_launches(2) == 1
     dev_batches = [st.stage_inputs(mb) for mb in wl.batches]
     losses = [torch.zeros(1, dtype=torch.float32, device=st.dev) for _ in range(n)]
-    gins = st.alloc_grad_inputs()
+    gins = [st.alloc_grad_inputs() for _ in range(n)]
     sched = TaskSchedule(st, n * wl.micro_batch, n, two_streams=True)
     outs = [[] for _ in range(n)]
     sched.minibatch(dev_batches, outputs=outs, grad_inputs=gins, losses=losses)     # eager first
-    torch.cuda.synchronize()
+    st.sync_status()
+    g_eager = st.grads_numpy()
+    res = [dict(loss=float(losses[j].cpu()[0]), outs={},
+                gin={i: t2n(t) for i, t in zip(st.input_ids, gins[j]) if t is not None}) for j in range(n)]
+    compare(wl, res, g_eager, ora_stage, ora_res, label="full size, grouped, eager")
     graphed = GraphedMinibatch(sched, dev_batches, outputs=outs, grad_inputs=gins, losses=losses)
     scratch = torch.zeros(1 << 20, device=st.dev)
     for rep in range(3):
@@ -169,11 +175,97 @@ def test_config2_full_size_in_the_launch_configuration_the_benchmark_times():
         graphed.replay()
         torch.cuda.synchronize()
         got = st.grads_numpy()
-        for i in g_serial:
-            for k in g_serial[i]:
-                assert np.array_equal(g_serial[i][k], got[i][k]), (rep, i, k)
-        for j, (ost, _) in enumerate(ora_res):
-            v = float(losses[j].cpu()[0])
-            assert abs(v - ost.loss) <= wl.tol * abs(ost.loss), (rep, j, v, ost.loss)
+        for i in g_eager:
+            for k in g_eager[i]:
+                assert np.array_equal(g_eager[i][k], got[i][k]), (rep, i, k)
+        for j in range(n):
+            assert float(losses[j].cpu()[0]) == res[j]["loss"], (rep, j)
     st.sync_status()
+    st.close()
+
+
+# ---- grouped weight gradients: the weight-gradient GEMMs of a run of backward passes as one launch whose
+# contraction runs over the stash slots of the whole run.  Sums are formed in another order than with one
+# accumulation per micro-batch, so the comparison with the serial run is to rounding, not bit for bit.
+
+def _close(a, b, tol):
+    n = np.linalg.norm(b)
+    return np.linalg.norm(a.astype(np.float64) - b) <= tol * max(n, 1e-30)
+
+
+@pytest.mark.parametrize("two_streams", [False, True])
+def test_grouped_weight_gradients_match_oracle_and_serial(two_streams):
+    for mb, act in [(48, "gelu"), (37, "relu"), (64, "relu")]:      # rows per slot: less than, not a multiple of, exactly one k-step
+        wl = W.candle_uno(micro_batch=mb, n_micro=7, widths=(70, 131, 9, 33), hidden=160, act=act)
+        _, g_serial = run_gpu(wl)
+        ora_stage, ora_res = run_oracle(wl)
+        for cap, k in [(1, 1), (3, 2), (4, 4), (7, 7), (5, 3)]:
+            print(f"[case] {wl.name} b={mb} grouped weight gradients cap={cap} k={k} two_streams={two_streams}", flush=True)
+            _, res, grads = _run(wl, cap, k, two_streams, reps=2, flags=B.FLAG_GROUPED_DW)
+            compare(wl, res, grads, ora_stage, ora_res, label=f"grouped cap={cap} k={k}")
+            for i in g_serial:
+                for kk in g_serial[i]:
+                    assert _close(grads[i][kk], g_serial[i][kk], 1e-5), (cap, k, i, kk)
+
+
+def test_grouped_weight_gradients_long_rows_per_slot():
+    # several k-steps per slot with a ragged last one (300 = 4 * 64 + 44), wide layers (large tiles, ragged edges)
+    wl = W.candle_uno(micro_batch=300, n_micro=4, widths=(264, 131, 520, 8), hidden=392, act="gelu")
+    ora_stage, ora_res = run_oracle(wl)
+    for cap, k in [(2, 2), (4, 4), (3, 2)]:
+        print(f"[case] {wl.name} b=300 grouped weight gradients cap={cap} k={k}", flush=True)
+        _, res, grads = _run(wl, cap, k, True, flags=B.FLAG_GROUPED_DW)
+        compare(wl, res, grads, ora_stage, ora_res, label=f"grouped long cap={cap} k={k}")
+
+
+def test_grouped_weight_gradients_with_embedding_tables_and_mid_pipeline_stage():
+    wl = W.dlrm(micro_batch=128, n_micro=5, n_tables=4, num_rows=3000, bottom=(64, 32, 128), top=(128, 64, 1))
+    ora_stage, ora_res = run_oracle(wl)
+    for cap, k in [(3, 2), (5, 5)]:
+        print(f"[case] {wl.name} grouped weight gradients cap={cap} k={k}", flush=True)
+        _, res, grads = _run(wl, cap, k, True, reps=2, flags=B.FLAG_GROUPED_DW)
+        compare(wl, res, grads, ora_stage, ora_res, label=f"dlrm grouped cap={cap} k={k}")
+    # a stage with outputs, bf16 (grouped) and fp32 (the flag changes nothing: no layer is taken)
+    for dtype in ("bf16", "f32"):
+        wl = W.hetero(micro_batch=9, n_micro=5, base_width=16, out_width=24, dtype=dtype, with_loss=False)
+        out = len(wl.ops) - 1
+        rng = np.random.default_rng(5)
+        gouts = [{out: rng.standard_normal((9, 192)).astype(np.float32)} for _ in range(5)]
+        ora_stage, ora_res = run_oracle(wl, gouts)
+        print(f"[case] {wl.name} {dtype} mid-pipeline grouped weight gradients", flush=True)
+        _, res, grads = _run(wl, 3, 2, True, gouts=gouts, flags=B.FLAG_GROUPED_DW)
+        compare(wl, res, grads, ora_stage, ora_res, label=f"mid grouped {dtype}")
+
+
+def test_grouped_weight_gradients_state_machine():
+    wl = W.candle_uno(micro_batch=16, n_micro=3, widths=(32, 40, 8, 24), hidden=64, act="gelu")
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=2, flags=B.FLAG_GROUPED_DW)
+    assert st.num_launches(2) == 1                 # every LINEAR of the stage in one grouped launch
+    st.grad_reset()
+    st.forward(0, wl.batches[0])
+    st.backward(0)
+    with pytest.raises(B.GppError) as e:
+        st.forward(0, wl.batches[1])               # the slot's operands still feed the weight gradients
+    assert e.value.status == B.GPP_ERR_ORDER
+    with pytest.raises(B.GppError) as e:
+        st.grad_reset()
+    assert e.value.status == B.GPP_ERR_ORDER
+    st.forward(1, wl.batches[1])
+    st.backward(1)
+    st.backward_weights()                          # slots 0 and 1 in one launch
+    st.forward(0, wl.batches[2])
+    st.backward(0)
+    st.backward_weights()
+    st.backward_weights()                          # nothing pending: no-op
+    st.sync_status()
+    got = st.grads_numpy()
+    st.close()
+    ora_stage, _ = run_oracle(wl)
+    for i, gr in ora_stage.grads.items():
+        for k, ref in gr.items():
+            assert _close(got[i][k], ref, wl.tol), (i, k)
+    # without the flag the call does nothing
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params)
+    assert st.num_launches(2) == 0
+    st.backward_weights()
     st.close()
