@@ -113,6 +113,8 @@ MEASURED_TRAFFIC = {
     # bytes per launch, averaged over the launches of the kernel family within a step
     ("candle_uno", "gemm_bwd_merged_dx_dw"): 50.5e6,
     ("candle_uno", "gemm_skinny_fwd"): 12.9e6,
+    ("candle_uno", "gemm_skinny_dx"): 20.3e6,
+    ("candle_uno", "gemm_big_dw"): 122.1e6,      # the grouped launch: eight slots, every Linear of the stage
     ("hetero", "gemm_bwd_merged_dx_dw"): 122.0e6,
     ("hetero", "gemm_skinny_fwd"): 48.8e6,
     ("mmt", "gemm_big_fwd"): 187.2e6,
@@ -151,6 +153,9 @@ def main():
                          "for a backward pass), off with the serial one (measured: replay is 1-3 %% slower than eager "
                          "launches there)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-serial-reference", action="store_true",
+                    help="skip the untimed-in-value reference pass that runs the same steps eagerly in serial order "
+                         "(keeps a kernel trace of the run to the launches of the timed schedule)")
     ap.add_argument("--no-kernel-pass", action="store_true", help="skip the event-instrumented second pass")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="before the steps, run 3 plain elementwise copies of MIB mebibytes (counter calibration)")
@@ -230,7 +235,7 @@ def main():
     samples_per_step = wl.micro_batch * wl.n_micro
     value = args.steps * samples_per_step / dt
     serial_value = None
-    if overlap or kfkb or graphed is not None:   # the same steps enqueued from the host in serial order, for reference
+    if (overlap or kfkb or graphed is not None) and not args.no_serial_reference:   # the same steps enqueued from the host in serial order, for reference
         for _ in range(2):
             eager_step(serial)
         torch.cuda.synchronize()
@@ -243,7 +248,10 @@ def main():
     # ---- instrumented pass: per-kernel durations from HIP events on the launch stream ----
     kernels, roofline = {}, None
     if not args.no_kernel_pass:
-        st.profile_enable(True)
+        # GEMM launches are issued 8 times inside each event bracket: the bracket's own dispatch latency (about
+        # 2 us, a quarter of a few-row launch) would otherwise be counted as kernel time
+        REP = 8
+        st.profile_enable(REP)
         k_steps = max(1, min(args.steps, 20))
         # per-kernel durations are taken with the calls back to back on ONE stream, eagerly: in serial order, or,
         # with grouped weight gradients (whose kernels depend on the grouping), in the timed task order
@@ -253,6 +261,10 @@ def main():
         torch.cuda.synchronize()
         prof = st.profile_read()
         st.profile_enable(False)
+        total_ms = sum(v[0] for v in prof.values())
+        # back to one launch per planned launch
+        prof = {name: ((ms / REP, launches / REP) if name.startswith("gemm_") and not name.startswith("gemm_generic") else (ms, launches))
+                for name, (ms, launches) in prof.items()}
         total_ms = sum(v[0] for v in prof.values())
         for name, (ms, launches) in sorted(prof.items(), key=lambda kv: -kv[1][0]):
             kernels[name] = {"ms_per_step": ms / k_steps, "launches_per_step": launches / k_steps,

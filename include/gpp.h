@@ -266,7 +266,10 @@ gpp_status_t gpp_stage_embedding_sort_result(gpp_stage_t *stage, int32_t op, con
  * with a pair of HIP events on the caller's stream (events are created on first use: the only
  * allocation these calls ever make, and only in this mode).  profile_read waits for the recorded
  * events and returns, per tag, the accumulated milliseconds and kernel launches since the last
- * reset; ms and launches are HOST arrays of GPP_PROFILE_TAGS entries. */
+ * reset; ms and launches are HOST arrays of GPP_PROFILE_TAGS entries.  enable = R > 1 (at most 64) is a
+ * TIMING-ONLY mode: every grouped GEMM launch is issued R times back to back inside its bracket, so that the
+ * bracket's own dispatch latency (about two microseconds) is spread over R launches; accumulated gradients
+ * and in-place sums of such a pass are meaningless. */
 #define GPP_PROFILE_TAGS 32
 gpp_status_t gpp_stage_profile_enable(gpp_stage_t *stage, int32_t enable);
 gpp_status_t gpp_stage_profile_read(gpp_stage_t *stage, double *ms, int64_t *launches, int32_t reset);

@@ -393,7 +393,9 @@ class Stage:
         gpp_stage_sync_status(self.handle, self.stream())
 
     def profile_enable(self, on):
-        _check(load().gpp_stage_profile_enable(self.handle, 1 if on else 0))
+        """on: False / True, or an integer R > 1 for the timing-only mode that launches every GEMM step R times
+        inside its event bracket."""
+        _check(load().gpp_stage_profile_enable(self.handle, int(on)))
 
     def profile_read(self, reset=True):
         """{tag name: (milliseconds, kernel launches)} accumulated since the last reset."""

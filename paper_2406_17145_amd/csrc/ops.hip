@@ -13,6 +13,31 @@ int elt_blocks(int rows, int cols) {
   return (int)((e + ELT_PER_BLOCK - 1) / ELT_PER_BLOCK);
 }
 
+// Plain copy / conversion (no addend, no derivative) with the storage types as template parameters and
+// every load of a thread requested before its first store: a run-time type test or a bounds branch in
+// front of each load makes the wave wait for the previous load, and the copy then pays one memory
+// latency per element instead of one per thread.  Elements beyond the end re-read the last element.
+template <int SD, int DD>
+__device__ __forceinline__ void elt_copy_body(const EltProb &p, const void *src, void *dst, uint32_t base, uint32_t total) {
+  constexpr int IT = ELT_PER_BLOCK / 256;
+  float v[IT];
+  uint32_t di[IT];
+#pragma unroll
+  for (int it = 0; it < IT; ++it) {
+    const uint32_t e = min(base + it * 256 + threadIdx.x, total - 1);
+    const uint32_t r = e / (uint32_t)p.cols, c = e - r * (uint32_t)p.cols;
+    const int64_t si = (int64_t)r * p.ld_src + c;
+    di[it] = r * (uint32_t)p.ld_dst + c;
+    v[it] = SD == DT_BF16 ? bf16_bits_to_f32(((const uint16_t *)src)[si]) : ((const float *)src)[si];
+  }
+#pragma unroll
+  for (int it = 0; it < IT; ++it)
+    if (base + it * 256 + threadIdx.x < total) {
+      if (DD == DT_BF16) ((uint16_t *)dst)[di[it]] = f32_to_bf16_bits(v[it]);
+      else ((float *)dst)[di[it]] = v[it];
+    }
+}
+
 __global__ __launch_bounds__(256) void k_elt(const EltProb *__restrict__ probs, int n, ExtPtrs ext) {
   const int pi = find_prob(probs, n, blockIdx.x);
   const EltProb p = probs[pi];
@@ -21,6 +46,14 @@ __global__ __launch_bounds__(256) void k_elt(const EltProb *__restrict__ probs, 
   if (!src || !dst) return;
   const int64_t total = (int64_t)p.rows * p.cols;
   const int64_t base = (int64_t)(blockIdx.x - p.blk_begin) * ELT_PER_BLOCK;
+  if (p.mode == 0 && !p.addend && p.src_dtype != DT_I32 && p.dst_dtype != DT_I32 && total < (1ll << 31) &&
+      (int64_t)p.rows * p.ld_dst < (1ll << 32)) {
+    const bool sb = p.src_dtype == DT_BF16, db = p.dst_dtype == DT_BF16;
+    if (sb && db) return elt_copy_body<DT_BF16, DT_BF16>(p, src, dst, (uint32_t)base, (uint32_t)total);
+    if (sb) return elt_copy_body<DT_BF16, DT_F32>(p, src, dst, (uint32_t)base, (uint32_t)total);
+    if (db) return elt_copy_body<DT_F32, DT_BF16>(p, src, dst, (uint32_t)base, (uint32_t)total);
+    return elt_copy_body<DT_F32, DT_F32>(p, src, dst, (uint32_t)base, (uint32_t)total);
+  }
 #pragma unroll
   for (int it = 0; it < ELT_PER_BLOCK / 256; ++it) {
     const int64_t e = base + it * 256 + threadIdx.x;

@@ -54,6 +54,7 @@ struct gpp_stage {
   int emb_sort_blocks = 0;
   // optional per-step timing (HIP events on the caller's stream)
   bool prof_on = false;
+  int prof_repeat = 1;               // timing mode: GEMM steps are launched this many times inside their bracket
   std::vector<hipEvent_t> prof_ev;   // pairs (begin, end)
   std::vector<int> prof_tag;         // tag of each recorded pair
   size_t prof_used = 0;
@@ -62,6 +63,11 @@ struct gpp_stage {
   // events of the schedule executor (created on first use, two per micro-batch, no timing)
   std::vector<hipEvent_t> sched_ev;
 };
+
+static bool gemm_step(const Step &sp) {
+  return sp.kern == K_GEMM_MFMA || sp.kern == K_GEMM_BIG || sp.kern == K_GEMM_SKINNY || sp.kern == K_GEMM_BWD_MERGED ||
+         sp.kern == K_GEMM_DW_KSPLIT || sp.kern == K_GEMM_DW_GROUP;
+}
 
 // profile tag of a step: grouped-GEMM steps are split by form, element-wise steps by direction
 static int step_tag(const Step &sp, bool backward) {
@@ -232,7 +238,7 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
       (void)hipEventRecord(st->prof_ev[st->prof_used], s);
       ev_end = st->prof_ev[st->prof_used + 1];
       st->prof_tag.resize(st->prof_used / 2 + 1);
-      st->prof_tag[st->prof_used / 2] = step_tag(sp, is_bwd) | (sp.launches << 8);
+      st->prof_tag[st->prof_used / 2] = step_tag(sp, is_bwd) | ((sp.launches * (gemm_step(sp) ? st->prof_repeat : 1)) << 8);
       st->prof_used += 2;
     }
     // per-call pointers the step's records refer to by index
@@ -249,6 +255,11 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
           ext.p[k] = ext_out ? ext_out[sp.ext_base + k] : nullptr;
       }
     }
+    // timing mode: a bracket of two events costs about two microseconds of dispatch latency, a quarter of a
+    // few-row GEMM launch; such steps are launched several times back to back inside one bracket (they
+    // only read their operands and tables; accumulating ones add again, which the timing pass ignores)
+    const int reps = (st->prof_on && gemm_step(sp)) ? st->prof_repeat : 1;
+    for (int rep = 0; rep < reps; ++rep)
     switch (sp.kern) {
       case K_ELT: launch_elt((const EltProb *)tab, sp.n, sp.blocks, ext, s); break;
       case K_GEMM_GENERIC: launch_gemm_generic((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a0, s); break;
@@ -508,6 +519,7 @@ gpp_status_t gpp_stage_sync_status(gpp_stage_t *st, void *hip_stream) {
 gpp_status_t gpp_stage_profile_enable(gpp_stage_t *st, int32_t enable) {
   if (!st) return fail(GPP_ERR_INVALID_ARG, "stage is null");
   st->prof_on = enable != 0;
+  st->prof_repeat = enable > 1 ? (enable < 64 ? enable : 64) : 1;
   return GPP_OK;
 }
 
