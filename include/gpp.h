@@ -244,7 +244,51 @@ gpp_status_t gpp_stage_run_schedule(gpp_stage_t *stage, const int32_t *tasks, in
  * stage's in_flight_slots.  Any pointer may be NULL. */
 gpp_status_t gpp_stage_memory(const gpp_stage_t *stage, size_t *slot_bytes, size_t *shared_bytes, size_t *total_bytes);
 
+/* ---- Several stages of a stage graph G_S on one GPU (paper section 3: G_S = (V_S, E_S); an edge (S_x, S_y)
+ * orders the two stages for every micro-batch, C2; stages without a path between them run concurrently,
+ * section 2).  Each stage keeps its own task list (gpp_schedule_tasks for its (i, k)) and its own pair of
+ * HIP streams, which stand in for the stage's devices; the edges become events between the streams and, for
+ * data edges, device buffers that carry the tensor forward and its gradient backward. ---- */
+typedef struct gpp_pipeline gpp_pipeline_t;
+typedef struct {
+  int32_t from_stage, from_output;  /* producer stage and which of its outputs; from_output = to_input = -1: an  */
+  int32_t to_stage, to_input;       /* order-only edge (a linearised, sequential pipeline chains stages this way) */
+} gpp_pipeline_edge_t;
+
+/* Bytes of DEVICE workspace for the edge tensors: per data edge, forward tensor and gradient, one copy per
+ * micro-batch the producer may hold in flight.  Validates the stage graph: GPP_ERR_BAD_GRAPH (cycle; producer
+ * wants a gradient the consumer's input does not return), GPP_ERR_SHAPE (tensor shapes or types differ),
+ * GPP_ERR_UNSUPPORTED (different micro-batch sizes; an output feeding several inputs -- fan-out lives inside
+ * a stage), GPP_ERR_ORDER (a stage has fewer stash slots than in_flight[s] / micro_batch).
+ *   stages[n_stages]   HOST array of created stages (borrowed until gpp_pipeline_destroy)
+ *   in_flight[s], k[s] HOST, the schedule configuration of stage s as gpp_assign_schedules returns it
+ *                      (in-flight SAMPLES and group size) */
+gpp_status_t gpp_pipeline_workspace_bytes(int32_t n_stages, gpp_stage_t *const *stages, int32_t n_edges,
+                                          const gpp_pipeline_edge_t *edges, const int64_t *in_flight, const int64_t *k,
+                                          size_t *bytes);
+/* `workspace`: DEVICE, 256-byte aligned, at least gpp_pipeline_workspace_bytes, the caller's, reserved until destroy. */
+gpp_status_t gpp_pipeline_create(int32_t n_stages, gpp_stage_t *const *stages, int32_t n_edges,
+                                 const gpp_pipeline_edge_t *edges, const int64_t *in_flight, const int64_t *k,
+                                 void *workspace, size_t workspace_bytes, gpp_pipeline_t **out);
+/* One mini-batch of n_micro micro-batches through every stage.
+ *   io[s][j]   HOST: the caller's pointers of stage s, micro-batch j (meaning as in gpp_stage_forward / backward);
+ *              entries of inputs, outputs and their gradients that an edge carries are ignored
+ *   streams_forward[s], streams_backward[s]   HOST arrays of HIP streams, one pair per stage (pairs may coincide)
+ * fw_j of a stage waits for fw_j of every predecessor, bw_j for bw_j of every successor; inside a stage the
+ * order is its task list.  Before anything is enqueued a dry run checks that the task lists cannot wait for
+ * each other (GPP_ERR_ORDER: in-flight counts too small for this stage graph).  Ordering against other work
+ * on the streams is the caller's. */
+gpp_status_t gpp_pipeline_run(gpp_pipeline_t *pipeline, int64_t n_micro, const gpp_microbatch_io_t *const *io,
+                              void *const *streams_forward, void *const *streams_backward);
+gpp_status_t gpp_pipeline_destroy(gpp_pipeline_t *pipeline);
+
 /* Introspection (tests, benchmarks). */
+/* micro-batch size, number of stash slots and flags the stage was created with (any pointer may be NULL) */
+gpp_status_t gpp_stage_info(const gpp_stage_t *stage, int64_t *micro_batch, int32_t *in_flight_slots, int32_t *flags);
+/* rows, features and gpp_dtype_t of the index-th input (is_output = 0) or output (1), and whether a gradient
+ * flows through it (an input that returns one / an output that expects one) */
+gpp_status_t gpp_stage_io_info(const gpp_stage_t *stage, int32_t is_output, int32_t index, int64_t *rows,
+                               int64_t *features, int32_t *dtype, int32_t *has_grad);
 int32_t gpp_stage_num_inputs(const gpp_stage_t *stage);
 int32_t gpp_stage_num_outputs(const gpp_stage_t *stage);
 /* op id of the i-th input / output; -1 if out of range */

@@ -51,13 +51,18 @@ EXPORTS = [
     "gpp_stage_num_outputs", "gpp_stage_input_op", "gpp_stage_output_op", "gpp_stage_num_launches",
     "gpp_stage_embedding_sort_result", "gpp_last_error", "gpp_stage_profile_enable", "gpp_stage_profile_read",
     "gpp_profile_tag_name", "gpp_compute_in_flight", "gpp_assign_schedules", "gpp_schedule_tasks",
-    "gpp_stage_run_schedule", "gpp_stage_memory", "gpp_stage_backward_weights",
+    "gpp_stage_run_schedule", "gpp_stage_memory", "gpp_stage_backward_weights", "gpp_stage_info", "gpp_stage_io_info",
+    "gpp_pipeline_workspace_bytes", "gpp_pipeline_create", "gpp_pipeline_run", "gpp_pipeline_destroy",
 ]
 GPP_PROFILE_TAGS = 32
 
 class MicrobatchIO(C.Structure):
     _fields_ = [("inputs", C.POINTER(C.c_void_p)), ("outputs", C.POINTER(C.c_void_p)), ("loss_out", C.c_void_p),
                 ("grad_outputs", C.POINTER(C.c_void_p)), ("grad_inputs", C.POINTER(C.c_void_p))]
+
+
+class PipelineEdge(C.Structure):
+    _fields_ = [("from_stage", C.c_int32), ("from_output", C.c_int32), ("to_stage", C.c_int32), ("to_input", C.c_int32)]
 
 
 _lib = None
@@ -113,6 +118,18 @@ def load():
     lib.gpp_stage_run_schedule.restype = i32
     lib.gpp_stage_run_schedule.argtypes = [vp, C.POINTER(i32), i64, C.POINTER(MicrobatchIO), i64, vp, vp]
     lib.gpp_stage_memory.restype, lib.gpp_stage_memory.argtypes = i32, [vp] + [C.POINTER(C.c_size_t)] * 3
+    lib.gpp_stage_info.restype = i32
+    lib.gpp_stage_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i32), C.POINTER(i32)]
+    lib.gpp_stage_io_info.restype = i32
+    lib.gpp_stage_io_info.argtypes = [vp, i32, i32, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32), C.POINTER(i32)]
+    pipe_args = [i32, C.POINTER(vp), i32, C.POINTER(PipelineEdge), C.POINTER(i64), C.POINTER(i64)]
+    lib.gpp_pipeline_workspace_bytes.restype = i32
+    lib.gpp_pipeline_workspace_bytes.argtypes = pipe_args + [C.POINTER(C.c_size_t)]
+    lib.gpp_pipeline_create.restype = i32
+    lib.gpp_pipeline_create.argtypes = pipe_args + [vp, C.c_size_t, C.POINTER(vp)]
+    lib.gpp_pipeline_run.restype = i32
+    lib.gpp_pipeline_run.argtypes = [vp, i64, C.POINTER(C.POINTER(MicrobatchIO)), C.POINTER(vp), C.POINTER(vp)]
+    lib.gpp_pipeline_destroy.restype, lib.gpp_pipeline_destroy.argtypes = i32, [vp]
     _lib = lib
     return lib
 
@@ -254,6 +271,70 @@ def gpp_stage_run_schedule(handle, tasks, io, stream_forward, stream_backward):
     t = (C.c_int32 * max(1, len(tasks)))(*tasks)
     _check(load().gpp_stage_run_schedule(handle, t, len(tasks), ios, len(io), stream_forward, stream_backward))
     return keep
+
+
+def _marshal_io(io, keep):
+    def arr(ptrs):
+        if ptrs is None:
+            return None
+        a = _ptr_array(ptrs)
+        keep.append(a)
+        return a
+    ios = (MicrobatchIO * max(1, len(io)))()
+    for m, (inp, out, loss, gout, gin) in zip(ios, io):
+        m.inputs, m.outputs, m.loss_out, m.grad_outputs, m.grad_inputs = arr(inp), arr(out), loss, arr(gout), arr(gin)
+    keep.append(ios)
+    return ios
+
+
+def _pipeline_args(stage_handles, edges, in_flight, k):
+    n, ne = len(stage_handles), len(edges)
+    hs = (C.c_void_p * n)(*[h.value if isinstance(h, C.c_void_p) else h for h in stage_handles])
+    es = (PipelineEdge * max(1, ne))(*[PipelineEdge(*e) for e in edges])
+    return [n, hs, ne, es, (C.c_int64 * n)(*in_flight), (C.c_int64 * n)(*k)]
+
+
+def gpp_pipeline_workspace_bytes(stage_handles, edges, in_flight, k):
+    """edges: (from_stage, from_output, to_stage, to_input) tuples; (x, -1, y, -1) is an order-only edge."""
+    out = C.c_size_t(0)
+    _check(load().gpp_pipeline_workspace_bytes(*_pipeline_args(stage_handles, edges, in_flight, k), C.byref(out)))
+    return out.value
+
+
+def gpp_pipeline_create(stage_handles, edges, in_flight, k, workspace_ptr, workspace_bytes):
+    h = C.c_void_p()
+    _check(load().gpp_pipeline_create(*_pipeline_args(stage_handles, edges, in_flight, k), workspace_ptr, workspace_bytes,
+                                      C.byref(h)))
+    return h
+
+
+def gpp_pipeline_run(handle, io, streams_forward, streams_backward):
+    """io[s][j]: the tuple gpp_stage_run_schedule takes, for stage s and micro-batch j."""
+    keep = []
+    per_stage = [_marshal_io(rows, keep) for rows in io]
+    n = len(io)
+    arr = (C.POINTER(MicrobatchIO) * n)(*[C.cast(a, C.POINTER(MicrobatchIO)) for a in per_stage])
+    n_micro = len(io[0]) if io else 0
+    _check(load().gpp_pipeline_run(handle, n_micro, arr, (C.c_void_p * n)(*streams_forward), (C.c_void_p * n)(*streams_backward)))
+    return keep
+
+
+def gpp_pipeline_destroy(handle):
+    _check(load().gpp_pipeline_destroy(handle))
+
+
+def gpp_stage_info(handle):
+    """(micro-batch size, stash slots, flags)."""
+    a, b, c = C.c_int64(), C.c_int32(), C.c_int32()
+    _check(load().gpp_stage_info(handle, C.byref(a), C.byref(b), C.byref(c)))
+    return a.value, b.value, c.value
+
+
+def gpp_stage_io_info(handle, is_output, index):
+    """(rows, features, dtype code, has_grad) of an input or output."""
+    r, f, d, g = C.c_int64(), C.c_int64(), C.c_int32(), C.c_int32()
+    _check(load().gpp_stage_io_info(handle, 1 if is_output else 0, index, C.byref(r), C.byref(f), C.byref(d), C.byref(g)))
+    return r.value, f.value, d.value, bool(g.value)
 
 
 def gpp_stage_memory(handle):

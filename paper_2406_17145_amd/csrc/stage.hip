@@ -207,6 +207,25 @@ int32_t gpp_stage_input_op(const gpp_stage_t *s, int32_t i) {
 int32_t gpp_stage_output_op(const gpp_stage_t *s, int32_t i) {
   return (s && i >= 0 && i < (int32_t)s->plan.output_ops.size()) ? s->plan.output_ops[i] : -1;
 }
+gpp_status_t gpp_stage_info(const gpp_stage_t *s, int64_t *micro_batch, int32_t *in_flight_slots, int32_t *flags) {
+  if (!s) return fail(GPP_ERR_INVALID_ARG, "stage is null");
+  if (micro_batch) *micro_batch = s->plan.micro_batch;
+  if (in_flight_slots) *in_flight_slots = s->plan.slots;
+  if (flags) *flags = s->plan.flags;
+  return GPP_OK;
+}
+gpp_status_t gpp_stage_io_info(const gpp_stage_t *s, int32_t is_output, int32_t index, int64_t *rows, int64_t *features,
+                               int32_t *dtype, int32_t *has_grad) {
+  if (!s) return fail(GPP_ERR_INVALID_ARG, "stage is null");
+  const std::vector<int> &ids = is_output ? s->plan.output_ops : s->plan.input_ops;
+  if (index < 0 || index >= (int32_t)ids.size()) return fail(GPP_ERR_INVALID_ARG, "input / output index out of range");
+  const Node &nd = s->plan.nodes[ids[index]];
+  if (rows) *rows = nd.rows;
+  if (features) *features = nd.feat;
+  if (dtype) *dtype = nd.d.dtype;
+  if (has_grad) *has_grad = nd.wants_grad ? 1 : 0;
+  return GPP_OK;
+}
 int32_t gpp_stage_num_launches(const gpp_stage_t *s, int32_t backward) {
   if (!s) return -1;
   int32_t n = 0;

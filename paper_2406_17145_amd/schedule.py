@@ -140,6 +140,71 @@ class TaskSchedule:
         return tasks
 
 
+class StagePipeline:
+    """Several stages of one stage graph on one GPU (paper section 3: G_S; section 2: stages without a path
+    between them run concurrently): the library's pipeline executor over stages created by the binding.  Every
+    stage gets its own pair of streams (they stand in for its devices), its schedule configuration (i, k) comes
+    from the library's reverse traversal of the stage graph (gpp_assign_schedules) unless given, and the
+    edges carry tensors forward and gradients backward through buffers of the pipeline's workspace.
+
+    edges: (from_stage, from_output, to_stage, to_input); (x, -1, y, -1) orders y after x without data (a
+    linearised pipeline chains independent stages this way).  A stage must have been created with at least
+    i / b stash slots (see in_flight_microbatches for the counts a stage graph needs)."""
+
+    @staticmethod
+    def in_flight_microbatches(n_stages, edges, micro_batch, k_candidates=None):
+        from . import binding as B
+        i, k = B.gpp_assign_schedules(n_stages, [(e[0], e[2]) for e in edges], [micro_batch] * n_stages,
+                                      k_candidates or [[1]] * n_stages)
+        return [v // micro_batch for v in i], k
+
+    def __init__(self, stages, edges, in_flight=None, k=None, streams_per_stage=2):
+        from . import binding as B
+        self.B, self.stages, self.edges = B, stages, list(edges)
+        torch = stages[0].torch
+        b = stages[0].b
+        if in_flight is None:
+            caps, k = self.in_flight_microbatches(len(stages), self.edges, b)
+            in_flight = [c * b for c in caps]
+        self.in_flight, self.k = list(in_flight), list(k or [1] * len(stages))
+        hs = [st.handle for st in stages]
+        self.ws_bytes = B.gpp_pipeline_workspace_bytes(hs, self.edges, self.in_flight, self.k)
+        self.ws = torch.empty(self.ws_bytes + 256, dtype=torch.uint8, device=stages[0].dev)
+        base = (self.ws.data_ptr() + 255) // 256 * 256
+        self.handle = B.gpp_pipeline_create(hs, self.edges, self.in_flight, self.k, base, self.ws_bytes)
+        dev = stages[0].dev
+        self.s_f = [torch.cuda.Stream(device=dev) for _ in stages]      # default priority on all
+        self.s_b = [torch.cuda.Stream(device=dev) for _ in stages] if streams_per_stage == 2 else self.s_f
+        self._keep = None
+
+    def minibatch(self, io):
+        """io[s][j] = (inputs, outputs, loss, grad_outputs, grad_inputs): lists of device tensors (None entries
+        where an edge carries the tensor), a loss tensor or None.  Kept alive until the next call."""
+        torch = self.stages[0].torch
+        main = torch.cuda.current_stream(self.stages[0].dev)
+        for s in set(self.s_f + self.s_b):
+            s.wait_stream(main)
+
+        def ptrs(x):
+            return None if x is None else [t.data_ptr() if t is not None else None for t in x]
+        raw = [[(ptrs(i), ptrs(o), None if l is None else l.data_ptr(), ptrs(go), ptrs(gi)) for (i, o, l, go, gi) in rows]
+               for rows in io]
+        self._keep = (self.B.gpp_pipeline_run(self.handle, raw, [s.cuda_stream for s in self.s_f],
+                                              [s.cuda_stream for s in self.s_b]), io)
+        for s in set(self.s_f + self.s_b):
+            main.wait_stream(s)
+
+    def stash_bytes(self):
+        """Per stage: bytes its in-flight micro-batches pin (slots it uses x bytes of a slot)."""
+        b = self.stages[0].b
+        return [max(1, i // b) * self.B.gpp_stage_memory(st.handle)[0] for i, st in zip(self.in_flight, self.stages)]
+
+    def close(self):
+        if self.handle is not None:
+            self.B.gpp_pipeline_destroy(self.handle)
+            self.handle = None
+
+
 class GraphedMinibatch:
     """One whole mini-batch of a schedule (gradient reset, every fw_j and bw_j, the events between
     the streams) captured once into a HIP graph and replayed: the stage's calls only enqueue kernels

@@ -334,3 +334,78 @@ CONFIGS = {
     "dlrm": dlrm,
     "hetero": hetero,
 }
+
+
+# --------------------------------------------------------------------------
+# cutting a workload's operator graph G_C into stages (paper section 3: the G_i partition G_C, C1;
+# an edge of G_C between two stages becomes an edge of the stage graph, C2).  Graph surgery only.
+# --------------------------------------------------------------------------
+@dataclass
+class StagePart:
+    ops: list              # the stage's operator list (local ids)
+    params: dict           # local op id -> parameter arrays
+    batches: list          # per micro-batch: {local input op id -> array} (the caller's inputs only)
+    global_of: list        # local op id -> op id in the whole graph (-1 for an input that an edge feeds)
+    output_global: list    # global ids of the stage's outputs, in the stage's output order
+
+
+def partition(wl: Workload, stage_of: dict, n_stages: int):
+    """stage_of: op id -> stage, for every non-input operator; an input goes where its consumers are.
+    A tensor that crosses a cut must have all its consumers in ONE other stage and none in its own (fan-out
+    lives inside a stage).  Returns (parts, edges): edges are (from_stage, from_output, to_stage, to_input)."""
+    ops = wl.ops
+    users = {i: [] for i in range(len(ops))}
+    for i, op in enumerate(ops):
+        for p in op["inputs"]:
+            users[p].append(i)
+    st = dict(stage_of)
+    for i, op in enumerate(ops):
+        if op["kind"] == "input":
+            homes = {st[u] for u in users[i]}
+            assert len(homes) == 1, f"input {i} feeds several stages"
+            st[i] = homes.pop()
+    seq = {}                                   # rows per sample of every tensor
+    for i, op in enumerate(ops):
+        if op["kind"] == "input":
+            seq[i] = op.get("seq_len", 1)
+        elif op["kind"] in ("meanpool", "embedding_bag_sum"):
+            seq[i] = 1
+        elif op["inputs"]:
+            seq[i] = seq[op["inputs"][0]]
+    cuts = []                                  # (producer id, consumer stage)
+    for i, op in enumerate(ops):
+        away = {st[u] for u in users[i]} - {st[i]}
+        if away:
+            assert len(away) == 1 and all(st[u] != st[i] for u in users[i]), f"tensor {i} fans out across a cut"
+            cuts.append((i, away.pop()))
+    parts, local = [], [dict() for _ in range(n_stages)]
+    for s in range(n_stages):
+        new_ops, global_of = [], []
+        for (prod, cs) in cuts:                # inputs that edges feed come first, in producer order
+            if cs != s:
+                continue
+            p = ops[prod]
+            new_ops.append(dict(kind="input", inputs=[], branch=p.get("branch", -1), out_features=p["out_features"],
+                                dtype=p.get("out_dtype", p["dtype"]), seq_len=seq[prod], rows_extra=0, role="data"))
+            local[s][("cut", prod)] = len(new_ops) - 1
+            global_of.append(-1)
+        for i, op in enumerate(ops):
+            if st[i] != s:
+                continue
+            o = dict(op)
+            o["inputs"] = [local[s][p] if p in local[s] else local[s][("cut", p)] for p in op["inputs"]]
+            new_ops.append(o)
+            local[s][i] = len(new_ops) - 1
+            global_of.append(i)
+        params = {local[s][i]: p for i, p in wl.params.items() if st[i] == s}
+        batches = [{local[s][i]: a for i, a in mb.items() if st[i] == s} for mb in wl.batches]
+        used = {p for o in new_ops for p in o["inputs"]}
+        outs = [global_of[l] for l, o in enumerate(new_ops)
+                if l not in used and o["kind"] != "input" and not o["kind"].startswith("loss")]
+        parts.append(StagePart(new_ops, params, batches, global_of, outs))
+    edges = []
+    for (prod, cs) in cuts:
+        ps = st[prod]
+        to_inputs = [l for l, o in enumerate(parts[cs].ops) if o["kind"] == "input"]
+        edges.append((ps, parts[ps].output_global.index(prod), cs, to_inputs.index(local[cs][("cut", prod)])))
+    return parts, edges

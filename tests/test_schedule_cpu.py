@@ -94,3 +94,34 @@ def test_task_list_errors():
         with pytest.raises(B.GppError) as e:
             B.gpp_schedule_tasks(*args)
         assert e.value.status == B.GPP_ERR_INVALID_ARG
+
+
+# ---- cutting an operator graph into stages (graph surgery of the workload module) and the stage graph's counts
+
+def test_partition_of_a_branchy_model_gives_its_stage_graph():
+    from paper_2406_17145_amd import workloads as W
+    from paper_2406_17145_amd.schedule import StagePipeline
+    wl = W.candle_uno(micro_batch=8, n_micro=2, widths=(70, 131, 33), hidden=96, act="gelu")
+    stage_of = {i: (op["branch"] if op["branch"] >= 0 else 3) for i, op in enumerate(wl.ops) if op["kind"] != "input"}
+    parts, edges = W.partition(wl, stage_of, 4)
+    assert edges == [(0, 0, 3, 0), (1, 0, 3, 1), (2, 0, 3, 2)]
+    assert [len(p.output_global) for p in parts] == [1, 1, 1, 0]
+    # every operator and parameter of the model is in exactly one stage (C1: the G_i partition G_C)
+    owned = sorted(g for p in parts for g in p.global_of if g >= 0)
+    assert owned == list(range(len(wl.ops)))
+    assert sorted(p.global_of[l] for p in parts for l in p.params) == sorted(wl.params)
+    # edge-fed inputs of the merge stage have the producers' widths and storage type
+    merge = parts[3].ops
+    assert [(o["kind"], o["out_features"], o["dtype"]) for o in merge[:3]] == [("input", 96, "bf16")] * 3
+    # the stage graph's in-flight micro-batches: side by side (depth 2) against chained (depth 4), section 2
+    assert StagePipeline.in_flight_microbatches(4, edges, 8)[0] == [2, 2, 2, 1]
+    assert StagePipeline.in_flight_microbatches(4, edges + [(0, -1, 1, -1), (1, -1, 2, -1)], 8)[0] == [4, 3, 2, 1]
+
+
+def test_partition_refuses_fan_out_across_a_cut():
+    from paper_2406_17145_amd import workloads as W
+    wl = W.tiny_mlp()
+    # the first layer of branch 0 alone in a stage is fine; cutting between an input and two stages is not
+    stage_of = {i: 0 for i, op in enumerate(wl.ops) if op["kind"] != "input"}
+    parts, edges = W.partition(wl, stage_of, 1)
+    assert edges == [] and len(parts[0].ops) == len(wl.ops)
