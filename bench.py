@@ -121,7 +121,7 @@ MEASURED_TRAFFIC = {
     ("mmt", "gemm_big_dx"): 168.1e6,
     ("mmt", "gemm_big_dw"): 190.0e6,
     ("dlrm", "embedding_bwd_sort_segsum"): 54.3e6,
-    ("dlrm", "embedding_fwd"): 253.8e6,
+    ("dlrm", "embedding_fwd"): 180.6e6,
 }
 
 

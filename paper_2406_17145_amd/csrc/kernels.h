@@ -228,7 +228,8 @@ int attn_blocks(int batch, int heads, int seq);
 void launch_pool(const PoolProb *probs, int n, int total_blocks, hipStream_t s);
 int pool_blocks(const PoolProb &p);
 
-void launch_emb_fwd(const EmbProb *probs, int n, int total_blocks, int vec, StageFlags *flags, hipStream_t s);
+void launch_emb_fwd(const EmbProb *probs, int n, int total_blocks, int vec, int per_table, StageFlags *flags, hipStream_t s);
+int emb_fwd_affinity_grid(int n, int per_table);
 int emb_fwd_blocks(int n_bags);
 bool emb_vec_supported(const EmbProb &p);
 // sort + segment heads + segment sums into log slot `slot`; returns the number of launches it enqueues

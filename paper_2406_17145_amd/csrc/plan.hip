@@ -1005,7 +1005,14 @@ void Emitter::forward() {
       }
       bool vec = true;
       for (auto &e : embs) vec = vec && emb_vec_supported(e);
-      add_step(K_EMB_FWD, push_table(embs), (int)embs.size(), blocks).a0 = vec ? 1 : 0;
+      // vector kernel with eight or more tables: table -> XCD affinity (see emb_fwd_affinity_grid); a1 = the
+      // largest workgroup count of a table, the grid is then laid out per table instead of by prefix sums
+      int per_table = 0;
+      for (auto &e : embs) per_table = std::max(per_table, emb_fwd_blocks(e.n_bags));
+      const bool affinity = vec && embs.size() >= 8;
+      Step &se = add_step(K_EMB_FWD, push_table(embs), (int)embs.size(), affinity ? emb_fwd_affinity_grid((int)embs.size(), per_table) : blocks);
+      se.a0 = vec ? 1 : 0;
+      se.a1 = affinity ? per_table : 0;
     }
     if (!inters.empty()) {
       int blocks = 0, mf = 0, md = 0;

@@ -309,7 +309,7 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
         else launch_attn_bwd_dkv((const AttnProb *)tab, sp.n, sp.blocks, sp.a0, s);
         break;
       case K_POOL: launch_pool((const PoolProb *)tab, sp.n, sp.blocks, s); break;
-      case K_EMB_FWD: launch_emb_fwd((const EmbProb *)tab, sp.n, sp.blocks, sp.a0, flags, s); break;
+      case K_EMB_FWD: launch_emb_fwd((const EmbProb *)tab, sp.n, sp.blocks, sp.a0, sp.a1, flags, s); break;
       case K_EMB_BWD: {
         if (st->emb_clear_pending) {
           launch_emb_reset((const EmbProb *)tab, sp.n, sp.a0, 0, s);

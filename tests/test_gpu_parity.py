@@ -92,6 +92,12 @@ def test_dlrm_bf16_small():
                 top=(128, 64, 1)))
 
 
+def test_dlrm_bf16_eleven_tables_ragged_bags():
+    # eight or more tables: the gather's workgroups are laid out per table (eight tables bound to one XCD each,
+    # three spread over all); 130 bags leave the last workgroup of every table half empty
+    both(W.dlrm(micro_batch=130, n_micro=2, n_tables=11, num_rows=2000, bottom=(64, 32, 128), top=(128, 64, 1)))
+
+
 def test_large_tile_gemm_ragged_edges():
     # many rows AND wide layers: the launches of the hidden layers go to the large-tile kernel
     # (forward, backward-data and backward-weight), with rows, columns and contraction lengths
