@@ -165,6 +165,39 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmProb &p, int local, u
     }
   };
 
+  // ---- what the epilogue reads from memory besides the product (residual / gradient addend, mask source
+  // or stashed derivative) is requested HERE, before the k-loop: a thread owns one 8-column piece of one
+  // row when the workgroup's threads cover the tile in one pass, and a load issued only after the
+  // reduction would add a whole memory round trip to a kernel that lasts a few of them.
+  constexpr int TPR = BN / 8, ROWS_PER_PASS = 64 * NW / TPR;
+  constexpr bool ONE_PASS = ROWS_PER_PASS >= BM;
+  const int cg = (threadIdx.x % TPR) * 8;
+  // Fast path: bf16 result (and bf16 residual / mask source / stash where present) in whole, aligned
+  // 16-byte chunks.  The storage types are known here, so no type test stands between the loads.
+  const bool chunked = Cout != nullptr && p.c_dtype == DT_BF16 && (p.N & 7) == 0 && (p.ldc & 7) == 0 && ((uintptr_t)Cout & 15) == 0 &&
+                       (!p.res || (p.res_dtype == DT_BF16 && (p.ldres & 7) == 0 && ((uintptr_t)p.res & 15) == 0)) &&
+                       (!p.aux || (p.aux_dtype == DT_BF16 && (p.ldaux & 7) == 0 && ((uintptr_t)p.aux & 15) == 0)) &&
+                       (FORM == FORM_DX || !p.bias || ((uintptr_t)p.bias & 15) == 0);
+  const bool use_aux_in = FORM == FORM_DX && p.act != ACT_NONE;
+  u32x4 pre_res = {0u, 0u, 0u, 0u}, pre_aux = {0u, 0u, 0u, 0u};
+  float pre_bias[8] = {};
+  if (ONE_PASS && chunked) {    // uniform: nothing is outstanding yet, so the branch costs no wait
+    // clamped to the tile's valid part: a thread without a piece reads a valid one and drops it
+    const int row = min(m0 + (int)threadIdx.x / TPR, p.M - 1), col = min(n0 + cg, p.N - 8);
+    if (FORM == FORM_FWD && p.bias) {
+      const float4 b0 = *(const float4 *)(p.bias + col), b1 = *(const float4 *)(p.bias + col + 4);
+      pre_bias[0] = b0.x; pre_bias[1] = b0.y; pre_bias[2] = b0.z; pre_bias[3] = b0.w;
+      pre_bias[4] = b1.x; pre_bias[5] = b1.y; pre_bias[6] = b1.z; pre_bias[7] = b1.w;
+    }
+    // an absent operand is read from the result buffer instead (valid memory, value unused): no
+    // branch stands between these loads and the loads of the k-loop behind them
+    const uint16_t *resp = p.res ? (const uint16_t *)p.res : (const uint16_t *)Cout;
+    const uint16_t *auxp = use_aux_in ? (const uint16_t *)p.aux : (const uint16_t *)Cout;
+    const int64_t ldr = p.res ? p.ldres : p.ldc, lda = use_aux_in ? p.ldaux : p.ldc;
+    pre_res = *(const u32x4 *)(resp + (int64_t)row * ldr + col);
+    pre_aux = *(const u32x4 *)(auxp + (int64_t)row * lda + col);
+  }
+
   // NS register sets rotate: while one step is multiplied, the next NS-1 are on their way from memory
   // (bounded by the register file: 256 VGPRs per lane at 8 waves)
   constexpr int NS = NW == 8 ? (TI + TJ <= 3 ? 3 : 2) : 3;
@@ -216,26 +249,19 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmProb &p, int local, u
   if (Cout == nullptr) return;     // the caller does not want this result (all barriers are behind us)
 
   // ---- epilogue, all waves: thread t owns 8 consecutive columns; BN / 8 threads per row
-  constexpr int TPR = BN / 8, ROWS_PER_PASS = 64 * NW / TPR;
-  const int cg = (threadIdx.x % TPR) * 8;
-  // Fast path: bf16 result (and bf16 residual / mask source / stash where present) in whole, aligned
-  // 16-byte chunks.  Everything a row needs from memory is requested as 16-byte loads before it is
-  // used, and the storage types are known here, so no type test stands between the loads.
-  const bool chunked = p.c_dtype == DT_BF16 && (p.N & 7) == 0 && (p.ldc & 7) == 0 && ((uintptr_t)Cout & 15) == 0 &&
-                       (!p.res || (p.res_dtype == DT_BF16 && (p.ldres & 7) == 0 && ((uintptr_t)p.res & 15) == 0)) &&
-                       (!p.aux || (p.aux_dtype == DT_BF16 && (p.ldaux & 7) == 0 && ((uintptr_t)p.aux & 15) == 0)) &&
-                       (FORM == FORM_DX || !p.bias || ((uintptr_t)p.bias & 15) == 0);
   if (chunked) {
     const int col = n0 + cg;
     if (col >= p.N) return;
     float bias[8] = {};
-    if (FORM == FORM_FWD && p.bias) {
+    if (ONE_PASS) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) bias[e] = pre_bias[e];
+    } else if (FORM == FORM_FWD && p.bias) {
       const float4 b0 = *(const float4 *)(p.bias + col), b1 = *(const float4 *)(p.bias + col + 4);
       bias[0] = b0.x; bias[1] = b0.y; bias[2] = b0.z; bias[3] = b0.w;
       bias[4] = b1.x; bias[5] = b1.y; bias[6] = b1.z; bias[7] = b1.w;
     }
-    const bool use_aux_in = FORM == FORM_DX && p.act != ACT_NONE;
-    // an absent operand is read from the result buffer instead (valid memory, value unused): the two
+    // (several passes over the tile) an absent operand is read from the result buffer instead (valid memory, value unused): the two
     // loads of a row then carry no branch
     const uint16_t *resp = p.res ? (const uint16_t *)p.res : (const uint16_t *)Cout;
     const uint16_t *auxp = use_aux_in ? (const uint16_t *)p.aux : (const uint16_t *)Cout;
@@ -243,8 +269,11 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmProb &p, int local, u
     for (int lr = threadIdx.x / TPR; lr < BM; lr += ROWS_PER_PASS) {
       const int row = m0 + lr;
       if (row >= p.M) break;
-      const u32x4 res_raw = *(const u32x4 *)(resp + (int64_t)row * ldr + col);
-      const u32x4 aux_raw = *(const u32x4 *)(auxp + (int64_t)row * lda + col);
+      u32x4 res_raw = pre_res, aux_raw = pre_aux;
+      if (!ONE_PASS) {
+        res_raw = *(const u32x4 *)(resp + (int64_t)row * ldr + col);
+        aux_raw = *(const u32x4 *)(auxp + (int64_t)row * lda + col);
+      }
       float v[8], rs[8], ax[8];
       {
         const float4 a = *(const float4 *)(r1 + lr * BN + cg), b = *(const float4 *)(r1 + lr * BN + cg + 4);

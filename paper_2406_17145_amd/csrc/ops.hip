@@ -661,7 +661,8 @@ void launch_loss_fwd(const LossProb *probs, int n, int total_blocks, hipStream_t
 
 // Small heads (all of a stage's losses together at most a few tens of thousands of elements): one
 // workgroup computes every loss and their sum, so the forward pass needs one launch, not two.
-// MSE / BCE: a thread per element, strided; cross-entropy: a wave per row.  All sums in a fixed order.
+// MSE / BCE: a thread per element, strided (and, where the record names a gradient buffer, the
+// gradient with it); cross-entropy: a wave per row.  All sums in a fixed order.
 int loss_small_limit() { return 65536; }
 __global__ __launch_bounds__(256) void k_loss_fwd_small(const LossProb *__restrict__ probs, int n, float *out) {
   __shared__ float red[4];
@@ -694,6 +695,10 @@ __global__ __launch_bounds__(256) void k_loss_fwd_small(const LossProb *__restri
         } else {
           acc += softplus_f(y) - t * y;
         }
+        // the gradient with the value (stages whose gradient buffers are per stash slot ask for it)
+        if (p.dy)
+          store_from_f32(p.dy, p.dy_dtype, (int64_t)r * p.ld_dy + c,
+                         p.kind == 9 ? 2.0f * p.scale * (y - t) : p.scale * (sigmoid_f(y) - t));
       }
     }
     acc = wave_sum(acc);

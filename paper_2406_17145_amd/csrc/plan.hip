@@ -386,6 +386,7 @@ struct Emitter {
   std::vector<char> dz_ready;
   int64_t part_need = 0, cnt_need = 0;  // split-K scratch high-water marks over all launches
   std::vector<GemmProb> dw_group;   // backward-weight records left to the launch over a group of slots
+  std::vector<char> loss_fused;     // per node: this loss's gradient is written by the forward pass
   std::vector<int> written_level;   // level whose launches first wrote the node's gradient
   int cur_level = 0;
   int64_t shared_tmp_top;
@@ -759,6 +760,7 @@ void Emitter::forward() {
   steps->clear();
   bool loss_summed = false;
   auto &N = pl.nodes;
+  loss_fused.assign(N.size(), 0);
 
   // ingest: copy the caller's dense inputs into the (padded) stash buffers
   {
@@ -953,6 +955,15 @@ void Emitter::forward() {
           l.cols = (int32_t)y.feat;
           l.kind = d.kind;
           l.scale = (float)d.loss_scale;
+          // per-slot gradient buffers (grouped weight gradients): an element-wise loss whose prediction
+          // has no other consumer writes its gradient in the forward pass, one launch less per backward
+          if ((pl.flags & 4) && d.kind != GPP_OP_LOSS_CE && y.wants_grad && y.users.size() == 1 && y.gout_parent < 0 &&
+              y.fused_add < 0 && y.gout.space == SP_SLOT) {
+            l.dy = ptr(y.gout);
+            l.ld_dy = y.gout.ld;
+            l.dy_dtype = y.gout.dtype;
+            loss_fused[i] = 1;
+          }
           losses.push_back(l);
           break;
         }
@@ -1038,6 +1049,7 @@ void Emitter::forward() {
         add_step(K_LOSS_FWD_SMALL, push_table(losses), (int)losses.size(), 1);   // value and sum in one launch
         loss_summed = true;
       } else {
+        for (int i : pl.by_level[L]) loss_fused[i] = 0;   // only the one-workgroup kernel writes gradients
         add_step(K_LOSS_FWD, push_table(losses), (int)losses.size(), blocks);
       }
     }
@@ -1134,6 +1146,9 @@ void Emitter::backward() {
         const Node &t = N[nd.in[1]];
         const Buf &yv = y.fused_add >= 0 ? N[y.fused_add].val : y.val;
         Target tg = acquire(nd.in[0], false);
+        // written by the forward pass already (the prediction's only consumer is this loss, so the
+        // gradient buffer itself is the target and nothing is added to it)
+        if (loss_fused[i] && !tg.post && !tg.addend.valid() && tg.dst.space == y.gout.space && tg.dst.off == y.gout.off) continue;
         LossProb l;
         memset(&l, 0, sizeof(l));
         l.y = ptr(yv);
