@@ -269,3 +269,26 @@ def test_grouped_weight_gradients_state_machine():
     assert st.num_launches(2) == 0
     st.backward_weights()
     st.close()
+
+
+def test_grouped_weight_gradients_degenerate_sizes():
+    # one and three rows per stash slot (a k-step of the grouped contraction is almost empty), one micro-batch
+    # per mini-batch (a group of one), and more micro-batches than slots (several groups, the later ones add)
+    for mb, n_micro, cap, k in [(1, 5, 5, 5), (3, 4, 2, 2), (5, 1, 1, 1), (2, 9, 3, 3)]:
+        wl = W.candle_uno(micro_batch=mb, n_micro=n_micro, widths=(40, 72, 8, 24), hidden=64, act="gelu")
+        ora_stage, ora_res = run_oracle(wl)
+        print(f"[case] {wl.name} b={mb} x {n_micro}, grouped weight gradients cap={cap} k={k}", flush=True)
+        _, res, grads = _run(wl, cap, k, True, flags=B.FLAG_GROUPED_DW)
+        compare(wl, res, grads, ora_stage, ora_res, label=f"grouped degenerate b={mb}")
+
+
+def test_executor_with_no_micro_batches_is_a_gradient_reset():
+    import torch
+    wl = W.tiny_mlp()
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=2)
+    s = torch.cuda.current_stream().cuda_stream
+    B.gpp_stage_run_schedule(st.handle, [], [], s, s)
+    st.forward(0, wl.batches[0])          # the stage is usable afterwards
+    st.backward(0)
+    st.sync_status()
+    st.close()
