@@ -1,0 +1,136 @@
+"""Pins of the partitioner oracle (no GPU, no product code): small stage-graph problems whose answer follows
+from the paper's statements or from counting by hand."""
+import random
+
+import pytest
+
+from oracle import partition_oracle as P
+
+BIG = 1e30
+
+
+def chain(n):
+    return [(i, i + 1) for i in range(n - 1)]
+
+
+def branches(n_br, depth):
+    """n_br independent chains of `depth` operators feeding one merge operator (the last id)."""
+    edges, op = [], 0
+    lasts = []
+    for _ in range(n_br):
+        for k in range(depth):
+            if k:
+                edges.append((op - 1, op))
+            op += 1
+        lasts.append(op - 1)
+    for l in lasts:
+        edges.append((l, op))
+    return op + 1, edges
+
+
+# ---- series-parallel structure
+
+def test_tree_of_a_diamond_a_chain_and_a_graph_that_is_not_series_parallel():
+    assert P.sp_tree(4, [(0, 1), (0, 2), (1, 3), (2, 3)]) == \
+        ("series", [("leaf", 0), ("parallel", [("leaf", 1), ("leaf", 2)]), ("leaf", 3)])
+    assert P.sp_tree(3, chain(3)) == ("series", [("leaf", 0), ("leaf", 1), ("leaf", 2)])
+    # a -> c, a -> d, b -> d: connected, and no operator is related to all others
+    assert P.sp_tree(4, [(0, 2), (0, 3), (1, 3)]) == ("block", [0, 1, 2, 3])
+    n, e = branches(3, 2)
+    assert P.sp_tree(n, e) == ("series", [("parallel", [("series", [("leaf", 0), ("leaf", 1)]),
+                                                       ("series", [("leaf", 2), ("leaf", 3)]),
+                                                       ("series", [("leaf", 4), ("leaf", 5)])]), ("leaf", 6)])
+
+
+def test_tree_keeps_every_operator_exactly_once_on_random_graphs():
+    r = random.Random(3)
+    for _ in range(200):
+        n = r.randrange(1, 12)
+        edges = [(u, v) for u in range(n) for v in range(u + 1, n) if r.random() < 0.25]
+        assert sorted(P.ops_of(P.sp_tree(n, edges))) == list(range(n))
+
+
+# ---- section 6: a sequential pipeline of n equal stages holds (n + 1 - x) b samples at stage x
+
+@pytest.mark.parametrize("n,b", [(1, 4), (3, 2), (5, 1)])
+def test_chain_of_equal_operators_on_as_many_devices(n, b):
+    # with any cost for keeping replicas in step, one operator per device beats data parallelism
+    plan, ev = P.best_stage_graph(n, chain(n), [1.0] * n, [1.0] * n, [1.0] * n, n, b, BIG, sync_per_byte=0.01, mini_batch=8)
+    assert [sorted(ops) for ops, _ in plan] == [[i] for i in range(n)]
+    assert [d for _, d in plan] == [1] * n
+    assert ev["tps"] == 1.0
+    assert ev["in_flight"] == [(n - x) * b for x in range(n)]
+
+
+def test_chain_with_fewer_devices_and_unequal_costs():
+    sync = dict(sync_per_byte=0.01, mini_batch=8)
+    plan, ev = P.best_stage_graph(4, chain(4), [1.0] * 4, [1.0] * 4, [0.0] * 4, 2, 1, BIG, **sync)
+    assert ev["tps"] == 2.0 and sorted(sorted(o) for o, _ in plan) == [[0, 1], [2, 3]]
+    # 3 + 1 + 1 + 1 on two devices, replicas for free: [3 | 1 1 1] and one data-parallel stage both reach 3;
+    # the single stage holds fewer samples in flight
+    plan, ev = P.best_stage_graph(4, chain(4), [3.0, 1.0, 1.0, 1.0], [0.0] * 4, [0.0] * 4, 2, 1, BIG)
+    assert ev["tps"] == 3.0 and len(plan) == 1 and plan[0][1] == 2 and ev["in_flight"] == [1]
+    # ... and with a cost for replicas the pipeline wins
+    plan, ev = P.best_stage_graph(4, chain(4), [3.0, 1.0, 1.0, 1.0], [1.0] * 4, [0.0] * 4, 2, 1, BIG, **sync)
+    assert ev["tps"] == 3.0 and sorted(sorted(o) for o, _ in plan) == [[0], [1, 2, 3]] and ev["in_flight"] == [2, 1]
+
+
+def test_one_device_is_one_stage_and_an_impossible_budget_gives_nothing():
+    n, e = branches(2, 2)
+    plan, ev = P.best_stage_graph(n, e, [1.0] * n, [1.0] * n, [1.0] * n, 1, 2, BIG)
+    assert len(plan) == 1 and ev["tps"] == float(n) and ev["in_flight"] == [2]
+    assert P.best_stage_graph(n, e, [1.0] * n, [1.0] * n, [1.0] * n, 1, 2, memory=4.0) is None   # weights alone are 5
+
+
+# ---- section 2: independent branches as parallel stages: depth 2 instead of depth 4
+
+def test_branches_become_parallel_stages_with_depth_two_counts():
+    n, e = branches(3, 1)                  # three one-operator branches and a merge operator
+    b = 4
+    plan, ev = P.best_stage_graph(n, e, [1.0] * n, [1.0] * n, [1.0] * n, 4, b, BIG, sync_per_byte=0.01, mini_batch=8)
+    assert ev["tps"] == 1.0 and len(plan) == 4
+    assert ev["in_flight"] == [2 * b, 2 * b, 2 * b, b]
+    assert ev["edges"] == [(0, 3), (1, 3), (2, 3)]
+
+
+def test_memory_budget_decides_the_stage_graph():
+    n, e = branches(2, 1)                  # two branches (operators 0, 1) and a merge operator (2), three devices
+    t, w, a, b = [2.0, 2.0, 1.0], [1.0] * 3, [10.0, 10.0, 1.0], 1
+    sync = dict(sync_per_byte=3.0, mini_batch=4)       # a replica costs 2 (d-1)/d x 3/4 seconds per sample and weight byte
+    # plenty of memory: every operator its own stage, bottleneck 2; the branch stages hold 2 samples: 1 + 20 bytes
+    plan, ev = P.best_stage_graph(n, e, t, w, a, 3, b, BIG, **sync)
+    assert ev["tps"] == 2.0 and len(plan) == 3 and ev["memory"][:2] == [21.0, 21.0]
+    # 15 bytes per device: two samples of a branch no longer fit one device.  What is left: everything in one
+    # data-parallel stage on three devices: 5 / 3 + 2 (2/3) x 3 bytes x 3/4 = 4.67 per sample, 3 + 21 / 3 = 10 bytes
+    plan, ev = P.best_stage_graph(n, e, t, w, a, 3, b, 15.0, **sync)
+    assert len(plan) == 1 and plan[0][1] == 3 and ev["tps"] == pytest.approx(5.0 / 3.0 + 3.0) and ev["memory"] == [10.0]
+    # 5 bytes: nothing fits
+    assert P.best_stage_graph(n, e, t, w, a, 3, b, 5.0, **sync) is None
+
+
+# ---- conditions C1 - C3 (section 3) on whatever comes back
+
+def test_returned_stage_graphs_satisfy_c1_c2_c3_on_random_series_parallel_models():
+    r = random.Random(9)
+    for trial in range(40):
+        n, e = branches(r.randrange(1, 4), r.randrange(1, 3))
+        extra = r.randrange(0, 3)          # a tail of operators behind the merge
+        e = e + [(n - 1 + k, n + k) for k in range(extra)]
+        n += extra
+        t = [r.choice((0.5, 1.0, 2.0, 3.0)) for _ in range(n)]
+        w = [r.choice((0.0, 1.0, 4.0)) for _ in range(n)]
+        a = [r.choice((0.0, 1.0, 2.0)) for _ in range(n)]
+        D = r.randrange(1, 5)
+        got = P.best_stage_graph(n, e, t, w, a, D, 2, r.choice((BIG, 30.0, 12.0)))
+        if got is None:
+            continue
+        plan, ev = got
+        ops = sorted(o for st, _ in plan for o in st)
+        assert ops == list(range(n))                                  # C1: a partition of the operators
+        assert sum(d for _, d in plan) == D and all(d >= 1 for _, d in plan)   # C3
+        stage_of = {o: s for s, (st, _) in enumerate(plan) for o in st}
+        for u, v in e:                                                # C2: an operator edge across stages is a stage edge
+            if stage_of[u] != stage_of[v]:
+                assert (stage_of[u], stage_of[v]) in ev["edges"]
+        assert ev["tps"] == max(sum(t[o] for o in st) / d for st, d in plan)     # no synchronisation cost in this test
+        assert ev["tps"] <= sum(t) + 1e-12                            # never worse than one device running everything
