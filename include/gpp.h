@@ -244,6 +244,34 @@ gpp_status_t gpp_stage_run_schedule(gpp_stage_t *stage, const int32_t *tasks, in
  * stage's in_flight_slots.  Any pointer may be NULL. */
 gpp_status_t gpp_stage_memory(const gpp_stage_t *stage, size_t *slot_bytes, size_t *shared_bytes, size_t *total_bytes);
 
+/* ---- Pipeline stage partitioner (paper section 5, Alg. 1; problem statement of section 3).  HOST-only.
+ * Cuts the operator graph G_C into stages, gives every stage a number of devices and returns the stage graph
+ * whose bottleneck stage has the smallest time per sample among those that fit the memory of their devices
+ * with the in-flight micro-batches their schedules need.  Method as in the paper: series-parallel structure
+ * of G_C, a dynamic programme over it (value: the fewest in-flight samples at the first stages of a
+ * sub-graph, given a bound on every stage's time per sample; in-flight samples by ComputeInFlight), binary
+ * search on the bound until the interval is below eps_rel of its upper end.
+ * Model (what the paper leaves open):
+ *   - default schedule configuration of section 6: 1F1B everywhere, one micro-batch size b;
+ *   - a stage on d devices is data-parallel: time per sample = sum of t / d, plus for d > 1 a ring all-reduce
+ *     of its parameters per mini-batch: 2 (d-1)/d * sum of w * sync_seconds_per_byte / mini_batch;
+ *   - memory of a stage per device = sum of w + in-flight samples / d * sum of a;
+ *   - operators are nodes: operators that fall into several weakly connected parts are composed in PARALLEL,
+ *     a connected set is split in SERIES at every operator all others are ancestors or descendants of, a
+ *     connected set without one is an indivisible block; a stage is a node of that tree or a run of
+ *     consecutive children of one node; every device is used and a stage has at least one.
+ *   t[o] seconds per sample on one device (forward + backward), w[o] parameter and gradient bytes,
+ *   a[o] stashed bytes per sample of operator o                                   HOST, n_ops entries each
+ *   stage_of_op[n_ops]; stage_devices, stage_in_flight (samples): room for n_ops entries, *n_stages written
+ * *n_stages = 0 (status GPP_OK) when no stage graph fits the memory.  *bottleneck: time per sample of the
+ * slowest stage of the result; *dp_states (may be NULL): states the dynamic programme evaluated over all
+ * steps of the binary search.  GPP_ERR_BAD_GRAPH if G_C has a cycle. */
+gpp_status_t gpp_partition(int32_t n_ops, int32_t n_edges, const int32_t *edge_from, const int32_t *edge_to,
+                           const double *t, const double *w, const double *a, int32_t n_devices, int64_t b,
+                           double memory_bytes, double sync_seconds_per_byte, int64_t mini_batch, double eps_rel,
+                           int32_t *stage_of_op, int32_t *n_stages, int32_t *stage_devices, int64_t *stage_in_flight,
+                           double *bottleneck, int64_t *dp_states);
+
 /* ---- Several stages of a stage graph G_S on one GPU (paper section 3: G_S = (V_S, E_S); an edge (S_x, S_y)
  * orders the two stages for every micro-batch, C2; stages without a path between them run concurrently,
  * section 2).  Each stage keeps its own task list (gpp_schedule_tasks for its (i, k)) and its own pair of

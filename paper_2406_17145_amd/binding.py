@@ -52,7 +52,7 @@ EXPORTS = [
     "gpp_stage_embedding_sort_result", "gpp_last_error", "gpp_stage_profile_enable", "gpp_stage_profile_read",
     "gpp_profile_tag_name", "gpp_compute_in_flight", "gpp_assign_schedules", "gpp_schedule_tasks",
     "gpp_stage_run_schedule", "gpp_stage_memory", "gpp_stage_backward_weights", "gpp_stage_info", "gpp_stage_io_info",
-    "gpp_pipeline_workspace_bytes", "gpp_pipeline_create", "gpp_pipeline_run", "gpp_pipeline_destroy",
+    "gpp_partition", "gpp_pipeline_workspace_bytes", "gpp_pipeline_create", "gpp_pipeline_run", "gpp_pipeline_destroy",
 ]
 GPP_PROFILE_TAGS = 32
 
@@ -130,6 +130,10 @@ def load():
     lib.gpp_pipeline_run.restype = i32
     lib.gpp_pipeline_run.argtypes = [vp, i64, C.POINTER(C.POINTER(MicrobatchIO)), C.POINTER(vp), C.POINTER(vp)]
     lib.gpp_pipeline_destroy.restype, lib.gpp_pipeline_destroy.argtypes = i32, [vp]
+    dp = C.POINTER(C.c_double)
+    lib.gpp_partition.restype = i32
+    lib.gpp_partition.argtypes = [i32, i32, C.POINTER(i32), C.POINTER(i32), dp, dp, dp, i32, i64, C.c_double, C.c_double, i64,
+                                  C.c_double, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32), C.POINTER(i64), dp, C.POINTER(i64)]
     _lib = lib
     return lib
 
@@ -335,6 +339,25 @@ def gpp_stage_io_info(handle, is_output, index):
     r, f, d, g = C.c_int64(), C.c_int64(), C.c_int32(), C.c_int32()
     _check(load().gpp_stage_io_info(handle, 1 if is_output else 0, index, C.byref(r), C.byref(f), C.byref(d), C.byref(g)))
     return r.value, f.value, d.value, bool(g.value)
+
+
+def gpp_partition(n_ops, edges, t, w, a, n_devices, b, memory_bytes, sync_seconds_per_byte=0.0, mini_batch=1, eps_rel=1e-9):
+    """edges: (u, v) operator pairs.  Returns None when nothing fits, else a dict: stage_of_op, devices and
+    in_flight (samples) per stage, bottleneck (seconds per sample), dp_states."""
+    ne = len(edges)
+    ef = (C.c_int32 * max(1, ne))(*[e[0] for e in edges])
+    et = (C.c_int32 * max(1, ne))(*[e[1] for e in edges])
+    dbl = C.c_double * n_ops
+    stage_of, ns = (C.c_int32 * n_ops)(), C.c_int32()
+    dev, inf = (C.c_int32 * n_ops)(), (C.c_int64 * n_ops)()
+    tps, states = C.c_double(), C.c_int64()
+    _check(load().gpp_partition(n_ops, ne, ef, et, dbl(*t), dbl(*w), dbl(*a), n_devices, b, memory_bytes,
+                                sync_seconds_per_byte, mini_batch, eps_rel, stage_of, C.byref(ns), dev, inf,
+                                C.byref(tps), C.byref(states)))
+    if ns.value == 0:
+        return None
+    return dict(stage_of_op=list(stage_of), devices=list(dev)[:ns.value], in_flight=list(inf)[:ns.value],
+                bottleneck=tps.value, dp_states=states.value)
 
 
 def gpp_stage_memory(handle):

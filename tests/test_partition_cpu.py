@@ -1,0 +1,125 @@
+"""The library's partitioner (C ABI, host only) against the partitioner oracle: the oracle enumerates every stage
+graph and evaluates it from the definitions; the library must find a stage graph with the same bottleneck time per
+sample, and what it returns must itself evaluate (by the oracle's definitions) to what it reports."""
+import random
+
+import pytest
+
+from oracle import partition_oracle as P
+from paper_2406_17145_amd import binding as B
+
+BIG = 1e30
+
+
+def _model(r):
+    """Branches of chains into a merge operator, a tail behind it, sometimes a skip edge: shaped like the paper's models."""
+    n_br, depth = r.randrange(1, 4), r.randrange(1, 3)
+    edges, op, lasts, firsts = [], 0, [], []
+    for _ in range(n_br):
+        firsts.append(op)
+        for k in range(depth):
+            if k:
+                edges.append((op - 1, op))
+            op += 1
+        lasts.append(op - 1)
+    for l in lasts:
+        edges.append((l, op))
+    merge = op
+    op += 1
+    for _ in range(r.randrange(0, 3)):
+        edges.append((op - 1, op))
+        op += 1
+    if op - 1 > merge + 1 and r.random() < 0.4:
+        edges.append((merge, op - 1))            # a residual connection over the tail
+    if r.random() < 0.3:                         # a stem in front of the branches
+        edges += [(op, f) for f in firsts]
+        op += 1
+    return op, edges
+
+
+def _check(n, edges, t, w, a, D, b, mem, sync, mini):
+    want = P.best_stage_graph(n, edges, t, w, a, D, b, mem, sync, mini)
+    got = B.gpp_partition(n, edges, t, w, a, D, b, mem, sync, mini, 1e-9)
+    assert (want is None) == (got is None), (n, edges, t, w, a, D, mem)
+    if want is None:
+        return None
+    _, ev = want
+    assert got["bottleneck"] == pytest.approx(ev["tps"], rel=1e-7), (n, edges, t, w, a, D, mem, got, ev)
+    # the library's own stage graph, evaluated by the definitions
+    ns = len(got["devices"])
+    plan = tuple((frozenset(o for o in range(n) if got["stage_of_op"][o] == s), got["devices"][s]) for s in range(ns))
+    assert all(st for st, _ in plan) and sum(d for _, d in plan) == D and all(d >= 1 for _, d in plan)   # C1, C3
+    mine = P.evaluate(plan, n, edges, t, w, a, b, mem, sync, mini)
+    assert mine is not None, "the returned stage graph has a cycle or does not fit the memory"
+    assert mine["tps"] == pytest.approx(got["bottleneck"], rel=1e-12)
+    assert mine["in_flight"] == got["in_flight"]          # incremental bookkeeping == reverse traversal of the stage graph
+    assert mine["source_in_flight"] == ev["source_in_flight"]
+    return got
+
+
+def test_partitioner_matches_oracle_on_random_branchy_models():
+    r = random.Random(21)
+    for trial in range(250):
+        n, edges = _model(r)
+        t = [r.choice((0.5, 1.0, 2.0, 3.0, 7.0)) for _ in range(n)]
+        w = [r.choice((0.0, 1.0, 4.0)) for _ in range(n)]
+        a = [r.choice((0.0, 1.0, 2.0)) for _ in range(n)]
+        _check(n, edges, t, w, a, r.randrange(1, 6), r.choice((1, 2, 4)), r.choice((BIG, 40.0, 20.0, 9.0)),
+               r.choice((0.0, 0.05, 0.5)), r.choice((1, 8)))
+
+
+def test_partitioner_matches_oracle_on_random_dags_with_indivisible_blocks():
+    r = random.Random(22)
+    for trial in range(150):
+        n = r.randrange(1, 9)
+        edges = [(u, v) for u in range(n) for v in range(u + 1, n) if r.random() < 0.3]
+        t = [r.choice((1.0, 2.0, 5.0)) for _ in range(n)]
+        w = [r.choice((0.0, 2.0)) for _ in range(n)]
+        a = [r.choice((0.0, 1.0)) for _ in range(n)]
+        _check(n, edges, t, w, a, r.randrange(1, 5), 2, r.choice((BIG, 15.0)), r.choice((0.0, 0.1)), 4)
+
+
+def test_partitioner_on_the_papers_examples():
+    # a sequential pipeline of five equal stages: (n + 1 - x) b samples in flight at stage x (section 6)
+    got = B.gpp_partition(5, [(i, i + 1) for i in range(4)], [1.0] * 5, [1.0] * 5, [1.0] * 5, 5, 2, BIG, 0.01, 8)
+    assert got["stage_of_op"] == [0, 1, 2, 3, 4] and got["in_flight"] == [10, 8, 6, 4, 2] and got["bottleneck"] == 1.0
+    # three independent branches in front of a merge operator on four devices: parallel stages, depth 2 (section 2)
+    got = B.gpp_partition(4, [(0, 3), (1, 3), (2, 3)], [1.0] * 4, [1.0] * 4, [1.0] * 4, 4, 4, BIG, 0.01, 8)
+    assert sorted(got["stage_of_op"]) == [0, 1, 2, 3] and sorted(got["in_flight"]) == [4, 8, 8, 8]
+
+
+def test_partitioner_errors_and_no_strategy():
+    assert B.gpp_partition(2, [(0, 1)], [1.0, 1.0], [8.0, 8.0], [1.0, 1.0], 2, 1, memory_bytes=4.0) is None
+    with pytest.raises(B.GppError) as e:
+        B.gpp_partition(2, [(0, 1), (1, 0)], [1.0, 1.0], [0.0, 0.0], [0.0, 0.0], 2, 1, BIG)
+    assert e.value.status == B.GPP_ERR_BAD_GRAPH
+    for bad in [dict(n_devices=0), dict(b=0), dict(memory_bytes=0.0), dict(eps_rel=0.0), dict(mini_batch=0)]:
+        kw = dict(n_ops=2, edges=[(0, 1)], t=[1.0, 1.0], w=[0.0, 0.0], a=[0.0, 0.0], n_devices=2, b=1, memory_bytes=BIG)
+        kw.update(bad)
+        with pytest.raises(B.GppError) as e:
+            B.gpp_partition(**kw)
+        assert e.value.status == B.GPP_ERR_INVALID_ARG
+    with pytest.raises(B.GppError):
+        B.gpp_partition(2, [(0, 5)], [1.0, 1.0], [0.0, 0.0], [0.0, 0.0], 2, 1, BIG)
+    with pytest.raises(B.GppError):
+        B.gpp_partition(2, [(0, 1)], [1.0, -1.0], [0.0, 0.0], [0.0, 0.0], 2, 1, BIG)
+
+
+def test_dp_states_stay_far_below_the_number_of_stage_graphs():
+    # eight branches of three operators and a tail: the enumeration would be astronomically large, the dynamic
+    # programme visits a few thousand states per bound (section 5: complexity linear in the number of sub-graphs)
+    edges, op, lasts = [], 0, []
+    for _ in range(8):
+        for k in range(3):
+            if k:
+                edges.append((op - 1, op))
+            op += 1
+        lasts.append(op - 1)
+    edges += [(l, op) for l in lasts]
+    op += 1
+    for _ in range(4):
+        edges.append((op - 1, op))
+        op += 1
+    got = B.gpp_partition(op, edges, [1.0 + (i % 3) for i in range(op)], [1.0] * op, [1.0] * op, 16, 4, BIG, 0.01, 64, 1e-6)
+    assert got is not None and sum(got["devices"]) == 16
+    assert got["dp_states"] < 2_000_000
