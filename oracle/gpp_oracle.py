@@ -218,6 +218,38 @@ def embedding_bag_bwd(dout, saved, g):
     return (sorted_pos, unique_rows, seg_offsets)
 
 
+def embedding_bag_concat_fwd(indices, offsets, p, op):
+    """Embedding bag whose rows are CONCATENATED (paper appendix, DLRM: the embeddings of a bag are
+    concatenated): out[s, j*d:(j+1)*d] = table[indices[offsets[s] + j], :] for the j-th index of bag s;
+    slots beyond the bag's length (bags may be shorter than bag_size) are zero."""
+    table = p["table"]
+    d, cap = table.shape[1], op["bag_size"]
+    idx = indices.reshape(-1)
+    off = offsets.reshape(-1).astype(np.int64)
+    n_bags = off.shape[0] - 1
+    n_used = int(off[-1])
+    if n_used and (idx[:n_used].min() < 0 or idx[:n_used].max() >= table.shape[0]):
+        raise IndexError("embedding index out of range")
+    bag = bag_of_position(off, n_used)
+    slot = np.arange(n_used) - off[bag]
+    if n_used and slot.max() >= cap:
+        raise IndexError("a bag is longer than bag_size")
+    out = np.zeros((n_bags, cap, d))
+    out[bag, slot] = table[idx[:n_used]]
+    return out.reshape(n_bags, cap * d), (idx[:n_used].copy(), bag, slot)
+
+
+def embedding_bag_concat_bwd(dout, saved, g):
+    """dTable[r,:] += sum over the positions p that hold row r, in sorted (= ascending original
+    position) order, of dout[bag(p), slot(p)*d:(slot(p)+1)*d]."""
+    idx_used, bag, slot = saved
+    d = g["table"].shape[1]
+    sorted_pos, unique_rows, seg_offsets = embedding_sort(idx_used)
+    pieces = dout.reshape(dout.shape[0], -1, d)[bag[sorted_pos], slot[sorted_pos]]
+    np.add.at(g["table"], idx_used[sorted_pos], pieces)
+    return (sorted_pos, unique_rows, seg_offsets)
+
+
 def interact_terms(n_vec):
     """Strictly-lower-triangular pairs (i, j), i > j, enumerated row by row."""
     return [(i, j) for i in range(n_vec) for j in range(i)]
@@ -381,6 +413,8 @@ class OracleStage:
                 val[i] = np.concatenate(src, axis=1)
             elif k == "embedding_bag_sum":
                 val[i], st.saved[i] = embedding_bag_fwd(src[0], src[1], self.params[i], op)
+            elif k == "embedding_bag_concat":
+                val[i], st.saved[i] = embedding_bag_concat_fwd(src[0], src[1], self.params[i], op)
             elif k == "dot_interact":
                 val[i], st.saved[i] = dot_interact_fwd(src[0], op)
             elif k.startswith("loss"):
@@ -436,6 +470,9 @@ class OracleStage:
                     c += w
             elif k == "embedding_bag_sum":
                 st.embedding_artefacts[i] = embedding_bag_bwd(dy, st.saved[i], self.grads[i])
+                continue
+            elif k == "embedding_bag_concat":
+                st.embedding_artefacts[i] = embedding_bag_concat_bwd(dy, st.saved[i], self.grads[i])
                 continue
             elif k == "dot_interact":
                 dxs = dot_interact_bwd(dy, st.saved[i], op)

@@ -458,6 +458,45 @@ def test_embedding_backward_matches_one_hot_brute_force(seed):
     assert np.array_equal(seg_offsets, np.concatenate([[0], np.cumsum(counts)]))
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_concatenated_embedding_bag_matches_loops_and_one_hot_brute_force(seed):
+    # the paper's DLRM concatenates the rows of a bag: slot j of sample s holds the row of its j-th index
+    rng = np.random.default_rng(seed)
+    rows, dim, nb, cap = 11, 3, 6, 4
+    lens = rng.integers(0, cap + 1, nb)             # empty, partial and full bags
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    idx = rng.integers(0, rows, nb * cap).astype(np.int32)
+    table = rng.standard_normal((rows, dim))
+    out, saved = O.embedding_bag_concat_fwd(idx, off, {"table": table}, {"bag_size": cap})
+    ref = np.zeros((nb, cap * dim))
+    for s in range(nb):
+        for j in range(off[s], off[s + 1]):
+            ref[s, (j - off[s]) * dim:(j - off[s] + 1) * dim] = table[idx[j]]
+    assert np.array_equal(out, ref)
+    # summing the slots of the concatenated bag gives the sum-pooled bag
+    pooled, _ = O.embedding_bag_fwd(idx, off, {"table": table}, {})
+    assert np.allclose(out.reshape(nb, cap, dim).sum(axis=1), pooled, atol=1e-15)
+    dout = rng.standard_normal((nb, cap * dim))
+    g = {"table": np.zeros_like(table)}
+    sorted_pos, unique_rows, seg_offsets = O.embedding_bag_concat_bwd(dout, saved, g)
+    n = int(off[-1])
+    onehot = np.zeros((n, rows))
+    onehot[np.arange(n), idx[:n]] = 1.0
+    piece = np.stack([dout[s, (j - off[s]) * dim:(j - off[s] + 1) * dim] for s in range(nb) for j in range(off[s], off[s + 1])]) \
+        if n else np.zeros((0, dim))
+    assert np.allclose(g["table"], onehot.T @ piece, atol=1e-14)
+    # the gradient is linear in dout: <dTable, dT> == <dout, d out / d table [dT]> for a random direction
+    dT = rng.standard_normal(table.shape)
+    out_dir, _ = O.embedding_bag_concat_fwd(idx, off, {"table": dT}, {"bag_size": cap})
+    assert np.isclose((g["table"] * dT).sum(), (dout * out_dir).sum(), atol=1e-12)
+    assert [p[1] for p in sorted((int(idx[j]), j) for j in range(n))] == sorted_pos.tolist()
+
+
+def test_concatenated_embedding_bag_rejects_a_bag_longer_than_its_capacity():
+    with pytest.raises(IndexError):
+        O.embedding_bag_concat_fwd(np.zeros(6, np.int32), np.array([0, 3], np.int32), {"table": np.zeros((4, 2))}, {"bag_size": 2})
+
+
 def test_embedding_rejects_out_of_range_index():
     with pytest.raises(IndexError):
         O.embedding_bag_fwd(np.array([0, 9], np.int32), np.array([0, 2], np.int32),
