@@ -82,7 +82,11 @@ typedef enum {
                                <v_i,v_j> for i>j in row-major order (1,0),(2,0),(2,1),...] */
   GPP_OP_LOSS_MSE = 9,      /* in = (prediction, target f32); L = loss_scale * sum (y-t)^2 */
   GPP_OP_LOSS_CE = 10,      /* in = (logits, labels i32 [b,1]); L = -loss_scale * sum log softmax(y)[label] */
-  GPP_OP_LOSS_BCE_LOGITS = 11 /* in = (logits, targets f32); L = loss_scale * sum softplus(y) - t*y */
+  GPP_OP_LOSS_BCE_LOGITS = 11, /* in = (logits, targets f32); L = loss_scale * sum softplus(y) - t*y */
+  GPP_OP_EMBEDDING_BAG_CONCAT = 12 /* producers as EMBEDDING_BAG_SUM; the rows of a bag are concatenated (the
+                                   paper's DLRM, appendix "DNN Model Configurations"): in_features = row width d,
+                                   out_features = bag_size * d (a multiple of 64),
+                                   out[s, j*d:(j+1)*d] = table[idx[off[s] + j], :], zero for j >= the bag's length */
 } gpp_op_kind_t;
 
 typedef enum { GPP_ACT_NONE = 0, GPP_ACT_RELU = 1, GPP_ACT_GELU_ERF = 2 } gpp_act_t;
@@ -110,7 +114,8 @@ typedef struct {
   int32_t dtype;         /* gpp_dtype_t of the output tensor as stored */
   int32_t param_dtype;   /* LINEAR: dtype of W (must equal the producer's dtype); others ignored */
   void *param[2];        /* DEVICE. LINEAR: W, bias(f32) | LAYERNORM: gamma(f32), beta(f32) |
-                            EMBEDDING: table f32 [num_rows, gpp_ld(out_features)] */
+                            EMBEDDING_BAG_SUM: table f32 [num_rows, gpp_ld(out_features)];
+                            EMBEDDING_BAG_CONCAT: table f32 [num_rows, gpp_ld(in_features)] */
   void *grad[2];         /* DEVICE, f32 accumulators with the layout of param[] (W's gradient is f32
                             [out_features, gpp_ld(in_features)]) */
 } gpp_op_desc_t;

@@ -23,7 +23,8 @@ STATUS_NAMES = ["GPP_OK", "GPP_ERR_INVALID_ARG", "GPP_ERR_BAD_GRAPH", "GPP_ERR_S
  GPP_ERR_INDEX, GPP_ERR_DEVICE) = range(1, 9)
 DTYPES = {"f32": 0, "bf16": 1, "i32": 2}
 KINDS = {"input": 0, "linear": 1, "layernorm": 2, "attention": 3, "add": 4, "meanpool": 5, "concat": 6,
-         "embedding_bag_sum": 7, "dot_interact": 8, "loss_mse": 9, "loss_ce": 10, "loss_bce": 11}
+         "embedding_bag_sum": 7, "dot_interact": 8, "loss_mse": 9, "loss_ce": 10, "loss_bce": 11,
+         "embedding_bag_concat": 12}
 ACTS = {"none": 0, "relu": 1, "gelu": 2}
 FLAG_FORCE_GENERIC_GEMM = 1
 FLAG_SPLIT_K = 2
@@ -389,7 +390,8 @@ class Stage:
         self.p_t, self.g_t, pp, gp = {}, {}, {}, {}
         for i, p in params.items():
             op = ops[i]
-            names = {"linear": ["W", "b"], "layernorm": ["gamma", "beta"], "embedding_bag_sum": ["table"]}[op["kind"]]
+            names = {"linear": ["W", "b"], "layernorm": ["gamma", "beta"], "embedding_bag_sum": ["table"],
+                     "embedding_bag_concat": ["table"]}[op["kind"]]
             self.p_t[i], self.g_t[i] = {}, {}
             pp[i], gp[i] = [None, None], [None, None]
             for k, nm in enumerate(names):
@@ -425,7 +427,7 @@ class Stage:
         op = self.ops[op_id]
         if op["kind"] == "input":
             return self.b * op.get("seq_len", 1) + op.get("rows_extra", 0)
-        if op["kind"] == "meanpool" or op["kind"] == "embedding_bag_sum":
+        if op["kind"] in ("meanpool", "embedding_bag_sum", "embedding_bag_concat"):
             return self.b
         return self._rows(op["inputs"][0])
 
@@ -522,7 +524,8 @@ class Stage:
             for nm, t in g.items():
                 a = t.cpu().numpy()
                 if a.ndim == 2:
-                    ref_cols = {"W": self.ops[i].get("in_features"), "table": self.ops[i].get("out_features")}[nm]
+                    ref_cols = {"W": self.ops[i].get("in_features"), "table": self.ops[i].get("in_features") if self.ops[i]["kind"] == "embedding_bag_concat"
+                                else self.ops[i].get("out_features")}[nm]
                     a = a[:, :ref_cols]
                 out[i][nm] = a
         return out

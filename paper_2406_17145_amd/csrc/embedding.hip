@@ -61,6 +61,67 @@ __device__ __forceinline__ void store4(void *base, int dtype, int64_t idx, float
 }
 
 // ------------------------------------------------------------------ forward
+// Concatenated bag (one wave per bag): row j of the bag is copied to columns [j * dim, (j + 1) * dim) of
+// the sample's output, slots beyond the bag's length are cleared.  VEC: dim is a multiple of 4 and the
+// buffers are 16-byte aligned; dim / 4 lanes then move one row with one 16-byte load each, 64 / (dim / 4)
+// rows per load instruction, CONCAT_UNROLL instructions requested before the first store.
+constexpr int CONCAT_UNROLL = 8;
+template <bool VEC>
+__device__ __forceinline__ void emb_fwd_concat_body(const EmbProb &p, int bag, StageFlags *flags) {
+  const int lane = threadIdx.x & 63;
+  int lo = p.offsets[bag], hi = p.offsets[bag + 1];
+  bool bad = lo < 0 || hi < lo || hi > p.capacity || hi - lo > p.bag_size;
+  lo = max(0, min(lo, p.capacity));
+  hi = max(lo, min(min(hi, p.capacity), lo + p.bag_size));
+  const int len = hi - lo;
+  const int64_t out0 = (int64_t)bag * p.ld_out;
+  const int lpr = VEC ? max(1, p.dim >> 2) : 64, rpi = VEC ? max(1, 64 / lpr) : 1;
+  const int sub = lane / lpr, c4 = (lane % lpr) * 4;
+  for (int base = 0; base < len; base += 64) {
+    const int cnt = min(64, len - base);
+    int my = -1;
+    if (lane < cnt) {
+      my = p.indices[lo + base + lane];
+      p.bag_of[lo + base + lane] = bag;
+      if (my < 0 || my >= p.num_rows) {
+        bad = true;
+        my = -1;
+      }
+    }
+    if (VEC) {
+      for (int j0 = 0; j0 < cnt; j0 += rpi * CONCAT_UNROLL) {
+        float4 v[CONCAT_UNROLL];
+#pragma unroll
+        for (int u = 0; u < CONCAT_UNROLL; ++u) {
+          const int j = j0 + u * rpi + sub;
+          const int r = __shfl(my, min(j, 63), 64);
+          v[u] = *(const float4 *)(p.table + (int64_t)max(r, 0) * p.ld_table + (sub < rpi ? c4 : 0));
+          if (r < 0) v[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);     // an index out of range leaves a zero row
+        }
+#pragma unroll
+        for (int u = 0; u < CONCAT_UNROLL; ++u) {
+          const int j = j0 + u * rpi + sub;
+          if (j < cnt && sub < rpi) store4(p.out, p.out_dtype, out0 + (int64_t)(base + j) * p.dim + c4, v[u]);
+        }
+      }
+    } else {
+      for (int j = 0; j < cnt; ++j) {
+        const int r = __shfl(my, j, 64);
+        for (int c = lane; c < p.dim; c += 64)
+          store_from_f32(p.out, p.out_dtype, out0 + (int64_t)(base + j) * p.dim + c, r >= 0 ? p.table[(int64_t)r * p.ld_table + c] : 0.0f);
+      }
+    }
+  }
+  // slots the bag does not fill
+  const int tail0 = len * p.dim, tail1 = p.bag_size * p.dim;
+  if (VEC) {
+    for (int c = tail0 + 4 * lane; c < tail1; c += 256) store4(p.out, p.out_dtype, out0 + c, make_float4(0.0f, 0.0f, 0.0f, 0.0f));
+  } else {
+    for (int c = tail0 + lane; c < tail1; c += 64) store_from_f32(p.out, p.out_dtype, out0 + c, 0.0f);
+  }
+  if (__any(bad) && lane == 0) flags->index_error = 1;
+}
+
 // generic: one wave per bag, a lane per column (any dimension up to 256)
 __global__ __launch_bounds__(256) void k_emb_fwd(const EmbProb *__restrict__ probs, int n, StageFlags *flags) {
   const int pi = find_prob(probs, n, blockIdx.x);
@@ -68,6 +129,7 @@ __global__ __launch_bounds__(256) void k_emb_fwd(const EmbProb *__restrict__ pro
   const int lane = threadIdx.x & 63;
   const int bag = (blockIdx.x - p.blk_begin) * 4 + (threadIdx.x >> 6);
   if (bag >= p.n_bags) return;
+  if (p.concat) return emb_fwd_concat_body<false>(p, bag, flags);
   int lo = p.offsets[bag], hi = p.offsets[bag + 1];
   bool bad = lo < 0 || hi < lo || hi > p.capacity;
   lo = max(0, min(lo, p.capacity));
@@ -132,6 +194,7 @@ __global__ __launch_bounds__(256) void k_emb_fwd_vec(const EmbProb *__restrict__
   const int lane = threadIdx.x & 63;
   const int bag = blk * 4 + (threadIdx.x >> 6);
   if (bag >= p.n_bags) return;
+  if (p.concat) return emb_fwd_concat_body<true>(p, bag, flags);
   int lo = p.offsets[bag], hi = p.offsets[bag + 1];
   bool bad = lo < 0 || hi < lo || hi > p.capacity;
   lo = max(0, min(lo, p.capacity));
@@ -319,7 +382,10 @@ __global__ __launch_bounds__(256) void k_sort_scatter(const EmbProb *__restrict_
     for (int r = 0; r < SORT_ROUNDS; ++r) {
       const int row = p.indices[pos[r]];
       const int b = p.bag_of[pos[r]];
-      bag[r] = (row >= 0 && row < p.num_rows) ? b : -1;
+      // what the sums gather by: the bag, or, for concatenated bags, the slot of the position in the
+      // gradient seen as [bags * bag_size, dim]
+      const int piece = p.concat ? b * p.bag_size + (pos[r] - p.offsets[b]) : b;
+      bag[r] = (row >= 0 && row < p.num_rows) ? piece : -1;
     }
   }
   for (int d = threadIdx.x; d < 4 * RADIX; d += 256) (&off[0][0])[d] = 0;

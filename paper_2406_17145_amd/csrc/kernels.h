@@ -129,6 +129,11 @@ struct EmbProb {
   int32_t out_dtype;
   int32_t sort_blocks, passes;
   int32_t blk_begin;
+  // concat != 0: the rows of a bag are concatenated instead of summed.  Forward: row j of bag s goes to
+  // out[s, j * dim ..]; backward: `out` is the gradient seen as [n_bags * bag_size, dim] (ld_out = dim) and
+  // sbag holds s * bag_size + j, so the segment sums read one piece per position exactly as they read one
+  // pooled row per position when summing
+  int32_t concat, bag_size;
 };
 
 // ---- pairwise-dot interaction --------------------------------------------------

@@ -41,7 +41,7 @@ gpp_status_t Plan::analyse(const gpp_stage_desc_t *desc) {
   for (int i = 0; i < n; ++i) {
     Node &nd = nodes[i];
     nd.d = desc->ops[i];
-    if (nd.d.kind < GPP_OP_INPUT || nd.d.kind > GPP_OP_LOSS_BCE_LOGITS) FAIL(GPP_ERR_INVALID_ARG, "unknown operator kind");
+    if (nd.d.kind < GPP_OP_INPUT || nd.d.kind > GPP_OP_EMBEDDING_BAG_CONCAT) FAIL(GPP_ERR_INVALID_ARG, "unknown operator kind");
     if (nd.d.n_in < 0 || nd.d.n_in > 4096 || (nd.d.n_in > 0 && !nd.d.in)) FAIL(GPP_ERR_INVALID_ARG, "bad producer list");
     for (int k = 0; k < nd.d.n_in; ++k) {
       int p = nd.d.in[k];
@@ -61,7 +61,7 @@ gpp_status_t Plan::analyse(const gpp_stage_desc_t *desc) {
       case GPP_OP_INPUT: want = 0; break;
       case GPP_OP_LINEAR: case GPP_OP_LAYERNORM: case GPP_OP_ATTENTION: case GPP_OP_MEANPOOL_SEQ:
       case GPP_OP_DOT_INTERACT: want = 1; break;
-      case GPP_OP_ADD: case GPP_OP_EMBEDDING_BAG_SUM: case GPP_OP_LOSS_MSE: case GPP_OP_LOSS_CE:
+      case GPP_OP_ADD: case GPP_OP_EMBEDDING_BAG_SUM: case GPP_OP_EMBEDDING_BAG_CONCAT: case GPP_OP_LOSS_MSE: case GPP_OP_LOSS_CE:
       case GPP_OP_LOSS_BCE_LOGITS: want = 2; break;
       default: break;
     }
@@ -95,7 +95,7 @@ gpp_status_t Plan::analyse(const gpp_stage_desc_t *desc) {
     nd.level = 0;
     for (int p : nd.in) nd.level = std::max(nd.level, nodes[p].level + 1);
     max_level = std::max(max_level, nd.level);
-    nd.is_loss = d.kind >= GPP_OP_LOSS_MSE;
+    nd.is_loss = d.kind >= GPP_OP_LOSS_MSE && d.kind <= GPP_OP_LOSS_BCE_LOGITS;
     if (!nd.is_loss && (d.out_features <= 0 || d.out_features > (1ll << 31) - 64)) FAIL(GPP_ERR_SHAPE, "out_features out of range");
     if (d.dtype < GPP_F32 || d.dtype > GPP_I32) FAIL(GPP_ERR_INVALID_ARG, "bad dtype");
     for (int p : nd.in)
@@ -154,13 +154,19 @@ gpp_status_t Plan::analyse(const gpp_stage_desc_t *desc) {
         break;
       }
       case GPP_OP_EMBEDDING_BAG_SUM:
+      case GPP_OP_EMBEDDING_BAG_CONCAT:
         nd.rows = micro_batch;
+        if (d.kind == GPP_OP_EMBEDDING_BAG_CONCAT) {
+          if (d.in_features <= 0 || d.in_features > 256) FAIL(GPP_ERR_UNSUPPORTED, "embedding bag: row width must be 1..256");
+          if (d.out_features != d.bag_size * d.in_features) FAIL(GPP_ERR_SHAPE, "concatenated embedding bag: out_features must be bag_size * in_features");
+          if (d.out_features % 64) FAIL(GPP_ERR_UNSUPPORTED, "concatenated embedding bag: bag_size * in_features must be a multiple of 64");
+        }
         if (in(0).d.kind != GPP_OP_INPUT || in(1).d.kind != GPP_OP_INPUT || in(0).d.dtype != GPP_I32 || in(1).d.dtype != GPP_I32)
           FAIL(GPP_ERR_BAD_GRAPH, "embedding bag: producers must be i32 inputs (indices, offsets)");
         if (d.bag_size <= 0 || in(0).feat != d.bag_size || in(0).rows != micro_batch) FAIL(GPP_ERR_SHAPE, "embedding bag: indices input must be [micro_batch, bag_size]");
         if (in(1).feat != 1 || in(1).rows != micro_batch + 1) FAIL(GPP_ERR_SHAPE, "embedding bag: offsets input must have micro_batch+1 entries");
         if (d.num_rows <= 0 || d.num_rows > (1ll << 31) - 1) FAIL(GPP_ERR_SHAPE, "embedding bag: num_rows out of range");
-        if (d.out_features > 256) FAIL(GPP_ERR_UNSUPPORTED, "embedding bag: dimension above 256");
+        if (d.kind == GPP_OP_EMBEDDING_BAG_SUM && d.out_features > 256) FAIL(GPP_ERR_UNSUPPORTED, "embedding bag: dimension above 256");
         if (micro_batch * d.bag_size > (1ll << 30)) FAIL(GPP_ERR_UNSUPPORTED, "embedding bag: too many indices");
         if (!is_float(d.dtype)) FAIL(GPP_ERR_UNSUPPORTED, "embedding bag: float output only");
         break;
@@ -212,7 +218,7 @@ gpp_status_t Plan::analyse(const gpp_stage_desc_t *desc) {
     Node &nd = nodes[i];
     const int k = nd.d.kind;
     nd.wants_grad = (k == GPP_OP_INPUT) ? nd.d.requires_grad != 0
-                                        : (k == GPP_OP_LINEAR || k == GPP_OP_LAYERNORM || k == GPP_OP_EMBEDDING_BAG_SUM);
+                                        : (k == GPP_OP_LINEAR || k == GPP_OP_LAYERNORM || k == GPP_OP_EMBEDDING_BAG_SUM || k == GPP_OP_EMBEDDING_BAG_CONCAT);
     if (k != GPP_OP_INPUT && !nd.is_loss)
       for (int p : nd.in) nd.wants_grad = nd.wants_grad || nodes[p].wants_grad;
     if (nd.is_loss) nd.wants_grad = false;
@@ -248,7 +254,8 @@ gpp_status_t Plan::analyse(const gpp_stage_desc_t *desc) {
         m.val_parent = i;
         m.val_col = col;
       }
-      if (sole && m.gdtype == c.gdtype && m.wants_grad) {
+      // (a concatenated embedding bag reads its gradient as a dense [b * bag_size, d] matrix: own buffer)
+      if (sole && m.gdtype == c.gdtype && m.wants_grad && m.d.kind != GPP_OP_EMBEDDING_BAG_CONCAT) {
         m.gout_parent = i;
         m.gout_col = col;
       }
@@ -261,7 +268,8 @@ gpp_status_t Plan::analyse(const gpp_stage_desc_t *desc) {
     for (int p : a.in) {
       Node &m = nodes[p];
       const bool plain = !(m.d.kind == GPP_OP_LINEAR && m.d.act != GPP_ACT_NONE);
-      if (m.users.size() == 1 && plain && m.gdtype == a.gdtype && m.wants_grad && m.d.kind != GPP_OP_INPUT) {
+      if (m.users.size() == 1 && plain && m.gdtype == a.gdtype && m.wants_grad && m.d.kind != GPP_OP_INPUT &&
+          m.d.kind != GPP_OP_EMBEDDING_BAG_CONCAT) {
         m.gout_parent = i;
         m.gout_col = 0;
       }
@@ -326,8 +334,9 @@ gpp_status_t Plan::analyse(const gpp_stage_desc_t *desc) {
       nd.stat0 = alloc(SP_SLOT, 1, micro_batch * d.heads * d.seq_len, DT_F32);    // log-sum-exp
       nd.stat1 = alloc(SP_SHARED, 1, micro_batch * d.heads * d.seq_len, DT_F32);  // rowsum(dO*O)
     }
-    if (d.kind == GPP_OP_EMBEDDING_BAG_SUM) {
+    if (d.kind == GPP_OP_EMBEDDING_BAG_SUM || d.kind == GPP_OP_EMBEDDING_BAG_CONCAT) {
       const int64_t cap = micro_batch * d.bag_size;
+      const int64_t row_width = d.kind == GPP_OP_EMBEDDING_BAG_CONCAT ? d.in_features : nd.feat;
       nd.extra = alloc(SP_SLOT, 1, cap, DT_I32);  // bag id of each position
       int bits = 0;
       while ((1ll << bits) < d.num_rows) ++bits;
@@ -340,7 +349,7 @@ gpp_status_t Plan::analyse(const gpp_stage_desc_t *desc) {
       nd.more.push_back(alloc(SP_SHARED, 1, cap + 1, DT_I32));                // segment offsets
       nd.more.push_back(alloc(SP_SHARED, 1, 4 * emb_log_slots(), DT_I32));    // counts per log slot
       nd.more.push_back(alloc(SP_SHARED, 1, 4 * (int64_t)emb_long_entries((int)cap), DT_I32));       // queued slices of long segments
-      nd.more.push_back(alloc(SP_SHARED, emb_long_entries((int)cap), ld_of(nd.feat), DT_F32));       // their partial rows
+      nd.more.push_back(alloc(SP_SHARED, emb_long_entries((int)cap), ld_of(row_width), DT_F32));     // their partial rows
       nd.more.push_back(alloc(SP_SHARED, 1, cap, DT_I32));                    // bag id of every sorted position
       nd.more.push_back(alloc(SP_SHARED, 1, cap, DT_I32));                    // distinct rows (scalar path, inspection)
       nd.emb_passes = passes;
@@ -905,11 +914,15 @@ void Emitter::forward() {
           }
           break;
         }
-        case GPP_OP_EMBEDDING_BAG_SUM: {
+        case GPP_OP_EMBEDDING_BAG_SUM:
+        case GPP_OP_EMBEDDING_BAG_CONCAT: {
           EmbProb e;
           memset(&e, 0, sizeof(e));
+          e.concat = d.kind == GPP_OP_EMBEDDING_BAG_CONCAT;
+          e.bag_size = (int32_t)d.bag_size;
+          e.dim = (int32_t)(e.concat ? d.in_features : nd.feat);
           e.table = (const float *)d.param[0];
-          e.ld_table = ld_of(nd.feat);
+          e.ld_table = ld_of(e.dim);
           e.indices = (const int32_t *)ptr(N[nd.in[0]].val);
           e.offsets = (const int32_t *)ptr(N[nd.in[1]].val);
           e.out = ptr(nd.val);
@@ -918,7 +931,6 @@ void Emitter::forward() {
           e.bag_of = (int32_t *)ptr(nd.extra);
           e.n_bags = (int32_t)pl.micro_batch;
           e.capacity = (int32_t)(pl.micro_batch * d.bag_size);
-          e.dim = (int32_t)nd.feat;
           e.num_rows = (int32_t)d.num_rows;
           embs.push_back(e);
           break;
@@ -1388,16 +1400,22 @@ void Emitter::backward() {
           pools.push_back(p);
           break;
         }
-        case GPP_OP_EMBEDDING_BAG_SUM: {
+        case GPP_OP_EMBEDDING_BAG_SUM:
+        case GPP_OP_EMBEDDING_BAG_CONCAT: {
           EmbProb e;
           memset(&e, 0, sizeof(e));
+          e.concat = d.kind == GPP_OP_EMBEDDING_BAG_CONCAT;
+          e.bag_size = (int32_t)d.bag_size;
+          e.dim = (int32_t)(e.concat ? d.in_features : nd.feat);
           e.table = (const float *)d.param[0];
           e.dtable = (float *)d.grad[0];
-          e.ld_table = ld_of(nd.feat);
+          e.ld_table = ld_of(e.dim);
           e.indices = (const int32_t *)ptr(N[nd.in[0]].val);
           e.offsets = (const int32_t *)ptr(N[nd.in[1]].val);
           e.out = ptr(nd.gout);
-          e.ld_out = nd.gout.ld;
+          // concatenated bags: bag_size * dim is a multiple of 64, so the gradient rows carry no padding and
+          // the matrix is also [micro_batch * bag_size, dim] with leading dimension dim
+          e.ld_out = e.concat ? e.dim : nd.gout.ld;
           e.out_dtype = nd.gout.dtype;
           e.bag_of = (int32_t *)ptr(nd.extra);
           e.keys_a = (int32_t *)ptr(nd.more[0]);
@@ -1414,7 +1432,6 @@ void Emitter::backward() {
           e.seg_rows = (int32_t *)ptr(nd.more[11]);
           e.n_bags = (int32_t)pl.micro_batch;
           e.capacity = (int32_t)(pl.micro_batch * d.bag_size);
-          e.dim = (int32_t)nd.feat;
           e.num_rows = (int32_t)d.num_rows;
           e.passes = nd.emb_passes;
           e.sort_blocks = nd.emb_sort_blocks;

@@ -146,7 +146,7 @@ gpp_status_t gpp_stage_create(const gpp_stage_desc_t *desc, void *workspace, siz
   for (size_t i = 0; i < pl.nodes.size(); ++i) {
     const gpp_op_desc_t &d = pl.nodes[i].d;
     bool need2 = (d.kind == GPP_OP_LINEAR && d.has_bias) || d.kind == GPP_OP_LAYERNORM;
-    bool need1 = d.kind == GPP_OP_LINEAR || d.kind == GPP_OP_LAYERNORM || d.kind == GPP_OP_EMBEDDING_BAG_SUM;
+    bool need1 = d.kind == GPP_OP_LINEAR || d.kind == GPP_OP_LAYERNORM || d.kind == GPP_OP_EMBEDDING_BAG_SUM || d.kind == GPP_OP_EMBEDDING_BAG_CONCAT;
     if ((need1 && (!d.param[0] || !d.grad[0])) || (need2 && (!d.param[1] || !d.grad[1]))) {
       delete st;
       return fail(GPP_ERR_INVALID_ARG, "operator " + std::to_string(i) + ": parameter or gradient pointer is null");
@@ -570,7 +570,7 @@ gpp_status_t gpp_stage_embedding_sort_result(gpp_stage_t *st, int32_t op, const 
                                              const int32_t **seg_offsets, const int32_t **counts) {
   if (!st) return fail(GPP_ERR_INVALID_ARG, "stage is null");
   Plan &pl = st->plan;
-  if (op < 0 || op >= (int32_t)pl.nodes.size() || pl.nodes[op].d.kind != GPP_OP_EMBEDDING_BAG_SUM)
+  if (op < 0 || op >= (int32_t)pl.nodes.size() || (pl.nodes[op].d.kind != GPP_OP_EMBEDDING_BAG_SUM && pl.nodes[op].d.kind != GPP_OP_EMBEDDING_BAG_CONCAT))
     return fail(GPP_ERR_INVALID_ARG, "op is not an embedding bag");
   const Node &nd = pl.nodes[op];
   if (!st->emb_last_table) return fail(GPP_ERR_ORDER, "no backward pass has run yet");

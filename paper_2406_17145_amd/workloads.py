@@ -21,6 +21,7 @@ Graph vocabulary (one dict per operator, `inputs` are producer op ids):
   meanpool   mean over the seq_len rows of each sample
   concat     feature-wise concatenation
   embedding_bag_sum   inputs (indices, offsets); sums table rows per bag
+  embedding_bag_concat  same inputs; concatenates the rows of a bag (in_features = row width)
   dot_interact        input [b, F*d] viewed as F vectors of d; out = [vec0 | lower-triangle dots]
   loss_mse / loss_ce / loss_bce   inputs (prediction, target)
 
@@ -103,8 +104,9 @@ def _draw_params(ops, rng, table_init=0.01):
         elif k == "layernorm":
             d = op["out_features"]
             params[i] = {"gamma": np.ones(d, np.float32), "beta": np.zeros(d, np.float32)}
-        elif k == "embedding_bag_sum":
-            t = rng.uniform(-table_init, table_init, (op["num_rows"], op["out_features"]))
+        elif k in ("embedding_bag_sum", "embedding_bag_concat"):
+            t = rng.uniform(-table_init, table_init,
+                            (op["num_rows"], op["in_features"] if k == "embedding_bag_concat" else op["out_features"]))
             params[i] = {"table": t.astype(np.float32)}
     return params
 
@@ -327,12 +329,86 @@ def hetero(micro_batch=128, n_micro=1, seed=7, n_branches=8, base_width=256, out
                     2e-2 if dtype == BF16 else 1e-4)
 
 
+# --------------------------------------------------------------------------
+# the paper's own model shapes (appendix "DNN Model Configurations"), as a second set of workloads
+# --------------------------------------------------------------------------
+def paper_mmt(micro_batch=2, n_micro=1, seed=13, **kw):
+    """Four parallel branches of EIGHT transformer layers, sequence length 256, hidden 1024, 16 heads, FFN 4096."""
+    args = dict(n_branches=4, n_layers=8, d_model=1024, heads=16, d_ff=4096, seq_len=256)
+    args.update(kw)
+    wl = mmt(micro_batch=micro_batch, n_micro=n_micro, seed=seed, **args)
+    wl.name = "paper_mmt"
+    return wl
+
+
+def paper_candle(micro_batch=64, n_micro=1, seed=12, n_branches=7, width=4096, depth=4, **kw):
+    """Seven branches of four feed-forward layers, hidden size 4096 (the paper names no input widths: 4096 too)."""
+    wl = candle_uno(micro_batch=micro_batch, n_micro=n_micro, seed=seed, widths=(width,) * n_branches, hidden=width,
+                    depth=depth, **kw)
+    wl.name = "paper_candle"
+    return wl
+
+
+def paper_dlrm(micro_batch=256, n_micro=1, seed=14, n_dense=7, width=4096, depth=4, n_tables=7, num_rows=1_000_000,
+               dim=64, bag=100, top=(4096, 4096, 1), alpha=1.05, pos_rate=0.03, dtype=BF16, ragged=False):
+    """Seven dense branches (a 4096-wide feature through four feed-forward layers of 4096) and seven sparse
+    branches (a table of one million rows of 64, a bag of 100 whose rows are CONCATENATED), all concatenated,
+    then feed-forward layers of 4096 and a logit."""
+    g = _Graph()
+    outs = []
+    for br in range(n_dense):
+        x = g.input(width, dtype, branch=br)
+        for _ in range(depth):
+            x = g.linear(x, width, width, "relu", dtype, branch=br)
+        outs.append(x)
+    idx_ids, off_ids = [], []
+    for t in range(n_tables):
+        idx = g.input(bag, I32, branch=n_dense + t, role="indices")
+        off = g.input(1, I32, branch=n_dense + t, rows_extra=1, role="offsets")
+        idx_ids.append(idx)
+        off_ids.append(off)
+        outs.append(g.add("embedding_bag_concat", (idx, off), in_features=dim, out_features=bag * dim,
+                          num_rows=num_rows, bag_size=bag, dtype=dtype, branch=n_dense + t))
+    k = n_dense * width + n_tables * bag * dim
+    z = g.add("concat", outs, out_features=k, dtype=dtype)
+    for j, w in enumerate(top):
+        last = j == len(top) - 1
+        z = g.linear(z, k, w, "none" if last else "relu", dtype, out_dtype=F32 if last else dtype)
+        k = w
+    lab = g.input(1, F32, role="target")
+    g.add("loss_bce", (z, lab), loss_scale=1.0 / (micro_batch * n_micro))
+    rng = np.random.Generator(np.random.PCG64(seed))
+    params = _draw_params(g.ops, rng)
+    cdf = bounded_zipf_cdf(num_rows, alpha)
+    perms = [rng.permutation(num_rows).astype(np.int32) for _ in range(n_tables)]
+
+    def make_idx(t):
+        def f(r, s):
+            rank = np.minimum(np.searchsorted(cdf, r.random(s), side="left"), num_rows - 1)
+            return perms[t][rank]
+        return f
+
+    def make_off(t):
+        def f(r, s):
+            lens = r.integers(0, bag + 1, micro_batch) if ragged else np.full(micro_batch, bag)
+            return np.concatenate([[0], np.cumsum(lens)]).reshape(s)
+        return f
+    samplers = {x_id: make_idx(t) for t, x_id in enumerate(idx_ids)}
+    samplers.update({o_id: make_off(t) for t, o_id in enumerate(off_ids)})
+    samplers[lab] = lambda r, s: (r.random(s) < pos_rate).astype(np.float32)
+    batches = _draw_batches(g.ops, micro_batch, n_micro, rng, samplers)
+    return Workload("paper_dlrm", g.ops, micro_batch, n_micro, params, batches, 2e-2 if dtype == BF16 else 1e-4)
+
+
 CONFIGS = {
     "tiny_mlp": tiny_mlp,
     "candle_uno": candle_uno,
     "mmt": mmt,
     "dlrm": dlrm,
     "hetero": hetero,
+    "paper_mmt": paper_mmt,
+    "paper_candle": paper_candle,
+    "paper_dlrm": paper_dlrm,
 }
 
 
@@ -368,7 +444,7 @@ def partition(wl: Workload, stage_of: dict, n_stages: int):
     for i, op in enumerate(ops):
         if op["kind"] == "input":
             seq[i] = op.get("seq_len", 1)
-        elif op["kind"] in ("meanpool", "embedding_bag_sum"):
+        elif op["kind"] in ("meanpool", "embedding_bag_sum", "embedding_bag_concat"):
             seq[i] = 1
         elif op["inputs"]:
             seq[i] = seq[op["inputs"][0]]

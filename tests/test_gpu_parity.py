@@ -98,6 +98,23 @@ def test_dlrm_bf16_eleven_tables_ragged_bags():
     both(W.dlrm(micro_batch=130, n_micro=2, n_tables=11, num_rows=2000, bottom=(64, 32, 128), top=(128, 64, 1)))
 
 
+def test_paper_dlrm_concatenated_bags():
+    # the paper's DLRM shape in small: dense branches next to sparse branches whose bags are CONCATENATED
+    # (ragged bags: empty, partial and full; unused slots must come out zero), bf16 and fp32 storage
+    both(W.paper_dlrm(micro_batch=37, n_micro=2, n_dense=2, width=96, depth=2, n_tables=3, num_rows=700, dim=16, bag=8,
+                      top=(64, 1), ragged=True))
+    both(W.paper_dlrm(micro_batch=20, n_micro=2, n_dense=1, width=64, depth=1, n_tables=9, num_rows=3000, dim=64, bag=100,
+                      top=(128, 1)))
+    both(W.paper_dlrm(micro_batch=9, n_micro=2, n_dense=1, width=32, depth=1, n_tables=2, num_rows=300, dim=8, bag=24,
+                      top=(32, 1), ragged=True, dtype="f32"))
+
+
+def test_paper_model_shapes_small():
+    both(W.paper_mmt(micro_batch=1, n_layers=3, d_model=128, heads=2, d_ff=256, seq_len=64, d_head_out=64, n_classes=20,
+                     n_branches=2))
+    both(W.paper_candle(micro_batch=33, n_micro=2, n_branches=7, width=96, depth=4))
+
+
 def test_large_tile_gemm_ragged_edges():
     # many rows AND wide layers: the launches of the hidden layers go to the large-tile kernel
     # (forward, backward-data and backward-weight), with rows, columns and contraction lengths
