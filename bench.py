@@ -39,7 +39,7 @@ def gemm_traffic(wl):
     for i, op in enumerate(wl.ops):
         if op["kind"] == "input":
             rows[i] = b * op.get("seq_len", 1) + op.get("rows_extra", 0)
-        elif op["kind"] in ("meanpool", "embedding_bag_sum"):
+        elif op["kind"] in ("meanpool", "embedding_bag_sum", "embedding_bag_concat"):
             rows[i] = b
         elif op["kind"].startswith("loss"):
             rows[i] = 0
@@ -130,7 +130,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="candle_uno", choices=["tiny_mlp", "candle_uno", "mmt", "dlrm", "hetero"])
+    ap.add_argument("--config", default="candle_uno", choices=["tiny_mlp", "candle_uno", "mmt", "dlrm", "hetero", "paper_mmt", "paper_candle", "paper_dlrm"])
     ap.add_argument("--micro-batch", type=int, default=0, help="override the config's micro-batch size")
     ap.add_argument("--in-flight", type=int, default=0, metavar="M",
                     help="--schedule kfkb: micro-batches the stage may hold (its stash slots; i = M * micro-batch samples); "
