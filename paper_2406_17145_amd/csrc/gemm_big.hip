@@ -24,13 +24,15 @@ constexpr int GB_BK = 64;           // contraction elements per k-step
 constexpr int GB_KST = GB_BK + 8;   // LDS row stride of k-contiguous tiles: 144-byte rows, conflict-free b128 reads
 
 // tile geometry: WGM x WGN waves, each WTM x WTN MFMA tiles of 32 x 32; LDS buffers (1 or 2)
-template <int FORM, int WGM, int WGN, int WTM, int WTN, int BUFS>
+// DIRECT: the operand tiles go from memory straight into LDS (buffer loads with the LDS destination,
+// no staging registers), unpadded and XOR-swizzled instead of padded (see the direct loaders below).
+template <int FORM, int WGM, int WGN, int WTM, int WTN, int BUFS, bool DIRECT = false>
 struct BigCfg {
   static constexpr int NW = WGM * WGN, THREADS = 64 * NW;
   static constexpr int BM = 32 * WTM * WGM, BN = 32 * WTN * WGN;
   static constexpr bool A_TR = FORM == FORM_DW, B_TR = FORM != FORM_FWD;
-  static constexpr int A_ELEMS = A_TR ? GB_BK * (BM + PAD_TR) : BM * GB_KST;
-  static constexpr int B_ELEMS = B_TR ? GB_BK * (BN + PAD_TR) : BN * GB_KST;
+  static constexpr int A_ELEMS = DIRECT ? GB_BK * BM : (A_TR ? GB_BK * (BM + PAD_TR) : BM * GB_KST);
+  static constexpr int B_ELEMS = DIRECT ? GB_BK * BN : (B_TR ? GB_BK * (BN + PAD_TR) : BN * GB_KST);
   static constexpr int LDS_ELEMS = BUFS * (A_ELEMS + B_ELEMS);
   static_assert(LDS_ELEMS * 2 <= 160 * 1024, "tile does not fit the LDS");
 };
@@ -89,6 +91,66 @@ __device__ __forceinline__ bf16x8 big_frag_kmajor(const uint16_t *lds, int row0,
   return *(const bf16x8 *)(lds + (row0 + (l & 31)) * GB_KST + k0 + 8 * (l >> 5));
 }
 
+// ---- direct loads: memory -> LDS without passing through registers.  One load instruction of a wave
+// fills 1 KB of consecutive LDS (lane l writes 16 bytes at 16 l behind the wave-uniform destination), so
+// the layout of a tile in LDS is the order of its 16-byte chunks, and the padding that keeps the operand
+// reads free of bank conflicts in the staged path is replaced by a swizzle: WHICH chunk of memory a lane
+// loads.  The asynchronous copy runs while the previous k-step is multiplied; nothing waits in registers.
+typedef __attribute__((address_space(3))) void lds_void_t;
+// k-contiguous operand, tile [EXT][64]: 128-byte rows, chunk c of row r sits at chunk position
+// c ^ (r % 8): the 8 lanes that read one chunk column of 8 consecutive rows hit 8 different positions
+template <int EXT, int THREADS>
+__device__ __forceinline__ void big_direct_kmajor(__amdgpu_buffer_rsrc_t rs, int64_t ld, int r0, int k0, int k_lim,
+                                                  uint16_t *tile, int tid) {
+  constexpr int NW = THREADS / 64, ROWS_PER_WAVE = EXT / NW, INSTR = ROWS_PER_WAVE / 8;
+  static_assert(EXT % (8 * NW) == 0, "a wave loads whole groups of eight rows");
+  const int wave = tid >> 6, l = tid & 63;
+#pragma unroll
+  for (int q = 0; q < INSTR; ++q) {
+    const int row = wave * ROWS_PER_WAVE + 8 * q + (l >> 3);
+    const int k = k0 + (((l & 7) ^ (row & 7)) << 3);
+    const uint32_t oob = (uint32_t)-(int32_t)(k >= k_lim) & OOB_OFFSET;
+    const uint32_t off = (uint32_t)(((int64_t)(r0 + row) * ld + k) * 2) | oob;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_t *)(tile + (wave * ROWS_PER_WAVE + 8 * q) * GB_BK), 16, off, 0, 0, 0);
+  }
+}
+__device__ __forceinline__ bf16x8 big_direct_frag_kmajor(const uint16_t *tile, int row0, int k0) {
+  const int l = threadIdx.x & 63;
+  const int row = row0 + (l & 31), c = (k0 >> 3) + (l >> 5);
+  return *(const bf16x8 *)(tile + row * GB_BK + ((c ^ (row & 7)) << 3));
+}
+// contraction-major operand, tile [64][EXT]: rows of EXT elements, chunk c of row k sits at chunk position
+// c ^ (2 (k % 4)): a 16-lane block of the transposing read touches 32 bytes in each of four consecutive
+// rows, which the swizzle spreads over the four 32-byte quarters of a 128-byte bank line
+template <int EXT, int THREADS>
+__device__ __forceinline__ void big_direct_tr(__amdgpu_buffer_rsrc_t rs, int64_t ld, int k0, int c0, uint16_t *tile, int tid) {
+  constexpr int CPR = EXT / 8;                         // chunks per row
+  constexpr int NW = THREADS / 64, INSTR = GB_BK * CPR / 64 / NW;
+  static_assert((GB_BK * CPR) % (64 * NW) == 0, "whole load instructions per wave");
+  const int wave = tid >> 6, l = tid & 63;
+#pragma unroll
+  for (int q = 0; q < INSTR; ++q) {
+    const int first = (wave * INSTR + q) * 64;         // first chunk (in LDS order) of this instruction
+    const int row = (first + l) / CPR, pos = (first + l) % CPR;
+    const int col = c0 + ((pos ^ ((row & 3) << 1)) << 3);
+    // the whole address in the vector offset: the descriptor's range check (rows at or beyond the contraction
+    // length read zero) does not cover a scalar offset
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_t *)(tile + first * 8), 16,
+                                             (uint32_t)(((int64_t)(k0 + row) * ld + col) * 2), 0, 0, 0);
+  }
+}
+template <int COLS>
+__device__ __forceinline__ bf16x8 big_direct_frag_tr(const uint16_t *tile, int col0, int k0) {
+  const int l = threadIdx.x & 63;
+  const int blk = l >> 4, q = l & 15;
+  const int row = k0 + 8 * (blk >> 1) + (q >> 2), col = col0 + 16 * (blk & 1) + 4 * (q & 3);
+  const uint16_t *p = tile + row * COLS + ((((col >> 3) ^ ((row & 3) << 1)) << 3) | (col & 7));
+  typedef __attribute__((address_space(3))) s16x4 lds_v4;
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)p);
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(p + 4 * COLS));     // row + 4: same swizzle
+  return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
 // what every tile kernel of this file does first: XCD-aware spreading (consecutive workgroup ids go
 // round-robin over the 8 XCDs; give each XCD one contiguous range of tiles instead, so that
 // neighbours share operand panels in one L2), then (record, tile) from the records' prefix sums
@@ -120,11 +182,12 @@ __device__ __forceinline__ BigTile big_locate(const GemmProb *__restrict__ probs
 // the other -- the weight gradient of a group of backward passes in one pass over the accumulator.
 // Both operands live in the slots at the same offsets: slot g of the group is `grp.stride` bytes times
 // its slot number behind slot 0, whose addresses the record holds.
-template <int FORM, int WGM, int WGN, int WTM, int WTN, int BUFS, int NS, bool GROUP = false>
+template <int FORM, int WGM, int WGN, int WTM, int WTN, int BUFS, int NS, bool GROUP = false, bool DIRECT = false>
 __device__ __forceinline__ void big_tile_body(const GemmProb &p, int m0, int n0, uint16_t *lds, int accumulate_dw,
                                               const ExtPtrs &ext, const SlotGroup grp = SlotGroup()) {
   static_assert(!GROUP || FORM == FORM_DW, "only the weight gradient contracts over a group of slots");
-  typedef BigCfg<FORM, WGM, WGN, WTM, WTN, BUFS> C;
+  static_assert(!DIRECT || BUFS == 2, "direct loads fill the other LDS buffer while one is multiplied");
+  typedef BigCfg<FORM, WGM, WGN, WTM, WTN, BUFS, DIRECT> C;
   constexpr int BM = C::BM, BN = C::BN, THREADS = C::THREADS;
   constexpr bool A_TR = C::A_TR, B_TR = C::B_TR;
   static_assert(BUFS == 1 || NS % 2 == 0, "the LDS double buffer alternates with the ring slot");
@@ -149,8 +212,8 @@ __device__ __forceinline__ void big_tile_body(const GemmProb &p, int m0, int n0,
 
   typedef BigRegs<BM, THREADS> RegsA;
   typedef BigRegs<BN, THREADS> RegsB;
-  RegsA ra[NS];
-  RegsB rb[NS];
+  RegsA ra[DIRECT ? 1 : NS];       // unused (and removed by the compiler) with direct loads
+  RegsB rb[DIRECT ? 1 : NS];
   const int nk_slot = cdiv(p.K, GB_BK);              // k-steps of one slot (of the whole contraction without a group)
   const int nk = GROUP ? nk_slot * grp.n : nk_slot;
   // k-step `kt` of the tile: without a group, contraction elements [64 kt, 64 kt + 64)
@@ -172,6 +235,29 @@ __device__ __forceinline__ void big_tile_body(const GemmProb &p, int m0, int n0,
     if (B_TR) big_fetch_tr<BN, THREADS>(xb, rs_b, p.ldb, k0, n0, tid);
     else      big_fetch_kmajor<BN, THREADS>(xb, rs_b, p.ldb, n0, k0, p.K, tid);
   };
+  // LDS buffers of the direct path as offsets from the array itself: a pointer picked out of a small array
+  // of pointers loses its address space, and the operand reads then turn into generic (flat) loads
+  auto da = [&](int b) { return lds + b * C::A_ELEMS; };
+  auto db = [&](int b) { return lds + BUFS * C::A_ELEMS + b * C::B_ELEMS; };
+  // the same k-step straight into LDS buffer `buf`
+  auto fetch_direct = [&](int kt, int buf) {
+    if (GROUP) {
+      const int g = kt / nk_slot, k0 = (kt - g * nk_slot) * GB_BK;
+      int slot = grp.first + g;
+      slot = slot >= grp.total ? slot - grp.total : slot;
+      const int64_t off = (int64_t)slot * grp.stride;
+      const __amdgpu_buffer_rsrc_t ga = matrix_rsrc((const char *)p.A + off, p.K, p.lda, p.M);
+      const __amdgpu_buffer_rsrc_t gb = matrix_rsrc((const char *)p.B + off, p.K, p.ldb, p.N);
+      big_direct_tr<BM, THREADS>(ga, p.lda, k0, m0, da(buf), tid);
+      big_direct_tr<BN, THREADS>(gb, p.ldb, k0, n0, db(buf), tid);
+      return;
+    }
+    const int k0 = kt * GB_BK;
+    if (A_TR) big_direct_tr<BM, THREADS>(rs_a, p.lda, k0, m0, da(buf), tid);
+    else      big_direct_kmajor<BM, THREADS>(rs_a, p.lda, m0, k0, p.K, da(buf), tid);
+    if (B_TR) big_direct_tr<BN, THREADS>(rs_b, p.ldb, k0, n0, db(buf), tid);
+    else      big_direct_kmajor<BN, THREADS>(rs_b, p.ldb, n0, k0, p.K, db(buf), tid);
+  };
   auto to_lds = [&](const RegsA &xa, const RegsB &xb, int buf) {
     if (A_TR) big_store_tr<BM, THREADS>(xa, lds_a[buf], tid);
     else      big_store_kmajor<BM, THREADS>(xa, lds_a[buf], tid);
@@ -184,10 +270,12 @@ __device__ __forceinline__ void big_tile_body(const GemmProb &p, int m0, int n0,
       bf16x8 a[WTM], b[WTN];
 #pragma unroll
       for (int i = 0; i < WTM; ++i)
-        a[i] = A_TR ? frag_tr<BM>(lds_a[buf], wi0 + 32 * i, kc) : big_frag_kmajor(lds_a[buf], wi0 + 32 * i, kc);
+        a[i] = DIRECT ? (A_TR ? big_direct_frag_tr<BM>(da(buf), wi0 + 32 * i, kc) : big_direct_frag_kmajor(da(buf), wi0 + 32 * i, kc))
+                      : (A_TR ? frag_tr<BM>(lds_a[buf], wi0 + 32 * i, kc) : big_frag_kmajor(lds_a[buf], wi0 + 32 * i, kc));
 #pragma unroll
       for (int j = 0; j < WTN; ++j)
-        b[j] = B_TR ? frag_tr<BN>(lds_b[buf], wj0 + 32 * j, kc) : big_frag_kmajor(lds_b[buf], wj0 + 32 * j, kc);
+        b[j] = DIRECT ? (B_TR ? big_direct_frag_tr<BN>(db(buf), wj0 + 32 * j, kc) : big_direct_frag_kmajor(db(buf), wj0 + 32 * j, kc))
+                      : (B_TR ? frag_tr<BN>(lds_b[buf], wj0 + 32 * j, kc) : big_frag_kmajor(lds_b[buf], wj0 + 32 * j, kc));
 #pragma unroll
       for (int i = 0; i < WTM; ++i)
 #pragma unroll
@@ -202,13 +290,35 @@ __device__ __forceinline__ void big_tile_body(const GemmProb &p, int m0, int n0,
   float bsum = 0.0f;
   auto bias_rows = [&](int buf) {
     if (FORM == FORM_DW && do_bias) {
-      const uint16_t *la = lds_a[buf] + (tid / BM) * BROWS * (BM + PAD_TR) + (tid % BM);
+      if (DIRECT) {       // swizzled rows of BM elements
+        const int m = tid % BM, kr0 = (tid / BM) * BROWS;
 #pragma unroll
-      for (int rr = 0; rr < BROWS; ++rr) bsum += bf16_bits_to_f32(la[rr * (BM + PAD_TR)]);
+        for (int rr = 0; rr < BROWS; ++rr) {
+          const int k = kr0 + rr;
+          bsum += bf16_bits_to_f32(da(buf)[k * BM + ((((m >> 3) ^ ((k & 3) << 1)) << 3) | (m & 7))]);
+        }
+      } else {
+        const uint16_t *la = lds_a[buf] + (tid / BM) * BROWS * (BM + PAD_TR) + (tid % BM);
+#pragma unroll
+        for (int rr = 0; rr < BROWS; ++rr) bsum += bf16_bits_to_f32(la[rr * (BM + PAD_TR)]);
+      }
     }
   };
 
-  if (BUFS == 2) {
+  if (DIRECT) {
+    // vmcnt(0): this wave's asynchronous copies have landed; the barrier then covers every wave's
+    fetch_direct(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0f70);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+      const int cur = kt & 1;
+      if (kt + 1 < nk) fetch_direct(kt + 1, cur ^ 1);   // flies while this k-step is multiplied
+      multiply(cur);
+      bias_rows(cur);
+      __builtin_amdgcn_s_waitcnt(0x0f70);
+      __syncthreads();
+    }
+  } else if (BUFS == 2) {
 #pragma unroll
     for (int u = 0; u < NS - 1; ++u)
       if (u < nk) fetch(ra[u], rb[u], u);
@@ -278,14 +388,14 @@ __device__ __forceinline__ void big_tile_body(const GemmProb &p, int m0, int n0,
   }
 }
 
-template <int FORM, int WTM, int WTN, int NS>
+template <int FORM, int WTM, int WTN, int NS, bool DIRECT>
 __global__ __launch_bounds__(512) void k_gemm_big(const GemmProb *__restrict__ probs, int n, int total_blocks,
                                                   int accumulate_dw, ExtPtrs ext) {
-  typedef BigCfg<FORM, 2, 4, WTM, WTN, 2> C;
+  typedef BigCfg<FORM, 2, 4, WTM, WTN, 2, DIRECT> C;
   __shared__ __attribute__((aligned(16))) uint16_t lds[C::LDS_ELEMS];
   const BigTile t = big_locate<C::BM, C::BN>(probs, n, total_blocks);
   const GemmProb p = probs[t.pi];
-  big_tile_body<FORM, 2, 4, WTM, WTN, 2, NS>(p, t.m0, t.n0, lds, accumulate_dw, ext);
+  big_tile_body<FORM, 2, 4, WTM, WTN, 2, NS, false, DIRECT>(p, t.m0, t.n0, lds, accumulate_dw, ext);
 }
 
 // 128 x 128 tile, 2 x 2 waves of 64 x 64, one LDS buffer, three waves per SIMD
@@ -300,15 +410,15 @@ __global__ __launch_bounds__(256, 3) void k_gemm_mid(const GemmProb *__restrict_
 }
 
 // backward-weight over a group of stash slots (see big_tile_body)
-template <int WTM, int WTN, int NS>
+template <int WTM, int WTN, int NS, bool DIRECT>
 __global__ __launch_bounds__(512) void k_gemm_big_dw_group(const GemmProb *__restrict__ probs, int n, int total_blocks,
                                                            int accumulate_dw, SlotGroup grp) {
-  typedef BigCfg<FORM_DW, 2, 4, WTM, WTN, 2> C;
+  typedef BigCfg<FORM_DW, 2, 4, WTM, WTN, 2, DIRECT> C;
   __shared__ __attribute__((aligned(16))) uint16_t lds[C::LDS_ELEMS];
   const BigTile t = big_locate<C::BM, C::BN>(probs, n, total_blocks);
   const GemmProb p = probs[t.pi];
   ExtPtrs none;
-  big_tile_body<FORM_DW, 2, 4, WTM, WTN, 2, NS, true>(p, t.m0, t.n0, lds, accumulate_dw, none, grp);
+  big_tile_body<FORM_DW, 2, 4, WTM, WTN, 2, NS, true, DIRECT>(p, t.m0, t.n0, lds, accumulate_dw, none, grp);
 }
 __global__ __launch_bounds__(256, 3) void k_gemm_mid_dw_group(const GemmProb *__restrict__ probs, int n, int total_blocks,
                                                               int accumulate_dw, SlotGroup grp) {
@@ -323,6 +433,11 @@ __global__ __launch_bounds__(256, 3) void k_gemm_mid_dw_group(const GemmProb *__
 // ---- host side -------------------------------------------------------------------------
 // The kernels take a problem when the chunks of its k-contiguous operands are whole (contraction
 // length a multiple of 8) and the matrices fit the 32-bit buffer offsets.
+// Direct loads move whole, aligned 16-byte chunks: rows and base pointers of both operands must be 16-byte
+// aligned (the planner pads leading dimensions to 64 elements, so only unusual callers fail this).
+bool gemm_big_direct_ok(const GemmProb &p) {
+  return (p.lda & 7) == 0 && (p.ldb & 7) == 0 && ((uintptr_t)p.A & 15) == 0 && ((uintptr_t)p.B & 15) == 0;
+}
 bool gemm_big_supported(const GemmProb &p) {
   if (!gemm_mfma_supported(p)) return false;
   if (p.form != FORM_DW && (p.K & 7)) return false;
@@ -358,29 +473,33 @@ int gemm_big_tiles_for(int tile_rows, int M, int N, int *tiles_n) {
 }
 
 template <int FORM>
-static void launch_big_form(const GemmProb *probs, int n, int blocks, int acc, int tile_rows, const ExtPtrs &ext, hipStream_t s) {
-  if (tile_rows == 256)
-    hipLaunchKernelGGL((k_gemm_big<FORM, 4, 2, 2>), dim3(blocks), dim3(512), 0, s, probs, n, blocks, acc, ext);
-  else if (tile_rows == 128)
-    hipLaunchKernelGGL((k_gemm_big<FORM, 2, 2, 2>), dim3(blocks), dim3(512), 0, s, probs, n, blocks, acc, ext);
-  else
-    hipLaunchKernelGGL((k_gemm_mid<FORM>), dim3(blocks), dim3(256), 0, s, probs, n, blocks, acc, ext);
+static void launch_big_form(const GemmProb *probs, int n, int blocks, int acc, int tile_rows, int direct, const ExtPtrs &ext,
+                            hipStream_t s) {
+  const dim3 g(blocks), b(512);
+  if (tile_rows == 256 && direct) hipLaunchKernelGGL((k_gemm_big<FORM, 4, 2, 2, true>), g, b, 0, s, probs, n, blocks, acc, ext);
+  else if (tile_rows == 256) hipLaunchKernelGGL((k_gemm_big<FORM, 4, 2, 2, false>), g, b, 0, s, probs, n, blocks, acc, ext);
+  else if (tile_rows == 128 && direct) hipLaunchKernelGGL((k_gemm_big<FORM, 2, 2, 2, true>), g, b, 0, s, probs, n, blocks, acc, ext);
+  else if (tile_rows == 128) hipLaunchKernelGGL((k_gemm_big<FORM, 2, 2, 2, false>), g, b, 0, s, probs, n, blocks, acc, ext);
+  else hipLaunchKernelGGL((k_gemm_mid<FORM>), g, dim3(256), 0, s, probs, n, blocks, acc, ext);
 }
-void launch_gemm_big(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int form, int tile_rows,
+// direct != 0: operands straight into LDS (every record must pass gemm_big_direct_ok; the 128 x 128 kernel
+// has one LDS buffer and always stages through registers)
+void launch_gemm_big(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int form, int tile_rows, int direct,
                      const ExtPtrs &ext, hipStream_t s) {
   if (total_blocks <= 0) return;
-  if (form == FORM_FWD) launch_big_form<FORM_FWD>(probs, n, total_blocks, accumulate_dw, tile_rows, ext, s);
-  else if (form == FORM_DX) launch_big_form<FORM_DX>(probs, n, total_blocks, accumulate_dw, tile_rows, ext, s);
-  else launch_big_form<FORM_DW>(probs, n, total_blocks, accumulate_dw, tile_rows, ext, s);
+  if (form == FORM_FWD) launch_big_form<FORM_FWD>(probs, n, total_blocks, accumulate_dw, tile_rows, direct, ext, s);
+  else if (form == FORM_DX) launch_big_form<FORM_DX>(probs, n, total_blocks, accumulate_dw, tile_rows, direct, ext, s);
+  else launch_big_form<FORM_DW>(probs, n, total_blocks, accumulate_dw, tile_rows, direct, ext, s);
 }
 
-void launch_gemm_dw_group(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int tile_rows,
+void launch_gemm_dw_group(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int tile_rows, int direct,
                           const SlotGroup &grp, hipStream_t s) {
   if (total_blocks <= 0 || grp.n <= 0) return;
-  if (tile_rows == 256)
-    hipLaunchKernelGGL((k_gemm_big_dw_group<4, 2, 2>), dim3(total_blocks), dim3(512), 0, s, probs, n, total_blocks, accumulate_dw, grp);
-  else if (tile_rows == 128)
-    hipLaunchKernelGGL((k_gemm_big_dw_group<2, 2, 2>), dim3(total_blocks), dim3(512), 0, s, probs, n, total_blocks, accumulate_dw, grp);
+  const dim3 g(total_blocks), b(512);
+  if (tile_rows == 256 && direct) hipLaunchKernelGGL((k_gemm_big_dw_group<4, 2, 2, true>), g, b, 0, s, probs, n, total_blocks, accumulate_dw, grp);
+  else if (tile_rows == 256) hipLaunchKernelGGL((k_gemm_big_dw_group<4, 2, 2, false>), g, b, 0, s, probs, n, total_blocks, accumulate_dw, grp);
+  else if (tile_rows == 128 && direct) hipLaunchKernelGGL((k_gemm_big_dw_group<2, 2, 2, true>), g, b, 0, s, probs, n, total_blocks, accumulate_dw, grp);
+  else if (tile_rows == 128) hipLaunchKernelGGL((k_gemm_big_dw_group<2, 2, 2, false>), g, b, 0, s, probs, n, total_blocks, accumulate_dw, grp);
   else
     hipLaunchKernelGGL(k_gemm_mid_dw_group, dim3(total_blocks), dim3(256), 0, s, probs, n, total_blocks, accumulate_dw, grp);
 }

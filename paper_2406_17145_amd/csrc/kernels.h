@@ -180,16 +180,17 @@ int gemm_mfma_tiles_for(int tile, int M, int N, int *tiles_n);
 int gemm_mfma_partial_floats(int tile);
 // large-tile kernels: 256 x 256 or 128 x 256 outputs per workgroup of eight waves (tile_rows 256 / 128),
 // 128 x 128 outputs per workgroup of four waves, three workgroups per compute unit (tile_rows 64)
-void launch_gemm_big(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int form, int tile_rows,
+void launch_gemm_big(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int form, int tile_rows, int direct,
                      const ExtPtrs &ext, hipStream_t s);
 bool gemm_big_supported(const GemmProb &p);
+bool gemm_big_direct_ok(const GemmProb &p);
 // Backward-weight whose contraction runs over the rows of `n` stash slots, starting at slot `first` and
 // wrapping at `total`; slot s lies s * stride bytes behind slot 0, whose addresses the records hold.
 struct SlotGroup {
   int32_t first = 0, n = 1, total = 1, pad = 0;
   int64_t stride = 0;
 };
-void launch_gemm_dw_group(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int tile_rows,
+void launch_gemm_dw_group(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int tile_rows, int direct,
                           const SlotGroup &grp, hipStream_t s);
 int gemm_big_tile_rows(int maxM, int maxN, int64_t launch_elems, int tiles256, int tiles128);
 int gemm_big_tiles_for(int tile_rows, int M, int N, int *tiles_n);

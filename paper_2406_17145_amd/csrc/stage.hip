@@ -283,11 +283,11 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
       case K_ELT: launch_elt((const EltProb *)tab, sp.n, sp.blocks, ext, s); break;
       case K_GEMM_GENERIC: launch_gemm_generic((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a0, s); break;
       case K_GEMM_MFMA: launch_gemm_mfma((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a1, sp.a2, ext, s); break;
-      case K_GEMM_BIG: launch_gemm_big((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a1, sp.a2, ext, s); break;
+      case K_GEMM_BIG: launch_gemm_big((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a1, sp.a2, sp.a0, ext, s); break;
       case K_GEMM_DW_KSPLIT: launch_gemm_dw_ksplit((const GemmProb *)tab, sp.n, sp.blocks, accumulate, s); break;
       case K_GEMM_DW_GROUP:
         if (!grp) return fail(GPP_ERR_UNSUPPORTED, "internal: group launch without a group");
-        launch_gemm_dw_group((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a2, *grp, s);
+        launch_gemm_dw_group((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a2, sp.a0, *grp, s);
         break;
       case K_GEMM_SKINNY: launch_gemm_skinny((const GemmProb *)tab, sp.n, sp.blocks, sp.a1, sp.a2, sp.a0, ext, s); break;
       case K_GEMM_BWD_MERGED: launch_gemm_bwd_merged((const GemmProb *)tab, sp.n, sp.blocks, sp.a2, sp.a1, accumulate, ext, s); break;
