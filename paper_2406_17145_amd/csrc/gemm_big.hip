@@ -97,8 +97,10 @@ __device__ __forceinline__ bf16x8 big_frag_kmajor(const uint16_t *lds, int row0,
 // reads free of bank conflicts in the staged path is replaced by a swizzle: WHICH chunk of memory a lane
 // loads.  The asynchronous copy runs while the previous k-step is multiplied; nothing waits in registers.
 typedef __attribute__((address_space(3))) void lds_void_t;
-// k-contiguous operand, tile [EXT][64]: 128-byte rows, chunk c of row r sits at chunk position
-// c ^ (r % 8): the 8 lanes that read one chunk column of 8 consecutive rows hit 8 different positions
+// The LDS moves 256 bytes per cycle (64 banks of 4 bytes), so what must not collide is:
+// k-contiguous operand, tile [EXT][64]: 128-byte rows, two per bank line; a 16-byte operand read serves 16
+// lanes per cycle, the same chunk column of 16 consecutive rows.  Chunk c of row r sits at chunk position
+// c ^ ((r / 2) % 8): the two rows of a bank line keep their halves, the eight row pairs take eight positions
 template <int EXT, int THREADS>
 __device__ __forceinline__ void big_direct_kmajor(__amdgpu_buffer_rsrc_t rs, int64_t ld, int r0, int k0, int k_lim,
                                                   uint16_t *tile, int tid) {
@@ -108,7 +110,7 @@ __device__ __forceinline__ void big_direct_kmajor(__amdgpu_buffer_rsrc_t rs, int
 #pragma unroll
   for (int q = 0; q < INSTR; ++q) {
     const int row = wave * ROWS_PER_WAVE + 8 * q + (l >> 3);
-    const int k = k0 + (((l & 7) ^ (row & 7)) << 3);
+    const int k = k0 + (((l & 7) ^ ((row >> 1) & 7)) << 3);
     const uint32_t oob = (uint32_t)-(int32_t)(k >= k_lim) & OOB_OFFSET;
     const uint32_t off = (uint32_t)(((int64_t)(r0 + row) * ld + k) * 2) | oob;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_t *)(tile + (wave * ROWS_PER_WAVE + 8 * q) * GB_BK), 16, off, 0, 0, 0);
@@ -117,11 +119,11 @@ __device__ __forceinline__ void big_direct_kmajor(__amdgpu_buffer_rsrc_t rs, int
 __device__ __forceinline__ bf16x8 big_direct_frag_kmajor(const uint16_t *tile, int row0, int k0) {
   const int l = threadIdx.x & 63;
   const int row = row0 + (l & 31), c = (k0 >> 3) + (l >> 5);
-  return *(const bf16x8 *)(tile + row * GB_BK + ((c ^ (row & 7)) << 3));
+  return *(const bf16x8 *)(tile + row * GB_BK + ((c ^ ((row >> 1) & 7)) << 3));
 }
-// contraction-major operand, tile [64][EXT]: rows of EXT elements, chunk c of row k sits at chunk position
-// c ^ (2 (k % 4)): a 16-lane block of the transposing read touches 32 bytes in each of four consecutive
-// rows, which the swizzle spreads over the four 32-byte quarters of a 128-byte bank line
+// contraction-major operand, tile [64][EXT]: rows of EXT elements (a multiple of 256 bytes).  The transposing
+// 8-byte read serves 32 lanes per cycle: 64 bytes in each of four consecutive rows.  Chunk c of row k sits at
+// chunk position c ^ (4 (k % 4)), which spreads the four rows over the four 64-byte quarters of a bank line
 template <int EXT, int THREADS>
 __device__ __forceinline__ void big_direct_tr(__amdgpu_buffer_rsrc_t rs, int64_t ld, int k0, int c0, uint16_t *tile, int tid) {
   constexpr int CPR = EXT / 8;                         // chunks per row
@@ -132,7 +134,7 @@ __device__ __forceinline__ void big_direct_tr(__amdgpu_buffer_rsrc_t rs, int64_t
   for (int q = 0; q < INSTR; ++q) {
     const int first = (wave * INSTR + q) * 64;         // first chunk (in LDS order) of this instruction
     const int row = (first + l) / CPR, pos = (first + l) % CPR;
-    const int col = c0 + ((pos ^ ((row & 3) << 1)) << 3);
+    const int col = c0 + ((pos ^ ((row & 3) << 2)) << 3);
     // the whole address in the vector offset: the descriptor's range check (rows at or beyond the contraction
     // length read zero) does not cover a scalar offset
     __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_t *)(tile + first * 8), 16,
@@ -144,7 +146,7 @@ __device__ __forceinline__ bf16x8 big_direct_frag_tr(const uint16_t *tile, int c
   const int l = threadIdx.x & 63;
   const int blk = l >> 4, q = l & 15;
   const int row = k0 + 8 * (blk >> 1) + (q >> 2), col = col0 + 16 * (blk & 1) + 4 * (q & 3);
-  const uint16_t *p = tile + row * COLS + ((((col >> 3) ^ ((row & 3) << 1)) << 3) | (col & 7));
+  const uint16_t *p = tile + row * COLS + ((((col >> 3) ^ ((row & 3) << 2)) << 3) | (col & 7));
   typedef __attribute__((address_space(3))) s16x4 lds_v4;
   s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)p);
   s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(p + 4 * COLS));     // row + 4: same swizzle
@@ -295,7 +297,7 @@ __device__ __forceinline__ void big_tile_body(const GemmProb &p, int m0, int n0,
 #pragma unroll
         for (int rr = 0; rr < BROWS; ++rr) {
           const int k = kr0 + rr;
-          bsum += bf16_bits_to_f32(da(buf)[k * BM + ((((m >> 3) ^ ((k & 3) << 1)) << 3) | (m & 7))]);
+          bsum += bf16_bits_to_f32(da(buf)[k * BM + ((((m >> 3) ^ ((k & 3) << 2)) << 3) | (m & 7))]);
         }
       } else {
         const uint16_t *la = lds_a[buf] + (tid / BM) * BROWS * (BM + PAD_TR) + (tid % BM);
