@@ -152,6 +152,8 @@ def main():
                          "when the stage has a slot per micro-batch of the step (a captured forward pass cannot wait "
                          "for a backward pass), off with the serial one (measured: replay is 1-3 %% slower than eager "
                          "launches there)")
+    ap.add_argument("--side-stream", action="store_true",
+                    help="stage flag bit 3: the embedding bags' launches on a side stream of the stage, next to the dense branches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-serial-reference", action="store_true",
                     help="skip the untimed-in-value reference pass that runs the same steps eagerly in serial order "
@@ -184,7 +186,7 @@ def main():
     # call waits for a backward call (the form a HIP graph can hold, see schedule.py)
     n_slots = min(wl.n_micro, 8) if overlap else (max(1, min(args.in_flight, wl.n_micro)) if kfkb else 1)
     grouped = args.grouped_dw == "on" or (args.grouped_dw == "auto" and kfkb)
-    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=n_slots, flags=B.FLAG_GROUPED_DW if grouped else 0)
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=n_slots, flags=(B.FLAG_GROUPED_DW if grouped else 0) | (B.FLAG_SIDE_STREAM if args.side_stream else 0))
     dev_batches = [st.stage_inputs(mb) for mb in wl.batches]       # resident in HBM
     outs = [st.alloc_outputs() for _ in range(max(n_slots, 2))]    # one set per in-flight slot
     gins = st.alloc_grad_inputs()

@@ -128,7 +128,12 @@ typedef struct {
   int32_t flags;              /* bit 0: force the generic (non-MFMA) GEMM kernels (testing);
                                  bit 1: split the contraction of small grouped GEMMs over several
                                  workgroups (deterministic; measured slower, off by default);
-                                 bit 2: grouped weight gradients, see gpp_stage_backward_weights */
+                                 bit 2: grouped weight gradients, see gpp_stage_backward_weights;
+                                 bit 3: a stage that holds embedding bags next to dense branches runs the
+                                 bags' gather and their sort + segment sums on a side stream of its own
+                                 (created with the stage at default priority, forked from and joined to the
+                                 caller's stream by events inside every forward / backward call); off by
+                                 default: it pays only for large micro-batches */
 } gpp_stage_desc_t;
 
 /* Leading dimension used for parameters and gradient accumulators. */

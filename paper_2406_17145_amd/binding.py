@@ -29,6 +29,7 @@ ACTS = {"none": 0, "relu": 1, "gelu": 2}
 FLAG_FORCE_GENERIC_GEMM = 1
 FLAG_SPLIT_K = 2
 FLAG_GROUPED_DW = 4
+FLAG_SIDE_STREAM = 8
 
 
 class OpDesc(C.Structure):

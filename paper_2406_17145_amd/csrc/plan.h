@@ -27,7 +27,7 @@ struct Buf {
 enum Kern : int32_t {
   K_ELT, K_GEMM_GENERIC, K_GEMM_MFMA, K_COLSUM, K_LN_FWD, K_LN_BWD, K_LN_BWD_PARAMS, K_ATTN_FWD, K_ATTN_DQ,
   K_ATTN_DKV, K_POOL, K_EMB_FWD, K_EMB_BWD, K_INTERACT_FWD, K_INTERACT_BWD, K_LOSS_FWD, K_LOSS_BWD, K_LOSS_SUM,
-  K_GEMM_SKINNY, K_GEMM_BWD_MERGED, K_LOSS_FWD_SMALL, K_GEMM_BIG, K_GEMM_DW_KSPLIT, K_GEMM_DW_GROUP
+  K_GEMM_SKINNY, K_GEMM_BWD_MERGED, K_LOSS_FWD_SMALL, K_GEMM_BIG, K_GEMM_DW_KSPLIT, K_GEMM_DW_GROUP, K_FORK, K_JOIN
 };
 enum ExtKind : int32_t { EXT_NONE = 0, EXT_INPUTS, EXT_OUTPUTS, EXT_GRAD_OUTPUTS, EXT_GRAD_INPUTS };
 
@@ -39,6 +39,7 @@ struct Step {
   int32_t a0, a1, a2; // kernel-specific launch arguments
   int32_t ext_kind, ext_base;
   int32_t launches;   // kernel launches this step enqueues
+  int32_t lane;       // 0: the caller's stream; 1: the stage's side stream (between a K_FORK and a K_JOIN)
 };
 
 struct Node {
@@ -74,6 +75,7 @@ struct Plan {
   Buf loss_scalars;                  // f32 partial losses per slot
   int loss_parts = 0;
   std::vector<Step> fwd, bwd;
+  bool lanes = false;                // the step lists hold side-stream steps: the stage needs its side streams
   std::vector<Step> dwg;             // weight gradients of a group of backward passes (flag bit 2), slot 0's tables
   std::vector<uint8_t> blob;         // tables of the slot being emitted
   std::string error;

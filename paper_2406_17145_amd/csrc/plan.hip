@@ -396,6 +396,13 @@ struct Emitter {
   int64_t part_need = 0, cnt_need = 0;  // split-K scratch high-water marks over all launches
   std::vector<GemmProb> dw_group;   // backward-weight records left to the launch over a group of slots
   std::vector<char> loss_fused;     // per node: this loss's gradient is written by the forward pass
+  // Embedding bags next to dense branches: the gather (forward) and the sort + segment sums (backward) are long
+  // chains of launches that nothing on the dense side depends on until the branches merge.  They run on the
+  // stage's side stream: K_FORK (side stream waits for what has been issued), the steps with lane 1, K_JOIN
+  // before the first step that needs them.  emb_level = level of the first real consumer of a bag's output.
+  int emb_level = -1;
+  bool fork_open = false;
+  std::vector<char> emb_hoisted;    // per node: its backward was issued early, on the side stream
   std::vector<int> written_level;   // level whose launches first wrote the node's gradient
   int cur_level = 0;
   int64_t shared_tmp_top;
@@ -425,6 +432,98 @@ struct Emitter {
     s.launches = 1;
     steps->push_back(s);
     return steps->back();
+  }
+
+  void fork() {
+    add_step(K_FORK, 0, 0, 0).launches = 0;
+    fork_open = true;
+    pl.lanes = true;
+  }
+  void join() {
+    if (!fork_open) return;
+    add_step(K_JOIN, 0, 0, 0).launches = 0;
+    fork_open = false;
+  }
+  // level of the first operator that really reads node i's value (a concat the node is written into in place
+  // is looked through)
+  int consumer_level(int i) const {
+    int m = 1 << 30;
+    for (int u : pl.nodes[i].users) {
+      const Node &c = pl.nodes[u];
+      m = std::min(m, (c.d.kind == GPP_OP_CONCAT && pl.nodes[i].val_parent == u) ? consumer_level(u) : c.level);
+    }
+    return m;
+  }
+  void find_emb_level() {
+    emb_level = -1;
+    if (!(pl.flags & 8)) return;     // opt-in: measured -5 % at 128-512 rows, +3 % at 2048 rows per micro-batch
+    bool dense = false;
+    int lvl = 1 << 30;
+    for (size_t i = 0; i < pl.nodes.size(); ++i) {
+      const int k = pl.nodes[i].d.kind;
+      if (k == GPP_OP_LINEAR) dense = true;
+      if (k == GPP_OP_EMBEDDING_BAG_SUM || k == GPP_OP_EMBEDDING_BAG_CONCAT) lvl = std::min(lvl, consumer_level((int)i));
+    }
+    if (dense && lvl < (1 << 30)) emb_level = lvl;
+  }
+
+  EmbProb emb_bwd_record(int i) {
+    auto &N = pl.nodes;
+    Node &nd = N[i];
+    const gpp_op_desc_t &d = nd.d;
+    EmbProb e;
+    memset(&e, 0, sizeof(e));
+    e.concat = d.kind == GPP_OP_EMBEDDING_BAG_CONCAT;
+    e.bag_size = (int32_t)d.bag_size;
+    e.dim = (int32_t)(e.concat ? d.in_features : nd.feat);
+    e.table = (const float *)d.param[0];
+    e.dtable = (float *)d.grad[0];
+    e.ld_table = ld_of(e.dim);
+    e.indices = (const int32_t *)ptr(N[nd.in[0]].val);
+    e.offsets = (const int32_t *)ptr(N[nd.in[1]].val);
+    e.out = ptr(nd.gout);
+    // concatenated bags: bag_size * dim is a multiple of 64, so the gradient rows carry no padding and
+    // the matrix is also [micro_batch * bag_size, dim] with leading dimension dim
+    e.ld_out = e.concat ? e.dim : nd.gout.ld;
+    e.out_dtype = nd.gout.dtype;
+    e.bag_of = (int32_t *)ptr(nd.extra);
+    e.keys_a = (int32_t *)ptr(nd.more[0]);
+    e.keys_b = (int32_t *)ptr(nd.more[1]);
+    e.pos_a = (int32_t *)ptr(nd.more[2]);
+    e.pos_b = (int32_t *)ptr(nd.more[3]);
+    e.hist = (int32_t *)ptr(nd.more[4]);
+    e.unique_rows = (int32_t *)ptr(nd.more[5]);
+    e.seg_offsets = (int32_t *)ptr(nd.more[6]);
+    e.counts = (int32_t *)ptr(nd.more[7]);
+    e.long_list = (int32_t *)ptr(nd.more[8]);
+    e.partial = (float *)ptr(nd.more[9]);
+    e.sbag = (int32_t *)ptr(nd.more[10]);
+    e.seg_rows = (int32_t *)ptr(nd.more[11]);
+    e.n_bags = (int32_t)pl.micro_batch;
+    e.capacity = (int32_t)(pl.micro_batch * d.bag_size);
+    e.num_rows = (int32_t)d.num_rows;
+    e.passes = nd.emb_passes;
+    e.sort_blocks = nd.emb_sort_blocks;
+    return e;
+  }
+  void emit_emb_bwd(std::vector<EmbProb> &embs, int lane) {
+    if (embs.empty()) return;
+    int cap = 0, sb = 0, ps = 0, md = 0, odt = embs[0].out_dtype;
+    for (auto &e : embs) {
+      cap = std::max(cap, e.capacity);
+      sb = std::max(sb, e.sort_blocks);
+      ps = std::max(ps, e.passes);
+      md = std::max(md, e.dim);
+      if (e.out_dtype != odt) odt = 3;   // mixed
+    }
+    bool vec = true;
+    for (auto &e : embs) vec = vec && emb_vec_supported(e);
+    Step &s = add_step(K_EMB_BWD, push_table(embs), (int)embs.size(), 0);
+    s.a0 = cap;
+    s.a1 = sb;
+    s.a2 = ps | (vec ? 256 : 0) | (odt << 9) | (md << 11);   // passes (8 bits), vector path, gradient dtype (2 bits), largest dimension
+    s.launches = emb_bwd_num_launches(ps, vec ? 1 : 0);
+    s.lane = lane;
   }
 
   // ---- elementwise helper ------------------------------------------------
@@ -775,6 +874,8 @@ void Emitter::forward() {
   bool loss_summed = false;
   auto &N = pl.nodes;
   loss_fused.assign(N.size(), 0);
+  find_emb_level();
+  fork_open = false;
 
   // ingest: copy the caller's dense inputs into the (padded) stash buffers
   {
@@ -798,6 +899,7 @@ void Emitter::forward() {
   }
 
   for (size_t L = 1; L < pl.by_level.size(); ++L) {
+    if ((int)L == emb_level) join();     // the first operator that reads a bag's output is on this level
     std::vector<GemmProb> gemms;
     std::vector<LnProb> lns;
     std::vector<AttnProb> attns;
@@ -987,6 +1089,27 @@ void Emitter::forward() {
         default: break;
       }
     }
+    // the gather first: on the side stream it runs next to everything else of this and the next levels
+    if (!embs.empty()) {
+      int blocks = 0;
+      for (auto &e : embs) {
+        e.blk_begin = blocks;
+        blocks += emb_fwd_blocks(e.n_bags);
+      }
+      bool vec = true;
+      for (auto &e : embs) vec = vec && emb_vec_supported(e);
+      // vector kernel with eight or more tables: table -> XCD affinity (see emb_fwd_affinity_grid); a1 = the
+      // largest workgroup count of a table, the grid is then laid out per table instead of by prefix sums
+      int per_table = 0;
+      for (auto &e : embs) per_table = std::max(per_table, emb_fwd_blocks(e.n_bags));
+      const bool affinity = vec && embs.size() >= 8;
+      const bool side = emb_level > (int)L;     // something else can run before the bags are needed
+      if (side && !fork_open) fork();
+      Step &se = add_step(K_EMB_FWD, push_table(embs), (int)embs.size(), affinity ? emb_fwd_affinity_grid((int)embs.size(), per_table) : blocks);
+      se.a0 = vec ? 1 : 0;
+      se.a1 = affinity ? per_table : 0;
+      se.lane = side ? 1 : 0;
+    }
     emit_gemms(gemms);
     if (!lns.empty()) {
       int blocks = 0;
@@ -1025,23 +1148,6 @@ void Emitter::forward() {
       }
       add_step(K_POOL, push_table(pools), (int)pools.size(), blocks);
     }
-    if (!embs.empty()) {
-      int blocks = 0;
-      for (auto &e : embs) {
-        e.blk_begin = blocks;
-        blocks += emb_fwd_blocks(e.n_bags);
-      }
-      bool vec = true;
-      for (auto &e : embs) vec = vec && emb_vec_supported(e);
-      // vector kernel with eight or more tables: table -> XCD affinity (see emb_fwd_affinity_grid); a1 = the
-      // largest workgroup count of a table, the grid is then laid out per table instead of by prefix sums
-      int per_table = 0;
-      for (auto &e : embs) per_table = std::max(per_table, emb_fwd_blocks(e.n_bags));
-      const bool affinity = vec && embs.size() >= 8;
-      Step &se = add_step(K_EMB_FWD, push_table(embs), (int)embs.size(), affinity ? emb_fwd_affinity_grid((int)embs.size(), per_table) : blocks);
-      se.a0 = vec ? 1 : 0;
-      se.a1 = affinity ? per_table : 0;
-    }
     if (!inters.empty()) {
       int blocks = 0, mf = 0, md = 0;
       for (auto &p : inters) {
@@ -1072,6 +1178,7 @@ void Emitter::forward() {
     }
   }
 
+  join();
   // egress: stage outputs to the caller's dense buffers, loss scalars summed
   {
     std::vector<EltProb> recs;
@@ -1107,6 +1214,8 @@ void Emitter::backward() {
   dz_ready.assign(n, 0);
   written_level.assign(n, -1);
   post_copies.clear();
+  emb_hoisted.assign(n, 0);
+  fork_open = false;
 
   // ingest the caller's output gradients
   {
@@ -1407,40 +1516,8 @@ void Emitter::backward() {
         }
         case GPP_OP_EMBEDDING_BAG_SUM:
         case GPP_OP_EMBEDDING_BAG_CONCAT: {
-          EmbProb e;
-          memset(&e, 0, sizeof(e));
-          e.concat = d.kind == GPP_OP_EMBEDDING_BAG_CONCAT;
-          e.bag_size = (int32_t)d.bag_size;
-          e.dim = (int32_t)(e.concat ? d.in_features : nd.feat);
-          e.table = (const float *)d.param[0];
-          e.dtable = (float *)d.grad[0];
-          e.ld_table = ld_of(e.dim);
-          e.indices = (const int32_t *)ptr(N[nd.in[0]].val);
-          e.offsets = (const int32_t *)ptr(N[nd.in[1]].val);
-          e.out = ptr(nd.gout);
-          // concatenated bags: bag_size * dim is a multiple of 64, so the gradient rows carry no padding and
-          // the matrix is also [micro_batch * bag_size, dim] with leading dimension dim
-          e.ld_out = e.concat ? e.dim : nd.gout.ld;
-          e.out_dtype = nd.gout.dtype;
-          e.bag_of = (int32_t *)ptr(nd.extra);
-          e.keys_a = (int32_t *)ptr(nd.more[0]);
-          e.keys_b = (int32_t *)ptr(nd.more[1]);
-          e.pos_a = (int32_t *)ptr(nd.more[2]);
-          e.pos_b = (int32_t *)ptr(nd.more[3]);
-          e.hist = (int32_t *)ptr(nd.more[4]);
-          e.unique_rows = (int32_t *)ptr(nd.more[5]);
-          e.seg_offsets = (int32_t *)ptr(nd.more[6]);
-          e.counts = (int32_t *)ptr(nd.more[7]);
-          e.long_list = (int32_t *)ptr(nd.more[8]);
-          e.partial = (float *)ptr(nd.more[9]);
-          e.sbag = (int32_t *)ptr(nd.more[10]);
-          e.seg_rows = (int32_t *)ptr(nd.more[11]);
-          e.n_bags = (int32_t)pl.micro_batch;
-          e.capacity = (int32_t)(pl.micro_batch * d.bag_size);
-          e.num_rows = (int32_t)d.num_rows;
-          e.passes = nd.emb_passes;
-          e.sort_blocks = nd.emb_sort_blocks;
-          embs.push_back(e);
+          if (emb_hoisted[i]) break;          // issued early, on the side stream
+          embs.push_back(emb_bwd_record(i));
           break;
         }
         case GPP_OP_DOT_INTERACT: {
@@ -1533,23 +1610,7 @@ void Emitter::backward() {
       }
       add_step(K_POOL, push_table(pools), (int)pools.size(), blocks);
     }
-    if (!embs.empty()) {
-      int cap = 0, sb = 0, ps = 0, md = 0, odt = embs[0].out_dtype;
-      for (auto &e : embs) {
-        cap = std::max(cap, e.capacity);
-        sb = std::max(sb, e.sort_blocks);
-        ps = std::max(ps, e.passes);
-        md = std::max(md, e.dim);
-        if (e.out_dtype != odt) odt = 3;   // mixed
-      }
-      bool vec = true;
-      for (auto &e : embs) vec = vec && emb_vec_supported(e);
-      Step &s = add_step(K_EMB_BWD, push_table(embs), (int)embs.size(), 0);
-      s.a0 = cap;
-      s.a1 = sb;
-      s.a2 = ps | (vec ? 256 : 0) | (odt << 9) | (md << 11);   // passes (8 bits), vector path, gradient dtype (2 bits), largest dimension
-      s.launches = emb_bwd_num_launches(ps, vec ? 1 : 0);
-    }
+    emit_emb_bwd(embs, 0);
     if (!inters.empty()) {
       int blocks = 0, mf = 0, md = 0;
       for (auto &p : inters) {
@@ -1563,7 +1624,31 @@ void Emitter::backward() {
       s.a1 = md;
     }
     flush_post();
+    // bags whose gradient is complete now (it is a slice of the merge buffer that this level's operators
+    // have just written) start their sort and segment sums on the side stream, next to the backward
+    // passes of the dense branches
+    // (all bags or none: the gradient reset works from ONE table of all embedding records)
+    if (L == emb_level && L > 1) {
+      std::vector<int> bags, ready;
+      for (size_t i = 0; i < N.size(); ++i) {
+        const int k = N[i].d.kind;
+        if (k != GPP_OP_EMBEDDING_BAG_SUM && k != GPP_OP_EMBEDDING_BAG_CONCAT) continue;
+        bags.push_back((int)i);
+        if (N[i].gout_parent >= 0 && N[i].level < L && N[i].wants_grad && state_of((int)i) == G_WRITTEN && consumer_level((int)i) == L)
+          ready.push_back((int)i);
+      }
+      if (!ready.empty() && ready.size() == bags.size()) {
+        std::vector<EmbProb> early;
+        for (int i : ready) {
+          early.push_back(emb_bwd_record(i));
+          emb_hoisted[i] = 1;
+        }
+        fork();
+        emit_emb_bwd(early, 1);
+      }
+    }
   }
+  join();
 
   // egress: input gradients to the caller's dense buffers
   {

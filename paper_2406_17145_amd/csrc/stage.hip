@@ -62,6 +62,10 @@ struct gpp_stage {
   int64_t prof_launches[GPP_PROFILE_TAGS] = {0};
   // events of the schedule executor (created on first use, two per micro-batch, no timing)
   std::vector<hipEvent_t> sched_ev;
+  // side streams (one for forward calls, one for backward calls) and their fork / join events, created with the
+  // stage when its plan runs embedding bags next to dense branches
+  hipStream_t lane_stream[2] = {nullptr, nullptr};
+  hipEvent_t lane_fork[2] = {nullptr, nullptr}, lane_join[2] = {nullptr, nullptr};
 };
 
 static bool gemm_step(const Step &sp) {
@@ -180,6 +184,18 @@ gpp_status_t gpp_stage_create(const gpp_stage_desc_t *desc, void *workspace, siz
     return fail(he != hipSuccess ? GPP_ERR_DEVICE : rc, e);
   }
   st->slot_busy.assign(pl.slots, 0);
+  if (pl.lanes) {
+    for (int k = 0; k < 2 && he == hipSuccess; ++k) {
+      he = hipStreamCreateWithFlags(&st->lane_stream[k], hipStreamNonBlocking);      // default priority
+      if (he == hipSuccess) he = hipEventCreateWithFlags(&st->lane_fork[k], hipEventDisableTiming);
+      if (he == hipSuccess) he = hipEventCreateWithFlags(&st->lane_join[k], hipEventDisableTiming);
+    }
+    if (he != hipSuccess) {
+      const std::string e = std::string("HIP: ") + hipGetErrorString(he);
+      gpp_stage_destroy(st);
+      return fail(GPP_ERR_DEVICE, e);
+    }
+  }
   for (const Step &s : pl.bwd)
     if (s.kern == K_EMB_BWD) {
       st->emb_table_off = s.table_off;
@@ -194,6 +210,11 @@ gpp_status_t gpp_stage_destroy(gpp_stage_t *stage) {
   if (stage) {
     for (hipEvent_t e : stage->prof_ev) (void)hipEventDestroy(e);
     for (hipEvent_t e : stage->sched_ev) (void)hipEventDestroy(e);
+    for (int k = 0; k < 2; ++k) {
+      if (stage->lane_fork[k]) (void)hipEventDestroy(stage->lane_fork[k]);
+      if (stage->lane_join[k]) (void)hipEventDestroy(stage->lane_join[k]);
+      if (stage->lane_stream[k]) (void)hipStreamDestroy(stage->lane_stream[k]);
+    }
   }
   delete stage;
   return GPP_OK;
@@ -243,7 +264,26 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
   const char *tables = st->ws + pl.off_tables + (int64_t)slot * pl.table_bytes;
   StageFlags *flags = (StageFlags *)(st->ws + pl.off_flags);
   const bool is_bwd = &steps == &pl.bwd;
+  const int side = is_bwd ? 1 : 0;
+  hipStream_t caller = s;
   for (const Step &sp : steps) {
+    // side-stream steps: the fork makes the side stream wait for everything issued so far on the caller's
+    // stream, the join makes the caller's stream wait for the side stream (default priorities; under graph
+    // capture the two waits pull the side stream into the capture and back out)
+    if (sp.kern == K_FORK || sp.kern == K_JOIN) {
+      if (!st->lane_stream[side]) return fail(GPP_ERR_UNSUPPORTED, "internal: side stream missing");
+      hipError_t he;
+      if (sp.kern == K_FORK) {
+        he = hipEventRecord(st->lane_fork[side], caller);
+        if (he == hipSuccess) he = hipStreamWaitEvent(st->lane_stream[side], st->lane_fork[side], 0);
+      } else {
+        he = hipEventRecord(st->lane_join[side], st->lane_stream[side]);
+        if (he == hipSuccess) he = hipStreamWaitEvent(caller, st->lane_join[side], 0);
+      }
+      if (he != hipSuccess) return fail(GPP_ERR_DEVICE, std::string("HIP event: ") + hipGetErrorString(he));
+      continue;
+    }
+    s = sp.lane ? st->lane_stream[side] : caller;
     const void *tab = tables + sp.table_off;
     hipEvent_t ev_end = nullptr;
     if (st->prof_on) {

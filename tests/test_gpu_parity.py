@@ -92,6 +92,19 @@ def test_dlrm_bf16_small():
                 top=(128, 64, 1)))
 
 
+def test_dlrm_embedding_bags_on_the_side_stream():
+    # stage flag bit 3: gather and sort + segment sums on the stage's side stream next to the dense branches;
+    # same kernels, same order per stream, so the results are those of the one-stream run bit for bit
+    wl = W.dlrm(micro_batch=256, n_micro=3, n_tables=6, num_rows=5000, bottom=(64, 32, 128), top=(128, 64, 1))
+    both(wl, flags=B.FLAG_SIDE_STREAM)
+    res_a, g_a = run_gpu(wl)
+    res_b, g_b = run_gpu(wl, flags=B.FLAG_SIDE_STREAM, slots=2)
+    for i in g_a:
+        for k in g_a[i]:
+            assert np.array_equal(g_a[i][k], g_b[i][k]), (i, k)
+    assert [r["loss"] for r in res_a] == [r["loss"] for r in res_b]
+
+
 def test_dlrm_bf16_eleven_tables_ragged_bags():
     # eight or more tables: the gather's workgroups are laid out per table (eight tables bound to one XCD each,
     # three spread over all); 130 bags leave the last workgroup of every table half empty
