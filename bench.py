@@ -117,7 +117,7 @@ MEASURED_TRAFFIC = {
     ("candle_uno", "gemm_big_dw"): 122.1e6,      # the grouped launch: eight slots, every Linear of the stage
     ("hetero", "gemm_bwd_merged_dx_dw"): 122.0e6,
     ("hetero", "gemm_skinny_fwd"): 48.8e6,
-    ("mmt", "gemm_big_fwd"): 187.2e6,
+    ("mmt", "gemm_big_fwd"): 193.4e6,
     ("mmt", "gemm_big_dx"): 168.1e6,
     ("mmt", "gemm_big_dw"): 190.0e6,
     ("dlrm", "embedding_bwd_sort_segsum"): 54.3e6,
