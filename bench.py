@@ -109,6 +109,9 @@ def other_traffic(wl):
 # HBM bytes per launch of the dominant kernel of each workload, from two rocprofv3 --pmc runs
 # (FETCH_SIZE, then WRITE_SIZE) scaled by what the same counters read for a copy of known size
 # (--copy-calibration); the summaries are kept under profiles/.  None where not measured.
+AUTO_SHARED_LANES = True   # fw_j and bw_j of a micro-batch on one stream: a chain of launches per micro-batch
+AUTO_LANES = (4, 4)     # --lanes auto, where the stage allows several streams per direction
+
 MEASURED_TRAFFIC = {
     # bytes per launch, averaged over the launches of the kernel family within a step
     ("candle_uno", "gemm_bwd_merged_dx_dw"): 50.5e6,
@@ -139,6 +142,11 @@ def main():
     ap.add_argument("--grouped-dw", default="auto", choices=["auto", "on", "off"],
                     help="weight gradients of each run of backward passes in one launch over the run's stash slots "
                          "(gpp_stage_backward_weights); auto: on with the kfkb schedule")
+    ap.add_argument("--lanes", default="auto", metavar="F,B",
+                    help="--schedule kfkb: streams for the forward and for the backward passes (pass j on stream j mod F / B); "
+                         "auto: 4,4 where the stage allows several streams per direction (gpp_stage_lanes), else 1")
+    ap.add_argument("--shared-lanes", default="auto", choices=["auto", "on", "off"],
+                    help="--lanes F,F: the backward passes use the forward streams (one chain of launches per micro-batch)")
     ap.add_argument("--one-stream", action="store_true", help="--schedule kfkb: all tasks on one stream, in task order")
     ap.add_argument("--schedule", default="auto", choices=["auto", "serial", "overlap", "kfkb"],
                     help="micro-batch schedule of a step: serial = fw_k bw_k in turn on one stream; overlap = fw_{k+1} "
@@ -194,15 +202,29 @@ def main():
     losses = [torch.zeros(1, dtype=torch.float32, device=st.dev) for _ in range(max(n_slots, 2))]
     serial = SerialSchedule(st)
     sched = OverlapSchedule(st) if overlap else serial
+    lanes = (1, 1)
+    if kfkb and not args.one_stream:
+        ok_f, ok_b = B.gpp_stage_lanes(st.handle)
+        if args.lanes == "auto":
+            lanes = (AUTO_LANES[0] if ok_f else 1, AUTO_LANES[1] if ok_b else 1)
+        else:
+            lanes = tuple(int(v) for v in args.lanes.split(","))
+        lanes = (max(1, min(lanes[0], n_slots)), max(1, min(lanes[1], n_slots)))
+    shared_lanes = lanes[0] == lanes[1] and lanes[0] > 1 and (args.shared_lanes == "on" or (args.shared_lanes == "auto" and AUTO_SHARED_LANES))
+    gins_sched = gins
+    if lanes[1] > 1:     # backward passes on different streams may overlap: a set of gradient-input buffers each
+        gins_sched = [gins] + [st.alloc_grad_inputs() for _ in range(lanes[1] - 1)]
     if kfkb:
-        sched = TaskSchedule(st, n_slots * wl.micro_batch, args.k, two_streams=not args.one_stream)
+        sched = TaskSchedule(st, n_slots * wl.micro_batch, args.k, two_streams=not args.one_stream, lanes=lanes,
+                             shared_lanes=shared_lanes)
 
     def eager_step(schedule=None):
         schedule = schedule or sched
         if schedule is serial:
             schedule.minibatch(dev_batches, outputs=outs[0], grad_outputs=gouts, grad_inputs=gins, losses=losses[:1])
         else:
-            schedule.minibatch(dev_batches, outputs=outs, grad_outputs=gouts, grad_inputs=gins, losses=losses)
+            schedule.minibatch(dev_batches, outputs=outs, grad_outputs=gouts, grad_inputs=gins_sched if schedule is sched else gins,
+                               losses=losses)
 
     step = eager_step
 
@@ -213,7 +235,7 @@ def main():
         if sched is serial:
             graphed = GraphedMinibatch(sched, dev_batches, outputs=outs[0], grad_outputs=gouts, grad_inputs=gins, losses=losses[:1])
         else:
-            graphed = GraphedMinibatch(sched, dev_batches, outputs=outs, grad_outputs=gouts, grad_inputs=gins, losses=losses)
+            graphed = GraphedMinibatch(sched, dev_batches, outputs=outs, grad_outputs=gouts, grad_inputs=gins_sched, losses=losses)
         step = graphed.replay       # the timed steps replay the graph
 
     if args.copy_calibration:
@@ -368,7 +390,9 @@ def main():
         "config": {"workload": f"{args.config}: micro-batch {wl.micro_batch} x {wl.n_micro} micro-batches per step",
                    "micro_batch": wl.micro_batch, "micro_batches_per_step": wl.n_micro,
                    "schedule": (f"kFkB from the scheduler: i = {n_slots * wl.micro_batch} samples ({n_slots} micro-batches in flight), k = {args.k}, "
-                                + ("one stream" if args.one_stream else "forward and backward passes on two streams")) if kfkb else
+                                + ("one stream" if args.one_stream else
+                                   (f"micro-batch j on stream j mod {lanes[0]} (forward and backward pass)" if shared_lanes else
+                                    f"forward passes on {lanes[0]} stream(s), backward passes on {lanes[1]} other stream(s)"))) if kfkb else
                                (f"overlap: forward calls on one stream, backward calls on another, {n_slots} in-flight slots" if overlap else "serial"),
                    "stash_bytes_per_slot": B.gpp_stage_memory(st.handle)[0],
                    "peak_stash_bytes": n_slots * B.gpp_stage_memory(st.handle)[0],

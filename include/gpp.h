@@ -249,6 +249,24 @@ gpp_status_t gpp_stage_run_schedule(gpp_stage_t *stage, const int32_t *tasks, in
                                     const gpp_microbatch_io_t *io, int64_t n_micro, void *stream_forward,
                                     void *stream_backward);
 
+/* gpp_stage_run_schedule with several streams per direction: forward pass j is enqueued on
+ * streams_forward[j % n_forward], backward pass j on streams_backward[j % n_backward] (HOST arrays of HIP
+ * streams, 1 to 16 each).  Micro-batches are independent computations (section 2: operators without a path
+ * between them may run concurrently), so on a GPU that one few-row micro-batch cannot fill, neighbouring
+ * passes of a kFkB group overlap.  C4 still governs everything whose ORDER can be observed: tasks are issued
+ * in list order, a slot is reused only after its backward pass (and group launch), and the weight-gradient
+ * launches add into the accumulators in list order, so every result is bit-identical to the one-stream run.
+ *   n_forward > 1    needs forward steps that touch no memory shared between slots
+ *   n_backward > 1   needs backward steps that touch no shared memory and accumulate no parameter gradient
+ *                    themselves: Linear-only stages created with grouped weight gradients (flag bit 2)
+ *   otherwise GPP_ERR_UNSUPPORTED (nothing has run).  gpp_stage_lanes reports both properties.
+ * Micro-batches that may be in flight together need their own outputs, loss_out and grad_inputs buffers
+ * (passes j and j' share a stream, hence run in order, when j = j' modulo the lane count).
+ * Ordering against work on other streams before and after the call is the caller's, on every stream. */
+gpp_status_t gpp_stage_run_schedule_lanes(gpp_stage_t *stage, const int32_t *tasks, int64_t n_tasks,
+                                          const gpp_microbatch_io_t *io, int64_t n_micro, void *const *streams_forward,
+                                          int32_t n_forward, void *const *streams_backward, int32_t n_backward);
+
 /* Workspace use: bytes of ONE activation stash slot (the memory an in-flight micro-batch pins, section 2),
  * bytes shared by all slots (backward scratch, launch tables, sort buffers), and their total for this
  * stage's in_flight_slots.  Any pointer may be NULL. */
@@ -323,6 +341,8 @@ gpp_status_t gpp_pipeline_destroy(gpp_pipeline_t *pipeline);
 /* Introspection (tests, benchmarks). */
 /* micro-batch size, number of stash slots and flags the stage was created with (any pointer may be NULL) */
 gpp_status_t gpp_stage_info(const gpp_stage_t *stage, int64_t *micro_batch, int32_t *in_flight_slots, int32_t *flags);
+/* whether several forward / backward streams are allowed in gpp_stage_run_schedule_lanes (1) or not (0) */
+gpp_status_t gpp_stage_lanes(const gpp_stage_t *stage, int32_t *forward_ok, int32_t *backward_ok);
 /* rows, features and gpp_dtype_t of the index-th input (is_output = 0) or output (1), and whether a gradient
  * flows through it (an input that returns one / an output that expects one) */
 gpp_status_t gpp_stage_io_info(const gpp_stage_t *stage, int32_t is_output, int32_t index, int64_t *rows,

@@ -54,6 +54,7 @@ EXPORTS = [
     "gpp_stage_embedding_sort_result", "gpp_last_error", "gpp_stage_profile_enable", "gpp_stage_profile_read",
     "gpp_profile_tag_name", "gpp_compute_in_flight", "gpp_assign_schedules", "gpp_schedule_tasks",
     "gpp_stage_run_schedule", "gpp_stage_memory", "gpp_stage_backward_weights", "gpp_stage_info", "gpp_stage_io_info",
+    "gpp_stage_run_schedule_lanes", "gpp_stage_lanes",
     "gpp_partition", "gpp_pipeline_workspace_bytes", "gpp_pipeline_create", "gpp_pipeline_run", "gpp_pipeline_destroy",
 ]
 GPP_PROFILE_TAGS = 32
@@ -119,6 +120,10 @@ def load():
     lib.gpp_schedule_tasks.restype, lib.gpp_schedule_tasks.argtypes = i32, [i64, i64, i64, i64, C.POINTER(i32)]
     lib.gpp_stage_run_schedule.restype = i32
     lib.gpp_stage_run_schedule.argtypes = [vp, C.POINTER(i32), i64, C.POINTER(MicrobatchIO), i64, vp, vp]
+    lib.gpp_stage_run_schedule_lanes.restype = i32
+    lib.gpp_stage_run_schedule_lanes.argtypes = [vp, C.POINTER(i32), i64, C.POINTER(MicrobatchIO), i64, C.POINTER(vp), i32,
+                                                 C.POINTER(vp), i32]
+    lib.gpp_stage_lanes.restype, lib.gpp_stage_lanes.argtypes = i32, [vp, C.POINTER(i32), C.POINTER(i32)]
     lib.gpp_stage_memory.restype, lib.gpp_stage_memory.argtypes = i32, [vp] + [C.POINTER(C.c_size_t)] * 3
     lib.gpp_stage_info.restype = i32
     lib.gpp_stage_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i32), C.POINTER(i32)]
@@ -277,6 +282,24 @@ def gpp_stage_run_schedule(handle, tasks, io, stream_forward, stream_backward):
     t = (C.c_int32 * max(1, len(tasks)))(*tasks)
     _check(load().gpp_stage_run_schedule(handle, t, len(tasks), ios, len(io), stream_forward, stream_backward))
     return keep
+
+
+def gpp_stage_run_schedule_lanes(handle, tasks, io, streams_forward, streams_backward):
+    """gpp_stage_run_schedule with lists of streams: pass j of a direction goes to stream j % len(list)."""
+    keep = []
+    ios = _marshal_io(io, keep)
+    t = (C.c_int32 * max(1, len(tasks)))(*tasks)
+    sf, sb = _ptr_array(streams_forward), _ptr_array(streams_backward)
+    _check(load().gpp_stage_run_schedule_lanes(handle, t, len(tasks), ios, len(io), sf, len(streams_forward), sb,
+                                               len(streams_backward)))
+    return keep
+
+
+def gpp_stage_lanes(handle):
+    """(several forward streams allowed, several backward streams allowed)."""
+    f, b = C.c_int32(), C.c_int32()
+    _check(load().gpp_stage_lanes(handle, C.byref(f), C.byref(b)))
+    return bool(f.value), bool(b.value)
 
 
 def _marshal_io(io, keep):

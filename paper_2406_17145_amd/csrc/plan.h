@@ -76,6 +76,9 @@ struct Plan {
   int loss_parts = 0;
   std::vector<Step> fwd, bwd;
   bool lanes = false;                // the step lists hold side-stream steps: the stage needs its side streams
+  // the forward (backward) steps touch workspace memory that all slots share: passes of different
+  // micro-batches must then run one after the other
+  bool fwd_shared = false, bwd_shared = false;
   std::vector<Step> dwg;             // weight gradients of a group of backward passes (flag bit 2), slot 0's tables
   std::vector<uint8_t> blob;         // tables of the slot being emitted
   std::string error;

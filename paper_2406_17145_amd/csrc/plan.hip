@@ -413,6 +413,9 @@ struct Emitter {
     if (!b.valid()) return nullptr;
     if (b.space == SP_ABS) return (void *)b.off;
     if (b.space == SP_SLOT) return ws + pl.off_slots + (int64_t)slot * pl.slot_bytes + b.off;
+    // memory every slot shares: passes of different slots that use it may not overlap
+    if (steps == &pl.fwd) pl.fwd_shared = true;
+    else if (steps == &pl.bwd) pl.bwd_shared = true;
     return ws + pl.off_shared + b.off;
   }
   template <typename T>
@@ -518,6 +521,7 @@ struct Emitter {
     }
     bool vec = true;
     for (auto &e : embs) vec = vec && emb_vec_supported(e);
+    pl.bwd_shared = true;   // accumulates parameter gradients in the order of the backward passes
     Step &s = add_step(K_EMB_BWD, push_table(embs), (int)embs.size(), 0);
     s.a0 = cap;
     s.a1 = sb;
@@ -827,6 +831,7 @@ struct Emitter {
             // rows of the streamed operands that one tile covers: the output's rows for FWD / DX
             r.split_k = (pl.flags & 2) ? gemm_mfma_pick_split(tile, launch_tiles, form == FORM_DW ? tile : r.M, r.K) : 1;
             if (r.split_k > 1) {  // partial tiles and arrival counters live behind the shared region
+              pl.fwd_shared = pl.bwd_shared = true;
               r.partial = (float *)(ws + pl.off_shared + pl.shared_bytes + pl.tmp_bytes + part_off);
               r.counters = (int32_t *)(ws + pl.off_shared + pl.shared_bytes + pl.tmp_bytes + pl.gemm_partial_bytes + cnt_off);
               part_off += (int64_t)tiles * r.split_k * gemm_mfma_partial_floats(tile) * 4;
@@ -1368,7 +1373,10 @@ void Emitter::backward() {
             c.cols = (int32_t)nd.feat;
             colsums.push_back(c);
           }
-          if (!grouped) gemms.push_back(w);
+          if (!grouped) {
+            gemms.push_back(w);
+            pl.bwd_shared = true;   // accumulates into the parameter's gradient: backward passes stay in order
+          }
           if (x.wants_grad) {
             Target tg = acquire(nd.in[0], true);
             GemmProb g;
@@ -1550,6 +1558,7 @@ void Emitter::backward() {
         c.blk_begin = blocks;
         blocks += colsum_blocks(c.cols);
       }
+      pl.bwd_shared = true;   // accumulates parameter gradients in the order of the backward passes
       add_step(K_COLSUM, push_table(colsums), (int)colsums.size(), blocks);
     }
     emit_gemms(gemms);
@@ -1583,6 +1592,7 @@ void Emitter::backward() {
         l.blk_begin = blocks;
         blocks += ln_param_blocks(l.d);
       }
+      pl.bwd_shared = true;   // accumulates parameter gradients in the order of the backward passes
       add_step(K_LN_BWD_PARAMS, push_table(lns), (int)lns.size(), blocks);
     }
     if (!attns.empty()) {

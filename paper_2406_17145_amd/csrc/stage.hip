@@ -235,6 +235,12 @@ gpp_status_t gpp_stage_info(const gpp_stage_t *s, int64_t *micro_batch, int32_t 
   if (flags) *flags = s->plan.flags;
   return GPP_OK;
 }
+gpp_status_t gpp_stage_lanes(const gpp_stage_t *s, int32_t *forward_ok, int32_t *backward_ok) {
+  if (!s) return fail(GPP_ERR_INVALID_ARG, "stage is null");
+  if (forward_ok) *forward_ok = !(s->plan.fwd_shared || s->plan.lanes);
+  if (backward_ok) *backward_ok = !(s->plan.bwd_shared || s->plan.lanes);
+  return GPP_OK;
+}
 gpp_status_t gpp_stage_io_info(const gpp_stage_t *s, int32_t is_output, int32_t index, int64_t *rows, int64_t *features,
                                int32_t *dtype, int32_t *has_grad) {
   if (!s) return fail(GPP_ERR_INVALID_ARG, "stage is null");
@@ -488,13 +494,30 @@ gpp_status_t gpp_stage_memory(const gpp_stage_t *st, size_t *slot_bytes, size_t 
 
 // One mini-batch under a task list.  The whole list is checked against C4 and the number of stash
 // slots before the first kernel is enqueued, so a refused list leaves the stage untouched.
-gpp_status_t gpp_stage_run_schedule(gpp_stage_t *st, const int32_t *tasks, int64_t n_tasks, const gpp_microbatch_io_t *io,
-                                    int64_t n_micro, void *stream_forward, void *stream_backward) {
+//
+// Lanes: forward pass j goes to forward stream j mod nf, backward pass j to backward stream j mod nb.
+// Passes of different micro-batches have no data in common when the stage's steps use slot memory
+// only (and, for backward passes, leave every parameter gradient to the group launch), so several
+// lanes only change WHEN the kernels run: the task list still fixes the order of issue, the use of
+// the stash slots, and the order in which the group launches add into the accumulators.
+// Events per micro-batch j: 3j forward done, 3j+1 slot free again, 3j+2 backward done.
+static gpp_status_t run_schedule_lanes(gpp_stage_t *st, const int32_t *tasks, int64_t n_tasks, const gpp_microbatch_io_t *io,
+                                       int64_t n_micro, void *const *streams_forward, int32_t nf, void *const *streams_backward,
+                                       int32_t nb) {
   if (!st) return fail(GPP_ERR_INVALID_ARG, "stage is null");
   if (n_micro < 0 || n_tasks != 2 * n_micro) return fail(GPP_ERR_INVALID_ARG, "a mini-batch of n micro-batches has 2n tasks");
   if (n_micro > 0 && (!tasks || !io)) return fail(GPP_ERR_INVALID_ARG, "tasks or io is null");
+  if (nf < 1 || nb < 1 || nf > 16 || nb > 16 || !streams_forward || !streams_backward)
+    return fail(GPP_ERR_INVALID_ARG, "1 to 16 forward streams and 1 to 16 backward streams");
   if (!st->fifo.empty() || !st->pending.empty()) return fail(GPP_ERR_ORDER, "run_schedule while a micro-batch is in flight");
-  const int slots = st->plan.slots;
+  const Plan &pl = st->plan;
+  if (nf > 1 && (pl.fwd_shared || pl.lanes))
+    return fail(GPP_ERR_UNSUPPORTED, "forward passes of this stage use memory that its slots share: one forward stream only");
+  if (nb > 1 && (pl.bwd_shared || pl.lanes))
+    return fail(GPP_ERR_UNSUPPORTED,
+                "backward passes of this stage accumulate parameter gradients or use memory that its slots share "
+                "(grouped weight gradients, stage flag bit 2, lift this for Linear layers): one backward stream only");
+  const int slots = pl.slots;
   {
     int64_t f = 0, b = 0;   // forward / backward passes seen so far
     for (int64_t t = 0; t < n_tasks; ++t) {
@@ -514,52 +537,78 @@ gpp_status_t gpp_stage_run_schedule(gpp_stage_t *st, const int32_t *tasks, int64
       }
     }
   }
-  hipStream_t sf = (hipStream_t)stream_forward, sb = (hipStream_t)stream_backward;
-  const bool two = sf != sb;
+  bool two = false;   // more than one stream in play: order across streams comes from events
+  for (int k = 0; k < nf; ++k) two = two || streams_forward[k] != streams_forward[0];
+  for (int k = 0; k < nb; ++k) two = two || streams_backward[k] != streams_forward[0];
   if (two) {
-    while ((int64_t)st->sched_ev.size() < 2 * n_micro) {
+    while ((int64_t)st->sched_ev.size() < 3 * n_micro) {
       hipEvent_t e;
       if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return fail(GPP_ERR_DEVICE, "hipEventCreate failed");
       st->sched_ev.push_back(e);
     }
   }
-  gpp_status_t rc = gpp_stage_grad_reset(st, sb);
+  gpp_status_t rc = gpp_stage_grad_reset(st, streams_backward[0]);
   if (rc != GPP_OK) return rc;
+  int64_t last_group = -1;   // micro-batch whose slot-free event follows the latest group launch
   for (int64_t t = 0; t < n_tasks; ++t) {
     const int64_t j = (tasks[t] > 0 ? tasks[t] : -tasks[t]) - 1;
     const int32_t slot = (int32_t)(j % slots);
     const gpp_microbatch_io_t &m = io[j];
     hipError_t he = hipSuccess;
     if (tasks[t] > 0) {
+      hipStream_t sf = (hipStream_t)streams_forward[j % nf];
       // the slot's previous micro-batch must have been consumed by its backward pass
-      if (two && j >= slots) he = hipStreamWaitEvent(sf, st->sched_ev[2 * (j - slots) + 1], 0);
+      if (two && j >= slots) he = hipStreamWaitEvent(sf, st->sched_ev[3 * (j - slots) + 1], 0);
       if (he == hipSuccess) {
         rc = gpp_stage_forward(st, slot, m.inputs, m.outputs, m.loss_out, sf);
         if (rc != GPP_OK) return rc;
-        if (two) he = hipEventRecord(st->sched_ev[2 * j], sf);
+        if (two) he = hipEventRecord(st->sched_ev[3 * j], sf);
       }
     } else {
-      if (two) he = hipStreamWaitEvent(sb, st->sched_ev[2 * j], 0);
+      hipStream_t sb = (hipStream_t)streams_backward[j % nb];
+      // (a backward pass on its forward pass's own stream follows it there without an event)
+      if (two && (void *)sb != streams_forward[j % nf]) he = hipStreamWaitEvent(sb, st->sched_ev[3 * j], 0);
       if (he == hipSuccess) {
         rc = gpp_stage_backward(st, slot, m.grad_outputs, m.grad_inputs, sb);
         if (rc != GPP_OK) return rc;
         // grouped weight gradients: one launch after the last backward pass of a run of backward
         // tasks; only then are the run's slots free for the forward passes that wait for them
         const bool run_ends = t + 1 == n_tasks || tasks[t + 1] > 0;
-        if (!st->pending.empty() && run_ends) {
+        if (st->pending.empty()) {
+          if (two) he = hipEventRecord(st->sched_ev[3 * j + 1], sb);
+        } else if (!run_ends) {
+          if (nb > 1) he = hipEventRecord(st->sched_ev[3 * j + 2], sb);
+        } else {
           const int64_t run = (int64_t)st->pending.size();
-          rc = gpp_stage_backward_weights(st, sb);
-          if (rc != GPP_OK) return rc;
+          // the launch follows every backward pass of its run (other lanes: their events) and the
+          // group launch before it (both add into the same accumulators)
+          for (int64_t q = j - run + 1; q < j && he == hipSuccess; ++q)
+            if (nb > 1 && streams_backward[q % nb] != (void *)sb) he = hipStreamWaitEvent(sb, st->sched_ev[3 * q + 2], 0);
+          if (nb > 1 && last_group >= 0 && he == hipSuccess) he = hipStreamWaitEvent(sb, st->sched_ev[3 * last_group + 1], 0);
+          if (he == hipSuccess) {
+            rc = gpp_stage_backward_weights(st, sb);
+            if (rc != GPP_OK) return rc;
+          }
           if (two)
-            for (int64_t q = j - run + 1; q <= j && he == hipSuccess; ++q) he = hipEventRecord(st->sched_ev[2 * q + 1], sb);
-        } else if (two && st->pending.empty()) {
-          he = hipEventRecord(st->sched_ev[2 * j + 1], sb);
+            for (int64_t q = j - run + 1; q <= j && he == hipSuccess; ++q) he = hipEventRecord(st->sched_ev[3 * q + 1], sb);
+          last_group = j;
         }
       }
     }
     if (he != hipSuccess) return fail(GPP_ERR_DEVICE, std::string("HIP event: ") + hipGetErrorString(he));
   }
   return GPP_OK;
+}
+
+gpp_status_t gpp_stage_run_schedule(gpp_stage_t *st, const int32_t *tasks, int64_t n_tasks, const gpp_microbatch_io_t *io,
+                                    int64_t n_micro, void *stream_forward, void *stream_backward) {
+  return run_schedule_lanes(st, tasks, n_tasks, io, n_micro, &stream_forward, 1, &stream_backward, 1);
+}
+
+gpp_status_t gpp_stage_run_schedule_lanes(gpp_stage_t *st, const int32_t *tasks, int64_t n_tasks, const gpp_microbatch_io_t *io,
+                                          int64_t n_micro, void *const *streams_forward, int32_t n_forward,
+                                          void *const *streams_backward, int32_t n_backward) {
+  return run_schedule_lanes(st, tasks, n_tasks, io, n_micro, streams_forward, n_forward, streams_backward, n_backward);
 }
 
 gpp_status_t gpp_stage_sync_status(gpp_stage_t *st, void *hip_stream) {

@@ -84,9 +84,12 @@ class TaskSchedule:
     i / b forward passes, then k backward and k forward passes in turn, cool-down.  The stage must have been
     created with at least i / b stash slots.  With two_streams the forward passes go to one stream and the
     backward passes to another (C4 allows them to overlap); otherwise everything runs in task order on the
-    current stream."""
+    current stream.  lanes = (forward streams, backward streams): passes of neighbouring micro-batches go to
+    different streams (gpp_stage_run_schedule_lanes; the stage must allow it, see gpp_stage_lanes); with
+    shared_lanes the backward passes use the forward streams (fw_j and bw_j of a micro-batch then follow each
+    other on ONE stream: no event between them, one chain of launches per micro-batch)."""
 
-    def __init__(self, stage, in_flight_samples, k, two_streams=True):
+    def __init__(self, stage, in_flight_samples, k, two_streams=True, lanes=(1, 1), shared_lanes=False):
         from . import binding as B
         torch = stage.torch
         self.B, self.st = B, stage
@@ -95,9 +98,18 @@ class TaskSchedule:
         if stage.slots < cap:
             raise ValueError(f"{cap} micro-batches in flight need a stage with in_flight_slots >= {cap}")
         self.two = bool(two_streams)
-        if self.two:
-            self.s_f = torch.cuda.Stream(device=stage.dev)   # default priority on both
-            self.s_b = torch.cuda.Stream(device=stage.dev)
+        self.lanes = (int(lanes[0]), int(lanes[1]))
+        if self.lanes != (1, 1) and not self.two:
+            raise ValueError("lanes need two_streams")
+        if self.two:                                         # default priority on all
+            self.fw_streams = [torch.cuda.Stream(device=stage.dev) for _ in range(self.lanes[0])]
+            if shared_lanes:
+                if self.lanes[0] != self.lanes[1]:
+                    raise ValueError("shared lanes: as many backward as forward streams")
+                self.bw_streams = self.fw_streams
+            else:
+                self.bw_streams = [torch.cuda.Stream(device=stage.dev) for _ in range(self.lanes[1])]
+            self.s_f, self.s_b = self.fw_streams[0], self.bw_streams[0]
         self._keep = None
 
     def tasks(self, n_micro):
@@ -111,8 +123,9 @@ class TaskSchedule:
         st, torch, B = self.st, self.st.torch, self.B
         if outputs is None:
             outputs = self._outs = getattr(self, "_outs", None) or [st.alloc_outputs() for _ in range(st.slots)]
-        if grad_inputs is None:
-            grad_inputs = self._gin = getattr(self, "_gin", None) or st.alloc_grad_inputs()
+        if grad_inputs is None:     # one set per backward stream: passes on different streams may overlap
+            grad_inputs = self._gin = getattr(self, "_gin", None) or (
+                st.alloc_grad_inputs() if self.lanes[1] == 1 else [st.alloc_grad_inputs() for _ in range(self.lanes[1])])
         if losses is None:
             losses = [st.loss]
 
@@ -128,15 +141,19 @@ class TaskSchedule:
         tasks = self.tasks(len(batches))
         main = torch.cuda.current_stream(st.dev)
         if self.two:
-            self.s_f.wait_stream(main)
-            self.s_b.wait_stream(main)
-            sf, sb = self.s_f.cuda_stream, self.s_b.cuda_stream
+            every = list(dict.fromkeys(self.fw_streams + self.bw_streams))
+            for s in every:
+                s.wait_stream(main)
+            if self.lanes == (1, 1):
+                keep = B.gpp_stage_run_schedule(st.handle, tasks, io, self.s_f.cuda_stream, self.s_b.cuda_stream)
+            else:
+                keep = B.gpp_stage_run_schedule_lanes(st.handle, tasks, io, [s.cuda_stream for s in self.fw_streams],
+                                                      [s.cuda_stream for s in self.bw_streams])
+            for s in every:
+                main.wait_stream(s)
         else:
-            sf = sb = main.cuda_stream
-        self._keep = (B.gpp_stage_run_schedule(st.handle, tasks, io, sf, sb), batches, outputs, grad_outputs, grad_inputs, losses)
-        if self.two:
-            main.wait_stream(self.s_f)
-            main.wait_stream(self.s_b)
+            keep = B.gpp_stage_run_schedule(st.handle, tasks, io, main.cuda_stream, main.cuda_stream)
+        self._keep = (keep, batches, outputs, grad_outputs, grad_inputs, losses)
         return tasks
 
 

@@ -17,7 +17,7 @@ def _codes(tasks):
     return [(j + 1) if w == "F" else -(j + 1) for w, j in tasks]
 
 
-def _run(wl, cap, k, two_streams, slots=None, gouts=None, reps=1, flags=0):
+def _run(wl, cap, k, two_streams, slots=None, gouts=None, reps=1, flags=0, lanes=(1, 1), shared_lanes=False):
     import torch
     st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=slots or cap, flags=flags)
     n = len(wl.batches)
@@ -26,7 +26,7 @@ def _run(wl, cap, k, two_streams, slots=None, gouts=None, reps=1, flags=0):
     outs = [st.alloc_outputs() for _ in range(n)]
     gins = [st.alloc_grad_inputs() for _ in range(n)]
     dg = None if gouts is None else [[st.to_device(i, g[i]) for i in st.output_ids] for g in gouts]
-    sched = TaskSchedule(st, cap * wl.micro_batch, k, two_streams=two_streams)
+    sched = TaskSchedule(st, cap * wl.micro_batch, k, two_streams=two_streams, lanes=lanes, shared_lanes=shared_lanes)
     for _ in range(reps):
         tasks = sched.minibatch(dev_batches, outputs=outs, grad_outputs=dg, grad_inputs=gins, losses=losses)
     st.sync_status()
@@ -138,8 +138,9 @@ def test_stage_memory_report():
 
 def test_config2_full_size_in_the_launch_configuration_the_benchmark_times():
     # the benchmark's default step: the full CANDLE-Uno-shaped stage, a stash slot per micro-batch, the scheduler's
-    # task list for that many in-flight micro-batches run by the executor on two streams, weight gradients of the
-    # whole run of backward passes in one grouped launch, everything captured once into a HIP graph and replayed.
+    # task list for that many in-flight micro-batches run by the executor with micro-batch j on stream j mod 4
+    # (forward and backward pass), weight gradients of the whole run of backward passes in one grouped launch,
+    # everything captured once into a HIP graph and replayed.
     # Checked against the oracle in full (losses, input gradients, every accumulated gradient); every replay
     # (accumulators poisoned, eager work and synchronisations in between) must reproduce the eager run of the
     # same configuration bit for bit.
@@ -154,7 +155,7 @@ def test_config2_full_size_in_the_launch_configuration_the_benchmark_times():
     dev_batches = [st.stage_inputs(mb) for mb in wl.batches]
     losses = [torch.zeros(1, dtype=torch.float32, device=st.dev) for _ in range(n)]
     gins = [st.alloc_grad_inputs() for _ in range(n)]
-    sched = TaskSchedule(st, n * wl.micro_batch, n, two_streams=True)
+    sched = TaskSchedule(st, n * wl.micro_batch, n, two_streams=True, lanes=(4, 4), shared_lanes=True)
     outs = [[] for _ in range(n)]
     sched.minibatch(dev_batches, outputs=outs, grad_inputs=gins, losses=losses)     # eager first
     st.sync_status()
@@ -291,4 +292,120 @@ def test_executor_with_no_micro_batches_is_a_gradient_reset():
     st.forward(0, wl.batches[0])          # the stage is usable afterwards
     st.backward(0)
     st.sync_status()
+    st.close()
+
+
+# ---- several streams per direction (gpp_stage_run_schedule_lanes) ------------------------------------
+
+def _same(res_a, grads_a, res_b, grads_b, label):
+    for j, (a, b) in enumerate(zip(res_a, res_b)):
+        assert a["loss"] == b["loss"], (label, j)
+        for kind in ("outs", "gin"):
+            for i in a[kind]:
+                assert np.array_equal(a[kind][i], b[kind][i]), (label, j, kind, i)
+    for i in grads_a:
+        for kk in grads_a[i]:
+            assert np.array_equal(grads_a[i][kk], grads_b[i][kk]), (label, i, kk)
+
+
+def test_lanes_give_the_one_stream_results_bit_for_bit():
+    wl = W.candle_uno(micro_batch=48, n_micro=7, widths=(70, 131, 9, 33), hidden=160, act="gelu")
+    ora_stage, ora_res = run_oracle(wl)
+    for cap, k in [(7, 7), (4, 4), (5, 3), (3, 2)]:
+        _, res1, grads1 = _run(wl, cap, k, False, reps=2, flags=B.FLAG_GROUPED_DW)
+        compare(wl, res1, grads1, ora_stage, ora_res, label=f"one stream cap={cap} k={k}")
+        for lanes in [(2, 1), (1, 2), (2, 2), (3, 2), (4, 4)]:
+            print(f"[case] {wl.name} lanes={lanes} cap={cap} k={k}", flush=True)
+            _, res, grads = _run(wl, cap, k, True, reps=2, flags=B.FLAG_GROUPED_DW, lanes=lanes)
+            _same(res, grads, res1, grads1, f"lanes={lanes} cap={cap} k={k}")
+        for n in (2, 4):       # the backward passes on the forward streams: one chain of launches per micro-batch
+            print(f"[case] {wl.name} {n} shared lanes cap={cap} k={k}", flush=True)
+            _, res, grads = _run(wl, cap, k, True, reps=2, flags=B.FLAG_GROUPED_DW, lanes=(n, n), shared_lanes=True)
+            _same(res, grads, res1, grads1, f"shared lanes={n} cap={cap} k={k}")
+
+
+def test_lanes_on_a_mid_pipeline_stage():
+    wl = W.hetero(micro_batch=9, n_micro=6, base_width=16, out_width=24, dtype="bf16", with_loss=False)
+    out = len(wl.ops) - 1
+    rng = np.random.default_rng(11)
+    gouts = [{out: rng.standard_normal((9, 192)).astype(np.float32)} for _ in range(6)]
+    ora_stage, ora_res = run_oracle(wl, gouts)
+    _, res1, grads1 = _run(wl, 4, 2, False, gouts=gouts, flags=B.FLAG_GROUPED_DW)
+    compare(wl, res1, grads1, ora_stage, ora_res, label="mid one stream")
+    for lanes in [(2, 2), (3, 4)]:
+        print(f"[case] {wl.name} mid-pipeline lanes={lanes}", flush=True)
+        _, res, grads = _run(wl, 4, 2, True, gouts=gouts, flags=B.FLAG_GROUPED_DW, lanes=lanes)
+        _same(res, grads, res1, grads1, f"mid lanes={lanes}")
+
+
+def test_lanes_are_refused_where_passes_share_memory_or_accumulate():
+    import torch
+    cases = [
+        (W.candle_uno(micro_batch=16, n_micro=3, widths=(32, 40, 8, 24), hidden=64, act="relu"), 0, (True, False)),
+        (W.candle_uno(micro_batch=16, n_micro=3, widths=(32, 40, 8, 24), hidden=64, act="relu"), B.FLAG_GROUPED_DW, (True, True)),
+        (W.dlrm(micro_batch=32, n_micro=3, n_tables=3, num_rows=500, bottom=(64, 32, 128), top=(128, 64, 1)), B.FLAG_GROUPED_DW, (None, False)),
+        (W.mmt(micro_batch=2, n_micro=3, n_branches=2, seq_len=64, d_model=128, heads=2, n_layers=1, d_ff=256, d_head_out=128, n_classes=10), B.FLAG_GROUPED_DW, (None, False)),
+    ]
+    for wl, flags, (want_f, want_b) in cases:
+        st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=3, flags=flags)
+        ok_f, ok_b = B.gpp_stage_lanes(st.handle)
+        print(f"[case] {wl.name} flags={flags}: lanes allowed forward={ok_f} backward={ok_b}", flush=True)
+        assert ok_b == want_b and (want_f is None or ok_f == want_f)
+        dev = [st.stage_inputs(mb) for mb in wl.batches]
+        outs = [st.alloc_outputs() for _ in dev]
+        gin = [st.alloc_grad_inputs() for _ in dev]
+        loss = torch.zeros(1, dtype=torch.float32, device=st.dev)
+        io = [([t.data_ptr() for t in mb], [t.data_ptr() for t in outs[j]], loss.data_ptr(), None,
+               [t.data_ptr() if t is not None else None for t in gin[j]]) for j, mb in enumerate(dev)]
+        tasks = B.gpp_schedule_tasks(3, 3 * wl.micro_batch, 3, wl.micro_batch)
+        streams = [torch.cuda.Stream(device=st.dev) for _ in range(4)]
+        sp = [s.cuda_stream for s in streams]
+        for nf, nb, allowed in [(2, 1, ok_f), (1, 2, ok_b)]:
+            if allowed:
+                B.gpp_stage_run_schedule_lanes(st.handle, tasks, io, sp[:nf], sp[2:2 + nb])
+                torch.cuda.synchronize()
+            else:
+                with pytest.raises(B.GppError) as e:
+                    B.gpp_stage_run_schedule_lanes(st.handle, tasks, io, sp[:nf], sp[2:2 + nb])
+                assert e.value.status == B.GPP_ERR_UNSUPPORTED
+        with pytest.raises(B.GppError) as e:
+            B.gpp_stage_run_schedule_lanes(st.handle, tasks, io, [], sp[:1])
+        assert e.value.status == B.GPP_ERR_INVALID_ARG
+        # the stage is untouched by a refusal: one more mini-batch on one stream
+        main = torch.cuda.current_stream(st.dev).cuda_stream
+        B.gpp_stage_run_schedule(st.handle, tasks, io, main, main)
+        st.sync_status()
+        st.close()
+
+
+@pytest.mark.parametrize("lanes,shared", [((2, 3), False), ((4, 4), True)])
+def test_lanes_in_a_captured_graph_replay_like_the_eager_run(lanes, shared):
+    import torch
+    from paper_2406_17145_amd.schedule import GraphedMinibatch
+    wl = W.candle_uno(micro_batch=64, n_micro=6, widths=(70, 131, 9, 33), hidden=160, act="relu")
+    _, res1, grads1 = _run(wl, 6, 6, False, flags=B.FLAG_GROUPED_DW)
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=6, flags=B.FLAG_GROUPED_DW)
+    dev = [st.stage_inputs(mb) for mb in wl.batches]
+    losses = [torch.zeros(1, dtype=torch.float32, device=st.dev) for _ in dev]
+    outs = [st.alloc_outputs() for _ in dev]
+    gins = [st.alloc_grad_inputs() for _ in dev]
+    sched = TaskSchedule(st, 6 * wl.micro_batch, 6, two_streams=True, lanes=lanes, shared_lanes=shared)
+    sched.minibatch(dev, outputs=outs, grad_inputs=gins, losses=losses)
+    torch.cuda.synchronize()
+    g = GraphedMinibatch(sched, dev, outputs=outs, grad_inputs=gins, losses=losses)
+    for rep in range(3):
+        for t in losses:
+            t.zero_()                      # eager work between the replays
+        for row in gins:
+            for t in row:
+                if t is not None:
+                    t.zero_()
+        torch.cuda.synchronize()
+        print(f"[case] captured lanes {lanes} shared={shared}, replay {rep}", flush=True)
+        g.replay()
+        torch.cuda.synchronize()
+        st.sync_status()
+        res = [dict(loss=float(losses[j].cpu()[0]), outs={i: t2n(t) for i, t in zip(st.output_ids, outs[j])},
+                    gin={i: t2n(t) for i, t in zip(st.input_ids, gins[j]) if t is not None}) for j in range(len(dev))]
+        _same(res, st.grads_numpy(), res1, grads1, f"replay {rep}")
     st.close()
