@@ -131,8 +131,8 @@ MEASURED_TRAFFIC = {
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--config", default="candle_uno", choices=["tiny_mlp", "candle_uno", "mmt", "dlrm", "hetero", "paper_mmt", "paper_candle", "paper_dlrm"])
     ap.add_argument("--micro-batch", type=int, default=0, help="override the config's micro-batch size")
     ap.add_argument("--in-flight", type=int, default=0, metavar="M",
@@ -194,7 +194,14 @@ def main():
     # call waits for a backward call (the form a HIP graph can hold, see schedule.py)
     n_slots = min(wl.n_micro, 8) if overlap else (max(1, min(args.in_flight, wl.n_micro)) if kfkb else 1)
     grouped = args.grouped_dw == "on" or (args.grouped_dw == "auto" and kfkb)
-    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=n_slots, flags=(B.FLAG_GROUPED_DW if grouped else 0) | (B.FLAG_SIDE_STREAM if args.side_stream else 0))
+    base_flags = (B.FLAG_GROUPED_DW if grouped else 0) | (B.FLAG_SIDE_STREAM if args.side_stream else 0)
+    # several streams per direction (decided below): the stage's launches then share the GPU, and it is created
+    # with the workgroup sizes for that; whether the stage allows such streams is known once it exists
+    want_lanes = kfkb and not args.one_stream and n_slots > 1 and args.lanes != "1,1"
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=n_slots, flags=base_flags | (B.FLAG_SHARED_GPU if want_lanes else 0))
+    if want_lanes and args.lanes == "auto" and not any(B.gpp_stage_lanes(st.handle)):
+        st.close()
+        st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=n_slots, flags=base_flags)
     dev_batches = [st.stage_inputs(mb) for mb in wl.batches]       # resident in HBM
     outs = [st.alloc_outputs() for _ in range(max(n_slots, 2))]    # one set per in-flight slot
     gins = st.alloc_grad_inputs()
@@ -264,10 +271,11 @@ def main():
             eager_step(serial)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        for _ in range(args.steps):
+        ref_steps = min(args.steps, 200)
+        for _ in range(ref_steps):
             eager_step(serial)
         torch.cuda.synchronize()
-        serial_value = args.steps * samples_per_step / (time.perf_counter() - t1)
+        serial_value = ref_steps * samples_per_step / (time.perf_counter() - t1)
 
     # ---- instrumented pass: per-kernel durations from HIP events on the launch stream ----
     kernels, roofline = {}, None
@@ -351,6 +359,12 @@ def main():
         else:
             roofline = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
                         "traffic": None, "kernel": dom}
+        # the timed step as a whole: algorithmic bytes of every counted kernel over the step time.  The launch
+        # durations above are each kernel ALONE on the GPU (one stream); in the timed step launches of
+        # several streams overlap, so the step moves more bytes per second than its kernels do one by one
+        step_bytes = sum(v[0] for v in alg.values())
+        roofline["step_algorithmic_gbs"] = step_bytes / (dt / args.steps) / 1e9
+        roofline["step_frac_of_hbm_peak"] = roofline["step_algorithmic_gbs"] / HBM_PEAK_GBS
         # every kernel with a known algorithmic count: achieved rates beside the durations
         for name, k in kernels.items():
             if name in alg and k["ms_per_step"] > 0:

@@ -30,6 +30,7 @@ FLAG_FORCE_GENERIC_GEMM = 1
 FLAG_SPLIT_K = 2
 FLAG_GROUPED_DW = 4
 FLAG_SIDE_STREAM = 8
+FLAG_SHARED_GPU = 16
 
 
 class OpDesc(C.Structure):

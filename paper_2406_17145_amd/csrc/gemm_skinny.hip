@@ -49,9 +49,9 @@ struct SkWaves {
 };
 
 // LDS bytes of the few-row body
-template <int FORM, int TI, int TJ>
+template <int FORM, int TI, int TJ, int NW_ = SkWaves<TI>::value>
 struct SkLds {
-  static constexpr int NW = SkWaves<TI>::value;
+  static constexpr int NW = NW_;
   static constexpr int BM = 32 * TI, BN = 32 * TJ;
   static constexpr int RED_FLOATS = (NW / 2) * BM * BN;
   // W tile: forward [BN][64 + 8]; backward-data [64][BN + pad], read with the transposing read.  A
@@ -70,9 +70,9 @@ struct SkLds {
 // round-robin over the 8 XCDs (one L2 each): the column blocks of a record are spread over all of them
 // (a wide problem's weights then stream through every L2 and memory channel), while the row blocks
 // of ONE column block, which read the same slice of W, get ids 8 apart and so meet in one L2.
-template <int FORM, int TI, int TJ>
+template <int FORM, int TI, int TJ, int NW_ = SkWaves<TI>::value>
 __device__ __forceinline__ void gemm_skinny_body(const GemmProb &p, int local, unsigned char *lds_raw, const ExtPtrs &ext) {
-  typedef SkLds<FORM, TI, TJ> L;
+  typedef SkLds<FORM, TI, TJ, NW_> L;
   constexpr int NW = L::NW, BM = L::BM, BN = L::BN, SB = L::SB, WAVE_ELEMS = L::WAVE_ELEMS;
   float *red = (float *)lds_raw;           // after the k-loop: NW/2 BM x BN fp32 buffers
   void *Cout = result_ptr(p, ext);
@@ -200,7 +200,7 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmProb &p, int local, u
 
   // NS register sets rotate: while one step is multiplied, the next NS-1 are on their way from memory
   // (bounded by the register file: 256 VGPRs per lane at 8 waves)
-  constexpr int NS = NW == 8 ? (TI + TJ <= 3 ? 3 : 2) : 3;
+  constexpr int NS = NW == 8 ? (TI + TJ <= 3 ? 3 : 2) : (TI + TJ <= 2 ? 4 : 3);
   SkStep<TI, TJ> f[NS];
 #pragma unroll
   for (int u = 0; u < NS; ++u)
@@ -334,12 +334,12 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmProb &p, int local, u
   }
 }
 
-template <int FORM, int TI, int TJ>
-__global__ __launch_bounds__(64 * SkWaves<TI>::value) void k_gemm_skinny(const GemmProb *__restrict__ probs, int n, ExtPtrs ext) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[SkLds<FORM, TI, TJ>::BYTES];
+template <int FORM, int TI, int TJ, int NW = SkWaves<TI>::value>
+__global__ __launch_bounds__(64 * NW) void k_gemm_skinny(const GemmProb *__restrict__ probs, int n, ExtPtrs ext) {
+  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[SkLds<FORM, TI, TJ, NW>::BYTES];
   const int pi = find_prob(probs, n, blockIdx.x);
   const GemmProb p = probs[pi];
-  gemm_skinny_body<FORM, TI, TJ>(p, blockIdx.x - p.blk_begin, lds_raw, ext);
+  gemm_skinny_body<FORM, TI, TJ, NW>(p, blockIdx.x - p.blk_begin, lds_raw, ext);
 }
 
 // backward of one level in one launch: records with form DX run the few-row body; records with
@@ -381,18 +381,27 @@ int gemm_bwd_merged_dw_blocks(int M, int N) {
 }
 
 template <int FORM>
-static void launch_rows(const GemmProb *probs, int n, int blocks, int row_tiles, int col_tiles, const ExtPtrs &ext, hipStream_t s) {
+static void launch_rows(const GemmProb *probs, int n, int blocks, int row_tiles, int col_tiles, int waves, const ExtPtrs &ext,
+                        hipStream_t s) {
+  if (waves == 4) {   // workgroups sized to share a compute unit with those of concurrent launches
+    const dim3 g4(blocks), b4(256);
+    if (row_tiles == 1 && col_tiles == 1) hipLaunchKernelGGL((k_gemm_skinny<FORM, 1, 1, 4>), g4, b4, 0, s, probs, n, ext);
+    else if (row_tiles == 1) hipLaunchKernelGGL((k_gemm_skinny<FORM, 1, 2, 4>), g4, b4, 0, s, probs, n, ext);
+    else if (col_tiles == 1) hipLaunchKernelGGL((k_gemm_skinny<FORM, 2, 1, 4>), g4, b4, 0, s, probs, n, ext);
+    else hipLaunchKernelGGL((k_gemm_skinny<FORM, 2, 2, 4>), g4, b4, 0, s, probs, n, ext);
+    return;
+  }
   const dim3 g(blocks), b(512);
   if (row_tiles == 1 && col_tiles == 1) hipLaunchKernelGGL((k_gemm_skinny<FORM, 1, 1>), g, b, 0, s, probs, n, ext);
   else if (row_tiles == 1) hipLaunchKernelGGL((k_gemm_skinny<FORM, 1, 2>), g, b, 0, s, probs, n, ext);
   else if (col_tiles == 1) hipLaunchKernelGGL((k_gemm_skinny<FORM, 2, 1>), g, b, 0, s, probs, n, ext);
   else hipLaunchKernelGGL((k_gemm_skinny<FORM, 2, 2>), g, b, 0, s, probs, n, ext);
 }
-void launch_gemm_skinny(const GemmProb *probs, int n, int total_blocks, int form, int row_tiles, int col_tiles,
+void launch_gemm_skinny(const GemmProb *probs, int n, int total_blocks, int form, int row_tiles, int col_tiles, int waves,
                         const ExtPtrs &ext, hipStream_t s) {
   if (total_blocks <= 0) return;
-  if (form == FORM_FWD) launch_rows<FORM_FWD>(probs, n, total_blocks, row_tiles, col_tiles, ext, s);
-  else launch_rows<FORM_DX>(probs, n, total_blocks, row_tiles, col_tiles, ext, s);
+  if (form == FORM_FWD) launch_rows<FORM_FWD>(probs, n, total_blocks, row_tiles, col_tiles, waves, ext, s);
+  else launch_rows<FORM_DX>(probs, n, total_blocks, row_tiles, col_tiles, waves, ext, s);
 }
 void launch_gemm_bwd_merged(const GemmProb *probs, int n, int total_blocks, int row_tiles, int col_tiles, int accumulate_dw,
                             const ExtPtrs &ext, hipStream_t s) {

@@ -198,7 +198,7 @@ int gemm_big_tiles_for(int tile_rows, int M, int N, int *tiles_n);
 void launch_gemm_dw_ksplit(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, hipStream_t s);
 int gemm_dw_ksplit_blocks(int M, int N);
 // few-row (micro-batch <= 256 rows) forward / backward-data kernel
-void launch_gemm_skinny(const GemmProb *probs, int n, int total_blocks, int form, int row_tiles, int col_tiles,
+void launch_gemm_skinny(const GemmProb *probs, int n, int total_blocks, int form, int row_tiles, int col_tiles, int waves,
                         const ExtPtrs &ext, hipStream_t s);
 // backward of a level with few rows in one launch: records of form DX (few-row body) first, then
 // records of form DW (tile body, two tiles per workgroup)

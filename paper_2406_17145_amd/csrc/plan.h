@@ -36,7 +36,7 @@ struct Step {
   int64_t table_off;  // bytes into the slot's table blob
   int32_t n;          // records
   int32_t blocks;     // workgroups
-  int32_t a0, a1, a2; // kernel-specific launch arguments
+  int32_t a0, a1, a2, a3; // kernel-specific launch arguments
   int32_t ext_kind, ext_base;
   int32_t launches;   // kernel launches this step enqueues
   int32_t lane;       // 0: the caller's stream; 1: the stage's side stream (between a K_FORK and a K_JOIN)

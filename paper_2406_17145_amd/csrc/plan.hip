@@ -762,6 +762,7 @@ struct Emitter {
             s.a0 = col_tiles;
             s.a1 = form;
             s.a2 = row_tiles;
+            s.a3 = (pl.flags & 16) ? 4 : 8;     // waves per workgroup
             if (wants_ext(g)) s.ext_kind = EXT_GRAD_INPUTS;
             continue;
           }

@@ -335,7 +335,7 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
         if (!grp) return fail(GPP_ERR_UNSUPPORTED, "internal: group launch without a group");
         launch_gemm_dw_group((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a2, sp.a0, *grp, s);
         break;
-      case K_GEMM_SKINNY: launch_gemm_skinny((const GemmProb *)tab, sp.n, sp.blocks, sp.a1, sp.a2, sp.a0, ext, s); break;
+      case K_GEMM_SKINNY: launch_gemm_skinny((const GemmProb *)tab, sp.n, sp.blocks, sp.a1, sp.a2, sp.a0, sp.a3, ext, s); break;
       case K_GEMM_BWD_MERGED: launch_gemm_bwd_merged((const GemmProb *)tab, sp.n, sp.blocks, sp.a2, sp.a1, accumulate, ext, s); break;
       case K_LOSS_FWD_SMALL: launch_loss_fwd_small((const LossProb *)tab, sp.n, loss_out, s); break;
       case K_COLSUM: launch_colsum((const ColsumProb *)tab, sp.n, sp.blocks, accumulate, s); break;

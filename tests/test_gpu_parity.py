@@ -352,6 +352,17 @@ def test_generic_and_default_gemm_paths_agree_with_oracle():
     both(wl)
 
 
+def test_four_wave_few_row_kernels_agree_with_oracle():
+    # stage flag bit 4 (launches that share the GPU): every tile shape of the few-row kernel, ragged K and N,
+    # 1 to 256 rows, forward and backward-data, stand-alone and next to the merged backward launch
+    for mb, widths, hidden, act in [(64, (96, 200, 8, 64), 128, "gelu"), (20, (942, 77, 2048, 1), 1000, "relu"),
+                                    (200, (70, 131, 9, 33), 160, "gelu"), (1, (264, 131, 520, 8), 392, "relu")]:
+        wl = W.candle_uno(micro_batch=mb, n_micro=2, widths=widths, hidden=hidden, act=act)
+        both(wl, flags=B.FLAG_SHARED_GPU)
+    both(W.hetero(micro_batch=33, n_micro=2, base_width=32, out_width=64), flags=B.FLAG_SHARED_GPU)
+    both(W.hetero(micro_batch=128, n_micro=1, base_width=64, out_width=128), flags=B.FLAG_SHARED_GPU)
+
+
 def test_split_k_is_deterministic_and_matches_unsplit():
     # long contraction, few output tiles: with the flag set the planner splits K across workgroups
     wl = W.candle_uno(micro_batch=48, n_micro=2, widths=(2048, 1500, 8, 64), hidden=96, act="gelu")

@@ -150,8 +150,9 @@ def test_config2_full_size_in_the_launch_configuration_the_benchmark_times():
     n = wl.n_micro
     print(f"[case] {wl.name} full size, {n} in flight, grouped weight gradients, graph replay", flush=True)
     ora_stage, ora_res = run_oracle(wl)
-    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=n, flags=B.FLAG_GROUPED_DW)
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=n, flags=B.FLAG_GROUPED_DW | B.FLAG_SHARED_GPU)
     assert st.num_launches(2) == 1
+    assert B.gpp_stage_lanes(st.handle) == (True, True)
     dev_batches = [st.stage_inputs(mb) for mb in wl.batches]
     losses = [torch.zeros(1, dtype=torch.float32, device=st.dev) for _ in range(n)]
     gins = [st.alloc_grad_inputs() for _ in range(n)]
@@ -322,6 +323,12 @@ def test_lanes_give_the_one_stream_results_bit_for_bit():
             print(f"[case] {wl.name} {n} shared lanes cap={cap} k={k}", flush=True)
             _, res, grads = _run(wl, cap, k, True, reps=2, flags=B.FLAG_GROUPED_DW, lanes=(n, n), shared_lanes=True)
             _same(res, grads, res1, grads1, f"shared lanes={n} cap={cap} k={k}")
+        # with the workgroup sizes for a shared GPU (other kernels: compared with their own one-stream run)
+        _, res4, grads4 = _run(wl, cap, k, False, reps=2, flags=B.FLAG_GROUPED_DW | B.FLAG_SHARED_GPU)
+        compare(wl, res4, grads4, ora_stage, ora_res, label=f"four waves, one stream cap={cap} k={k}")
+        print(f"[case] {wl.name} 4 shared lanes, four-wave workgroups cap={cap} k={k}", flush=True)
+        _, res, grads = _run(wl, cap, k, True, reps=2, flags=B.FLAG_GROUPED_DW | B.FLAG_SHARED_GPU, lanes=(4, 4), shared_lanes=True)
+        _same(res, grads, res4, grads4, f"four waves, shared lanes cap={cap} k={k}")
 
 
 def test_lanes_on_a_mid_pipeline_stage():
