@@ -136,10 +136,10 @@ typedef struct {
                                  default: it pays only for large micro-batches;
                                  bit 4: the stage's launches will share the GPU with other launches (several
                                  streams per direction in gpp_stage_run_schedule_lanes, other stages of a
-                                 pipeline): the few-row GEMM kernels then use workgroups of four waves instead
-                                 of eight (half the LDS and registers per workgroup, so workgroups of
-                                 concurrent launches fit a compute unit side by side; a launch that has the
-                                 GPU to itself is ~10 % slower that way) */
+                                 pipeline): few-row GEMM launches of at most 64 rows then use workgroups of
+                                 four waves instead of eight (half the LDS and registers per workgroup, so
+                                 workgroups of concurrent launches fit a compute unit side by side; a launch
+                                 that has the GPU to itself is ~10 % slower that way) */
 } gpp_stage_desc_t;
 
 /* Leading dimension used for parameters and gradient accumulators. */
