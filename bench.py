@@ -115,7 +115,7 @@ AUTO_LANES = (4, 4)     # --lanes auto, where the stage allows several streams p
 MEASURED_TRAFFIC = {
     # bytes per launch, averaged over the launches of the kernel family within a step
     ("candle_uno", "gemm_bwd_merged_dx_dw"): 50.5e6,
-    ("candle_uno", "gemm_skinny_fwd"): 12.9e6,
+    ("candle_uno", "gemm_skinny_fwd"): 13.0e6,
     ("candle_uno", "gemm_skinny_dx"): 20.3e6,
     ("candle_uno", "gemm_big_dw"): 122.1e6,      # the grouped launch: eight slots, every Linear of the stage
     ("hetero", "gemm_bwd_merged_dx_dw"): 122.0e6,
@@ -147,6 +147,9 @@ def main():
                          "auto: 4,4 where the stage allows several streams per direction (gpp_stage_lanes), else 1")
     ap.add_argument("--shared-lanes", default="auto", choices=["auto", "on", "off"],
                     help="--lanes F,F: the backward passes use the forward streams (one chain of launches per micro-batch)")
+    ap.add_argument("--shared-gpu", default="auto", choices=["auto", "on", "off"],
+                    help="stage flag bit 4 (workgroup sizes for launches that share the GPU); auto: on when several "
+                         "streams per direction are used; on: also for a one-stream profiling run of the same kernels")
     ap.add_argument("--one-stream", action="store_true", help="--schedule kfkb: all tasks on one stream, in task order")
     ap.add_argument("--schedule", default="auto", choices=["auto", "serial", "overlap", "kfkb"],
                     help="micro-batch schedule of a step: serial = fw_k bw_k in turn on one stream; overlap = fw_{k+1} "
@@ -198,8 +201,9 @@ def main():
     # several streams per direction (decided below): the stage's launches then share the GPU, and it is created
     # with the workgroup sizes for that; whether the stage allows such streams is known once it exists
     want_lanes = kfkb and not args.one_stream and n_slots > 1 and args.lanes != "1,1"
-    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=n_slots, flags=base_flags | (B.FLAG_SHARED_GPU if want_lanes else 0))
-    if want_lanes and args.lanes == "auto" and not any(B.gpp_stage_lanes(st.handle)):
+    shared_gpu = args.shared_gpu == "on" or (args.shared_gpu == "auto" and want_lanes)
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=n_slots, flags=base_flags | (B.FLAG_SHARED_GPU if shared_gpu else 0))
+    if args.shared_gpu == "auto" and want_lanes and args.lanes == "auto" and not any(B.gpp_stage_lanes(st.handle)):
         st.close()
         st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=n_slots, flags=base_flags)
     dev_batches = [st.stage_inputs(mb) for mb in wl.batches]       # resident in HBM

@@ -55,11 +55,13 @@ struct SkLds {
   static constexpr int BM = 32 * TI, BN = 32 * TJ;
   static constexpr int RED_FLOATS = (NW / 2) * BM * BN;
   // W tile: forward [BN][64 + 8]; backward-data [64][BN + pad], read with the transposing read.  A
-  // 16-lane block of that read touches 32 bytes in each of four consecutive rows, so the row stride
-  // should put those rows on disjoint banks: 96 bytes for 32-wide rows, 192 for 64-wide ones (the
-  // latter only when the waves' tiles still fit in the 160 KB of LDS, else 144)
+  // 16-lane block of that read touches 32 bytes in each of four consecutive rows, and the neighbouring
+  // block the next 32 bytes of the same rows, so the row stride should spread four rows over the 64
+  // banks (256 bytes): 64 bytes for 32-wide rows (no padding: four rows are exactly the 64 banks, and the
+  // staging stores are contiguous), 192 for 64-wide ones (only when the waves' tiles still fit in the
+  // 160 KB of LDS, else 144)
   static constexpr int SB = FORM == FORM_FWD ? SK_ST
-                            : BN == 32       ? BN + 16
+                            : BN == 32       ? BN
                                              : (NW * (BM * SK_ST + SK_KS * (BN + 32)) * 2 <= 160 * 1024 ? BN + 32 : BN + 8);
   static constexpr int B_ROWS = FORM == FORM_FWD ? BN : SK_KS;
   static constexpr int WAVE_ELEMS = BM * SK_ST + B_ROWS * SB;     // a wave's private A and B tiles

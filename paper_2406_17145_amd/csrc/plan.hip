@@ -763,7 +763,8 @@ struct Emitter {
             s.a1 = form;
             s.a2 = row_tiles;
             // waves per workgroup: four where the launch shares the GPU (flag bit 4) and has at most 64 rows
-            // (measured on the feature-tower workload with four streams: 64 rows +21 %, 96 rows -6 %)
+            // (measured on the feature-tower workload with four streams: 64 rows +21 %, 96 rows -6 %; keeping
+            // eight waves for the launches with long contractions lowers their latency but the step gets 2 % slower)
             s.a3 = ((pl.flags & 16) && max_m <= 64) ? 4 : 8;
             if (wants_ext(g)) s.ext_kind = EXT_GRAD_INPUTS;
             continue;
