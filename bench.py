@@ -115,8 +115,8 @@ AUTO_LANES = (4, 4)     # --lanes auto, where the stage allows several streams p
 MEASURED_TRAFFIC = {
     # bytes per launch, averaged over the launches of the kernel family within a step
     ("candle_uno", "gemm_bwd_merged_dx_dw"): 50.5e6,
-    ("candle_uno", "gemm_skinny_fwd"): 13.0e6,
-    ("candle_uno", "gemm_skinny_dx"): 20.3e6,
+    ("candle_uno", "gemm_skinny_fwd"): 16.2e6,
+    ("candle_uno", "gemm_skinny_dx"): 25.2e6,
     ("candle_uno", "gemm_big_dw"): 122.1e6,      # the grouped launch: eight slots, every Linear of the stage
     ("hetero", "gemm_bwd_merged_dx_dw"): 122.0e6,
     ("hetero", "gemm_skinny_fwd"): 48.8e6,

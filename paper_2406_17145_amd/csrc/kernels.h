@@ -160,6 +160,23 @@ struct LossProb {
   int32_t blk_begin;
 };
 
+// A one-column head: Linear(K -> 1) without activation whose only consumer is an element-wise loss,
+// with everything of it that depends on forward values alone, in one launch of one workgroup.
+struct HeadProb {
+  const void *x;        // [rows x K] bf16: the head's input
+  const void *w;        // [K] bf16: the Linear's weight row
+  const float *bias;    // one float, or null
+  const void *target;   // [rows] f32, stride ld_t
+  const void *mask;     // [rows x K] bf16: what the derivative of x's activation is taken from, or null
+  void *y;              // [rows] prediction out, stride ld_y
+  void *dy;             // [rows] loss gradient out, stride ld_dy
+  void *dx;             // [rows x K] bf16: gradient of x (times the derivative of its activation) out
+  int64_t ld_x, ld_t, ld_mask, ld_y, ld_dy, ld_dx;
+  int32_t rows, K, kind;      // kind = gpp_op_kind_t value of the loss
+  int32_t y_dtype, dy_dtype, act;
+  float scale;
+};
+
 struct ExtPtrs {
   void *p[64];
 };
@@ -261,6 +278,8 @@ int loss_fwd_blocks(const LossProb &p);
 // records at most loss_small_limit()); a null `out` skips the launch
 void launch_loss_fwd_small(const LossProb *probs, int n, float *out, hipStream_t s);
 int loss_small_limit();
+bool head_loss_supported(int64_t rows, int64_t K);
+void launch_head_loss(const HeadProb *prob, int rows, int K, float *out, hipStream_t s);
 void launch_loss_bwd(const LossProb *probs, int n, int total_blocks, hipStream_t s);
 int loss_bwd_blocks(const LossProb &p);
 

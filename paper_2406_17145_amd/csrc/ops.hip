@@ -735,6 +735,145 @@ void launch_loss_fwd_small(const LossProb *probs, int n, float *out, hipStream_t
   hipLaunchKernelGGL(k_loss_fwd_small, dim3(1), dim3(256), 0, s, probs, n, out);
 }
 
+// One-column head (see HeadProb): per row  y = x . w + b,  the loss term and its gradient dy, and the
+// gradient of x:  dx = dy w (.) act'(mask).  Workgroups of eight waves.  Workgroup 0 computes every row's
+// prediction, loss term and loss gradient (a wave takes four rows at a time) and the loss sum; workgroup
+// b >= 1 computes dx for rows 8 (b - 1) .. + 7, a wave per row, and for that RECOMPUTES its rows' dot
+// products and gradients with the same arithmetic (same order, same roundings) instead of waiting for
+// workgroup 0: a fifth of the work done twice buys a launch without any exchange between workgroups.  (One
+// workgroup for everything was measured at 11 us for 64 x 1000: it is bound by the arithmetic of ONE
+// compute unit.)  w sits in LDS as floats.  Every value passes through the storage type it has in the
+// unfused path (y and dy are rounded before they are used), and all sums have a fixed order.
+constexpr int HEAD_MAX_K = 8192, HEAD_MAX_ROWS = 256, HEAD_ROWS_IN_FLIGHT = 4, HEAD_WAVES = 8;
+bool head_loss_supported(int64_t rows, int64_t K) { return rows >= 1 && rows <= HEAD_MAX_ROWS && K >= 8 && K <= HEAD_MAX_K && (K & 7) == 0; }
+// prediction and loss gradient of one row from its dot product, as the backward pass will read them
+__device__ __forceinline__ void head_row(const HeadProb &p, float dot, float bias, float t, float &y, float &g) {
+  y = wave_sum(dot) + bias;
+  if (p.y_dtype == DT_BF16) y = bf16_bits_to_f32(f32_to_bf16_bits(y));
+  g = p.kind == 9 ? 2.0f * p.scale * (y - t) : p.scale * (sigmoid_f(y) - t);
+  if (p.dy_dtype == DT_BF16) g = bf16_bits_to_f32(f32_to_bf16_bits(g));
+}
+__device__ __forceinline__ float head_dot8(const ln_u32x4 &x, const float *w8) {
+  float d = 0.0f;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    d += __uint_as_float(x[e] << 16) * w8[2 * e];
+    d += __uint_as_float(x[e] & 0xffff0000u) * w8[2 * e + 1];
+  }
+  return d;
+}
+__global__ __launch_bounds__(64 * HEAD_WAVES) void k_head_loss(const HeadProb *__restrict__ prob, float *out) {
+  __shared__ float w_f[HEAD_MAX_K];
+  __shared__ float red[HEAD_WAVES];
+  const HeadProb p = prob[0];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int chunks = p.K >> 3;
+  for (int c = threadIdx.x; c < chunks; c += 64 * HEAD_WAVES) {
+    const ln_u32x4 v = *(const ln_u32x4 *)((const uint16_t *)p.w + 8 * c);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      w_f[8 * c + 2 * e] = __uint_as_float(v[e] << 16);
+      w_f[8 * c + 2 * e + 1] = __uint_as_float(v[e] & 0xffff0000u);
+    }
+  }
+  const float bias = p.bias ? p.bias[0] : 0.0f;
+  if (blockIdx.x == 0) {
+    constexpr int R = HEAD_ROWS_IN_FLIGHT;
+    float tv[R];
+    const int first = wave * R;
+#pragma unroll
+    for (int q = 0; q < R; ++q) tv[q] = ((const float *)p.target)[(int64_t)min(first + q, p.rows - 1) * p.ld_t];
+    __syncthreads();
+    float loss_acc = 0.0f;      // lane 0 of each wave: the loss terms of the wave's rows, in row order
+    for (int r0 = first; r0 < p.rows; r0 += HEAD_WAVES * R) {
+      if (r0 != first) {
+#pragma unroll
+        for (int q = 0; q < R; ++q) tv[q] = ((const float *)p.target)[(int64_t)min(r0 + q, p.rows - 1) * p.ld_t];
+      }
+      float dot[R];
+#pragma unroll
+      for (int q = 0; q < R; ++q) dot[q] = 0.0f;
+      for (int c = lane; c < chunks; c += 64) {
+        ln_u32x4 xr[R];
+#pragma unroll
+        for (int q = 0; q < R; ++q) xr[q] = *(const ln_u32x4 *)((const uint16_t *)p.x + (int64_t)min(r0 + q, p.rows - 1) * p.ld_x + 8 * c);
+#pragma unroll
+        for (int q = 0; q < R; ++q) dot[q] += head_dot8(xr[q], w_f + 8 * c);
+      }
+#pragma unroll
+      for (int q = 0; q < R; ++q) {
+        float y, g;
+        head_row(p, dot[q], bias, tv[q], y, g);
+        const int r = r0 + q;
+        if (r < p.rows && lane == 0) {
+          if (p.kind == 9) {
+            const float d = y - tv[q];
+            loss_acc += d * d;
+          } else {
+            loss_acc += softplus_f(y) - tv[q] * y;
+          }
+          store_from_f32(p.y, p.y_dtype, (int64_t)r * p.ld_y, y);
+          store_from_f32(p.dy, p.dy_dtype, (int64_t)r * p.ld_dy, g);
+        }
+      }
+    }
+    if (lane == 0) red[wave] = loss_acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      float total = 0.0f;
+      for (int k = 0; k < HEAD_WAVES; ++k) total += red[k];
+      out[0] = total * p.scale;
+    }
+    return;
+  }
+  // ---- dx of one row per wave
+  const int row = (blockIdx.x - 1) * HEAD_WAVES + wave;
+  const int rc = min(row, p.rows - 1);
+  const float t = ((const float *)p.target)[(int64_t)rc * p.ld_t];
+  const bool masked = p.mask != nullptr, own_mask = masked && p.mask != p.x;
+  constexpr int KEEP = 4;       // chunks of the row (and of its mask source) a lane keeps: K <= 2048 needs no second read
+  ln_u32x4 xk[KEEP], mk[KEEP];
+#pragma unroll
+  for (int j = 0; j < KEEP; ++j) {
+    const int c = min(lane + 64 * j, chunks - 1);
+    xk[j] = *(const ln_u32x4 *)((const uint16_t *)p.x + (int64_t)rc * p.ld_x + 8 * c);
+    mk[j] = own_mask ? *(const ln_u32x4 *)((const uint16_t *)p.mask + (int64_t)rc * p.ld_mask + 8 * c) : xk[j];
+  }
+  __syncthreads();
+  float dot = 0.0f;     // the same chunks in the same order as workgroup 0's lane
+#pragma unroll
+  for (int j = 0; j < KEEP; ++j)
+    if (lane + 64 * j < chunks) dot += head_dot8(xk[j], w_f + 8 * (lane + 64 * j));
+  for (int c = lane + 64 * KEEP; c < chunks; c += 64)
+    dot += head_dot8(*(const ln_u32x4 *)((const uint16_t *)p.x + (int64_t)rc * p.ld_x + 8 * c), w_f + 8 * c);
+  float y, g;
+  head_row(p, dot, bias, t, y, g);
+  if (row >= p.rows || !p.dx) return;
+  auto put = [&](int c, const ln_u32x4 &m) {
+    ln_u32x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float lo = g * w_f[8 * c + 2 * e], hi = g * w_f[8 * c + 2 * e + 1];
+      if (masked) {
+        lo *= act_grad(__uint_as_float(m[e] << 16), p.act);
+        hi *= act_grad(__uint_as_float(m[e] & 0xffff0000u), p.act);
+      }
+      o[e] = (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
+    }
+    *(ln_u32x4 *)((uint16_t *)p.dx + (int64_t)row * p.ld_dx + 8 * c) = o;
+  };
+#pragma unroll
+  for (int j = 0; j < KEEP; ++j)
+    if (lane + 64 * j < chunks) put(lane + 64 * j, mk[j]);
+  for (int c = lane + 64 * KEEP; c < chunks; c += 64)
+    put(c, masked ? *(const ln_u32x4 *)((const uint16_t *)p.mask + (int64_t)row * p.ld_mask + 8 * c) : ln_u32x4{0u, 0u, 0u, 0u});
+}
+void launch_head_loss(const HeadProb *prob, int rows, int K, float *out, hipStream_t s) {
+  (void)K;
+  if (!out || rows <= 0) return;
+  hipLaunchKernelGGL(k_head_loss, dim3(1 + (rows + HEAD_WAVES - 1) / HEAD_WAVES), dim3(64 * HEAD_WAVES), 0, s, prob, out);
+}
+
 int loss_bwd_blocks(const LossProb &p) { return (p.rows + 3) / 4; }
 // one wave per row; LossProb has no prefix field, so block ranges are passed as rows/4 per record in order
 __global__ __launch_bounds__(256) void k_loss_bwd(const LossProb *__restrict__ probs, int n) {

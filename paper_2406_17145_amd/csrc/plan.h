@@ -27,7 +27,8 @@ struct Buf {
 enum Kern : int32_t {
   K_ELT, K_GEMM_GENERIC, K_GEMM_MFMA, K_COLSUM, K_LN_FWD, K_LN_BWD, K_LN_BWD_PARAMS, K_ATTN_FWD, K_ATTN_DQ,
   K_ATTN_DKV, K_POOL, K_EMB_FWD, K_EMB_BWD, K_INTERACT_FWD, K_INTERACT_BWD, K_LOSS_FWD, K_LOSS_BWD, K_LOSS_SUM,
-  K_GEMM_SKINNY, K_GEMM_BWD_MERGED, K_LOSS_FWD_SMALL, K_GEMM_BIG, K_GEMM_DW_KSPLIT, K_GEMM_DW_GROUP, K_FORK, K_JOIN
+  K_GEMM_SKINNY, K_GEMM_BWD_MERGED, K_LOSS_FWD_SMALL, K_GEMM_BIG, K_GEMM_DW_KSPLIT, K_GEMM_DW_GROUP, K_FORK, K_JOIN,
+  K_HEAD_LOSS
 };
 enum ExtKind : int32_t { EXT_NONE = 0, EXT_INPUTS, EXT_OUTPUTS, EXT_GRAD_OUTPUTS, EXT_GRAD_INPUTS };
 

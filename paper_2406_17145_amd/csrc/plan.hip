@@ -396,6 +396,7 @@ struct Emitter {
   int64_t part_need = 0, cnt_need = 0;  // split-K scratch high-water marks over all launches
   std::vector<GemmProb> dw_group;   // backward-weight records left to the launch over a group of slots
   std::vector<char> loss_fused;     // per node: this loss's gradient is written by the forward pass
+  std::vector<int> head_loss;       // per LINEAR node: the loss that computes it (one-column head fused into its loss), or -1
   // Embedding bags next to dense branches: the gather (forward) and the sort + segment sums (backward) are long
   // chains of launches that nothing on the dense side depends on until the branches merge.  They run on the
   // stage's side stream: K_FORK (side stream waits for what has been issued), the steps with lane 1, K_JOIN
@@ -883,6 +884,28 @@ void Emitter::forward() {
   bool loss_summed = false;
   auto &N = pl.nodes;
   loss_fused.assign(N.size(), 0);
+  // One-column heads: Linear(K -> 1) without activation feeding nothing but an element-wise loss, in a stage
+  // with per-slot gradient buffers (grouped weight gradients).  The loss's launch then also computes the
+  // Linear itself, the loss gradient and the gradient of the Linear's input (all of which depend on forward
+  // values only): three launches of a micro-batch's chain become one.
+  head_loss.assign(N.size(), -1);
+  if ((pl.flags & 4) && !(pl.flags & 1) && pl.loss_ops.size() == 1) {
+    const int li = pl.loss_ops[0];
+    const Node &ls = N[li];
+    const int yi = ls.in[0];
+    const Node &y = N[yi];
+    bool ok = ls.d.kind != GPP_OP_LOSS_CE && y.d.kind == GPP_OP_LINEAR && y.feat == 1 && y.d.act == GPP_ACT_NONE &&
+              y.d.param_dtype == GPP_BF16 && y.wants_grad && y.users.size() == 1 && y.gout_parent < 0 && y.val_parent < 0 &&
+              y.fused_add < 0 && !y.is_output && y.gout.space == SP_SLOT && y.rows <= loss_small_limit();
+    if (ok) {
+      const Node &x = N[y.in[0]];
+      ok = x.d.kind == GPP_OP_LINEAR && x.wants_grad && x.users.size() == 1 && x.gout_parent < 0 && x.val_parent < 0 && x.fused_add < 0 && x.fused_by < 0 &&
+           x.input_index < 0 && x.gout.space == SP_SLOT && x.val.dtype == DT_BF16 && x.gout.dtype == DT_BF16 && x.rows == y.rows &&
+           head_loss_supported(x.rows, x.feat) && (x.val.ld & 7) == 0 && (x.gout.ld & 7) == 0 &&
+           (x.d.act == GPP_ACT_NONE || (x.d.act == GPP_ACT_GELU_ERF ? x.aux : x.val).dtype == DT_BF16);
+    }
+    if (ok) head_loss[yi] = li;
+  }
   find_emb_level();
   fork_open = false;
 
@@ -917,11 +940,13 @@ void Emitter::forward() {
     std::vector<EmbProb> embs;
     std::vector<InteractProb> inters;
     std::vector<LossProb> losses;
+    std::vector<HeadProb> heads;
     for (int i : pl.by_level[L]) {
       Node &nd = N[i];
       const gpp_op_desc_t &d = nd.d;
       switch (d.kind) {
         case GPP_OP_LINEAR: {
+          if (head_loss[i] >= 0) break;      // computed by its loss's launch
           const Node &x = N[nd.in[0]];
           GemmProb g;
           memset(&g, 0, sizeof(g));
@@ -1071,6 +1096,38 @@ void Emitter::forward() {
           const Node &y = N[nd.in[0]];
           const Node &t = N[nd.in[1]];
           const Buf &yv = y.fused_add >= 0 ? N[y.fused_add].val : y.val;
+          if (head_loss[nd.in[0]] == i) {     // the one-column head and its loss in one launch
+            const Node &x = N[y.in[0]];
+            HeadProb h;
+            memset(&h, 0, sizeof(h));
+            h.x = ptr(x.val);
+            h.ld_x = x.val.ld;
+            h.w = y.d.param[0];
+            h.bias = y.d.has_bias ? (const float *)y.d.param[1] : nullptr;
+            h.target = ptr(t.val);
+            h.ld_t = t.val.ld;
+            if (x.d.act != GPP_ACT_NONE) {
+              const Buf &ms = x.d.act == GPP_ACT_GELU_ERF ? x.aux : x.val;
+              h.mask = ptr(ms);
+              h.ld_mask = ms.ld;
+              h.act = x.d.act;
+            }
+            h.y = ptr(y.val);
+            h.ld_y = y.val.ld;
+            h.y_dtype = y.val.dtype;
+            h.dy = ptr(y.gout);
+            h.ld_dy = y.gout.ld;
+            h.dy_dtype = y.gout.dtype;
+            h.dx = ptr(x.gout);
+            h.ld_dx = x.gout.ld;
+            h.rows = (int32_t)y.rows;
+            h.K = (int32_t)x.feat;
+            h.kind = d.kind;
+            h.scale = (float)d.loss_scale;
+            heads.push_back(h);
+            loss_fused[i] = 1;
+            break;
+          }
           LossProb l;
           memset(&l, 0, sizeof(l));
           l.y = ptr(yv);
@@ -1168,6 +1225,12 @@ void Emitter::forward() {
       Step &s = add_step(K_INTERACT_FWD, push_table(inters), (int)inters.size(), blocks);
       s.a0 = mf;
       s.a1 = md;
+    }
+    if (!heads.empty()) {      // (the stage's only loss)
+      Step &sh = add_step(K_HEAD_LOSS, push_table(heads), 1, 1);
+      sh.a0 = heads[0].rows;
+      sh.a1 = heads[0].K;
+      loss_summed = true;
     }
     if (!losses.empty()) {
       int blocks = 0;
@@ -1380,6 +1443,13 @@ void Emitter::backward() {
           if (!grouped) {
             gemms.push_back(w);
             pl.bwd_shared = true;   // accumulates into the parameter's gradient: backward passes stay in order
+          }
+          if (head_loss[i] >= 0) {
+            // the forward pass wrote the input's gradient, activation derivative included (its only consumer
+            // is this head, so the gradient buffer itself was the target)
+            (void)acquire(nd.in[0], true);
+            if (x.d.act != GPP_ACT_NONE) dz_ready[nd.in[0]] = 1;
+            break;
           }
           if (x.wants_grad) {
             Target tg = acquire(nd.in[0], true);

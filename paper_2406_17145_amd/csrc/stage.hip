@@ -83,6 +83,7 @@ static int step_tag(const Step &sp, bool backward) {
     case K_GEMM_DW_KSPLIT: return 31;
     case K_GEMM_DW_GROUP: return 30;
     case K_LOSS_FWD_SMALL: return 21;
+    case K_HEAD_LOSS: return 21;
     case K_GEMM_GENERIC: return backward ? 5 : 4;
     case K_ELT: return backward ? 7 : 6;
     case K_COLSUM: return 8;
@@ -337,7 +338,18 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
         break;
       case K_GEMM_SKINNY: launch_gemm_skinny((const GemmProb *)tab, sp.n, sp.blocks, sp.a1, sp.a2, sp.a0, sp.a3, ext, s); break;
       case K_GEMM_BWD_MERGED: launch_gemm_bwd_merged((const GemmProb *)tab, sp.n, sp.blocks, sp.a2, sp.a1, accumulate, ext, s); break;
-      case K_LOSS_FWD_SMALL: launch_loss_fwd_small((const LossProb *)tab, sp.n, loss_out, s); break;
+      case K_HEAD_LOSS: {   // always runs: it also writes the prediction and two gradients
+        float *sink = loss_out ? loss_out : (float *)(st->ws + pl.off_slots + (int64_t)slot * pl.slot_bytes + pl.loss_scalars.off);
+        launch_head_loss((const HeadProb *)tab, sp.a0, sp.a1, sink, s);
+        break;
+      }
+      case K_LOSS_FWD_SMALL: {
+        // the launch may also write the loss gradient (per-slot gradient buffers), so it runs without a
+        // loss_out too: the sum then goes to the slot's own loss scalars
+        float *sink = loss_out ? loss_out : (float *)(st->ws + pl.off_slots + (int64_t)slot * pl.slot_bytes + pl.loss_scalars.off);
+        launch_loss_fwd_small((const LossProb *)tab, sp.n, sink, s);
+        break;
+      }
       case K_COLSUM: launch_colsum((const ColsumProb *)tab, sp.n, sp.blocks, accumulate, s); break;
       case K_LN_FWD: launch_ln_fwd((const LnProb *)tab, sp.n, sp.blocks, sp.a0, s); break;
       case K_LN_BWD: launch_ln_bwd((const LnProb *)tab, sp.n, sp.blocks, sp.a0, sp.a1, s); break;

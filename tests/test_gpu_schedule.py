@@ -416,3 +416,54 @@ def test_lanes_in_a_captured_graph_replay_like_the_eager_run(lanes, shared):
                     gin={i: t2n(t) for i, t in zip(st.input_ids, gins[j]) if t is not None}) for j in range(len(dev))]
         _same(res, st.grads_numpy(), res1, grads1, f"replay {rep}")
     st.close()
+
+
+# ---- one-column head fused into its loss (stages with per-slot gradient buffers) -----------------------
+
+def test_one_column_head_and_its_loss_in_one_launch():
+    # Linear(K -> 1) + element-wise loss: with grouped weight gradients the loss's launch also computes the
+    # Linear, the loss gradient and the gradient of the Linear's input.  Rows 1 ... 256 (one workgroup, four rows
+    # of a wave in flight, ragged groups), every activation in front of the head, MSE and BCE, and sizes the
+    # fusion does not take (more than 256 rows; a width that is not a multiple of 8)
+    for mb, hidden, act, fused in [(1, 160, "relu", True), (37, 160, "gelu", True), (64, 1000, "relu", True), (200, 72, "none", True),
+                                   (8, 1536, "gelu", True), (40, 1536, "relu", True), (256, 160, "gelu", True), (300, 160, "relu", False), (16, 100, "relu", False)]:
+        wl = W.candle_uno(micro_batch=mb, n_micro=3, widths=(70, 131, 9, 33), hidden=hidden, act=act)
+        st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=3, flags=B.FLAG_GROUPED_DW)
+        launches = st.num_launches(False) + st.num_launches(True)
+        st.close()
+        st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=1)
+        plain = st.num_launches(False) + st.num_launches(True)
+        st.close()
+        print(f"[case] {wl.name} b={mb} hidden={hidden} act={act}: {launches} launches per micro-batch (plain stage {plain})", flush=True)
+        ora_stage, ora_res = run_oracle(wl)
+        _, res, grads = _run(wl, 3, 3, False, reps=2, flags=B.FLAG_GROUPED_DW)
+        compare(wl, res, grads, ora_stage, ora_res, label=f"head b={mb} hidden={hidden} act={act}")
+        if fused:
+            assert launches <= plain - 2, (launches, plain)
+    wl = W.dlrm(micro_batch=128, n_micro=3, n_tables=4, num_rows=3000, bottom=(64, 32, 128), top=(128, 64, 1))
+    ora_stage, ora_res = run_oracle(wl)
+    print(f"[case] {wl.name} b=128 BCE head", flush=True)
+    _, res, grads = _run(wl, 3, 3, True, reps=2, flags=B.FLAG_GROUPED_DW)
+    compare(wl, res, grads, ora_stage, ora_res, label="dlrm BCE head")
+
+
+def test_forward_without_a_loss_pointer_still_seeds_the_backward_pass():
+    # per-slot gradient buffers: the forward pass writes the loss gradient, also when the caller wants no loss value
+    import torch
+    for hidden in (160, 100):          # with and without the fused head
+        wl = W.candle_uno(micro_batch=16, n_micro=2, widths=(32, 40, 8, 24), hidden=hidden, act="relu")
+        ora_stage, ora_res = run_oracle(wl)
+        st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=2, flags=B.FLAG_GROUPED_DW)
+        dev = [st.stage_inputs(mb) for mb in wl.batches]
+        gins = [st.alloc_grad_inputs() for _ in dev]
+        io = [([t.data_ptr() for t in mb], [], None, None, [t.data_ptr() if t is not None else None for t in gins[j]])
+              for j, mb in enumerate(dev)]
+        main = torch.cuda.current_stream(st.dev).cuda_stream
+        tasks = B.gpp_schedule_tasks(2, 2 * wl.micro_batch, 2, wl.micro_batch)
+        print(f"[case] {wl.name} hidden={hidden} forward passes with loss_out = NULL", flush=True)
+        B.gpp_stage_run_schedule(st.handle, tasks, io, main, main)
+        st.sync_status()
+        res = [dict(loss=ora_res[j][0].loss, outs={}, gin={i: t2n(t) for i, t in zip(st.input_ids, gins[j]) if t is not None})
+               for j in range(2)]
+        compare(wl, res, st.grads_numpy(), ora_stage, ora_res, label=f"no loss pointer hidden={hidden}")
+        st.close()
