@@ -635,6 +635,19 @@ __global__ __launch_bounds__(256) void k_loss_fwd(const LossProb *__restrict__ p
               acc += softplus_f(y[e]) - tv[e] * y[e];
             }
           }
+          // the gradient with the value (stages whose gradient buffers are per stash slot ask for it)
+          if (p.dy) {
+            float g[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) g[e] = p.kind == 9 ? 2.0f * p.scale * (y[e] - tv[e]) : p.scale * (sigmoid_f(y[e]) - tv[e]);
+            const int64_t go = (int64_t)r * p.ld_dy + c;
+            if ((p.ld_dy & 7) == 0 && ((uintptr_t)p.dy & 15) == 0) {
+              store8_from_f32(p.dy, p.dy_dtype, go, g);
+            } else {
+#pragma unroll
+              for (int e = 0; e < 8; ++e) store_from_f32(p.dy, p.dy_dtype, go + e, g[e]);
+            }
+          }
         }
       } else {
         for (int c = lane; c < p.cols; c += 64) {
@@ -645,6 +658,8 @@ __global__ __launch_bounds__(256) void k_loss_fwd(const LossProb *__restrict__ p
           } else {
             acc += softplus_f(y) - t[c] * y;
           }
+          if (p.dy)
+            store_from_f32(p.dy, p.dy_dtype, (int64_t)r * p.ld_dy + c, p.kind == 9 ? 2.0f * p.scale * (y - t[c]) : p.scale * (sigmoid_f(y) - t[c]));
         }
       }
     }

@@ -1244,8 +1244,7 @@ void Emitter::forward() {
         add_step(K_LOSS_FWD_SMALL, push_table(losses), (int)losses.size(), 1);   // value and sum in one launch
         loss_summed = true;
       } else {
-        for (int i : pl.by_level[L]) loss_fused[i] = 0;   // only the one-workgroup kernel writes gradients
-        add_step(K_LOSS_FWD, push_table(losses), (int)losses.size(), blocks);
+        add_step(K_LOSS_FWD, push_table(losses), (int)losses.size(), blocks);   // (writes the gradients its records name, too)
       }
     }
   }

@@ -467,3 +467,20 @@ def test_forward_without_a_loss_pointer_still_seeds_the_backward_pass():
                for j in range(2)]
         compare(wl, res, st.grads_numpy(), ora_stage, ora_res, label=f"no loss pointer hidden={hidden}")
         st.close()
+
+
+def test_large_elementwise_loss_writes_its_gradient_in_the_forward_pass():
+    # more loss elements than the one-workgroup loss kernel takes: the row-parallel loss kernel writes the
+    # gradient as well (per-slot gradient buffers), so the backward pass has no loss launch
+    for mb, dtype in [(40, "bf16"), (33, "f32")]:
+        wl = W.hetero(micro_batch=mb, n_micro=3, base_width=32, out_width=64, dtype=dtype)
+        st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=3, flags=B.FLAG_GROUPED_DW)
+        bwd = st.num_launches(True)
+        st.close()
+        st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=1)
+        bwd_plain = st.num_launches(True)
+        st.close()
+        print(f"[case] {wl.name} {dtype} b={mb}: backward launches {bwd} (plain stage {bwd_plain})", flush=True)
+        ora_stage, ora_res = run_oracle(wl)
+        _, res, grads = _run(wl, 3, 2, True, reps=2, flags=B.FLAG_GROUPED_DW)
+        compare(wl, res, grads, ora_stage, ora_res, label=f"large loss {dtype}")
