@@ -869,6 +869,12 @@ struct Emitter {
       return b;
     };
     col_tiles = gemm_skinny_col_tiles(count(row_tiles, 2));
+    // up to 64 rows a workgroup's k-loop is the whole launch: 32 columns halve it, as long as the launch
+    // stays at two workgroups per compute unit (branches of 256 ... 4096 columns, 304 workgroups: +15 % at
+    // 64 rows, +7 % at 16 rows, -11 % at 128 rows; seven branches of 4096 columns, 896 workgroups: -8 %)
+    int max_m = 0;
+    for (auto &r : g) max_m = std::max(max_m, r.M);
+    if (max_m <= 64 && count(row_tiles, 1) <= 512) col_tiles = 1;
     if (shrink_rows && col_tiles == 1 && row_tiles == 2 && count(2, 1) <= 256) row_tiles = 1;
   }
 
