@@ -110,13 +110,13 @@ def other_traffic(wl):
 # (FETCH_SIZE, then WRITE_SIZE) scaled by what the same counters read for a copy of known size
 # (--copy-calibration); the summaries are kept under profiles/.  None where not measured.
 AUTO_SHARED_LANES = True   # fw_j and bw_j of a micro-batch on one stream: a chain of launches per micro-batch
-AUTO_LANES = (4, 4)     # --lanes auto, where the stage allows several streams per direction
+AUTO_LANES = (2, 2)     # --lanes auto, where the stage allows several streams per direction
 
 MEASURED_TRAFFIC = {
     # bytes per launch, averaged over the launches of the kernel family within a step
     ("candle_uno", "gemm_bwd_merged_dx_dw"): 50.5e6,
-    ("candle_uno", "gemm_skinny_fwd"): 16.2e6,
-    ("candle_uno", "gemm_skinny_dx"): 25.2e6,
+    ("candle_uno", "gemm_skinny_fwd"): 35.1e6,     # a launch covers four micro-batches (group launches)
+    ("candle_uno", "gemm_skinny_dx"): 66.4e6,
     ("candle_uno", "gemm_big_dw"): 122.1e6,      # the grouped launch: eight slots, every Linear of the stage
     ("hetero", "gemm_skinny_fwd"): 48.7e6,
     ("hetero", "gemm_skinny_dx"): 47.2e6,
@@ -146,12 +146,17 @@ def main():
                          "(gpp_stage_backward_weights); auto: on")
     ap.add_argument("--lanes", default="auto", metavar="F,B",
                     help="--schedule kfkb: streams for the forward and for the backward passes (pass j on stream j mod F / B); "
-                         "auto: 4,4 where the stage allows several streams per direction (gpp_stage_lanes), else 1")
+                         "auto: 2,2 where the stage allows several streams per direction (gpp_stage_lanes), else 1")
     ap.add_argument("--shared-lanes", default="auto", choices=["auto", "on", "off"],
                     help="--lanes F,F: the backward passes use the forward streams (one chain of launches per micro-batch)")
     ap.add_argument("--shared-gpu", default="auto", choices=["auto", "on", "off"],
                     help="stage flag bit 4 (workgroup sizes for launches that share the GPU); auto: on when several "
                          "streams per direction are used; on: also for a one-stream profiling run of the same kernels")
+    ap.add_argument("--group-launches", default="auto", choices=["auto", "on", "off"],
+                    help="stage flag bits 8-11: the micro-batches that a run of tasks puts on one stream share one launch per step")
+    ap.add_argument("--same-stream", action="store_true",
+                    help="--schedule kfkb: the calls of all lanes (and their group launches) on ONE stream: the launches of the "
+                         "timed configuration one after the other, for kernel traces")
     ap.add_argument("--one-stream", action="store_true", help="--schedule kfkb: all tasks on one stream, in task order")
     ap.add_argument("--schedule", default="auto", choices=["auto", "serial", "overlap", "kfkb"],
                     help="micro-batch schedule of a step: serial = fw_k bw_k in turn on one stream; overlap = fw_{k+1} "
@@ -206,10 +211,20 @@ def main():
     # with the workgroup sizes for that; whether the stage allows such streams is known once it exists
     want_lanes = kfkb and not args.one_stream and n_slots > 1 and args.lanes != "1,1"
     shared_gpu = args.shared_gpu == "on" or (args.shared_gpu == "auto" and want_lanes)
-    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=n_slots, flags=base_flags | (B.FLAG_SHARED_GPU if shared_gpu else 0))
-    if args.shared_gpu == "auto" and want_lanes and args.lanes == "auto" and not any(B.gpp_stage_lanes(st.handle)):
+    # group launches: the micro-batches that a run of tasks puts on one stream share one launch per step
+    group_flag = 0
+    if kfkb and not args.one_stream and n_slots > 1 and args.group_launches != "off":
+        n_l = AUTO_LANES[0] if args.lanes == "auto" else int(args.lanes.split(",")[0])
+        if n_slots % n_l == 0 and n_slots // n_l >= 2:
+            group_flag = B.flag_group_launches(n_l)
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=n_slots, flags=base_flags | group_flag | (B.FLAG_SHARED_GPU if shared_gpu else 0))
+    lanes_refused = args.shared_gpu == "auto" and want_lanes and args.lanes == "auto" and not any(B.gpp_stage_lanes(st.handle))
+    if lanes_refused or (group_flag and B.gpp_stage_group_launches(st.handle) == (0, 0)):
+        # the stage has steps without a group form, or allows no lanes at all: created again without what it cannot use
         st.close()
-        st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=n_slots, flags=base_flags)
+        group_flag = 0
+        st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=n_slots,
+                     flags=base_flags | (B.FLAG_SHARED_GPU if shared_gpu and not lanes_refused else 0))
     dev_batches = [st.stage_inputs(mb) for mb in wl.batches]       # resident in HBM
     outs = [st.alloc_outputs() for _ in range(max(n_slots, 2))]    # one set per in-flight slot
     gins = st.alloc_grad_inputs()
@@ -229,17 +244,19 @@ def main():
     gins_sched = gins
     if lanes[1] > 1:     # backward passes on different streams may overlap: a set of gradient-input buffers each
         gins_sched = [gins] + [st.alloc_grad_inputs() for _ in range(lanes[1] - 1)]
+    if (B.gpp_stage_info(st.handle)[2] >> 8) & 15:     # group launches: a set per micro-batch in flight
+        gins_sched = [gins] + [st.alloc_grad_inputs() for _ in range(n_slots - 1)]
     if kfkb:
-        sched = TaskSchedule(st, n_slots * wl.micro_batch, args.k, two_streams=not args.one_stream, lanes=lanes,
-                             shared_lanes=shared_lanes)
+        sched = TaskSchedule(st, n_slots * wl.micro_batch, args.k, two_streams=not (args.one_stream or args.same_stream), lanes=lanes,
+                             shared_lanes=shared_lanes and not args.same_stream, same_stream=args.same_stream)
 
     def eager_step(schedule=None):
         schedule = schedule or sched
         if schedule is serial:
             schedule.minibatch(dev_batches, outputs=outs[0], grad_outputs=gouts, grad_inputs=gins, losses=losses[:1])
         else:
-            schedule.minibatch(dev_batches, outputs=outs, grad_outputs=gouts, grad_inputs=gins_sched if schedule is sched else gins,
-                               losses=losses)
+            schedule.minibatch(dev_batches, outputs=outs, grad_outputs=gouts,
+                               grad_inputs=gins_sched if isinstance(schedule, TaskSchedule) else gins, losses=losses)
 
     step = eager_step
 
@@ -295,7 +312,7 @@ def main():
         k_steps = max(1, min(args.steps, 20))
         # per-kernel durations are taken with the calls back to back on ONE stream, eagerly: in serial order, or,
         # with grouped weight gradients (whose kernels depend on the grouping), in the timed task order
-        inst = TaskSchedule(st, n_slots * wl.micro_batch, args.k, two_streams=False) if (kfkb and grouped) else serial
+        inst = TaskSchedule(st, n_slots * wl.micro_batch, args.k, two_streams=False, lanes=lanes, same_stream=True) if (kfkb and grouped) else serial
         for _ in range(k_steps):
             eager_step(inst)
         torch.cuda.synchronize()
@@ -413,7 +430,9 @@ def main():
                    "micro_batch": wl.micro_batch, "micro_batches_per_step": wl.n_micro,
                    "schedule": (f"kFkB from the scheduler: i = {n_slots * wl.micro_batch} samples ({n_slots} micro-batches in flight), k = {args.k}, "
                                 + ("one stream" if args.one_stream else
-                                   (f"micro-batch j on stream j mod {lanes[0]} (forward and backward pass)" if shared_lanes else
+                                   (f"micro-batch j on stream j mod {lanes[0]} (forward and backward pass)"
+                                    + (f", one launch per step for the {n_slots // lanes[0]} micro-batches of a stream" if group_flag else "")
+                                    if shared_lanes else
                                     f"forward passes on {lanes[0]} stream(s), backward passes on {lanes[1]} other stream(s)"))) if kfkb else
                                (f"overlap: forward calls on one stream, backward calls on another, {n_slots} in-flight slots" if overlap else "serial"),
                    "stash_bytes_per_slot": B.gpp_stage_memory(st.handle)[0],

@@ -139,7 +139,19 @@ typedef struct {
                                  pipeline): few-row GEMM launches of at most 64 rows then use workgroups of
                                  four waves instead of eight (half the LDS and registers per workgroup, so
                                  workgroups of concurrent launches fit a compute unit side by side; a launch
-                                 that has the GPU to itself is ~10 % slower that way) */
+                                 that has the GPU to itself is ~10 % slower that way);
+                                 bits 8-11: L > 0 asks for GROUP LAUNCHES in gpp_stage_run_schedule_lanes with L
+                                 streams per direction (needs bit 2, in_flight_slots a multiple of L and at
+                                 least 2 L): where a run of forward (backward) tasks puts several micro-batches
+                                 on one stream, each step of the pass is ONE launch over all of them -- the
+                                 launch tables of their slots one after the other (a second copy of the
+                                 tables, per lane) -- instead of one launch per micro-batch.  Same kernels,
+                                 same tiles per micro-batch, so the results do not change; the chain of
+                                 dependent launches on a stream gets shorter.  Taken where every step has a
+                                 group form (element-wise copies, few-row GEMMs, the fused head) and a run
+                                 starts at slot 0 of each lane; otherwise the call launches per micro-batch.  The
+                                 micro-batches of one launch write their outputs, losses and input gradients
+                                 together: every micro-batch in flight needs buffers of its own */
 } gpp_stage_desc_t;
 
 /* Leading dimension used for parameters and gradient accumulators. */
@@ -349,6 +361,10 @@ gpp_status_t gpp_pipeline_destroy(gpp_pipeline_t *pipeline);
 gpp_status_t gpp_stage_info(const gpp_stage_t *stage, int64_t *micro_batch, int32_t *in_flight_slots, int32_t *flags);
 /* whether several forward / backward streams are allowed in gpp_stage_run_schedule_lanes (1) or not (0) */
 gpp_status_t gpp_stage_lanes(const gpp_stage_t *stage, int32_t *forward_ok, int32_t *backward_ok);
+/* group launches (flag bits 8-11): the number of streams per direction they are set up for and the most
+ * micro-batches one launch covers; 0, 0 when the stage was created without them or has a step without a
+ * group form */
+gpp_status_t gpp_stage_group_launches(const gpp_stage_t *stage, int32_t *lanes, int32_t *members);
 /* rows, features and gpp_dtype_t of the index-th input (is_output = 0) or output (1), and whether a gradient
  * flows through it (an input that returns one / an output that expects one) */
 gpp_status_t gpp_stage_io_info(const gpp_stage_t *stage, int32_t is_output, int32_t index, int64_t *rows,

@@ -33,6 +33,11 @@ FLAG_SIDE_STREAM = 8
 FLAG_SHARED_GPU = 16
 
 
+def flag_group_launches(lanes):
+    """Stage flag bits 8-11: group launches for `lanes` streams per direction."""
+    return (int(lanes) & 15) << 8
+
+
 class OpDesc(C.Structure):
     _fields_ = [
         ("kind", C.c_int32), ("n_in", C.c_int32), ("in_", C.POINTER(C.c_int32)), ("branch", C.c_int32),
@@ -55,7 +60,7 @@ EXPORTS = [
     "gpp_stage_embedding_sort_result", "gpp_last_error", "gpp_stage_profile_enable", "gpp_stage_profile_read",
     "gpp_profile_tag_name", "gpp_compute_in_flight", "gpp_assign_schedules", "gpp_schedule_tasks",
     "gpp_stage_run_schedule", "gpp_stage_memory", "gpp_stage_backward_weights", "gpp_stage_info", "gpp_stage_io_info",
-    "gpp_stage_run_schedule_lanes", "gpp_stage_lanes",
+    "gpp_stage_run_schedule_lanes", "gpp_stage_lanes", "gpp_stage_group_launches",
     "gpp_partition", "gpp_pipeline_workspace_bytes", "gpp_pipeline_create", "gpp_pipeline_run", "gpp_pipeline_destroy",
 ]
 GPP_PROFILE_TAGS = 32
@@ -125,6 +130,7 @@ def load():
     lib.gpp_stage_run_schedule_lanes.argtypes = [vp, C.POINTER(i32), i64, C.POINTER(MicrobatchIO), i64, C.POINTER(vp), i32,
                                                  C.POINTER(vp), i32]
     lib.gpp_stage_lanes.restype, lib.gpp_stage_lanes.argtypes = i32, [vp, C.POINTER(i32), C.POINTER(i32)]
+    lib.gpp_stage_group_launches.restype, lib.gpp_stage_group_launches.argtypes = i32, [vp, C.POINTER(i32), C.POINTER(i32)]
     lib.gpp_stage_memory.restype, lib.gpp_stage_memory.argtypes = i32, [vp] + [C.POINTER(C.c_size_t)] * 3
     lib.gpp_stage_info.restype = i32
     lib.gpp_stage_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i32), C.POINTER(i32)]
@@ -301,6 +307,13 @@ def gpp_stage_lanes(handle):
     f, b = C.c_int32(), C.c_int32()
     _check(load().gpp_stage_lanes(handle, C.byref(f), C.byref(b)))
     return bool(f.value), bool(b.value)
+
+
+def gpp_stage_group_launches(handle):
+    """(streams per direction the group launches are set up for, most micro-batches per launch); (0, 0) = none."""
+    a, b = C.c_int32(), C.c_int32()
+    _check(load().gpp_stage_group_launches(handle, C.byref(a), C.byref(b)))
+    return a.value, b.value
 
 
 def _marshal_io(io, keep):

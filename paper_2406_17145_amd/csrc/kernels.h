@@ -177,6 +177,11 @@ struct HeadProb {
   float scale;
 };
 
+constexpr int HEAD_GROUP_MAX = 16;
+struct HeadOuts {
+  float *p[HEAD_GROUP_MAX];   // where each member's loss sum goes
+};
+
 struct ExtPtrs {
   void *p[64];
 };
@@ -279,7 +284,7 @@ int loss_fwd_blocks(const LossProb &p);
 void launch_loss_fwd_small(const LossProb *probs, int n, float *out, hipStream_t s);
 int loss_small_limit();
 bool head_loss_supported(int64_t rows, int64_t K);
-void launch_head_loss(const HeadProb *prob, int rows, int K, float *out, hipStream_t s);
+void launch_head_loss(const HeadProb *prob, int members, int rows, const HeadOuts &outs, hipStream_t s);
 void launch_loss_bwd(const LossProb *probs, int n, int total_blocks, hipStream_t s);
 int loss_bwd_blocks(const LossProb &p);
 

@@ -777,10 +777,11 @@ __device__ __forceinline__ float head_dot8(const ln_u32x4 &x, const float *w8) {
   }
   return d;
 }
-__global__ __launch_bounds__(64 * HEAD_WAVES) void k_head_loss(const HeadProb *__restrict__ prob, float *out) {
+__global__ __launch_bounds__(64 * HEAD_WAVES) void k_head_loss(const HeadProb *__restrict__ prob, HeadOuts outs) {
   __shared__ float w_f[HEAD_MAX_K];
   __shared__ float red[HEAD_WAVES];
-  const HeadProb p = prob[0];
+  const HeadProb p = prob[blockIdx.y];      // one record per micro-batch of a group launch
+  float *out = outs.p[blockIdx.y];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int chunks = p.K >> 3;
   for (int c = threadIdx.x; c < chunks; c += 64 * HEAD_WAVES) {
@@ -883,10 +884,9 @@ __global__ __launch_bounds__(64 * HEAD_WAVES) void k_head_loss(const HeadProb *_
   for (int c = lane + 64 * KEEP; c < chunks; c += 64)
     put(c, masked ? *(const ln_u32x4 *)((const uint16_t *)p.mask + (int64_t)row * p.ld_mask + 8 * c) : ln_u32x4{0u, 0u, 0u, 0u});
 }
-void launch_head_loss(const HeadProb *prob, int rows, int K, float *out, hipStream_t s) {
-  (void)K;
-  if (!out || rows <= 0) return;
-  hipLaunchKernelGGL(k_head_loss, dim3(1 + (rows + HEAD_WAVES - 1) / HEAD_WAVES), dim3(64 * HEAD_WAVES), 0, s, prob, out);
+void launch_head_loss(const HeadProb *prob, int members, int rows, const HeadOuts &outs, hipStream_t s) {
+  if (members <= 0 || members > HEAD_GROUP_MAX || rows <= 0) return;
+  hipLaunchKernelGGL(k_head_loss, dim3(1 + (rows + HEAD_WAVES - 1) / HEAD_WAVES, members), dim3(64 * HEAD_WAVES), 0, s, prob, outs);
 }
 
 int loss_bwd_blocks(const LossProb &p) { return (p.rows + 3) / 4; }

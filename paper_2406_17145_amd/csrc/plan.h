@@ -72,7 +72,11 @@ struct Plan {
   int32_t slots = 1, flags = 0;
   int64_t slot_bytes = 0, shared_bytes = 0, table_bytes = 0, tmp_bytes = 0;
   int64_t gemm_partial_bytes = 0, gemm_counter_bytes = 0;   // split-K partial tiles and arrival counters
-  int64_t off_flags = 0, off_tables = 0, off_slots = 0, off_shared = 0, total_bytes = 0;
+  int64_t off_flags = 0, off_tables = 0, off_group_tables = 0, off_slots = 0, off_shared = 0, total_bytes = 0;
+  // group launches (flag bits 8-11 = L): a second copy of the launch tables in which the records of the slots
+  // l, l + L, l + 2L, ... follow each other, one table per lane l, so that ONE launch covers a step of several
+  // micro-batches of a kFkB group; 0 = none
+  int32_t group_lanes = 0;
   Buf loss_scalars;                  // f32 partial losses per slot
   int loss_parts = 0;
   std::vector<Step> fwd, bwd;

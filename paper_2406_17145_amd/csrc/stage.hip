@@ -62,6 +62,7 @@ struct gpp_stage {
   int64_t prof_launches[GPP_PROFILE_TAGS] = {0};
   // events of the schedule executor (created on first use, two per micro-batch, no timing)
   std::vector<hipEvent_t> sched_ev;
+  bool group_ok = false;     // group tables are in place (see Plan::group_lanes)
   // side streams (one for forward calls, one for backward calls) and their fork / join events, created with the
   // stage when its plan runs embedding bags next to dense branches
   hipStream_t lane_stream[2] = {nullptr, nullptr};
@@ -110,6 +111,27 @@ static const char *const kTagNames[GPP_PROFILE_TAGS] = {
     "attention_bwd_dkv", "meanpool_fwd", "meanpool_bwd", "embedding_fwd", "embedding_bwd_sort_segsum", "interact_fwd",
     "interact_bwd", "loss_fwd", "loss_bwd", "loss_sum", "embedding_grad_clear", "gemm_skinny_fwd", "gemm_skinny_dx", "gemm_bwd_merged_dx_dw", "gemm_big_fwd", "gemm_big_dx", "gemm_big_dw",
     "gemm_dw_ksplit"};
+
+// Group launches: one launch for a step of several micro-batches (the records of their slots one after the
+// other).  Possible where every step is one of the kinds below, runs on the caller's stream, touches slot
+// memory only, and the per-call pointers of all members fit one pointer block.
+static size_t group_record_bytes(int kern) {
+  return kern == K_ELT ? sizeof(EltProb) : kern == K_GEMM_SKINNY ? sizeof(GemmProb) : kern == K_HEAD_LOSS ? sizeof(HeadProb) : 0;
+}
+static bool group_supported(const Plan &pl) {
+  if (pl.group_lanes <= 0 || pl.fwd_shared || pl.bwd_shared || pl.lanes) return false;
+  const int G = pl.slots / pl.group_lanes;
+  if (G > HEAD_GROUP_MAX) return false;
+  for (const std::vector<Step> *list : {&pl.fwd, &pl.bwd})
+    for (const Step &sp : *list) {
+      if (group_record_bytes(sp.kern) == 0 || sp.lane != 0 || sp.launches != 1) return false;
+      if (sp.ext_kind != EXT_NONE) {
+        const int total = (sp.ext_kind == EXT_INPUTS || sp.ext_kind == EXT_GRAD_INPUTS) ? (int)pl.input_ops.size() : (int)pl.output_ops.size();
+        if (sp.ext_base != 0 || G * total > 64) return false;
+      }
+    }
+  return true;
+}
 
 extern "C" {
 
@@ -172,11 +194,45 @@ gpp_status_t gpp_stage_create(const gpp_stage_desc_t *desc, void *workspace, siz
   }
   st->ws = (char *)workspace;
   hipError_t he = hipMemset(workspace, 0, (size_t)pl.total_bytes);
+  std::vector<std::vector<uint8_t>> blobs;
   for (int s = 0; he == hipSuccess && s < pl.slots; ++s) {
     rc = pl.emit(s, st->ws);
     if (rc != GPP_OK) break;
     if (!pl.blob.empty())
       he = hipMemcpy(st->ws + pl.off_tables + (int64_t)s * pl.table_bytes, pl.blob.data(), pl.blob.size(), hipMemcpyHostToDevice);
+    if (pl.group_lanes > 0) blobs.push_back(pl.blob);
+  }
+  if (he == hipSuccess && rc == GPP_OK && pl.group_lanes > 0 && group_supported(pl)) {
+    const int L = pl.group_lanes, G = pl.slots / L;
+    for (int l = 0; l < L && he == hipSuccess; ++l) {
+      std::vector<uint8_t> gb((size_t)G * pl.table_bytes, 0);
+      for (int i = 0; i < G; ++i) {
+        const std::vector<uint8_t> &src = blobs[l + L * i];
+        for (const std::vector<Step> *list : {&pl.fwd, &pl.bwd})
+          for (const Step &sp : *list) {
+            const size_t rec = group_record_bytes(sp.kern);
+            uint8_t *dst = gb.data() + (size_t)G * sp.table_off + (size_t)i * sp.n * rec;
+            memcpy(dst, src.data() + sp.table_off, (size_t)sp.n * rec);
+            const int ext_total = sp.ext_kind == EXT_NONE ? 0
+                                  : ((sp.ext_kind == EXT_INPUTS || sp.ext_kind == EXT_GRAD_INPUTS) ? (int)pl.input_ops.size()
+                                                                                                   : (int)pl.output_ops.size());
+            for (int r = 0; r < sp.n; ++r) {     // member i's workgroups and per-call pointers follow those of members 0 .. i-1
+              if (sp.kern == K_ELT) {
+                EltProb *e = (EltProb *)dst + r;
+                e->blk_begin += i * sp.blocks;
+                if (e->ext_src >= 0) e->ext_src += i * ext_total;
+                if (e->ext_dst >= 0) e->ext_dst += i * ext_total;
+              } else if (sp.kern == K_GEMM_SKINNY) {
+                GemmProb *g = (GemmProb *)dst + r;
+                g->blk_begin += i * sp.blocks;
+                if (g->c_ext > 0) g->c_ext += i * ext_total;
+              }
+            }
+          }
+      }
+      he = hipMemcpy(st->ws + pl.off_group_tables + (int64_t)l * G * pl.table_bytes, gb.data(), gb.size(), hipMemcpyHostToDevice);
+    }
+    st->group_ok = he == hipSuccess;
   }
   if (he == hipSuccess) he = hipDeviceSynchronize();
   if (he != hipSuccess || rc != GPP_OK) {
@@ -240,6 +296,12 @@ gpp_status_t gpp_stage_lanes(const gpp_stage_t *s, int32_t *forward_ok, int32_t 
   if (!s) return fail(GPP_ERR_INVALID_ARG, "stage is null");
   if (forward_ok) *forward_ok = !(s->plan.fwd_shared || s->plan.lanes);
   if (backward_ok) *backward_ok = !(s->plan.bwd_shared || s->plan.lanes);
+  return GPP_OK;
+}
+gpp_status_t gpp_stage_group_launches(const gpp_stage_t *s, int32_t *lanes, int32_t *members) {
+  if (!s) return fail(GPP_ERR_INVALID_ARG, "stage is null");
+  if (lanes) *lanes = s->group_ok ? s->plan.group_lanes : 0;
+  if (members) *members = s->group_ok ? s->plan.slots / s->plan.group_lanes : 0;
   return GPP_OK;
 }
 gpp_status_t gpp_stage_io_info(const gpp_stage_t *s, int32_t is_output, int32_t index, int64_t *rows, int64_t *features,
@@ -340,7 +402,10 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
       case K_GEMM_BWD_MERGED: launch_gemm_bwd_merged((const GemmProb *)tab, sp.n, sp.blocks, sp.a2, sp.a1, accumulate, ext, s); break;
       case K_HEAD_LOSS: {   // always runs: it also writes the prediction and two gradients
         float *sink = loss_out ? loss_out : (float *)(st->ws + pl.off_slots + (int64_t)slot * pl.slot_bytes + pl.loss_scalars.off);
-        launch_head_loss((const HeadProb *)tab, sp.a0, sp.a1, sink, s);
+        HeadOuts ho;
+        memset(&ho, 0, sizeof(ho));
+        ho.p[0] = sink;
+        launch_head_loss((const HeadProb *)tab, 1, sp.a0, ho, s);
         break;
       }
       case K_LOSS_FWD_SMALL: {
@@ -396,6 +461,75 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
         }
         break;
       default: return fail(GPP_ERR_UNSUPPORTED, "internal: unknown step");
+    }
+    if (ev_end) (void)hipEventRecord(ev_end, s);
+  }
+  hipError_t he = hipGetLastError();
+  if (he != hipSuccess) return fail(GPP_ERR_DEVICE, std::string("HIP launch: ") + hipGetErrorString(he));
+  return GPP_OK;
+}
+
+// One launch per step for the micro-batches `members` (ids into io) of lane `lane`: their slots are
+// lane, lane + L, lane + 2 L, ... in this order (the caller has checked it).
+static gpp_status_t run_steps_group(gpp_stage *st, const std::vector<Step> &steps, int lane, const std::vector<int64_t> &members,
+                                    const gpp_microbatch_io_t *io, hipStream_t s) {
+  Plan &pl = st->plan;
+  const int G = pl.slots / pl.group_lanes, m = (int)members.size();
+  const char *tables = st->ws + pl.off_group_tables + (int64_t)lane * G * pl.table_bytes;
+  const bool is_bwd = &steps == &pl.bwd;
+  for (const Step &sp : steps) {
+    const void *tab = tables + (int64_t)G * sp.table_off;
+    ExtPtrs ext;
+    memset(&ext, 0, sizeof(ext));
+    if (sp.ext_kind != EXT_NONE) {
+      const int total = (sp.ext_kind == EXT_INPUTS || sp.ext_kind == EXT_GRAD_INPUTS) ? (int)pl.input_ops.size()
+                                                                                     : (int)pl.output_ops.size();
+      for (int i = 0; i < m; ++i) {
+        const gpp_microbatch_io_t &mb = io[members[i]];
+        for (int k = 0; k < total; ++k) {
+          const void *ptr = nullptr;
+          switch (sp.ext_kind) {
+            case EXT_INPUTS: ptr = mb.inputs ? mb.inputs[k] : nullptr; break;
+            case EXT_OUTPUTS: ptr = mb.outputs ? mb.outputs[k] : nullptr; break;
+            case EXT_GRAD_OUTPUTS: ptr = mb.grad_outputs ? mb.grad_outputs[k] : nullptr; break;
+            default: ptr = mb.grad_inputs ? mb.grad_inputs[k] : nullptr; break;
+          }
+          ext.p[i * total + k] = (void *)ptr;
+        }
+      }
+    }
+    hipEvent_t ev_end = nullptr;
+    if (st->prof_on) {       // as in run_steps: a bracket of two events per step, GEMM steps repeated inside it
+      if (st->prof_used + 2 > st->prof_ev.size()) {
+        for (int k = 0; k < 2; ++k) {
+          hipEvent_t e;
+          if (hipEventCreate(&e) != hipSuccess) return fail(GPP_ERR_DEVICE, "hipEventCreate failed");
+          st->prof_ev.push_back(e);
+        }
+      }
+      (void)hipEventRecord(st->prof_ev[st->prof_used], s);
+      ev_end = st->prof_ev[st->prof_used + 1];
+      st->prof_tag.resize(st->prof_used / 2 + 1);
+      st->prof_tag[st->prof_used / 2] = step_tag(sp, is_bwd) | ((sp.launches * (gemm_step(sp) ? st->prof_repeat : 1)) << 8);
+      st->prof_used += 2;
+    }
+    const int reps = (st->prof_on && gemm_step(sp)) ? st->prof_repeat : 1;
+    for (int rep = 0; rep < reps; ++rep)
+    switch (sp.kern) {
+      case K_ELT: launch_elt((const EltProb *)tab, m * sp.n, m * sp.blocks, ext, s); break;
+      case K_GEMM_SKINNY: launch_gemm_skinny((const GemmProb *)tab, m * sp.n, m * sp.blocks, sp.a1, sp.a2, sp.a0, sp.a3, ext, s); break;
+      case K_HEAD_LOSS: {
+        HeadOuts ho;
+        memset(&ho, 0, sizeof(ho));
+        for (int i = 0; i < m; ++i) {
+          const int slot = lane + pl.group_lanes * i;
+          float *lo = io[members[i]].loss_out;
+          ho.p[i] = lo ? lo : (float *)(st->ws + pl.off_slots + (int64_t)slot * pl.slot_bytes + pl.loss_scalars.off);
+        }
+        launch_head_loss((const HeadProb *)tab, m, sp.a0, ho, s);
+        break;
+      }
+      default: return fail(GPP_ERR_UNSUPPORTED, "internal: step without a group form");
     }
     if (ev_end) (void)hipEventRecord(ev_end, s);
   }
@@ -561,53 +695,148 @@ static gpp_status_t run_schedule_lanes(gpp_stage_t *st, const int32_t *tasks, in
   }
   gpp_status_t rc = gpp_stage_grad_reset(st, streams_backward[0]);
   if (rc != GPP_OK) return rc;
-  int64_t last_group = -1;   // micro-batch whose slot-free event follows the latest group launch
-  for (int64_t t = 0; t < n_tasks; ++t) {
-    const int64_t j = (tasks[t] > 0 ? tasks[t] : -tasks[t]) - 1;
-    const int32_t slot = (int32_t)(j % slots);
-    const gpp_microbatch_io_t &m = io[j];
-    hipError_t he = hipSuccess;
-    if (tasks[t] > 0) {
-      hipStream_t sf = (hipStream_t)streams_forward[j % nf];
-      // the slot's previous micro-batch must have been consumed by its backward pass
-      if (two && j >= slots) he = hipStreamWaitEvent(sf, st->sched_ev[3 * (j - slots) + 1], 0);
-      if (he == hipSuccess) {
-        rc = gpp_stage_forward(st, slot, m.inputs, m.outputs, m.loss_out, sf);
+  int64_t last_group = -1;   // micro-batch whose slot-free event follows the latest group launch of weight gradients
+  hipError_t he = hipSuccess;
+  const int L = pl.group_lanes;
+
+  // after the last backward pass of a run (micro-batches j - run + 1 .. j, the last one on stream sb): the
+  // grouped weight gradients, which follow every backward pass of the run (other lanes: their events) and the
+  // group launch before it (both add into the same accumulators); only then are the run's slots free
+  auto finish_backward_run = [&](int64_t j, hipStream_t sb) -> gpp_status_t {
+    const int64_t run = (int64_t)st->pending.size();
+    for (int64_t q = j - run + 1; q < j && he == hipSuccess; ++q)
+      if (two && nb > 1 && streams_backward[q % nb] != (void *)sb) he = hipStreamWaitEvent(sb, st->sched_ev[3 * q + 2], 0);
+    if (two && nb > 1 && last_group >= 0 && he == hipSuccess) he = hipStreamWaitEvent(sb, st->sched_ev[3 * last_group + 1], 0);
+    if (he == hipSuccess) {
+      gpp_status_t r = gpp_stage_backward_weights(st, sb);
+      if (r != GPP_OK) return r;
+    }
+    if (two)
+      for (int64_t q = j - run + 1; q <= j && he == hipSuccess; ++q) he = hipEventRecord(st->sched_ev[3 * q + 1], sb);
+    last_group = j;
+    return GPP_OK;
+  };
+
+  for (int64_t t = 0; t < n_tasks;) {
+    const bool fwd = tasks[t] > 0;
+    int64_t e = t + 1;
+    while (e < n_tasks && (tasks[e] > 0) == fwd) ++e;
+    const int64_t j0 = (fwd ? tasks[t] : -tasks[t]) - 1, m = e - t;     // the run: micro-batches j0 .. j0 + m - 1
+
+    // ---- group launches: per lane, ONE launch per step for all micro-batches of the run on that lane
+    bool grouped_run = st->group_ok && m >= 2 && L == (fwd ? nf : nb);
+    std::vector<std::vector<int64_t>> members(grouped_run ? L : 0);
+    if (grouped_run) {
+      for (int64_t j = j0; j < j0 + m; ++j) members[j % L].push_back(j);
+      for (int l = 0; l < L && grouped_run; ++l)
+        for (size_t i = 0; i < members[l].size(); ++i)
+          if ((int)(members[l][i] % slots) != l + L * (int)i) grouped_run = false;    // not the slots the lane's table holds, in its order
+    }
+    if (grouped_run && fwd) {
+      for (int64_t j = j0; j < j0 + m; ++j) {
+        const gpp_microbatch_io_t &mb = io[j];
+        if (!mb.inputs) return fail(GPP_ERR_INVALID_ARG, "inputs is null");
+        for (size_t k = 0; k < pl.input_ops.size(); ++k)
+          if (!mb.inputs[k] || ((uintptr_t)mb.inputs[k] & 3)) return fail(GPP_ERR_INVALID_ARG, "input " + std::to_string(k) + " is null or misaligned");
+        if (!pl.output_ops.empty() && !mb.outputs) return fail(GPP_ERR_INVALID_ARG, "outputs is null but the stage has outputs");
+        if (st->slot_busy[j % slots]) return fail(GPP_ERR_ORDER, "slot " + std::to_string(j % slots) + " still holds a micro-batch in flight");
+      }
+      for (int l = 0; l < L && he == hipSuccess; ++l) {
+        if (members[l].empty()) continue;
+        hipStream_t sf = (hipStream_t)streams_forward[l];
+        for (int64_t j : members[l])
+          if (two && j >= slots && he == hipSuccess) he = hipStreamWaitEvent(sf, st->sched_ev[3 * (j - slots) + 1], 0);
+        if (he != hipSuccess) break;
+        rc = run_steps_group(st, pl.fwd, l, members[l], io, sf);
         if (rc != GPP_OK) return rc;
-        if (two) he = hipEventRecord(st->sched_ev[3 * j], sf);
+        for (int64_t j : members[l])
+          if (two && he == hipSuccess) he = hipEventRecord(st->sched_ev[3 * j], sf);
+      }
+      for (int64_t j = j0; j < j0 + m; ++j) {
+        st->slot_busy[j % slots] = 1;
+        st->fifo.push_back((int32_t)(j % slots));
+      }
+    } else if (grouped_run) {
+      for (int64_t j = j0; j < j0 + m; ++j) {
+        const gpp_microbatch_io_t &mb = io[j];
+        if (!pl.output_ops.empty()) {
+          if (!mb.grad_outputs) return fail(GPP_ERR_INVALID_ARG, "grad_outputs is null but the stage has outputs");
+          for (size_t k = 0; k < pl.output_ops.size(); ++k)
+            if (pl.nodes[pl.output_ops[k]].wants_grad && !mb.grad_outputs[k]) return fail(GPP_ERR_INVALID_ARG, "grad_outputs[" + std::to_string(k) + "] is null");
+        }
+        if (st->slot_busy[j % slots] != 1 || (int64_t)st->fifo.size() <= j - j0 || st->fifo[j - j0] != (int32_t)(j % slots))
+          return fail(GPP_ERR_ORDER, "backward out of order (C4)");
+      }
+      for (int l = 0; l < L && he == hipSuccess; ++l) {
+        if (members[l].empty()) continue;
+        hipStream_t sb = (hipStream_t)streams_backward[l];
+        for (int64_t j : members[l])
+          if (two && (void *)sb != streams_forward[j % nf] && he == hipSuccess) he = hipStreamWaitEvent(sb, st->sched_ev[3 * j], 0);
+        if (he != hipSuccess) break;
+        rc = run_steps_group(st, pl.bwd, l, members[l], io, sb);
+        if (rc != GPP_OK) return rc;
+        for (int64_t j : members[l])
+          if (two && nb > 1 && he == hipSuccess) he = hipEventRecord(st->sched_ev[3 * j + 2], sb);
+      }
+      st->fresh = false;
+      for (int64_t j = j0; j < j0 + m; ++j) {
+        st->fifo.pop_front();
+        if (pl.dwg.empty()) {
+          st->slot_busy[j % slots] = 0;
+        } else {
+          st->slot_busy[j % slots] = 2;
+          st->pending.push_back((int32_t)(j % slots));
+        }
+      }
+      const int64_t jl = j0 + m - 1;
+      hipStream_t sl = (hipStream_t)streams_backward[jl % nb];
+      if (he == hipSuccess) {
+        if (!st->pending.empty()) {
+          rc = finish_backward_run(jl, sl);
+          if (rc != GPP_OK) return rc;
+        } else if (two) {     // no grouped weight gradients: every slot is free after its lane's launch
+          for (int64_t j = j0; j < j0 + m && he == hipSuccess; ++j) he = hipEventRecord(st->sched_ev[3 * j + 1], (hipStream_t)streams_backward[j % nb]);
+        }
       }
     } else {
-      hipStream_t sb = (hipStream_t)streams_backward[j % nb];
-      // (a backward pass on its forward pass's own stream follows it there without an event)
-      if (two && (void *)sb != streams_forward[j % nf]) he = hipStreamWaitEvent(sb, st->sched_ev[3 * j], 0);
-      if (he == hipSuccess) {
-        rc = gpp_stage_backward(st, slot, m.grad_outputs, m.grad_inputs, sb);
-        if (rc != GPP_OK) return rc;
-        // grouped weight gradients: one launch after the last backward pass of a run of backward
-        // tasks; only then are the run's slots free for the forward passes that wait for them
-        const bool run_ends = t + 1 == n_tasks || tasks[t + 1] > 0;
-        if (st->pending.empty()) {
-          if (two) he = hipEventRecord(st->sched_ev[3 * j + 1], sb);
-        } else if (!run_ends) {
-          if (nb > 1) he = hipEventRecord(st->sched_ev[3 * j + 2], sb);
-        } else {
-          const int64_t run = (int64_t)st->pending.size();
-          // the launch follows every backward pass of its run (other lanes: their events) and the
-          // group launch before it (both add into the same accumulators)
-          for (int64_t q = j - run + 1; q < j && he == hipSuccess; ++q)
-            if (nb > 1 && streams_backward[q % nb] != (void *)sb) he = hipStreamWaitEvent(sb, st->sched_ev[3 * q + 2], 0);
-          if (nb > 1 && last_group >= 0 && he == hipSuccess) he = hipStreamWaitEvent(sb, st->sched_ev[3 * last_group + 1], 0);
+      // ---- one micro-batch at a time
+      for (int64_t u = t; u < e; ++u) {
+        const int64_t j = (tasks[u] > 0 ? tasks[u] : -tasks[u]) - 1;
+        const int32_t slot = (int32_t)(j % slots);
+        const gpp_microbatch_io_t &mb = io[j];
+        if (fwd) {
+          hipStream_t sf = (hipStream_t)streams_forward[j % nf];
+          // the slot's previous micro-batch must have been consumed by its backward pass
+          if (two && j >= slots) he = hipStreamWaitEvent(sf, st->sched_ev[3 * (j - slots) + 1], 0);
           if (he == hipSuccess) {
-            rc = gpp_stage_backward_weights(st, sb);
+            rc = gpp_stage_forward(st, slot, mb.inputs, mb.outputs, mb.loss_out, sf);
             if (rc != GPP_OK) return rc;
+            if (two) he = hipEventRecord(st->sched_ev[3 * j], sf);
           }
-          if (two)
-            for (int64_t q = j - run + 1; q <= j && he == hipSuccess; ++q) he = hipEventRecord(st->sched_ev[3 * q + 1], sb);
-          last_group = j;
+        } else {
+          hipStream_t sb = (hipStream_t)streams_backward[j % nb];
+          // (a backward pass on its forward pass's own stream follows it there without an event)
+          if (two && (void *)sb != streams_forward[j % nf]) he = hipStreamWaitEvent(sb, st->sched_ev[3 * j], 0);
+          if (he == hipSuccess) {
+            rc = gpp_stage_backward(st, slot, mb.grad_outputs, mb.grad_inputs, sb);
+            if (rc != GPP_OK) return rc;
+            // grouped weight gradients: one launch after the last backward pass of a run of backward
+            // tasks; only then are the run's slots free for the forward passes that wait for them
+            if (st->pending.empty()) {
+              if (two) he = hipEventRecord(st->sched_ev[3 * j + 1], sb);
+            } else if (u + 1 < e) {
+              if (two && nb > 1) he = hipEventRecord(st->sched_ev[3 * j + 2], sb);
+            } else {
+              rc = finish_backward_run(j, sb);
+              if (rc != GPP_OK) return rc;
+            }
+          }
         }
+        if (he != hipSuccess) break;
       }
     }
     if (he != hipSuccess) return fail(GPP_ERR_DEVICE, std::string("HIP event: ") + hipGetErrorString(he));
+    t = e;
   }
   return GPP_OK;
 }

@@ -89,7 +89,7 @@ class TaskSchedule:
     shared_lanes the backward passes use the forward streams (fw_j and bw_j of a micro-batch then follow each
     other on ONE stream: no event between them, one chain of launches per micro-batch)."""
 
-    def __init__(self, stage, in_flight_samples, k, two_streams=True, lanes=(1, 1), shared_lanes=False):
+    def __init__(self, stage, in_flight_samples, k, two_streams=True, lanes=(1, 1), shared_lanes=False, same_stream=False):
         from . import binding as B
         torch = stage.torch
         self.B, self.st = B, stage
@@ -99,7 +99,9 @@ class TaskSchedule:
             raise ValueError(f"{cap} micro-batches in flight need a stage with in_flight_slots >= {cap}")
         self.two = bool(two_streams)
         self.lanes = (int(lanes[0]), int(lanes[1]))
-        if self.lanes != (1, 1) and not self.two:
+        # same_stream: the lanes' calls (and their group launches) all on the current stream, for timing passes
+        self.same_stream = bool(same_stream) and self.lanes != (1, 1)
+        if self.lanes != (1, 1) and not self.two and not self.same_stream:
             raise ValueError("lanes need two_streams")
         if self.two:                                         # default priority on all
             self.fw_streams = [torch.cuda.Stream(device=stage.dev) for _ in range(self.lanes[0])]
@@ -124,8 +126,10 @@ class TaskSchedule:
         if outputs is None:
             outputs = self._outs = getattr(self, "_outs", None) or [st.alloc_outputs() for _ in range(st.slots)]
         if grad_inputs is None:     # one set per backward stream: passes on different streams may overlap
+            grouped = (B.gpp_stage_info(st.handle)[2] >> 8) & 15     # group launches: a set per micro-batch in flight
+            sets = st.slots if grouped else self.lanes[1]
             grad_inputs = self._gin = getattr(self, "_gin", None) or (
-                st.alloc_grad_inputs() if self.lanes[1] == 1 else [st.alloc_grad_inputs() for _ in range(self.lanes[1])])
+                st.alloc_grad_inputs() if sets == 1 else [st.alloc_grad_inputs() for _ in range(sets)])
         if losses is None:
             losses = [st.loss]
 
@@ -151,6 +155,8 @@ class TaskSchedule:
                                                       [s.cuda_stream for s in self.bw_streams])
             for s in every:
                 main.wait_stream(s)
+        elif self.same_stream:
+            keep = B.gpp_stage_run_schedule_lanes(st.handle, tasks, io, [main.cuda_stream] * self.lanes[0], [main.cuda_stream] * self.lanes[1])
         else:
             keep = B.gpp_stage_run_schedule(st.handle, tasks, io, main.cuda_stream, main.cuda_stream)
         self._keep = (keep, batches, outputs, grad_outputs, grad_inputs, losses)

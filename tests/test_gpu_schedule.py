@@ -17,7 +17,7 @@ def _codes(tasks):
     return [(j + 1) if w == "F" else -(j + 1) for w, j in tasks]
 
 
-def _run(wl, cap, k, two_streams, slots=None, gouts=None, reps=1, flags=0, lanes=(1, 1), shared_lanes=False):
+def _run(wl, cap, k, two_streams, slots=None, gouts=None, reps=1, flags=0, lanes=(1, 1), shared_lanes=False, same_stream=False):
     import torch
     st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=slots or cap, flags=flags)
     n = len(wl.batches)
@@ -26,7 +26,7 @@ def _run(wl, cap, k, two_streams, slots=None, gouts=None, reps=1, flags=0, lanes
     outs = [st.alloc_outputs() for _ in range(n)]
     gins = [st.alloc_grad_inputs() for _ in range(n)]
     dg = None if gouts is None else [[st.to_device(i, g[i]) for i in st.output_ids] for g in gouts]
-    sched = TaskSchedule(st, cap * wl.micro_batch, k, two_streams=two_streams, lanes=lanes, shared_lanes=shared_lanes)
+    sched = TaskSchedule(st, cap * wl.micro_batch, k, two_streams=two_streams, lanes=lanes, shared_lanes=shared_lanes, same_stream=same_stream)
     for _ in range(reps):
         tasks = sched.minibatch(dev_batches, outputs=outs, grad_outputs=dg, grad_inputs=gins, losses=losses)
     st.sync_status()
@@ -138,9 +138,9 @@ def test_stage_memory_report():
 
 def test_config2_full_size_in_the_launch_configuration_the_benchmark_times():
     # the benchmark's default step: the full CANDLE-Uno-shaped stage, a stash slot per micro-batch, the scheduler's
-    # task list for that many in-flight micro-batches run by the executor with micro-batch j on stream j mod 4
-    # (forward and backward pass), weight gradients of the whole run of backward passes in one grouped launch,
-    # everything captured once into a HIP graph and replayed.
+    # task list for that many in-flight micro-batches run by the executor with micro-batch j on stream j mod 2
+    # (forward and backward pass), one launch per step for the four micro-batches of a stream, weight gradients of
+    # the whole run of backward passes in one grouped launch, everything captured once into a HIP graph and replayed.
     # Checked against the oracle in full (losses, input gradients, every accumulated gradient); every replay
     # (accumulators poisoned, eager work and synchronisations in between) must reproduce the eager run of the
     # same configuration bit for bit.
@@ -150,13 +150,14 @@ def test_config2_full_size_in_the_launch_configuration_the_benchmark_times():
     n = wl.n_micro
     print(f"[case] {wl.name} full size, {n} in flight, grouped weight gradients, graph replay", flush=True)
     ora_stage, ora_res = run_oracle(wl)
-    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=n, flags=B.FLAG_GROUPED_DW | B.FLAG_SHARED_GPU)
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=n, flags=B.FLAG_GROUPED_DW | B.FLAG_SHARED_GPU | B.flag_group_launches(2))
     assert st.num_launches(2) == 1
     assert B.gpp_stage_lanes(st.handle) == (True, True)
+    assert B.gpp_stage_group_launches(st.handle) == (2, n // 2)
     dev_batches = [st.stage_inputs(mb) for mb in wl.batches]
     losses = [torch.zeros(1, dtype=torch.float32, device=st.dev) for _ in range(n)]
     gins = [st.alloc_grad_inputs() for _ in range(n)]
-    sched = TaskSchedule(st, n * wl.micro_batch, n, two_streams=True, lanes=(4, 4), shared_lanes=True)
+    sched = TaskSchedule(st, n * wl.micro_batch, n, two_streams=True, lanes=(2, 2), shared_lanes=True)
     outs = [[] for _ in range(n)]
     sched.minibatch(dev_batches, outputs=outs, grad_inputs=gins, losses=losses)     # eager first
     st.sync_status()
@@ -484,3 +485,53 @@ def test_large_elementwise_loss_writes_its_gradient_in_the_forward_pass():
         ora_stage, ora_res = run_oracle(wl)
         _, res, grads = _run(wl, 3, 2, True, reps=2, flags=B.FLAG_GROUPED_DW)
         compare(wl, res, grads, ora_stage, ora_res, label=f"large loss {dtype}")
+
+
+# ---- group launches: the micro-batches a run of tasks puts on one stream share one launch per step ------
+
+def test_group_launches_give_the_one_stream_results_bit_for_bit():
+    for mb, hidden, act in [(48, 160, "gelu"), (64, 1000, "relu"), (300, 160, "relu")]:      # (the last one has steps without a group form)
+        for n_micro, slots, lanes in [(8, 8, 4), (7, 8, 4), (8, 8, 2), (12, 8, 4), (6, 6, 3), (5, 4, 2)]:
+            wl = W.candle_uno(micro_batch=mb, n_micro=n_micro, widths=(70, 131, 9, 33), hidden=hidden, act=act)
+            flags = B.FLAG_GROUPED_DW | B.FLAG_SHARED_GPU
+            _, res1, grads1 = _run(wl, slots, slots, False, reps=2, flags=flags)
+            st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=slots, flags=flags | B.flag_group_launches(lanes))
+            assert B.gpp_stage_group_launches(st.handle) == ((lanes, slots // lanes) if mb <= 256 else (0, 0))
+            st.close()
+            for shared in (True, False):
+                print(f"[case] {wl.name} b={mb} hidden={hidden} group launches: {n_micro} micro-batches, {slots} slots, {lanes} lanes, "
+                      f"shared={shared}", flush=True)
+                _, res, grads = _run(wl, slots, slots, True, reps=2, flags=flags | B.flag_group_launches(lanes), lanes=(lanes, lanes),
+                                     shared_lanes=shared)
+                _same(res, grads, res1, grads1, f"group launches n={n_micro} slots={slots} lanes={lanes} shared={shared}")
+            # every lane on the caller's stream (no events at all), on a stage that has never seen two streams
+            _, res, grads = _run(wl, slots, slots, False, reps=2, flags=flags | B.flag_group_launches(lanes), lanes=(lanes, lanes),
+                                 same_stream=True)
+            _same(res, grads, res1, grads1, f"group launches n={n_micro} slots={slots} lanes={lanes} on one stream")
+        if hidden == 160:
+            ora_stage, ora_res = run_oracle(wl)
+            compare(wl, res, grads, ora_stage, ora_res, label="group launches vs oracle")
+
+
+def test_group_launches_on_a_mid_pipeline_stage_and_where_they_do_not_apply():
+    wl = W.hetero(micro_batch=9, n_micro=8, base_width=16, out_width=24, dtype="bf16", with_loss=False)
+    out = len(wl.ops) - 1
+    rng = np.random.default_rng(12)
+    gouts = [{out: rng.standard_normal((9, 192)).astype(np.float32)} for _ in range(8)]
+    ora_stage, ora_res = run_oracle(wl, gouts)
+    flags = B.FLAG_GROUPED_DW
+    _, res1, grads1 = _run(wl, 8, 8, False, gouts=gouts, flags=flags)
+    compare(wl, res1, grads1, ora_stage, ora_res, label="mid one stream")
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=8, flags=flags | B.flag_group_launches(4))
+    print(f"[case] {wl.name} mid-pipeline stage: group launches {B.gpp_stage_group_launches(st.handle)}", flush=True)
+    st.close()
+    _, res, grads = _run(wl, 8, 8, True, gouts=gouts, flags=flags | B.flag_group_launches(4), lanes=(4, 4), shared_lanes=True)
+    _same(res, grads, res1, grads1, "mid group launches")
+    # stages with steps that have no group form keep launching per micro-batch, whatever the flag asks for
+    wl = W.dlrm(micro_batch=32, n_micro=4, n_tables=3, num_rows=500, bottom=(64, 32, 128), top=(128, 64, 1))
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=4, flags=flags | B.flag_group_launches(2))
+    assert B.gpp_stage_group_launches(st.handle) == (0, 0)
+    st.close()
+    ora_stage, ora_res = run_oracle(wl)
+    _, res, grads = _run(wl, 4, 4, True, flags=flags | B.flag_group_launches(2))
+    compare(wl, res, grads, ora_stage, ora_res, label="dlrm with the group flag")
