@@ -118,13 +118,15 @@ static const char *const kTagNames[GPP_PROFILE_TAGS] = {
 static size_t group_record_bytes(int kern) {
   return kern == K_ELT ? sizeof(EltProb) : kern == K_GEMM_SKINNY ? sizeof(GemmProb) : kern == K_HEAD_LOSS ? sizeof(HeadProb) : 0;
 }
+// (the loss sum of a stage without losses has no records: it only clears the caller's loss value)
+static bool group_form(const Step &sp) { return group_record_bytes(sp.kern) != 0 || (sp.kern == K_LOSS_SUM && sp.n == 0); }
 static bool group_supported(const Plan &pl) {
   if (pl.group_lanes <= 0 || pl.fwd_shared || pl.bwd_shared || pl.lanes) return false;
   const int G = pl.slots / pl.group_lanes;
   if (G > HEAD_GROUP_MAX) return false;
   for (const std::vector<Step> *list : {&pl.fwd, &pl.bwd})
     for (const Step &sp : *list) {
-      if (group_record_bytes(sp.kern) == 0 || sp.lane != 0 || sp.launches != 1) return false;
+      if (!group_form(sp) || sp.lane != 0 || sp.launches != 1) return false;
       if (sp.ext_kind != EXT_NONE) {
         const int total = (sp.ext_kind == EXT_INPUTS || sp.ext_kind == EXT_GRAD_INPUTS) ? (int)pl.input_ops.size() : (int)pl.output_ops.size();
         if (sp.ext_base != 0 || G * total > 64) return false;
@@ -212,6 +214,7 @@ gpp_status_t gpp_stage_create(const gpp_stage_desc_t *desc, void *workspace, siz
           for (const Step &sp : *list) {
             const size_t rec = group_record_bytes(sp.kern);
             uint8_t *dst = gb.data() + (size_t)G * sp.table_off + (size_t)i * sp.n * rec;
+            if (sp.n <= 0 || rec == 0) continue;
             memcpy(dst, src.data() + sp.table_off, (size_t)sp.n * rec);
             const int ext_total = sp.ext_kind == EXT_NONE ? 0
                                   : ((sp.ext_kind == EXT_INPUTS || sp.ext_kind == EXT_GRAD_INPUTS) ? (int)pl.input_ops.size()
@@ -529,6 +532,10 @@ static gpp_status_t run_steps_group(gpp_stage *st, const std::vector<Step> &step
         launch_head_loss((const HeadProb *)tab, m, sp.a0, ho, s);
         break;
       }
+      case K_LOSS_SUM:       // no loss operators: every member that asks for a loss value gets zero
+        for (int i = 0; i < m; ++i)
+          if (io[members[i]].loss_out) launch_loss_sum(nullptr, 0, io[members[i]].loss_out, s);
+        break;
       default: return fail(GPP_ERR_UNSUPPORTED, "internal: step without a group form");
     }
     if (ev_end) (void)hipEventRecord(ev_end, s);

@@ -514,19 +514,23 @@ def test_group_launches_give_the_one_stream_results_bit_for_bit():
 
 
 def test_group_launches_on_a_mid_pipeline_stage_and_where_they_do_not_apply():
-    wl = W.hetero(micro_batch=9, n_micro=8, base_width=16, out_width=24, dtype="bf16", with_loss=False)
+    # a stage with outputs: the group launches carry the output, output-gradient and input-gradient pointers of all
+    # their micro-batches
+    wl = W.hetero(micro_batch=16, n_micro=8, base_width=64, out_width=64, dtype="bf16", with_loss=False)
     out = len(wl.ops) - 1
     rng = np.random.default_rng(12)
-    gouts = [{out: rng.standard_normal((9, 192)).astype(np.float32)} for _ in range(8)]
+    gouts = [{out: rng.standard_normal((16, 512)).astype(np.float32)} for _ in range(8)]
     ora_stage, ora_res = run_oracle(wl, gouts)
     flags = B.FLAG_GROUPED_DW
     _, res1, grads1 = _run(wl, 8, 8, False, gouts=gouts, flags=flags)
     compare(wl, res1, grads1, ora_stage, ora_res, label="mid one stream")
-    st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=8, flags=flags | B.flag_group_launches(4))
-    print(f"[case] {wl.name} mid-pipeline stage: group launches {B.gpp_stage_group_launches(st.handle)}", flush=True)
-    st.close()
-    _, res, grads = _run(wl, 8, 8, True, gouts=gouts, flags=flags | B.flag_group_launches(4), lanes=(4, 4), shared_lanes=True)
-    _same(res, grads, res1, grads1, "mid group launches")
+    for lanes in (4, 2):
+        st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=8, flags=flags | B.flag_group_launches(lanes))
+        print(f"[case] {wl.name} mid-pipeline stage: group launches {B.gpp_stage_group_launches(st.handle)}", flush=True)
+        assert B.gpp_stage_group_launches(st.handle) == (lanes, 8 // lanes)
+        st.close()
+        _, res, grads = _run(wl, 8, 8, True, gouts=gouts, flags=flags | B.flag_group_launches(lanes), lanes=(lanes, lanes), shared_lanes=True)
+        _same(res, grads, res1, grads1, f"mid group launches, {lanes} lanes")
     # stages with steps that have no group form keep launching per micro-batch, whatever the flag asks for
     wl = W.dlrm(micro_batch=32, n_micro=4, n_tables=3, num_rows=500, bottom=(64, 32, 128), top=(128, 64, 1))
     st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=4, flags=flags | B.flag_group_launches(2))
