@@ -72,14 +72,23 @@ struct SkLds {
 // round-robin over the 8 XCDs (one L2 each): the column blocks of a record are spread over all of them
 // (a wide problem's weights then stream through every L2 and memory channel), while the row blocks
 // of ONE column block, which read the same slice of W, get ids 8 apart and so meet in one L2.
+// A group launch covers the same problems for several micro-batches ("members"): their operands and results
+// sit at the same offsets of stash slots `stride` bytes apart, and a member's per-call pointers `ext_stride`
+// entries behind the previous member's.  The members take the place of further row blocks of a column block:
+// their workgroups get ids 8 apart like the row blocks of one micro-batch, so the weight tile they all read
+// is fetched into one L2 once.
+struct SkGroup {
+  int32_t members, ext_stride;
+  int64_t stride;
+};
 template <int FORM, int TI, int TJ, int NW_ = SkWaves<TI>::value>
-__device__ __forceinline__ void gemm_skinny_body(const GemmProb &p, int local, unsigned char *lds_raw, const ExtPtrs &ext) {
+__device__ __forceinline__ void gemm_skinny_body(const GemmProb &pin, int local, unsigned char *lds_raw, const ExtPtrs &ext,
+                                                 const SkGroup &group) {
   typedef SkLds<FORM, TI, TJ, NW_> L;
   constexpr int NW = L::NW, BM = L::BM, BN = L::BN, SB = L::SB, WAVE_ELEMS = L::WAVE_ELEMS;
   float *red = (float *)lds_raw;           // after the k-loop: NW/2 BM x BN fp32 buffers
-  void *Cout = result_ptr(p, ext);
 
-  const int m_blocks = (p.M + BM - 1) / BM, n_blocks = (p.N + BN - 1) / BN;
+  const int m_blocks1 = (pin.M + BM - 1) / BM, m_blocks = m_blocks1 * group.members, n_blocks = (pin.N + BN - 1) / BN;
   int cb, rb;                      // column block, row block
   {
     const int grp = local / (8 * m_blocks), r = local - grp * 8 * m_blocks;
@@ -87,6 +96,18 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmProb &p, int local, u
     cb = 8 * grp + r % cols_here;
     rb = r / cols_here;
   }
+  GemmProb p = pin;
+  if (group.members > 1) {         // this workgroup's member: everything that lives in a stash slot moves with it
+    const int member = rb / m_blocks1;
+    rb -= member * m_blocks1;
+    const int64_t off = (int64_t)member * group.stride;
+    p.A = (const char *)p.A + off;
+    if (p.C) p.C = (char *)p.C + off;
+    if (p.aux) p.aux = (char *)p.aux + off;
+    if (p.res) p.res = (const char *)p.res + off;
+    if (p.c_ext > 0) p.c_ext += member * group.ext_stride;
+  }
+  void *Cout = result_ptr(p, ext);
   const int n0 = cb * BN;
   const int m0 = rb * BM;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -337,11 +358,19 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmProb &p, int local, u
 }
 
 template <int FORM, int TI, int TJ, int NW = SkWaves<TI>::value>
-__global__ __launch_bounds__(64 * NW) void k_gemm_skinny(const GemmProb *__restrict__ probs, int n, ExtPtrs ext) {
+__global__ __launch_bounds__(64 * NW) void k_gemm_skinny(const GemmProb *__restrict__ probs, int n, ExtPtrs ext, SkGroup group) {
   __shared__ __attribute__((aligned(16))) unsigned char lds_raw[SkLds<FORM, TI, TJ, NW>::BYTES];
-  const int pi = find_prob(probs, n, blockIdx.x);
-  const GemmProb p = probs[pi];
-  gemm_skinny_body<FORM, TI, TJ, NW>(p, blockIdx.x - p.blk_begin, lds_raw, ext);
+  // every record's workgroup range is `members` times the one in its table
+  int lo = 0, hi = n - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (probs[mid].blk_begin * group.members <= (int)blockIdx.x)
+      lo = mid;
+    else
+      hi = mid - 1;
+  }
+  const GemmProb p = probs[lo];
+  gemm_skinny_body<FORM, TI, TJ, NW>(p, blockIdx.x - p.blk_begin * group.members, lds_raw, ext, group);
 }
 
 // backward of one level in one launch: records with form DX run the few-row body; records with
@@ -365,7 +394,7 @@ __global__ __launch_bounds__(512) void k_gemm_bwd_merged(const GemmProb *__restr
   const GemmProb p = probs[pi];
   const int local = blockIdx.x - p.blk_begin;
   if (p.form == FORM_DX) {
-    gemm_skinny_body<FORM_DX, TI, TJ>(p, local, lds_raw, ext);
+    gemm_skinny_body<FORM_DX, TI, TJ>(p, local, lds_raw, ext, SkGroup{1, 0, 0});
   } else if (p.split_k == BWD_DW_KSPLIT) {
     gemm_dw_ksplit_body(p, local, lds_raw, accumulate_dw);
   } else {
@@ -384,26 +413,27 @@ int gemm_bwd_merged_dw_blocks(int M, int N) {
 
 template <int FORM>
 static void launch_rows(const GemmProb *probs, int n, int blocks, int row_tiles, int col_tiles, int waves, const ExtPtrs &ext,
-                        hipStream_t s) {
+                        const SkGroup &group, hipStream_t s) {
   if (waves == 4) {   // workgroups sized to share a compute unit with those of concurrent launches
     const dim3 g4(blocks), b4(256);
-    if (row_tiles == 1 && col_tiles == 1) hipLaunchKernelGGL((k_gemm_skinny<FORM, 1, 1, 4>), g4, b4, 0, s, probs, n, ext);
-    else if (row_tiles == 1) hipLaunchKernelGGL((k_gemm_skinny<FORM, 1, 2, 4>), g4, b4, 0, s, probs, n, ext);
-    else if (col_tiles == 1) hipLaunchKernelGGL((k_gemm_skinny<FORM, 2, 1, 4>), g4, b4, 0, s, probs, n, ext);
-    else hipLaunchKernelGGL((k_gemm_skinny<FORM, 2, 2, 4>), g4, b4, 0, s, probs, n, ext);
+    if (row_tiles == 1 && col_tiles == 1) hipLaunchKernelGGL((k_gemm_skinny<FORM, 1, 1, 4>), g4, b4, 0, s, probs, n, ext, group);
+    else if (row_tiles == 1) hipLaunchKernelGGL((k_gemm_skinny<FORM, 1, 2, 4>), g4, b4, 0, s, probs, n, ext, group);
+    else if (col_tiles == 1) hipLaunchKernelGGL((k_gemm_skinny<FORM, 2, 1, 4>), g4, b4, 0, s, probs, n, ext, group);
+    else hipLaunchKernelGGL((k_gemm_skinny<FORM, 2, 2, 4>), g4, b4, 0, s, probs, n, ext, group);
     return;
   }
   const dim3 g(blocks), b(512);
-  if (row_tiles == 1 && col_tiles == 1) hipLaunchKernelGGL((k_gemm_skinny<FORM, 1, 1>), g, b, 0, s, probs, n, ext);
-  else if (row_tiles == 1) hipLaunchKernelGGL((k_gemm_skinny<FORM, 1, 2>), g, b, 0, s, probs, n, ext);
-  else if (col_tiles == 1) hipLaunchKernelGGL((k_gemm_skinny<FORM, 2, 1>), g, b, 0, s, probs, n, ext);
-  else hipLaunchKernelGGL((k_gemm_skinny<FORM, 2, 2>), g, b, 0, s, probs, n, ext);
+  if (row_tiles == 1 && col_tiles == 1) hipLaunchKernelGGL((k_gemm_skinny<FORM, 1, 1>), g, b, 0, s, probs, n, ext, group);
+  else if (row_tiles == 1) hipLaunchKernelGGL((k_gemm_skinny<FORM, 1, 2>), g, b, 0, s, probs, n, ext, group);
+  else if (col_tiles == 1) hipLaunchKernelGGL((k_gemm_skinny<FORM, 2, 1>), g, b, 0, s, probs, n, ext, group);
+  else hipLaunchKernelGGL((k_gemm_skinny<FORM, 2, 2>), g, b, 0, s, probs, n, ext, group);
 }
 void launch_gemm_skinny(const GemmProb *probs, int n, int total_blocks, int form, int row_tiles, int col_tiles, int waves,
-                        const ExtPtrs &ext, hipStream_t s) {
-  if (total_blocks <= 0) return;
-  if (form == FORM_FWD) launch_rows<FORM_FWD>(probs, n, total_blocks, row_tiles, col_tiles, waves, ext, s);
-  else launch_rows<FORM_DX>(probs, n, total_blocks, row_tiles, col_tiles, waves, ext, s);
+                        const ExtPtrs &ext, hipStream_t s, int members, int64_t member_stride_bytes, int member_ext_stride) {
+  if (total_blocks <= 0 || members <= 0) return;
+  const SkGroup group{members, member_ext_stride, member_stride_bytes};
+  if (form == FORM_FWD) launch_rows<FORM_FWD>(probs, n, total_blocks * members, row_tiles, col_tiles, waves, ext, group, s);
+  else launch_rows<FORM_DX>(probs, n, total_blocks * members, row_tiles, col_tiles, waves, ext, group, s);
 }
 void launch_gemm_bwd_merged(const GemmProb *probs, int n, int total_blocks, int row_tiles, int col_tiles, int accumulate_dw,
                             const ExtPtrs &ext, hipStream_t s) {

@@ -220,8 +220,11 @@ int gemm_big_tiles_for(int tile_rows, int M, int N, int *tiles_n);
 void launch_gemm_dw_ksplit(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, hipStream_t s);
 int gemm_dw_ksplit_blocks(int M, int N);
 // few-row (micro-batch <= 256 rows) forward / backward-data kernel
+// members > 1: a group launch (the records are member 0's; member i's slot memory lies i * member_stride_bytes
+// further, its per-call pointers i * member_ext_stride entries further); total_blocks counts one member
 void launch_gemm_skinny(const GemmProb *probs, int n, int total_blocks, int form, int row_tiles, int col_tiles, int waves,
-                        const ExtPtrs &ext, hipStream_t s);
+                        const ExtPtrs &ext, hipStream_t s, int members = 1, int64_t member_stride_bytes = 0,
+                        int member_ext_stride = 0);
 // backward of a level with few rows in one launch: records of form DX (few-row body) first, then
 // records of form DW (tile body, two tiles per workgroup)
 void launch_gemm_bwd_merged(const GemmProb *probs, int n, int total_blocks, int row_tiles, int col_tiles,

@@ -520,7 +520,17 @@ static gpp_status_t run_steps_group(gpp_stage *st, const std::vector<Step> &step
     for (int rep = 0; rep < reps; ++rep)
     switch (sp.kern) {
       case K_ELT: launch_elt((const EltProb *)tab, m * sp.n, m * sp.blocks, ext, s); break;
-      case K_GEMM_SKINNY: launch_gemm_skinny((const GemmProb *)tab, m * sp.n, m * sp.blocks, sp.a1, sp.a2, sp.a0, sp.a3, ext, s); break;
+      case K_GEMM_SKINNY: {
+        // the records of the lane's first slot; the other members are that many further row blocks, their slot
+        // memory L slots further each (the weight tile of a column block then serves all members from one L2)
+        const void *tab0 = st->ws + pl.off_tables + (int64_t)lane * pl.table_bytes + sp.table_off;
+        const int ext_total = sp.ext_kind == EXT_NONE ? 0
+                              : ((sp.ext_kind == EXT_INPUTS || sp.ext_kind == EXT_GRAD_INPUTS) ? (int)pl.input_ops.size()
+                                                                                               : (int)pl.output_ops.size());
+        launch_gemm_skinny((const GemmProb *)tab0, sp.n, sp.blocks, sp.a1, sp.a2, sp.a0, sp.a3, ext, s, m,
+                           (int64_t)pl.group_lanes * pl.slot_bytes, ext_total);
+        break;
+      }
       case K_HEAD_LOSS: {
         HeadOuts ho;
         memset(&ho, 0, sizeof(ho));
