@@ -116,7 +116,7 @@ MEASURED_TRAFFIC = {
     # bytes per launch, averaged over the launches of the kernel family within a step
     ("candle_uno", "gemm_bwd_merged_dx_dw"): 50.5e6,
     ("candle_uno", "gemm_skinny_fwd"): 35.1e6,     # a launch covers four micro-batches (group launches)
-    ("candle_uno", "gemm_skinny_dx"): 66.4e6,
+    ("candle_uno", "gemm_skinny_dx"): 42.7e6,
     ("candle_uno", "gemm_big_dw"): 122.1e6,      # the grouped launch: eight slots, every Linear of the stage
     ("hetero", "gemm_skinny_fwd"): 48.7e6,
     ("hetero", "gemm_skinny_dx"): 47.2e6,
