@@ -1251,7 +1251,12 @@ void Emitter::forward() {
         blocks += loss_fwd_blocks(l);
         elems += (int64_t)l.rows * l.cols;
       }
-      if (losses.size() == pl.loss_ops.size() && elems <= loss_small_limit()) {
+      // the one-workgroup kernel: few elements in few rows (rows are padded to 64 elements, so a tall one-column
+      // prediction is a cache line per element: 2048 x 1 took 18 us there, 7 + 6 us with the row-parallel kernel
+      // and the sum)
+      int max_rows = 0;
+      for (auto &l : losses) max_rows = std::max(max_rows, l.rows);
+      if (losses.size() == pl.loss_ops.size() && elems <= loss_small_limit() && max_rows <= 512) {
         add_step(K_LOSS_FWD_SMALL, push_table(losses), (int)losses.size(), 1);   // value and sum in one launch
         loss_summed = true;
       } else {
