@@ -143,9 +143,10 @@ typedef struct {
                                  bits 8-11: L > 0 asks for GROUP LAUNCHES in gpp_stage_run_schedule_lanes with L
                                  streams per direction (needs bit 2, in_flight_slots a multiple of L and at
                                  least 2 L): where a run of forward (backward) tasks puts several micro-batches
-                                 on one stream, each step of the pass is ONE launch over all of them -- the
-                                 launch tables of their slots one after the other (a second copy of the
-                                 tables, per lane) -- instead of one launch per micro-batch.  Same kernels,
+                                 on one stream, each step of the pass is ONE launch over all of them (the
+                                 launch records of their slots one after the other, from a second copy of the
+                                 tables per lane; for the few-row GEMMs the first slot's records plus the slot
+                                 stride) instead of one launch per micro-batch.  Same kernels,
                                  same tiles per micro-batch, so the results do not change; the chain of
                                  dependent launches on a stream gets shorter.  Taken where every step has a
                                  group form (element-wise copies, few-row GEMMs, the fused head) and a run

@@ -214,7 +214,9 @@ gpp_status_t gpp_stage_create(const gpp_stage_desc_t *desc, void *workspace, siz
           for (const Step &sp : *list) {
             const size_t rec = group_record_bytes(sp.kern);
             uint8_t *dst = gb.data() + (size_t)G * sp.table_off + (size_t)i * sp.n * rec;
-            if (sp.n <= 0 || rec == 0) continue;
+            // (few-row GEMM steps need no copy: their group launch reads the first slot's records and reaches the
+            // other members by the slot stride, see run_steps_group)
+            if (sp.n <= 0 || rec == 0 || sp.kern == K_GEMM_SKINNY) continue;
             memcpy(dst, src.data() + sp.table_off, (size_t)sp.n * rec);
             const int ext_total = sp.ext_kind == EXT_NONE ? 0
                                   : ((sp.ext_kind == EXT_INPUTS || sp.ext_kind == EXT_GRAD_INPUTS) ? (int)pl.input_ops.size()
@@ -225,10 +227,6 @@ gpp_status_t gpp_stage_create(const gpp_stage_desc_t *desc, void *workspace, siz
                 e->blk_begin += i * sp.blocks;
                 if (e->ext_src >= 0) e->ext_src += i * ext_total;
                 if (e->ext_dst >= 0) e->ext_dst += i * ext_total;
-              } else if (sp.kern == K_GEMM_SKINNY) {
-                GemmProb *g = (GemmProb *)dst + r;
-                g->blk_begin += i * sp.blocks;
-                if (g->c_ext > 0) g->c_ext += i * ext_total;
               }
             }
           }
