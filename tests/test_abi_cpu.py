@@ -116,3 +116,23 @@ def test_create_rejects_missing_workspace_before_touching_the_gpu(lib):
     with pytest.raises(B.GppError) as e:
         B.gpp_stage_create(d2, 256, 1 << 30)
     assert e.value.status == B.GPP_ERR_INVALID_ARG
+
+
+def test_stage_flags_in_the_workspace_size(lib):
+    # per-slot gradient buffers (flag bit 2) and the second copy of the launch tables for group launches (bits 8-11)
+    # both show in the workspace; a lane count the slots cannot be split into, or group launches without per-slot
+    # gradient buffers, are ignored
+    wl = W.candle_uno(micro_batch=16, n_micro=1, widths=(32, 40, 8, 24), hidden=64)
+
+    def size(slots, flags):
+        d, keep = B.build_desc(wl.ops, wl.micro_batch, slots, flags=flags)
+        return B.gpp_stage_workspace_bytes(d)
+    plain, grouped = size(8, 0), size(8, B.FLAG_GROUPED_DW)
+    assert grouped > plain
+    with_tables = size(8, B.FLAG_GROUPED_DW | B.flag_group_launches(2))
+    assert with_tables > grouped
+    assert size(8, B.FLAG_GROUPED_DW | B.flag_group_launches(4)) == with_tables      # the same number of table copies
+    assert size(8, B.FLAG_GROUPED_DW | B.flag_group_launches(3)) == grouped          # 8 slots do not split into 3 lanes
+    assert size(8, B.FLAG_GROUPED_DW | B.flag_group_launches(8)) == grouped          # one micro-batch per lane: nothing to group
+    assert size(8, B.flag_group_launches(2)) == plain                                # needs per-slot gradient buffers
+    assert size(8, B.FLAG_GROUPED_DW | B.FLAG_SHARED_GPU) == grouped                 # workgroup sizes only
