@@ -171,6 +171,7 @@ struct HeadProb {
   void *y;              // [rows] prediction out, stride ld_y
   void *dy;             // [rows] loss gradient out, stride ld_dy
   void *dx;             // [rows x K] bf16: gradient of x (times the derivative of its activation) out
+  float *partials;      // tall heads (more rows than one workgroup sums): one partial loss per 8 rows, summed by the loss-sum launch
   int64_t ld_x, ld_t, ld_mask, ld_y, ld_dy, ld_dx;
   int32_t rows, K, kind;      // kind = gpp_op_kind_t value of the loss
   int32_t y_dtype, dy_dtype, act;
@@ -287,7 +288,9 @@ int loss_fwd_blocks(const LossProb &p);
 void launch_loss_fwd_small(const LossProb *probs, int n, float *out, hipStream_t s);
 int loss_small_limit();
 bool head_loss_supported(int64_t rows, int64_t K);
-void launch_head_loss(const HeadProb *prob, int members, int rows, const HeadOuts &outs, hipStream_t s);
+bool head_loss_is_tall(int64_t rows, int64_t K);
+int head_loss_parts(int64_t rows);
+void launch_head_loss(const HeadProb *prob, int members, int rows, int K, const HeadOuts &outs, hipStream_t s);
 void launch_loss_bwd(const LossProb *probs, int n, int total_blocks, hipStream_t s);
 int loss_bwd_blocks(const LossProb &p);
 

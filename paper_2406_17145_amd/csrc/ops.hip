@@ -760,7 +760,14 @@ void launch_loss_fwd_small(const LossProb *probs, int n, float *out, hipStream_t
 // compute unit.)  w sits in LDS as floats.  Every value passes through the storage type it has in the
 // unfused path (y and dy are rounded before they are used), and all sums have a fixed order.
 constexpr int HEAD_MAX_K = 8192, HEAD_MAX_ROWS = 256, HEAD_ROWS_IN_FLIGHT = 4, HEAD_WAVES = 8;
-bool head_loss_supported(int64_t rows, int64_t K) { return rows >= 1 && rows <= HEAD_MAX_ROWS && K >= 8 && K <= HEAD_MAX_K && (K & 7) == 0; }
+// Up to HEAD_MAX_ROWS rows workgroup 0 forms the loss sum itself; taller or larger heads (up to HEAD_TALL_ROWS) have no
+// workgroup 0: every workgroup of eight rows also stores its rows' prediction and loss gradient and ONE partial
+// loss, and the stage's loss-sum launch adds the partials in index order.
+constexpr int HEAD_TALL_ROWS = 16384;
+bool head_loss_supported(int64_t rows, int64_t K) { return rows >= 1 && rows <= HEAD_TALL_ROWS && K >= 8 && K <= HEAD_MAX_K && (K & 7) == 0; }
+// (also when workgroup 0 alone would have to form too many dot products: 256 x 4096 took 65 us there)
+bool head_loss_is_tall(int64_t rows, int64_t K) { return rows > HEAD_MAX_ROWS || rows * K > 128 * 1024; }
+int head_loss_parts(int64_t rows) { return (int)((rows + HEAD_WAVES - 1) / HEAD_WAVES); }
 // prediction and loss gradient of one row from its dot product, as the backward pass will read them
 __device__ __forceinline__ void head_row(const HeadProb &p, float dot, float bias, float t, float &y, float &g) {
   y = wave_sum(dot) + bias;
@@ -793,7 +800,8 @@ __global__ __launch_bounds__(64 * HEAD_WAVES) void k_head_loss(const HeadProb *_
     }
   }
   const float bias = p.bias ? p.bias[0] : 0.0f;
-  if (blockIdx.x == 0) {
+  const bool tall = p.partials != nullptr;
+  if (!tall && blockIdx.x == 0) {
     constexpr int R = HEAD_ROWS_IN_FLIGHT;
     float tv[R];
     const int first = wave * R;
@@ -843,7 +851,7 @@ __global__ __launch_bounds__(64 * HEAD_WAVES) void k_head_loss(const HeadProb *_
     return;
   }
   // ---- dx of one row per wave
-  const int row = (blockIdx.x - 1) * HEAD_WAVES + wave;
+  const int row = ((int)blockIdx.x - (tall ? 0 : 1)) * HEAD_WAVES + wave;
   const int rc = min(row, p.rows - 1);
   const float t = ((const float *)p.target)[(int64_t)rc * p.ld_t];
   const bool masked = p.mask != nullptr, own_mask = masked && p.mask != p.x;
@@ -864,6 +872,26 @@ __global__ __launch_bounds__(64 * HEAD_WAVES) void k_head_loss(const HeadProb *_
     dot += head_dot8(*(const ln_u32x4 *)((const uint16_t *)p.x + (int64_t)rc * p.ld_x + 8 * c), w_f + 8 * c);
   float y, g;
   head_row(p, dot, bias, t, y, g);
+  if (tall) {      // this workgroup also owns its rows' prediction, loss gradient and loss terms
+    float term = 0.0f;
+    if (row < p.rows && lane == 0) {
+      if (p.kind == 9) {
+        const float d = y - t;
+        term = d * d;
+      } else {
+        term = softplus_f(y) - t * y;
+      }
+      store_from_f32(p.y, p.y_dtype, (int64_t)row * p.ld_y, y);
+      store_from_f32(p.dy, p.dy_dtype, (int64_t)row * p.ld_dy, g);
+    }
+    if (lane == 0) red[wave] = term;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      float total = 0.0f;
+      for (int k = 0; k < HEAD_WAVES; ++k) total += red[k];
+      p.partials[blockIdx.x] = total * p.scale;
+    }
+  }
   if (row >= p.rows || !p.dx) return;
   auto put = [&](int c, const ln_u32x4 &m) {
     ln_u32x4 o;
@@ -884,9 +912,10 @@ __global__ __launch_bounds__(64 * HEAD_WAVES) void k_head_loss(const HeadProb *_
   for (int c = lane + 64 * KEEP; c < chunks; c += 64)
     put(c, masked ? *(const ln_u32x4 *)((const uint16_t *)p.mask + (int64_t)row * p.ld_mask + 8 * c) : ln_u32x4{0u, 0u, 0u, 0u});
 }
-void launch_head_loss(const HeadProb *prob, int members, int rows, const HeadOuts &outs, hipStream_t s) {
+void launch_head_loss(const HeadProb *prob, int members, int rows, int K, const HeadOuts &outs, hipStream_t s) {
   if (members <= 0 || members > HEAD_GROUP_MAX || rows <= 0) return;
-  hipLaunchKernelGGL(k_head_loss, dim3(1 + (rows + HEAD_WAVES - 1) / HEAD_WAVES, members), dim3(64 * HEAD_WAVES), 0, s, prob, outs);
+  const int blocks = (head_loss_is_tall(rows, K) ? 0 : 1) + head_loss_parts(rows);
+  hipLaunchKernelGGL(k_head_loss, dim3(blocks, members), dim3(64 * HEAD_WAVES), 0, s, prob, outs);
 }
 
 int loss_bwd_blocks(const LossProb &p) { return (p.rows + 3) / 4; }

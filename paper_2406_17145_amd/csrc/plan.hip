@@ -1133,6 +1133,8 @@ void Emitter::forward() {
             h.ld_dx = x.gout.ld;
             h.rows = (int32_t)y.rows;
             h.K = (int32_t)x.feat;
+            // tall heads leave the sum of their per-workgroup partial losses to the loss-sum launch
+            if (head_loss_is_tall(y.rows, x.feat)) h.partials = (float *)ptr(pl.loss_scalars) + nd.loss_index;
             h.kind = d.kind;
             h.scale = (float)d.loss_scale;
             heads.push_back(h);
@@ -1241,7 +1243,7 @@ void Emitter::forward() {
       Step &sh = add_step(K_HEAD_LOSS, push_table(heads), 1, 1);
       sh.a0 = heads[0].rows;
       sh.a1 = heads[0].K;
-      loss_summed = true;
+      loss_summed = heads[0].partials == nullptr;
     }
     if (!losses.empty()) {
       int blocks = 0;

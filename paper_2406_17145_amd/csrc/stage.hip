@@ -118,8 +118,8 @@ static const char *const kTagNames[GPP_PROFILE_TAGS] = {
 static size_t group_record_bytes(int kern) {
   return kern == K_ELT ? sizeof(EltProb) : kern == K_GEMM_SKINNY ? sizeof(GemmProb) : kern == K_HEAD_LOSS ? sizeof(HeadProb) : 0;
 }
-// (the loss sum of a stage without losses has no records: it only clears the caller's loss value)
-static bool group_form(const Step &sp) { return group_record_bytes(sp.kern) != 0 || (sp.kern == K_LOSS_SUM && sp.n == 0); }
+// (the loss sum has no records: one small launch per member adds that member's partial losses)
+static bool group_form(const Step &sp) { return group_record_bytes(sp.kern) != 0 || sp.kern == K_LOSS_SUM; }
 static bool group_supported(const Plan &pl) {
   if (pl.group_lanes <= 0 || pl.fwd_shared || pl.bwd_shared || pl.lanes) return false;
   const int G = pl.slots / pl.group_lanes;
@@ -406,7 +406,7 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
         HeadOuts ho;
         memset(&ho, 0, sizeof(ho));
         ho.p[0] = sink;
-        launch_head_loss((const HeadProb *)tab, 1, sp.a0, ho, s);
+        launch_head_loss((const HeadProb *)tab, 1, sp.a0, sp.a1, ho, s);
         break;
       }
       case K_LOSS_FWD_SMALL: {
@@ -537,12 +537,16 @@ static gpp_status_t run_steps_group(gpp_stage *st, const std::vector<Step> &step
           float *lo = io[members[i]].loss_out;
           ho.p[i] = lo ? lo : (float *)(st->ws + pl.off_slots + (int64_t)slot * pl.slot_bytes + pl.loss_scalars.off);
         }
-        launch_head_loss((const HeadProb *)tab, m, sp.a0, ho, s);
+        launch_head_loss((const HeadProb *)tab, m, sp.a0, sp.a1, ho, s);
         break;
       }
-      case K_LOSS_SUM:       // no loss operators: every member that asks for a loss value gets zero
+      case K_LOSS_SUM:       // per member: its partial losses (none: zero) to where the caller wants the loss value
         for (int i = 0; i < m; ++i)
-          if (io[members[i]].loss_out) launch_loss_sum(nullptr, 0, io[members[i]].loss_out, s);
+          if (io[members[i]].loss_out) {
+            const int slot = lane + pl.group_lanes * i;
+            const float *ls = (const float *)(st->ws + pl.off_slots + (int64_t)slot * pl.slot_bytes + pl.loss_scalars.off);
+            launch_loss_sum(ls, sp.n, io[members[i]].loss_out, s);
+          }
         break;
       default: return fail(GPP_ERR_UNSUPPORTED, "internal: step without a group form");
     }

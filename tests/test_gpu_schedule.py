@@ -425,9 +425,11 @@ def test_one_column_head_and_its_loss_in_one_launch():
     # Linear(K -> 1) + element-wise loss: with grouped weight gradients the loss's launch also computes the
     # Linear, the loss gradient and the gradient of the Linear's input.  Rows 1 ... 256 (one workgroup, four rows
     # of a wave in flight, ragged groups), every activation in front of the head, MSE and BCE, and sizes the
-    # fusion does not take (more than 256 rows; a width that is not a multiple of 8)
+    # fusion does not take (a width that is not a multiple of 8); above 256 rows the head's workgroups leave partial
+    # losses to the loss-sum launch
     for mb, hidden, act, fused in [(1, 160, "relu", True), (37, 160, "gelu", True), (64, 1000, "relu", True), (200, 72, "none", True),
-                                   (8, 1536, "gelu", True), (40, 1536, "relu", True), (256, 160, "gelu", True), (300, 160, "relu", False), (16, 100, "relu", False)]:
+                                   (8, 1536, "gelu", True), (40, 1536, "relu", True), (256, 160, "gelu", True), (300, 160, "relu", True), (701, 72, "gelu", True),
+                                   (16, 100, "relu", False)]:
         wl = W.candle_uno(micro_batch=mb, n_micro=3, widths=(70, 131, 9, 33), hidden=hidden, act=act)
         st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=3, flags=B.FLAG_GROUPED_DW)
         launches = st.num_launches(False) + st.num_launches(True)
@@ -446,6 +448,11 @@ def test_one_column_head_and_its_loss_in_one_launch():
     print(f"[case] {wl.name} b=128 BCE head", flush=True)
     _, res, grads = _run(wl, 3, 3, True, reps=2, flags=B.FLAG_GROUPED_DW)
     compare(wl, res, grads, ora_stage, ora_res, label="dlrm BCE head")
+    wl = W.dlrm(micro_batch=600, n_micro=2, n_tables=3, num_rows=2000, bottom=(64, 32, 128), top=(128, 64, 1))
+    ora_stage, ora_res = run_oracle(wl)
+    print(f"[case] {wl.name} b=600 tall BCE head", flush=True)
+    _, res, grads = _run(wl, 2, 2, False, reps=2, flags=B.FLAG_GROUPED_DW)
+    compare(wl, res, grads, ora_stage, ora_res, label="dlrm tall BCE head")
 
 
 def test_forward_without_a_loss_pointer_still_seeds_the_backward_pass():
@@ -490,13 +497,14 @@ def test_large_elementwise_loss_writes_its_gradient_in_the_forward_pass():
 # ---- group launches: the micro-batches a run of tasks puts on one stream share one launch per step ------
 
 def test_group_launches_give_the_one_stream_results_bit_for_bit():
-    for mb, hidden, act in [(48, 160, "gelu"), (64, 1000, "relu"), (300, 160, "relu")]:      # (the last one has steps without a group form)
-        for n_micro, slots, lanes in [(8, 8, 4), (7, 8, 4), (8, 8, 2), (12, 8, 4), (6, 6, 3), (5, 4, 2)]:
+    # (the last two have a head whose partial losses go through the loss-sum launch; 300 rows are five row blocks per member)
+    for mb, hidden, act in [(48, 160, "gelu"), (64, 1000, "relu"), (200, 1000, "relu"), (300, 160, "relu")]:
+        for n_micro, slots, lanes in ([(8, 8, 4), (7, 8, 4), (8, 8, 2), (12, 8, 4), (6, 6, 3), (5, 4, 2)] if mb != 200 else [(8, 8, 2), (7, 8, 4)]):
             wl = W.candle_uno(micro_batch=mb, n_micro=n_micro, widths=(70, 131, 9, 33), hidden=hidden, act=act)
             flags = B.FLAG_GROUPED_DW | B.FLAG_SHARED_GPU
             _, res1, grads1 = _run(wl, slots, slots, False, reps=2, flags=flags)
             st = B.Stage(wl.ops, wl.micro_batch, wl.params, slots=slots, flags=flags | B.flag_group_launches(lanes))
-            assert B.gpp_stage_group_launches(st.handle) == ((lanes, slots // lanes) if mb <= 256 else (0, 0))
+            assert B.gpp_stage_group_launches(st.handle) == (lanes, slots // lanes)
             st.close()
             for shared in (True, False):
                 print(f"[case] {wl.name} b={mb} hidden={hidden} group launches: {n_micro} micro-batches, {slots} slots, {lanes} lanes, "
