@@ -547,3 +547,14 @@ def test_group_launches_on_a_mid_pipeline_stage_and_where_they_do_not_apply():
     ora_stage, ora_res = run_oracle(wl)
     _, res, grads = _run(wl, 4, 4, True, flags=flags | B.flag_group_launches(2))
     compare(wl, res, grads, ora_stage, ora_res, label="dlrm with the group flag")
+
+
+@pytest.mark.parametrize("make", [W.hetero, W.dlrm, W.mmt], ids=["hetero", "dlrm", "mmt"])
+def test_full_size_single_micro_batch_workloads_as_the_benchmark_runs_them(make):
+    # one micro-batch per step, serial order, the weight gradients of every layer in one launch after the backward
+    # pass (stage flag bit 2) -- the configuration bench.py times for these workloads -- against the oracle in full
+    wl = make()
+    print(f"[case] {wl.name} full size, grouped weight gradients, serial", flush=True)
+    ora_stage, ora_res = run_oracle(wl)
+    _, res, grads = _run(wl, 1, 1, False, reps=2, flags=B.FLAG_GROUPED_DW)
+    compare(wl, res, grads, ora_stage, ora_res, label=f"{wl.name} full size, grouped")
