@@ -223,8 +223,8 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmProb &pin, int local,
 
   // NS register sets rotate: while one step is multiplied, the next NS-1 are on their way from memory
   // (bounded by the register file: 256 VGPRs per lane at 8 waves)
-  // (four-wave workgroups share a compute unit with others: the 64 x 32 and 32 x 64 tiles keep two sets, which
-  // leaves room for a third workgroup per SIMD; three sets measured 2 % slower in the step, four 30 %)
+  // (four-wave workgroups share a compute unit with others: the 64 x 32 and 32 x 64 tiles keep two sets, 188
+  // registers per lane; three sets measured 2 % slower in the step, four sets 30 %)
   constexpr int NS = NW == 8 ? (TI + TJ <= 3 ? 3 : 2) : (TI + TJ <= 2 ? 4 : (TI + TJ == 3 ? 2 : 3));
   SkStep<TI, TJ> f[NS];
 #pragma unroll
