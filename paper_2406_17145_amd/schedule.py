@@ -32,9 +32,8 @@ class OverlapSchedule:
     """Forward calls on one stream, backward calls (and the gradient reset) on another; micro-batch k
     uses stash slot k % slots, and fw_k waits for bw_{k - slots} (the slot's previous micro-batch).
     The stage must have at least two slots.  With as many slots as micro-batches no forward call ever
-    waits for a backward call; that is the form to capture into a HIP graph (GraphedMinibatch): on
-    this ROCm release the capture of a forward-stream wait on a backward-stream event ends in a crash
-    of the runtime when the capture is closed (host side, at three micro-batches or more)."""
+    waits for a backward call; that is the only form GraphedMinibatch accepts for capture into a HIP
+    graph (it refuses fewer slots than micro-batches and says why)."""
 
     def __init__(self, stage):
         torch = stage.torch
@@ -204,6 +203,7 @@ class StagePipeline:
         """io[s][j] = (inputs, outputs, loss, grad_outputs, grad_inputs): lists of device tensors (None entries
         where an edge carries the tensor), a loss tensor or None.  Kept alive until the next call."""
         torch = self.stages[0].torch
+        self.check_not_capturing_slot_reuse(io, torch.cuda.is_current_stream_capturing())
         main = torch.cuda.current_stream(self.stages[0].dev)
         for s in set(self.s_f + self.s_b):
             s.wait_stream(main)
@@ -216,6 +216,13 @@ class StagePipeline:
                                               [s.cuda_stream for s in self.s_b]), io)
         for s in set(self.s_f + self.s_b):
             main.wait_stream(s)
+
+    def check_not_capturing_slot_reuse(self, io, capturing):
+        """A pipeline step under stream capture is refused when a stage would reuse a stash slot inside the
+        step: the slot-reuse wait (a forward stream waiting for a backward stream's event) is the form whose
+        capture has crashed the runtime (see GraphedMinibatch)."""
+        if capturing and any(st.slots < len(rows) for st, rows in zip(self.stages, io)):
+            raise ValueError("capture refused: a stage of the pipeline has fewer stash slots than micro-batches")
 
     def stash_bytes(self):
         """Per stage: bytes its in-flight micro-batches pin (slots it uses x bytes of a slot)."""
@@ -240,9 +247,26 @@ class GraphedMinibatch:
     keeps the stage's host-side state (overwrite-on-first-backward, slots) consistent with the
     recorded launches.  Capture after at least one eager mini-batch (the first one may clear whole
     embedding-gradient tables, later ones only the touched rows).
+
+    Refused (ValueError, before anything touches the GPU): a schedule on more than one stream whose
+    stage has fewer stash slots than the mini-batch has micro-batches.  Such a schedule makes fw_k
+    wait for the event of bw_{k - slots} (the slot's previous micro-batch); the capture of that
+    forward-stream wait on a backward-stream event has ended in a host-side segmentation fault
+    inside the runtime's end-of-capture call (three micro-batches on two slots), and its cause is
+    not known.  With a slot per micro-batch no such wait is recorded.
     """
 
+    @staticmethod
+    def check_capturable(schedule, n_micro):
+        """Raises ValueError for the schedule / slot combinations described above."""
+        one_stream = isinstance(schedule, SerialSchedule) or (isinstance(schedule, TaskSchedule) and not schedule.two)
+        if not one_stream and schedule.st.slots < n_micro:
+            raise ValueError(f"capture refused: {n_micro} micro-batches on {schedule.st.slots} stash slots would record a "
+                             "forward-stream wait on a backward-stream event (slot reuse); give the stage a slot per "
+                             "micro-batch or run the schedule eagerly")
+
     def __init__(self, schedule, batches, outputs=None, grad_outputs=None, grad_inputs=None, losses=None):
+        self.check_capturable(schedule, len(batches))
         torch = schedule.st.torch
         self.schedule = schedule
         self.keep = (batches, outputs, grad_outputs, grad_inputs, losses)

@@ -7,29 +7,17 @@ Error measure, per tensor: "relative error" is the l2-relative error
 relative error is ill-defined at the zeros that ReLU and sparse table gradients
 produce, hence the norm-wise form.  A second, max-norm guard
 max|gpu-ref| / max|ref| catches localised corruption (a wrong tile, a missed
-tail): it uses the same tolerance in fp32 mode and 5x the tolerance in bf16
-mode, because there a single ReLU mask decision that falls on the other side of
-zero (fp32 vs fp64 accumulation, amplified at a bf16 rounding boundary of a
-stored activation) legitimately moves one sample's whole gradient row.
-
-Input gradients of bf16 graphs with ReLU layers are the one place where that
-effect is not small: the masks of every layer between an input and the loss
-multiply into its gradient, and a handful of opposite decisions per micro-batch
-(each worth about 0.5% of a [64, 1000]-wide layer) already add up to 1-3% in
-the l2 norm.  Two CPU runs of the oracle that differ only in the accumulation
-precision of the matrix products (float32 vs float64) show the same spread
-(tests/test_oracle_pins.py::test_relu_mask_noise_floor), so for those tensors
-the bar is 5e-2; every other tensor of every graph stays at the stated 2e-2.
-Their max-norm guard is 5x their own bar (0.25): one opposite mask decision
-moves one sample's whole input-gradient row, which in a narrow input (a few
-tens of columns, a few hundred rows) is one element at 10-15% of the tensor's
-largest; the guard still catches what it is for, errors of the order of the
-values themselves over a tile or a tail.
+tail).  The bars and the one exception (input gradients of bf16 graphs with ReLU
+layers, whose bar is derived from a CPU measurement on the oracle) are stated in
+tests/parity_bars.py.  Every comparison is also recorded (worst error per
+workload and tensor class); tests/conftest.py writes the record out after a GPU
+run.
 """
 import numpy as np
 
 from oracle import gpp_oracle as O
 from paper_2406_17145_amd import binding as B
+from tests import parity_bars as PB
 
 
 def rel_errors(got, ref):
@@ -83,28 +71,77 @@ def run_oracle(wl, gouts=None):
     return stage, res
 
 
-def compare(wl, gpu_res, gpu_grads, ora_stage, ora_res, tol=None, label=""):
-    tol = wl.tol if tol is None else tol
-    tol_max = tol if tol <= 1e-3 else 5 * tol
-    has_relu = any(op.get("act") == "relu" for op in wl.ops)
-    tol_gin = 5e-2 if (tol > 1e-3 and has_relu) else tol
-    worst = {}
+_SPREAD_CACHE = {}
+RECORD = {}          # label -> tensor class -> [worst l2, worst max-norm, l2 bar]; conftest writes it out
 
-    def chk(name, got, ref, t2=None):
-        t2 = tol if t2 is None else t2
-        e2, em = rel_errors(got, ref)
+
+def _relu_spread(wl):
+    key = PB.workload_key(wl)
+    if key in PB.RELU_SPREAD_PINNED:
+        return PB.RELU_SPREAD_PINNED[key]
+    key = key + (id(wl.ops),)
+    if key not in _SPREAD_CACHE:
+        from tests.relu_noise import measure
+        _SPREAD_CACHE[key] = measure(wl)
+    return _SPREAD_CACHE[key]
+
+
+def _tensor_class(name):
+    if ".out" in name:
+        return "output"
+    if ".gin" in name:
+        return "input gradient"
+    return "d" + name.split(".d", 1)[1]
+
+
+def compare(wl, gpu_res, gpu_grads, ora_stage, ora_res, tol=None, label=""):
+    """Every tensor against the oracle.  Bars: tests/parity_bars.py (the stated ones, except the
+    input gradients of bf16 graphs with ReLU, whose bars come from the spread the oracle itself
+    shows under re-ordered float32 sums)."""
+    tol = wl.tol if tol is None else tol
+    mode = "f32" if tol <= 1e-3 else "bf16"
+    tol_max = PB.STATED_MAX[mode] if tol == PB.STATED_L2[mode] else 5 * tol
+    has_relu = any(op.get("act") == "relu" for op in wl.ops)
+    worst = {}
+    n_par = sum(int(np.asarray(v).size) for p in wl.params.values() for v in p.values())
+    rec = RECORD.setdefault(f"{wl.name} b={wl.micro_batch} x{wl.n_micro} {mode} ({n_par} parameters)", {})
+
+    def note(name, e2, em, bar):
         worst[name] = (e2, em)
-        tm = max(tol_max, 2 * t2) if t2 == tol else 5 * t2
-        assert e2 <= t2 and em <= tm, f"{label} {name}: l2-rel {e2:.3e} (tol {t2}) max-rel {em:.3e} (tol {tm})"
+        r = rec.setdefault(_tensor_class(name), [0.0, 0.0, bar])
+        r[0], r[1], r[2] = max(r[0], e2), max(r[1], em), max(r[2], bar)
+
+    def chk(name, got, ref):
+        e2, em = rel_errors(got, ref)
+        note(name, e2, em, tol)
+        assert e2 <= tol and em <= tol_max, f"{label} {name}: l2-rel {e2:.3e} (bar {tol}) max-rel {em:.3e} (bar {tol_max})"
+
+    def chk_relu_gin(name, got, ref):
+        from tests.relu_noise import ROW_BAR, row_errors
+        b2, bm, brows = PB.relu_gin_bars(_relu_spread(wl), ref.shape[0])
+        e2, em = rel_errors(got, ref)
+        note(name, e2, em, b2)
+        assert e2 <= b2 and em <= bm, f"{label} {name}: l2-rel {e2:.3e} (bar {b2:.3e}) max-rel {em:.3e} (bar {bm:.3e})"
+        if ref.size // ref.shape[0] >= PB.ROW_CHECK_MIN_WIDTH:
+            over = float((row_errors(got, ref) > ROW_BAR).mean())
+            r = rec.setdefault("input gradient: share of rows over %g" % ROW_BAR, [0.0, 0.0, brows])
+            r[0], r[2] = max(r[0], over), max(r[2], brows)
+            assert over <= brows, f"{label} {name}: {over:.3f} of the rows over {ROW_BAR} (allowed {brows:.3f})"
 
     for j, (g, (st, gin)) in enumerate(zip(gpu_res, ora_res)):
         if ora_stage.ops and any(op["kind"].startswith("loss") for op in ora_stage.ops):
-            assert abs(g["loss"] - st.loss) <= tol * max(abs(st.loss), 1e-30), (label, "loss", j, g["loss"], st.loss)
+            el = abs(g["loss"] - st.loss) / max(abs(st.loss), 1e-30)
+            r = rec.setdefault("loss", [0.0, 0.0, tol])
+            r[0] = r[1] = max(r[0], el)
+            assert el <= tol, (label, "loss", j, g["loss"], st.loss)
         for i in ora_stage.output_ids:
             chk(f"mb{j}.out{i}", g["outs"][i], st.values[i])
         assert set(g["gin"]) == set(gin), (set(g["gin"]), set(gin))
         for i, ref in gin.items():
-            chk(f"mb{j}.gin{i}", g["gin"][i], ref, tol_gin)
+            if mode == "bf16" and has_relu:
+                chk_relu_gin(f"mb{j}.gin{i}", g["gin"][i], ref)
+            else:
+                chk(f"mb{j}.gin{i}", g["gin"][i], ref)
     for i, gr in ora_stage.grads.items():
         for k, ref in gr.items():
             chk(f"op{i}.d{k}", gpu_grads[i][k], ref)

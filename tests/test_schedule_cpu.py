@@ -125,3 +125,34 @@ def test_partition_refuses_fan_out_across_a_cut():
     stage_of = {i: 0 for i, op in enumerate(wl.ops) if op["kind"] != "input"}
     parts, edges = W.partition(wl, stage_of, 1)
     assert edges == [] and len(parts[0].ops) == len(wl.ops)
+
+
+def test_capture_of_slot_reuse_waits_is_refused_on_the_host():
+    """GraphedMinibatch / StagePipeline refuse, before any GPU call, the one form whose capture has crashed:
+    several streams and fewer stash slots than micro-batches."""
+    from types import SimpleNamespace
+    from paper_2406_17145_amd import schedule as S
+
+    def fake(cls, slots, **attrs):
+        obj = object.__new__(cls)
+        obj.st = SimpleNamespace(slots=slots)
+        for k, v in attrs.items():
+            setattr(obj, k, v)
+        return obj
+
+    batches = [None] * 3
+    with pytest.raises(ValueError, match="capture refused"):
+        S.GraphedMinibatch(fake(S.OverlapSchedule, 2), batches)
+    with pytest.raises(ValueError, match="capture refused"):
+        S.GraphedMinibatch(fake(S.TaskSchedule, 2, two=True), batches)
+    S.GraphedMinibatch.check_capturable(fake(S.OverlapSchedule, 3), 3)            # a slot per micro-batch: allowed
+    S.GraphedMinibatch.check_capturable(fake(S.TaskSchedule, 1, two=False), 3)    # one stream: no event waits
+    S.GraphedMinibatch.check_capturable(fake(S.SerialSchedule, 1), 3)
+    pipe = object.__new__(S.StagePipeline)
+    pipe.stages = [SimpleNamespace(slots=2), SimpleNamespace(slots=4)]
+    io = [[None] * 4, [None] * 4]
+    with pytest.raises(ValueError, match="capture refused"):
+        pipe.check_not_capturing_slot_reuse(io, capturing=True)
+    pipe.check_not_capturing_slot_reuse(io, capturing=False)
+    pipe.stages[0].slots = 4
+    pipe.check_not_capturing_slot_reuse(io, capturing=True)
