@@ -4,15 +4,26 @@
 A "step" is one pass of the whole hot path over one mini-batch of synthetic
 input: grad_reset, then for each of the workload's micro-batches fw_j and bw_j
 (weight gradients accumulate across them).  Inputs are resident in HBM before
-the timed region.  Default workload: the CANDLE-Uno-shaped feature-tower stage
-(micro-batch 64, 8 micro-batches, bf16 storage with fp32 accumulation).
+the timed region.
+
+Without --config the line's headline (`value`, `roofline`, `cpu_baseline`) is the
+multi-modal-transformer-shaped stage (micro-batch 4, the largest single-GPU
+workload and the only one bound by the matrix cores), and the key `configs`
+carries the other four workloads measured the same way in the same process:
+samples/s, median / min / max milliseconds per step, the dominant kernel and its
+fraction of the published peak; for the heterogeneous stage also the sweep over
+micro-batch sizes 1 ... 128, for the feature-tower stage also the schedules with
+two micro-batches in flight.  With --config NAME only that workload runs.
 
 Prints ONE JSON line.  Besides the driver's fields it carries
   roofline      the dominant kernel's algorithmic bytes (or flops) per launch over its average
-                launch duration, measured with HIP events on the launch stream in a second,
-                instrumented pass over the same steps
+                launch duration, measured with HIP events on the launch stream, one launch per
+                event bracket, in an instrumented pass over the same steps; `traffic` is read
+                from profiles/kernel_traffic.txt (written from rocprofv3 counter runs by
+                paper_2406_17145_amd/profile_summary.py), null when that file has no entry
   cpu_baseline  the CPU oracle timed on this host on a bounded sample of the same workload
   kernels       per-kernel breakdown of the instrumented pass
+  step_ms       median / min / max / spread of per-step times (HIP events around every step)
 """
 import argparse
 import json
@@ -106,36 +117,37 @@ def other_traffic(wl):
     return out
 
 
-# HBM bytes per launch of the dominant kernel of each workload, from two rocprofv3 --pmc runs
-# (FETCH_SIZE, then WRITE_SIZE) scaled by what the same counters read for a copy of known size
-# (--copy-calibration); the summaries are kept under profiles/.  None where not measured.
 AUTO_SHARED_LANES = True   # fw_j and bw_j of a micro-batch on one stream: a chain of launches per micro-batch
 AUTO_LANES = (2, 2)     # --lanes auto, where the stage allows several streams per direction
 
-MEASURED_TRAFFIC = {
-    # bytes per launch, averaged over the launches of the kernel family within a step
-    ("candle_uno", "gemm_bwd_merged_dx_dw"): 50.5e6,
-    ("candle_uno", "gemm_skinny_fwd"): 35.1e6,     # a launch covers four micro-batches (group launches)
-    ("candle_uno", "gemm_skinny_dx"): 42.7e6,
-    ("candle_uno", "gemm_big_dw"): 122.1e6,      # the grouped launch: eight slots, every Linear of the stage
-    ("hetero", "gemm_skinny_fwd"): 48.7e6,
-    ("hetero", "gemm_skinny_dx"): 47.2e6,
-    ("hetero", "gemm_big_dw"): 419.5e6,          # the grouped launch: every Linear of the stage
-    ("mmt", "gemm_big_fwd"): 186.0e6,
-    ("mmt", "gemm_big_dx"): 168.1e6,
-    ("mmt", "gemm_big_dw"): 2964.5e6,            # the grouped launch: every Linear of the stage (105.9 M parameters)
-    ("dlrm", "gemm_big_dw"): 68.4e6,
-    ("dlrm", "embedding_bwd_sort_segsum"): 54.3e6,
-    ("dlrm", "embedding_fwd"): 180.6e6,
-}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "kernel_traffic.txt")
 
 
-def main():
+def measured_traffic(config, kernel):
+    """HBM bytes per launch of a kernel family of a workload, from two rocprofv3 --pmc runs (FETCH_SIZE, then
+    WRITE_SIZE) scaled by what the same counters read for a copy of known size; the table is written by
+    paper_2406_17145_amd/profile_summary.py next to the summaries it comes from.  None where not measured."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                part = [v.strip() for v in line.split("|")]
+                if len(part) >= 3 and part[0] == config and part[1] == kernel:
+                    return float(part[2])
+    except OSError:
+        pass
+    return None
+
+
+CONFIG_NAMES = ["tiny_mlp", "candle_uno", "mmt", "dlrm", "hetero", "paper_mmt", "paper_candle", "paper_dlrm"]
+
+
+def build_parser():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1000)
-    ap.add_argument("--warmup", type=int, default=100)
-    ap.add_argument("--config", default="candle_uno", choices=["tiny_mlp", "candle_uno", "mmt", "dlrm", "hetero", "paper_mmt", "paper_candle", "paper_dlrm"])
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="all", choices=["all"] + CONFIG_NAMES,
+                    help="all (default): headline mmt, the other four workloads under the key `configs`")
     ap.add_argument("--micro-batch", type=int, default=0, help="override the config's micro-batch size")
     ap.add_argument("--in-flight", type=int, default=0, metavar="M",
                     help="--schedule kfkb: micro-batches the stage may hold (its stash slots; i = M * micro-batch samples); "
@@ -179,12 +191,11 @@ def main():
     ap.add_argument("--no-kernel-pass", action="store_true", help="skip the event-instrumented second pass")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="before the steps, run 3 plain elementwise copies of MIB mebibytes (counter calibration)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build measures one stage on ONE GPU (no collectives, no sharding); "
-              "--gpus must be 1", file=sys.stderr)
-        sys.exit(2)
+    return ap
 
+
+def run_one(args):
+    """One workload in one launch configuration: returns the JSON object of its line."""
     import numpy as np
     import torch
     from paper_2406_17145_amd import binding as B
@@ -194,6 +205,7 @@ def main():
     if args.micro_batch:
         kw["micro_batch"] = args.micro_batch
     wl = W.CONFIGS[args.config](**kw)
+    kernels, roofline = {}, None
     from paper_2406_17145_amd.schedule import GraphedMinibatch, OverlapSchedule, SerialSchedule, TaskSchedule
     kfkb = args.schedule == "kfkb" or (args.schedule == "auto" and wl.n_micro >= 2)
     overlap = args.schedule == "overlap"
@@ -279,42 +291,23 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    st.sync_status()
-    samples_per_step = wl.micro_batch * wl.n_micro
-    value = args.steps * samples_per_step / dt
-    serial_value = None
-    if (overlap or kfkb or graphed is not None) and not args.no_serial_reference:   # the same steps enqueued from the host in serial order, for reference
-        for _ in range(2):
-            eager_step(serial)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        ref_steps = min(args.steps, 200)
-        for _ in range(ref_steps):
-            eager_step(serial)
-        torch.cuda.synchronize()
-        serial_value = ref_steps * samples_per_step / (time.perf_counter() - t1)
-
-    # ---- instrumented pass: per-kernel durations from HIP events on the launch stream ----
-    kernels, roofline = {}, None
+    # ---- instrumented pass (before the timed region: it is set-up as far as the timed steps are concerned, and
+    # the GPU's clocks have settled by the time they start): per-kernel durations from HIP events on the launch stream
     if not args.no_kernel_pass:
-        # Two passes.  One launch per event bracket: right for launches of tens of microseconds, but the bracket's
-        # own dispatch latency (about 2 us) is a quarter of a few-row launch.  GEMM launches issued 8 times inside
-        # each bracket: right for those short launches, but a repeated launch finds its weights in the last-level
-        # cache, which flatters launches that stream tens of megabytes (hetero forward: 18.8 us repeated, 32 us by
-        # rocprofv3).  Each GEMM family takes the single-launch figure from 20 us on, the repeated one below.
+        # Two passes.  One launch per event bracket: this is the figure every rate below uses (it agrees with the
+        # rocprofv3 kernel trace from about 20 us per launch on; below that the bracket's own dispatch latency of
+        # about 2 us shows, so short launches read a little SLOWER here than in the trace).  GEMM launches issued 8
+        # times inside each bracket: reported beside it as `avg_launch_us_back_to_back` only -- a repeated launch
+        # finds its weights in the last-level cache, which flatters launches that stream tens of megabytes.
         REP = 8
         k_steps = max(1, min(args.steps, 20))
         # per-kernel durations are taken with the calls back to back on ONE stream, eagerly: in serial order, or,
         # with grouped weight gradients (whose kernels depend on the grouping), in the timed task order
         inst = TaskSchedule(st, n_slots * wl.micro_batch, args.k, two_streams=False, lanes=lanes, same_stream=True) if (kfkb and grouped) else serial
+
+        for _ in range(max(3, min(args.warmup, 20))):     # clocks and caches as in the timed steps
+            eager_step(inst)
+        torch.cuda.synchronize()
 
         def kernel_pass(rep):
             st.profile_enable(rep)
@@ -327,14 +320,13 @@ def main():
             return {name: ((ms / rep, launches / rep) if name.startswith("gemm_") and not name.startswith("gemm_generic") else (ms, launches))
                     for name, (ms, launches) in got.items()}
         single, repeated = kernel_pass(1), kernel_pass(REP)
-        prof = {}
-        for name, (ms, launches) in single.items():
-            long_launch = 1e3 * ms / max(launches, 1) >= 20.0
-            prof[name] = (ms, launches) if (long_launch or name not in repeated) else repeated[name]
+        prof = dict(single)
         total_ms = sum(v[0] for v in prof.values())
         for name, (ms, launches) in sorted(prof.items(), key=lambda kv: -kv[1][0]):
             kernels[name] = {"ms_per_step": ms / k_steps, "launches_per_step": launches / k_steps,
                              "avg_launch_us": 1e3 * ms / max(launches, 1), "share": ms / total_ms}
+            if name in repeated and name.startswith("gemm_"):
+                kernels[name]["avg_launch_us_back_to_back"] = 1e3 * repeated[name][0] / max(repeated[name][1], 1)
         tr = gemm_traffic(wl)
         nm = wl.n_micro
         # algorithmic bytes / flops per STEP of each GEMM role; a role's figure goes to the kernel family
@@ -379,10 +371,10 @@ def main():
             hbm_bound = by / (HBM_PEAK_GBS * 1e9) >= fl / (MFMA_BF16_PEAK_TFLOPS * 1e12)
             if hbm_bound:
                 roofline = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                            "frac": gbs / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((args.config, dom))}
+                            "frac": gbs / HBM_PEAK_GBS, "traffic": measured_traffic(args.config, dom)}
             else:
                 roofline = {"bound": "mfma", "achieved": tfl, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                            "frac": tfl / MFMA_BF16_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC.get((args.config, dom))}
+                            "frac": tfl / MFMA_BF16_PEAK_TFLOPS, "traffic": measured_traffic(args.config, dom)}
             roofline.update({"kernel": dom, "avg_launch_us": k["avg_launch_us"],
                              "launches_per_step": k["launches_per_step"],
                              "algorithmic_bytes_per_launch": by / k["launches_per_step"],
@@ -397,13 +389,55 @@ def main():
         # durations above are each kernel ALONE on the GPU (one stream); in the timed step launches of
         # several streams overlap, so the step moves more bytes per second than its kernels do one by one
         step_bytes = sum(v[0] for v in alg.values())
-        roofline["step_algorithmic_gbs"] = step_bytes / (dt / args.steps) / 1e9
-        roofline["step_frac_of_hbm_peak"] = roofline["step_algorithmic_gbs"] / HBM_PEAK_GBS
+        step_flops = sum(v[1] for v in alg.values())
         # every kernel with a known algorithmic count: achieved rates beside the durations
         for name, k in kernels.items():
             if name in alg and k["ms_per_step"] > 0:
                 k["algorithmic_gbs"] = alg[name][0] / (k["ms_per_step"] * 1e-3) / 1e9
                 k["algorithmic_tflops"] = alg[name][1] / (k["ms_per_step"] * 1e-3) / 1e12
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    st.sync_status()
+    samples_per_step = wl.micro_batch * wl.n_micro
+    value = args.steps * samples_per_step / dt
+    # per-step times: a HIP event on the caller's stream in front of every step (every schedule starts and ends
+    # a step on that stream), at least 50 steps; the difference of neighbouring events is one step
+    n_ev = max(args.steps, 50)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_ev + 1)]
+    for i in range(n_ev):
+        evs[i].record()
+        step()
+    evs[n_ev].record()
+    torch.cuda.synchronize()
+    per_step = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(n_ev))
+    med = per_step[n_ev // 2]
+    step_ms = {"median": med, "min": per_step[0], "max": per_step[-1], "p10": per_step[n_ev // 10], "p90": per_step[(9 * n_ev) // 10],
+               "spread_p10_p90": (per_step[(9 * n_ev) // 10] - per_step[n_ev // 10]) / med, "steps": n_ev,
+               "samples_per_s_at_median": samples_per_step / (med * 1e-3)}
+    serial_value = None
+    if (overlap or kfkb or graphed is not None) and not args.no_serial_reference:   # the same steps enqueued from the host in serial order, for reference
+        for _ in range(2):
+            eager_step(serial)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ref_steps = min(args.steps, 200)
+        for _ in range(ref_steps):
+            eager_step(serial)
+        torch.cuda.synchronize()
+        serial_value = ref_steps * samples_per_step / (time.perf_counter() - t1)
+
+    if roofline is not None and not args.no_kernel_pass:
+        roofline["step_algorithmic_gbs"] = step_bytes / (dt / args.steps) / 1e9
+        roofline["step_frac_of_hbm_peak"] = roofline["step_algorithmic_gbs"] / HBM_PEAK_GBS
+        roofline["step_algorithmic_tflops"] = step_flops / (dt / args.steps) / 1e12
+        roofline["step_frac_of_mfma_peak"] = roofline["step_algorithmic_tflops"] / MFMA_BF16_PEAK_TFLOPS
 
     # ---- CPU oracle on this host, bounded sample --------------------------------------------
     cpu = None
@@ -414,21 +448,30 @@ def main():
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
         except Exception:
             cores = os.cpu_count()
-        ost = O.OracleStage(wl.ops, wl.micro_batch, wl.params, model_storage=True)
-        s0 = ost.forward(wl.batches[0])        # warm-up
-        go = {i: np.zeros((s0.values[i].shape)) for i in ost.output_ids}
-        ost.backward(s0, go)
+        # a bounded sample of the same workload: about 10-30 s of CPU work.  A workload whose micro-batch costs
+        # more than that (the transformer stage: 1.3 TFLOP in fp64) is timed on ONE sample of it, once, cold
+        heavy = 3 * gemm_traffic(wl)["fwd"][1] > 2e11
+        cw = W.CONFIGS[args.config](micro_batch=1) if heavy else wl
+        ost = O.OracleStage(cw.ops, cw.micro_batch, cw.params, model_storage=True)
+        go = None
+        if not heavy:
+            s0 = ost.forward(cw.batches[0])        # warm-up
+            go = {i: np.zeros((s0.values[i].shape)) for i in ost.output_ids}
+            ost.backward(s0, go)
         n_done, t0 = 0, time.perf_counter()
         while True:
-            mb = wl.batches[n_done % len(wl.batches)]
+            mb = cw.batches[n_done % len(cw.batches)]
             s = ost.forward(mb)
+            if go is None:
+                go = {i: np.zeros((s.values[i].shape)) for i in ost.output_ids}
             ost.backward(s, go)
             n_done += 1
             el = time.perf_counter() - t0
             if el > 12.0 or n_done >= 64:
                 break
-        cpu = {"value": n_done * wl.micro_batch / el, "unit": "samples/s", "cores": cores, "kind": "oracle",
-               "sample": f"{n_done} micro-batch(es) of {wl.micro_batch} samples, forward+backward, fp64 numpy"}
+        cpu = {"value": n_done * cw.micro_batch / el, "unit": "samples/s", "cores": cores, "kind": "oracle",
+               "sample": f"{n_done} micro-batch(es) of {cw.micro_batch} sample(s) of the {args.config} workload, forward+backward, "
+                         f"fp64 numpy, {el:.1f} s" + (" (one cold pass, no warm-up)" if heavy else "")}
 
     out = {
         "metric": "stage fwd+bwd samples/s", "value": value, "unit": "samples/s", "n_gpus": 1,
@@ -450,10 +493,86 @@ def main():
                    "launch": "HIP graph replay of the whole step" if graphed is not None else "eager",
                    "launches_per_microbatch": st.num_launches(False) + st.num_launches(True),
                    "serial_eager_samples_per_s": serial_value},
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+        "roofline": roofline, "cpu_baseline": cpu, "step_ms": step_ms, "kernels": kernels,
     }
-    print(json.dumps(out))
     st.close()
+    return out
+
+
+def summary(out):
+    """The part of a workload's line that goes under `configs`."""
+    r = out["roofline"] or {}
+    keep = ("kernel", "bound", "achieved", "peak", "unit", "frac", "traffic", "avg_launch_us", "launches_per_step",
+            "step_algorithmic_gbs", "step_frac_of_hbm_peak", "step_algorithmic_tflops", "step_frac_of_mfma_peak", "logical_gbs")
+    top = sorted(out["kernels"].items(), key=lambda kv: -kv[1]["ms_per_step"])[:4]
+    return {"workload": out["config"]["workload"], "samples_per_s": out["value"], "ms_per_step": out["ms_per_step"],
+            "steps": out["steps"], "warmup": out["warmup"], "step_ms": out["step_ms"], "dtype": out["dtype"],
+            "schedule": out["config"]["schedule"], "launch": out["config"]["launch"],
+            "peak_stash_bytes": out["config"]["peak_stash_bytes"],
+            "dominant_kernel": {k: r.get(k) for k in keep if k in r},
+            "kernels": {name: {"avg_launch_us": k["avg_launch_us"], "launches_per_step": k["launches_per_step"], "share": k["share"],
+                               **({"algorithmic_gbs": k["algorithmic_gbs"], "algorithmic_tflops": k["algorithmic_tflops"]}
+                                  if "algorithmic_gbs" in k else {})} for name, k in top}}
+
+
+def main():
+    import copy
+    # the two measurements around the stage path: --mode pipeline (several stages of a stage graph on one GPU) and
+    # --mode partition (the partitioner on this build's operator graphs, host only) take their own flags
+    if "--mode" in sys.argv[1:]:
+        i = sys.argv.index("--mode")
+        mode, rest = (sys.argv[i + 1] if i + 1 < len(sys.argv) else ""), sys.argv[1:i] + sys.argv[i + 2:]
+        if mode == "pipeline":
+            from paper_2406_17145_amd.bench_pipeline import main as run
+            return run(rest)
+        if mode == "partition":
+            from paper_2406_17145_amd.bench_partition import main as run
+            return run(rest)
+        if mode != "stage":
+            sys.exit("bench.py: --mode is one of stage (default), pipeline, partition")
+        sys.argv = [sys.argv[0]] + rest
+    args = build_parser().parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one stage on ONE GPU (no collectives, no sharding); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    if args.config != "all":
+        print(json.dumps(run_one(args)))
+        return
+
+    def variant(config, **kw):
+        a = copy.copy(args)
+        a.config = config
+        a.no_cpu_baseline = True
+        # the driver may ask for few steps; the short-step workloads get enough of them for a stable median
+        a.steps, a.warmup = max(args.steps, 200), max(args.warmup, 20)
+        for k, v in kw.items():
+            setattr(a, k, v)
+        return a
+
+    head = copy.copy(args)
+    head.config = "mmt"
+    out = run_one(head)
+    configs = {"mmt": summary(out)}
+    configs["candle_uno"] = summary(run_one(variant("candle_uno")))
+    # the same stage with two micro-batches in flight (1F1B-like), beside the eight of the default: eager on two
+    # streams (a captured step would need a slot per micro-batch), and captured on one stream
+    two = run_one(variant("candle_uno", in_flight=2, k=1, no_kernel_pass=True, no_serial_reference=True))
+    two1 = run_one(variant("candle_uno", in_flight=2, k=1, one_stream=True, no_kernel_pass=True, no_serial_reference=True))
+    configs["candle_uno"]["two_in_flight"] = [
+        {"samples_per_s": o["value"], "step_ms": o["step_ms"], "schedule": o["config"]["schedule"], "launch": o["config"]["launch"],
+         "peak_stash_bytes": o["config"]["peak_stash_bytes"]} for o in (two, two1)]
+    configs["dlrm"] = summary(run_one(variant("dlrm")))
+    configs["hetero"] = summary(run_one(variant("hetero", micro_batch=128)))
+    sweep = []
+    for b in (1, 2, 4, 8, 16, 32, 64, 128):
+        o = run_one(variant("hetero", micro_batch=b, no_kernel_pass=True, no_serial_reference=True))
+        sweep.append({"micro_batch": b, "samples_per_s": o["value"], "ms_per_step": o["ms_per_step"], "median_ms": o["step_ms"]["median"],
+                      "min_ms": o["step_ms"]["min"], "max_ms": o["step_ms"]["max"]})
+    configs["hetero"]["micro_batch_sweep"] = sweep
+    configs["tiny_mlp"] = summary(run_one(variant("tiny_mlp")))
+    out["configs"] = configs
+    print(json.dumps(out))
 
 
 if __name__ == "__main__":

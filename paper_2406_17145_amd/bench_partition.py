@@ -1,4 +1,3 @@
-#!/usr/bin/env python3
 """Partitioner on the operator graphs of this build's workloads (host only, no GPU needed).
 
 For every workload: per-operator costs from a two-term model (time per sample = max(flops / matrix-core rate,
@@ -7,7 +6,7 @@ own kernels; parameter + gradient bytes; stashed bytes per sample), then gpp_par
 Prints one JSON line per (workload, devices): stages, devices per stage, in-flight micro-batches, bottleneck time
 per sample, speed-up over one device, search time and dynamic-programme states.
 
-  python bench_partition.py [--config NAME] [--memory-gb G]
+  python bench.py --mode partition [--config NAME] [--memory-gb G]
 """
 import argparse
 import json
@@ -54,11 +53,11 @@ def op_costs(wl):
     return edges, t, w, a
 
 
-def main():
-    ap = argparse.ArgumentParser()
+def main(argv=None):
+    ap = argparse.ArgumentParser(prog="bench.py --mode partition")
     ap.add_argument("--config", default="all")
     ap.add_argument("--memory-gb", type=float, default=288.0)
-    args = ap.parse_args()
+    args = ap.parse_args(argv)
     from paper_2406_17145_amd import binding as B
     from paper_2406_17145_amd import workloads as W
     names = ["candle_uno", "mmt", "dlrm", "hetero"] if args.config == "all" else [args.config]
@@ -81,7 +80,3 @@ def main():
                               "bottleneck_us_per_sample": 1e6 * got["bottleneck"],
                               "speedup_over_one_device": base / got["bottleneck"], "search_ms": round(ms, 2),
                               "dp_states": got["dp_states"]}))
-
-
-if __name__ == "__main__":
-    main()

@@ -1,4 +1,3 @@
-#!/usr/bin/env python3
 """Stage graph on one GPU: the CANDLE-Uno-shaped model cut into its four towers and a merge stage, run by the
 library's pipeline executor as a GRAPH pipeline (towers side by side: stage graph of depth 2) and as a SEQUENTIAL
 pipeline (the same stages chained: depth 5), the contrast of paper section 2 in miniature.
@@ -8,7 +7,7 @@ scheduler assigns (gpp_assign_schedules) and the stash bytes they pin.  All stag
 stand in for devices), so the times show what the dependency structure allows on one chip, not a multi-GPU
 speed-up; the in-flight counts and stash bytes are what the paper's memory argument is about.
 
-  python bench_pipeline.py [--steps K] [--warmup W] [--micro-batch B] [--micro-batches N] [--k K] [--grouped-dw]
+  python bench.py --mode pipeline [--steps K] [--warmup W] [--micro-batch B] [--micro-batches N] [--k K] [--grouped-dw]
 """
 import argparse
 import json
@@ -16,8 +15,8 @@ import sys
 import time
 
 
-def main():
-    ap = argparse.ArgumentParser()
+def main(argv=None):
+    ap = argparse.ArgumentParser(prog="bench.py --mode pipeline")
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--micro-batches", type=int, default=8)
@@ -26,7 +25,7 @@ def main():
                          "(about 3 us per launch or event) paces the eager pipeline, from about 1024 on the GPU does")
     ap.add_argument("--k", type=int, default=1, help="group size of every stage's kFkB list")
     ap.add_argument("--grouped-dw", action="store_true", help="stages with grouped weight gradients")
-    args = ap.parse_args()
+    args = ap.parse_args(argv)
 
     import torch
     from paper_2406_17145_amd import binding as B
@@ -78,7 +77,3 @@ def main():
         pipe.close()
         for st in stages:
             st.close()
-
-
-if __name__ == "__main__":
-    main()
