@@ -172,6 +172,22 @@ gpp_status_t gpp_stage_workspace_bytes(const gpp_stage_desc_t *desc, size_t *byt
 gpp_status_t gpp_stage_create(const gpp_stage_desc_t *desc, void *workspace, size_t workspace_bytes,
                               gpp_stage_t **out);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture set-up, tight serving loops,
+ * harnesses that forbid hipMalloc): gpp_stage_create with the workspace taken from a device array that is part
+ * of the library itself (GPP_STATIC_WORKSPACE_BYTES per GPU, held by every GPU the library runs on until the
+ * process ends).  The call allocates no device memory and calls no allocating routine; parameters, gradient
+ * accumulators and per-call tensors stay the caller's.  The created stage is an ordinary stage: forward,
+ * backward, grad_reset, the schedule executor and destroy work on it as on any other.
+ *   - GPP_ERR_WORKSPACE if the stage needs more than GPP_STATIC_WORKSPACE_BYTES (gpp_stage_workspace_bytes says
+ *     how much a descriptor needs); GPP_ERR_UNSUPPORTED with flag bit 3 (its side stream would have to be created).
+ *   - One stage per GPU holds the array at a time: GPP_ERR_ORDER while another stage created by this call on the
+ *     current GPU has not been destroyed.  The array keeps the previous stage's contents; the call clears the
+ *     part it uses (on the null stream, synchronously), so device work of a destroyed static stage must have
+ *     finished before the next one is created: calls that overlap on one GPU race.
+ *   - The GPU that is current at the call is the one whose array is used. */
+#define GPP_STATIC_WORKSPACE_BYTES (32u << 20)
+gpp_status_t gpp_stage_create_static(const gpp_stage_desc_t *desc, gpp_stage_t **out);
+
 /* fw_j: forward pass of one micro-batch into stash slot `slot`.
  *   inputs[i]   DEVICE, dense tensor of the i-th GPP_OP_INPUT in op-id order (read during the call's
  *               kernels only; the stage keeps its own copy for the backward pass)

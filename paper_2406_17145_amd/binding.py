@@ -54,7 +54,7 @@ class StageDesc(C.Structure):
 
 
 EXPORTS = [
-    "gpp_ld", "gpp_stage_workspace_bytes", "gpp_stage_create", "gpp_stage_forward", "gpp_stage_backward",
+    "gpp_ld", "gpp_stage_workspace_bytes", "gpp_stage_create", "gpp_stage_create_static", "gpp_stage_forward", "gpp_stage_backward",
     "gpp_stage_grad_reset", "gpp_stage_sync_status", "gpp_stage_destroy", "gpp_stage_num_inputs",
     "gpp_stage_num_outputs", "gpp_stage_input_op", "gpp_stage_output_op", "gpp_stage_num_launches",
     "gpp_stage_embedding_sort_result", "gpp_last_error", "gpp_stage_profile_enable", "gpp_stage_profile_read",
@@ -99,6 +99,8 @@ def load():
     lib.gpp_stage_workspace_bytes.argtypes = [C.POINTER(StageDesc), C.POINTER(C.c_size_t)]
     lib.gpp_stage_create.restype = i32
     lib.gpp_stage_create.argtypes = [C.POINTER(StageDesc), vp, C.c_size_t, C.POINTER(vp)]
+    lib.gpp_stage_create_static.restype = i32
+    lib.gpp_stage_create_static.argtypes = [C.POINTER(StageDesc), C.POINTER(vp)]
     lib.gpp_stage_forward.restype = i32
     lib.gpp_stage_forward.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(vp), vp, vp]
     lib.gpp_stage_backward.restype = i32
@@ -211,6 +213,12 @@ def gpp_stage_workspace_bytes(desc):
 def gpp_stage_create(desc, workspace_ptr, workspace_bytes):
     h = C.c_void_p()
     _check(load().gpp_stage_create(C.byref(desc), workspace_ptr, workspace_bytes, C.byref(h)))
+    return h
+
+
+def gpp_stage_create_static(desc):
+    h = C.c_void_p()
+    _check(load().gpp_stage_create_static(C.byref(desc), C.byref(h)))
     return h
 
 
@@ -417,7 +425,7 @@ class Stage:
     """Owns the device buffers of one stage (PyTorch tensors) and marshals numpy
     arrays to and from the C ABI."""
 
-    def __init__(self, ops, micro_batch, params, slots=1, flags=0, device="cuda:0"):
+    def __init__(self, ops, micro_batch, params, slots=1, flags=0, device="cuda:0", static_workspace=False):
         import torch
         self.torch = torch
         self.dev = torch.device(device)
@@ -448,9 +456,13 @@ class Stage:
                 pp[i][k], gp[i][k] = t.data_ptr(), g.data_ptr()
         self.desc, self._keep = build_desc(ops, micro_batch, slots, flags, pp, gp)
         self.ws_bytes = gpp_stage_workspace_bytes(self.desc)
-        self.ws = torch.empty(self.ws_bytes + 256, dtype=torch.uint8, device=self.dev)
-        base = (self.ws.data_ptr() + 255) // 256 * 256
-        self.handle = gpp_stage_create(self.desc, base, self.ws_bytes)
+        if static_workspace:      # the library's own device array: no workspace tensor
+            self.ws = None
+            self.handle = gpp_stage_create_static(self.desc)
+        else:
+            self.ws = torch.empty(self.ws_bytes + 256, dtype=torch.uint8, device=self.dev)
+            base = (self.ws.data_ptr() + 255) // 256 * 256
+            self.handle = gpp_stage_create(self.desc, base, self.ws_bytes)
         lib = load()
         self.input_ids = [lib.gpp_stage_input_op(self.handle, k) for k in range(lib.gpp_stage_num_inputs(self.handle))]
         self.output_ids = [lib.gpp_stage_output_op(self.handle, k) for k in range(lib.gpp_stage_num_outputs(self.handle))]

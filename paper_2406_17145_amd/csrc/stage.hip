@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstring>
 #include <deque>
+#include <mutex>
 #include <new>
 #include <string>
 
@@ -67,7 +68,17 @@ struct gpp_stage {
   // stage when its plan runs embedding bags next to dense branches
   hipStream_t lane_stream[2] = {nullptr, nullptr};
   hipEvent_t lane_fork[2] = {nullptr, nullptr}, lane_join[2] = {nullptr, nullptr};
+  int static_device = -1;    // >= 0: the workspace is the library's static device array of that GPU (gpp_stage_create_static)
 };
+
+// ---- the static workspace of gpp_stage_create_static: device memory that exists as soon as the library is
+// loaded on a GPU, so that a stage can be created without any allocation.  In host code the array's name is a
+// stand-in, not a device address: the address of THIS GPU's copy is asked for once per device and kept.
+static __device__ __align__(256) unsigned char scratch[GPP_STATIC_WORKSPACE_BYTES];
+constexpr int STATIC_MAX_DEVICES = 64;
+static std::mutex g_static_mutex;
+static void *g_static_ptr[STATIC_MAX_DEVICES] = {nullptr};          // per device: address of its copy of `scratch`
+static const gpp_stage *g_static_owner[STATIC_MAX_DEVICES] = {nullptr};   // per device: the stage that holds it
 
 static bool gemm_step(const Step &sp) {
   return sp.kern == K_GEMM_MFMA || sp.kern == K_GEMM_BIG || sp.kern == K_GEMM_SKINNY || sp.kern == K_GEMM_BWD_MERGED ||
@@ -160,8 +171,26 @@ gpp_status_t gpp_stage_workspace_bytes(const gpp_stage_desc_t *desc, size_t *byt
   return GPP_OK;
 }
 
-gpp_status_t gpp_stage_create(const gpp_stage_desc_t *desc, void *workspace, size_t workspace_bytes, gpp_stage_t **out) {
+// workspace == nullptr: take the static workspace of the current device (gpp_stage_create_static)
+static gpp_status_t stage_create(const gpp_stage_desc_t *desc, void *workspace, size_t workspace_bytes, gpp_stage_t **out) {
   if (!out) return fail(GPP_ERR_INVALID_ARG, "out is null");
+  const bool use_static = workspace == nullptr;
+  int dev = -1;
+  if (use_static) {
+    hipError_t he = hipGetDevice(&dev);
+    if (he != hipSuccess) return fail(GPP_ERR_DEVICE, std::string("HIP: ") + hipGetErrorString(he));
+    if (dev < 0 || dev >= STATIC_MAX_DEVICES) return fail(GPP_ERR_UNSUPPORTED, "device ordinal beyond the static workspace table");
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[dev]) {     // once per device, with that device current
+      void *ptr = nullptr;
+      he = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+      if (he != hipSuccess || !ptr) return fail(GPP_ERR_DEVICE, std::string("HIP: static workspace: ") + hipGetErrorString(he));
+      g_static_ptr[dev] = ptr;
+    }
+    if (g_static_owner[dev]) return fail(GPP_ERR_ORDER, "the static workspace of this GPU is held by another stage (destroy it first)");
+    workspace = g_static_ptr[dev];
+    workspace_bytes = GPP_STATIC_WORKSPACE_BYTES;
+  }
   gpp_stage *st = new (std::nothrow) gpp_stage();
   if (!st) return fail(GPP_ERR_INVALID_ARG, "out of host memory");
   gpp_status_t rc = build_plan(desc, st->plan);
@@ -191,8 +220,14 @@ gpp_status_t gpp_stage_create(const gpp_stage_desc_t *desc, void *workspace, siz
     return fail(GPP_ERR_WORKSPACE, "workspace is null or not 256-byte aligned");
   }
   if (workspace_bytes < (size_t)pl.total_bytes) {
+    const int64_t need = pl.total_bytes;
     delete st;
-    return fail(GPP_ERR_WORKSPACE, "workspace too small: need " + std::to_string(pl.total_bytes) + " bytes");
+    return fail(GPP_ERR_WORKSPACE, (use_static ? "the stage needs more than the static workspace holds: need " : "workspace too small: need ") +
+                                       std::to_string(need) + " bytes, have " + std::to_string(workspace_bytes));
+  }
+  if (use_static && pl.lanes) {      // the side stream and its events would have to be created here
+    delete st;
+    return fail(GPP_ERR_UNSUPPORTED, "stage flag bit 3 (side stream) is not available with the static workspace");
   }
   st->ws = (char *)workspace;
   hipError_t he = hipMemset(workspace, 0, (size_t)pl.total_bytes);
@@ -260,9 +295,25 @@ gpp_status_t gpp_stage_create(const gpp_stage_desc_t *desc, void *workspace, siz
       st->emb_count = s.n;
       st->emb_capacity = s.a0;
     }
+  if (use_static) {
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (g_static_owner[dev]) {     // another thread took it meanwhile
+      delete st;
+      return fail(GPP_ERR_ORDER, "the static workspace of this GPU is held by another stage (destroy it first)");
+    }
+    g_static_owner[dev] = st;
+    st->static_device = dev;
+  }
   *out = st;
   return GPP_OK;
 }
+
+gpp_status_t gpp_stage_create(const gpp_stage_desc_t *desc, void *workspace, size_t workspace_bytes, gpp_stage_t **out) {
+  if (!workspace) return fail(GPP_ERR_WORKSPACE, "workspace is null or not 256-byte aligned");
+  return stage_create(desc, workspace, workspace_bytes, out);
+}
+
+gpp_status_t gpp_stage_create_static(const gpp_stage_desc_t *desc, gpp_stage_t **out) { return stage_create(desc, nullptr, 0, out); }
 
 gpp_status_t gpp_stage_destroy(gpp_stage_t *stage) {
   if (stage) {
@@ -272,6 +323,10 @@ gpp_status_t gpp_stage_destroy(gpp_stage_t *stage) {
       if (stage->lane_fork[k]) (void)hipEventDestroy(stage->lane_fork[k]);
       if (stage->lane_join[k]) (void)hipEventDestroy(stage->lane_join[k]);
       if (stage->lane_stream[k]) (void)hipStreamDestroy(stage->lane_stream[k]);
+    }
+    if (stage->static_device >= 0) {
+      std::lock_guard<std::mutex> lock(g_static_mutex);
+      if (g_static_owner[stage->static_device] == stage) g_static_owner[stage->static_device] = nullptr;
     }
   }
   delete stage;
