@@ -188,7 +188,9 @@ def build_parser():
     ap.add_argument("--no-serial-reference", action="store_true",
                     help="skip the untimed-in-value reference pass that runs the same steps eagerly in serial order "
                          "(keeps a kernel trace of the run to the launches of the timed schedule)")
-    ap.add_argument("--no-kernel-pass", action="store_true", help="skip the event-instrumented second pass")
+    ap.add_argument("--no-kernel-pass", action="store_true", help="skip the event-instrumented pass")
+    ap.add_argument("--no-step-times", action="store_true",
+                    help="skip the pass that brackets every step with events (keeps a kernel trace to warm-up + steps)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="before the steps, run 3 plain elementwise copies of MIB mebibytes (counter calibration)")
     return ap
@@ -409,7 +411,7 @@ def run_one(args):
     value = args.steps * samples_per_step / dt
     # per-step times: a HIP event on the caller's stream in front of every step (every schedule starts and ends
     # a step on that stream), at least 50 steps; the difference of neighbouring events is one step
-    n_ev = max(args.steps, 50)
+    n_ev = 1 if args.no_step_times else max(args.steps, 50)
     evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_ev + 1)]
     for i in range(n_ev):
         evs[i].record()

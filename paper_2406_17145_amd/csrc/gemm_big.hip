@@ -153,6 +153,16 @@ __device__ __forceinline__ bf16x8 big_direct_frag_tr(const uint16_t *tile, int c
   return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
+// End of a k-step of the direct path: wait until at most VM of this wave's copy instructions are outstanding
+// (they land in issue order, so the older k-steps are in LDS) and until its LDS reads have returned, then the
+// workgroup barrier.  Written out instead of __syncthreads(): the fence in front of that barrier waits for ALL
+// outstanding copies, which would keep only one k-step in flight whatever the number of LDS buffers.  The
+// "memory" clobber keeps the compiler from moving LDS accesses across it.
+template <int VM>
+__device__ __forceinline__ void copies_landed_barrier() {
+  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(VM) : "memory");
+}
+
 // what every tile kernel of this file does first: XCD-aware spreading (consecutive workgroup ids go
 // round-robin over the 8 XCDs; give each XCD one contiguous range of tiles instead, so that
 // neighbours share operand panels in one L2), then (record, tile) from the records' prefix sums
@@ -188,13 +198,14 @@ template <int FORM, int WGM, int WGN, int WTM, int WTN, int BUFS, int NS, bool G
 __device__ __forceinline__ void big_tile_body(const GemmProb &p, int m0, int n0, uint16_t *lds, int accumulate_dw,
                                               const ExtPtrs &ext, const SlotGroup grp = SlotGroup()) {
   static_assert(!GROUP || FORM == FORM_DW, "only the weight gradient contracts over a group of slots");
-  static_assert(!DIRECT || BUFS == 2, "direct loads fill the other LDS buffer while one is multiplied");
+  static_assert(!DIRECT || BUFS >= 2, "direct loads fill the other LDS buffers while one is multiplied");
   typedef BigCfg<FORM, WGM, WGN, WTM, WTN, BUFS, DIRECT> C;
   constexpr int BM = C::BM, BN = C::BN, THREADS = C::THREADS;
   constexpr bool A_TR = C::A_TR, B_TR = C::B_TR;
   static_assert(BUFS == 1 || NS % 2 == 0, "the LDS double buffer alternates with the ring slot");
-  uint16_t *lds_a[2] = {lds, lds + (BUFS - 1) * C::A_ELEMS};
-  uint16_t *lds_b[2] = {lds + BUFS * C::A_ELEMS, lds + BUFS * C::A_ELEMS + (BUFS - 1) * C::B_ELEMS};
+  static_assert(DIRECT || BUFS <= 2, "the staged path has one or two LDS buffers");
+  uint16_t *lds_a[2] = {lds, lds + (BUFS > 1 ? 1 : 0) * C::A_ELEMS};
+  uint16_t *lds_b[2] = {lds + BUFS * C::A_ELEMS, lds + BUFS * C::A_ELEMS + (BUFS > 1 ? 1 : 0) * C::B_ELEMS};
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wi0 = (wave / WGN) * (32 * WTM), wj0 = (wave % WGN) * (32 * WTN);
 
@@ -308,17 +319,29 @@ __device__ __forceinline__ void big_tile_body(const GemmProb &p, int m0, int n0,
   };
 
   if (DIRECT) {
-    // vmcnt(0): this wave's asynchronous copies have landed; the barrier then covers every wave's
-    fetch_direct(0, 0);
-    __builtin_amdgcn_s_waitcnt(0x0f70);
-    __syncthreads();
+    // BUFS LDS buffers, k-steps kt + 1 .. kt + BUFS - 1 in flight while k-step kt is multiplied.  A wave's copies
+    // land in the order it issued them, so "k-step kt + 1 has landed" is "at most the (BUFS - 2) x LPF copies of
+    // the later k-steps are outstanding" (vmcnt), LPF = copy instructions of one k-step per wave; the barrier
+    // then covers every wave's copies.  Near the end fewer k-steps are in flight than that count assumes: wait
+    // for all of them (vmcnt(0)).
+    constexpr int LPF = (A_TR ? GB_BK * (BM / 8) / 64 / C::NW : BM / C::NW / 8) + (B_TR ? GB_BK * (BN / 8) / 64 / C::NW : BN / C::NW / 8);
+    constexpr int AHEAD = (BUFS > 2 ? BUFS - 2 : 0) * LPF;
+    static_assert(AHEAD < 64, "vmcnt is a 6-bit counter");
+#pragma unroll
+    for (int u = 0; u < BUFS - 1; ++u)
+      if (u < nk) fetch_direct(u, u);
+    if (BUFS - 1 <= nk) copies_landed_barrier<AHEAD>();
+    else copies_landed_barrier<0>();
+    int cur = 0, nxt = BUFS - 1;      // buffer of k-step kt, buffer of k-step kt + BUFS - 1 (multiplied one step ago)
     for (int kt = 0; kt < nk; ++kt) {
-      const int cur = kt & 1;
-      if (kt + 1 < nk) fetch_direct(kt + 1, cur ^ 1);   // flies while this k-step is multiplied
+      const bool more = kt + BUFS - 1 < nk;
+      if (more) fetch_direct(kt + BUFS - 1, nxt);
       multiply(cur);
       bias_rows(cur);
-      __builtin_amdgcn_s_waitcnt(0x0f70);
-      __syncthreads();
+      if (more) copies_landed_barrier<AHEAD>();
+      else copies_landed_barrier<0>();
+      cur = cur + 1 == BUFS ? 0 : cur + 1;
+      nxt = nxt + 1 == BUFS ? 0 : nxt + 1;
     }
   } else if (BUFS == 2) {
 #pragma unroll
@@ -390,14 +413,14 @@ __device__ __forceinline__ void big_tile_body(const GemmProb &p, int m0, int n0,
   }
 }
 
-template <int FORM, int WTM, int WTN, int NS, bool DIRECT>
+template <int FORM, int WTM, int WTN, int NS, bool DIRECT, int BUFS = 2>
 __global__ __launch_bounds__(512) void k_gemm_big(const GemmProb *__restrict__ probs, int n, int total_blocks,
                                                   int accumulate_dw, ExtPtrs ext) {
-  typedef BigCfg<FORM, 2, 4, WTM, WTN, 2, DIRECT> C;
+  typedef BigCfg<FORM, 2, 4, WTM, WTN, BUFS, DIRECT> C;
   __shared__ __attribute__((aligned(16))) uint16_t lds[C::LDS_ELEMS];
   const BigTile t = big_locate<C::BM, C::BN>(probs, n, total_blocks);
   const GemmProb p = probs[t.pi];
-  big_tile_body<FORM, 2, 4, WTM, WTN, 2, NS, false, DIRECT>(p, t.m0, t.n0, lds, accumulate_dw, ext);
+  big_tile_body<FORM, 2, 4, WTM, WTN, BUFS, NS, false, DIRECT>(p, t.m0, t.n0, lds, accumulate_dw, ext);
 }
 
 // 128 x 128 tile, 2 x 2 waves of 64 x 64, one LDS buffer, three waves per SIMD
@@ -480,6 +503,7 @@ static void launch_big_form(const GemmProb *probs, int n, int blocks, int acc, i
   const dim3 g(blocks), b(512);
   if (tile_rows == 256 && direct) hipLaunchKernelGGL((k_gemm_big<FORM, 4, 2, 2, true>), g, b, 0, s, probs, n, blocks, acc, ext);
   else if (tile_rows == 256) hipLaunchKernelGGL((k_gemm_big<FORM, 4, 2, 2, false>), g, b, 0, s, probs, n, blocks, acc, ext);
+  else if (tile_rows == 128 && direct == 3) hipLaunchKernelGGL((k_gemm_big<FORM, 2, 2, 2, true, 3>), g, b, 0, s, probs, n, blocks, acc, ext);
   else if (tile_rows == 128 && direct) hipLaunchKernelGGL((k_gemm_big<FORM, 2, 2, 2, true>), g, b, 0, s, probs, n, blocks, acc, ext);
   else if (tile_rows == 128) hipLaunchKernelGGL((k_gemm_big<FORM, 2, 2, 2, false>), g, b, 0, s, probs, n, blocks, acc, ext);
   else hipLaunchKernelGGL((k_gemm_mid<FORM>), g, dim3(256), 0, s, probs, n, blocks, acc, ext);

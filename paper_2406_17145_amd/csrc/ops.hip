@@ -38,6 +38,31 @@ __device__ __forceinline__ void elt_copy_body(const EltProb &p, const void *src,
     }
 }
 
+// Same-type copy whose rows are whole 16-byte chunks (columns, leading dimensions and base addresses multiples
+// of 16 bytes): a thread moves 16 bytes per load instead of one element (the 16 MB input copy of the
+// transformer stage: 59 -> 13 us).  Same block -> element range as the element-wise body.
+template <int ES>
+__device__ __forceinline__ void elt_copy_vec_body(const EltProb &p, const void *src, void *dst, uint32_t base, uint32_t total) {
+  constexpr int EPC = 16 / ES, IT = ELT_PER_BLOCK / EPC / 256;
+  typedef __attribute__((ext_vector_type(4))) uint32_t u4;
+  u4 v[IT];
+  int64_t di[IT];
+#pragma unroll
+  for (int it = 0; it < IT; ++it) {
+    const uint32_t e = min(base + (it * 256 + threadIdx.x) * EPC, total - EPC);
+    const uint32_t r = e / (uint32_t)p.cols, c = e - r * (uint32_t)p.cols;
+    di[it] = ((int64_t)r * p.ld_dst + c) * ES;
+    v[it] = *(const u4 *)((const char *)src + ((int64_t)r * p.ld_src + c) * ES);
+  }
+#pragma unroll
+  for (int it = 0; it < IT; ++it)
+    if (base + (it * 256 + threadIdx.x) * EPC < total) *(u4 *)((char *)dst + di[it]) = v[it];
+}
+__device__ __forceinline__ bool elt_vec_ok(const EltProb &p, const void *src, const void *dst, int es) {
+  const int epc = 16 / es;
+  return p.cols % epc == 0 && p.ld_src % epc == 0 && p.ld_dst % epc == 0 && (((uintptr_t)src | (uintptr_t)dst) & 15) == 0;
+}
+
 __global__ __launch_bounds__(256) void k_elt(const EltProb *__restrict__ probs, int n, ExtPtrs ext) {
   const int pi = find_prob(probs, n, blockIdx.x);
   const EltProb p = probs[pi];
@@ -49,6 +74,8 @@ __global__ __launch_bounds__(256) void k_elt(const EltProb *__restrict__ probs, 
   if (p.mode == 0 && !p.addend && p.src_dtype != DT_I32 && p.dst_dtype != DT_I32 && total < (1ll << 31) &&
       (int64_t)p.rows * p.ld_dst < (1ll << 32)) {
     const bool sb = p.src_dtype == DT_BF16, db = p.dst_dtype == DT_BF16;
+    if (sb && db && elt_vec_ok(p, src, dst, 2)) return elt_copy_vec_body<2>(p, src, dst, (uint32_t)base, (uint32_t)total);
+    if (!sb && !db && elt_vec_ok(p, src, dst, 4)) return elt_copy_vec_body<4>(p, src, dst, (uint32_t)base, (uint32_t)total);
     if (sb && db) return elt_copy_body<DT_BF16, DT_BF16>(p, src, dst, (uint32_t)base, (uint32_t)total);
     if (sb) return elt_copy_body<DT_BF16, DT_F32>(p, src, dst, (uint32_t)base, (uint32_t)total);
     if (db) return elt_copy_body<DT_F32, DT_BF16>(p, src, dst, (uint32_t)base, (uint32_t)total);
