@@ -193,3 +193,108 @@ def best_stage_graph(n, edges, t, w, a, n_devices, b, memory, sync_per_byte=0.0,
         if best is None or key < best[0]:
             best = (key, plan, ev)
     return None if best is None else (best[1], best[2])
+
+
+# ---- per-stage schedule configurations (paper section 5: the configuration loop of Alg. 1) -----------
+#
+# Alg. 1 does not only cut the graph: SearchStageGraph and the series case of DP enumerate schedule
+# configurations c = (i, b, k) -- micro-batch size b and group size k of a stage's kFkB schedule, with the
+# in-flight samples i that follow from them (section 6, appendix table) -- so that stages may run at
+# different micro-batch sizes.  The definition of the result stays the same (smallest bottleneck time per
+# sample among the stage graphs that fit), the search space grows: every stage of every stage graph takes
+# one (b, k) out of the candidate lists.
+#
+# Readings, beyond those at the top of this file:
+# * the time per sample of an operator depends on the micro-batch size of its stage (the paper profiles
+#   every operator; compute efficiency rises with the micro-batch size, section 2): t[o][j] is the time at
+#   micro-batch size b_values[j];
+# * tensors between stages cost time, affine per message as in the paper's "extrapolating communication
+#   latency by affine functions": a stage pays, per micro-batch, link_latency + bytes * link_seconds_per_byte
+#   for every operator edge with exactly one end inside it (activations in, gradients back), i.e. per sample
+#   cut_edges * link_latency / b + cut_bytes_per_sample * link_seconds_per_byte;
+# * k and b enter the memory side only through the in-flight samples (scheduler oracle, reverse traversal);
+# * Alg. 1 hands both halves of a PARALLEL decomposition the same c_f (they share the source in the paper's
+#   picture): the stages that come first inside a parallel composition all carry one configuration.  The
+#   enumeration below applies the same rule, so that it spans the space the method is defined over;
+# * SearchStageGraph's loop: the enumerated c is the configuration of the FIRST stage(s) of the whole graph,
+#   the dummy c_0 stands for the successor that the last stage does not have.
+
+def cut_of(ops, edges, x):
+    """(number, bytes per sample) of the operator edges with exactly one end in `ops`."""
+    n = 0
+    by = 0.0
+    for e, (u, v) in enumerate(edges):
+        if (u in ops) != (v in ops):
+            n += 1
+            by += x[e] if x is not None else 0.0
+    return n, by
+
+
+def stage_time_cfg(ops, d, j, tb, w, b_values, edges, x, sync_per_byte, mini_batch, link_latency, link_spb):
+    compute = sum(tb[o][j] for o in ops) / d
+    if d > 1:
+        compute += 2.0 * (d - 1) / d * sum(w[o] for o in ops) * sync_per_byte / mini_batch
+    n_cut, by = cut_of(ops, edges, x)
+    return compute + n_cut * link_latency / b_values[j] + by * link_spb
+
+
+def _parallel_sets(node, out):
+    kind, body = node
+    if kind in ("series", "parallel"):
+        if kind == "parallel":
+            out.append(frozenset(ops_of(node)))
+        for c in body:
+            _parallel_sets(c, out)
+    return out
+
+
+def evaluate_cfg(plan, cfg, n, edges, tb, w, a, b_values, k_values, memory, par_sets, x=None, sync_per_byte=0.0,
+                 mini_batch=1, link_latency=0.0, link_spb=0.0):
+    """One stage graph with one (index into b_values, index into k_values) per stage, from the definitions; None
+    if it breaks C1, the memory budget or the shared configuration inside a parallel composition."""
+    stage_of = {}
+    for s, (ops, _) in enumerate(plan):
+        for o in ops:
+            stage_of[o] = s
+    s_edges = sorted({(stage_of[u], stage_of[v]) for u, v in edges if stage_of[u] != stage_of[v]})
+    for pset in par_sets:
+        inside = [s for s, (ops, _) in enumerate(plan) if ops < pset]           # stages strictly inside the composition
+        first = [s for s in inside if not any(y == s and xx in inside for xx, y in s_edges)]
+        if len({cfg[s] for s in first}) > 1:
+            return None
+    try:
+        inflight, _ = S.assign_schedules(len(plan), s_edges, [b_values[cfg[s][0]] for s in range(len(plan))],
+                                         [[k_values[cfg[s][1]]] for s in range(len(plan))])
+    except ValueError:
+        return None
+    tps, mem = [], []
+    for s, (ops, d) in enumerate(plan):
+        tps.append(stage_time_cfg(ops, d, cfg[s][0], tb, w, b_values, edges, x, sync_per_byte, mini_batch, link_latency, link_spb))
+        mem.append(sum(w[o] for o in ops) + inflight[s] / d * sum(a[o] for o in ops))
+        if mem[-1] > memory:
+            return None
+    sources = [s for s in range(len(plan)) if all(y != s for _, y in s_edges)]
+    return dict(tps=max(tps), in_flight=inflight, memory=mem, edges=s_edges,
+                source_in_flight=max(inflight[s] for s in sources))
+
+
+def best_stage_graph_cfg(n, edges, tb, w, a, n_devices, b_values, k_values, memory, x=None, sync_per_byte=0.0,
+                         mini_batch=1, link_latency=0.0, link_spb=0.0):
+    """The definition with per-stage configurations: the feasible (stage graph, configuration per stage) with the
+    smallest bottleneck time per sample, then the fewest in-flight samples at the first stages.  Exhaustive:
+    every plan times every assignment of configurations.  Returns (plan, configurations, evaluation) or None."""
+    import itertools
+    tree = sp_tree(n, edges)
+    par_sets = _parallel_sets(tree, [])
+    cands = [(j, q) for j in range(len(b_values)) for q in range(len(k_values))]
+    best = None
+    for plan in _plans(tree, n_devices):
+        for cfg in itertools.product(cands, repeat=len(plan)):
+            ev = evaluate_cfg(plan, cfg, n, edges, tb, w, a, b_values, k_values, memory, par_sets, x, sync_per_byte,
+                              mini_batch, link_latency, link_spb)
+            if ev is None:
+                continue
+            key = (ev["tps"], ev["source_in_flight"], len(plan))
+            if best is None or key < best[0]:
+                best = (key, plan, cfg, ev)
+    return None if best is None else (best[1], best[2], best[3])

@@ -1789,49 +1789,30 @@ void Emitter::backward() {
   steps = &pl.dwg;
   steps->clear();
   if (!dw_group.empty()) {
-    // One tile shape does not suit every layer: the 256 x 256 tiles (one workgroup per compute unit) win where
-    // they fill the chip a whole number of times, the co-resident 128 x 128 tiles elsewhere (measured cold, four
-    // branches of 2048 rows: [4096 x 1024] 98 against 112 us, [3072 x 1024] 87 against 72, [1024 x 1024] 77
-    // against 40).  So the large layers (at least 64 tiles of 256 x 256 each) get a launch of their own when
-    // together they are a whole number of tiles per compute unit; everything else shares the second launch.
-    constexpr int CUS = 256;
-    std::vector<GemmProb> large, rest;
-    int large_tiles = 0;
+    // (a launch of their own for the largest layers with 256 x 256 tiles, which win on those shapes alone --
+    // 98 against 112 us on 4 x [4096 x 1024] over 2048 rows -- measured no faster for the step: 515 against
+    // 502 us for the transformer stage; one launch lets the co-resident tiles of all layers fill each other's tails)
+    int64_t elems = 0;
+    int tiles256 = 0, tiles128 = 0, max_m = 0, max_n = 0;
     for (auto &r : dw_group) {
-      const int t256 = ((r.M + 255) / 256) * ((r.N + 255) / 256);
-      if (r.M >= 256 && r.N >= 256 && t256 >= 64) large_tiles += t256;
+      elems += (int64_t)r.M * r.N;
+      tiles256 += ((r.M + 255) / 256) * ((r.N + 255) / 256);
+      tiles128 += ((r.M + 127) / 128) * ((r.N + 255) / 256);
+      max_m = std::max(max_m, r.M);
+      max_n = std::max(max_n, r.N);
     }
-    const bool split = large_tiles >= CUS && large_tiles % CUS == 0;
+    int tile_rows = gemm_big_tile_rows(max_m, max_n, elems, tiles256, tiles128);
+    if (tile_rows == 0) tile_rows = 64;
+    int blocks = 0;
     for (auto &r : dw_group) {
-      const int t256 = ((r.M + 255) / 256) * ((r.N + 255) / 256);
-      (split && r.M >= 256 && r.N >= 256 && t256 >= 64 ? large : rest).push_back(r);
+      r.blk_begin = blocks;
+      r.split_k = 1;
+      blocks += gemm_big_tiles_for(tile_rows, r.M, r.N, &r.tiles_n);
     }
-    auto launch_group = [&](std::vector<GemmProb> &g, int forced_tile) {
-      if (g.empty()) return;
-      int64_t elems = 0;
-      int tiles256 = 0, tiles128 = 0, max_m = 0, max_n = 0;
-      for (auto &r : g) {
-        elems += (int64_t)r.M * r.N;
-        tiles256 += ((r.M + 255) / 256) * ((r.N + 255) / 256);
-        tiles128 += ((r.M + 127) / 128) * ((r.N + 255) / 256);
-        max_m = std::max(max_m, r.M);
-        max_n = std::max(max_n, r.N);
-      }
-      int tile_rows = forced_tile ? forced_tile : gemm_big_tile_rows(max_m, max_n, elems, tiles256, tiles128);
-      if (tile_rows == 0) tile_rows = 64;
-      int blocks = 0;
-      for (auto &r : g) {
-        r.blk_begin = blocks;
-        r.split_k = 1;
-        blocks += gemm_big_tiles_for(tile_rows, r.M, r.N, &r.tiles_n);
-      }
-      const bool direct = false;    // contraction-major operands: staged loads are faster (see emit_gemms)
-      Step &sg = add_step(K_GEMM_DW_GROUP, push_table(g), (int)g.size(), blocks);
-      sg.a0 = direct ? 1 : 0;
-      sg.a2 = tile_rows;
-    };
-    launch_group(large, 256);
-    launch_group(rest, 0);
+    const bool direct = false;    // contraction-major operands: staged loads are faster (see emit_gemms)
+    Step &sg = add_step(K_GEMM_DW_GROUP, push_table(dw_group), (int)dw_group.size(), blocks);
+    sg.a0 = direct ? 1 : 0;
+    sg.a2 = tile_rows;
   }
   steps = &pl.bwd;
 }

@@ -558,3 +558,16 @@ def test_full_size_single_micro_batch_workloads_as_the_benchmark_runs_them(make)
     ora_stage, ora_res = run_oracle(wl)
     _, res, grads = _run(wl, 1, 1, False, reps=2, flags=B.FLAG_GROUPED_DW)
     compare(wl, res, grads, ora_stage, ora_res, label=f"{wl.name} full size, grouped")
+
+
+@pytest.mark.parametrize("make", [W.paper_candle, W.paper_mmt, W.paper_dlrm], ids=["paper_candle", "paper_mmt", "paper_dlrm"])
+def test_paper_model_shapes_full_size_as_the_benchmark_runs_them(make):
+    # the paper's own model shapes (appendix "DNN Model Configurations") at the sizes bench.py --config paper_* times
+    # them: CANDLE-Uno 7 branches x 4 layers of 4096 at 64 rows, the multi-modal transformer 4 branches x 8 layers at
+    # 2 x 256 tokens, DLRM 7 dense + 7 sparse branches (bags of 100 concatenated, 10^6-row tables) at 256 rows; one
+    # micro-batch per step, serial, every weight gradient in one launch; the oracle runs once per case
+    wl = make()
+    print(f"[case] {wl.name} full size b={wl.micro_batch}, grouped weight gradients, serial", flush=True)
+    ora_stage, ora_res = run_oracle(wl)
+    _, res, grads = _run(wl, 1, 1, False, reps=2, flags=B.FLAG_GROUPED_DW)
+    compare(wl, res, grads, ora_stage, ora_res, label=f"{wl.name} full size, grouped")

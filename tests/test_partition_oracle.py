@@ -134,3 +134,76 @@ def test_returned_stage_graphs_satisfy_c1_c2_c3_on_random_series_parallel_models
                 assert (stage_of[u], stage_of[v]) in ev["edges"]
         assert ev["tps"] == max(sum(t[o] for o in st) / d for st, d in plan)     # no synchronisation cost in this test
         assert ev["tps"] <= sum(t) + 1e-12                            # never worse than one device running everything
+
+
+# ---- per-stage schedule configurations (the configuration loop of Alg. 1) -----------------------------
+
+def _chain3():
+    # three operators in a chain whose smallest efficient micro-batch sizes are 1, 2 and 4 (section 6, worked example)
+    edges = [(0, 1), (1, 2)]
+    tb = [[1.0, 1.0, 1.0], [2.0, 1.0, 1.0], [4.0, 2.0, 1.0]]      # seconds per sample at micro-batch sizes 1, 2, 4
+    # parameters whose synchronisation makes data parallelism dear, so that the devices go to separate stages
+    return edges, tb, [10.0] * 3, [1.0, 0.0, 0.0]
+
+
+def test_worked_example_of_section_6_through_the_partition_definition():
+    edges, tb, w, a = _chain3()
+    # one micro-batch size (4, the only one at which every stage is efficient) and 1F1B: 12 in-flight samples at stage 1
+    kw = dict(sync_per_byte=1.0, mini_batch=1)
+    plan, cfg, ev = P.best_stage_graph_cfg(3, edges, [[r[2]] for r in tb], w, a, 3, [4], [1], memory=100.0, **kw)
+    assert len(plan) == 3 and ev["tps"] == 1.0 and ev["in_flight"] == [12, 8, 4]
+    # per-stage sizes and schedules: the same bottleneck with 10 in-flight samples at stage 1 (sizes 1, 2, 4)
+    plan, cfg, ev = P.best_stage_graph_cfg(3, edges, tb, w, a, 3, [1, 2, 4], [1, 2, 4], memory=100.0, **kw)
+    assert ev["tps"] == 1.0 and ev["source_in_flight"] == 10 and ev["in_flight"][1:] == [8, 4]
+    sizes = [[1, 2, 4][cfg[s][0]] for s in range(3)]
+    assert sizes == [1, 2, 4]
+    # a budget between the two: the uniform configuration no longer reaches the bottleneck of 1, the per-stage one does
+    # (stage 1 holds its 10 parameter bytes and one byte per in-flight sample)
+    uni = P.best_stage_graph_cfg(3, edges, [[r[2]] for r in tb], w, a, 3, [4], [1], memory=20.5, **kw)
+    per = P.best_stage_graph_cfg(3, edges, tb, w, a, 3, [1, 2, 4], [1, 2, 4], memory=20.5, **kw)
+    assert per[2]["tps"] == 1.0 and (uni is None or uni[2]["tps"] > 1.0)
+
+
+def test_configurations_reduce_to_the_default_search_with_one_candidate():
+    import random
+    rng = random.Random(3)
+    for _ in range(30):
+        n = rng.randint(2, 6)
+        edges = [(u, v) for u in range(n) for v in range(u + 1, n) if rng.random() < 0.45]
+        t = [rng.uniform(0.5, 2.0) for _ in range(n)]
+        w = [rng.uniform(0.0, 1.0) for _ in range(n)]
+        a = [rng.uniform(0.0, 1.0) for _ in range(n)]
+        d, mem = rng.randint(1, 4), rng.uniform(3.0, 12.0)
+        old = P.best_stage_graph(n, edges, t, w, a, d, 2, mem, 0.01, 8)
+        new = P.best_stage_graph_cfg(n, edges, [[v] for v in t], w, a, d, [2], [1], mem, None, 0.01, 8)
+        assert (old is None) == (new is None)
+        if old:
+            assert old[1]["tps"] == new[2]["tps"] and old[1]["source_in_flight"] == new[2]["source_in_flight"]
+
+
+def test_transfer_cost_is_affine_per_cut_edge_and_per_micro_batch():
+    edges = [(0, 1), (0, 2), (1, 3), (2, 3)]
+    x = [8.0, 8.0, 4.0, 4.0]
+    ops = frozenset({1})
+    assert P.cut_of(ops, edges, x) == (2, 12.0)
+    tb = [[1.0, 1.0]] * 4
+    got = P.stage_time_cfg(ops, 1, 1, tb, [0.0] * 4, [2, 8], edges, x, 0.0, 1, link_latency=0.5, link_spb=0.25)
+    assert got == 1.0 + 2 * 0.5 / 8 + 12.0 * 0.25
+    # a dear link keeps a chain in one stage although two devices are there ... as far as C3 allows: both devices
+    # must be used, so the two-stage cut is compared with the data-parallel single stage
+    plan, cfg, ev = P.best_stage_graph_cfg(2, [(0, 1)], [[1.0], [1.0]], [0.0, 0.0], [0.0, 0.0], 2, [1], [1], 100.0,
+                                           x=[1.0], link_latency=0.0, link_spb=5.0)
+    assert len(plan) == 1 and ev["tps"] == 1.0
+    plan, cfg, ev = P.best_stage_graph_cfg(2, [(0, 1)], [[1.0], [1.0]], [4.0, 4.0], [0.0, 0.0], 2, [1], [1], 100.0,
+                                           x=[1.0], sync_per_byte=1.0, mini_batch=1, link_latency=0.0, link_spb=0.1)
+    assert len(plan) == 2 and ev["tps"] == 1.1
+
+
+def test_first_stages_of_a_parallel_composition_share_one_configuration():
+    # two branches between a stem and a merge; one branch prefers small, the other large micro-batches
+    edges = [(0, 1), (0, 2), (1, 3), (2, 3)]
+    tb = [[1.0, 1.0], [1.0, 3.0], [3.0, 1.0], [1.0, 1.0]]
+    plan, cfg, ev = P.best_stage_graph_cfg(4, edges, tb, [5.0] * 4, [0.0] * 4, 4, [1, 4], [1], 100.0, sync_per_byte=1.0)
+    stages = {min(ops): cfg[s] for s, (ops, _) in enumerate(plan)}
+    assert len(plan) == 4 and stages[1] == stages[2]
+    assert ev["tps"] == 3.0        # with separate configurations it would be 1.0: the shared one costs one branch
