@@ -335,6 +335,31 @@ gpp_status_t gpp_partition(int32_t n_ops, int32_t n_edges, const int32_t *edge_f
                            int32_t *stage_of_op, int32_t *n_stages, int32_t *stage_devices, int64_t *stage_in_flight,
                            double *bottleneck, int64_t *dp_states);
 
+/* gpp_partition with the configuration loop of Alg. 1 (section 5: SearchStageGraph enumerates schedule configurations
+ * c = (i, b, k); the series case of DP enumerates the configuration c_m of the stage(s) in the middle): every stage
+ * takes a micro-batch size out of b_values and a kFkB group size out of k_values, the in-flight samples between two
+ * stages follow from both stages' (b, k) by ComputeInFlight, and tensors between stages are charged.
+ *   b_values[n_b], k_values[n_k]   HOST, the candidates (the paper considers powers of two); 1 to 64 of each
+ *   t[o * n_b + j]   HOST, seconds per sample of operator o on one device at micro-batch size b_values[j] (the paper
+ *                    profiles operators; efficiency rises with the micro-batch size, section 2)
+ *   x[e]             HOST or NULL, bytes per sample on operator edge e
+ *   link_latency, link_seconds_per_byte   the paper's affine communication model: per micro-batch, a stage pays
+ *                    link_latency + bytes * link_seconds_per_byte for every operator edge with exactly one end inside
+ *                    it (activations arriving, gradients coming back), i.e. per sample
+ *                    cut edges * link_latency / b + cut bytes per sample * link_seconds_per_byte
+ *   stage_b, stage_k room for n_ops entries each (may be NULL): the configuration chosen for every stage
+ * Everything else as in gpp_partition.  Readings: both halves of a parallel decomposition receive the same c_f
+ * (Alg. 1), so the stages that come first inside a parallel composition share one configuration; the configuration
+ * that SearchStageGraph enumerates is that of the first stage(s) of the whole graph, the dummy one stands for the
+ * successor the last stage does not have; b and k enter memory only through the in-flight samples. */
+gpp_status_t gpp_partition_search(int32_t n_ops, int32_t n_edges, const int32_t *edge_from, const int32_t *edge_to,
+                                  int32_t n_b, const int64_t *b_values, const double *t, const double *w, const double *a,
+                                  int32_t n_k, const int64_t *k_values, const double *x, double link_latency,
+                                  double link_seconds_per_byte, int32_t n_devices, double memory_bytes,
+                                  double sync_seconds_per_byte, int64_t mini_batch, double eps_rel, int32_t *stage_of_op,
+                                  int32_t *n_stages, int32_t *stage_devices, int64_t *stage_in_flight, int64_t *stage_b,
+                                  int64_t *stage_k, double *bottleneck, int64_t *dp_states);
+
 /* ---- Several stages of a stage graph G_S on one GPU (paper section 3: G_S = (V_S, E_S); an edge (S_x, S_y)
  * orders the two stages for every micro-batch, C2; stages without a path between them run concurrently,
  * section 2).  Each stage keeps its own task list (gpp_schedule_tasks for its (i, k)) and its own pair of

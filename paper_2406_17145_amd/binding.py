@@ -61,7 +61,7 @@ EXPORTS = [
     "gpp_profile_tag_name", "gpp_compute_in_flight", "gpp_assign_schedules", "gpp_schedule_tasks",
     "gpp_stage_run_schedule", "gpp_stage_memory", "gpp_stage_backward_weights", "gpp_stage_info", "gpp_stage_io_info",
     "gpp_stage_run_schedule_lanes", "gpp_stage_lanes", "gpp_stage_group_launches",
-    "gpp_partition", "gpp_pipeline_workspace_bytes", "gpp_pipeline_create", "gpp_pipeline_run", "gpp_pipeline_destroy",
+    "gpp_partition", "gpp_partition_search", "gpp_pipeline_workspace_bytes", "gpp_pipeline_create", "gpp_pipeline_run", "gpp_pipeline_destroy",
 ]
 GPP_PROFILE_TAGS = 32
 
@@ -404,6 +404,37 @@ def gpp_partition(n_ops, edges, t, w, a, n_devices, b, memory_bytes, sync_second
     if ns.value == 0:
         return None
     return dict(stage_of_op=list(stage_of), devices=list(dev)[:ns.value], in_flight=list(inf)[:ns.value],
+                bottleneck=tps.value, dp_states=states.value)
+
+
+def gpp_partition_search(n_ops, edges, b_values, t, w, a, k_values, n_devices, memory_bytes, x=None, link_latency=0.0,
+                         link_seconds_per_byte=0.0, sync_seconds_per_byte=0.0, mini_batch=1, eps_rel=1e-9):
+    """t[o][j]: seconds per sample of operator o at micro-batch size b_values[j]; x[e]: bytes per sample on edge e.
+    Returns None when nothing fits, else a dict as gpp_partition plus b and k per stage."""
+    lib = load()
+    i32, i64, dp = C.c_int32, C.c_int64, C.POINTER(C.c_double)
+    lib.gpp_partition_search.restype = i32
+    lib.gpp_partition_search.argtypes = [i32, i32, C.POINTER(i32), C.POINTER(i32), i32, C.POINTER(i64), dp, dp, dp, i32, C.POINTER(i64),
+                                         dp, C.c_double, C.c_double, i32, C.c_double, C.c_double, i64, C.c_double, C.POINTER(i32),
+                                         C.POINTER(i32), C.POINTER(i32), C.POINTER(i64), C.POINTER(i64), C.POINTER(i64), dp,
+                                         C.POINTER(i64)]
+    ne, nb, nk = len(edges), len(b_values), len(k_values)
+    ef = (i32 * max(1, ne))(*[e[0] for e in edges])
+    et = (i32 * max(1, ne))(*[e[1] for e in edges])
+    flat = [float(t[o][j]) for o in range(n_ops) for j in range(nb)]
+    dbl = C.c_double * n_ops
+    stage_of, ns = (i32 * n_ops)(), i32()
+    dev, inf, sb, sk = (i32 * n_ops)(), (i64 * n_ops)(), (i64 * n_ops)(), (i64 * n_ops)()
+    tps, states = C.c_double(), i64()
+    xs = None if x is None else (C.c_double * max(1, ne))(*x)
+    _check(lib.gpp_partition_search(n_ops, ne, ef, et, nb, (i64 * nb)(*b_values), (C.c_double * len(flat))(*flat), dbl(*w), dbl(*a),
+                                    nk, (i64 * nk)(*k_values), xs, link_latency, link_seconds_per_byte, n_devices, memory_bytes,
+                                    sync_seconds_per_byte, mini_batch, eps_rel, stage_of, C.byref(ns), dev, inf, sb, sk,
+                                    C.byref(tps), C.byref(states)))
+    if ns.value == 0:
+        return None
+    n = ns.value
+    return dict(stage_of_op=list(stage_of), devices=list(dev)[:n], in_flight=list(inf)[:n], b=list(sb)[:n], k=list(sk)[:n],
                 bottleneck=tps.value, dp_states=states.value)
 
 

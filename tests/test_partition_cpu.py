@@ -123,3 +123,64 @@ def test_dp_states_stay_far_below_the_number_of_stage_graphs():
     got = B.gpp_partition(op, edges, [1.0 + (i % 3) for i in range(op)], [1.0] * op, [1.0] * op, 16, 4, BIG, 0.01, 64, 1e-6)
     assert got is not None and sum(got["devices"]) == 16
     assert got["dp_states"] < 2_000_000
+
+
+# ---- the configuration loop of Alg. 1: per-stage micro-batch sizes and kFkB group sizes, transfer cost -----------
+
+def _check_cfg(n, edges, tb, w, a, D, bs, ks, mem, x, lat, spb, sync, mini):
+    want = P.best_stage_graph_cfg(n, edges, tb, w, a, D, bs, ks, mem, x, sync, mini, lat, spb)
+    got = B.gpp_partition_search(n, edges, bs, tb, w, a, ks, D, mem, x, lat, spb, sync, mini, 1e-9)
+    assert (want is None) == (got is None), (n, edges, tb, w, a, D, mem)
+    if want is None:
+        return None
+    _, _, ev = want
+    assert got["bottleneck"] == pytest.approx(ev["tps"], rel=1e-7), (n, edges, tb, w, a, D, mem, got, ev)
+    ns = len(got["devices"])
+    plan = tuple((frozenset(o for o in range(n) if got["stage_of_op"][o] == s), got["devices"][s]) for s in range(ns))
+    assert all(st for st, _ in plan) and sum(d for _, d in plan) == D and all(d >= 1 for _, d in plan)
+    cfg = tuple((bs.index(got["b"][s]), ks.index(got["k"][s])) for s in range(ns))
+    par_sets = P._parallel_sets(P.sp_tree(n, edges), [])
+    mine = P.evaluate_cfg(plan, cfg, n, edges, tb, w, a, bs, ks, mem, par_sets, x, sync, mini, lat, spb)
+    assert mine is not None, "the returned stage graph breaks C1, the memory budget or the shared configuration"
+    assert mine["tps"] == pytest.approx(got["bottleneck"], rel=1e-12)
+    assert mine["in_flight"] == got["in_flight"]
+    assert mine["source_in_flight"] == ev["source_in_flight"]
+    return got
+
+
+def test_configuration_search_finds_the_worked_example_of_section_6():
+    edges = [(0, 1), (1, 2)]
+    tb = [[1.0, 1.0, 1.0], [2.0, 1.0, 1.0], [4.0, 2.0, 1.0]]
+    got = _check_cfg(3, edges, tb, [10.0] * 3, [1.0, 0.0, 0.0], 3, [1, 2, 4], [1, 2, 4], 20.5, None, 0.0, 0.0, 1.0, 1)
+    assert got["b"] == [1, 2, 4] and got["in_flight"] == [10, 8, 4] and got["bottleneck"] == pytest.approx(1.0)
+    uni = B.gpp_partition_search(3, edges, [4], [[r[2]] for r in tb], [10.0] * 3, [1.0, 0.0, 0.0], [1], 3, 100.0,
+                                 sync_seconds_per_byte=1.0)
+    assert uni["in_flight"] == [12, 8, 4]
+
+
+def test_configuration_search_matches_the_exhaustive_oracle_on_random_models():
+    r = random.Random(11)
+    done = 0
+    for _ in range(120):
+        n, edges = _model(r)
+        if n > 6:
+            continue
+        bs, ks = r.choice([[1, 2], [2, 4], [1, 4]]), r.choice([[1], [1, 2], [1, 4]])
+        # faster per sample at the larger micro-batch size, by a different amount per operator
+        tb = [[v, v * r.uniform(0.4, 1.0)] for v in (r.uniform(0.5, 2.0) for _ in range(n))]
+        w = [r.uniform(0.0, 2.0) for _ in range(n)]
+        a = [r.uniform(0.0, 1.0) for _ in range(n)]
+        x = [r.uniform(0.0, 1.0) for _ in edges]
+        D = r.randrange(1, 4)
+        mem = r.choice([BIG, r.uniform(2.0, 10.0)])
+        lat, spb = r.choice([(0.0, 0.0), (r.uniform(0.0, 0.5), r.uniform(0.0, 0.5))])
+        _check_cfg(n, edges, tb, w, a, D, bs, ks, mem, x, lat, spb, r.choice([0.0, 0.3]), r.choice([1, 8]))
+        done += 1
+    assert done >= 60
+
+
+def test_configuration_search_rejects_bad_arguments():
+    with pytest.raises(B.GppError):
+        B.gpp_partition_search(2, [(0, 1)], [0], [[1.0], [1.0]], [0.0] * 2, [0.0] * 2, [1], 1, 1.0)
+    with pytest.raises(B.GppError):
+        B.gpp_partition_search(2, [(0, 1)], [1], [[1.0], [1.0]], [0.0] * 2, [0.0] * 2, [1], 1, 1.0, x=[-1.0], link_seconds_per_byte=1.0)
