@@ -57,7 +57,7 @@ typedef enum {
   GPP_ERR_UNSUPPORTED = 4, /* valid graph this library has no kernel for (e.g. dtype mix) */
   GPP_ERR_WORKSPACE = 5,   /* workspace too small or misaligned */
   GPP_ERR_ORDER = 6,       /* ordering condition C4 violated, or slot busy / free */
-  GPP_ERR_INDEX = 7,       /* an embedding index or offset was out of range (see gpp_stage_sync_status) */
+  GPP_ERR_INDEX = 7,       /* an embedding index, a bag offset or a class label was out of range (see gpp_stage_sync_status) */
   GPP_ERR_DEVICE = 8       /* a HIP call failed, see gpp_last_error */
 } gpp_status_t;
 
@@ -228,7 +228,9 @@ gpp_status_t gpp_stage_backward_weights(gpp_stage_t *stage, void *hip_stream);
 gpp_status_t gpp_stage_grad_reset(gpp_stage_t *stage, void *hip_stream);
 
 /* Waits for the stream and reports GPP_ERR_INDEX if any kernel since the last call met an embedding
- * index or offset out of range (such entries are skipped, never dereferenced). */
+ * index out of range, bag offsets that break their contract (first offset not 0, decreasing, beyond the
+ * capacity) or a class label outside [0, classes) (such entries are skipped, never dereferenced; the
+ * results of that micro-batch are then not those of the operator graph). */
 gpp_status_t gpp_stage_sync_status(gpp_stage_t *stage, void *hip_stream);
 
 gpp_status_t gpp_stage_destroy(gpp_stage_t *stage);

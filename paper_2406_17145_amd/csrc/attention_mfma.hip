@@ -29,7 +29,13 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int DH = 64;            // head dimension of the MFMA path
-constexpr int LDS_ST = DH + 8;    // LDS row stride (elements)
+constexpr int LDS_ST = DH + 8;    // LDS row stride (elements) of tiles read along their rows: 144-byte rows put sixteen
+                                  // consecutive rows' 16-byte pieces into sixteen different groups of four banks
+constexpr int LDS_TR = DH + 32;   // row stride of tiles read with the transposing read: that read serves 32 lanes per
+                                  // cycle, 64 bytes in each of four consecutive rows; 192-byte rows put the four rows into
+                                  // the four quarters of the 64 banks (with 144-byte rows two of them shared banks:
+                                  // 0.7 conflicts per LDS cycle).  No stride serves both reads, so a tile that is read
+                                  // both ways is kept twice
 constexpr int QT = 128;           // rows (queries or keys) owned by a workgroup: 4 waves x 32
 constexpr int KT = 32;            // rows of the streamed tile
 
@@ -78,15 +84,15 @@ __device__ __forceinline__ bf16x8 row_frag(const uint16_t *lds, int s) {
   const int l = threadIdx.x & 63;
   return *(const bf16x8 *)(lds + (l & 31) * LDS_ST + 16 * s + 8 * (l >> 5));
 }
-// transposed operand from an LDS tile [rows][LDS_ST]: lane takes column col0 + (l % 32) and rows
+// transposed operand from an LDS tile [rows][LDS_TR]: lane takes column col0 + (l % 32) and rows
 // 16 c + 4 (l / 32) + {0..3} and + 8 (matching accumulator registers 8c .. 8c+7 of a score tile)
 __device__ __forceinline__ bf16x8 tr_frag(const uint16_t *lds, int col0, int c) {
   const int l = threadIdx.x & 63;
   const int blk = l >> 4, q = l & 15;
-  const uint16_t *p = lds + (16 * c + 4 * (blk >> 1) + (q >> 2)) * LDS_ST + col0 + 16 * (blk & 1) + 4 * (q & 3);
+  const uint16_t *p = lds + (16 * c + 4 * (blk >> 1) + (q >> 2)) * LDS_TR + col0 + 16 * (blk & 1) + 4 * (q & 3);
   typedef __attribute__((address_space(3))) s16x4 lds_v4;
   s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)p);
-  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(p + 8 * LDS_ST));
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4 *)(p + 8 * LDS_TR));
   s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(bf16x8, v);
 }
@@ -109,10 +115,11 @@ __device__ __forceinline__ int acc_row(int r) { return 8 * (r >> 2) + 4 * ((thre
 struct Stream2 {
   u32x4 a, b;
 };
-__device__ __forceinline__ void stream_store(const Stream2 &t, uint16_t *la, uint16_t *lb) {
+// one 16-byte chunk per thread into a tile with row stride ST
+template <int ST>
+__device__ __forceinline__ void chunk_store(const u32x4 &v, uint16_t *tile) {
   const int c = threadIdx.x;
-  *(u32x4 *)(la + (c >> 3) * LDS_ST + (c & 7) * 8) = t.a;
-  *(u32x4 *)(lb + (c >> 3) * LDS_ST + (c & 7) * 8) = t.b;
+  *(u32x4 *)(tile + (c >> 3) * ST + (c & 7) * 8) = v;
 }
 
 // writes a wave's transposed 64 x 32 accumulator pair (rows = dh, lane column = its row of the block)
@@ -136,7 +143,7 @@ __device__ __forceinline__ void store_transposed(uint16_t *stage, const f32x16 (
 // ======================================================================= forward
 __global__ __launch_bounds__(256) void k_attn_fwd_mfma(const AttnProb *__restrict__ probs, int n) {
   __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][KT * LDS_ST];
-  __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][KT * LDS_ST];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][KT * LDS_TR];
   __shared__ __attribute__((aligned(16))) uint16_t stage[QT * LDS_ST];
   const int pi = find_prob(probs, n, blockIdx.x);
   const AttnProb p = probs[pi];
@@ -161,7 +168,8 @@ __global__ __launch_bounds__(256) void k_attn_fwd_mfma(const AttnProb *__restric
     return s;
   };
   Stream2 nxt = fetch(0);
-  stream_store(nxt, lds_k[0], lds_v[0]);
+  chunk_store<LDS_ST>(nxt.a, lds_k[0]);
+  chunk_store<LDS_TR>(nxt.b, lds_v[0]);
   __syncthreads();
   for (int t = 0; t < nt; ++t) {
     const int cur = t & 1;
@@ -206,7 +214,10 @@ __global__ __launch_bounds__(256) void k_attn_fwd_mfma(const AttnProb *__restric
 #pragma unroll
       for (int dd = 0; dd < 2; ++dd) o[dd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(lds_v[cur], 32 * dd, c), pf, o[dd], 0, 0, 0);
     }
-    if (t + 1 < nt) stream_store(nxt, lds_k[cur ^ 1], lds_v[cur ^ 1]);
+    if (t + 1 < nt) {
+      chunk_store<LDS_ST>(nxt.a, lds_k[cur ^ 1]);
+      chunk_store<LDS_TR>(nxt.b, lds_v[cur ^ 1]);
+    }
     __syncthreads();
   }
   lsum += __shfl_xor(lsum, 32, 64);
@@ -216,7 +227,8 @@ __global__ __launch_bounds__(256) void k_attn_fwd_mfma(const AttnProb *__restric
 
 // ======================================================================= backward: dQ (and delta)
 __global__ __launch_bounds__(256) void k_attn_bwd_dq_mfma(const AttnProb *__restrict__ probs, int n) {
-  __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][KT * LDS_ST];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][KT * LDS_ST];    // K read along its rows (scores)
+  __shared__ __attribute__((aligned(16))) uint16_t lds_kt[2][KT * LDS_TR];   // K read transposed (dQ)
   __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][KT * LDS_ST];
   __shared__ __attribute__((aligned(16))) uint16_t stage[QT * LDS_ST];
   const int pi = find_prob(probs, n, blockIdx.x);
@@ -256,7 +268,12 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dq_mfma(const AttnProb *__rest
     return s;
   };
   Stream2 nxt = fetch(0);
-  stream_store(nxt, lds_k[0], lds_v[0]);
+  auto put = [&](const Stream2 &x, int buf) {
+    chunk_store<LDS_ST>(x.a, lds_k[buf]);
+    chunk_store<LDS_TR>(x.a, lds_kt[buf]);
+    chunk_store<LDS_ST>(x.b, lds_v[buf]);
+  };
+  put(nxt, 0);
   __syncthreads();
   for (int t = 0; t < nt; ++t) {
     const int cur = t & 1;
@@ -278,9 +295,9 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dq_mfma(const AttnProb *__rest
     for (int c = 0; c < 2; ++c) {
       const bf16x8 sf = pack8(st, c);
 #pragma unroll
-      for (int dd = 0; dd < 2; ++dd) dq[dd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(lds_k[cur], 32 * dd, c), sf, dq[dd], 0, 0, 0);
+      for (int dd = 0; dd < 2; ++dd) dq[dd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(lds_kt[cur], 32 * dd, c), sf, dq[dd], 0, 0, 0);
     }
-    if (t + 1 < nt) stream_store(nxt, lds_k[cur ^ 1], lds_v[cur ^ 1]);
+    if (t + 1 < nt) put(nxt, cur ^ 1);
     __syncthreads();
   }
   store_transposed(stage, dq, scale, p.out, p.ld_out, first, w.r0, p.seq, w.h * DH);
@@ -288,8 +305,8 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dq_mfma(const AttnProb *__rest
 
 // ======================================================================= backward: dK, dV
 __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(const AttnProb *__restrict__ probs, int n) {
-  __shared__ __attribute__((aligned(16))) uint16_t lds_q[2][KT * LDS_ST];
-  __shared__ __attribute__((aligned(16))) uint16_t lds_g[2][KT * LDS_ST];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_q[2][KT * LDS_ST], lds_g[2][KT * LDS_ST];     // read along rows
+  __shared__ __attribute__((aligned(16))) uint16_t lds_qt[2][KT * LDS_TR], lds_gt[2][KT * LDS_TR];   // read transposed
   __shared__ float lds_lse[2][KT], lds_delta[2][KT];
   const int pi = find_prob(probs, n, blockIdx.x);
   const AttnProb p = probs[pi];
@@ -321,7 +338,10 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(const AttnProb *__res
     return s;
   };
   auto put = [&](const Stream2 &s, int buf) {
-    stream_store(s, lds_q[buf], lds_g[buf]);
+    chunk_store<LDS_ST>(s.a, lds_q[buf]);
+    chunk_store<LDS_TR>(s.a, lds_qt[buf]);
+    chunk_store<LDS_ST>(s.b, lds_g[buf]);
+    chunk_store<LDS_TR>(s.b, lds_gt[buf]);
     if (threadIdx.x < KT) {
       lds_lse[buf][threadIdx.x] = n_lse;
       lds_delta[buf][threadIdx.x] = n_delta;
@@ -353,8 +373,8 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(const AttnProb *__res
       const bf16x8 pf = pack8(st, c), sf = pack8(dp, c);
 #pragma unroll
       for (int dd = 0; dd < 2; ++dd) {
-        dv[dd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, tr_frag(lds_g[cur], 32 * dd, c), dv[dd], 0, 0, 0);
-        dk[dd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sf, tr_frag(lds_q[cur], 32 * dd, c), dk[dd], 0, 0, 0);
+        dv[dd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, tr_frag(lds_gt[cur], 32 * dd, c), dv[dd], 0, 0, 0);
+        dk[dd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sf, tr_frag(lds_qt[cur], 32 * dd, c), dk[dd], 0, 0, 0);
       }
     }
     if (t + 1 < nt) put(nxt, cur ^ 1);

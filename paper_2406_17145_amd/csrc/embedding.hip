@@ -70,7 +70,7 @@ template <bool VEC>
 __device__ __forceinline__ void emb_fwd_concat_body(const EmbProb &p, int bag, StageFlags *flags) {
   const int lane = threadIdx.x & 63;
   int lo = p.offsets[bag], hi = p.offsets[bag + 1];
-  bool bad = lo < 0 || hi < lo || hi > p.capacity || hi - lo > p.bag_size;
+  bool bad = lo < 0 || hi < lo || hi > p.capacity || hi - lo > p.bag_size || (bag == 0 && lo != 0);
   lo = max(0, min(lo, p.capacity));
   hi = max(lo, min(min(hi, p.capacity), lo + p.bag_size));
   const int len = hi - lo;
@@ -131,7 +131,7 @@ __global__ __launch_bounds__(256) void k_emb_fwd(const EmbProb *__restrict__ pro
   if (bag >= p.n_bags) return;
   if (p.concat) return emb_fwd_concat_body<false>(p, bag, flags);
   int lo = p.offsets[bag], hi = p.offsets[bag + 1];
-  bool bad = lo < 0 || hi < lo || hi > p.capacity;
+  bool bad = lo < 0 || hi < lo || hi > p.capacity || (bag == 0 && lo != 0);   // offsets start at 0 and do not decrease
   lo = max(0, min(lo, p.capacity));
   hi = max(lo, min(hi, p.capacity));
   float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -196,7 +196,7 @@ __global__ __launch_bounds__(256) void k_emb_fwd_vec(const EmbProb *__restrict__
   if (bag >= p.n_bags) return;
   if (p.concat) return emb_fwd_concat_body<true>(p, bag, flags);
   int lo = p.offsets[bag], hi = p.offsets[bag + 1];
-  bool bad = lo < 0 || hi < lo || hi > p.capacity;
+  bool bad = lo < 0 || hi < lo || hi > p.capacity || (bag == 0 && lo != 0);   // offsets start at 0 and do not decrease
   lo = max(0, min(lo, p.capacity));
   hi = max(lo, min(hi, p.capacity));
   const int lpr = lanes_per_row(p.dim), rpi = 64 / lpr;
@@ -249,7 +249,7 @@ void launch_emb_fwd(const EmbProb *probs, int n, int total_blocks, int vec, int 
 
 // ------------------------------------------------------------------ stable radix sort by row
 // LSD radix sort of (row, position) with RADIX_BITS-bit digits.  A workgroup owns SORT_CHUNK
-// consecutive keys, wave w of it the sub-range [512 w, 512 w + 512) in rounds of 64, so "key order"
+// consecutive keys, wave w of it the sub-range [256 w, 256 w + 256) in rounds of 64, so "key order"
 // is wave-major and the scatter can rank its keys with three workgroup barriers in all: the waves
 // count their digits privately, one pass turns the counts into per-wave start offsets (global
 // base of the digit + the workgroups before this one + the waves before this one), then every wave
@@ -382,10 +382,14 @@ __global__ __launch_bounds__(256) void k_sort_scatter(const EmbProb *__restrict_
     for (int r = 0; r < SORT_ROUNDS; ++r) {
       const int row = p.indices[pos[r]];
       const int b = p.bag_of[pos[r]];
+      // a position that no bag of this micro-batch covers (offsets that break the contract; the forward pass has
+      // flagged them) still holds what an earlier call wrote: only a real bag id is ever used as an index
+      const bool b_ok = (unsigned)b < (unsigned)p.n_bags;
       // what the sums gather by: the bag, or, for concatenated bags, the slot of the position in the
       // gradient seen as [bags * bag_size, dim]
-      const int piece = p.concat ? b * p.bag_size + (pos[r] - p.offsets[b]) : b;
-      bag[r] = (row >= 0 && row < p.num_rows) ? piece : -1;
+      const int slot_in_bag = p.concat ? pos[r] - p.offsets[b_ok ? b : 0] : 0;
+      const int piece = p.concat ? b * p.bag_size + slot_in_bag : b;
+      bag[r] = (b_ok && row >= 0 && row < p.num_rows && (unsigned)slot_in_bag < (unsigned)max(p.bag_size, 1)) ? piece : -1;
     }
   }
   for (int d = threadIdx.x; d < 4 * RADIX; d += 256) (&off[0][0])[d] = 0;

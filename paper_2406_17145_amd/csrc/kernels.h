@@ -189,7 +189,7 @@ struct ExtPtrs {
 
 // per-stage device flags
 struct StageFlags {
-  int32_t index_error;
+  int32_t index_error;    // an embedding index, a bag offset or a class label was out of range
 };
 
 // ---- launch entry points (defined next to the kernels) -------------------------
@@ -281,11 +281,11 @@ int emb_log_slots();
 // slots <= 0: clear whole tables; otherwise only the rows logged in slots [0, slots)
 void launch_emb_reset(const EmbProb *probs, int n, int max_capacity, int slots, hipStream_t s);
 
-void launch_loss_fwd(const LossProb *probs, int n, int total_blocks, hipStream_t s);
+void launch_loss_fwd(const LossProb *probs, int n, int total_blocks, StageFlags *flags, hipStream_t s);
 int loss_fwd_blocks(const LossProb &p);
 // every loss of the stage and their sum in one single-workgroup launch (rows x cols summed over the
 // records at most loss_small_limit()); a null `out` skips the launch
-void launch_loss_fwd_small(const LossProb *probs, int n, float *out, hipStream_t s);
+void launch_loss_fwd_small(const LossProb *probs, int n, float *out, StageFlags *flags, hipStream_t s);
 int loss_small_limit();
 bool head_loss_supported(int64_t rows, int64_t K);
 bool head_loss_is_tall(int64_t rows, int64_t K);

@@ -624,7 +624,7 @@ __device__ __forceinline__ bool loss_row_vec_ok(const LossProb &p) {
 
 // four rows per workgroup (one wave each); every workgroup writes one partial sum, already scaled
 int loss_fwd_blocks(const LossProb &p) { return (p.rows + 3) / 4; }
-__global__ __launch_bounds__(256) void k_loss_fwd(const LossProb *__restrict__ probs, int n) {
+__global__ __launch_bounds__(256) void k_loss_fwd(const LossProb *__restrict__ probs, int n, StageFlags *flags) {
   __shared__ float red[4];
   const int pi = find_prob(probs, n, blockIdx.x);
   const LossProb p = probs[pi];
@@ -643,6 +643,7 @@ __global__ __launch_bounds__(256) void k_loss_fwd(const LossProb *__restrict__ p
       se = wave_sum(se);
       const int lab = ((const int32_t *)p.target)[(int64_t)r * p.ld_t];
       if (lane == 0 && lab >= 0 && lab < p.cols) acc = (m + __logf(se)) - load_as_f32(p.y, p.y_dtype, yo + lab);
+      if (lane == 0 && (lab < 0 || lab >= p.cols)) flags->index_error = 1;    // a label outside the classes: no loss term, reported
     } else {
       const float *t = (const float *)p.target + (int64_t)r * p.ld_t;
       if (loss_row_vec_ok(p)) {
@@ -696,9 +697,9 @@ __global__ __launch_bounds__(256) void k_loss_fwd(const LossProb *__restrict__ p
   __syncthreads();
   if (threadIdx.x == 0) p.loss[blk] = ((red[0] + red[1]) + (red[2] + red[3])) * p.scale;
 }
-void launch_loss_fwd(const LossProb *probs, int n, int total_blocks, hipStream_t s) {
+void launch_loss_fwd(const LossProb *probs, int n, int total_blocks, StageFlags *flags, hipStream_t s) {
   if (total_blocks <= 0) return;
-  hipLaunchKernelGGL(k_loss_fwd, dim3(total_blocks), dim3(256), 0, s, probs, n);
+  hipLaunchKernelGGL(k_loss_fwd, dim3(total_blocks), dim3(256), 0, s, probs, n, flags);
 }
 
 // Small heads (all of a stage's losses together at most a few tens of thousands of elements): one
@@ -742,7 +743,7 @@ __device__ __forceinline__ float loss_small_elementwise(const LossProb &p) {
   }
   return acc;
 }
-__global__ __launch_bounds__(256) void k_loss_fwd_small(const LossProb *__restrict__ probs, int n, float *out) {
+__global__ __launch_bounds__(256) void k_loss_fwd_small(const LossProb *__restrict__ probs, int n, float *out, StageFlags *flags) {
   __shared__ float red[4];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   float total = 0.0f;
@@ -760,6 +761,7 @@ __global__ __launch_bounds__(256) void k_loss_fwd_small(const LossProb *__restri
         se = wave_sum(se);
         const int lab = ((const int32_t *)p.target)[(int64_t)r * p.ld_t];
         if (lane == 0 && lab >= 0 && lab < p.cols) acc += (m + __logf(se)) - load_as_f32(p.y, p.y_dtype, yo + lab);
+        if (lane == 0 && (lab < 0 || lab >= p.cols)) flags->index_error = 1;
       }
     } else {
       acc = p.y_dtype == DT_BF16 ? loss_small_elementwise<DT_BF16>(p) : loss_small_elementwise<DT_F32>(p);
@@ -772,9 +774,9 @@ __global__ __launch_bounds__(256) void k_loss_fwd_small(const LossProb *__restri
   }
   if (threadIdx.x == 0) out[0] = total;
 }
-void launch_loss_fwd_small(const LossProb *probs, int n, float *out, hipStream_t s) {
+void launch_loss_fwd_small(const LossProb *probs, int n, float *out, StageFlags *flags, hipStream_t s) {
   if (n <= 0 || !out) return;
-  hipLaunchKernelGGL(k_loss_fwd_small, dim3(1), dim3(256), 0, s, probs, n, out);
+  hipLaunchKernelGGL(k_loss_fwd_small, dim3(1), dim3(256), 0, s, probs, n, out, flags);
 }
 
 // One-column head (see HeadProb): per row  y = x . w + b,  the loss term and its gradient dy, and the

@@ -468,7 +468,7 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
         // the launch may also write the loss gradient (per-slot gradient buffers), so it runs without a
         // loss_out too: the sum then goes to the slot's own loss scalars
         float *sink = loss_out ? loss_out : (float *)(st->ws + pl.off_slots + (int64_t)slot * pl.slot_bytes + pl.loss_scalars.off);
-        launch_loss_fwd_small((const LossProb *)tab, sp.n, sink, s);
+        launch_loss_fwd_small((const LossProb *)tab, sp.n, sink, flags, s);
         break;
       }
       case K_COLSUM: launch_colsum((const ColsumProb *)tab, sp.n, sp.blocks, accumulate, s); break;
@@ -507,7 +507,7 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
       }
       case K_INTERACT_FWD: launch_interact_fwd((const InteractProb *)tab, sp.n, sp.blocks, sp.a0, sp.a1, s); break;
       case K_INTERACT_BWD: launch_interact_bwd((const InteractProb *)tab, sp.n, sp.blocks, sp.a0, sp.a1, s); break;
-      case K_LOSS_FWD: launch_loss_fwd((const LossProb *)tab, sp.n, sp.blocks, s); break;
+      case K_LOSS_FWD: launch_loss_fwd((const LossProb *)tab, sp.n, sp.blocks, flags, s); break;
       case K_LOSS_BWD: launch_loss_bwd((const LossProb *)tab, sp.n, sp.blocks, s); break;
       case K_LOSS_SUM:
         if (loss_out) {

@@ -73,7 +73,8 @@ def run_oracle(wl, gouts=None):
 
 # parameter counts of the workloads at the sizes the benchmark runs them: their comparisons are recorded one
 # by one, every other workload of a family (small, ragged, degenerate cases) as one worst-case line
-FULL_SIZE_PARAMETERS = {"tiny_mlp": 33152, "candle_uno": 18825001, "mmt": 105990120, "dlrm": 335168897, "hetero": 89558016}
+FULL_SIZE_PARAMETERS = {"tiny_mlp": 33152, "candle_uno": 18825001, "mmt": 105990120, "dlrm": 335168897, "hetero": 89558016,
+                        "paper_candle": 587325441, "paper_mmt": 408299496, "paper_dlrm": 1235607553}
 _SPREAD_CACHE = {}
 RECORD = {}          # label -> tensor class -> [worst l2, worst max-norm, l2 bar]; conftest writes it out
 
@@ -85,7 +86,9 @@ def _relu_spread(wl):
     key = key + (id(wl.ops),)
     if key not in _SPREAD_CACHE:
         from tests.relu_noise import measure
-        _SPREAD_CACHE[key] = measure(wl)
+        n_par = sum(int(np.asarray(v).size) for p in wl.params.values() for v in p.values())
+        # (a large workload that is not in the stored table: two of the four orders keep the test within minutes)
+        _SPREAD_CACHE[key] = measure(wl) if n_par < 50_000_000 else measure(wl, ("blas", "blk64g"))
     return _SPREAD_CACHE[key]
 
 
@@ -149,7 +152,14 @@ def compare(wl, gpu_res, gpu_grads, ora_stage, ora_res, tol=None, label=""):
                 chk_relu_gin(f"mb{j}.gin{i}", g["gin"][i], ref)
             else:
                 chk(f"mb{j}.gin{i}", g["gin"][i], ref)
+    derived = mode == "bf16" and has_relu and tol == PB.STATED_L2[mode]
     for i, gr in ora_stage.grads.items():
         for k, ref in gr.items():
-            chk(f"op{i}.d{k}", gpu_grads[i][k], ref)
+            bar = PB.relu_dw_bar(_relu_spread(wl), table=(k == "table")) if (derived and k in ("W", "b", "table")) else tol
+            if bar != tol:
+                e2, em = rel_errors(gpu_grads[i][k], ref)
+                note(f"op{i}.d{k}", e2, em, bar)
+                assert e2 <= bar and em <= 5 * bar, f"{label} op{i}.d{k}: l2-rel {e2:.3e} (bar {bar:.3e}) max-rel {em:.3e}"
+            else:
+                chk(f"op{i}.d{k}", gpu_grads[i][k], ref)
     return worst

@@ -89,12 +89,12 @@ def row_errors(got, ref):
 def measure(wl, variants=VARIANTS):
     """Returns a dict: worst l2-relative and max-relative difference of an input-gradient
     tensor between the fp64 oracle and any variant, the largest fraction of sample rows
-    that differ by more than ROW_BAR, the worst weight-gradient difference, and how many
+    that differ by more than ROW_BAR, the worst weight-gradient and table-gradient difference, and how many
     ReLU decisions were opposite / how many pre-activations lie within one bf16 step
     (2^-8 of the layer's r.m.s.) of zero."""
     ref, res = _run(wl, None)
     relu = [i for i, op in enumerate(wl.ops) if op["kind"] == "linear" and op.get("act") == "relu"]
-    out = dict(l2=0.0, max=0.0, rows_over=0.0, dw=0.0, flips=0, decisions=0, near_zero=0, per_variant={})
+    out = dict(l2=0.0, max=0.0, rows_over=0.0, dw=0.0, dt=0.0, flips=0, decisions=0, near_zero=0, per_variant={})
     for (st, _) in res:
         for i in relu:
             z = st.saved[i][1]
@@ -114,7 +114,12 @@ def measure(wl, variants=VARIANTS):
                 flips += int(((sa.saved[i][1] > 0) != (sb.saved[i][1] > 0)).sum())
         dw = max(np.linalg.norm(ref.grads[i][k] - r2.grads[i][k]) / max(np.linalg.norm(ref.grads[i][k]), 1e-300)
                  for i in ref.grads for k in ref.grads[i] if k != "table")
-        out["per_variant"][kind] = dict(l2=l2, max=mx, rows_over=rows, dw=dw, flips=flips)
+        # embedding tables sit in front of the ReLU stack like inputs: their gradients are the (scattered)
+        # gradients of the pooled vectors and carry the same opposite decisions
+        dt = max([np.linalg.norm(ref.grads[i][k] - r2.grads[i][k]) / max(np.linalg.norm(ref.grads[i][k]), 1e-300)
+                  for i in ref.grads for k in ref.grads[i] if k == "table"] or [0.0])
+        out["per_variant"][kind] = dict(l2=l2, max=mx, rows_over=rows, dw=dw, dt=dt, flips=flips)
+        out["dt"] = max(out["dt"], dt)
         out["l2"], out["max"] = max(out["l2"], l2), max(out["max"], mx)
         out["rows_over"], out["dw"] = max(out["rows_over"], rows), max(out["dw"], dw)
         out["flips"] = max(out["flips"], flips)

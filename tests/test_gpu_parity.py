@@ -302,6 +302,36 @@ def test_out_of_range_index_is_reported_not_dereferenced():
     st.close()
 
 
+def test_offsets_that_do_not_start_at_zero_and_labels_outside_the_classes_are_reported():
+    # the bag offsets must start at 0: a first offset of 1 leaves position 0 in no bag.  The forward pass flags it; the
+    # backward pass, which sorts every position below the last offset, must stay inside its buffers (the bag id it finds
+    # for position 0 is whatever an earlier call left there: it is only used when it is a bag id)
+    wl = W.dlrm(micro_batch=32, n_micro=1, n_tables=2, num_rows=64, dim=8, bag=4, bottom=(8,), top=(8, 1), dtype="f32")
+    off_id = next(i for i, op in enumerate(wl.ops) if op.get("role") == "offsets")
+    off = wl.batches[0][off_id]
+    off.reshape(-1)[0] = 1
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params)
+    st.grad_reset()
+    st.forward(0, wl.batches[0])
+    st.backward(0)
+    with pytest.raises(B.GppError) as e:
+        st.sync_status()
+    assert e.value.status == B.GPP_ERR_INDEX
+    st.close()
+    # a class label beyond the classifier's width: no loss term for that sample, and the status says so
+    wl = W.mmt(micro_batch=2, n_micro=1, n_branches=1, n_layers=1, d_model=64, heads=1, d_ff=64, seq_len=16, d_head_out=16, n_classes=5)
+    lab_id = next(i for i, op in enumerate(wl.ops) if op["kind"] == "input" and op["dtype"] == "i32")
+    wl.batches[0][lab_id].reshape(-1)[1] = 5
+    st = B.Stage(wl.ops, wl.micro_batch, wl.params)
+    st.grad_reset()
+    st.forward(0, wl.batches[0])
+    st.backward(0)
+    with pytest.raises(B.GppError) as e:
+        st.sync_status()
+    assert e.value.status == B.GPP_ERR_INDEX
+    st.close()
+
+
 # ---- ordering condition C4 and the slot state machine ---------------------------------
 
 def test_c4_order_violations_are_errors():

@@ -553,10 +553,10 @@ def test_relu_mask_noise_floor(which):
     print(f"[relu noise] {which}: l2 {m['l2']:.3e} max-norm {m['max']:.3e} rows over 2e-2 {m['rows_over']:.4f} "
           f"weight gradients {m['dw']:.3e}; opposite decisions at most {m['flips']} of {m['decisions']}, "
           f"{m['near_zero']} pre-activations within one bf16 step of zero")
-    for k in ("l2", "max", "rows_over"):
+    for k in ("l2", "max", "rows_over", "dw") + (("dt",) if which == "dlrm" else ()):
         assert pinned[k] / PB.BAND <= m[k] <= pinned[k] * PB.BAND, (k, m[k], pinned[k])
     assert 0 < m["flips"] < 1e-4 * m["decisions"] and m["flips"] < m["near_zero"]
-    assert m["dw"] < 0.5 * PB.STATED_L2["bf16"]
+    assert m["dw"] < 0.5 * PB.STATED_L2["bf16"] and PB.relu_dw_bar(pinned) == PB.STATED_L2["bf16"]   # weight gradients: stated bar
     # what follows for the GPU bars: the recommendation model needs no exception at all
     b2, bm, _ = PB.relu_gin_bars(pinned, wl.micro_batch)
     if which == "dlrm":
