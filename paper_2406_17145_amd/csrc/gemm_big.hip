@@ -13,9 +13,11 @@
 //
 // A k-step is 64 contraction elements, so a k-contiguous operand row contributes one whole 128-byte
 // cache line per step.  Operands come from memory through buffer loads (out-of-range rows read as
-// zero without a branch; a chunk beyond the contraction length is steered out of range), wait in
-// registers and go through LDS.  The three forms and the two LDS layouts (k-contiguous rows read
-// with b128, contraction-major rows read with the transposing read) are those of the smaller tile kernel.
+// zero without a branch; a chunk beyond the contraction length is steered out of range).  Two kinds of loop:
+// staged (operands wait in registers and are stored to padded LDS tiles) and direct (copied straight into
+// swizzled LDS tiles, with the LDS reads software-pipelined under the MFMAs).  The three forms and the two
+// LDS layouts (k-contiguous rows read with b128, contraction-major rows read with the transposing read) are
+// those of the smaller tile kernel.
 #include "gemm_tile_body.h"
 
 namespace gpp {
@@ -163,6 +165,16 @@ __device__ __forceinline__ void copies_landed_barrier() {
   asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(VM) : "memory");
 }
 
+// Order for the scheduler: one LDS read behind each of the next MF MFMAs (the last MFMA takes the reads left over)
+template <int MF, int READS, int Q = 0>
+__device__ __forceinline__ void big_mix() {
+  if constexpr (Q < MF) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    if constexpr (Q < READS) __builtin_amdgcn_sched_group_barrier(0x100, (Q + 1 == MF && READS > MF) ? READS - MF + 1 : 1, 0);
+    big_mix<MF, READS, Q + 1>();
+  }
+}
+
 // what every tile kernel of this file does first: XCD-aware spreading (consecutive workgroup ids go
 // round-robin over the 8 XCDs; give each XCD one contiguous range of tiles instead, so that
 // neighbours share operand panels in one L2), then (record, tile) from the records' prefix sums
@@ -194,10 +206,11 @@ __device__ __forceinline__ BigTile big_locate(const GemmProb *__restrict__ probs
 // the other -- the weight gradient of a group of backward passes in one pass over the accumulator.
 // Both operands live in the slots at the same offsets: slot g of the group is `grp.stride` bytes times
 // its slot number behind slot 0, whose addresses the record holds.
-template <int FORM, int WGM, int WGN, int WTM, int WTN, int BUFS, int NS, bool GROUP = false, bool DIRECT = false>
+template <int FORM, int WGM, int WGN, int WTM, int WTN, int BUFS, int NS, bool GROUP = false, int PIPE = 0>
 __device__ __forceinline__ void big_tile_body(const GemmProb &p, int m0, int n0, uint16_t *lds, int accumulate_dw,
                                               const ExtPtrs &ext, const SlotGroup grp = SlotGroup()) {
   static_assert(!GROUP || FORM == FORM_DW, "only the weight gradient contracts over a group of slots");
+  constexpr bool DIRECT = PIPE != 0;     // operands copied straight into LDS, software-pipelined loop 1 or 2 (below)
   static_assert(!DIRECT || BUFS >= 2, "direct loads fill the other LDS buffers while one is multiplied");
   typedef BigCfg<FORM, WGM, WGN, WTM, WTN, BUFS, DIRECT> C;
   constexpr int BM = C::BM, BN = C::BN, THREADS = C::THREADS;
@@ -252,19 +265,9 @@ __device__ __forceinline__ void big_tile_body(const GemmProb &p, int m0, int n0,
   // of pointers loses its address space, and the operand reads then turn into generic (flat) loads
   auto da = [&](int b) { return lds + b * C::A_ELEMS; };
   auto db = [&](int b) { return lds + BUFS * C::A_ELEMS + b * C::B_ELEMS; };
-  // the same k-step straight into LDS buffer `buf`
+  // the same k-step straight into LDS buffer `buf` (a k-step beyond the contraction copies zeros: its rows or
+  // chunks lie outside the buffer range)
   auto fetch_direct = [&](int kt, int buf) {
-    if (GROUP) {
-      const int g = kt / nk_slot, k0 = (kt - g * nk_slot) * GB_BK;
-      int slot = grp.first + g;
-      slot = slot >= grp.total ? slot - grp.total : slot;
-      const int64_t off = (int64_t)slot * grp.stride;
-      const __amdgpu_buffer_rsrc_t ga = matrix_rsrc((const char *)p.A + off, p.K, p.lda, p.M);
-      const __amdgpu_buffer_rsrc_t gb = matrix_rsrc((const char *)p.B + off, p.K, p.ldb, p.N);
-      big_direct_tr<BM, THREADS>(ga, p.lda, k0, m0, da(buf), tid);
-      big_direct_tr<BN, THREADS>(gb, p.ldb, k0, n0, db(buf), tid);
-      return;
-    }
     const int k0 = kt * GB_BK;
     if (A_TR) big_direct_tr<BM, THREADS>(rs_a, p.lda, k0, m0, da(buf), tid);
     else      big_direct_kmajor<BM, THREADS>(rs_a, p.lda, m0, k0, p.K, da(buf), tid);
@@ -277,18 +280,14 @@ __device__ __forceinline__ void big_tile_body(const GemmProb &p, int m0, int n0,
     if (B_TR) big_store_tr<BN, THREADS>(xb, lds_b[buf], tid);
     else      big_store_kmajor<BN, THREADS>(xb, lds_b[buf], tid);
   };
-  auto multiply = [&](int buf) {
+  auto multiply = [&](int buf) {       // staged loops
 #pragma unroll
     for (int kc = 0; kc < GB_BK; kc += 16) {
       bf16x8 a[WTM], b[WTN];
 #pragma unroll
-      for (int i = 0; i < WTM; ++i)
-        a[i] = DIRECT ? (A_TR ? big_direct_frag_tr<BM>(da(buf), wi0 + 32 * i, kc) : big_direct_frag_kmajor(da(buf), wi0 + 32 * i, kc))
-                      : (A_TR ? frag_tr<BM>(lds_a[buf], wi0 + 32 * i, kc) : big_frag_kmajor(lds_a[buf], wi0 + 32 * i, kc));
+      for (int i = 0; i < WTM; ++i) a[i] = A_TR ? frag_tr<BM>(lds_a[buf], wi0 + 32 * i, kc) : big_frag_kmajor(lds_a[buf], wi0 + 32 * i, kc);
 #pragma unroll
-      for (int j = 0; j < WTN; ++j)
-        b[j] = DIRECT ? (B_TR ? big_direct_frag_tr<BN>(db(buf), wj0 + 32 * j, kc) : big_direct_frag_kmajor(db(buf), wj0 + 32 * j, kc))
-                      : (B_TR ? frag_tr<BN>(lds_b[buf], wj0 + 32 * j, kc) : big_frag_kmajor(lds_b[buf], wj0 + 32 * j, kc));
+      for (int j = 0; j < WTN; ++j) b[j] = B_TR ? frag_tr<BN>(lds_b[buf], wj0 + 32 * j, kc) : big_frag_kmajor(lds_b[buf], wj0 + 32 * j, kc);
 #pragma unroll
       for (int i = 0; i < WTM; ++i)
 #pragma unroll
@@ -303,46 +302,138 @@ __device__ __forceinline__ void big_tile_body(const GemmProb &p, int m0, int n0,
   float bsum = 0.0f;
   auto bias_rows = [&](int buf) {
     if (FORM == FORM_DW && do_bias) {
-      if (DIRECT) {       // swizzled rows of BM elements
-        const int m = tid % BM, kr0 = (tid / BM) * BROWS;
+      const uint16_t *la = lds_a[buf] + (tid / BM) * BROWS * (BM + PAD_TR) + (tid % BM);
 #pragma unroll
-        for (int rr = 0; rr < BROWS; ++rr) {
-          const int k = kr0 + rr;
-          bsum += bf16_bits_to_f32(da(buf)[k * BM + ((((m >> 3) ^ ((k & 3) << 2)) << 3) | (m & 7))]);
-        }
-      } else {
-        const uint16_t *la = lds_a[buf] + (tid / BM) * BROWS * (BM + PAD_TR) + (tid % BM);
-#pragma unroll
-        for (int rr = 0; rr < BROWS; ++rr) bsum += bf16_bits_to_f32(la[rr * (BM + PAD_TR)]);
-      }
+      for (int rr = 0; rr < BROWS; ++rr) bsum += bf16_bits_to_f32(la[rr * (BM + PAD_TR)]);
     }
   };
+  static_assert(!DIRECT || (FORM != FORM_DW && !GROUP), "backward-weight stages its operands through registers");
 
-  if (DIRECT) {
-    // BUFS LDS buffers, k-steps kt + 1 .. kt + BUFS - 1 in flight while k-step kt is multiplied.  A wave's copies
-    // land in the order it issued them, so "k-step kt + 1 has landed" is "at most the (BUFS - 2) x LPF copies of
-    // the later k-steps are outstanding" (vmcnt), LPF = copy instructions of one k-step per wave; the barrier
-    // then covers every wave's copies.  Near the end fewer k-steps are in flight than that count assumes: wait
-    // for all of them (vmcnt(0)).
+  if constexpr (PIPE == 1) {
+    // Software-pipelined form: the operand fragments of 16-wide chunk c + 1 are read from LDS while the MFMAs
+    // of chunk c run (two register sets), also across the k-step boundary.  One barrier per k-step, in front of
+    // its LAST chunk: by then every wave has all fragments of the k-step in registers, so the buffer is free
+    // and is refilled at once with k-step kt + BUFS; behind the barrier the first fragments of k-step kt + 1
+    // (landed: at most BUFS - 2 later k-steps are outstanding) are read under the last chunk's MFMAs.
     constexpr int LPF = (A_TR ? GB_BK * (BM / 8) / 64 / C::NW : BM / C::NW / 8) + (B_TR ? GB_BK * (BN / 8) / 64 / C::NW : BN / C::NW / 8);
-    constexpr int AHEAD = (BUFS > 2 ? BUFS - 2 : 0) * LPF;
-    static_assert(AHEAD < 64, "vmcnt is a 6-bit counter");
+    bf16x8 fa[2][WTM], fb[2][WTN];
+    // read in the order of first use: the MFMAs run a-major, so the first of them needs every b and a[0]
+    auto frags = [&](int set, int buf, int kc) {
 #pragma unroll
-    for (int u = 0; u < BUFS - 1; ++u)
-      if (u < nk) fetch_direct(u, u);
-    if (BUFS - 1 <= nk) copies_landed_barrier<AHEAD>();
-    else copies_landed_barrier<0>();
-    int cur = 0, nxt = BUFS - 1;      // buffer of k-step kt, buffer of k-step kt + BUFS - 1 (multiplied one step ago)
+      for (int j = 0; j < WTN; ++j)
+        fb[set][j] = B_TR ? big_direct_frag_tr<BN>(db(buf), wj0 + 32 * j, kc) : big_direct_frag_kmajor(db(buf), wj0 + 32 * j, kc);
+#pragma unroll
+      for (int i = 0; i < WTM; ++i)
+        fa[set][i] = A_TR ? big_direct_frag_tr<BM>(da(buf), wi0 + 32 * i, kc) : big_direct_frag_kmajor(da(buf), wi0 + 32 * i, kc);
+    };
+    auto mfmas = [&](int set) {
+#pragma unroll
+      for (int i = 0; i < WTM; ++i)
+#pragma unroll
+        for (int j = 0; j < WTN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
+    };
+    constexpr int READS = (A_TR ? 2 : 1) * WTM + (B_TR ? 2 : 1) * WTN, MFMAS = WTM * WTN;
+    static_assert((BUFS - 1) * LPF < 64, "vmcnt is a 6-bit counter");
+    auto interleave = [&]() { big_mix<MFMAS, READS>(); };
+    // No branch inside the loop (a branch would end the scheduling region and the interleaving with it): k-steps
+    // beyond the contraction are copied like the others -- their rows lie outside the operand's buffer range and
+    // read zero -- into buffers nobody multiplies any more, and the fragments read for a k-step that does not
+    // exist are dropped.  The number of outstanding copies is then the same in every iteration.
+    // L2 prefetch PD k-steps ahead of the copies, issued BEHIND the copies of its iteration: the loads of a wave
+    // complete in order, so a wait for copies never includes the prefetch issued after them, only the one of the
+    // iteration before, which has had a whole k-step more
+#pragma unroll
+    for (int u = 0; u < BUFS; ++u) fetch_direct(u, u);
+    copies_landed_barrier<(BUFS - 1) * LPF>();
+    frags(0, 0, 0);
+    int cur = 0;
     for (int kt = 0; kt < nk; ++kt) {
-      const bool more = kt + BUFS - 1 < nk;
-      if (more) fetch_direct(kt + BUFS - 1, nxt);
-      multiply(cur);
-      bias_rows(cur);
-      if (more) copies_landed_barrier<AHEAD>();
-      else copies_landed_barrier<0>();
-      cur = cur + 1 == BUFS ? 0 : cur + 1;
-      nxt = nxt + 1 == BUFS ? 0 : nxt + 1;
+      const int nxt = cur + 1 == BUFS ? 0 : cur + 1;
+      frags(1, cur, 16); mfmas(0); interleave();
+      frags(0, cur, 32); mfmas(1); interleave();
+      frags(1, cur, 48); mfmas(0); interleave();
+      copies_landed_barrier<(BUFS - 2) * LPF>();
+      fetch_direct(kt + BUFS, cur);
+      frags(0, nxt, 0); mfmas(1); interleave();
+      cur = nxt;
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the copies of the k-steps beyond the end
+    __syncthreads();      // the epilogue reuses the operand LDS
+  } else if constexpr (PIPE == 2) {
+    // As above, and the copies of a k-step are issued in TWO batches so that the copy path never runs empty (with
+    // one batch per k-step and two buffers, a batch can only be issued when the batch before it has landed: one
+    // memory round trip per k-step in which nothing moves).  A wave multiplies the TOP half of its rows for all
+    // four 16-wide chunks first (keeping the b fragments of the four chunks), then the BOTTOM half: after the
+    // first phase the b tile and the top halves of the a tile are free and are refilled with k-step kt + 2 (batch
+    // 1) while the second phase runs; after the second phase the bottom halves follow (batch 2).  Every batch has
+    // one and a half k-steps to land, and two batches are in flight at any time.  Each accumulator still adds
+    // its chunks in the order 0..3, so the result is the same as in the other loops, bit by bit.
+    static_assert(!A_TR && BUFS == 2 && WTM % 2 == 0, "rows of a k-contiguous A split into halves");
+    constexpr int HM = WTM / 2, RB = 16 * WTM;                    // MFMA row tiles and rows of a half of a wave's rows
+    constexpr int A_HALF = BM / 2 / 8 / C::NW;                    // copy instructions per wave and half of the a tile
+    static_assert(A_HALF * C::NW * 8 * 2 == BM, "whole copy instructions");
+    constexpr int B_ALL = B_TR ? GB_BK * (BN / 8) / 64 / C::NW : BN / C::NW / 8;
+    constexpr int N1 = A_HALF + B_ALL, N2 = A_HALF;
+    static_assert(2 * (N1 + N2) < 64, "vmcnt is a 6-bit counter");
+    auto copy_a = [&](int kt, int buf, int h) {                   // rows [h RB, h RB + RB) of every wave row block
+      const int k0 = kt * GB_BK;
+#pragma unroll
+      for (int q = 0; q < A_HALF; ++q) {
+        const int idx = q * C::NW + wave, wr = idx / (RB / 8), sub = idx % (RB / 8);
+        const int base = wr * 32 * WTM + h * RB + sub * 8, row = base + (lane >> 3);
+        const int k = k0 + (((lane & 7) ^ ((row >> 1) & 7)) << 3);
+        const uint32_t oob = (uint32_t)-(int32_t)(k >= p.K) & OOB_OFFSET;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a, (lds_void_t *)(da(buf) + base * GB_BK), 16,
+                                                 (uint32_t)(((int64_t)(m0 + row) * p.lda + k) * 2) | oob, 0, 0, 0);
+      }
+    };
+    auto copy_b = [&](int kt, int buf) {
+      if (B_TR) big_direct_tr<BN, THREADS>(rs_b, p.ldb, kt * GB_BK, n0, db(buf), tid);
+      else big_direct_kmajor<BN, THREADS>(rs_b, p.ldb, n0, kt * GB_BK, p.K, db(buf), tid);
+    };
+    bf16x8 fa[2][HM], fb[4][WTN];
+    auto read_b = [&](int buf, int c) {
+#pragma unroll
+      for (int j = 0; j < WTN; ++j)
+        fb[c][j] = B_TR ? big_direct_frag_tr<BN>(db(buf), wj0 + 32 * j, 16 * c) : big_direct_frag_kmajor(db(buf), wj0 + 32 * j, 16 * c);
+    };
+    auto read_a = [&](int set, int buf, int h, int c) {
+#pragma unroll
+      for (int i = 0; i < HM; ++i) fa[set][i] = big_direct_frag_kmajor(da(buf), wi0 + 32 * (h * HM + i), 16 * c);
+    };
+    auto mf = [&](int set, int h, int c) {
+#pragma unroll
+      for (int i = 0; i < HM; ++i)
+#pragma unroll
+        for (int j = 0; j < WTN; ++j)
+          acc[h * HM + i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[c][j], acc[h * HM + i][j], 0, 0, 0);
+    };
+    constexpr int MF = HM * WTN, R1 = (B_TR ? 2 : 1) * WTN + HM, R2 = HM;
+    copy_a(0, 0, 0); copy_b(0, 0); copy_a(0, 0, 1);
+    copy_a(1, 1, 0); copy_b(1, 1); copy_a(1, 1, 1);
+    copies_landed_barrier<N2 + N1 + N2>();
+    read_b(0, 0); read_a(0, 0, 0, 0);
+    for (int kt = 0; kt < nk; ++kt) {
+      const int cur = kt & 1, nxt = cur ^ 1;
+      read_b(cur, 1); read_a(1, cur, 0, 1); mf(0, 0, 0); big_mix<MF, R1>();
+      read_b(cur, 2); read_a(0, cur, 0, 2); mf(1, 0, 1); big_mix<MF, R1>();
+      read_b(cur, 3); read_a(1, cur, 0, 3); mf(0, 0, 2); big_mix<MF, R1>();
+      copies_landed_barrier<N1 + N2>();        // the bottom halves of this k-step have landed; top halves and b are free
+      copy_a(kt + 2, cur, 0); copy_b(kt + 2, cur);
+      read_a(0, cur, 1, 0); mf(1, 0, 3);
+      __builtin_amdgcn_sched_group_barrier(0x010, N1, 0);      // the copies first: they have the longest way
+      big_mix<MF, R2>();
+      read_a(1, cur, 1, 1); mf(0, 1, 0); big_mix<MF, R2>();
+      read_a(0, cur, 1, 2); mf(1, 1, 1); big_mix<MF, R2>();
+      read_a(1, cur, 1, 3); mf(0, 1, 2); big_mix<MF, R2>();
+      copies_landed_barrier<N1 + N2>();        // top halves and b of the next k-step have landed; bottom halves are free
+      copy_a(kt + 2, cur, 1);
+      read_b(nxt, 0); read_a(0, nxt, 0, 0); mf(1, 1, 3);
+      __builtin_amdgcn_sched_group_barrier(0x010, N2, 0);
+      big_mix<MF, R1>();
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the copies of the k-steps beyond the end
+    __syncthreads();      // the epilogue reuses the operand LDS
   } else if (BUFS == 2) {
 #pragma unroll
     for (int u = 0; u < NS - 1; ++u)
@@ -413,14 +504,14 @@ __device__ __forceinline__ void big_tile_body(const GemmProb &p, int m0, int n0,
   }
 }
 
-template <int FORM, int WTM, int WTN, int NS, bool DIRECT, int BUFS = 2>
+template <int FORM, int WTM, int WTN, int NS, int PIPE, int BUFS = 2>
 __global__ __launch_bounds__(512) void k_gemm_big(const GemmProb *__restrict__ probs, int n, int total_blocks,
                                                   int accumulate_dw, ExtPtrs ext) {
-  typedef BigCfg<FORM, 2, 4, WTM, WTN, BUFS, DIRECT> C;
+  typedef BigCfg<FORM, 2, 4, WTM, WTN, BUFS, PIPE != 0> C;
   __shared__ __attribute__((aligned(16))) uint16_t lds[C::LDS_ELEMS];
   const BigTile t = big_locate<C::BM, C::BN>(probs, n, total_blocks);
   const GemmProb p = probs[t.pi];
-  big_tile_body<FORM, 2, 4, WTM, WTN, BUFS, NS, false, DIRECT>(p, t.m0, t.n0, lds, accumulate_dw, ext);
+  big_tile_body<FORM, 2, 4, WTM, WTN, BUFS, NS, false, PIPE>(p, t.m0, t.n0, lds, accumulate_dw, ext);
 }
 
 // 128 x 128 tile, 2 x 2 waves of 64 x 64, one LDS buffer, three waves per SIMD
@@ -435,15 +526,15 @@ __global__ __launch_bounds__(256, 3) void k_gemm_mid(const GemmProb *__restrict_
 }
 
 // backward-weight over a group of stash slots (see big_tile_body)
-template <int WTM, int WTN, int NS, bool DIRECT>
+template <int WTM, int WTN, int NS>
 __global__ __launch_bounds__(512) void k_gemm_big_dw_group(const GemmProb *__restrict__ probs, int n, int total_blocks,
                                                            int accumulate_dw, SlotGroup grp) {
-  typedef BigCfg<FORM_DW, 2, 4, WTM, WTN, 2, DIRECT> C;
+  typedef BigCfg<FORM_DW, 2, 4, WTM, WTN, 2> C;
   __shared__ __attribute__((aligned(16))) uint16_t lds[C::LDS_ELEMS];
   const BigTile t = big_locate<C::BM, C::BN>(probs, n, total_blocks);
   const GemmProb p = probs[t.pi];
   ExtPtrs none;
-  big_tile_body<FORM_DW, 2, 4, WTM, WTN, 2, NS, true, DIRECT>(p, t.m0, t.n0, lds, accumulate_dw, none, grp);
+  big_tile_body<FORM_DW, 2, 4, WTM, WTN, 2, NS, true>(p, t.m0, t.n0, lds, accumulate_dw, none, grp);
 }
 __global__ __launch_bounds__(256, 3) void k_gemm_mid_dw_group(const GemmProb *__restrict__ probs, int n, int total_blocks,
                                                               int accumulate_dw, SlotGroup grp) {
@@ -479,11 +570,14 @@ bool gemm_big_supported(const GemmProb &p) {
 //   forward N 4096 K 1024 (512 / 1024 tiles): 87 / 95 / 90      N 3072 K 1024 (384 / 768): 77 / 71 / 66
 //   forward N 1024 K 4096 (128 / 256):       127 / 88 / 92      N 1024 K 1024 (128 / 256): 39 / 26 / 26
 //   backward-weight [3072 x 1024], 2048 rows (192 / 384): 81 / 90 / 71     [1024 x 1024] (64 / 128): 73 / 46 / 38
-int gemm_big_tile_rows(int maxM, int maxN, int64_t launch_elems, int tiles256, int tiles128) {
+int gemm_big_tile_rows(int form, int maxM, int maxN, int64_t launch_elems, int tiles256, int tiles128) {
   constexpr int CUS = 256;
   if (maxM < 128 || maxN < 128) return 0;
   if (launch_elems < (int64_t)128 * 128 * 128) return 0;
   if (maxM >= 256 && maxN >= 256 && tiles256 >= CUS && tiles256 % CUS == 0) return 256;
+  // forward with the two-batch direct loop: a last round that still fills half of the compute units beats the
+  // co-resident small tiles (4 x [2048 x 3072 x 1024], 384 tiles: 70 against 74 us)
+  if (form == FORM_FWD && maxM >= 256 && maxN >= 256 && tiles256 >= CUS && tiles256 % CUS >= CUS / 2) return 256;
   if (maxN >= 256 && tiles128 == CUS) return 128;
   // the single-buffer small tiles hide their load latency only behind co-resident workgroups: with
   // fewer tiles than compute units (a lone [2048 x 1024 x 1024] problem: 28 us against 20 us) they lose
@@ -501,15 +595,27 @@ template <int FORM>
 static void launch_big_form(const GemmProb *probs, int n, int blocks, int acc, int tile_rows, int direct, const ExtPtrs &ext,
                             hipStream_t s) {
   const dim3 g(blocks), b(512);
-  if (tile_rows == 256 && direct) hipLaunchKernelGGL((k_gemm_big<FORM, 4, 2, 2, true>), g, b, 0, s, probs, n, blocks, acc, ext);
-  else if (tile_rows == 256) hipLaunchKernelGGL((k_gemm_big<FORM, 4, 2, 2, false>), g, b, 0, s, probs, n, blocks, acc, ext);
-  else if (tile_rows == 128 && direct == 3) hipLaunchKernelGGL((k_gemm_big<FORM, 2, 2, 2, true, 3>), g, b, 0, s, probs, n, blocks, acc, ext);
-  else if (tile_rows == 128 && direct) hipLaunchKernelGGL((k_gemm_big<FORM, 2, 2, 2, true>), g, b, 0, s, probs, n, blocks, acc, ext);
-  else if (tile_rows == 128) hipLaunchKernelGGL((k_gemm_big<FORM, 2, 2, 2, false>), g, b, 0, s, probs, n, blocks, acc, ext);
+  // direct: the forward form on both eight-wave tiles, backward-data on the 256 x 256 tile (its a operand is
+  // k-contiguous); backward-weight always stages through registers
+  constexpr int P256 = FORM == FORM_DW ? 0 : 2, P128 = FORM == FORM_FWD ? 1 : 0;
+  if constexpr (P256 != 0) {
+    if (tile_rows == 256 && direct) {
+      hipLaunchKernelGGL((k_gemm_big<FORM, 4, 2, 2, P256, 2>), g, b, 0, s, probs, n, blocks, acc, ext);
+      return;
+    }
+  }
+  if constexpr (P128 != 0) {
+    if (tile_rows == 128 && direct) {
+      hipLaunchKernelGGL((k_gemm_big<FORM, 2, 2, 2, P128, 3>), g, b, 0, s, probs, n, blocks, acc, ext);
+      return;
+    }
+  }
+  if (tile_rows == 256) hipLaunchKernelGGL((k_gemm_big<FORM, 4, 2, 2, 0, 2>), g, b, 0, s, probs, n, blocks, acc, ext);
+  else if (tile_rows == 128) hipLaunchKernelGGL((k_gemm_big<FORM, 2, 2, 2, 0, 2>), g, b, 0, s, probs, n, blocks, acc, ext);
   else hipLaunchKernelGGL((k_gemm_mid<FORM>), g, dim3(256), 0, s, probs, n, blocks, acc, ext);
 }
-// direct != 0: operands straight into LDS (every record must pass gemm_big_direct_ok; the 128 x 128 kernel
-// has one LDS buffer and always stages through registers)
+// direct != 0: operands straight into LDS where the form has such a loop (every record must pass
+// gemm_big_direct_ok); the other launches stage through registers
 void launch_gemm_big(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int form, int tile_rows, int direct,
                      const ExtPtrs &ext, hipStream_t s) {
   if (total_blocks <= 0) return;
@@ -518,16 +624,13 @@ void launch_gemm_big(const GemmProb *probs, int n, int total_blocks, int accumul
   else launch_big_form<FORM_DW>(probs, n, total_blocks, accumulate_dw, tile_rows, direct, ext, s);
 }
 
-void launch_gemm_dw_group(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int tile_rows, int direct,
-                          const SlotGroup &grp, hipStream_t s) {
+void launch_gemm_dw_group(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int tile_rows, const SlotGroup &grp,
+                          hipStream_t s) {
   if (total_blocks <= 0 || grp.n <= 0) return;
   const dim3 g(total_blocks), b(512);
-  if (tile_rows == 256 && direct) hipLaunchKernelGGL((k_gemm_big_dw_group<4, 2, 2, true>), g, b, 0, s, probs, n, total_blocks, accumulate_dw, grp);
-  else if (tile_rows == 256) hipLaunchKernelGGL((k_gemm_big_dw_group<4, 2, 2, false>), g, b, 0, s, probs, n, total_blocks, accumulate_dw, grp);
-  else if (tile_rows == 128 && direct) hipLaunchKernelGGL((k_gemm_big_dw_group<2, 2, 2, true>), g, b, 0, s, probs, n, total_blocks, accumulate_dw, grp);
-  else if (tile_rows == 128) hipLaunchKernelGGL((k_gemm_big_dw_group<2, 2, 2, false>), g, b, 0, s, probs, n, total_blocks, accumulate_dw, grp);
-  else
-    hipLaunchKernelGGL(k_gemm_mid_dw_group, dim3(total_blocks), dim3(256), 0, s, probs, n, total_blocks, accumulate_dw, grp);
+  if (tile_rows == 256) hipLaunchKernelGGL((k_gemm_big_dw_group<4, 2, 2>), g, b, 0, s, probs, n, total_blocks, accumulate_dw, grp);
+  else if (tile_rows == 128) hipLaunchKernelGGL((k_gemm_big_dw_group<2, 2, 2>), g, b, 0, s, probs, n, total_blocks, accumulate_dw, grp);
+  else hipLaunchKernelGGL(k_gemm_mid_dw_group, dim3(total_blocks), dim3(256), 0, s, probs, n, total_blocks, accumulate_dw, grp);
 }
 
 }  // namespace gpp

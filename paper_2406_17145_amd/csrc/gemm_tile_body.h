@@ -345,9 +345,11 @@ __device__ __forceinline__ void epilogue_wave_lds(const GemmProb &p, void *Cout,
   const bool aux_out = FORM == FORM_FWD && p.act == ACT_GELU && p.aux != nullptr;   // derivative is stashed
   // an absent bf16 operand is read from the result buffer instead (valid memory, value unused), so
   // that the loads of a block carry no branch
+  // (with a row stride of zero: every row reads the same few lines of the result's first row, which stay in the
+  // cache -- the loads cost no memory traffic)
   const uint16_t *resp = use_res ? (const uint16_t *)p.res : (const uint16_t *)Cout;
   const uint16_t *auxp = aux_in ? (const uint16_t *)p.aux : (const uint16_t *)Cout;
-  const int64_t ldr = use_res ? p.ldres : p.ldc, lda = aux_in ? p.ldaux : p.ldc;
+  const int64_t ldr = use_res ? p.ldres : 0, lda = aux_in ? p.ldaux : 0;
 #pragma unroll
   for (int i = 0; i < TI; ++i) {
     // accumulators of the 32-row block -> LDS, in their own layout (a half-wave writes 32 consecutive floats)

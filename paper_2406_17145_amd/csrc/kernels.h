@@ -213,9 +213,9 @@ struct SlotGroup {
   int32_t first = 0, n = 1, total = 1, pad = 0;
   int64_t stride = 0;
 };
-void launch_gemm_dw_group(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int tile_rows, int direct,
-                          const SlotGroup &grp, hipStream_t s);
-int gemm_big_tile_rows(int maxM, int maxN, int64_t launch_elems, int tiles256, int tiles128);
+void launch_gemm_dw_group(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, int tile_rows, const SlotGroup &grp,
+                          hipStream_t s);
+int gemm_big_tile_rows(int form, int maxM, int maxN, int64_t launch_elems, int tiles256, int tiles128);
 int gemm_big_tiles_for(int tile_rows, int M, int N, int *tiles_n);
 // backward-weight for small weight matrices and many rows: 64 x 64 tiles, the contraction split over the waves
 void launch_gemm_dw_ksplit(const GemmProb *probs, int n, int total_blocks, int accumulate_dw, hipStream_t s);

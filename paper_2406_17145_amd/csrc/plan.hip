@@ -786,13 +786,8 @@ struct Emitter {
               tiles256 += ((r.M + 255) / 256) * ((r.N + 255) / 256);
               tiles128 += ((r.M + 127) / 128) * ((r.N + 255) / 256);
             }
-            int tile_rows = ok ? gemm_big_tile_rows(max_m, max_n, elems, tiles256, tiles128) : 0;
+            int tile_rows = ok ? gemm_big_tile_rows(form, max_m, max_n, elems, tiles256, tiles128) : 0;
             if (tile_rows > 0) {
-              // operands straight into LDS where both are k-contiguous (forward: 83 -> 73 us on 4 x
-              // [2048 x 4096 x 1024]); with a contraction-major operand the direct form measured 2-5 % slower
-              // than staging through registers, so the backward forms keep that
-              bool direct = form == FORM_FWD;
-              for (auto &r : g) direct = direct && gemm_big_direct_ok(r);
               // backward-data whose epilogue streams a second matrix (the stashed derivative or the mask source):
               // the 256 x 256 tiles' epilogues all fall together at the end of a round of tiles; three co-resident
               // 128 x 128 workgroups hide them behind each other's k-loops (measured cold on 4 x [2048 x 4096 x 1024]
@@ -802,6 +797,13 @@ struct Emitter {
                 for (auto &r : g) second = second && r.act != ACT_NONE;
                 if (second) tile_rows = 64;
               }
+              // operands copied straight into LDS (software-pipelined loops of the eight-wave tiles) where the
+              // a operand is k-contiguous and the tile has such a loop: forward on both tiles (4 x [2048 x 4096 x
+              // 1024] cold: 83 staged, 82 plain direct loop, 78 pipelined), backward-data on the 256 x 256 tile
+              // (4 x [2048 x 4096 x 4096]: 336 staged, 297 pipelined; on the 128 x 256 tile the two 8-byte transposing
+              // reads per fragment of W keep the staged loop ahead: 96 against 112 us)
+              bool direct = form == FORM_FWD || (form == FORM_DX && tile_rows == 256);
+              for (auto &r : g) direct = direct && gemm_big_direct_ok(r);
               int blocks = 0;
               for (auto &r : g) {
                 r.blk_begin = blocks;
@@ -809,9 +811,7 @@ struct Emitter {
                 blocks += gemm_big_tiles_for(tile_rows, r.M, r.N, &r.tiles_n);
               }
               Step &s = add_step(K_GEMM_BIG, push_table(g), (int)g.size(), blocks);
-              // the 128 x 256 tile has room for three LDS buffers: two k-steps in flight instead of one (operands that
-              // come from memory rather than the last-level cache: 4 x [2048 x 1024 x 4096] 94 -> 80 us)
-              s.a0 = direct ? (tile_rows == 128 ? 3 : 1) : 0;
+              s.a0 = direct ? 1 : 0;
               s.a1 = form;
               s.a2 = tile_rows;
               if (wants_ext(g)) s.ext_kind = EXT_GRAD_INPUTS;
@@ -1801,7 +1801,7 @@ void Emitter::backward() {
       max_m = std::max(max_m, r.M);
       max_n = std::max(max_n, r.N);
     }
-    int tile_rows = gemm_big_tile_rows(max_m, max_n, elems, tiles256, tiles128);
+    int tile_rows = gemm_big_tile_rows(FORM_DW, max_m, max_n, elems, tiles256, tiles128);
     if (tile_rows == 0) tile_rows = 64;
     int blocks = 0;
     for (auto &r : dw_group) {
@@ -1809,9 +1809,8 @@ void Emitter::backward() {
       r.split_k = 1;
       blocks += gemm_big_tiles_for(tile_rows, r.M, r.N, &r.tiles_n);
     }
-    const bool direct = false;    // contraction-major operands: staged loads are faster (see emit_gemms)
+    // (contraction-major operands: staged through registers, see emit_gemms)
     Step &sg = add_step(K_GEMM_DW_GROUP, push_table(dw_group), (int)dw_group.size(), blocks);
-    sg.a0 = direct ? 1 : 0;
     sg.a2 = tile_rows;
   }
   steps = &pl.bwd;

@@ -452,7 +452,7 @@ static gpp_status_t run_steps(gpp_stage *st, const std::vector<Step> &steps, int
       case K_GEMM_DW_KSPLIT: launch_gemm_dw_ksplit((const GemmProb *)tab, sp.n, sp.blocks, accumulate, s); break;
       case K_GEMM_DW_GROUP:
         if (!grp) return fail(GPP_ERR_UNSUPPORTED, "internal: group launch without a group");
-        launch_gemm_dw_group((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a2, sp.a0, *grp, s);
+        launch_gemm_dw_group((const GemmProb *)tab, sp.n, sp.blocks, accumulate, sp.a2, *grp, s);
         break;
       case K_GEMM_SKINNY: launch_gemm_skinny((const GemmProb *)tab, sp.n, sp.blocks, sp.a1, sp.a2, sp.a0, sp.a3, ext, s); break;
       case K_GEMM_BWD_MERGED: launch_gemm_bwd_merged((const GemmProb *)tab, sp.n, sp.blocks, sp.a2, sp.a1, accumulate, ext, s); break;
