@@ -111,6 +111,12 @@ __device__ __forceinline__ f32x16 zero16() {
 // row index inside a 32-row score tile held by accumulator register r of this lane
 __device__ __forceinline__ int acc_row(int r) { return 8 * (r >> 2) + 4 * ((threadIdx.x & 63) >> 5) + (r & 3); }
 
+// Before a loop that keeps loads of the next tile in flight: wait for every load issued so far (s_waitcnt vmcnt(0),
+// the other counters left alone).  The compiler counts loads in issue order; fragments loaded once in front of
+// the loop would otherwise be "the n-th last load" for it in every iteration, and its wait for them would take
+// in the loads of the next tile, which were meant to fly under the whole step.
+__device__ __forceinline__ void loads_landed() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 // two streamed 32 x 64 tiles (one 16-byte chunk per thread each)
 struct Stream2 {
   u32x4 a, b;
@@ -141,10 +147,15 @@ __device__ __forceinline__ void store_transposed(uint16_t *stage, const f32x16 (
 }
 
 // ======================================================================= forward
-__global__ __launch_bounds__(256) void k_attn_fwd_mfma(const AttnProb *__restrict__ probs, int n) {
-  __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][KT * LDS_ST];
-  __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][KT * LDS_TR];
-  __shared__ __attribute__((aligned(16))) uint16_t stage[QT * LDS_ST];
+__global__ __launch_bounds__(256, 4) void k_attn_fwd_mfma(const AttnProb *__restrict__ probs, int n) {
+  // one array: the streamed tiles, and over them (they are dead after the loop, which ends with a barrier) the
+  // block through which the result is written.  21 KB and at most 128 registers: four workgroups per compute unit
+  constexpr int TILES = 2 * KT * LDS_ST + 2 * KT * LDS_TR;
+  static_assert(TILES >= QT * LDS_ST, "the output block fits over the tiles");
+  __shared__ __attribute__((aligned(16))) uint16_t lds[TILES];
+  uint16_t(*lds_k)[KT * LDS_ST] = (uint16_t(*)[KT * LDS_ST])lds;
+  uint16_t(*lds_v)[KT * LDS_TR] = (uint16_t(*)[KT * LDS_TR])(lds + 2 * KT * LDS_ST);
+  uint16_t *stage = lds;
   const int pi = find_prob(probs, n, blockIdx.x);
   const AttnProb p = probs[pi];
   const Where w = where(p, blockIdx.x - p.blk_begin);
@@ -171,6 +182,7 @@ __global__ __launch_bounds__(256) void k_attn_fwd_mfma(const AttnProb *__restric
   chunk_store<LDS_ST>(nxt.a, lds_k[0]);
   chunk_store<LDS_TR>(nxt.b, lds_v[0]);
   __syncthreads();
+  loads_landed();
   for (int t = 0; t < nt; ++t) {
     const int cur = t & 1;
     if (t + 1 < nt) nxt = fetch(t + 1);
@@ -226,11 +238,15 @@ __global__ __launch_bounds__(256) void k_attn_fwd_mfma(const AttnProb *__restric
 }
 
 // ======================================================================= backward: dQ (and delta)
-__global__ __launch_bounds__(256) void k_attn_bwd_dq_mfma(const AttnProb *__restrict__ probs, int n) {
-  __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][KT * LDS_ST];    // K read along its rows (scores)
-  __shared__ __attribute__((aligned(16))) uint16_t lds_kt[2][KT * LDS_TR];   // K read transposed (dQ)
-  __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][KT * LDS_ST];
-  __shared__ __attribute__((aligned(16))) uint16_t stage[QT * LDS_ST];
+__global__ __launch_bounds__(256, 4) void k_attn_bwd_dq_mfma(const AttnProb *__restrict__ probs, int n) {
+  // K read along its rows (scores), K read transposed (dQ), V; the output block lies over them as in the forward
+  constexpr int TILES = 4 * KT * LDS_ST + 2 * KT * LDS_TR;
+  static_assert(TILES >= QT * LDS_ST, "the output block fits over the tiles");
+  __shared__ __attribute__((aligned(16))) uint16_t lds[TILES];
+  uint16_t(*lds_k)[KT * LDS_ST] = (uint16_t(*)[KT * LDS_ST])lds;
+  uint16_t(*lds_v)[KT * LDS_ST] = (uint16_t(*)[KT * LDS_ST])(lds + 2 * KT * LDS_ST);
+  uint16_t(*lds_kt)[KT * LDS_TR] = (uint16_t(*)[KT * LDS_TR])(lds + 4 * KT * LDS_ST);
+  uint16_t *stage = lds;
   const int pi = find_prob(probs, n, blockIdx.x);
   const AttnProb p = probs[pi];
   const Where w = where(p, blockIdx.x - p.blk_begin);
@@ -275,6 +291,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dq_mfma(const AttnProb *__rest
   };
   put(nxt, 0);
   __syncthreads();
+  loads_landed();
   for (int t = 0; t < nt; ++t) {
     const int cur = t & 1;
     if (t + 1 < nt) nxt = fetch(t + 1);
@@ -330,11 +347,10 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(const AttnProb *__res
     const int row = t * KT + (threadIdx.x >> 3), cc = (threadIdx.x & 7) * 8;
     s.a = row_chunk(p.qkv, p.ld_qkv, first, row, p.seq, qcol + cc);
     s.b = row_chunk(p.dout, p.ld_dout, first, row, p.seq, w.h * DH + cc);
-    if (threadIdx.x < KT) {
-      const int q = t * KT + threadIdx.x;
-      n_lse = q < p.seq ? p.lse[stat0 + q] * 1.4426950408889634f : 0.0f;   // base 2
-      n_delta = q < p.seq ? p.delta[stat0 + q] : 0.0f;
-    }
+    // (the statistics: plain loads whose values are first touched in put(), so that nothing waits for them here)
+    const int q = min(t * KT + (int)(threadIdx.x & (KT - 1)), p.seq - 1);
+    n_lse = p.lse[stat0 + q];
+    n_delta = p.delta[stat0 + q];
     return s;
   };
   auto put = [&](const Stream2 &s, int buf) {
@@ -343,13 +359,14 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(const AttnProb *__res
     chunk_store<LDS_ST>(s.b, lds_g[buf]);
     chunk_store<LDS_TR>(s.b, lds_gt[buf]);
     if (threadIdx.x < KT) {
-      lds_lse[buf][threadIdx.x] = n_lse;
+      lds_lse[buf][threadIdx.x] = n_lse * 1.4426950408889634f;   // base 2
       lds_delta[buf][threadIdx.x] = n_delta;
     }
   };
   Stream2 nxt = fetch(0);
   put(nxt, 0);
   __syncthreads();
+  loads_landed();
   for (int t = 0; t < nt; ++t) {
     const int cur = t & 1;
     if (t + 1 < nt) nxt = fetch(t + 1);
@@ -381,7 +398,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(const AttnProb *__res
     __syncthreads();
   }
   // dk/dv: rows = this wave's keys (accumulator rows), lane column = dh: 64-byte runs per register
-  uint16_t *out = (uint16_t *)p.out;
+  GPP_G uint16_t *out = (GPP_G uint16_t *)p.out;
 #pragma unroll
   for (int dd = 0; dd < 2; ++dd)
 #pragma unroll

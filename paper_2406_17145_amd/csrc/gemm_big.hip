@@ -474,7 +474,7 @@ __device__ __forceinline__ void big_tile_body(const GemmProb &p, int m0, int n0,
       float total = 0.0f;
 #pragma unroll
       for (int g = 0; g < BGROUPS; ++g) total += red[g * BM + tid];
-      float *db = const_cast<float *>(p.bias) + m0 + tid;
+      GPP_G float *db = (GPP_G float *)p.bias + m0 + tid;
       *db = accumulate_dw ? *db + total : total;
     }
   }

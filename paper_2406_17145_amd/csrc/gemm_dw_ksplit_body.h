@@ -151,7 +151,7 @@ __device__ __forceinline__ void gemm_dw_ksplit_body(const GemmProb &p, int local
     float total = 0.0f;
 #pragma unroll
     for (int w = 0; w < KS_NW; ++w) total += bias_part[w][threadIdx.x];
-    float *db = const_cast<float *>(p.bias) + m0 + threadIdx.x;
+    GPP_G float *db = (GPP_G float *)p.bias + m0 + threadIdx.x;
     *db = accumulate_dw ? *db + total : total;
   }
   if (m0 + er < p.M) {

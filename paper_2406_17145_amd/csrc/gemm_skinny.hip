@@ -101,10 +101,10 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmProb &pin, int local,
     const int member = rb / m_blocks1;
     rb -= member * m_blocks1;
     const int64_t off = (int64_t)member * group.stride;
-    p.A = (const char *)p.A + off;
-    if (p.C) p.C = (char *)p.C + off;
-    if (p.aux) p.aux = (char *)p.aux + off;
-    if (p.res) p.res = (const char *)p.res + off;
+    p.A = (const GPP_G char *)p.A + off;
+    if (p.C) p.C = (GPP_G char *)p.C + off;
+    if (p.aux) p.aux = (GPP_G char *)p.aux + off;
+    if (p.res) p.res = (const GPP_G char *)p.res + off;
     if (p.c_ext > 0) p.c_ext += member * group.ext_stride;
   }
   void *Cout = result_ptr(p, ext);

@@ -613,7 +613,7 @@ __device__ __forceinline__ void gemm_tile_body(const GemmProb &p, int local, int
     }
   }
   if (FORM == FORM_DW && do_bias && tid < BM && m0 + tid < p.M) {
-    float *db = const_cast<float *>(p.bias) + m0 + tid;
+    GPP_G float *db = (GPP_G float *)p.bias + m0 + tid;
     *db = accumulate_dw ? *db + bias_total : bias_total;
   }
   if (Cout == nullptr) return;   // the caller does not want this result (all barriers are behind us)

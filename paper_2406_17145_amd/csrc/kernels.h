@@ -10,6 +10,18 @@
 namespace gpp {
 
 enum : int32_t { DT_F32 = 0, DT_BF16 = 1, DT_I32 = 2 };
+
+// Every buffer a record names is device global memory.  The device pass is told so in the field types: a pointer
+// that comes out of a record in memory otherwise has no known address space, and the compiler then uses flat
+// loads and stores, which count on BOTH wait counters -- every wait for an LDS read (or for a cross-lane
+// ds_bpermute) also waits for the global loads in flight, a whole memory round trip inside loops that meant
+// to overlap them.  Same size and layout on the host, where the records are filled (the planner's source files
+// hold no kernel and see the plain types in both compiler passes).
+#if defined(__HIP_DEVICE_COMPILE__) && !defined(GPP_HOST_ONLY_UNIT)
+#define GPP_G __attribute__((address_space(1)))
+#else
+#define GPP_G
+#endif
 enum : int32_t { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU = 2 };
 enum : int32_t { FORM_FWD = 0, FORM_DX = 1, FORM_DW = 2 };
 
@@ -19,11 +31,11 @@ enum : int32_t { FORM_FWD = 0, FORM_DX = 1, FORM_DW = 2 };
 // FORM_DW   C[n,k] (+)= sum_m A[m,n] * B[m,k]                                  A = dZ, B = X
 // M, N are the output's rows / columns, K the contraction length.
 struct GemmProb {
-  const void *A, *B;
-  void *C;
-  const float *bias;
-  void *aux;        // FWD + GELU: stash of the activation derivative (written). DX: mask source / derivative (read).
-  const void *res;  // FWD: residual addend. DX: gradient addend (may equal C: accumulate).
+  const GPP_G void *A, *B;
+  GPP_G void *C;
+  const GPP_G float *bias;
+  GPP_G void *aux;        // FWD + GELU: stash of the activation derivative (written). DX: mask source / derivative (read).
+  const GPP_G void *res;  // FWD: residual addend. DX: gradient addend (may equal C: accumulate).
   int64_t lda, ldb, ldc, ldaux, ldres;
   int32_t M, N, K;
   int32_t form, act;
@@ -32,8 +44,8 @@ struct GemmProb {
   int32_t blk_begin;  // first workgroup of this record
   int32_t tiles_n;    // tile columns of this record
   int32_t split_k;    // workgroups that share one output tile, each summing a slice of K
-  float *partial;     // split_k > 1: fp32 partial tiles [tile][split][tile elements + tile rows]
-  int32_t *counters;  // split_k > 1: arrival counter per tile (zero between launches)
+  GPP_G float *partial;     // split_k > 1: fp32 partial tiles [tile][split][tile elements + tile rows]
+  GPP_G int32_t *counters;  // split_k > 1: arrival counter per tile (zero between launches)
   int32_t c_ext;      // > 0: C is entry c_ext - 1 of the launch's per-call pointer block (may be null: result not wanted)
 };
 
@@ -42,9 +54,9 @@ struct GemmProb {
 // mode 1 (act backward, in place on dst): dst[r,c] = dst[r,c] * act'(src[r,c])
 // mode 2 (add): dst = src + addend
 struct EltProb {
-  const void *src;
-  void *dst;
-  const void *addend;
+  const GPP_G void *src;
+  GPP_G void *dst;
+  const GPP_G void *addend;
   int64_t ld_src, ld_dst, ld_add;
   int32_t rows, cols;
   int32_t src_dtype, dst_dtype, add_dtype;
@@ -55,8 +67,8 @@ struct EltProb {
 
 // ---- column sums: out[c] (+)= sum_r src[r,c]  (bias gradients) ----------
 struct ColsumProb {
-  const void *src;
-  float *out;
+  const GPP_G void *src;
+  GPP_G float *out;
   int64_t ld;
   int32_t rows, cols, dtype;
   int32_t blk_begin;
@@ -64,14 +76,14 @@ struct ColsumProb {
 
 // ---- LayerNorm ------------------------------------------------------------
 struct LnProb {
-  const void *x;      // input rows
-  void *y;            // fwd: output; bwd: dx
-  const void *dy;     // bwd
-  const void *addend; // bwd: optional gradient addend for dx
-  const float *gamma, *beta;
-  float *mean, *rstd;        // per-row statistics (written fwd, read bwd)
-  float *dgamma, *dbeta;     // accumulators
-  float *partial;            // bwd scratch: [row_blocks, 2, d]
+  const GPP_G void *x;      // input rows
+  GPP_G void *y;            // fwd: output; bwd: dx
+  const GPP_G void *dy;     // bwd
+  const GPP_G void *addend; // bwd: optional gradient addend for dx
+  const GPP_G float *gamma, *beta;
+  GPP_G float *mean, *rstd;        // per-row statistics (written fwd, read bwd)
+  GPP_G float *dgamma, *dbeta;     // accumulators
+  GPP_G float *partial;            // bwd scratch: [row_blocks, 2, d]
   int64_t ldx, ldy, lddy, ldadd;
   int32_t rows, d;
   int32_t x_dtype, y_dtype, dy_dtype, add_dtype;
@@ -82,12 +94,12 @@ struct LnProb {
 
 // ---- attention -------------------------------------------------------------
 struct AttnProb {
-  const void *qkv;   // [b*S, 3d]
-  void *out;         // fwd: O [b*S, d]; bwd: dqkv [b*S, 3d]
-  const void *dout;  // bwd: dO
-  const void *o;     // bwd: O (forward output)
-  float *lse;        // [b*heads, S] log-sum-exp of scaled scores
-  float *delta;      // [b*heads, S] rowsum(dO * O)
+  const GPP_G void *qkv;   // [b*S, 3d]
+  GPP_G void *out;         // fwd: O [b*S, d]; bwd: dqkv [b*S, 3d]
+  const GPP_G void *dout;  // bwd: dO
+  const GPP_G void *o;     // bwd: O (forward output)
+  GPP_G float *lse;        // [b*heads, S] log-sum-exp of scaled scores
+  GPP_G float *delta;      // [b*heads, S] rowsum(dO * O)
   int64_t ld_qkv, ld_out, ld_dout, ld_o;
   int32_t batch, heads, seq, dh;
   int32_t dtype, out_dtype;
@@ -97,8 +109,8 @@ struct AttnProb {
 
 // ---- mean-pool over the sequence -------------------------------------------
 struct PoolProb {
-  const void *src;
-  void *dst;
+  const GPP_G void *src;
+  GPP_G void *dst;
   int64_t ld_src, ld_dst;
   int32_t batch, seq, d;
   int32_t src_dtype, dst_dtype;
@@ -108,22 +120,22 @@ struct PoolProb {
 
 // ---- embedding bag ------------------------------------------------------------
 struct EmbProb {
-  const float *table;
-  float *dtable;
-  const int32_t *indices;  // [capacity]
-  const int32_t *offsets;  // [n_bags+1]
-  void *out;               // fwd: pooled output; bwd: gradient w.r.t. pooled output (read)
-  int32_t *bag_of;         // [capacity] bag id of each index position (written fwd)
-  int32_t *keys_a, *keys_b, *pos_a, *pos_b;  // sort ping-pong buffers [capacity]
-  int32_t *hist;           // [radix, sort_blocks]
-  int32_t *unique_rows;    // [log_slots][capacity]: the SORTED rows of the last backward passes, one log slot each
+  const GPP_G float *table;
+  GPP_G float *dtable;
+  const GPP_G int32_t *indices;  // [capacity]
+  const GPP_G int32_t *offsets;  // [n_bags+1]
+  GPP_G void *out;               // fwd: pooled output; bwd: gradient w.r.t. pooled output (read)
+  GPP_G int32_t *bag_of;         // [capacity] bag id of each index position (written fwd)
+  GPP_G int32_t *keys_a, *keys_b, *pos_a, *pos_b;  // sort ping-pong buffers [capacity]
+  GPP_G int32_t *hist;           // [radix, sort_blocks]
+  GPP_G int32_t *unique_rows;    // [log_slots][capacity]: the SORTED rows of the last backward passes, one log slot each
                            // (a position whose row differs from the row before starts a distinct row)
-  int32_t *sbag;           // [capacity]: bag id of every sorted position (-1: index out of range)
-  int32_t *seg_rows;       // [capacity]: distinct rows in ascending order (scalar path and inspection only)
-  int32_t *seg_offsets;    // [capacity+1]: first sorted position of every distinct row (same)
-  int32_t *counts;         // [log_slots][4]: n_used, n_unique (inspection only), queued slices, -
-  int32_t *long_list;      // [emb_long_entries][4]: queued slices of long segments (start, count, row, slices)
-  float *partial;          // [emb_long_entries][ld_table]: partial row of each queued slice
+  GPP_G int32_t *sbag;           // [capacity]: bag id of every sorted position (-1: index out of range)
+  GPP_G int32_t *seg_rows;       // [capacity]: distinct rows in ascending order (scalar path and inspection only)
+  GPP_G int32_t *seg_offsets;    // [capacity+1]: first sorted position of every distinct row (same)
+  GPP_G int32_t *counts;         // [log_slots][4]: n_used, n_unique (inspection only), queued slices, -
+  GPP_G int32_t *long_list;      // [emb_long_entries][4]: queued slices of long segments (start, count, row, slices)
+  GPP_G float *partial;          // [emb_long_entries][ld_table]: partial row of each queued slice
   int64_t ld_table, ld_out;
   int32_t n_bags, capacity, dim, num_rows;
   int32_t out_dtype;
@@ -138,9 +150,9 @@ struct EmbProb {
 
 // ---- pairwise-dot interaction --------------------------------------------------
 struct InteractProb {
-  const void *x;   // [b, F*d]
-  void *y;         // fwd: [b, d + F(F-1)/2]; bwd: dx [b, F*d]
-  const void *dy;  // bwd
+  const GPP_G void *x;   // [b, F*d]
+  GPP_G void *y;         // fwd: [b, d + F(F-1)/2]; bwd: dx [b, F*d]
+  const GPP_G void *dy;  // bwd
   int64_t ld_x, ld_y, ld_dy;
   int32_t batch, F, d;
   int32_t x_dtype, y_dtype, dy_dtype;
@@ -149,10 +161,10 @@ struct InteractProb {
 
 // ---- loss heads -------------------------------------------------------------------
 struct LossProb {
-  const void *y;        // prediction
-  const void *target;   // f32 targets or i32 labels
-  float *loss;          // fwd: scalar out
-  void *dy;             // bwd: gradient out
+  const GPP_G void *y;        // prediction
+  const GPP_G void *target;   // f32 targets or i32 labels
+  GPP_G float *loss;          // fwd: scalar out
+  GPP_G void *dy;             // bwd: gradient out
   int64_t ld_y, ld_t, ld_dy;
   int32_t rows, cols, kind;   // kind = gpp_op_kind_t value
   int32_t y_dtype, dy_dtype;
@@ -163,15 +175,15 @@ struct LossProb {
 // A one-column head: Linear(K -> 1) without activation whose only consumer is an element-wise loss,
 // with everything of it that depends on forward values alone, in one launch of one workgroup.
 struct HeadProb {
-  const void *x;        // [rows x K] bf16: the head's input
-  const void *w;        // [K] bf16: the Linear's weight row
-  const float *bias;    // one float, or null
-  const void *target;   // [rows] f32, stride ld_t
-  const void *mask;     // [rows x K] bf16: what the derivative of x's activation is taken from, or null
-  void *y;              // [rows] prediction out, stride ld_y
-  void *dy;             // [rows] loss gradient out, stride ld_dy
-  void *dx;             // [rows x K] bf16: gradient of x (times the derivative of its activation) out
-  float *partials;      // tall heads (more rows than one workgroup sums): one partial loss per 8 rows, summed by the loss-sum launch
+  const GPP_G void *x;        // [rows x K] bf16: the head's input
+  const GPP_G void *w;        // [K] bf16: the Linear's weight row
+  const GPP_G float *bias;    // one float, or null
+  const GPP_G void *target;   // [rows] f32, stride ld_t
+  const GPP_G void *mask;     // [rows x K] bf16: what the derivative of x's activation is taken from, or null
+  GPP_G void *y;              // [rows] prediction out, stride ld_y
+  GPP_G void *dy;             // [rows] loss gradient out, stride ld_dy
+  GPP_G void *dx;             // [rows x K] bf16: gradient of x (times the derivative of its activation) out
+  GPP_G float *partials;      // tall heads (more rows than one workgroup sums): one partial loss per 8 rows, summed by the loss-sum launch
   int64_t ld_x, ld_t, ld_mask, ld_y, ld_dy, ld_dx;
   int32_t rows, K, kind;      // kind = gpp_op_kind_t value of the loss
   int32_t y_dtype, dy_dtype, act;
@@ -180,11 +192,11 @@ struct HeadProb {
 
 constexpr int HEAD_GROUP_MAX = 16;
 struct HeadOuts {
-  float *p[HEAD_GROUP_MAX];   // where each member's loss sum goes
+  GPP_G float *p[HEAD_GROUP_MAX];   // where each member's loss sum goes
 };
 
 struct ExtPtrs {
-  void *p[64];
+  GPP_G void *p[64];
 };
 
 // per-stage device flags

@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "../../include/gpp.h"
+#define GPP_HOST_ONLY_UNIT      // host code only in the files that include this header: records with plain pointers
 #include "kernels.h"
 
 namespace gpp {
