@@ -486,13 +486,11 @@ __device__ __forceinline__ void big_tile_body(const GemmProb &p, int m0, int n0,
   // the k-loop and the bias sums ended with a barrier); the rest keeps the accumulator layout.
   static_assert(C::NW * epi_lds_floats<WTN>() * 4 <= C::LDS_ELEMS * 2, "epilogue blocks do not fit the operand LDS");
   if (m0 + BM <= p.M && n0 + BN <= p.N) {
-    // worth it when the epilogue streams a second matrix (residual / gradient addend, stashed
-    // derivative or mask source, old gradient); a plain bias / ReLU / cast epilogue is faster straight
-    // from the accumulators (measured: 87 against 95 us on 4 x [2048 x 4096 x 1024] forward, but
-    // 104 against 176 us for the backward-data launch that multiplies by the stashed GELU derivative)
-    const bool second_stream = FORM == FORM_DW || p.res != nullptr || (FORM == FORM_DX && p.act != ACT_NONE) ||
-                               (FORM == FORM_FWD && p.act == ACT_GELU);
-    if (second_stream && epi_lds_ok(p, Cout, FORM)) {
+    // (also for a plain bias / cast epilogue: rows in 16-byte pieces beat the accumulator layout's 2-byte pieces
+    // sixteen rows apart -- 4 x [2048 x 4096 x 1024] forward 78 -> 75.5 us, a one-k-step launch of the same output
+    // 29 -> 26 us.  While the stores were flat instructions, which count on the LDS wait counter as well, it
+    // was the other way round: 87 against 95 us)
+    if (epi_lds_ok(p, Cout, FORM)) {
       if (FORM == FORM_DW && do_bias) __syncthreads();   // the bias sums were read from LDS after the last barrier
       epilogue_wave_lds<FORM, WTM, WTN>(p, Cout, acc, m0 + wi0, n0 + wj0, lane, accumulate_dw,
                                         (float *)lds + wave * epi_lds_floats<WTN>());

@@ -146,7 +146,8 @@ void launch_colsum(const ColsumProb *probs, int n, int total_blocks, int accumul
 
 // ------------------------------------------------------------------ LayerNorm
 int ln_rows_per_block() { return 4; }
-int ln_param_blocks(int d) { return (d + 63) / 64; }
+constexpr int LNP_COLS = 16, LNP_GROUPS = 16;      // columns and row groups of a parameter-gradient workgroup
+int ln_param_blocks(int d) { return (d + LNP_COLS - 1) / LNP_COLS; }
 
 __global__ __launch_bounds__(256) void k_ln_fwd(const LnProb *__restrict__ probs, int n) {
   const int pi = find_prob(probs, n, blockIdx.x);
@@ -192,6 +193,16 @@ __global__ __launch_bounds__(256) void k_ln_fwd_vec(const LnProb *__restrict__ p
     const int ch = lane + 64 * j;
     raw[j] = *(const lnf_u32x4 *)(xr + (ch < nchunks ? ch : 0) * 8);
   }
+  // gamma and beta are asked for here, behind the row: they arrive while the two wave-wide sums run
+  float4 gb[NCH][4];
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const int cc = (lane + 64 * j < nchunks ? lane + 64 * j : 0) * 8;
+    gb[j][0] = *(const float4 *)(p.gamma + cc);
+    gb[j][1] = *(const float4 *)(p.gamma + cc + 4);
+    gb[j][2] = *(const float4 *)(p.beta + cc);
+    gb[j][3] = *(const float4 *)(p.beta + cc + 4);
+  }
   float v[NCH][8];
   float s = 0.0f;
 #pragma unroll
@@ -221,8 +232,7 @@ __global__ __launch_bounds__(256) void k_ln_fwd_vec(const LnProb *__restrict__ p
   for (int j = 0; j < NCH; ++j) {
     const int ch = lane + 64 * j;
     if (ch >= nchunks) continue;
-    const float4 g0 = *(const float4 *)(p.gamma + ch * 8), g1 = *(const float4 *)(p.gamma + ch * 8 + 4);
-    const float4 b0 = *(const float4 *)(p.beta + ch * 8), b1 = *(const float4 *)(p.beta + ch * 8 + 4);
+    const float4 g0 = gb[j][0], g1 = gb[j][1], b0 = gb[j][2], b1 = gb[j][3];
     const float ga[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
     const float be[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
     lnf_u32x4 o;
@@ -253,12 +263,13 @@ void launch_ln_fwd(const LnProb *probs, int n, int total_blocks, int vec, hipStr
   else hipLaunchKernelGGL(k_ln_fwd, dim3(total_blocks), dim3(256), 0, s, probs, n);
 }
 
-// LayerNorm backward.  One workgroup owns 32 consecutive rows (8 per wave):
+// LayerNorm backward.  One workgroup owns 4 LN_RPW consecutive rows (LN_RPW per wave):
 //   dx = rstd * (g - mean(g) - xhat * mean(g * xhat)) (+ addend), g = dy * gamma
 // and, while the rows are in flight, each lane adds dy*xhat and dy of its own columns into
 // per-wave LDS sums; the four waves are combined in a fixed order into partial[row_block][2][d].
 // k_ln_bwd_params then folds the row blocks, again in a fixed order, into dgamma / dbeta.
-int ln_bwd_rows_per_block() { return 32; }
+constexpr int LN_RPW = 8;     // rows per wave (two: 22.6 us instead of 24.8, but four times the partial sums to fold)
+int ln_bwd_rows_per_block() { return 4 * LN_RPW; }
 int ln_bwd_max_d() { return 2048; }
 
 __global__ __launch_bounds__(256) void k_ln_bwd(const LnProb *__restrict__ probs, int n) {
@@ -270,8 +281,8 @@ __global__ __launch_bounds__(256) void k_ln_bwd(const LnProb *__restrict__ probs
   float *pg = part + (size_t)wave * 2 * p.d, *pb = pg + p.d;
   if (p.partial)
     for (int c = lane; c < p.d; c += 64) pg[c] = pb[c] = 0.0f;
-  for (int rr = 0; rr < 8; ++rr) {
-    const int row = blk * 32 + wave * 8 + rr;
+  for (int rr = 0; rr < LN_RPW; ++rr) {
+    const int row = blk * 4 * LN_RPW + wave * LN_RPW + rr;
     if (row >= p.rows) break;
     const float mu = p.mean[row], rstd = p.rstd[row];
     const int64_t xo = (int64_t)row * p.ldx, go = (int64_t)row * p.lddy;
@@ -306,7 +317,7 @@ __global__ __launch_bounds__(256) void k_ln_bwd(const LnProb *__restrict__ probs
 }
 // Vector variant for bf16 rows whose width is a multiple of 8: a lane owns NCH chunks of 8 columns,
 // keeps the row in registers between the two passes, and carries the parameter partial sums of its
-// columns in registers across the wave's 8 rows.
+// columns in registers across the wave's rows.
 typedef __attribute__((ext_vector_type(4))) uint32_t ln_u32x4;
 __device__ __forceinline__ void unpack8(const ln_u32x4 &v, float (&f)[8]) {
 #pragma unroll
@@ -349,7 +360,7 @@ __global__ __launch_bounds__(256) void k_ln_bwd_vec(const LnProb *__restrict__ p
   };
   const uint16_t *addp = p.addend ? (const uint16_t *)p.addend : (const uint16_t *)p.dy;
   const int64_t ldadd = p.addend ? p.ldadd : p.lddy;
-  const int row_first = blk * 32 + wave * 8;
+  const int row_first = blk * 4 * LN_RPW + wave * LN_RPW;
   auto fetch_row = [&](RowRaw &r, int row) {
     const int rc = min(row, p.rows - 1);
     r.mu = p.mean[rc];
@@ -364,10 +375,10 @@ __global__ __launch_bounds__(256) void k_ln_bwd_vec(const LnProb *__restrict__ p
   };
   RowRaw cur, nxt;
   fetch_row(cur, row_first);
-  for (int rr = 0; rr < 8; ++rr) {
+  for (int rr = 0; rr < LN_RPW; ++rr) {
     const int row = row_first + rr;
     if (row >= p.rows) break;
-    if (rr + 1 < 8) fetch_row(nxt, row + 1);
+    if (rr + 1 < LN_RPW) fetch_row(nxt, row + 1);
     const float mu = cur.mu, rstd = cur.rstd;
     float xh[NCH][8], g[NCH][8];
     float s1 = 0.0f, s2 = 0.0f;
@@ -446,23 +457,36 @@ void launch_ln_bwd(const LnProb *probs, int n, int total_blocks, int max_d, int 
   else hipLaunchKernelGGL(k_ln_bwd, dim3(total_blocks), dim3(256), sh, s, probs, n);
 }
 
-// dgamma[c] (+)= sum over rows of dy*xhat ; dbeta[c] (+)= sum of dy.  64 columns per workgroup, four
+// dgamma[c] (+)= sum over rows of dy*xhat ; dbeta[c] (+)= sum of dy.  16 columns per workgroup, sixteen
 // groups of row blocks (or of rows, when no partial sums exist) reduced through LDS in a fixed order.
 __global__ __launch_bounds__(256) void k_ln_bwd_params(const LnProb *__restrict__ probs, int n, int accumulate) {
-  __shared__ float red[2][4][64];
+  __shared__ float red[2][LNP_GROUPS][LNP_COLS];
   const int pi = find_prob(probs, n, blockIdx.x);
   const LnProb p = probs[pi];
-  const int cl = threadIdx.x & 63, rg = threadIdx.x >> 6;
-  const int c = (blockIdx.x - p.blk_begin) * 64 + cl;
+  const int cl = threadIdx.x % LNP_COLS, rg = threadIdx.x / LNP_COLS;
+  const int c = (blockIdx.x - p.blk_begin) * LNP_COLS + cl;
   float sg = 0.0f, sb = 0.0f;
   if (c < p.d) {
     if (p.partial) {
-      for (int rb = rg; rb < p.row_blocks; rb += 4) {
-        sg += p.partial[(int64_t)rb * 2 * p.d + c];
-        sb += p.partial[(int64_t)rb * 2 * p.d + p.d + c];
+      // four row blocks per round, all eight loads out before the first add (a loop of load-then-add
+      // is one memory round trip per row block: 10 us for 64 row blocks)
+      for (int rb = rg; rb < p.row_blocks; rb += 4 * LNP_GROUPS) {
+        float g[4], b[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int r = min(rb + u * LNP_GROUPS, p.row_blocks - 1);
+          g[u] = p.partial[(int64_t)r * 2 * p.d + c];
+          b[u] = p.partial[(int64_t)r * 2 * p.d + p.d + c];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const bool ok = rb + u * LNP_GROUPS < p.row_blocks;
+          sg += ok ? g[u] : 0.0f;
+          sb += ok ? b[u] : 0.0f;
+        }
       }
     } else {
-      for (int r = rg; r < p.rows; r += 4) {
+      for (int r = rg; r < p.rows; r += LNP_GROUPS) {
         float dy = load_as_f32(p.dy, p.dy_dtype, (int64_t)r * p.lddy + c);
         float xh = (load_as_f32(p.x, p.x_dtype, (int64_t)r * p.ldx + c) - p.mean[r]) * p.rstd[r];
         sg += dy * xh;
@@ -473,9 +497,13 @@ __global__ __launch_bounds__(256) void k_ln_bwd_params(const LnProb *__restrict_
   red[0][rg][cl] = sg;
   red[1][rg][cl] = sb;
   __syncthreads();
-  if (rg == 0 && c < p.d) {
-    float g = (red[0][0][cl] + red[0][1][cl]) + (red[0][2][cl] + red[0][3][cl]);
-    float b = (red[1][0][cl] + red[1][1][cl]) + (red[1][2][cl] + red[1][3][cl]);
+  if (rg == 0 && c < p.d) {      // the groups in a fixed order
+    float g = 0.0f, b = 0.0f;
+#pragma unroll
+    for (int q = 0; q < LNP_GROUPS; ++q) {
+      g += red[0][q][cl];
+      b += red[1][q][cl];
+    }
     p.dgamma[c] = accumulate ? p.dgamma[c] + g : g;
     p.dbeta[c] = accumulate ? p.dbeta[c] + b : b;
   }
