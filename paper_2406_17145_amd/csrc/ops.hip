@@ -543,12 +543,14 @@ __device__ __forceinline__ void store8_from_f32(void *base, int32_t dtype, int64
 }
 
 // ------------------------------------------------------------------ mean-pool
-// forward: a workgroup per (sample, 128 columns): 16 lanes x 8 columns cover the 128 columns of a
-// row, the 16 lane groups stride over the sequence with four rows in flight, and are combined in a
-// fixed order.  backward: a thread per 8 columns of an output row.  Both have a vector body (bf16 or
+// forward: a workgroup per (sample, 64 columns): 8 lanes x 8 columns cover the 64 columns of a
+// row, the 32 lane groups stride over the sequence with eight rows in flight, and are combined in a
+// fixed order (128 columns, 16 groups and four rows in flight left the 16 x 8 workgroups of the transformer
+// stage with eight dependent round trips each: 12.7 us for 16 MB).  backward: a thread per 8 columns of an
+// output row.  Both have a vector body (bf16 or
 // f32 rows of whole, aligned 16-byte chunks; the storage types are template parameters, so that no
 // type test stands in front of a load) and a scalar body for everything else.
-constexpr int POOL_COLS = 128;
+constexpr int POOL_COLS = 64, POOL_LANES = POOL_COLS / 8, POOL_GROUPS = 256 / POOL_LANES, POOL_FLIGHT = 8;
 int pool_blocks(const PoolProb &p) {
   if (!p.backward) return p.batch * ((p.d + POOL_COLS - 1) / POOL_COLS);
   int64_t chunks = (int64_t)p.batch * p.seq * ((p.d + 7) / 8);
@@ -562,18 +564,19 @@ __device__ __forceinline__ void pool_body(const PoolProb &p, int blk, float (*re
   if (!p.backward) {
     const int chunks = (p.d + POOL_COLS - 1) / POOL_COLS;
     const int b = blk / chunks, c0 = (blk % chunks) * POOL_COLS;
-    const int l16 = threadIdx.x & 15, grp = threadIdx.x >> 4;
+    const int l16 = threadIdx.x % POOL_LANES, grp = threadIdx.x / POOL_LANES;
     const int c = c0 + 8 * l16;
     const bool col_ok = c < p.d;
     float acc[8] = {};
     const int64_t base = (int64_t)b * p.seq * p.ld_src + (col_ok ? c : 0);
-    for (int t = grp; t < p.seq; t += 64) {      // rows t, t + 16, t + 32, t + 48 in flight
-      float v[4][8];
+    for (int t = grp; t < p.seq; t += POOL_GROUPS * POOL_FLIGHT) {      // rows t, t + POOL_GROUPS, ... in flight
+      float v[POOL_FLIGHT][8];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) load8_as_f32(p.src, SDT, base + (int64_t)min(t + 16 * u, p.seq - 1) * p.ld_src, v[u]);
+      for (int u = 0; u < POOL_FLIGHT; ++u)
+        load8_as_f32(p.src, SDT, base + (int64_t)min(t + POOL_GROUPS * u, p.seq - 1) * p.ld_src, v[u]);
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
-        if (t + 16 * u < p.seq) {
+      for (int u = 0; u < POOL_FLIGHT; ++u)
+        if (t + POOL_GROUPS * u < p.seq) {
 #pragma unroll
           for (int e = 0; e < 8; ++e) acc[e] += v[u][e];
         }
@@ -584,7 +587,7 @@ __device__ __forceinline__ void pool_body(const PoolProb &p, int blk, float (*re
     if (threadIdx.x < POOL_COLS && c0 + (int)threadIdx.x < p.d) {
       float s = 0.0f;
 #pragma unroll
-      for (int g = 0; g < 16; ++g) s += red[g][threadIdx.x];
+      for (int g = 0; g < POOL_GROUPS; ++g) s += red[g][threadIdx.x];
       store_from_f32(p.dst, DDT, (int64_t)b * p.ld_dst + c0 + threadIdx.x, s / (float)p.seq);
     }
   } else {
@@ -604,14 +607,20 @@ __device__ __forceinline__ void pool_body_scalar(const PoolProb &p, int blk, flo
   if (!p.backward) {
     const int chunks = (p.d + POOL_COLS - 1) / POOL_COLS;
     const int b = blk / chunks, c0 = (blk % chunks) * POOL_COLS;
-    const int cl = threadIdx.x & (POOL_COLS - 1), rg = threadIdx.x / POOL_COLS;   // two row groups
+    constexpr int RG = 256 / POOL_COLS;                                            // row groups
+    const int cl = threadIdx.x & (POOL_COLS - 1), rg = threadIdx.x / POOL_COLS;
     const int c = c0 + cl;
     float s = 0.0f;
     if (c < p.d)
-      for (int t = rg; t < p.seq; t += 256 / POOL_COLS) s += load_as_f32(p.src, p.src_dtype, ((int64_t)b * p.seq + t) * p.ld_src + c);
+      for (int t = rg; t < p.seq; t += RG) s += load_as_f32(p.src, p.src_dtype, ((int64_t)b * p.seq + t) * p.ld_src + c);
     red[rg][cl] = s;
     __syncthreads();
-    if (rg == 0 && c < p.d) store_from_f32(p.dst, p.dst_dtype, (int64_t)b * p.ld_dst + c, (red[0][cl] + red[1][cl]) / (float)p.seq);
+    if (rg == 0 && c < p.d) {
+      float total = 0.0f;
+#pragma unroll
+      for (int g = 0; g < RG; ++g) total += red[g][cl];
+      store_from_f32(p.dst, p.dst_dtype, (int64_t)b * p.ld_dst + c, total / (float)p.seq);
+    }
   } else {
     const int cpr = (p.d + 7) >> 3;
     const int64_t ch = (int64_t)blk * 256 + threadIdx.x;
@@ -623,7 +632,7 @@ __device__ __forceinline__ void pool_body_scalar(const PoolProb &p, int blk, flo
   }
 }
 __global__ __launch_bounds__(256) void k_pool(const PoolProb *__restrict__ probs, int n) {
-  __shared__ float red[16][POOL_COLS];
+  __shared__ float red[POOL_GROUPS][POOL_COLS];
   const int pi = find_prob(probs, n, blockIdx.x);
   const PoolProb p = probs[pi];
   const int blk = blockIdx.x - p.blk_begin;
