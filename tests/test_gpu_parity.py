@@ -135,6 +135,16 @@ def test_large_tile_gemm_ragged_edges():
     both(W.candle_uno(micro_batch=1100, n_micro=2, widths=(512, 264, 1000, 8), hidden=1096, act="gelu"))
 
 
+@pytest.mark.parametrize("act", ["gelu", "none"])
+def test_direct_large_tile_loops_ragged(act):
+    # launches of exactly one round of 256 x 256 tiles (4 branches x [1000 x 4000]: 4 x 16 tiles each), which
+    # take the software-pipelined direct loops: forward with contraction lengths that end inside a k-step
+    # (1000, 520, 264, 776) and a last row tile of 232 rows; with act "none" the backward-data launch of the
+    # second level (contraction 4000 = 62 k-steps + 32) takes the direct loop too, with "gelu" its epilogue
+    # multiplies by the stashed derivative and the forward epilogue writes that stash
+    both(W.candle_uno(micro_batch=1000, n_micro=1, widths=(1000, 520, 264, 776), hidden=4000, depth=2, act=act))
+
+
 def test_backward_weight_contraction_split_ragged():
     # many rows, small weight matrices: the backward-weight launches split the contraction over the
     # waves of a workgroup; 600 rows = 9 steps of 64 + 24, matrix edges 200 / 70 / 131 / 1 / 33
