@@ -46,7 +46,7 @@ __device__ __forceinline__ float to_f32<uint16_t>(uint16_t v) {
 // same exponential over sqrt(2 pi).
 __device__ __forceinline__ void gelu_both(float z, float &y, float &dy) {
   const float az = fabsf(z) * 0.70710678118654752f;
-  const float t = __frcp_rn(1.0f + 0.3275911f * az);
+  const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * az);     // v_rcp_f32 (1 ulp); the exact reciprocal is ten instructions
   const float e = __expf(-az * az);
   const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
   const float erf_abs = 1.0f - poly * e;
