@@ -80,15 +80,31 @@ __device__ __forceinline__ float act_grad(float src, int32_t act) {
   return src;
 }
 
+// Wave-wide sum / maximum, the same value in every lane, in a fixed order.  Inside a row of 16 lanes the partner
+// values come through the DPP operand path (quad permutations, then the half-row and row mirrors: after each step
+// the lanes of a growing group hold that group's total); the four row totals are read out as scalars and combined.
+// Six cross-lane LDS permutations (ds_bpermute, ~100 cycles each, and on the LDS wait counter) were 0.5 us per
+// reduction: most of a LayerNorm row's critical path.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float lane_f32(float v, int lane) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  v += dpp_f32<0xB1>(v);      // quad_perm [1, 0, 3, 2]
+  v += dpp_f32<0x4E>(v);      // quad_perm [2, 3, 0, 1]
+  v += dpp_f32<0x141>(v);     // row_half_mirror
+  v += dpp_f32<0x140>(v);     // row_mirror
+  return (lane_f32(v, 0) + lane_f32(v, 16)) + (lane_f32(v, 32) + lane_f32(v, 48));
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-  return v;
+  v = fmaxf(v, dpp_f32<0xB1>(v));
+  v = fmaxf(v, dpp_f32<0x4E>(v));
+  v = fmaxf(v, dpp_f32<0x141>(v));
+  v = fmaxf(v, dpp_f32<0x140>(v));
+  return fmaxf(fmaxf(lane_f32(v, 0), lane_f32(v, 16)), fmaxf(lane_f32(v, 32), lane_f32(v, 48)));
 }
 
 // Finds the record whose [blk_begin, next blk_begin) range holds `blk`.

@@ -91,17 +91,20 @@ __device__ __forceinline__ void emb_fwd_concat_body(const EmbProb &p, int bag, S
     if (VEC) {
       for (int j0 = 0; j0 < cnt; j0 += rpi * CONCAT_UNROLL) {
         float4 v[CONCAT_UNROLL];
+        bool none[CONCAT_UNROLL];
 #pragma unroll
         for (int u = 0; u < CONCAT_UNROLL; ++u) {
           const int j = j0 + u * rpi + sub;
           const int r = __shfl(my, min(j, 63), 64);
           v[u] = *(const float4 *)(p.table + (int64_t)max(r, 0) * p.ld_table + (sub < rpi ? c4 : 0));
-          if (r < 0) v[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);     // an index out of range leaves a zero row
+          none[u] = r < 0;       // (applied at the store: overwriting v[u] here would wait for its load, row by row)
         }
 #pragma unroll
         for (int u = 0; u < CONCAT_UNROLL; ++u) {
           const int j = j0 + u * rpi + sub;
-          if (j < cnt && sub < rpi) store4(p.out, p.out_dtype, out0 + (int64_t)(base + j) * p.dim + c4, v[u]);
+          // an index out of range leaves a zero row
+          const float4 w = none[u] ? make_float4(0.0f, 0.0f, 0.0f, 0.0f) : v[u];
+          if (j < cnt && sub < rpi) store4(p.out, p.out_dtype, out0 + (int64_t)(base + j) * p.dim + c4, w);
         }
       }
     } else {

@@ -373,12 +373,21 @@ __global__ __launch_bounds__(256) void k_ln_bwd_vec(const LnProb *__restrict__ p
       r.a[j] = *(const ln_u32x4 *)(addp + (int64_t)rc * ldadd + cc);
     }
   };
-  RowRaw cur, nxt;
-  fetch_row(cur, row_first);
+  // AHEAD rows ahead: 12 KB per wave on their way while a row is reduced (one row ahead: 24.8 us, two: 19.0).  A ring of register sets indexed by
+  // constants (the row loop is unrolled): copying a set whose loads are still in flight would wait for them
+  constexpr int AHEAD = NCH <= 2 ? 2 : 1;      // (three ahead measured the same; rows of more than 1024 columns hold 48 registers per row in flight)
+  RowRaw ring[AHEAD + 1];
+#pragma unroll
+  for (int u = 0; u < AHEAD; ++u) fetch_row(ring[u], row_first + u);
+  // every load so far has landed before the loop starts (s_waitcnt vmcnt(0)): the compiler counts loads in issue
+  // order, and gamma, loaded once up here, would otherwise stay "an early load" whose wait takes in the rows in flight
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+#pragma unroll
   for (int rr = 0; rr < LN_RPW; ++rr) {
     const int row = row_first + rr;
     if (row >= p.rows) break;
-    if (rr + 1 < LN_RPW) fetch_row(nxt, row + 1);
+    if (rr + AHEAD < LN_RPW) fetch_row(ring[(rr + AHEAD) % (AHEAD + 1)], row + AHEAD);
+    const RowRaw &cur = ring[rr % (AHEAD + 1)];
     const float mu = cur.mu, rstd = cur.rstd;
     float xh[NCH][8], g[NCH][8];
     float s1 = 0.0f, s2 = 0.0f;
@@ -417,7 +426,6 @@ __global__ __launch_bounds__(256) void k_ln_bwd_vec(const LnProb *__restrict__ p
         *(ln_u32x4 *)((uint16_t *)p.y + (int64_t)row * p.ldy + ch * 8) = pack8f(v);
       }
     }
-    cur = nxt;
   }
   if (!p.partial) return;
   float *mine = part + (size_t)wave * 2 * p.d;
