@@ -145,7 +145,8 @@ void launch_colsum(const ColsumProb *probs, int n, int total_blocks, int accumul
 }
 
 // ------------------------------------------------------------------ LayerNorm
-int ln_rows_per_block() { return 4; }
+constexpr int LNF_RPW = 4;     // rows per wave of the forward kernels
+int ln_rows_per_block() { return 4 * LNF_RPW; }
 constexpr int LNP_COLS = 16, LNP_GROUPS = 16;      // columns and row groups of a parameter-gradient workgroup
 int ln_param_blocks(int d) { return (d + LNP_COLS - 1) / LNP_COLS; }
 
@@ -153,47 +154,57 @@ __global__ __launch_bounds__(256) void k_ln_fwd(const LnProb *__restrict__ probs
   const int pi = find_prob(probs, n, blockIdx.x);
   const LnProb p = probs[pi];
   const int lane = threadIdx.x & 63;
-  const int row = (blockIdx.x - p.blk_begin) * 4 + (threadIdx.x >> 6);
-  if (row >= p.rows) return;
-  const int64_t xo = (int64_t)row * p.ldx;
-  float s = 0.0f;
-  for (int c = lane; c < p.d; c += 64) s += load_as_f32(p.x, p.x_dtype, xo + c);
-  const float mu = wave_sum(s) / (float)p.d;
-  float q = 0.0f;
-  for (int c = lane; c < p.d; c += 64) {
-    float v = load_as_f32(p.x, p.x_dtype, xo + c) - mu;
-    q += v * v;
-  }
-  const float rstd = rsqrtf(wave_sum(q) / (float)p.d + p.eps);
-  for (int c = lane; c < p.d; c += 64) {
-    float v = (load_as_f32(p.x, p.x_dtype, xo + c) - mu) * rstd;
-    store_from_f32(p.y, p.y_dtype, (int64_t)row * p.ldy + c, v * p.gamma[c] + p.beta[c]);
-  }
-  if (lane == 0) {
-    p.mean[row] = mu;
-    p.rstd[row] = rstd;
+  for (int rr = 0; rr < LNF_RPW; ++rr) {
+    const int row = ((blockIdx.x - p.blk_begin) * 4 + (threadIdx.x >> 6)) * LNF_RPW + rr;
+    if (row >= p.rows) return;
+    const int64_t xo = (int64_t)row * p.ldx;
+    float s = 0.0f;
+    for (int c = lane; c < p.d; c += 64) s += load_as_f32(p.x, p.x_dtype, xo + c);
+    const float mu = wave_sum(s) / (float)p.d;
+    float q = 0.0f;
+    for (int c = lane; c < p.d; c += 64) {
+      float v = load_as_f32(p.x, p.x_dtype, xo + c) - mu;
+      q += v * v;
+    }
+    const float rstd = rsqrtf(wave_sum(q) / (float)p.d + p.eps);
+    for (int c = lane; c < p.d; c += 64) {
+      float v = (load_as_f32(p.x, p.x_dtype, xo + c) - mu) * rstd;
+      store_from_f32(p.y, p.y_dtype, (int64_t)row * p.ldy + c, v * p.gamma[c] + p.beta[c]);
+    }
+    if (lane == 0) {
+      p.mean[row] = mu;
+      p.rstd[row] = rstd;
+    }
   }
 }
-// Vector path: bf16 rows of up to 2048 columns in whole 16-byte chunks.  A wave per row; the row stays
-// in registers (NCH chunks of 8 columns per lane) for the mean, the centred second moment and the
-// output, so it is read once; loads carry no branch (a lane without a chunk reads chunk 0 and drops it).
+// Vector path: bf16 rows of up to 2048 columns in whole 16-byte chunks.  A wave takes LNF_RPW consecutive rows;
+// a row stays in registers (NCH chunks of 8 columns per lane) for the mean, the centred second moment and the
+// output, so it is read once, and the next two rows are already on their way (a ring of register sets indexed by
+// constants: the row loop is unrolled).  With one row per wave all waves of a launch loaded, then all stored:
+// the two halves of the traffic never overlapped.  Loads carry no branch (a lane without a chunk reads chunk 0
+// and drops it, a row beyond the end re-reads the last row).
 typedef __attribute__((ext_vector_type(4))) uint32_t lnf_u32x4;
 template <int NCH>
 __global__ __launch_bounds__(256) void k_ln_fwd_vec(const LnProb *__restrict__ probs, int n) {
   const int pi = find_prob(probs, n, blockIdx.x);
   const LnProb p = probs[pi];
   const int lane = threadIdx.x & 63;
-  const int row = (blockIdx.x - p.blk_begin) * 4 + (threadIdx.x >> 6);
-  if (row >= p.rows) return;
+  const int row0 = ((blockIdx.x - p.blk_begin) * 4 + (threadIdx.x >> 6)) * LNF_RPW;
+  if (row0 >= p.rows) return;
   const int nchunks = p.d >> 3;
-  const uint16_t *xr = (const uint16_t *)p.x + (int64_t)row * p.ldx;
-  lnf_u32x4 raw[NCH];
+  constexpr int AHEAD = NCH <= 2 ? 2 : 1;
+  lnf_u32x4 ring[AHEAD + 1][NCH];
+  auto fetch = [&](lnf_u32x4 (&raw)[NCH], int row) {
+    const uint16_t *xr = (const uint16_t *)p.x + (int64_t)min(row, p.rows - 1) * p.ldx;
 #pragma unroll
-  for (int j = 0; j < NCH; ++j) {
-    const int ch = lane + 64 * j;
-    raw[j] = *(const lnf_u32x4 *)(xr + (ch < nchunks ? ch : 0) * 8);
-  }
-  // gamma and beta are asked for here, behind the row: they arrive while the two wave-wide sums run
+    for (int j = 0; j < NCH; ++j) {
+      const int ch = lane + 64 * j;
+      raw[j] = *(const lnf_u32x4 *)(xr + (ch < nchunks ? ch : 0) * 8);
+    }
+  };
+#pragma unroll
+  for (int u = 0; u < AHEAD; ++u) fetch(ring[u], row0 + u);
+  // gamma and beta once per wave
   float4 gb[NCH][4];
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
@@ -203,48 +214,58 @@ __global__ __launch_bounds__(256) void k_ln_fwd_vec(const LnProb *__restrict__ p
     gb[j][2] = *(const float4 *)(p.beta + cc);
     gb[j][3] = *(const float4 *)(p.beta + cc + 4);
   }
-  float v[NCH][8];
-  float s = 0.0f;
+  // everything asked for so far has landed before the loop starts (s_waitcnt vmcnt(0)): the compiler counts
+  // loads in issue order, and gamma / beta would otherwise stay "early loads" whose wait takes in the rows in flight
+  __builtin_amdgcn_s_waitcnt(0x0F70);
 #pragma unroll
-  for (int j = 0; j < NCH; ++j) {
-    const bool ok = lane + 64 * j < nchunks;
+  for (int rr = 0; rr < LNF_RPW; ++rr) {
+    const int row = row0 + rr;
+    if (row >= p.rows) break;
+    if (rr + AHEAD < LNF_RPW) fetch(ring[(rr + AHEAD) % (AHEAD + 1)], row + AHEAD);
+    const lnf_u32x4 (&raw)[NCH] = ring[rr % (AHEAD + 1)];
+    float v[NCH][8];
+    float s = 0.0f;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      v[j][2 * e] = ok ? __uint_as_float(raw[j][e] << 16) : 0.0f;
-      v[j][2 * e + 1] = ok ? __uint_as_float(raw[j][e] & 0xffff0000u) : 0.0f;
-      s += v[j][2 * e] + v[j][2 * e + 1];
+    for (int j = 0; j < NCH; ++j) {
+      const bool ok = lane + 64 * j < nchunks;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        v[j][2 * e] = ok ? __uint_as_float(raw[j][e] << 16) : 0.0f;
+        v[j][2 * e + 1] = ok ? __uint_as_float(raw[j][e] & 0xffff0000u) : 0.0f;
+        s += v[j][2 * e] + v[j][2 * e + 1];
+      }
     }
-  }
-  const float mu = wave_sum(s) / (float)p.d;
-  float q = 0.0f;
+    const float mu = wave_sum(s) / (float)p.d;
+    float q = 0.0f;
 #pragma unroll
-  for (int j = 0; j < NCH; ++j) {
-    const bool ok = lane + 64 * j < nchunks;
+    for (int j = 0; j < NCH; ++j) {
+      const bool ok = lane + 64 * j < nchunks;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float c = ok ? v[j][e] - mu : 0.0f;
-      v[j][e] = c;
-      q += c * c;
+      for (int e = 0; e < 8; ++e) {
+        const float c = ok ? v[j][e] - mu : 0.0f;
+        v[j][e] = c;
+        q += c * c;
+      }
     }
-  }
-  const float rstd = rsqrtf(wave_sum(q) / (float)p.d + p.eps);
+    const float rstd = rsqrtf(wave_sum(q) / (float)p.d + p.eps);
 #pragma unroll
-  for (int j = 0; j < NCH; ++j) {
-    const int ch = lane + 64 * j;
-    if (ch >= nchunks) continue;
-    const float4 g0 = gb[j][0], g1 = gb[j][1], b0 = gb[j][2], b1 = gb[j][3];
-    const float ga[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
-    const float be[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
-    lnf_u32x4 o;
+    for (int j = 0; j < NCH; ++j) {
+      const int ch = lane + 64 * j;
+      if (ch >= nchunks) continue;
+      const float4 g0 = gb[j][0], g1 = gb[j][1], b0 = gb[j][2], b1 = gb[j][3];
+      const float ga[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+      const float be[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+      lnf_u32x4 o;
 #pragma unroll
-    for (int e = 0; e < 4; ++e)
-      o[e] = (uint32_t)f32_to_bf16_bits(v[j][2 * e] * rstd * ga[2 * e] + be[2 * e]) |
-             ((uint32_t)f32_to_bf16_bits(v[j][2 * e + 1] * rstd * ga[2 * e + 1] + be[2 * e + 1]) << 16);
-    *(lnf_u32x4 *)((uint16_t *)p.y + (int64_t)row * p.ldy + ch * 8) = o;
-  }
-  if (lane == 0) {
-    p.mean[row] = mu;
-    p.rstd[row] = rstd;
+      for (int e = 0; e < 4; ++e)
+        o[e] = (uint32_t)f32_to_bf16_bits(v[j][2 * e] * rstd * ga[2 * e] + be[2 * e]) |
+               ((uint32_t)f32_to_bf16_bits(v[j][2 * e + 1] * rstd * ga[2 * e + 1] + be[2 * e + 1]) << 16);
+      *(lnf_u32x4 *)((uint16_t *)p.y + (int64_t)row * p.ldy + ch * 8) = o;
+    }
+    if (lane == 0) {
+      p.mean[row] = mu;
+      p.rstd[row] = rstd;
+    }
   }
 }
 bool ln_fwd_vec_supported(const LnProb &p) {
