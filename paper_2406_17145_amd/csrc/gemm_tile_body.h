@@ -143,6 +143,16 @@ __device__ __forceinline__ void put_partial(float *p, float v) {
 __device__ __forceinline__ float get_partial(const float *p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// After a workgroup's put_partial stores and before one of its threads takes the tile's ticket: every wave waits
+// until its own stores have been acknowledged (s_waitcnt vmcnt(0); stores count there), then the workgroup meets.
+// A workgroup-scope release fence alone compiles to no wait for stores: it orders them for the waves of this
+// compute unit only, and the ticket could overtake partial tiles that are still on their way to memory, where
+// the last workgroup, on another compute unit, reads them.
+__device__ __forceinline__ void partials_published() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  __syncthreads();
+}
 
 // ---- epilogue of one 32 x 32 accumulator tile, in two phases -----------------------------
 // Register r of the tile holds row row0 + 8 * (r / 4) + r % 4 (row0 already includes this lane's
@@ -587,10 +597,9 @@ __device__ __forceinline__ void gemm_tile_body(const GemmProb &p, int local, int
 #pragma unroll
         for (int r = 0; r < 16; ++r) put_partial(mine + ((i * TJ + j) * 16 + r) * 256 + tid, acc[i][j][r]);
     if (FORM == FORM_DW && tid < BM) put_partial(mine + BM * BN + tid, bias_total);
-    // the partial stores go through to memory; once this wave's stores have been acknowledged and
+    // the partial stores go through to memory; once every wave's stores have been acknowledged and
     // the workgroup has met, one thread takes a ticket
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __syncthreads();
+    partials_published();
     int *ticket = (int *)lds_a[0];
     if (tid == 0) *ticket = __hip_atomic_fetch_add(&p.counters[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
