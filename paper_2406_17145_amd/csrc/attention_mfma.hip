@@ -321,10 +321,18 @@ __global__ __launch_bounds__(256, 4) void k_attn_bwd_dq_mfma(const AttnProb *__r
 }
 
 // ======================================================================= backward: dK, dV
-__global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(const AttnProb *__restrict__ probs, int n) {
-  __shared__ __attribute__((aligned(16))) uint16_t lds_q[2][KT * LDS_ST], lds_g[2][KT * LDS_ST];     // read along rows
-  __shared__ __attribute__((aligned(16))) uint16_t lds_qt[2][KT * LDS_TR], lds_gt[2][KT * LDS_TR];   // read transposed
-  __shared__ float lds_lse[2][KT], lds_delta[2][KT];
+// 220 registers per lane leave two waves per SIMD, too few to hide one wave's chain (LDS reads -> score products ->
+// exponentials -> gradient products) behind another's.  The loop is therefore software-pipelined inside the wave:
+// the score products of query tile t + 1 are issued BEFORE the exponentials of tile t and run on the matrix pipe
+// under them; the gradient products of tile t run under the next iteration's loads and exponentials.  Tile t + 1 is
+// read while tile t is still needed and tile t + 2 is being written: three LDS buffers.  Loads and LDS writes past
+// the last tile are not skipped but clamped to the last query row (finite values in a buffer nobody reads, products
+// nobody uses): the loop body has no branches, so every wait in it is for exactly the loads it needs.
+__global__ __launch_bounds__(256, 2) void k_attn_bwd_dkv_mfma(const AttnProb *__restrict__ probs, int n) {
+  constexpr int NB = 3;
+  __shared__ __attribute__((aligned(16))) uint16_t lds_q[NB][KT * LDS_ST], lds_g[NB][KT * LDS_ST];     // read along rows
+  __shared__ __attribute__((aligned(16))) uint16_t lds_qt[NB][KT * LDS_TR], lds_gt[NB][KT * LDS_TR];   // read transposed
+  __shared__ float lds_lse[NB][KT], lds_delta[NB][KT];
   const int pi = find_prob(probs, n, blockIdx.x);
   const AttnProb p = probs[pi];
   const Where w = where(p, blockIdx.x - p.blk_begin);
@@ -342,7 +350,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(const AttnProb *__res
 
   const int nt = (p.seq + KT - 1) / KT;
   float n_lse = 0.0f, n_delta = 0.0f;
-  auto fetch = [&](int t) {
+  auto fetch = [&](int t) {   // (rows beyond the sequence: the last row, see row_chunk)
     Stream2 s;
     const int row = t * KT + (threadIdx.x >> 3), cc = (threadIdx.x & 7) * 8;
     s.a = row_chunk(p.qkv, p.ld_qkv, first, row, p.seq, qcol + cc);
@@ -363,40 +371,67 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(const AttnProb *__res
       lds_delta[buf][threadIdx.x] = n_delta;
     }
   };
-  Stream2 nxt = fetch(0);
-  put(nxt, 0);
-  __syncthreads();
-  loads_landed();
-  for (int t = 0; t < nt; ++t) {
-    const int cur = t & 1;
-    if (t + 1 < nt) nxt = fetch(t + 1);
-    f32x16 st = zero16(), dp = zero16();   // rows = queries of the tile, lane column = this lane's key
+  // S = Q K^T and dP = dO V^T of the tile in `buf`: rows = queries of the tile, lane column = this lane's key
+  auto scores = [&](int buf, f32x16 &st, f32x16 &dp) {
+    st = zero16();
+    dp = zero16();
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-      st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(lds_q[cur], s), kf.f[s], st, 0, 0, 0);
-      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(lds_g[cur], s), vf.f[s], dp, 0, 0, 0);
+      st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(lds_q[buf], s), kf.f[s], st, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(lds_g[buf], s), vf.f[s], dp, 0, 0, 0);
     }
-    const bool tail = t == nt - 1 && (p.seq % KT);
+  };
+  // probabilities and score gradients of tile t (in `buf`) from its products, then dV += P^T dO, dK += dS^T Q
+  auto gradients = [&](int t, int buf, f32x16 &st, f32x16 &dp) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int qi = acc_row(r);
-      float pr = __builtin_amdgcn_exp2f(st[r] * scale2 - lds_lse[cur][qi]);
-      if (tail && t * KT + qi >= p.seq) pr = 0.0f;   // queries beyond a ragged sequence
-      dp[r] = pr * (dp[r] - lds_delta[cur][qi]);
-      st[r] = pr;
+      st[r] = __builtin_amdgcn_exp2f(st[r] * scale2 - lds_lse[buf][qi]);
+      dp[r] = st[r] * (dp[r] - lds_delta[buf][qi]);
+    }
+    if (t == nt - 1 && (p.seq % KT)) {   // queries beyond a ragged sequence (uniform, last tile only)
+      asm volatile("");                  // keeps this a branch: as selects it costs three instructions per element in EVERY step
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (t * KT + acc_row(r) >= p.seq) st[r] = dp[r] = 0.0f;
     }
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
       const bf16x8 pf = pack8(st, c), sf = pack8(dp, c);
 #pragma unroll
       for (int dd = 0; dd < 2; ++dd) {
-        dv[dd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, tr_frag(lds_gt[cur], 32 * dd, c), dv[dd], 0, 0, 0);
-        dk[dd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sf, tr_frag(lds_qt[cur], 32 * dd, c), dk[dd], 0, 0, 0);
+        dv[dd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, tr_frag(lds_gt[buf], 32 * dd, c), dv[dd], 0, 0, 0);
+        dk[dd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sf, tr_frag(lds_qt[buf], 32 * dd, c), dk[dd], 0, 0, 0);
       }
     }
-    if (t + 1 < nt) put(nxt, cur ^ 1);
+  };
+  // one step: tile t's products are in (st, dp); tile t + 1's go to (st_n, dp_n); tile t + 2 comes in
+  auto step = [&](int t, int b_cur, int b_nxt, int b_in, f32x16 &st, f32x16 &dp, f32x16 &st_n, f32x16 &dp_n) {
+    const Stream2 in = fetch(t + 2);
+    scores(b_nxt, st_n, dp_n);
+    __builtin_amdgcn_sched_barrier(0);     // the score products go out before the exponentials, not after them
+    gradients(t, b_cur, st, dp);
+    put(in, b_in);                         // over tile t - 1, which every wave left at the last barrier
     __syncthreads();
+  };
+
+  put(fetch(0), 0);
+  put(fetch(1), 1);
+  __syncthreads();
+  loads_landed();
+  f32x16 st_a, dp_a, st_b, dp_b;
+  scores(0, st_a, dp_a);
+  int b0 = 0, b1 = 1, b2 = 2;              // buffers of tiles t, t + 1, t + 2
+  int t = 0;
+  for (; t + 1 < nt; t += 2) {
+    step(t, b0, b1, b2, st_a, dp_a, st_b, dp_b);
+    step(t + 1, b1, b2, b0, st_b, dp_b, st_a, dp_a);
+    const int o0 = b0;
+    b0 = b2;
+    b2 = b1;
+    b1 = o0;
   }
+  if (t < nt) step(t, b0, b1, b2, st_a, dp_a, st_b, dp_b);
   // dk/dv: rows = this wave's keys (accumulator rows), lane column = dh: 64-byte runs per register
   GPP_G uint16_t *out = (GPP_G uint16_t *)p.out;
 #pragma unroll
