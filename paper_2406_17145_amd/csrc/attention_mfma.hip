@@ -304,6 +304,7 @@ __global__ __launch_bounds__(256, 4) void k_attn_bwd_dq_mfma(const AttnProb *__r
 #pragma unroll
     for (int r = 0; r < 16; ++r) st[r] = __builtin_amdgcn_exp2f(st[r] * scale2 - lse2) * (dp[r] - delta);
     if (t == nt - 1 && (p.seq % KT)) {   // keys beyond a ragged sequence
+      asm volatile("");                  // keeps this a branch (as selects it costs an instruction per element in every step)
 #pragma unroll
       for (int r = 0; r < 16; ++r)
         if (t * KT + acc_row(r) >= p.seq) st[r] = 0.0f;
