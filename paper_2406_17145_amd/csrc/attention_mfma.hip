@@ -433,18 +433,28 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_dkv_mfma(const AttnProb *__
     b1 = o0;
   }
   if (t < nt) step(t, b0, b1, b2, st_a, dp_a, st_b, dp_b);
-  // dk/dv: rows = this wave's keys (accumulator rows), lane column = dh: 64-byte runs per register
-  GPP_G uint16_t *out = (GPP_G uint16_t *)p.out;
+  // dk/dv: rows = this wave's keys (accumulator rows), lane column = dh.  Stored straight from the registers that is
+  // 64 two-byte stores per lane; instead each wave turns its two 32 x 64 blocks in LDS (the transposed-read tiles are
+  // dead after the loop's last barrier; a wave's 32 rows of stride LDS_ST take a quarter of one array) and writes
+  // whole 16-byte pieces of rows.
+  static_assert(sizeof(lds_qt) >= 4 * 32 * LDS_ST * sizeof(uint16_t), "a block per wave fits the dead tiles");
+  uint16_t *blk_k = &lds_qt[0][0] + wave * 32 * LDS_ST, *blk_v = &lds_gt[0][0] + wave * 32 * LDS_ST;
 #pragma unroll
   for (int dd = 0; dd < 2; ++dd)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const int key = w.r0 + wave * 32 + acc_row(r);
-      if (key >= p.seq) continue;
-      const int64_t ro = (first + key) * p.ld_out + w.h * DH + 32 * dd + (lane & 31);
-      out[ro + d] = f32_to_bf16_bits(dk[dd][r] * scale);
-      out[ro + 2 * d] = f32_to_bf16_bits(dv[dd][r]);
+      blk_k[acc_row(r) * LDS_ST + 32 * dd + (lane & 31)] = f32_to_bf16_bits(dk[dd][r] * scale);
+      blk_v[acc_row(r) * LDS_ST + 32 * dd + (lane & 31)] = f32_to_bf16_bits(dv[dd][r]);
     }
+  GPP_G uint16_t *out = (GPP_G uint16_t *)p.out;
+#pragma unroll
+  for (int c = lane; c < 32 * (DH / 8); c += 64) {
+    const int row = c >> 3, cc = (c & 7) * 8, key = w.r0 + wave * 32 + row;
+    if (key >= p.seq) continue;
+    const int64_t ro = (first + key) * p.ld_out + w.h * DH + cc;
+    *(GPP_G u32x4 *)(out + ro + d) = *(const u32x4 *)(blk_k + row * LDS_ST + cc);
+    *(GPP_G u32x4 *)(out + ro + 2 * d) = *(const u32x4 *)(blk_v + row * LDS_ST + cc);
+  }
 }
 
 void launch_attn_fwd_mfma(const AttnProb *probs, int n, int total_blocks, hipStream_t s) {
