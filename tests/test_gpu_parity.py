@@ -85,6 +85,11 @@ def test_transformer_bf16_ragged_sequence():
                seq_len=83, d_head_out=40, n_classes=30))
     both(W.mmt(micro_batch=1, n_micro=1, n_branches=1, n_layers=1, d_model=64, heads=1, d_ff=64,
                seq_len=301, d_head_out=16, n_classes=5))
+    # one key / query tile (the pipelined backward loop then prefetches only tiles that do not exist), one tile
+    # exactly, and a second tile of a single row
+    for seq_len in (20, 32, 33):
+        both(W.mmt(micro_batch=2, n_micro=1, n_branches=1, n_layers=1, d_model=128, heads=2, d_ff=64,
+                   seq_len=seq_len, d_head_out=16, n_classes=5))
 
 
 def test_dlrm_bf16_small():
