@@ -10,8 +10,8 @@
 // k-steps with fully coalesced 16-byte loads (eight lanes per 128-byte row),
 // keeps several steps in flight in registers, stages them in a wave-private LDS tile
 // and reads MFMA operands from there; W in the backward-data form is read
-// with the transposing LDS read.  The partial accumulators are added in a
-// fixed tree order through LDS, then all waves share the epilogue.
+// with the transposing LDS read.  The partial accumulators meet in LDS and are
+// added in wave order by the threads of the epilogue, which all waves share.
 //
 // The backward pass of a level runs both consumers of dZ in ONE launch: workgroups of the first
 // records compute dX with the few-row body, the rest compute dW (+ db) with the tile body, two
@@ -53,7 +53,7 @@ template <int FORM, int TI, int TJ, int NW_ = SkWaves<TI>::value>
 struct SkLds {
   static constexpr int NW = NW_;
   static constexpr int BM = 32 * TI, BN = 32 * TJ;
-  static constexpr int RED_FLOATS = (NW / 2) * BM * BN;
+  static constexpr int RED_FLOATS = NW * BM * BN;      // after the k-loop: every wave's partial tile
   // W tile: forward [BN][64 + 8]; backward-data [64][BN + pad], read with the transposing read.  A
   // 16-lane block of that read touches 32 bytes in each of four consecutive rows, and the neighbouring
   // block the next 32 bytes of the same rows, so the row stride should spread four rows over the 64
@@ -86,7 +86,7 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmProb &pin, int local,
                                                  const SkGroup &group) {
   typedef SkLds<FORM, TI, TJ, NW_> L;
   constexpr int NW = L::NW, BM = L::BM, BN = L::BN, SB = L::SB, WAVE_ELEMS = L::WAVE_ELEMS;
-  float *red = (float *)lds_raw;           // after the k-loop: NW/2 BM x BN fp32 buffers
+  float *red = (float *)lds_raw;           // after the k-loop: NW BM x BN fp32 buffers, one per wave
 
   const int m_blocks1 = (pin.M + BM - 1) / BM, m_blocks = m_blocks1 * group.members, n_blocks = (pin.N + BN - 1) / BN;
   int cb, rb;                      // column block, row block
@@ -240,37 +240,36 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmProb &pin, int local,
     }
   }
 
-  // ---- add the waves' partial tiles through LDS
-  auto put = [&](float *buf) {
+  // ---- the waves' partial tiles meet in LDS: every wave stores its own, one barrier, and whoever needs an element
+  // of the result adds the NW partials in wave order (a fixed order: the result does not depend on timing).  A
+  // tree of hand-overs between waves took three rounds of store, barrier, add, barrier plus a last store: seven
+  // barriers and four LDS round trips in a kernel that lasts a few microseconds.
+  __syncthreads();                 // the waves' private operand tiles are dead from here on
+  {
+    float *buf = red + wave * BM * BN;
 #pragma unroll
     for (int i = 0; i < TI; ++i)
 #pragma unroll
       for (int j = 0; j < TJ; ++j)
 #pragma unroll
         for (int q = 0; q < 16; ++q) buf[(32 * i + 8 * (q >> 2) + 4 * h + (q & 3)) * BN + 32 * j + r] = acc[i][j][q];
-  };
-  auto add = [&](const float *buf) {
-#pragma unroll
-    for (int i = 0; i < TI; ++i)
-#pragma unroll
-      for (int j = 0; j < TJ; ++j)
-#pragma unroll
-        for (int q = 0; q < 16; ++q) acc[i][j][q] += buf[(32 * i + 8 * (q >> 2) + 4 * h + (q & 3)) * BN + 32 * j + r];
-  };
-  // binary tree with a fixed shape: in every round the upper half of the live waves hands its tile
-  // to the lower half; the final sum ends up in buffer 0
-  __syncthreads();                 // the waves' private operand tiles are dead from here on
-#pragma unroll
-  for (int live = NW; live > 1; live >>= 1) {
-    const int half = live >> 1;
-    if (wave >= half && wave < live) put(red + (wave - half) * BM * BN);
-    __syncthreads();
-    if (wave < half) add(red + wave * BM * BN);
-    __syncthreads();
   }
-  if (wave == 0) put(red);
   __syncthreads();
-  const float *r1 = red;
+  // eight consecutive elements of row lr of the tile, from column c on
+  auto summed8 = [&](int lr, int c, float (&v)[8]) {
+    float4 a[NW], b[NW];
+#pragma unroll
+    for (int w8 = 0; w8 < NW; ++w8) {
+      a[w8] = *(const float4 *)(red + w8 * BM * BN + lr * BN + c);
+      b[w8] = *(const float4 *)(red + w8 * BM * BN + lr * BN + c + 4);
+    }
+    v[0] = a[0].x; v[1] = a[0].y; v[2] = a[0].z; v[3] = a[0].w; v[4] = b[0].x; v[5] = b[0].y; v[6] = b[0].z; v[7] = b[0].w;
+#pragma unroll
+    for (int w8 = 1; w8 < NW; ++w8) {
+      v[0] += a[w8].x; v[1] += a[w8].y; v[2] += a[w8].z; v[3] += a[w8].w;
+      v[4] += b[w8].x; v[5] += b[w8].y; v[6] += b[w8].z; v[7] += b[w8].w;
+    }
+  };
   if (Cout == nullptr) return;     // the caller does not want this result (all barriers are behind us)
 
   // ---- epilogue, all waves: thread t owns 8 consecutive columns; BN / 8 threads per row
@@ -300,10 +299,7 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmProb &pin, int local,
         aux_raw = *(const u32x4 *)(auxp + (int64_t)row * lda + col);
       }
       float v[8], rs[8], ax[8];
-      {
-        const float4 a = *(const float4 *)(r1 + lr * BN + cg), b = *(const float4 *)(r1 + lr * BN + cg + 4);
-        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-      }
+      summed8(lr, cg, v);
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         rs[2 * e] = __uint_as_float(res_raw[e] << 16);
@@ -339,11 +335,13 @@ __device__ __forceinline__ void gemm_skinny_body(const GemmProb &pin, int local,
   for (int lr = threadIdx.x / TPR; lr < BM; lr += ROWS_PER_PASS) {
     const int row = m0 + lr;
     if (row >= p.M) break;
+    float v8[8];
+    summed8(lr, cg, v8);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const int col = n0 + cg + e;
       if (col >= p.N) break;
-      float v = r1[lr * BN + cg + e];
+      float v = v8[e];
       const int64_t ci = (int64_t)row * p.ldc + col;
       if (FORM == FORM_FWD) {
         if (p.bias) v += p.bias[col];
