@@ -5,8 +5,8 @@
 // A workgroup owns a 64 x 64 tile of dW; its eight waves each take a contiguous slice of the rows m
 // and run without workgroup barriers: 64-row steps fetched with coalesced 16-byte buffer loads, kept
 // two steps ahead in registers, staged in a wave-private LDS tile and read with the transposing LDS
-// read (both operands have the contraction index as their row).  The eight partial tiles are added
-// in a fixed tree order through LDS.  Tiles of the first column block also produce the bias gradient
+// read (both operands have the contraction index as their row).  The eight partial tiles meet in LDS
+// and are added in wave order.  Tiles of the first column block also produce the bias gradient
 // db[n] = sum_m dZ[m,n] from the dZ tiles they stage.  The old gradient values are requested before
 // the k-loop so that their round trip overlaps it.
 #include "gemm_dw_ksplit_body.h"

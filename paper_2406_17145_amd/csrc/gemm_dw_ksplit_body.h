@@ -28,7 +28,7 @@ struct KsStep {
 };
 
 constexpr int KS_WAVE_ELEMS = 2 * KS_T * KS_ST;
-constexpr int KS_RED_FLOATS = (KS_NW / 2) * KS_T * KS_T;
+constexpr int KS_RED_FLOATS = KS_NW * KS_T * KS_T;   // after the k-loop: every wave's partial tile
 constexpr int KS_MAIN_BYTES = KS_RED_FLOATS * 4 > KS_NW * KS_WAVE_ELEMS * 2 ? KS_RED_FLOATS * 4 : KS_NW * KS_WAVE_ELEMS * 2;
 constexpr int KS_LDS_BYTES = KS_MAIN_BYTES + KS_NW * KS_T * 4;   // + the waves' bias-gradient partials
 
@@ -117,34 +117,19 @@ __device__ __forceinline__ void gemm_dw_ksplit_body(const GemmProb &p, int local
     }
   }
 
-  // ---- add the waves' partial tiles through LDS (fixed tree), and the bias partials in wave order
-  auto put = [&](float *buf) {
+  // ---- the waves' partial tiles meet in LDS behind one barrier; the epilogue's threads add them, and the bias
+  // partials, in wave order (a fixed order; a tree of hand-overs between the waves cost seven barriers)
+  bias_part[wave][lane] = bsum;
+  __syncthreads();                 // the waves' private operand tiles are dead from here on
+  {
+    float *buf = red + wave * KS_T * KS_T;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int q = 0; q < 16; ++q) buf[(32 * i + 8 * (q >> 2) + 4 * h + (q & 3)) * KS_T + 32 * j + r] = acc[i][j][q];
-  };
-  auto add = [&](const float *buf) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int q = 0; q < 16; ++q) acc[i][j][q] += buf[(32 * i + 8 * (q >> 2) + 4 * h + (q & 3)) * KS_T + 32 * j + r];
-  };
-  bias_part[wave][lane] = bsum;
-  __syncthreads();                 // the waves' private operand tiles are dead from here on
-#pragma unroll
-  for (int live = KS_NW; live > 1; live >>= 1) {
-    const int half = live >> 1;
-    if (wave >= half && wave < live) put(red + (wave - half) * KS_T * KS_T);
-    __syncthreads();
-    if (wave < half) add(red + wave * KS_T * KS_T);
-    __syncthreads();
   }
-  if (wave == 0) put(red);
   __syncthreads();
 
   if (do_bias && threadIdx.x < KS_T && m0 + (int)threadIdx.x < p.M) {
@@ -157,8 +142,12 @@ __device__ __forceinline__ void gemm_dw_ksplit_body(const GemmProb &p, int local
   if (m0 + er < p.M) {
     float *c = (float *)p.C + (int64_t)(m0 + er) * p.ldc + n0 + ec;
 #pragma unroll
-    for (int e = 0; e < 8; ++e)
-      if (n0 + ec + e < p.N) c[e] = c_old[e] + red[er * KS_T + ec + e];
+    for (int e = 0; e < 8; ++e) {
+      float v = red[er * KS_T + ec + e];
+#pragma unroll
+      for (int w = 1; w < KS_NW; ++w) v += red[w * KS_T * KS_T + er * KS_T + ec + e];
+      if (n0 + ec + e < p.N) c[e] = c_old[e] + v;
+    }
   }
 }
 
