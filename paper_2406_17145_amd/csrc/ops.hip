@@ -688,6 +688,34 @@ __device__ __forceinline__ bool loss_row_vec_ok(const LossProb &p) {
   return (p.cols & 7) == 0 && (p.ld_y & 7) == 0 && (p.ld_t & 7) == 0 && (((uintptr_t)p.y | (uintptr_t)p.target) & 15) == 0;
 }
 
+// One row of logits in a wave's registers for the softmax cross-entropy: lane l keeps columns l, l + 64, ... (NU of
+// them; -inf beyond the row).  The loads are unconditional (a column beyond the row reads the last one) and all go
+// out before the first value is used: a loop that loads an element, uses it and loads the next makes every pass over
+// the row a chain of trips to memory, and the loss needs two passes, its gradient three.
+template <int NU>
+__device__ __forceinline__ void ce_row_load(const void *y, int32_t y_dtype, int64_t yo, int cols, int lane, float (&v)[NU]) {
+#pragma unroll
+  for (int u = 0; u < NU; ++u) v[u] = load_as_f32(y, y_dtype, yo + min(lane + 64 * u, cols - 1));
+#pragma unroll
+  for (int u = 0; u < NU; ++u)
+    if (lane + 64 * u >= cols) v[u] = -INFINITY;
+}
+// row maximum and sum of exp(v - max), the same in every lane; v becomes exp(v - max)
+template <int NU>
+__device__ __forceinline__ void ce_row_softmax(float (&v)[NU], float &m, float &se) {
+  m = -INFINITY;
+#pragma unroll
+  for (int u = 0; u < NU; ++u) m = fmaxf(m, v[u]);
+  m = wave_max(m);
+  se = 0.0f;
+#pragma unroll
+  for (int u = 0; u < NU; ++u) {
+    v[u] = __expf(v[u] - m);
+    se += v[u];
+  }
+  se = wave_sum(se);
+}
+constexpr int CE_NU = 16;      // rows of up to 1024 classes take the register path
 // four rows per workgroup (one wave each); every workgroup writes one partial sum, already scaled
 int loss_fwd_blocks(const LossProb &p) { return (p.rows + 3) / 4; }
 __global__ __launch_bounds__(256) void k_loss_fwd(const LossProb *__restrict__ probs, int n, StageFlags *flags) {
@@ -701,13 +729,20 @@ __global__ __launch_bounds__(256) void k_loss_fwd(const LossProb *__restrict__ p
   if (r < p.rows) {
     const int64_t yo = (int64_t)r * p.ld_y;
     if (p.kind == 10) {
-      float m = -INFINITY;
-      for (int c = lane; c < p.cols; c += 64) m = fmaxf(m, load_as_f32(p.y, p.y_dtype, yo + c));
-      m = wave_max(m);
-      float se = 0.0f;
-      for (int c = lane; c < p.cols; c += 64) se += __expf(load_as_f32(p.y, p.y_dtype, yo + c) - m);
-      se = wave_sum(se);
       const int lab = ((const int32_t *)p.target)[(int64_t)r * p.ld_t];
+      float m, se;
+      if (p.cols <= 64 * CE_NU) {
+        float v[CE_NU];
+        ce_row_load<CE_NU>(p.y, p.y_dtype, yo, p.cols, lane, v);
+        ce_row_softmax<CE_NU>(v, m, se);
+      } else {
+        m = -INFINITY;
+        for (int c = lane; c < p.cols; c += 64) m = fmaxf(m, load_as_f32(p.y, p.y_dtype, yo + c));
+        m = wave_max(m);
+        se = 0.0f;
+        for (int c = lane; c < p.cols; c += 64) se += __expf(load_as_f32(p.y, p.y_dtype, yo + c) - m);
+        se = wave_sum(se);
+      }
       if (lane == 0 && lab >= 0 && lab < p.cols) acc = (m + __logf(se)) - load_as_f32(p.y, p.y_dtype, yo + lab);
       if (lane == 0 && (lab < 0 || lab >= p.cols)) flags->index_error = 1;    // a label outside the classes: no loss term, reported
     } else {
@@ -809,34 +844,6 @@ __device__ __forceinline__ float loss_small_elementwise(const LossProb &p) {
   }
   return acc;
 }
-// One row of logits in a wave's registers for the softmax cross-entropy: lane l keeps columns l, l + 64, ... (NU of
-// them; -inf beyond the row).  The loads are unconditional (a column beyond the row reads the last one) and all go
-// out before the first value is used: a loop that loads an element, uses it and loads the next makes every pass over
-// the row a chain of trips to memory, and the loss needs two passes, its gradient three.
-template <int NU>
-__device__ __forceinline__ void ce_row_load(const void *y, int32_t y_dtype, int64_t yo, int cols, int lane, float (&v)[NU]) {
-#pragma unroll
-  for (int u = 0; u < NU; ++u) v[u] = load_as_f32(y, y_dtype, yo + min(lane + 64 * u, cols - 1));
-#pragma unroll
-  for (int u = 0; u < NU; ++u)
-    if (lane + 64 * u >= cols) v[u] = -INFINITY;
-}
-// row maximum and sum of exp(v - max), the same in every lane; v becomes exp(v - max)
-template <int NU>
-__device__ __forceinline__ void ce_row_softmax(float (&v)[NU], float &m, float &se) {
-  m = -INFINITY;
-#pragma unroll
-  for (int u = 0; u < NU; ++u) m = fmaxf(m, v[u]);
-  m = wave_max(m);
-  se = 0.0f;
-#pragma unroll
-  for (int u = 0; u < NU; ++u) {
-    v[u] = __expf(v[u] - m);
-    se += v[u];
-  }
-  se = wave_sum(se);
-}
-constexpr int CE_NU = 16;      // rows of up to 1024 classes take the register path
 __global__ __launch_bounds__(256) void k_loss_fwd_small(const LossProb *__restrict__ probs, int n, float *out, StageFlags *flags) {
   __shared__ float red[4];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;

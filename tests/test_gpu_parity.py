@@ -92,6 +92,16 @@ def test_transformer_bf16_ragged_sequence():
                    seq_len=seq_len, d_head_out=16, n_classes=5))
 
 
+def test_cross_entropy_row_paths():
+    # the loss and its gradient keep a row of up to 1024 logits in registers, longer rows take the looping form;
+    # above 16384 logits per micro-batch the loss comes from the kernel with a wave per row and partial sums
+    kw = dict(n_micro=1, n_branches=1, n_layers=1, d_model=64, heads=1, d_ff=64, seq_len=8, d_head_out=32)
+    both(W.mmt(micro_batch=20, n_classes=1000, **kw))
+    both(W.mmt(micro_batch=12, n_classes=1500, **kw))
+    both(W.mmt(micro_batch=2, n_classes=1500, **kw))
+    both(W.mmt(micro_batch=3, n_classes=1024, **kw))
+
+
 def test_dlrm_bf16_small():
     both(W.dlrm(micro_batch=256, n_micro=2, n_tables=6, num_rows=5000, bottom=(64, 32, 128),
                 top=(128, 64, 1)))
