@@ -44,5 +44,21 @@ def build_library(verbose=True):
     return LIB
 
 
+def build_microbench(verbose=True):
+    """Stand-alone measurement programs under microbench/ (not part of the library): one executable each in _build/."""
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    outs = []
+    for src in sorted(glob.glob(os.path.join(HERE, "microbench", "*.hip"))):
+        exe = os.path.join(OBJ_DIR, os.path.splitext(os.path.basename(src))[0])
+        r = subprocess.run([HIPCC, *[f for f in FLAGS if f != "-fPIC"], src, "-o", exe], capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc failed for {src}:\n{r.stderr}")
+        outs.append(exe)
+    if verbose and outs:
+        print("built " + ", ".join(outs))
+    return outs
+
+
 if __name__ == "__main__":
     build_library()
+    build_microbench()
