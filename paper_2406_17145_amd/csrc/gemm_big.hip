@@ -539,7 +539,9 @@ __global__ __launch_bounds__(512) void k_gemm_big_dw_group(const GemmProb *__res
                                                            int accumulate_dw, SlotGroup grp) {
   typedef BigCfg<FORM_DW, 2, 4, WTM, WTN, 2> C;
   __shared__ __attribute__((aligned(16))) uint16_t lds[C::LDS_ELEMS];
-  const BigTile t = big_locate<C::BM, C::BN>(probs, n, total_blocks);
+  // (bands of four tile rows: one workgroup per compute unit, 32 tiles in flight per XCD as a 4 x 8 block; seven
+  // [4096 x 4096] gradients over 2048 rows: 3226 -> 2684 us)
+  const BigTile t = big_locate<C::BM, C::BN, 4>(probs, n, total_blocks);
   const GemmProb p = probs[t.pi];
   ExtPtrs none;
   big_tile_body<FORM_DW, 2, 4, WTM, WTN, 2, NS, true>(p, t.m0, t.n0, lds, accumulate_dw, none, grp);
