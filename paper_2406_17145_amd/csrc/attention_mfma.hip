@@ -48,6 +48,15 @@ bool attn_mfma_supported(const AttnProb &p) {
   return true;
 }
 
+// Consecutive workgroup ids go round-robin over the 8 XCDs (one L2 each).  The workgroups of one (sample, head) read the
+// same K and V (the same Q and dO in the dK/dV kernel): numbered one after the other they would land on four or more
+// different XCDs and fetch those rows into as many L2s.  Each XCD takes a contiguous run of the numbering instead.
+__device__ __forceinline__ int xcd_contiguous_block() {
+  const int total = gridDim.x, bid = blockIdx.x;
+  const int xcd = bid & 7, idx = bid >> 3, per = total >> 3, rem = total & 7;
+  return xcd * per + min(xcd, rem) + idx;
+}
+
 struct Where {
   int b, h, r0;  // sample, head, first row of this workgroup's 128-row block
 };
@@ -156,9 +165,10 @@ __global__ __launch_bounds__(256, 4) void k_attn_fwd_mfma(const AttnProb *__rest
   uint16_t(*lds_k)[KT * LDS_ST] = (uint16_t(*)[KT * LDS_ST])lds;
   uint16_t(*lds_v)[KT * LDS_TR] = (uint16_t(*)[KT * LDS_TR])(lds + 2 * KT * LDS_ST);
   uint16_t *stage = lds;
-  const int pi = find_prob(probs, n, blockIdx.x);
+  const int bid = xcd_contiguous_block();
+  const int pi = find_prob(probs, n, bid);
   const AttnProb p = probs[pi];
-  const Where w = where(p, blockIdx.x - p.blk_begin);
+  const Where w = where(p, bid - p.blk_begin);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int d = p.heads * DH;
   const int64_t first = (int64_t)w.b * p.seq;
@@ -247,9 +257,10 @@ __global__ __launch_bounds__(256, 4) void k_attn_bwd_dq_mfma(const AttnProb *__r
   uint16_t(*lds_v)[KT * LDS_ST] = (uint16_t(*)[KT * LDS_ST])(lds + 2 * KT * LDS_ST);
   uint16_t(*lds_kt)[KT * LDS_TR] = (uint16_t(*)[KT * LDS_TR])(lds + 4 * KT * LDS_ST);
   uint16_t *stage = lds;
-  const int pi = find_prob(probs, n, blockIdx.x);
+  const int bid = xcd_contiguous_block();
+  const int pi = find_prob(probs, n, bid);
   const AttnProb p = probs[pi];
-  const Where w = where(p, blockIdx.x - p.blk_begin);
+  const Where w = where(p, bid - p.blk_begin);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int d = p.heads * DH;
   const int64_t first = (int64_t)w.b * p.seq;
@@ -334,9 +345,10 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_dkv_mfma(const AttnProb *__
   __shared__ __attribute__((aligned(16))) uint16_t lds_q[NB][KT * LDS_ST], lds_g[NB][KT * LDS_ST];     // read along rows
   __shared__ __attribute__((aligned(16))) uint16_t lds_qt[NB][KT * LDS_TR], lds_gt[NB][KT * LDS_TR];   // read transposed
   __shared__ float lds_lse[NB][KT], lds_delta[NB][KT];
-  const int pi = find_prob(probs, n, blockIdx.x);
+  const int bid = xcd_contiguous_block();
+  const int pi = find_prob(probs, n, bid);
   const AttnProb p = probs[pi];
-  const Where w = where(p, blockIdx.x - p.blk_begin);
+  const Where w = where(p, bid - p.blk_begin);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int d = p.heads * DH;
   const int64_t first = (int64_t)w.b * p.seq;
