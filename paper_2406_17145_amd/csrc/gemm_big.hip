@@ -551,7 +551,9 @@ __global__ __launch_bounds__(512) void k_gemm_big_dw_group(const GemmProb *__res
 // (36 operand panels of 512 KB through a 4 MB L2), in bands 8 x 16 (24 panels).  Measured on the transformer stage's
 // launch of all layers: 497-505 -> 483 us (bands of 4: 497, of 16: 487 scaled to the same box).
 constexpr int DW_BAND = 8;
-__global__ __launch_bounds__(256, 3) void k_gemm_mid_dw_group(const GemmProb *__restrict__ probs, int n, int total_blocks,
+// (four workgroups per compute unit: 40 KB of LDS and 128 registers each; with three the transformer stage's launch
+// is 6 % slower)
+__global__ __launch_bounds__(256, 4) void k_gemm_mid_dw_group(const GemmProb *__restrict__ probs, int n, int total_blocks,
                                                               int accumulate_dw, SlotGroup grp) {
   typedef BigCfg<FORM_DW, 2, 2, 2, 2, 1> C;
   __shared__ __attribute__((aligned(16))) uint16_t lds[C::LDS_ELEMS];
