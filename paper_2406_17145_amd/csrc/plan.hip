@@ -397,6 +397,7 @@ struct Emitter {
   std::vector<Buf> gaddend;
   std::vector<char> dz_ready;
   int64_t part_need = 0, cnt_need = 0;  // split-K scratch high-water marks over all launches
+  std::vector<LnProb> ln_fold_later;    // LayerNorm parameter folds of the whole backward pass (see backward())
   std::vector<GemmProb> dw_group;   // backward-weight records left to the launch over a group of slots
   std::vector<char> loss_fused;     // per node: this loss's gradient is written by the forward pass
   std::vector<int> head_loss;       // per LINEAR node: the loss that computes it (one-column head fused into its loss), or -1
@@ -1689,13 +1690,21 @@ void Emitter::backward() {
         st.a0 = max_d;
         st.a1 = !vec ? 0 : (widest <= 512 ? 1 : (widest <= 1024 ? 2 : 4));
       }
-      blocks = 0;
-      for (auto &l : lns) {
-        l.blk_begin = blocks;
-        blocks += ln_param_blocks(l.d);
-      }
+      // second kernel: the fold into the parameter gradients.  Operators with partial sums (a buffer of their
+      // own in the shared region, read by nothing else) are folded by ONE launch at the end of the backward
+      // pass instead of one per level (four launches of 6 us in the two-layer transformer stage); the others read
+      // x and dy, which later levels may overwrite, and are folded here.
+      std::vector<LnProb> now;
+      for (auto &l : lns) (l.partial ? ln_fold_later : now).push_back(l);
       pl.bwd_shared = true;   // accumulates parameter gradients in the order of the backward passes
-      add_step(K_LN_BWD_PARAMS, push_table(lns), (int)lns.size(), blocks);
+      if (!now.empty()) {
+        blocks = 0;
+        for (auto &l : now) {
+          l.blk_begin = blocks;
+          blocks += ln_param_blocks(l.d);
+        }
+        add_step(K_LN_BWD_PARAMS, push_table(now), (int)now.size(), blocks);
+      }
     }
     if (!attns.empty()) {
       int blocks = 0, ms = 0;
@@ -1761,6 +1770,15 @@ void Emitter::backward() {
     }
   }
   join();
+  if (!ln_fold_later.empty()) {
+    int blocks = 0;
+    for (auto &l : ln_fold_later) {
+      l.blk_begin = blocks;
+      blocks += ln_param_blocks(l.d);
+    }
+    add_step(K_LN_BWD_PARAMS, push_table(ln_fold_later), (int)ln_fold_later.size(), blocks);
+    ln_fold_later.clear();
+  }
 
   // egress: input gradients to the caller's dense buffers
   {
