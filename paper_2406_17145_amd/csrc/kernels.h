@@ -299,6 +299,7 @@ int loss_fwd_blocks(const LossProb &p);
 // records at most loss_small_limit()); a null `out` skips the launch
 void launch_loss_fwd_small(const LossProb *probs, int n, float *out, StageFlags *flags, hipStream_t s);
 int loss_small_limit();
+int loss_ce_row_limit();   // longest softmax cross-entropy row whose gradient the forward kernels can write
 bool head_loss_supported(int64_t rows, int64_t K);
 bool head_loss_is_tall(int64_t rows, int64_t K);
 int head_loss_parts(int64_t rows);

@@ -716,6 +716,19 @@ __device__ __forceinline__ void ce_row_softmax(float (&v)[NU], float &m, float &
   se = wave_sum(se);
 }
 constexpr int CE_NU = 16;      // rows of up to 1024 classes take the register path
+int loss_ce_row_limit() { return 64 * CE_NU; }
+// gradient of the row's loss term with respect to its logits, scale * (softmax - one-hot), from the exponentials
+// that ce_row_softmax left in v (what the backward kernel computes; written in the forward pass where the stage's
+// gradient buffers are per stash slot)
+template <int NU>
+__device__ __forceinline__ void ce_row_grad(const LossProb &p, int64_t go, int lane, int lab, const float (&v)[NU], float se) {
+  const float inv = 1.0f / se;
+#pragma unroll
+  for (int u = 0; u < NU; ++u) {
+    const int c = lane + 64 * u;
+    if (c < p.cols) store_from_f32(p.dy, p.dy_dtype, go + c, p.scale * (v[u] * inv - (c == lab ? 1.0f : 0.0f)));
+  }
+}
 // four rows per workgroup (one wave each); every workgroup writes one partial sum, already scaled
 int loss_fwd_blocks(const LossProb &p) { return (p.rows + 3) / 4; }
 __global__ __launch_bounds__(256) void k_loss_fwd(const LossProb *__restrict__ probs, int n, StageFlags *flags) {
@@ -735,6 +748,7 @@ __global__ __launch_bounds__(256) void k_loss_fwd(const LossProb *__restrict__ p
         float v[CE_NU];
         ce_row_load<CE_NU>(p.y, p.y_dtype, yo, p.cols, lane, v);
         ce_row_softmax<CE_NU>(v, m, se);
+        if (p.dy) ce_row_grad<CE_NU>(p, (int64_t)r * p.ld_dy, lane, lab, v, se);
       } else {
         m = -INFINITY;
         for (int c = lane; c < p.cols; c += 64) m = fmaxf(m, load_as_f32(p.y, p.y_dtype, yo + c));
@@ -860,6 +874,7 @@ __global__ __launch_bounds__(256) void k_loss_fwd_small(const LossProb *__restri
           float v[CE_NU];
           ce_row_load<CE_NU>(p.y, p.y_dtype, yo, p.cols, lane, v);
           ce_row_softmax<CE_NU>(v, m, se);
+          if (p.dy) ce_row_grad<CE_NU>(p, (int64_t)r * p.ld_dy, lane, lab, v, se);
         } else {
           m = -INFINITY;
           for (int c = lane; c < p.cols; c += 64) m = fmaxf(m, load_as_f32(p.y, p.y_dtype, yo + c));
@@ -1075,12 +1090,7 @@ __global__ __launch_bounds__(256) void k_loss_bwd(const LossProb *__restrict__ p
     float v[CE_NU], m, se;
     ce_row_load<CE_NU>(p.y, p.y_dtype, yo, p.cols, lane, v);
     ce_row_softmax<CE_NU>(v, m, se);
-    const float inv = 1.0f / se;
-#pragma unroll
-    for (int u = 0; u < CE_NU; ++u) {
-      const int c = lane + 64 * u;
-      if (c < p.cols) store_from_f32(p.dy, p.dy_dtype, go + c, p.scale * (v[u] * inv - (c == lab ? 1.0f : 0.0f)));
-    }
+    ce_row_grad<CE_NU>(p, go, lane, lab, v, se);
   } else if (p.kind == 10) {
     float m = -INFINITY;
     for (int c = lane; c < p.cols; c += 64) m = fmaxf(m, load_as_f32(p.y, p.y_dtype, yo + c));

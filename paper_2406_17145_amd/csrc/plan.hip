@@ -1167,8 +1167,9 @@ void Emitter::forward() {
           l.scale = (float)d.loss_scale;
           // per-slot gradient buffers (grouped weight gradients): an element-wise loss whose prediction
           // has no other consumer writes its gradient in the forward pass, one launch less per backward
-          if ((pl.flags & 4) && d.kind != GPP_OP_LOSS_CE && y.wants_grad && y.users.size() == 1 && y.gout_parent < 0 &&
-              y.fused_add < 0 && y.gout.space == SP_SLOT) {
+          // (the softmax cross-entropy too, where its kernels keep a whole row of logits in registers)
+          if ((pl.flags & 4) && (d.kind != GPP_OP_LOSS_CE || y.feat <= loss_ce_row_limit()) && y.wants_grad && y.users.size() == 1 &&
+              y.gout_parent < 0 && y.fused_add < 0 && y.gout.space == SP_SLOT) {
             l.dy = ptr(y.gout);
             l.ld_dy = y.gout.ld;
             l.dy_dtype = y.gout.dtype;

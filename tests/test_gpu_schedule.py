@@ -221,6 +221,20 @@ def test_grouped_weight_gradients_long_rows_per_slot():
         compare(wl, res, grads, ora_stage, ora_res, label=f"grouped long cap={cap} k={k}")
 
 
+def test_grouped_weight_gradients_transformer_stage():
+    # per-slot gradient buffers: the cross-entropy kernels of the forward pass also write the loss gradient where a
+    # row of logits fits their registers (50 and 1024 classes), and leave it to the backward pass where not (1500);
+    # LayerNorm parameter gradients are folded once per backward pass
+    for n_classes in (50, 1024, 1500):
+        wl = W.mmt(micro_batch=2, n_micro=4, n_branches=2, n_layers=2, d_model=128, heads=2, d_ff=256, seq_len=48,
+                   d_head_out=64, n_classes=n_classes)
+        ora_stage, ora_res = run_oracle(wl)
+        for cap, k in [(2, 2), (4, 4), (3, 1)]:
+            print(f"[case] {wl.name} {n_classes} classes, grouped weight gradients cap={cap} k={k}", flush=True)
+            _, res, grads = _run(wl, cap, k, True, reps=2, flags=B.FLAG_GROUPED_DW)
+            compare(wl, res, grads, ora_stage, ora_res, label=f"mmt grouped {n_classes} cap={cap} k={k}")
+
+
 def test_grouped_weight_gradients_with_embedding_tables_and_mid_pipeline_stage():
     wl = W.dlrm(micro_batch=128, n_micro=5, n_tables=4, num_rows=3000, bottom=(64, 32, 128), top=(128, 64, 1))
     ora_stage, ora_res = run_oracle(wl)
